@@ -1,0 +1,136 @@
+/*
+ * sp3d.h -- C ABI of the spatially partitioned 3x3x3 convolution library for MI355X (gfx950).
+ *
+ * The operations are the steps of the paper's method (arxiv 1909.03108, Sec. 2, third
+ * paragraph, and Fig. 1): a volume is cut into non-overlapping patches ("tiles"); before every
+ * convolution each tile receives the margins ("halo", half the kernel size wide) of its
+ * neighbours and is padded with them; then each tile is convolved on its own.  Forward and
+ * backward of the convolutions are both on the path (Sec. 3, "Computational efficiency").
+ * Here all tiles of the grid live in one GPU's memory and the exchange is an index mapping.
+ *
+ * General rules for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller, at least 16-byte aligned.
+ *     The library allocates nothing, frees nothing and keeps no state between calls except
+ *     the code of the last HIP error.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call checks
+ *     its arguments on the host, enqueues its kernels on `stream` and returns without
+ *     synchronising.
+ *   - Return value: SP_OK (0) or a negative error code; on error nothing has been enqueued.
+ *   - Geometry: volume extents (n, d, h, w); tile grid (gd, gh, gw) over the D, H, W axes, which
+ *     must divide d, h, w; halo width `halo` (only 1 = floor(3/2) is supported).  Tile extents
+ *     td = d/gd, th = h/gh, tw = w/gw; padded tile extents pd = td + 2*halo, etc.
+ *
+ * Layouts (C = channels, fastest)
+ *   volume        V[n][d][h][w][C]
+ *   padded tiles  P[n][gd][gh][gw][pd][ph][pw][C]; a tile's own voxels sit at [halo, halo+t) on
+ *                 each axis ("interior"), the rest is its margin
+ *   messages      M[n][gd][gh][gw][R][C], R = pd*ph*pw - td*th*tw; the R voxels of a tile are its
+ *                 26 regions in lexicographic order of the direction (dd,dh,dw) in {-1,0,1}^3
+ *                 without (0,0,0), each region row-major over its own (d,h,w) extents.  Region
+ *                 `dir` holds the tile's own voxels nearest to the neighbour in direction `dir`:
+ *                 on an axis with dir = -1 the first `halo` planes, +1 the last `halo`, 0 all.
+ *   weights       w[3][3][3][Cin][Cout] in the tensor dtype; weight gradient same shape, float
+ *   bias          float[Cout]; bias gradient float[Cout]
+ */
+#ifndef SP3D_H
+#define SP3D_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sp_geom {
+    int32_t n, d, h, w;   /* whole-volume extents in voxels                     */
+    int32_t gd, gh, gw;   /* tile grid over D, H, W; must divide d, h, w        */
+    int32_t halo;         /* margin width; 1 for the 3x3x3 kernel               */
+} sp_geom_t;
+
+typedef enum sp_dtype { SP_F32 = 0, SP_BF16 = 1 } sp_dtype_t;
+
+enum {
+    SP_OK = 0,
+    SP_EINVAL = -1,        /* null pointer, misaligned pointer, non-positive extent/channels */
+    SP_EGEOM = -2,         /* grid does not divide the volume, or a tile is thinner than halo */
+    SP_EUNSUPPORTED = -3,  /* halo != 1, unknown dtype, channel count with no kernel          */
+    SP_EWORKSPACE = -4,    /* workspace missing or smaller than sp_workspace_bytes says       */
+    SP_ELAUNCH = -5        /* HIP reported an error; see sp_last_hip_error()                  */
+};
+
+enum { SP_FLAG_RELU = 1 };                                /* conv3d_fwd: y = max(z, 0) */
+enum { SP_OP_FWD = 0, SP_OP_DGRAD = 1, SP_OP_WGRAD = 2 }; /* sp_workspace_bytes `op`   */
+
+/* ---- host-only helpers (no GPU needed) --------------------------------------------------- */
+
+/* Number of elements of the padded-tile array P / of the message array M for C channels;
+ * 0 if the geometry is invalid. */
+size_t sp_padded_elems(const sp_geom_t *g, int c);
+size_t sp_msg_elems(const sp_geom_t *g, int c);
+/* Bytes of scratch the convolution `op` needs for these sizes (may be 0); (size_t)-1 if the
+ * combination is invalid or unsupported. */
+size_t sp_workspace_bytes(int op, const sp_geom_t *g, int cin, int cout, sp_dtype_t dt);
+/* SP_OK or the error the geometry would raise. */
+int sp_check_geom(const sp_geom_t *g);
+const char *sp_strerror(int code);
+/* hipError_t of the most recent failing HIP call made by this library (0 if none). */
+int sp_last_hip_error(void);
+
+/* ---- partitioning (Fig. 1a; the "partitioning, reshaping" operations of Sec. 3) ------------ */
+
+/* Copy every tile of V into the interior of its slot of P.  Margins of P are not written.
+ * V and P must not overlap.  Bit-exact copy. */
+int sp_partition(const void *vol, void *P, const sp_geom_t *g, int c, sp_dtype_t dt, void *stream);
+/* Inverse: drop the margins of P and reassemble V.  Bit-exact copy. */
+int sp_unpartition(const void *P, void *vol, const sp_geom_t *g, int c, sp_dtype_t dt, void *stream);
+
+/* ---- halo exchange (Fig. 1b; Sec. 2: "exchange margins ... pad the patches") ---------------- */
+
+/* Sending side: copy the 26 boundary regions of every tile's interior into its message.
+ * Reads P's interiors only.  Bit-exact. */
+int halo_pack(const void *P, void *msg, const sp_geom_t *g, int c, sp_dtype_t dt, void *stream);
+/* Receiving side: for every tile and direction `dir`, fill the margin region lying in direction
+ * `dir` from region -dir of the message of the neighbour tile at +dir; zero-fill it when that
+ * neighbour is outside the grid (zero 'same' padding at the volume border).  Writes margins
+ * only; interiors are untouched.  P is updated in place.  Bit-exact. */
+int halo_unpack(void *P, const void *msg, const sp_geom_t *g, int c, sp_dtype_t dt, void *stream);
+
+/* ---- convolution on padded tiles (Sec. 2: "finally apply convolution"; Sec. 3: fwd + bwd) --- */
+
+/* Forward.  z[v,co] = bias[co] + sum_{kd,kh,kw,ci} Px[v + (kd,kh,kw)][ci] * w[kd][kh][kw][ci][co]
+ * for every interior voxel v of every tile (v in padded coordinates minus halo, so tap (1,1,1)
+ * is the voxel itself): the 'valid' cross-correlation of each padded tile, which equals the
+ * zero-padded 'same' convolution of the whole volume once halo_unpack has run on Px.
+ * Writes y = z (or max(z,0) with SP_FLAG_RELU) into the interiors of Py; Py's margins are left
+ * as they are.  bias may be NULL.  Px [..][Cin], Py [..][Cout] must not overlap.
+ * bf16: products of bf16 values accumulated in fp32, result rounded to nearest-even bf16.
+ * f32: fp32 throughout. */
+int conv3d_fwd(const void *Px, const void *w, const float *bias, void *Py, const sp_geom_t *g,
+               int cin, int cout, sp_dtype_t dt, uint32_t flags, void *ws, size_t ws_bytes,
+               void *stream);
+
+/* Data gradient.  dx[v,ci] = sum_{kd,kh,kw,co} Pdz[v + (2-kd,2-kh,2-kw)][co] * w[kd][kh][kw][ci][co]
+ * over interior voxels v, i.e. the same correlation with the taps mirrored and the channel roles
+ * swapped, reading halo-exchanged dz (run halo_pack/halo_unpack on Pdz first).  Writes the
+ * interiors of Pdx [..][Cin].  Precision as conv3d_fwd. */
+int conv3d_dgrad(const void *Pdz, const void *w, void *Pdx, const sp_geom_t *g, int cin, int cout,
+                 sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream);
+
+/* Weight gradient.  dw[kd][kh][kw][ci][co] = sum over tiles and interior voxels v of
+ * Px[v + (kd,kh,kw)][ci] * Pdz[v + (1,1,1)][co];  db[co] = sum of Pdz interiors (db may be NULL).
+ * Px must hold its halos (as left by the forward pass); only the interiors of Pdz are read.
+ * Products accumulated in fp32; the sum over workgroups is taken in a fixed order, so results
+ * are reproducible run to run.  dw, db are float and are overwritten (not accumulated). */
+int conv3d_wgrad(const void *Px, const void *Pdz, float *dw, float *db, const sp_geom_t *g,
+                 int cin, int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream);
+
+/* Element-wise ReLU backward on padded tiles: Pdz = Pdy where Py > 0, else 0 (all elements,
+ * margins included; the derivative at 0 is taken as 0).  Pdz may alias Pdy. */
+int sp_relu_bwd(const void *Pdy, const void *Py, void *Pdz, const sp_geom_t *g, int c,
+                sp_dtype_t dt, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SP3D_H */

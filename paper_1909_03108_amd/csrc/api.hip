@@ -1,0 +1,261 @@
+// C-ABI entry points of libsp3d: argument checks, workspace sizing, kernel dispatch.
+// Every check happens on the host before anything is enqueued.
+#include "common.h"
+
+#include <atomic>
+
+namespace sp3d {
+
+static std::atomic<int> g_last_hip_error{0};
+
+int record_hip(hipError_t e) {
+    if (e == hipSuccess) return SP_OK;
+    g_last_hip_error.store(static_cast<int>(e));
+    return SP_ELAUNCH;
+}
+
+int make_geo(const sp_geom_t *g, Geo *out) {
+    if (!g) return SP_EINVAL;
+    if (g->n <= 0 || g->d <= 0 || g->h <= 0 || g->w <= 0 || g->gd <= 0 || g->gh <= 0 ||
+        g->gw <= 0 || g->halo < 0)
+        return SP_EINVAL;
+    if (g->d % g->gd || g->h % g->gh || g->w % g->gw) return SP_EGEOM;
+    if (g->halo != 1) return SP_EUNSUPPORTED;
+    Geo o;
+    o.n = g->n; o.gd = g->gd; o.gh = g->gh; o.gw = g->gw;
+    o.td = g->d / g->gd; o.th = g->h / g->gh; o.tw = g->w / g->gw;
+    o.halo = g->halo;
+    if (o.td < o.halo || o.th < o.halo || o.tw < o.halo) return SP_EGEOM;
+    o.pd = o.td + 2 * o.halo; o.ph = o.th + 2 * o.halo; o.pw = o.tw + 2 * o.halo;
+    long long nt = 1LL * o.n * o.gd * o.gh * o.gw;
+    if (nt > 0x7fffffffLL) return SP_EGEOM;
+    o.ntiles = static_cast<int>(nt);
+    o.tile_vox = 1LL * o.pd * o.ph * o.pw;
+    o.int_vox = 1LL * o.td * o.th * o.tw;
+    o.msg_vox = o.tile_vox - o.int_vox;
+    if (o.tile_vox > 0x7fffffffLL) return SP_EGEOM;   // per-tile voxel indices stay 32-bit
+    if (out) *out = o;
+    return SP_OK;
+}
+
+void make_regions(const Geo &g, RegionTable *t) {
+    const int ext[3] = {g.td, g.th, g.tw};
+    int k = 0;
+    long long off = 0;
+    for (int dd = -1; dd <= 1; ++dd)
+        for (int dh = -1; dh <= 1; ++dh)
+            for (int dw = -1; dw <= 1; ++dw) {
+                if (!dd && !dh && !dw) continue;
+                Region &r = t->r[k];
+                const int dl[3] = {dd, dh, dw};
+                long long n = 1;
+                for (int a = 0; a < 3; ++a) {
+                    r.delta[a] = dl[a];
+                    r.ext[a] = dl[a] ? g.halo : ext[a];
+                    // sent box: own voxels nearest to the neighbour (padded coordinates)
+                    r.send[a] = g.halo + (dl[a] > 0 ? ext[a] - g.halo : 0);
+                    // margin box lying in direction delta
+                    r.recv[a] = dl[a] < 0 ? 0 : (dl[a] == 0 ? g.halo : g.halo + ext[a]);
+                    n *= r.ext[a];
+                }
+                r.off = off;
+                off += n;
+                r.opposite = 25 - k;   // lexicographic order is symmetric under negation
+                ++k;
+            }
+}
+
+static bool chan_ok(int c) { return c > 0 && c <= 4096; }
+static bool dtype_ok(sp_dtype_t dt) { return dt == SP_F32 || dt == SP_BF16; }
+
+static bool overlap(const void *a, size_t na, const void *b, size_t nb) {
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    return x < y + nb && y < x + na;
+}
+
+}  // namespace sp3d
+
+using namespace sp3d;
+
+extern "C" {
+
+size_t sp_padded_elems(const sp_geom_t *g, int c) {
+    Geo o;
+    if (make_geo(g, &o) != SP_OK || c <= 0) return 0;
+    return static_cast<size_t>(o.ntiles) * o.tile_vox * c;
+}
+
+size_t sp_msg_elems(const sp_geom_t *g, int c) {
+    Geo o;
+    if (make_geo(g, &o) != SP_OK || c <= 0) return 0;
+    return static_cast<size_t>(o.ntiles) * o.msg_vox * c;
+}
+
+int sp_check_geom(const sp_geom_t *g) { return make_geo(g, nullptr); }
+
+size_t sp_workspace_bytes(int op, const sp_geom_t *g, int cin, int cout, sp_dtype_t dt) {
+    Geo o;
+    if (make_geo(g, &o) != SP_OK || !chan_ok(cin) || !chan_ok(cout) || !dtype_ok(dt))
+        return static_cast<size_t>(-1);
+    switch (op) {
+    case SP_OP_FWD:
+    case SP_OP_DGRAD: {
+        // dgrad swaps the channel roles of the same kernel
+        const int ki = op == SP_OP_FWD ? cin : cout, ko = op == SP_OP_FWD ? cout : cin;
+        return conv_mfma_supported(o, ki, ko, dt) ? conv_mfma_ws_bytes(o, ki, ko) : 0;
+    }
+    case SP_OP_WGRAD:
+        return wgrad_mfma_supported(o, cin, cout, dt) ? wgrad_mfma_ws_bytes(o, cin, cout)
+                                                      : wgrad_direct_ws_bytes(o, cin, cout);
+    default:
+        return static_cast<size_t>(-1);
+    }
+}
+
+const char *sp_strerror(int code) {
+    switch (code) {
+    case SP_OK: return "ok";
+    case SP_EINVAL: return "invalid argument (null or misaligned pointer, non-positive size, overlap)";
+    case SP_EGEOM: return "tile grid does not divide the volume, or a tile is thinner than the halo";
+    case SP_EUNSUPPORTED: return "unsupported halo width, dtype or channel count";
+    case SP_EWORKSPACE: return "workspace missing or too small";
+    case SP_ELAUNCH: return "HIP error at launch (see sp_last_hip_error)";
+    default: return "unknown error";
+    }
+}
+
+int sp_last_hip_error(void) { return g_last_hip_error.load(); }
+
+static int check_copy_args(const void *a, const void *b, const sp_geom_t *g, int c, sp_dtype_t dt,
+                           Geo *o) {
+    if (!a || !b) return SP_EINVAL;
+    int rc = make_geo(g, o);
+    if (rc != SP_OK) return rc;
+    if (!chan_ok(c)) return SP_EINVAL;
+    if (!dtype_ok(dt)) return SP_EUNSUPPORTED;
+    if (!aligned16(a) || !aligned16(b)) return SP_EINVAL;
+    return SP_OK;
+}
+
+int sp_partition(const void *vol, void *P, const sp_geom_t *g, int c, sp_dtype_t dt, void *stream) {
+    Geo o;
+    int rc = check_copy_args(vol, P, g, c, dt, &o);
+    if (rc != SP_OK) return rc;
+    const size_t es = elem_size(dt);
+    if (overlap(vol, static_cast<size_t>(o.ntiles) * o.int_vox * c * es, P,
+                static_cast<size_t>(o.ntiles) * o.tile_vox * c * es))
+        return SP_EINVAL;
+    return launch_partition(vol, P, o, c, dt, false, static_cast<hipStream_t>(stream));
+}
+
+int sp_unpartition(const void *P, void *vol, const sp_geom_t *g, int c, sp_dtype_t dt, void *stream) {
+    Geo o;
+    int rc = check_copy_args(P, vol, g, c, dt, &o);
+    if (rc != SP_OK) return rc;
+    const size_t es = elem_size(dt);
+    if (overlap(vol, static_cast<size_t>(o.ntiles) * o.int_vox * c * es, P,
+                static_cast<size_t>(o.ntiles) * o.tile_vox * c * es))
+        return SP_EINVAL;
+    return launch_partition(vol, const_cast<void *>(P), o, c, dt, true,
+                            static_cast<hipStream_t>(stream));
+}
+
+int halo_pack(const void *P, void *msg, const sp_geom_t *g, int c, sp_dtype_t dt, void *stream) {
+    Geo o;
+    int rc = check_copy_args(P, msg, g, c, dt, &o);
+    if (rc != SP_OK) return rc;
+    const size_t es = elem_size(dt);
+    if (overlap(P, static_cast<size_t>(o.ntiles) * o.tile_vox * c * es, msg,
+                static_cast<size_t>(o.ntiles) * o.msg_vox * c * es))
+        return SP_EINVAL;
+    return launch_halo_pack(P, msg, o, c, dt, static_cast<hipStream_t>(stream));
+}
+
+int halo_unpack(void *P, const void *msg, const sp_geom_t *g, int c, sp_dtype_t dt, void *stream) {
+    Geo o;
+    int rc = check_copy_args(P, msg, g, c, dt, &o);
+    if (rc != SP_OK) return rc;
+    const size_t es = elem_size(dt);
+    if (overlap(P, static_cast<size_t>(o.ntiles) * o.tile_vox * c * es, msg,
+                static_cast<size_t>(o.ntiles) * o.msg_vox * c * es))
+        return SP_EINVAL;
+    return launch_halo_unpack(P, msg, o, c, dt, static_cast<hipStream_t>(stream));
+}
+
+static int check_conv_args(const void *a, const void *b, const void *c, const sp_geom_t *g, int cin,
+                           int cout, sp_dtype_t dt, Geo *o) {
+    if (!a || !b || !c) return SP_EINVAL;
+    int rc = make_geo(g, o);
+    if (rc != SP_OK) return rc;
+    if (cin <= 0 || cout <= 0) return SP_EINVAL;
+    if (!dtype_ok(dt) || !chan_ok(cin) || !chan_ok(cout)) return SP_EUNSUPPORTED;
+    if (!aligned16(a) || !aligned16(b) || !aligned16(c)) return SP_EINVAL;
+    return SP_OK;
+}
+
+int conv3d_fwd(const void *Px, const void *w, const float *bias, void *Py, const sp_geom_t *g,
+               int cin, int cout, sp_dtype_t dt, uint32_t flags, void *ws, size_t ws_bytes,
+               void *stream) {
+    Geo o;
+    int rc = check_conv_args(Px, w, Py, g, cin, cout, dt, &o);
+    if (rc != SP_OK) return rc;
+    if (flags & ~static_cast<uint32_t>(SP_FLAG_RELU)) return SP_EINVAL;
+    const size_t es = elem_size(dt);
+    const size_t pv = static_cast<size_t>(o.ntiles) * o.tile_vox;
+    if (overlap(Px, pv * cin * es, Py, pv * cout * es)) return SP_EINVAL;
+    const bool relu = flags & SP_FLAG_RELU;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (conv_mfma_supported(o, cin, cout, dt)) {
+        const size_t need = conv_mfma_ws_bytes(o, cin, cout);
+        if (need && (!ws || ws_bytes < need || !aligned16(ws))) return SP_EWORKSPACE;
+        return launch_conv_mfma(Px, w, bias, Py, o, cin, cout, relu, false, ws, s);
+    }
+    return launch_conv_direct(Px, w, bias, Py, o, cin, cout, dt, relu, false, s);
+}
+
+int conv3d_dgrad(const void *Pdz, const void *w, void *Pdx, const sp_geom_t *g, int cin, int cout,
+                 sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream) {
+    Geo o;
+    int rc = check_conv_args(Pdz, w, Pdx, g, cin, cout, dt, &o);
+    if (rc != SP_OK) return rc;
+    const size_t es = elem_size(dt);
+    const size_t pv = static_cast<size_t>(o.ntiles) * o.tile_vox;
+    if (overlap(Pdz, pv * cout * es, Pdx, pv * cin * es)) return SP_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // the kernel's "input channels" are cout and its "output channels" are cin
+    if (conv_mfma_supported(o, cout, cin, dt)) {
+        const size_t need = conv_mfma_ws_bytes(o, cout, cin);
+        if (need && (!ws || ws_bytes < need || !aligned16(ws))) return SP_EWORKSPACE;
+        return launch_conv_mfma(Pdz, w, nullptr, Pdx, o, cout, cin, false, true, ws, s);
+    }
+    return launch_conv_direct(Pdz, w, nullptr, Pdx, o, cout, cin, dt, false, true, s);
+}
+
+int conv3d_wgrad(const void *Px, const void *Pdz, float *dw, float *db, const sp_geom_t *g, int cin,
+                 int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream) {
+    Geo o;
+    int rc = check_conv_args(Px, Pdz, dw, g, cin, cout, dt, &o);
+    if (rc != SP_OK) return rc;
+    if (db && (reinterpret_cast<uintptr_t>(db) & 3u)) return SP_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool mfma = wgrad_mfma_supported(o, cin, cout, dt);
+    const size_t need = mfma ? wgrad_mfma_ws_bytes(o, cin, cout) : wgrad_direct_ws_bytes(o, cin, cout);
+    if (need && (!ws || ws_bytes < need || !aligned16(ws))) return SP_EWORKSPACE;
+    if (mfma) return launch_wgrad_mfma(Px, Pdz, dw, db, o, cin, cout, ws, s);
+    return launch_wgrad_direct(Px, Pdz, dw, db, o, cin, cout, dt, ws, s);
+}
+
+int sp_relu_bwd(const void *Pdy, const void *Py, void *Pdz, const sp_geom_t *g, int c, sp_dtype_t dt,
+                void *stream) {
+    Geo o;
+    if (!Pdy || !Py || !Pdz) return SP_EINVAL;
+    int rc = make_geo(g, &o);
+    if (rc != SP_OK) return rc;
+    if (!chan_ok(c)) return SP_EINVAL;
+    if (!dtype_ok(dt)) return SP_EUNSUPPORTED;
+    if (!aligned16(Pdy) || !aligned16(Py) || !aligned16(Pdz)) return SP_EINVAL;
+    return launch_relu_bwd(Pdy, Py, Pdz, static_cast<size_t>(o.ntiles) * o.tile_vox * c, dt,
+                           static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,79 @@
+// Internal declarations shared by the HIP sources of libsp3d (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "sp3d.h"
+
+namespace sp3d {
+
+// Geometry in the form the kernels use: tile extents, padded extents and strides in voxels.
+struct Geo {
+    int n, gd, gh, gw;       // batch and tile grid
+    int td, th, tw;          // tile extents
+    int pd, ph, pw;          // padded tile extents (t + 2*halo)
+    int halo;
+    int ntiles;              // n * gd * gh * gw
+    long long tile_vox;      // pd * ph * pw   (voxels per padded tile)
+    long long int_vox;       // td * th * tw   (interior voxels per tile)
+    long long msg_vox;       // tile_vox - int_vox (margin voxels per tile)
+};
+
+int make_geo(const sp_geom_t *g, Geo *out);       // SP_OK or error code
+int record_hip(hipError_t e);                      // stores e, returns SP_ELAUNCH if e != success
+inline size_t elem_size(sp_dtype_t dt) { return dt == SP_BF16 ? 2 : 4; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// One of the 26 halo regions, in message order.
+struct Region {
+    int ext[3];      // extents (d,h,w) of the region
+    int send[3];     // origin of the sent box in padded coordinates of the sending tile
+    int recv[3];     // origin of the margin box in padded coordinates of the receiving tile
+    int delta[3];    // direction
+    int opposite;    // index of the region with direction -delta
+    long long off;   // voxel offset of the region inside a tile's message
+};
+struct RegionTable {
+    Region r[26];
+};
+void make_regions(const Geo &g, RegionTable *t);
+
+// launchers implemented in the kernel sources -------------------------------------------------
+int launch_partition(const void *vol, void *P, const Geo &g, int c, sp_dtype_t dt, bool inverse,
+                     hipStream_t s);
+int launch_halo_pack(const void *P, void *msg, const Geo &g, int c, sp_dtype_t dt, hipStream_t s);
+int launch_halo_unpack(void *P, const void *msg, const Geo &g, int c, sp_dtype_t dt, hipStream_t s);
+int launch_relu_bwd(const void *dy, const void *y, void *dz, size_t elems, sp_dtype_t dt,
+                    hipStream_t s);
+
+int launch_conv_direct(const void *Pin, const void *w, const float *bias, void *Pout, const Geo &g,
+                       int cin, int cout, sp_dtype_t dt, bool relu, bool dgrad, hipStream_t s);
+size_t wgrad_direct_ws_bytes(const Geo &g, int cin, int cout);
+int launch_wgrad_direct(const void *Px, const void *Pdz, float *dw, float *db, const Geo &g,
+                        int cin, int cout, sp_dtype_t dt, void *ws, hipStream_t s);
+
+int launch_reduce_partials(const float *part, float *out, int nparts, long long n, hipStream_t s);
+
+bool conv_mfma_supported(const Geo &g, int cin, int cout, sp_dtype_t dt);
+size_t conv_mfma_ws_bytes(const Geo &g, int cin, int cout);
+int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Pout, const Geo &g,
+                     int cin, int cout, bool relu, bool dgrad, void *ws, hipStream_t s);
+
+bool wgrad_mfma_supported(const Geo &g, int cin, int cout, sp_dtype_t dt);
+size_t wgrad_mfma_ws_bytes(const Geo &g, int cin, int cout);
+int launch_wgrad_mfma(const void *Px, const void *Pdz, float *dw, float *db, const Geo &g,
+                      int cin, int cout, void *ws, hipStream_t s);
+
+// device helpers ------------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) {
+    return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+// round to nearest, ties to even; NaN stays NaN
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return static_cast<uint16_t>(u >> 16);
+}
+
+}  // namespace sp3d

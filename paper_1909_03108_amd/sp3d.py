@@ -1,0 +1,181 @@
+"""ctypes binding of libsp3d.so: same names as the C ABI (include/sp3d.h), argument
+marshalling only.  Tensors are torch tensors on the GPU (used for their device memory and
+stream); every operation runs in the library's HIP kernels.  There is no CPU fallback: if the
+library has not been built the import of the library raises.
+"""
+import ctypes
+import os
+
+SP_F32, SP_BF16 = 0, 1
+SP_OK, SP_EINVAL, SP_EGEOM, SP_EUNSUPPORTED, SP_EWORKSPACE, SP_ELAUNCH = 0, -1, -2, -3, -4, -5
+SP_FLAG_RELU = 1
+SP_OP_FWD, SP_OP_DGRAD, SP_OP_WGRAD = 0, 1, 2
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsp3d.so")
+
+EXPORTS = ["sp_padded_elems", "sp_msg_elems", "sp_workspace_bytes", "sp_check_geom", "sp_strerror",
+           "sp_last_hip_error", "sp_partition", "sp_unpartition", "halo_pack", "halo_unpack",
+           "conv3d_fwd", "conv3d_dgrad", "conv3d_wgrad", "sp_relu_bwd"]
+
+
+class Geom(ctypes.Structure):
+    """sp_geom_t: volume extents, tile grid (D,H,W order) and halo width."""
+    _fields_ = [(k, ctypes.c_int32) for k in ("n", "d", "h", "w", "gd", "gh", "gw", "halo")]
+
+    def __init__(self, n, dhw, grid, halo=1):
+        super().__init__(n, dhw[0], dhw[1], dhw[2], grid[0], grid[1], grid[2], halo)
+
+    @property
+    def tile(self):
+        return self.d // self.gd, self.h // self.gh, self.w // self.gw
+
+    @property
+    def padded_shape(self):
+        """Shape of the padded tile array without the channel axis."""
+        t = self.tile
+        return (self.n, self.gd, self.gh, self.gw) + tuple(e + 2 * self.halo for e in t)
+
+
+class Sp3dError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__("%s: %s (code %d, hip error %d)" % (
+            where, lib().sp_strerror(code).decode(), code, lib().sp_last_hip_error()))
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libsp3d.so is not built: run `python -c 'import __graft_entry__ as g;"
+                              " g.build()'` (or paper_1909_03108_amd/build.py) first")
+        L = ctypes.CDLL(LIB_PATH)
+        G, P, I, U, Z = ctypes.POINTER(Geom), ctypes.c_void_p, ctypes.c_int, ctypes.c_uint32, ctypes.c_size_t
+        L.sp_padded_elems.argtypes, L.sp_padded_elems.restype = [G, I], Z
+        L.sp_msg_elems.argtypes, L.sp_msg_elems.restype = [G, I], Z
+        L.sp_workspace_bytes.argtypes, L.sp_workspace_bytes.restype = [I, G, I, I, I], Z
+        L.sp_check_geom.argtypes, L.sp_check_geom.restype = [G], I
+        L.sp_strerror.argtypes, L.sp_strerror.restype = [I], ctypes.c_char_p
+        L.sp_last_hip_error.argtypes, L.sp_last_hip_error.restype = [], I
+        for name in ("sp_partition", "sp_unpartition", "halo_pack", "halo_unpack"):
+            f = getattr(L, name)
+            f.argtypes, f.restype = [P, P, G, I, I, P], I
+        L.conv3d_fwd.argtypes, L.conv3d_fwd.restype = [P, P, P, P, G, I, I, I, U, P, Z, P], I
+        L.conv3d_dgrad.argtypes, L.conv3d_dgrad.restype = [P, P, P, G, I, I, I, P, Z, P], I
+        L.conv3d_wgrad.argtypes, L.conv3d_wgrad.restype = [P, P, P, P, G, I, I, I, P, Z, P], I
+        L.sp_relu_bwd.argtypes, L.sp_relu_bwd.restype = [P, P, P, G, I, I, P], I
+        _lib = L
+    return _lib
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def _ws(ws):
+    if ws is None:
+        return None, 0
+    return ws.data_ptr(), ws.numel() * ws.element_size()
+
+
+def _check(rc, where):
+    if rc != SP_OK:
+        raise Sp3dError(rc, where)
+
+
+def sp_padded_elems(g, c):
+    return lib().sp_padded_elems(ctypes.byref(g), c)
+
+
+def sp_msg_elems(g, c):
+    return lib().sp_msg_elems(ctypes.byref(g), c)
+
+
+def sp_workspace_bytes(op, g, cin, cout, dt):
+    r = lib().sp_workspace_bytes(op, ctypes.byref(g), cin, cout, dt)
+    if r == ctypes.c_size_t(-1).value:
+        raise Sp3dError(SP_EUNSUPPORTED, "sp_workspace_bytes")
+    return r
+
+
+def sp_check_geom(g):
+    return lib().sp_check_geom(ctypes.byref(g))
+
+
+def sp_partition(vol, P, g, c, dt, stream=None):
+    _check(lib().sp_partition(_ptr(vol), _ptr(P), ctypes.byref(g), c, dt, _stream(stream)), "sp_partition")
+
+
+def sp_unpartition(P, vol, g, c, dt, stream=None):
+    _check(lib().sp_unpartition(_ptr(P), _ptr(vol), ctypes.byref(g), c, dt, _stream(stream)),
+           "sp_unpartition")
+
+
+def halo_pack(P, msg, g, c, dt, stream=None):
+    _check(lib().halo_pack(_ptr(P), _ptr(msg), ctypes.byref(g), c, dt, _stream(stream)), "halo_pack")
+
+
+def halo_unpack(P, msg, g, c, dt, stream=None):
+    _check(lib().halo_unpack(_ptr(P), _ptr(msg), ctypes.byref(g), c, dt, _stream(stream)), "halo_unpack")
+
+
+def conv3d_fwd(Px, w, bias, Py, g, cin, cout, dt, flags=0, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib().conv3d_fwd(_ptr(Px), _ptr(w), _ptr(bias), _ptr(Py), ctypes.byref(g), cin, cout, dt,
+                            flags, wp, wb, _stream(stream)), "conv3d_fwd")
+
+
+def conv3d_dgrad(Pdz, w, Pdx, g, cin, cout, dt, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib().conv3d_dgrad(_ptr(Pdz), _ptr(w), _ptr(Pdx), ctypes.byref(g), cin, cout, dt, wp, wb,
+                              _stream(stream)), "conv3d_dgrad")
+
+
+def conv3d_wgrad(Px, Pdz, dw, db, g, cin, cout, dt, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib().conv3d_wgrad(_ptr(Px), _ptr(Pdz), _ptr(dw), _ptr(db), ctypes.byref(g), cin, cout, dt,
+                              wp, wb, _stream(stream)), "conv3d_wgrad")
+
+
+def sp_relu_bwd(Pdy, Py, Pdz, g, c, dt, stream=None):
+    _check(lib().sp_relu_bwd(_ptr(Pdy), _ptr(Py), _ptr(Pdz), ctypes.byref(g), c, dt, _stream(stream)),
+           "sp_relu_bwd")
+
+
+# ---- plumbing helpers (device memory only; no arithmetic) ---------------------------------------
+
+def torch_dtype(dt):
+    import torch
+    return torch.bfloat16 if dt == SP_BF16 else torch.float32
+
+
+def alloc_padded(g, c, dt, zero=True, device="cuda"):
+    """Device buffer for the padded tile array P[n,gd,gh,gw,pd,ph,pw,c]."""
+    import torch
+    f = torch.zeros if zero else torch.empty
+    return f(g.padded_shape + (c,), dtype=torch_dtype(dt), device=device)
+
+
+def alloc_msg(g, c, dt, device="cuda"):
+    import torch
+    return torch.empty((sp_msg_elems(g, c),), dtype=torch_dtype(dt), device=device)
+
+
+def alloc_ws(nbytes, device="cuda"):
+    import torch
+    return torch.empty((max(int(nbytes), 16),), dtype=torch.uint8, device=device)

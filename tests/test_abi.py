@@ -1,0 +1,93 @@
+"""Host-side checks of the C-ABI library (no GPU needed): it loads, exports every symbol the
+header declares, sizes agree with the slicing oracle, and bad arguments are rejected before
+anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import tiling
+from paper_1909_03108_amd import sp3d
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000   # non-null, 16-byte aligned; never dereferenced because every call below fails validation
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sp3d.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\([^;{}]*\)\s*;", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    L = sp3d.lib()
+    names = declared_functions()
+    assert len(names) >= 14
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(sp3d.EXPORTS) == names
+
+
+@pytest.mark.parametrize("n,dhw,grid,c", [(1, (32, 32, 32), (2, 2, 1), 8), (1, (128, 128, 128), (4, 4, 1), 32),
+                                          (1, (256, 256, 256), (4, 4, 2), 1), (2, (6, 4, 8), (3, 2, 4), 5),
+                                          (1, (512, 512, 512), (4, 4, 1), 32)])
+def test_size_helpers_match_the_oracle_formulas(n, dhw, grid, c):
+    g = sp3d.Geom(n, dhw, grid)
+    tile = tiling.tile_extents(dhw, grid)
+    ntiles = n * grid[0] * grid[1] * grid[2]
+    assert sp3d.sp_msg_elems(g, c) == ntiles * tiling.margin_voxels(tile, 1) * c
+    assert sp3d.sp_padded_elems(g, c) == ntiles * (tile[0] + 2) * (tile[1] + 2) * (tile[2] + 2) * c
+    assert g.padded_shape == (n,) + grid + tuple(t + 2 for t in tile)
+
+
+def test_margin_voxel_counts_of_the_workload_configurations():
+    # per-tile margin voxels for the 16x16x32, 32x32x128, 64x64x128 and 128x128x512 tiles
+    for dhw, grid, expect in [((32, 32, 32), (2, 2, 1), 2824), ((128, 128, 128), (4, 4, 1), 19208),
+                              ((256, 256, 256), (4, 4, 2), 41992), ((512, 512, 512), (4, 4, 1), 297992)]:
+        g = sp3d.Geom(1, dhw, grid)
+        assert sp3d.sp_msg_elems(g, 1) == expect * grid[0] * grid[1] * grid[2]
+
+
+def test_geometry_errors():
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (8, 8, 8), (2, 2, 2))) == sp3d.SP_OK
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (8, 8, 8), (3, 2, 2))) == sp3d.SP_EGEOM
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (8, 8, 8), (2, 2, 2), halo=2)) == sp3d.SP_EUNSUPPORTED
+    assert sp3d.sp_check_geom(sp3d.Geom(0, (8, 8, 8), (2, 2, 2))) == sp3d.SP_EINVAL
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (8, 8, 8), (2, 0, 2))) == sp3d.SP_EINVAL
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (2, 2, 2), (2, 2, 2))) == sp3d.SP_OK     # 1-voxel tiles are legal
+    assert sp3d.sp_padded_elems(sp3d.Geom(1, (8, 8, 8), (3, 2, 2)), 4) == 0
+
+
+def test_calls_reject_bad_arguments_before_launching():
+    L = sp3d.lib()
+    g = sp3d.Geom(1, (8, 8, 8), (2, 2, 2))
+    bad = sp3d.Geom(1, (8, 8, 8), (3, 2, 2))
+    gp, bp = ctypes.byref(g), ctypes.byref(bad)
+    assert L.sp_partition(None, FAKE, gp, 4, sp3d.SP_BF16, None) == sp3d.SP_EINVAL
+    assert L.sp_partition(FAKE, FAKE + 8, gp, 4, sp3d.SP_BF16, None) == sp3d.SP_EINVAL      # misaligned
+    assert L.sp_partition(FAKE, FAKE, gp, 4, sp3d.SP_BF16, None) == sp3d.SP_EINVAL          # overlap
+    assert L.sp_partition(FAKE, FAKE * 16, bp, 4, sp3d.SP_BF16, None) == sp3d.SP_EGEOM
+    assert L.sp_unpartition(FAKE, FAKE * 16, gp, 0, sp3d.SP_BF16, None) == sp3d.SP_EINVAL
+    assert L.halo_pack(FAKE, FAKE * 16, gp, 4, 7, None) == sp3d.SP_EUNSUPPORTED
+    assert L.halo_unpack(FAKE, None, gp, 4, sp3d.SP_BF16, None) == sp3d.SP_EINVAL
+    assert L.conv3d_fwd(FAKE, FAKE * 2, None, FAKE * 16, bp, 4, 4, sp3d.SP_F32, 0, None, 0, None) == sp3d.SP_EGEOM
+    assert L.conv3d_fwd(FAKE, FAKE * 2, None, FAKE * 16, gp, 4, 4, sp3d.SP_F32, 2, None, 0, None) == sp3d.SP_EINVAL
+    assert L.conv3d_fwd(FAKE, FAKE * 2, None, FAKE, gp, 4, 4, sp3d.SP_F32, 0, None, 0, None) == sp3d.SP_EINVAL
+    assert L.conv3d_dgrad(FAKE, None, FAKE * 16, gp, 4, 4, sp3d.SP_F32, None, 0, None) == sp3d.SP_EINVAL
+    assert L.conv3d_dgrad(FAKE, FAKE * 2, FAKE * 16, gp, -1, 4, sp3d.SP_F32, None, 0, None) == sp3d.SP_EINVAL
+    # weight gradient always needs scratch for its fixed-order reduction
+    need = sp3d.sp_workspace_bytes(sp3d.SP_OP_WGRAD, g, 4, 4, sp3d.SP_F32)
+    assert need > 0
+    assert L.conv3d_wgrad(FAKE, FAKE * 2, FAKE * 4, None, gp, 4, 4, sp3d.SP_F32, None, 0, None) == sp3d.SP_EWORKSPACE
+    assert L.conv3d_wgrad(FAKE, FAKE * 2, FAKE * 4, None, gp, 4, 4, sp3d.SP_F32, FAKE * 8, need - 1, None) == sp3d.SP_EWORKSPACE
+    assert L.sp_relu_bwd(FAKE, FAKE, None, gp, 4, sp3d.SP_F32, None) == sp3d.SP_EINVAL
+    assert L.sp_workspace_bytes(9, gp, 4, 4, sp3d.SP_F32) == ctypes.c_size_t(-1).value
+    assert L.sp_workspace_bytes(sp3d.SP_OP_FWD, bp, 4, 4, sp3d.SP_F32) == ctypes.c_size_t(-1).value
+
+
+def test_error_strings():
+    L = sp3d.lib()
+    seen = {L.sp_strerror(c) for c in range(-5, 1)}
+    assert len(seen) == 6 and all(s for s in seen)
+    assert L.sp_last_hip_error() == 0

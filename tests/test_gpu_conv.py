@@ -1,0 +1,162 @@
+"""GPU parity of conv3d_fwd / conv3d_dgrad / conv3d_wgrad against the fp64 direct-convolution
+oracle on the unpartitioned volume.  Inputs are the same stored values on both sides; the bound is
+max_i |g_i - r_i| / max(|r_i|, rms(r)) <= 1e-2 for bf16 (fp32 accumulation, one bf16 rounding of the
+result) and <= 1e-5 for fp32."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import conv3d, tiling
+from paper_1909_03108_amd import sp3d, synth
+from gpu_util import DT, TOL, bits, f64, rel_err, to_dev, widen
+
+pytestmark = pytest.mark.gpu
+
+
+class Layer:
+    """Device-side plumbing for one convolution layer on a tile grid (no arithmetic here)."""
+
+    def __init__(self, n, dhw, grid, cin, cout, dtype):
+        self.g = sp3d.Geom(n, dhw, grid)
+        self.cin, self.cout, self.dtype, self.dt = cin, cout, dtype, DT[dtype]
+        g, dt = self.g, self.dt
+        self.ws = {op: sp3d.alloc_ws(sp3d.sp_workspace_bytes(op, g, cin, cout, dt))
+                   for op in (sp3d.SP_OP_FWD, sp3d.SP_OP_DGRAD, sp3d.SP_OP_WGRAD)}
+
+    def padded(self, V, c):
+        """volume (host storage array) -> halo-exchanged padded tiles on the device"""
+        P = sp3d.alloc_padded(self.g, c, self.dt)
+        sp3d.sp_partition(to_dev(V), P, self.g, c, self.dt)
+        M = sp3d.alloc_msg(self.g, c, self.dt)
+        sp3d.halo_pack(P, M, self.g, c, self.dt)
+        sp3d.halo_unpack(P, M, self.g, c, self.dt)
+        return P
+
+    def volume(self, P, c):
+        V = torch.empty((self.g.n, self.g.d, self.g.h, self.g.w, c), dtype=P.dtype, device="cuda")
+        sp3d.sp_unpartition(P, V, self.g, c, self.dt)
+        return V
+
+    def fwd(self, x, w, bias=None, relu=False):
+        Px = self.padded(x, self.cin)
+        Py = sp3d.alloc_padded(self.g, self.cout, self.dt)
+        b = None if bias is None else torch.from_numpy(np.asarray(bias, dtype=np.float32)).cuda()
+        sp3d.conv3d_fwd(Px, to_dev(w), b, Py, self.g, self.cin, self.cout, self.dt,
+                        sp3d.SP_FLAG_RELU if relu else 0, self.ws[sp3d.SP_OP_FWD])
+        return self.volume(Py, self.cout)
+
+    def dgrad(self, dz, w):
+        Pz = self.padded(dz, self.cout)
+        Pdx = sp3d.alloc_padded(self.g, self.cin, self.dt)
+        sp3d.conv3d_dgrad(Pz, to_dev(w), Pdx, self.g, self.cin, self.cout, self.dt,
+                          self.ws[sp3d.SP_OP_DGRAD])
+        return self.volume(Pdx, self.cin)
+
+    def wgrad(self, x, dz, want_db=True):
+        Px = self.padded(x, self.cin)
+        Pz = sp3d.alloc_padded(self.g, self.cout, self.dt)
+        sp3d.sp_partition(to_dev(dz), Pz, self.g, self.cout, self.dt)      # margins not needed
+        dw = torch.full((3, 3, 3, self.cin, self.cout), 123.0, dtype=torch.float32, device="cuda")
+        db = torch.full((self.cout,), 123.0, dtype=torch.float32, device="cuda") if want_db else None
+        sp3d.conv3d_wgrad(Px, Pz, dw, db, self.g, self.cin, self.cout, self.dt,
+                          self.ws[sp3d.SP_OP_WGRAD])
+        return dw, db
+
+
+def draw(dtype, shape, seed, std=1.0):
+    return synth.normal_volume(shape, seed, dtype, std=std)
+
+
+SMALL = [
+    # n, dhw, grid, cin, cout, dtype
+    (1, (8, 8, 8), (2, 2, 1), 8, 16, "f32"),
+    (2, (6, 4, 10), (3, 2, 5), 3, 5, "f32"),
+    (1, (3, 2, 5), (3, 2, 5), 2, 2, "bf16"),          # 1-voxel tiles
+    (1, (8, 12, 16), (2, 2, 2), 1, 32, "bf16"),       # first-layer shape
+    (1, (8, 16, 64), (2, 2, 1), 32, 32, "bf16"),      # the 32->32 shape, whole 8x32 patches
+    (1, (12, 20, 72), (2, 2, 1), 32, 32, "bf16"),     # ragged rows and columns
+    (1, (6, 10, 40), (1, 1, 2), 32, 32, "bf16"),      # split along W
+    (2, (4, 8, 32), (2, 1, 1), 32, 32, "bf16"),       # batch 2
+    (1, (4, 8, 16), (1, 2, 2), 64, 32, "bf16"),
+    (1, (4, 8, 16), (1, 2, 2), 32, 64, "bf16"),
+    (1, (5, 3, 7), (1, 1, 1), 16, 48, "bf16"),
+]
+
+
+@pytest.mark.parametrize("n,dhw,grid,cin,cout,dtype", SMALL)
+def test_fwd_dgrad_wgrad_match_oracle(n, dhw, grid, cin, cout, dtype):
+    L = Layer(n, dhw, grid, cin, cout, dtype)
+    x = draw(dtype, (n,) + dhw + (cin,), 1)
+    dz = draw(dtype, (n,) + dhw + (cout,), 2)
+    w = synth.weights(cin, cout, 3, dtype)
+    bias = np.linspace(-0.5, 0.5, cout).astype(np.float32)
+    tol = TOL[dtype]
+
+    for relu in (False, True):
+        y = L.fwd(x, w, bias, relu)
+        ref = conv3d.conv3d_fwd(x, widen(w), bias.astype(np.float64), relu)
+        assert rel_err(f64(y), ref) <= tol, ("fwd", relu)
+    dx = L.dgrad(dz, w)
+    assert rel_err(f64(dx), conv3d.conv3d_dgrad(dz, widen(w))) <= tol
+    dw, db = L.wgrad(x, dz)
+    assert rel_err(f64(dw), conv3d.conv3d_wgrad(x, dz)) <= tol
+    assert rel_err(f64(db), conv3d.bias_grad(dz)) <= tol
+    # reproducible run to run (fixed-order reduction)
+    dw2, db2 = L.wgrad(x, dz)
+    assert torch.equal(dw, dw2) and torch.equal(db, db2)
+    dw3, none = L.wgrad(x, dz, want_db=False)
+    assert none is None and torch.equal(dw, dw3)
+
+
+@pytest.mark.parametrize("dtype,c", [("bf16", 32), ("f32", 4), ("bf16", 3)])
+def test_identity_and_shift_kernels_are_exact_across_tile_borders(dtype, c):
+    """One-hot taps copy the input shifted by tap-1 with zero fill: exact in any precision, and each
+    of the 26 off-centre taps reads through a different halo region."""
+    n, dhw, grid = 1, (4, 6, 64), (2, 3, 2)
+    L = Layer(n, dhw, grid, c, c, dtype)
+    x = draw(dtype, (n,) + dhw + (c,), 5)
+    xv = widen(x)
+    for tap in itertools.product(range(3), repeat=3):
+        wf = np.zeros((3, 3, 3, c, c), dtype=np.float32)
+        wf[tap] = np.eye(c)
+        w = synth.f32_to_bf16_bits(wf) if dtype == "bf16" else wf
+        y = f64(L.fwd(x, w))
+        expect = np.zeros_like(xv)
+        src = [slice(max(0, t - 1), e + min(0, t - 1)) for t, e in zip(tap, dhw)]
+        dst = [slice(max(0, 1 - t), e + min(0, 1 - t)) for t, e in zip(tap, dhw)]
+        expect[(0,) + tuple(dst)] = xv[(0,) + tuple(src)]
+        assert np.array_equal(y, expect), tap
+        # dgrad with the same one-hot weight shifts the other way
+        dx = f64(L.dgrad(x, w))
+        expect_t = np.zeros_like(xv)
+        expect_t[(0,) + tuple(src)] = xv[(0,) + tuple(dst)]
+        assert np.array_equal(dx, expect_t), tap
+
+
+def test_outputs_touch_interiors_only():
+    """conv3d_* write interior voxels; margins of the output array keep what they held."""
+    n, dhw, grid, c = 1, (8, 8, 32), (2, 2, 1), 32
+    L = Layer(n, dhw, grid, c, c, "bf16")
+    x = draw("bf16", (n,) + dhw + (c,), 7)
+    w = synth.weights(c, c, 8, "bf16")
+    Px = L.padded(x, c)
+    Py = torch.full(L.g.padded_shape + (c,), 3.0, dtype=torch.bfloat16, device="cuda")
+    sp3d.conv3d_fwd(Px, to_dev(w), None, Py, L.g, c, c, L.dt, 0, L.ws[sp3d.SP_OP_FWD])
+    got = Py.float().cpu().numpy()
+    mask = np.ones(got.shape, dtype=bool)
+    mask[(slice(None),) * 4 + (slice(1, -1),) * 3] = False
+    assert np.all(got[mask] == 3.0)
+    Pdx = torch.full(L.g.padded_shape + (c,), 3.0, dtype=torch.bfloat16, device="cuda")
+    sp3d.conv3d_dgrad(Px, to_dev(w), Pdx, L.g, c, c, L.dt, L.ws[sp3d.SP_OP_DGRAD])
+    assert np.all(Pdx.float().cpu().numpy()[mask] == 3.0)
+
+
+def test_configuration_1_fp32_full():
+    """32^3, 8 -> 16 channels, fp32, 2x2x1 grid: tiled GPU output equals the unpartitioned oracle."""
+    c = synth.CONFIGS[1]
+    x, ws, _ = synth.config_tensors(1)
+    L = Layer(c["n"], c["dhw"], c["grid"], 8, 16, "f32")
+    y = L.fwd(x, ws[0], np.zeros(16, dtype=np.float32))
+    assert rel_err(f64(y), conv3d.conv3d_fwd(x, widen(ws[0]))) <= TOL["f32"]

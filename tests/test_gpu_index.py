@@ -1,0 +1,87 @@
+"""GPU parity of the data-movement entry points against the slicing oracle: bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tiling
+from paper_1909_03108_amd import sp3d
+from gpu_util import DT, bits, guard_alloc, guards_intact, to_dev
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # n, dhw, grid, c, dtype
+    (1, (32, 32, 32), (2, 2, 1), 8, "f32"),        # configuration 1 geometry
+    (1, (16, 16, 64), (4, 4, 1), 32, "bf16"),      # configuration 2/4 grid, small
+    (1, (8, 8, 12), (4, 4, 2), 1, "bf16"),         # configuration 3 grid, single channel (2-byte records)
+    (1, (8, 8, 12), (4, 4, 2), 32, "bf16"),
+    (2, (6, 4, 10), (3, 2, 5), 3, "f32"),          # 12-byte records, batch 2
+    (1, (3, 2, 5), (3, 2, 5), 5, "bf16"),          # 1-voxel tiles, 10-byte records
+    (1, (5, 7, 9), (1, 1, 1), 4, "bf16"),          # single tile: every margin is zero fill
+    (1, (24, 40, 72), (2, 2, 1), 32, "bf16"),      # rows longer than one block pass, ragged
+    (1, (4, 6, 260), (2, 3, 2), 16, "f32"),
+]
+
+
+def make_volume(n, dhw, c, dtype, seed):
+    rng = np.random.default_rng(seed)
+    if dtype == "bf16":
+        return rng.integers(1, 0x7F00, size=(n,) + dhw + (c,), dtype=np.uint16)   # distinct-ish bit patterns
+    return rng.standard_normal((n,) + dhw + (c,)).astype(np.float32)
+
+
+@pytest.mark.parametrize("n,dhw,grid,c,dtype", CASES)
+def test_partition_pack_unpack_unpartition_bit_exact(n, dhw, grid, c, dtype):
+    g = sp3d.Geom(n, dhw, grid)
+    dt = DT[dtype]
+    V = make_volume(n, dhw, c, dtype, 11)
+    tdt = sp3d.torch_dtype(dt)
+    fill = 7.0
+    fill_bits = bits(torch.tensor([fill], dtype=tdt, device="cuda"))[0]
+
+    # partition: interiors written, margins untouched (still the fill value)
+    pbuf, P = guard_alloc(g.padded_shape + (c,), tdt, fill)
+    sp3d.sp_partition(to_dev(V), P, g, c, dt)
+    ref_P = tiling.partition(V, grid)
+    got = bits(P)
+    inner = (slice(None),) * 4 + (slice(1, -1),) * 3
+    assert np.array_equal(got[inner], ref_P[inner])
+    mask = np.ones(got.shape, dtype=bool)
+    mask[inner] = False
+    assert np.all(got[mask] == fill_bits)
+    assert guards_intact(pbuf, fill)
+
+    # pack
+    mbuf, M = guard_alloc((sp3d.sp_msg_elems(g, c),), tdt, fill)
+    sp3d.halo_pack(P, M, g, c, dt)
+    ref_M = tiling.halo_pack(ref_P)
+    assert np.array_equal(bits(M).reshape(ref_M.shape), ref_M)
+    assert guards_intact(mbuf, fill)
+
+    # unpack: margins from neighbours or zero; interior untouched
+    sp3d.halo_unpack(P, M, g, c, dt)
+    ref_full = tiling.padded_reference(V, grid)
+    assert np.array_equal(bits(P), ref_full)
+    assert np.array_equal(tiling.halo_unpack(ref_P, ref_M), ref_full)
+    assert guards_intact(pbuf, fill)
+
+    # unpartition
+    vbuf, V2 = guard_alloc((n,) + dhw + (c,), tdt, fill)
+    sp3d.sp_unpartition(P, V2, g, c, dt)
+    assert np.array_equal(bits(V2), V)
+    assert guards_intact(vbuf, fill)
+
+
+def test_relu_bwd_mask_bit_exact():
+    g = sp3d.Geom(1, (6, 4, 10), (3, 2, 5))
+    for dtype in ("bf16", "f32"):
+        dt = DT[dtype]
+        tdt = sp3d.torch_dtype(dt)
+        shape = g.padded_shape + (3,)
+        y = torch.randn(shape, device="cuda").clamp_min(0).to(tdt)
+        y.view(-1)[::7] = -0.0
+        dy = torch.randn(shape, device="cuda").to(tdt)
+        dz = torch.empty_like(dy)
+        sp3d.sp_relu_bwd(dy, y, dz, g, 3, dt)
+        ref = torch.where(y > 0, dy, torch.zeros_like(dy))
+        assert torch.equal(dz, ref)
