@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of the spatially partitioned 3x3x3 convolution hot path on one MI355X.
+
+One "step" is one pass of the whole path over one synthetic 512^3 x 32-channel bf16 volume on a
+4x4x1 tile grid (the one-GPU share at the paper's largest resolution):
+
+    partition x -> halo pack -> halo unpack -> conv3d_fwd -> unpartition y
+    partition dy -> halo pack -> halo unpack -> conv3d_dgrad -> unpartition dx
+    conv3d_wgrad (dw, db)
+
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line (see the design doc for the
+meaning of every field).  `value` is 3 conv passes' FLOPs divided by the whole step time, i.e. it
+is charged for partitioning and halo exchange too.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+# HBM traffic per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (see profiles/ and the design doc for the scaling against a plain copy kernel); None = not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--size", type=int, default=512, help="volume edge (512 = headline workload)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also launch one plain 1 GiB device copy (torch copy_) so that profiler "
+                         "byte counters can be scaled against a kernel of known traffic")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (all tiles of the grid live in one HBM); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1909_03108_amd import sp3d, synth
+
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[4]
+    S = args.size
+    dhw, grid, c = (S, S, S), cfg["grid"], 32
+    n = 1
+    g = sp3d.Geom(n, dhw, grid)
+    dt = sp3d.SP_BF16
+
+    # ---- seeded synthetic inputs (host), then resident in HBM -------------------------------------
+    t0 = time.time()
+    x_h, ws_h, dy_h = synth.config_tensors(4, dhw=dhw)
+    w_h = ws_h[0]
+    t_gen = time.time() - t0
+
+    def dev(a):
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+
+    x_vol, dy_vol, w = dev(x_h), dev(dy_h), dev(w_h)
+    vol_shape = (n,) + dhw + (c,)
+    y_vol = torch.empty(vol_shape, dtype=torch.bfloat16, device="cuda")
+    dx_vol = torch.empty(vol_shape, dtype=torch.bfloat16, device="cuda")
+    Px, Py = sp3d.alloc_padded(g, c, dt), sp3d.alloc_padded(g, c, dt)
+    Pdy, Pdx = sp3d.alloc_padded(g, c, dt), sp3d.alloc_padded(g, c, dt)
+    M = sp3d.alloc_msg(g, c, dt)
+    dw = torch.empty((3, 3, 3, c, c), dtype=torch.float32, device="cuda")
+    db = torch.empty((c,), dtype=torch.float32, device="cuda")
+    wsp = {op: sp3d.alloc_ws(sp3d.sp_workspace_bytes(op, g, c, c, dt)) for op in (0, 1, 2)}
+    stream = torch.cuda.current_stream()
+
+    calls = [
+        ("sp_partition", lambda: sp3d.sp_partition(x_vol, Px, g, c, dt, stream)),
+        ("halo_pack", lambda: sp3d.halo_pack(Px, M, g, c, dt, stream)),
+        ("halo_unpack", lambda: sp3d.halo_unpack(Px, M, g, c, dt, stream)),
+        ("conv3d_fwd", lambda: sp3d.conv3d_fwd(Px, w, None, Py, g, c, c, dt, 0, wsp[0], stream)),
+        ("sp_unpartition", lambda: sp3d.sp_unpartition(Py, y_vol, g, c, dt, stream)),
+        ("sp_partition", lambda: sp3d.sp_partition(dy_vol, Pdy, g, c, dt, stream)),
+        ("halo_pack", lambda: sp3d.halo_pack(Pdy, M, g, c, dt, stream)),
+        ("halo_unpack", lambda: sp3d.halo_unpack(Pdy, M, g, c, dt, stream)),
+        ("conv3d_dgrad", lambda: sp3d.conv3d_dgrad(Pdy, w, Pdx, g, c, c, dt, wsp[1], stream)),
+        ("sp_unpartition", lambda: sp3d.sp_unpartition(Pdx, dx_vol, g, c, dt, stream)),
+        ("conv3d_wgrad", lambda: sp3d.conv3d_wgrad(Px, Pdy, dw, db, g, c, c, dt, wsp[2], stream)),
+    ]
+
+    def step(events=None):
+        for name, f in calls:
+            if events is not None:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                f()
+                e1.record(stream)
+                events.append((name, e0, e1))
+            else:
+                f()
+
+    if args.calib_copy:
+        a = torch.empty((1 << 30,), dtype=torch.uint8, device="cuda")
+        b = torch.ones((1 << 30,), dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()
+        a.copy_(b)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del a, b
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    per = {}
+    for name, e0, e1 in events:
+        per.setdefault(name, []).append(e0.elapsed_time(e1))
+    avg_ms = {k: sum(v) / len(v) for k, v in per.items()}            # per launch
+    count = {k: len(v) // args.steps for k, v in per.items()}        # launches per step
+
+    vox = n * S * S * S
+    flop_pass = 2.0 * 27 * c * c * vox
+    value = 3 * flop_pass / (ms_per_step * 1e-3) / 1e12
+    halo_ms = (avg_ms["halo_pack"] * count["halo_pack"] + avg_ms["halo_unpack"] * count["halo_unpack"])
+    part_ms = (avg_ms["sp_partition"] * count["sp_partition"]
+               + avg_ms["sp_unpartition"] * count["sp_unpartition"])
+    kernel_ms = sum(avg_ms[k] * count[k] for k in avg_ms)
+
+    # dominant kernel: the implicit-GEMM conv kernel behind conv3d_fwd and conv3d_dgrad
+    conv_ms = 0.5 * (avg_ms["conv3d_fwd"] + avg_ms["conv3d_dgrad"])
+    achieved = flop_pass / (conv_ms * 1e-3) / 1e12
+    roofline = {"kernel": "conv_mfma_kernel (conv3d_fwd / conv3d_dgrad)", "bound": "mfma",
+                "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(S)}
+    msg_bytes = sp3d.sp_msg_elems(g, c) * 2
+    other = [
+        {"kernel": "wgrad_mfma_kernel (conv3d_wgrad)", "bound": "mfma",
+         "achieved": round(flop_pass / (avg_ms["conv3d_wgrad"] * 1e-3) / 1e12, 1),
+         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+         "frac": round(flop_pass / (avg_ms["conv3d_wgrad"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)},
+        {"kernel": "halo_pack", "bound": "hbm",
+         "achieved": round(2 * msg_bytes / (avg_ms["halo_pack"] * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
+         "unit": "GB/s", "frac": round(2 * msg_bytes / (avg_ms["halo_pack"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+        {"kernel": "sp_partition", "bound": "hbm",
+         "achieved": round(2 * vox * c * 2 / (avg_ms["sp_partition"] * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
+         "unit": "GB/s",
+         "frac": round(2 * vox * c * 2 / (avg_ms["sp_partition"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+    ]
+
+    out = {
+        "metric": "conv3d fwd+bwd TFLOP/s (bf16) at 512^3 tiles; halo overhead % of step time",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: %d^3 volume, Cin=Cout=32, grid %dx%dx%d, halo 1, "
+                               "fwd+dgrad+wgrad with partition/halo/unpartition"
+                               % (cfg["name"] if S == 512 else "c4 recipe at reduced size", S, *grid),
+                   "input_gen_s": round(t_gen, 1)},
+        "halo_overhead_pct": round(100.0 * halo_ms / kernel_ms, 2),
+        "partition_halo_overhead_pct": round(100.0 * (halo_ms + part_ms) / kernel_ms, 2),
+        "paper_context": "paper reports ~5% of training time for partitioning+reshaping+halo exchange "
+                         "on TPU pods (its own hardware; not a target)",
+        "ms_per_launch": {k: round(v, 4) for k, v in avg_ms.items()},
+        "roofline": roofline,
+        "roofline_other": other,
+    }
+
+    # ---- CPU baseline: the fp64 oracle, as it stands, on a bounded sample of the same workload ----
+    if not args.no_cpu_baseline:
+        from oracle import conv3d as oc
+        b = min(96, S)
+        xs = np.ascontiguousarray(x_h[:, :b, :b, :b])
+        dys = np.ascontiguousarray(dy_h[:, :b, :b, :b])
+        w64 = synth.bf16_bits_to_f32(w_h).astype(np.float64)
+        t0 = time.perf_counter()
+        oc.conv3d_fwd(xs, w64)
+        oc.conv3d_dgrad(dys, w64)
+        oc.conv3d_wgrad(xs, dys)
+        t_cpu = time.perf_counter() - t0
+        out["cpu_baseline"] = {
+            "value": round(3 * 2.0 * 27 * c * c * b ** 3 / t_cpu / 1e12, 5), "unit": "TFLOP/s",
+            "cores": int(os.environ.get("OMP_NUM_THREADS", 0)) or len(os.sched_getaffinity(0)),
+            "kind": "oracle",
+            "sample": "fp64 direct-convolution oracle (gcc -O2 -fopenmp, untuned): fwd + dgrad + wgrad "
+                      "on the %d^3 corner box of the same tensors, %.1f s" % (b, t_cpu)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
