@@ -31,13 +31,19 @@ constexpr int LROWS = PH + 2, LCOLS = PW + 2;
 constexpr int PLANE_VOX = LROWS * LCOLS;    // 340
 constexpr int PLANE_CHUNKS = PLANE_VOX * 4; // 16-byte chunks per plane
 constexpr int ROW_CHUNKS = LCOLS * 4;       // 136
-constexpr int LOADS = (PLANE_CHUNKS + kThreads - 1) / kThreads;   // 6
+constexpr int LOADS = (PLANE_VOX + 63) / 64;   // wave-wide staging loads per chunk plane: 6
+constexpr int NBUF = 3;                     // LDS ring of staged planes
 constexpr int NFRAG = 27 * 2;               // weight fragments per lane (16 bytes each)
 
-// Byte offset of 16-byte chunk c (0..3) of voxel v in a staged plane.  The chunk index is XORed
-// with bits 1..2 of the voxel index so that 8 consecutive voxels at the same logical chunk fall
-// into 8 different 16-byte bank groups (a voxel record is 64 bytes = half of the 128-byte bank row).
-__device__ __forceinline__ int lds_off(int v, int c) { return v * 64 + ((c ^ ((v >> 1) & 3)) << 4); }
+// LDS layout of a staged plane: four chunk planes (16-byte chunk c of every voxel record), each an
+// array of 16-byte entries indexed by the patch-local voxel.  A fragment read (32 consecutive voxels,
+// same chunk) is then 512 contiguous bytes per half wave, and every read address is one per-lane base
+// plus a compile-time offset.  The chunk-plane stride is 342 entries (== 6 mod 8) so that the four
+// chunks of one voxel, written by four neighbouring lanes, fall into different bank groups.
+constexpr int CH_STRIDE = (PLANE_VOX + 2) * 16;     // 5472 bytes
+constexpr int PLANE_BYTES = 4 * CH_STRIDE;          // 21888 bytes
+__device__ __forceinline__ int lds_off(int v, int c) { return c * CH_STRIDE + v * 16; }
+constexpr int LDS_BYTES = NBUF * PLANE_BYTES;
 
 struct ConvArgs {
     const uint16_t *in;
@@ -63,38 +69,56 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t *__res
     wpack[i] = dgrad ? w[((26 - tap) * C + m) * C + k] : w[(tap * C + k) * C + m];
 }
 
+// All MFMAs of one staged input plane.  `lbase` = this lane's read base inside the plane:
+// voxel (first row of the wave, column lane%32), chunk lane/32.  Fragments are fetched one
+// (kw, K-half) group of RH+2 rows ahead of the MFMAs that consume them.
 template <int P>   // P = (input plane index) mod 3
-__device__ __forceinline__ void plane_step(const char *lds, const bf16x8 (&wf)[NFRAG],
-                                           f32x16 (&acc)[3][RH], int wave, int lane) {
-    const int col = lane & 31, hi = lane >> 5;
+__device__ __forceinline__ void plane_step(const char *lbase, const bf16x8 (&wf)[NFRAG],
+                                           f32x16 (&acc)[3][RH]) {
+    constexpr int NG = 6, NR = RH + 2;
+    bf16x8 b[2][NR];
 #pragma unroll
-    for (int kw = 0; kw < 3; ++kw)
+    for (int r = 0; r < NR; ++r)
+        b[0][r] = *reinterpret_cast<const bf16x8 *>(lbase + (r * LCOLS) * 16);
 #pragma unroll
-        for (int half = 0; half < 2; ++half)
+    for (int gi = 0; gi < NG; ++gi) {
+        const int kw = gi >> 1, half = gi & 1;
+        if (gi + 1 < NG) {
+            const int kw2 = (gi + 1) >> 1, half2 = (gi + 1) & 1;
 #pragma unroll
-            for (int r = 0; r < RH + 2; ++r) {
-                const int v = (wave * RH + r) * LCOLS + col + kw;
-                const bf16x8 b = *reinterpret_cast<const bf16x8 *>(lds + lds_off(v, 2 * half + hi));
+            for (int r = 0; r < NR; ++r)
+                b[(gi + 1) & 1][r] = *reinterpret_cast<const bf16x8 *>(
+                    lbase + half2 * 2 * CH_STRIDE + (r * LCOLS + kw2) * 16);
+        }
+        // keep the reads of the next group ahead of this group's MFMAs (the scheduler would
+        // otherwise sink every read to just before its first use and expose the LDS latency)
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int kh = 0; kh < 3; ++kh) {
-                    const int h = r - kh;
-                    if (h < 0 || h >= RH) continue;
+        for (int r = 0; r < NR; ++r)
 #pragma unroll
-                    for (int kd = 0; kd < 3; ++kd) {
-                        const int slot = (P - kd + 3) % 3;
-                        acc[slot][h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            wf[((kd * 3 + kh) * 3 + kw) * 2 + half], b, acc[slot][h], 0, 0, 0);
-                    }
+            for (int kh = 0; kh < 3; ++kh) {
+                const int h = r - kh;
+                if (h < 0 || h >= RH) continue;
+#pragma unroll
+                for (int kd = 0; kd < 3; ++kd) {
+                    const int slot = (P - kd + 3) % 3;
+                    acc[slot][h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        wf[((kd * 3 + kh) * 3 + kw) * 2 + half], b[gi & 1][r], acc[slot][h], 0, 0, 0);
                 }
             }
+    }
 }
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+// two floats -> packed bf16, round to nearest even (one v_cvt_pk_bf16_f32 on gfx950)
 __device__ __forceinline__ uint32_t pack2(float a, float b) {
-    return static_cast<uint32_t>(f32_to_bf16(a)) | (static_cast<uint32_t>(f32_to_bf16(b)) << 16);
+    union { bf16x2 v; uint32_t u; } r;
+    r.v = __builtin_convertvector(f32x2{a, b}, bf16x2);
+    return r.u;
 }
-
 __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
-    extern __shared__ __attribute__((aligned(16))) char lds[];   // 2 planes of PLANE_VOX * 64 bytes
+    extern __shared__ __attribute__((aligned(16))) char lds[];   // NBUF planes of PLANE_BYTES
     const Geo &g = a.g;
     // Consecutive hardware workgroup ids rotate over the 8 XCDs; give each XCD a contiguous range of
     // logical ids so that patches sharing halo rows/columns meet in the same L2.
@@ -120,32 +144,36 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
         wf[f] = *reinterpret_cast<const bf16x8 *>(&q);
     }
 
-    // staging: this thread's chunks of a plane.  Patch-local (row, col) -> padded tile (h0+row, w0+col);
-    // chunks outside the padded tile (ragged patches) are staged as zeros.
-    int src_off[LOADS], dst_off[LOADS];
+    // Staging: global -> LDS directly (no registers in between) with global_load_lds_dwordx4: lane l of
+    // a wave-wide load supplies its own global address and the 16 bytes land at LDS base + 16*l.  Wave
+    // c fills chunk plane c (channels 8c..8c+7 of every voxel): load j covers patch-local voxels
+    // 64j..64j+63, so a plane takes 6 loads per wave.  Voxels outside the padded tile (ragged patches)
+    // are clamped to a valid address; they only feed outputs that are never stored.
+    int goff[LOADS];
 #pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-        const int q = tid + i * kThreads;
-        const int row = q / ROW_CHUNKS, rem = q % ROW_CHUNKS, colv = rem >> 2, c = rem & 3;
-        const bool ok = q < PLANE_CHUNKS && h0 + row < g.ph && w0 + colv < g.pw;
-        src_off[i] = ok ? ((h0 + row) * g.pw + w0 + colv) * C + c * 8 : -1;
-        dst_off[i] = q < PLANE_CHUNKS ? lds_off(row * LCOLS + colv, c) : -1;
+    for (int j = 0; j < LOADS; ++j) {
+        const int v = 64 * j + lane;
+        const int row = min(h0 + v / LCOLS, g.ph - 1), colv = min(w0 + v % LCOLS, g.pw - 1);
+        goff[j] = (row * g.pw + colv) * C + wave * 8;
     }
     const size_t plane_elems = static_cast<size_t>(g.ph) * g.pw * C;
-    uint4 stage[LOADS];
-    auto fetch = [&](int dplane) {   // padded plane index d0 + dplane
+    auto issue = [&](int dplane) {   // padded plane d0 + dplane -> ring buffer dplane % NBUF
         const uint16_t *p = tin + (d0 + dplane) * plane_elems;
+        char *dst = lds + (dplane % NBUF) * PLANE_BYTES + wave * CH_STRIDE;
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i)
-            stage[i] = src_off[i] >= 0 ? *reinterpret_cast<const uint4 *>(p + src_off[i])
-                                       : make_uint4(0, 0, 0, 0);
+        for (int j = 0; j < LOADS; ++j)
+            if (64 * j + lane < PLANE_VOX)
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void *)(p + goff[j]),
+                    (__attribute__((address_space(3))) void *)(dst + j * 1024), 16, 0, 0);
     };
-    auto commit = [&](int buf) {
-        char *base = lds + buf * (PLANE_VOX * 64);
+
+    const int col = lane & 31, hi = lane >> 5;
+    const char *lbase = lds + lds_off(wave * RH * LCOLS + col, hi);
+    // the bias is folded into the accumulators: a slot starts from the bias instead of zero
+    float bv[16];
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i)
-            if (dst_off[i] >= 0) *reinterpret_cast<uint4 *>(base + dst_off[i]) = stage[i];
-    };
+    for (int i = 0; i < 16; ++i) bv[i] = a.bias ? a.bias[8 * (i >> 2) + 4 * hi + (i & 3)] : 0.f;
 
     f32x16 acc[3][RH];
 #pragma unroll
@@ -153,12 +181,7 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
 #pragma unroll
         for (int h = 0; h < RH; ++h)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[s][h][i] = 0.f;
-
-    const int col = lane & 31, hi = lane >> 5;
-    float bv[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) bv[i] = a.bias ? a.bias[8 * (i >> 2) + 4 * hi + (i & 3)] : 0.f;
+            for (int i = 0; i < 16; ++i) acc[s][h][i] = bv[i];
 
     // Finish output plane d (local index) held in `slot`: bias, ReLU, bf16, store, clear.
     auto finish = [&](int d, f32x16 (&s)[RH]) {
@@ -171,8 +194,8 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
                                   4 * hi;
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        float v0 = s[h][4 * q] + bv[4 * q], v1 = s[h][4 * q + 1] + bv[4 * q + 1];
-                        float v2 = s[h][4 * q + 2] + bv[4 * q + 2], v3 = s[h][4 * q + 3] + bv[4 * q + 3];
+                        float v0 = s[h][4 * q], v1 = s[h][4 * q + 1];
+                        float v2 = s[h][4 * q + 2], v3 = s[h][4 * q + 3];
                         if (a.relu) {
                             v0 = v0 > 0.f ? v0 : 0.f; v1 = v1 > 0.f ? v1 : 0.f;
                             v2 = v2 > 0.f ? v2 : 0.f; v3 = v3 > 0.f ? v3 : 0.f;
@@ -185,12 +208,14 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
 #pragma unroll
         for (int h = 0; h < RH; ++h)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) s[h][i] = 0.f;
+            for (int i = 0; i < 16; ++i) s[h][i] = bv[i];
     };
 
-    // prologue: plane 0 into buffer 0
-    fetch(0);
-    commit(0);
+    // Prologue: planes 0 and 1 in flight; plane 0 must have landed before the first MFMA.
+    // Loads complete in issue order, so "at most LOADS outstanding" means every older one is done.
+    issue(0);
+    issue(1);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
     __syncthreads();
 
     const int nplanes = dn + 2;
@@ -199,14 +224,20 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
         for (int p = 0; p < 3; ++p) {
             const int Dp = D + p;
             if (Dp < nplanes) {
-                const int buf = Dp & 1;
-                if (Dp + 1 < nplanes) fetch(Dp + 1);
-                const char *cur = lds + buf * (PLANE_VOX * 64);
-                if (p == 0) plane_step<0>(cur, wf, acc, wave, lane);
-                else if (p == 1) plane_step<1>(cur, wf, acc, wave, lane);
-                else plane_step<2>(cur, wf, acc, wave, lane);
-                if (Dp + 1 < nplanes) commit(buf ^ 1);
-                __syncthreads();
+                // plane Dp+2 goes into the buffer that held plane Dp-1 (or Dp-2): every wave left that
+                // plane behind at the barrier that ended the previous step
+                const bool more = Dp + 2 < nplanes;
+                if (more) issue(Dp + 2);
+                const char *cur = lbase + (Dp % NBUF) * PLANE_BYTES;
+                if (p == 0) plane_step<0>(cur, wf, acc);
+                else if (p == 1) plane_step<1>(cur, wf, acc);
+                else plane_step<2>(cur, wf, acc);
+                // plane Dp+1 must be complete before anyone reads it in the next step; only the
+                // loads of plane Dp+2, issued after it, may still be in flight
+                // (a bare s_barrier: __syncthreads() would make the compiler drain every staging load)
+                if (more) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
                 // output plane Dp-2 has now received all three kd contributions
                 finish(Dp - 2, acc[(p + 1) % 3]);
             }
@@ -249,7 +280,7 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
     a.nblocks = static_cast<int>(nb);
     a.relu = relu ? 1 : 0;
     const unsigned grid = static_cast<unsigned>((nb + 7) / 8 * 8);
-    hipLaunchKernelGGL(conv_mfma_kernel, dim3(grid), dim3(kThreads), 2 * PLANE_VOX * 64, s, a);
+    hipLaunchKernelGGL(conv_mfma_kernel, dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
     return record_hip(hipGetLastError());
 }
 
