@@ -2,25 +2,32 @@
 // cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation).  Serves conv3d_fwd and, with mirrored taps
 // and swapped channel roles, conv3d_dgrad.
 //
-// Work decomposition.  A workgroup (4 waves) owns an output patch of 8 rows (H) x 32 columns (W)
-// of one tile and marches along D.  Each input plane (10 x 34 voxels x 32 channels, 21.25 KB) is
-// staged once in LDS (double buffered: the next plane is fetched from HBM into registers while the
-// current one is consumed).  A wave owns 2 of the 8 rows and keeps the accumulators of THREE
-// consecutive output planes in registers: input plane D feeds output planes D, D-1, D-2 through
-// taps kd = 0, 1, 2, so an input fragment read from LDS once is used by up to 3 (kd) x 2 (kh)
-// MFMAs.  All 27 x 2 weight fragments (32 x 16 each) live in registers for the whole march.
+// Work decomposition.  A workgroup (4 waves, one per SIMD) owns an output patch of 8 rows (H) x 32
+// columns (W) of one tile and marches along D.  Each input plane (10 x 34 voxels x 32 channels) is
+// staged once in LDS by direct global->LDS loads, three planes ahead of the plane being consumed
+// (ring of four).  A wave owns 2 of the 8 rows and keeps the accumulators of consecutive output
+// planes in registers: input plane D feeds output planes D, D-1, D-2 through taps kd = 0, 1, 2, so an
+// input fragment read from LDS once is used by up to 3 (kd) x 2 (kh) MFMAs.  A fourth accumulator
+// slot holds the plane finished in the previous step, whose conversion and stores are spread over
+// the MFMA stream of the current step.  All 27 x 2 weight fragments (32 x 16 each) live in
+// registers for the whole march.
 //
 // MFMA operand roles: A = weights [M = Cout][K = 16 input channels], B = voxels [K][N = 32 voxels
 // along W], D[M = Cout][N = voxel].  Lane l of B supplies voxel l%32, channels 8*(l/32)..+7 of the
 // 16-channel half; lane l of D holds voxel l%32, channels 8*(i/4) + 4*(l/32) + i%4 for i = 0..15.
 #include "common.h"
 
+#ifndef SP3D_EXP
+#define SP3D_EXP 0
+#endif
 namespace sp3d {
 
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int C = 32;                       // channels in and out
 constexpr int kWaves = 4, kThreads = 256;
@@ -29,21 +36,21 @@ constexpr int PH = RH * kWaves;             // patch rows
 constexpr int PW = 32;                      // patch columns = MFMA N
 constexpr int LROWS = PH + 2, LCOLS = PW + 2;
 constexpr int PLANE_VOX = LROWS * LCOLS;    // 340
-constexpr int PLANE_CHUNKS = PLANE_VOX * 4; // 16-byte chunks per plane
-constexpr int ROW_CHUNKS = LCOLS * 4;       // 136
 constexpr int LOADS = (PLANE_VOX + 63) / 64;   // wave-wide staging loads per chunk plane: 6
-constexpr int NBUF = 3;                     // LDS ring of staged planes
+constexpr int NBUF = 4;                     // LDS ring of staged planes
+constexpr int DIST = 3;                     // planes fetched ahead of the one being consumed
 constexpr int NFRAG = 27 * 2;               // weight fragments per lane (16 bytes each)
+constexpr int NG = 6;                       // (kw, K-half) groups per plane
+static_assert(LOADS == NG, "one staging load is issued per MFMA group");
 
 // LDS layout of a staged plane: four chunk planes (16-byte chunk c of every voxel record), each an
 // array of 16-byte entries indexed by the patch-local voxel.  A fragment read (32 consecutive voxels,
 // same chunk) is then 512 contiguous bytes per half wave, and every read address is one per-lane base
-// plus a compile-time offset.  The chunk-plane stride is 342 entries (== 6 mod 8) so that the four
-// chunks of one voxel, written by four neighbouring lanes, fall into different bank groups.
+// plus a compile-time offset.
 constexpr int CH_STRIDE = (PLANE_VOX + 2) * 16;     // 5472 bytes
 constexpr int PLANE_BYTES = 4 * CH_STRIDE;          // 21888 bytes
+constexpr int LDS_BYTES = NBUF * PLANE_BYTES;       // 87552 bytes
 __device__ __forceinline__ int lds_off(int v, int c) { return c * CH_STRIDE + v * 16; }
-constexpr int LDS_BYTES = NBUF * PLANE_BYTES;
 
 struct ConvArgs {
     const uint16_t *in;
@@ -69,13 +76,23 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t *__res
     wpack[i] = dgrad ? w[((26 - tap) * C + m) * C + k] : w[(tap * C + k) * C + m];
 }
 
-// All MFMAs of one staged input plane.  `lbase` = this lane's read base inside the plane:
-// voxel (first row of the wave, column lane%32), chunk lane/32.  Fragments are fetched one
-// (kw, K-half) group of RH+2 rows ahead of the MFMAs that consume them.
-template <int P>   // P = (input plane index) mod 3
+// two floats -> packed bf16, round to nearest even (one v_cvt_pk_bf16_f32 on gfx950)
+__device__ __forceinline__ uint32_t pack2(float a, float b) {
+    union { bf16x2 v; uint32_t u; } r;
+    r.v = __builtin_convertvector(f32x2{a, b}, bf16x2);
+    return r.u;
+}
+
+// All MFMAs of one staged input plane, with the step's side work (staging loads for a later plane,
+// conversion and stores of the plane finished one step earlier) spread over the six MFMA groups.
+// `lbase` = this lane's read base inside the plane: voxel (first row of the wave, column lane%32),
+// chunk lane/32.  Fragments are fetched one (kw, K-half) group of RH+2 rows ahead of the MFMAs that
+// consume them.  P = (input plane index) mod 4: output plane D-kd lives in slot (P-kd) mod 4 and the
+// plane finished in the previous step in slot (P-3) mod 4.
+template <int P, typename Side>
 __device__ __forceinline__ void plane_step(const char *lbase, const bf16x8 (&wf)[NFRAG],
-                                           f32x16 (&acc)[3][RH]) {
-    constexpr int NG = 6, NR = RH + 2;
+                                           f32x16 (&acc)[4][RH], Side &&side) {
+    constexpr int NR = RH + 2;
     bf16x8 b[2][NR];
 #pragma unroll
     for (int r = 0; r < NR; ++r)
@@ -93,6 +110,7 @@ __device__ __forceinline__ void plane_step(const char *lbase, const bf16x8 (&wf)
         // keep the reads of the next group ahead of this group's MFMAs (the scheduler would
         // otherwise sink every read to just before its first use and expose the LDS latency)
         __builtin_amdgcn_sched_barrier(0);
+        side(gi, acc[(P + 1) & 3]);
 #pragma unroll
         for (int r = 0; r < NR; ++r)
 #pragma unroll
@@ -101,7 +119,7 @@ __device__ __forceinline__ void plane_step(const char *lbase, const bf16x8 (&wf)
                 if (h < 0 || h >= RH) continue;
 #pragma unroll
                 for (int kd = 0; kd < 3; ++kd) {
-                    const int slot = (P - kd + 3) % 3;
+                    const int slot = (P - kd + 4) & 3;
                     acc[slot][h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                         wf[((kd * 3 + kh) * 3 + kw) * 2 + half], b[gi & 1][r], acc[slot][h], 0, 0, 0);
                 }
@@ -109,14 +127,7 @@ __device__ __forceinline__ void plane_step(const char *lbase, const bf16x8 (&wf)
     }
 }
 
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-// two floats -> packed bf16, round to nearest even (one v_cvt_pk_bf16_f32 on gfx950)
-__device__ __forceinline__ uint32_t pack2(float a, float b) {
-    union { bf16x2 v; uint32_t u; } r;
-    r.v = __builtin_convertvector(f32x2{a, b}, bf16x2);
-    return r.u;
-}
+template <bool HAS_BIAS>
 __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];   // NBUF planes of PLANE_BYTES
     const Geo &g = a.g;
@@ -148,7 +159,9 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
     // a wave-wide load supplies its own global address and the 16 bytes land at LDS base + 16*l.  Wave
     // c fills chunk plane c (channels 8c..8c+7 of every voxel): load j covers patch-local voxels
     // 64j..64j+63, so a plane takes 6 loads per wave.  Voxels outside the padded tile (ragged patches)
-    // are clamped to a valid address; they only feed outputs that are never stored.
+    // are clamped to a valid address; they only feed outputs that are never stored.  Planes past the
+    // last one needed are clamped too (their ring slot is never read), so every step issues exactly
+    // LOADS loads and the wait counts below hold without branches.
     int goff[LOADS];
 #pragma unroll
     for (int j = 0; j < LOADS; ++j) {
@@ -157,99 +170,128 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
         goff[j] = (row * g.pw + colv) * C + wave * 8;
     }
     const size_t plane_elems = static_cast<size_t>(g.ph) * g.pw * C;
-    auto issue = [&](int dplane) {   // padded plane d0 + dplane -> ring buffer dplane % NBUF
-        const uint16_t *p = tin + (d0 + dplane) * plane_elems;
-        char *dst = lds + (dplane % NBUF) * PLANE_BYTES + wave * CH_STRIDE;
-#pragma unroll
-        for (int j = 0; j < LOADS; ++j)
-            if (64 * j + lane < PLANE_VOX)
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)(p + goff[j]),
-                    (__attribute__((address_space(3))) void *)(dst + j * 1024), 16, 0, 0);
+    const int nplanes = dn + 2;
+    auto stage = [&](int dplane, int j) {   // load j of padded plane d0 + dplane -> ring slot dplane % NBUF
+#if (SP3D_EXP & 8)
+        const uint16_t *p = tin + (d0 + min(dplane, 0)) * plane_elems;
+#else
+        const uint16_t *p = tin + (d0 + min(dplane, nplanes - 1)) * plane_elems;
+#endif
+        char *dst = lds + (dplane % NBUF) * PLANE_BYTES + wave * CH_STRIDE + j * 1024;
+        if (64 * j + lane < PLANE_VOX)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p + goff[j]),
+                                             (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
     };
 
     const int col = lane & 31, hi = lane >> 5;
     const char *lbase = lds + lds_off(wave * RH * LCOLS + col, hi);
     // the bias is folded into the accumulators: a slot starts from the bias instead of zero
-    float bv[16];
+    // (without a bias the slots start from the constant zero and no registers are spent on it)
+    float bv[HAS_BIAS ? 16 : 1];
+    if (HAS_BIAS) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) bv[i] = a.bias ? a.bias[8 * (i >> 2) + 4 * hi + (i & 3)] : 0.f;
-
-    f32x16 acc[3][RH];
+        for (int i = 0; i < 16; ++i) bv[HAS_BIAS ? i : 0] = a.bias[8 * (i >> 2) + 4 * hi + (i & 3)];
+    }
+    f32x16 acc[4][RH];
 #pragma unroll
-    for (int s = 0; s < 3; ++s)
+    for (int s = 0; s < 4; ++s)
 #pragma unroll
         for (int h = 0; h < RH; ++h)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[s][h][i] = bv[i];
+            for (int i = 0; i < 16; ++i) acc[s][h][i] = HAS_BIAS ? bv[HAS_BIAS ? i : 0] : 0.f;
 
-    // Finish output plane d (local index) held in `slot`: bias, ReLU, bf16, store, clear.
-    auto finish = [&](int d, f32x16 (&s)[RH]) {
-        if (d >= 0 && d < dn) {
+    // Output side.  Lane (voxel col, channel group hi) stores 4 channels (8 bytes) per unit (h, q):
+    // channels 8q + 4hi .. +3 of row h.  Rows / columns outside the tile interior are masked.
+    bool okrow[RH];
 #pragma unroll
-            for (int h = 0; h < RH; ++h) {
-                const int oh = h0 + wave * RH + h, ow = w0 + col;
-                if (oh < g.th && ow < g.tw) {
-                    uint16_t *o = tout + ((static_cast<size_t>(d0 + d + 1) * g.ph + oh + 1) * g.pw + ow + 1) * C +
-                                  4 * hi;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        float v0 = s[h][4 * q], v1 = s[h][4 * q + 1];
-                        float v2 = s[h][4 * q + 2], v3 = s[h][4 * q + 3];
-                        if (a.relu) {
-                            v0 = v0 > 0.f ? v0 : 0.f; v1 = v1 > 0.f ? v1 : 0.f;
-                            v2 = v2 > 0.f ? v2 : 0.f; v3 = v3 > 0.f ? v3 : 0.f;
-                        }
-                        *reinterpret_cast<uint2 *>(o + 8 * q) = make_uint2(pack2(v0, v1), pack2(v2, v3));
-                    }
-                }
-            }
+    for (int h = 0; h < RH; ++h) okrow[h] = h0 + wave * RH + h < g.th && w0 + col < g.tw;
+    const size_t orow = static_cast<size_t>(g.pw) * C;
+    uint16_t *obase = tout + ((static_cast<size_t>(d0 + 1) * g.ph + h0 + wave * RH + 1) * g.pw + w0 + col + 1) * C +
+                      4 * hi;
+    auto store_unit = [&](int d, const f32x16 (&s)[RH], int h, int q) {
+        float v0 = s[h][4 * q], v1 = s[h][4 * q + 1], v2 = s[h][4 * q + 2], v3 = s[h][4 * q + 3];
+        if (a.relu) {
+            v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f);
         }
+        const uint2 pk = make_uint2(pack2(v0, v1), pack2(v2, v3));
+#if (SP3D_EXP & 16)
+        if (okrow[h]) *reinterpret_cast<uint2 *>(obase + min(d, 0) * plane_elems + h * orow + 8 * q) = pk;
+#else
+        if (okrow[h]) *reinterpret_cast<uint2 *>(obase + d * plane_elems + h * orow + 8 * q) = pk;
+#endif
+    };
+    auto reset_half = [&](f32x16 (&s)[RH], int h) {
 #pragma unroll
-        for (int h = 0; h < RH; ++h)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) s[h][i] = bv[i];
+        for (int i = 0; i < 16; ++i) s[h][i] = HAS_BIAS ? bv[HAS_BIAS ? i : 0] : 0.f;
     };
 
-    // Prologue: planes 0 and 1 in flight; plane 0 must have landed before the first MFMA.
-    // Loads complete in issue order, so "at most LOADS outstanding" means every older one is done.
-    issue(0);
-    issue(1);
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
+    // Prologue: planes 0 .. DIST-1 in flight; plane 0 must have landed before the first MFMA.
+#pragma unroll
+    for (int i = 0; i < DIST; ++i)
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) stage(i, j);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
-    const int nplanes = dn + 2;
-    for (int D = 0; D < nplanes; D += 3) {
+    // One step per input plane Dp.  Side work of step Dp: stage plane Dp+DIST (one load per MFMA
+    // group) and, from the fourth step on, convert and store output plane Dp-3, which received its last
+    // contribution in step Dp-1, then return its accumulator slot to the bias.
+    for (int D = 0; D < nplanes; D += 4) {
 #pragma unroll
-        for (int p = 0; p < 3; ++p) {
+        for (int p = 0; p < 4; ++p) {
             const int Dp = D + p;
             if (Dp < nplanes) {
-                // plane Dp+2 goes into the buffer that held plane Dp-1 (or Dp-2): every wave left that
-                // plane behind at the barrier that ended the previous step
-                const bool more = Dp + 2 < nplanes;
-                if (more) issue(Dp + 2);
+                const bool epi = Dp >= 3;     // Dp - 3 < dn always holds inside the loop
+                auto side = [&](int gi, f32x16 (&done)[RH]) {
+                    stage(Dp + DIST, gi);
+                    if (gi < 4) {
+                        if (epi) {
+                            store_unit(Dp - 3, done, 0, gi);
+                            store_unit(Dp - 3, done, 1, gi);
+                        }
+                    } else {
+                        reset_half(done, gi - 4);
+                    }
+                };
                 const char *cur = lbase + (Dp % NBUF) * PLANE_BYTES;
-                if (p == 0) plane_step<0>(cur, wf, acc);
-                else if (p == 1) plane_step<1>(cur, wf, acc);
-                else plane_step<2>(cur, wf, acc);
-                // plane Dp+1 must be complete before anyone reads it in the next step; only the
-                // loads of plane Dp+2, issued after it, may still be in flight
-                // (a bare s_barrier: __syncthreads() would make the compiler drain every staging load)
-                if (more) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
-                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                if (p == 0) plane_step<0>(cur, wf, acc, side);
+                else if (p == 1) plane_step<1>(cur, wf, acc, side);
+                else if (p == 2) plane_step<2>(cur, wf, acc, side);
+                else plane_step<3>(cur, wf, acc, side);
+                // Plane Dp+1 must be complete before anyone reads it in the next step.  Loads complete in
+                // issue order and the only loads issued after plane Dp+1's are those of planes Dp+2 and
+                // Dp+3, so "at most 2*LOADS vector memory operations outstanding" implies it is done
+                // (stores share the counter and only make the wait more conservative).  A bare
+                // s_barrier: __syncthreads() would make the compiler drain every staging load.
+#if (SP3D_EXP & 4)
+                asm volatile("s_waitcnt vmcnt(30)" ::: "memory");
+#else
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DIST - 1) * LOADS) : "memory");
+#endif
                 __builtin_amdgcn_s_barrier();
-                // output plane Dp-2 has now received all three kd contributions
-                finish(Dp - 2, acc[(p + 1) % 3]);
             }
         }
+    }
+    // the last output plane finished in the last step
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    {
+        const int slot = (nplanes - 3) & 3;     // plane dn-1 = step nplanes-1 minus kd = 2
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+            if (s == slot) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    store_unit(dn - 1, acc[s], 0, q);
+                    store_unit(dn - 1, acc[s], 1, q);
+                }
+            }
     }
 }
 
 }  // namespace
 
 bool conv_mfma_supported(const Geo &g, int ki, int ko, sp_dtype_t dt) {
-    (void)g;
-    return dt == SP_BF16 && ki == C && ko == C;
+    return dt == SP_BF16 && ki == C && ko == C && 1LL * g.ph * g.pw * C < 0x7fffffffLL;
 }
 
 size_t conv_mfma_ws_bytes(const Geo &, int, int) { return static_cast<size_t>(NFRAG) * 64 * 16; }
@@ -280,7 +322,19 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
     a.nblocks = static_cast<int>(nb);
     a.relu = relu ? 1 : 0;
     const unsigned grid = static_cast<unsigned>((nb + 7) / 8 * 8);
-    hipLaunchKernelGGL(conv_mfma_kernel, dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
+    // more than 64 KB of dynamic LDS has to be requested explicitly
+    static const hipError_t attr0 = hipFuncSetAttribute(
+        reinterpret_cast<const void *>(conv_mfma_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize,
+        LDS_BYTES);
+    static const hipError_t attr1 = hipFuncSetAttribute(
+        reinterpret_cast<const void *>(conv_mfma_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize,
+        LDS_BYTES);
+    if (attr0 != hipSuccess) return record_hip(attr0);
+    if (attr1 != hipSuccess) return record_hip(attr1);
+    if (bias)
+        hipLaunchKernelGGL(conv_mfma_kernel<true>, dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
+    else
+        hipLaunchKernelGGL(conv_mfma_kernel<false>, dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
     return record_hip(hipGetLastError());
 }
 
