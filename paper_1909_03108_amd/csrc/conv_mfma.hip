@@ -17,9 +17,8 @@
 // 16-channel half; lane l of D holds voxel l%32, channels 8*(i/4) + 4*(l/32) + i%4 for i = 0..15.
 #include "common.h"
 
-#ifndef SP3D_EXP
-#define SP3D_EXP 0
-#endif
+#include <type_traits>
+
 namespace sp3d {
 
 namespace {
@@ -83,16 +82,58 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
     return r.u;
 }
 
-// All MFMAs of one staged input plane, with the step's side work (staging loads for a later plane,
-// conversion and stores of the plane finished one step earlier) spread over the six MFMA groups.
+// Per-wave state of the march that the side work of a step needs.
+template <bool HAS_BIAS>
+struct Ctx {
+    const uint16_t *tin0;       // first padded input plane of this workgroup's D chunk
+    size_t plane_elems;         // elements per padded plane of the tile
+    int nplanes;                // input planes of the chunk (output planes + 2)
+    int goff[LOADS];            // per-lane source offsets of the staging loads (elements)
+    char *lds_stage;            // LDS chunk plane this wave fills (ring slot 0)
+    uint16_t *obase;            // output address of (plane 0, first row of the wave, this lane)
+    size_t orow;                // elements per padded row
+    bool okrow[RH];             // row/column of this lane lies inside the tile interior
+    float bv[HAS_BIAS ? 16 : 1];
+};
+
+// Staging load j of padded plane `dplane` of the chunk -> ring slot dplane % NBUF.  global_load_lds:
+// lane l supplies its own global address and the 16 bytes land at LDS base + 16*l.  Planes past the last
+// one needed are clamped (their ring slot is never read), so every step issues exactly LOADS loads.
+template <bool HAS_BIAS>
+__device__ __forceinline__ void stage(const Ctx<HAS_BIAS> &c, int dplane, int j, int lane) {
+    const uint16_t *p = c.tin0 + min(dplane, c.nplanes - 1) * c.plane_elems;
+    char *dst = c.lds_stage + (dplane % NBUF) * PLANE_BYTES + j * 1024;
+    if (64 * j + lane < PLANE_VOX)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p + c.goff[j]),
+                                         (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+}
+
+// Convert and store 4 channels (8 bytes) of row h of a finished plane: channels 8q + 4*(lane/32) .. +3.
+template <bool RELU, bool FULL, bool HAS_BIAS>
+__device__ __forceinline__ void store_unit(const Ctx<HAS_BIAS> &c, int d, const f32x16 (&s)[RH], int h, int q) {
+    float v0 = s[h][4 * q], v1 = s[h][4 * q + 1], v2 = s[h][4 * q + 2], v3 = s[h][4 * q + 3];
+    if (RELU) {
+        v0 = v0 < 0.f ? 0.f : v0; v1 = v1 < 0.f ? 0.f : v1;
+        v2 = v2 < 0.f ? 0.f : v2; v3 = v3 < 0.f ? 0.f : v3;
+    }
+    const uint2 pk = make_uint2(pack2(v0, v1), pack2(v2, v3));
+    uint2 *o = reinterpret_cast<uint2 *>(c.obase + d * c.plane_elems + h * c.orow + 8 * q);
+    if (FULL || c.okrow[h]) *o = pk;
+}
+
+// All MFMAs of one staged input plane Dp, with the step's side work spread over the six MFMA groups:
+// the staging loads of plane Dp+DIST and (EPI) the conversion and stores of output plane Dp-3, which
+// received its last contribution in step Dp-1, after which its accumulator slot returns to the bias.
 // `lbase` = this lane's read base inside the plane: voxel (first row of the wave, column lane%32),
 // chunk lane/32.  Fragments are fetched one (kw, K-half) group of RH+2 rows ahead of the MFMAs that
-// consume them.  P = (input plane index) mod 4: output plane D-kd lives in slot (P-kd) mod 4 and the
-// plane finished in the previous step in slot (P-3) mod 4.
-template <int P, typename Side>
-__device__ __forceinline__ void plane_step(const char *lbase, const bf16x8 (&wf)[NFRAG],
-                                           f32x16 (&acc)[4][RH], Side &&side) {
+// consume them.  P = Dp mod 4: output plane Dp-kd lives in slot (P-kd) mod 4, plane Dp-3 in slot (P+1) mod 4.
+// FULL: the patch lies completely inside the tile interior, so stores need no mask (no branches in
+// the step, which lets the scheduler weave the side work between the MFMAs).
+template <int P, bool EPI, bool RELU, bool FULL, bool HAS_BIAS>
+__device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, int lane, const char *lbase,
+                                           const bf16x8 (&wf)[NFRAG], f32x16 (&acc)[4][RH]) {
     constexpr int NR = RH + 2;
+    constexpr int DONE = (P + 1) & 3;
     bf16x8 b[2][NR];
 #pragma unroll
     for (int r = 0; r < NR; ++r)
@@ -110,7 +151,16 @@ __device__ __forceinline__ void plane_step(const char *lbase, const bf16x8 (&wf)
         // keep the reads of the next group ahead of this group's MFMAs (the scheduler would
         // otherwise sink every read to just before its first use and expose the LDS latency)
         __builtin_amdgcn_sched_barrier(0);
-        side(gi, acc[(P + 1) & 3]);
+        stage(c, Dp + DIST, gi, lane);
+        if (gi < 4) {
+            if (EPI) {
+                store_unit<RELU, FULL>(c, Dp - 3, acc[DONE], 0, gi);
+                store_unit<RELU, FULL>(c, Dp - 3, acc[DONE], 1, gi);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[DONE][gi - 4][i] = HAS_BIAS ? c.bv[HAS_BIAS ? i : 0] : 0.f;
+        }
 #pragma unroll
         for (int r = 0; r < NR; ++r)
 #pragma unroll
@@ -124,10 +174,17 @@ __device__ __forceinline__ void plane_step(const char *lbase, const bf16x8 (&wf)
                         wf[((kd * 3 + kh) * 3 + kw) * 2 + half], b[gi & 1][r], acc[slot][h], 0, 0, 0);
                 }
             }
+        // weave: after each MFMA let a few of the side-work instructions issue while it executes
+#pragma unroll
+        for (int i = 0; i < 3 * (RH + 1) * 2; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x006, 3, 0);   // up to three VALU / SALU
+            if (i % 6 == 2) __builtin_amdgcn_sched_group_barrier(0x060, 1, 0);   // a vector memory op
+        }
     }
 }
 
-template <bool HAS_BIAS>
+template <bool HAS_BIAS, bool RELU>
 __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];   // NBUF planes of PLANE_BYTES
     const Geo &g = a.g;
@@ -144,8 +201,7 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
     const int d0 = pd_i * a.dchunk, h0 = ph_i * PH, w0 = pw_i * PW;      // interior coordinates
     const int dn = min(a.dchunk, g.td - d0);                            // output planes to produce
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint16_t *tin = a.in + static_cast<size_t>(tile) * g.tile_vox * C;
-    uint16_t *tout = a.out + static_cast<size_t>(tile) * g.tile_vox * C;
+    const int col = lane & 31, hi = lane >> 5;
 
     // weight fragments: 54 x 16 bytes per lane, resident for the whole march
     bf16x8 wf[NFRAG];
@@ -155,42 +211,30 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
         wf[f] = *reinterpret_cast<const bf16x8 *>(&q);
     }
 
-    // Staging: global -> LDS directly (no registers in between) with global_load_lds_dwordx4: lane l of
-    // a wave-wide load supplies its own global address and the 16 bytes land at LDS base + 16*l.  Wave
-    // c fills chunk plane c (channels 8c..8c+7 of every voxel): load j covers patch-local voxels
-    // 64j..64j+63, so a plane takes 6 loads per wave.  Voxels outside the padded tile (ragged patches)
-    // are clamped to a valid address; they only feed outputs that are never stored.  Planes past the
-    // last one needed are clamped too (their ring slot is never read), so every step issues exactly
-    // LOADS loads and the wait counts below hold without branches.
-    int goff[LOADS];
+    Ctx<HAS_BIAS> c;
+    c.plane_elems = static_cast<size_t>(g.ph) * g.pw * C;
+    c.tin0 = a.in + static_cast<size_t>(tile) * g.tile_vox * C + d0 * c.plane_elems;
+    c.nplanes = dn + 2;
+    // Wave w fills chunk plane w (channels 8w..8w+7 of every voxel); load j covers patch-local voxels
+    // 64j..64j+63.  Voxels outside the padded tile (ragged patches) are clamped to a valid address;
+    // they only feed outputs that are never stored.
 #pragma unroll
     for (int j = 0; j < LOADS; ++j) {
         const int v = 64 * j + lane;
         const int row = min(h0 + v / LCOLS, g.ph - 1), colv = min(w0 + v % LCOLS, g.pw - 1);
-        goff[j] = (row * g.pw + colv) * C + wave * 8;
+        c.goff[j] = (row * g.pw + colv) * C + wave * 8;
     }
-    const size_t plane_elems = static_cast<size_t>(g.ph) * g.pw * C;
-    const int nplanes = dn + 2;
-    auto stage = [&](int dplane, int j) {   // load j of padded plane d0 + dplane -> ring slot dplane % NBUF
-#if (SP3D_EXP & 8)
-        const uint16_t *p = tin + (d0 + min(dplane, 0)) * plane_elems;
-#else
-        const uint16_t *p = tin + (d0 + min(dplane, nplanes - 1)) * plane_elems;
-#endif
-        char *dst = lds + (dplane % NBUF) * PLANE_BYTES + wave * CH_STRIDE + j * 1024;
-        if (64 * j + lane < PLANE_VOX)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p + goff[j]),
-                                             (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
-    };
-
-    const int col = lane & 31, hi = lane >> 5;
-    const char *lbase = lds + lds_off(wave * RH * LCOLS + col, hi);
+    c.lds_stage = lds + wave * CH_STRIDE;
+    c.orow = static_cast<size_t>(g.pw) * C;
+    c.obase = a.out + static_cast<size_t>(tile) * g.tile_vox * C +
+              ((static_cast<size_t>(d0 + 1) * g.ph + h0 + wave * RH + 1) * g.pw + w0 + col + 1) * C + 4 * hi;
+#pragma unroll
+    for (int h = 0; h < RH; ++h) c.okrow[h] = h0 + wave * RH + h < g.th && w0 + col < g.tw;
     // the bias is folded into the accumulators: a slot starts from the bias instead of zero
     // (without a bias the slots start from the constant zero and no registers are spent on it)
-    float bv[HAS_BIAS ? 16 : 1];
     if (HAS_BIAS) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) bv[HAS_BIAS ? i : 0] = a.bias[8 * (i >> 2) + 4 * hi + (i & 3)];
+        for (int i = 0; i < 16; ++i) c.bv[HAS_BIAS ? i : 0] = a.bias[8 * (i >> 2) + 4 * hi + (i & 3)];
     }
     f32x16 acc[4][RH];
 #pragma unroll
@@ -198,94 +242,67 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
 #pragma unroll
         for (int h = 0; h < RH; ++h)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[s][h][i] = HAS_BIAS ? bv[HAS_BIAS ? i : 0] : 0.f;
+            for (int i = 0; i < 16; ++i) acc[s][h][i] = HAS_BIAS ? c.bv[HAS_BIAS ? i : 0] : 0.f;
 
-    // Output side.  Lane (voxel col, channel group hi) stores 4 channels (8 bytes) per unit (h, q):
-    // channels 8q + 4hi .. +3 of row h.  Rows / columns outside the tile interior are masked.
-    bool okrow[RH];
-#pragma unroll
-    for (int h = 0; h < RH; ++h) okrow[h] = h0 + wave * RH + h < g.th && w0 + col < g.tw;
-    const size_t orow = static_cast<size_t>(g.pw) * C;
-    uint16_t *obase = tout + ((static_cast<size_t>(d0 + 1) * g.ph + h0 + wave * RH + 1) * g.pw + w0 + col + 1) * C +
-                      4 * hi;
-    auto store_unit = [&](int d, const f32x16 (&s)[RH], int h, int q) {
-        float v0 = s[h][4 * q], v1 = s[h][4 * q + 1], v2 = s[h][4 * q + 2], v3 = s[h][4 * q + 3];
-        if (a.relu) {
-            v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f);
-        }
-        const uint2 pk = make_uint2(pack2(v0, v1), pack2(v2, v3));
-#if (SP3D_EXP & 16)
-        if (okrow[h]) *reinterpret_cast<uint2 *>(obase + min(d, 0) * plane_elems + h * orow + 8 * q) = pk;
-#else
-        if (okrow[h]) *reinterpret_cast<uint2 *>(obase + d * plane_elems + h * orow + 8 * q) = pk;
-#endif
-    };
-    auto reset_half = [&](f32x16 (&s)[RH], int h) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s[h][i] = HAS_BIAS ? bv[HAS_BIAS ? i : 0] : 0.f;
-    };
+    const char *lbase = lds + lds_off(wave * RH * LCOLS + col, hi);
+    const int nplanes = c.nplanes;
 
     // Prologue: planes 0 .. DIST-1 in flight; plane 0 must have landed before the first MFMA.
 #pragma unroll
     for (int i = 0; i < DIST; ++i)
 #pragma unroll
-        for (int j = 0; j < LOADS; ++j) stage(i, j);
+        for (int j = 0; j < LOADS; ++j) stage(c, i, j, lane);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
-    // One step per input plane Dp.  Side work of step Dp: stage plane Dp+DIST (one load per MFMA
-    // group) and, from the fourth step on, convert and store output plane Dp-3, which received its last
-    // contribution in step Dp-1, then return its accumulator slot to the bias.
-    for (int D = 0; D < nplanes; D += 4) {
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int Dp = D + p;
-            if (Dp < nplanes) {
-                const bool epi = Dp >= 3;     // Dp - 3 < dn always holds inside the loop
-                auto side = [&](int gi, f32x16 (&done)[RH]) {
-                    stage(Dp + DIST, gi);
-                    if (gi < 4) {
-                        if (epi) {
-                            store_unit(Dp - 3, done, 0, gi);
-                            store_unit(Dp - 3, done, 1, gi);
-                        }
-                    } else {
-                        reset_half(done, gi - 4);
-                    }
-                };
-                const char *cur = lbase + (Dp % NBUF) * PLANE_BYTES;
-                if (p == 0) plane_step<0>(cur, wf, acc, side);
-                else if (p == 1) plane_step<1>(cur, wf, acc, side);
-                else if (p == 2) plane_step<2>(cur, wf, acc, side);
-                else plane_step<3>(cur, wf, acc, side);
-                // Plane Dp+1 must be complete before anyone reads it in the next step.  Loads complete in
-                // issue order and the only loads issued after plane Dp+1's are those of planes Dp+2 and
-                // Dp+3, so "at most 2*LOADS vector memory operations outstanding" implies it is done
-                // (stores share the counter and only make the wait more conservative).  A bare
-                // s_barrier: __syncthreads() would make the compiler drain every staging load.
-#if (SP3D_EXP & 4)
-                asm volatile("s_waitcnt vmcnt(30)" ::: "memory");
-#else
-                asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DIST - 1) * LOADS) : "memory");
-#endif
-                __builtin_amdgcn_s_barrier();
-            }
-        }
+    // End of a step: plane Dp+1 must be complete before anyone reads it in the next step.  Loads
+    // complete in issue order and the only loads issued after plane Dp+1's are those of planes Dp+2 and
+    // Dp+3, so "at most 2*LOADS vector memory operations outstanding" implies it is done (stores share
+    // the counter and only make the wait more conservative).  A bare s_barrier: __syncthreads() would
+    // make the compiler drain every staging load.
+#define SP3D_STEP_END()                                                              \
+    do {                                                                             \
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DIST - 1) * LOADS) : "memory");    \
+        __builtin_amdgcn_s_barrier();                                                \
+    } while (0)
+
+    auto march = [&](auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        // the first three steps have no finished plane to store (nplanes >= 3 always)
+        plane_step<0, false, RELU, FULL>(c, 0, lane, lbase, wf, acc);
+        SP3D_STEP_END();
+        plane_step<1, false, RELU, FULL>(c, 1, lane, lbase + PLANE_BYTES, wf, acc);
+        SP3D_STEP_END();
+        plane_step<2, false, RELU, FULL>(c, 2, lane, lbase + 2 * PLANE_BYTES, wf, acc);
+        SP3D_STEP_END();
+        // steps 3, 4, 5, 6, 7, ...: planes mod 4 = 3, 0, 1, 2, 3, ...
+#define SP3D_MAIN_STEP(OFF, PHASE)                                                                   \
+    if (D + (OFF) < nplanes) {                                                                       \
+        plane_step<PHASE, true, RELU, FULL>(c, D + (OFF), lane, lbase + (PHASE) * PLANE_BYTES, wf, acc); \
+        SP3D_STEP_END();                                                                             \
     }
-    // the last output plane finished in the last step
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    {
-        const int slot = (nplanes - 3) & 3;     // plane dn-1 = step nplanes-1 minus kd = 2
+        for (int D = 3; D < nplanes; D += 4) {
+            SP3D_MAIN_STEP(0, 3)
+            SP3D_MAIN_STEP(1, 0)
+            SP3D_MAIN_STEP(2, 1)
+            SP3D_MAIN_STEP(3, 2)
+        }
+#undef SP3D_MAIN_STEP
+        // the last output plane (dn-1) finished in the last step; it sits in slot (dn-1) mod 4
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
         for (int s = 0; s < 4; ++s)
-            if (s == slot) {
+            if (s == ((dn - 1) & 3)) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    store_unit(dn - 1, acc[s], 0, q);
-                    store_unit(dn - 1, acc[s], 1, q);
+                    store_unit<RELU, FULL>(c, dn - 1, acc[s], 0, q);
+                    store_unit<RELU, FULL>(c, dn - 1, acc[s], 1, q);
                 }
             }
-    }
+    };
+    if (h0 + PH <= g.th && w0 + PW <= g.tw) march(std::true_type{});
+    else march(std::false_type{});
+#undef SP3D_STEP_END
 }
 
 }  // namespace
@@ -323,18 +340,19 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
     a.relu = relu ? 1 : 0;
     const unsigned grid = static_cast<unsigned>((nb + 7) / 8 * 8);
     // more than 64 KB of dynamic LDS has to be requested explicitly
-    static const hipError_t attr0 = hipFuncSetAttribute(
-        reinterpret_cast<const void *>(conv_mfma_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize,
-        LDS_BYTES);
-    static const hipError_t attr1 = hipFuncSetAttribute(
-        reinterpret_cast<const void *>(conv_mfma_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize,
-        LDS_BYTES);
-    if (attr0 != hipSuccess) return record_hip(attr0);
-    if (attr1 != hipSuccess) return record_hip(attr1);
-    if (bias)
-        hipLaunchKernelGGL(conv_mfma_kernel<true>, dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
-    else
-        hipLaunchKernelGGL(conv_mfma_kernel<false>, dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
+    using Kern = void (*)(ConvArgs);
+    static const Kern kern[2][2] = {{conv_mfma_kernel<false, false>, conv_mfma_kernel<false, true>},
+                                    {conv_mfma_kernel<true, false>, conv_mfma_kernel<true, true>}};
+    static const hipError_t attr = [] {
+        for (int i = 0; i < 4; ++i) {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern[i >> 1][i & 1]),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }();
+    if (attr != hipSuccess) return record_hip(attr);
+    hipLaunchKernelGGL(kern[bias ? 1 : 0][relu ? 1 : 0], dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
     return record_hip(hipGetLastError());
 }
 
