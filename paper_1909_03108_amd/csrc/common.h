@@ -64,6 +64,34 @@ size_t wgrad_mfma_ws_bytes(const Geo &g, int cin, int cout);
 int launch_wgrad_mfma(const void *Px, const void *Pdz, float *dw, float *db, const Geo &g,
                       int cin, int cout, void *ws, hipStream_t s);
 
+// Division of a 32-bit index by a launch-time constant without the ~25-instruction software divide:
+// multiply-high by a precomputed reciprocal, with the one-bit-wider "add" form where the 32-bit
+// reciprocal is not exact (Granlund & Montgomery, "Division by invariant integers using
+// multiplication").  Exact for every 32-bit numerator.
+struct FastDiv {
+    uint32_t d, magic, shift, add;
+};
+inline FastDiv make_fastdiv(uint32_t d) {
+    FastDiv f{d, 0, 0, 0};
+    uint32_t L = 31;
+    while (!((d >> L) & 1)) --L;                               // floor(log2 d), d >= 1
+    if ((d & (d - 1)) == 0) { f.shift = L; return f; }         // power of two: plain shift
+    const uint64_t two = 1ull << (32 + L);
+    uint64_t m = two / d;
+    const uint64_t rem = two - m * d;
+    if (d - rem < (1ull << L)) { f.magic = static_cast<uint32_t>(m + 1); f.shift = L; return f; }
+    m = 2 * m + (2 * rem >= d ? 1 : 0);                        // one more quotient bit
+    f.magic = static_cast<uint32_t>(m + 1); f.shift = L; f.add = 1;
+    return f;
+}
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv &f) {
+    if (!f.magic) return n >> f.shift;
+    uint32_t q = __umulhi(n, f.magic);
+    if (f.add) q = ((n - q) >> 1) + q;
+    return q >> f.shift;
+}
+__device__ __forceinline__ uint32_t fmod_(uint32_t n, uint32_t q, const FastDiv &f) { return n - q * f.d; }
+
 // device helpers ------------------------------------------------------------------------------
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) {
     return __uint_as_float(static_cast<uint32_t>(b) << 16);
