@@ -60,7 +60,11 @@ enum {
 };
 
 enum { SP_FLAG_RELU = 1 };                                /* conv3d_fwd: y = max(z, 0) */
-enum { SP_OP_FWD = 0, SP_OP_DGRAD = 1, SP_OP_WGRAD = 2 }; /* sp_workspace_bytes `op`   */
+enum {                                                    /* sp_workspace_bytes `op`   */
+    SP_OP_FWD = 0, SP_OP_DGRAD = 1, SP_OP_WGRAD = 2,      /* the 3x3x3 convolution     */
+    SP_OP_UPCONV_WGRAD = 3,                               /* sp_upconv2_wgrad          */
+    SP_OP_POINTWISE_WGRAD = 4                             /* sp_pointwise_wgrad        */
+};
 
 /* ---- host-only helpers (no GPU needed) --------------------------------------------------- */
 
@@ -129,6 +133,51 @@ int conv3d_wgrad(const void *Px, const void *Pdz, float *dw, float *db, const sp
  * margins included; the derivative at 0 is taken as 0).  Pdz may alias Pdy. */
 int sp_relu_bwd(const void *Pdy, const void *Py, void *Pdz, const sp_geom_t *g, int c,
                 sp_dtype_t dt, void *stream);
+
+/* ---- U-Net glue around the convolutions (Sec. 3, first paragraph: blocks of convolutions with
+ * max-pooling on the way down and a symmetric up-sampling path).  The paper names neither the
+ * up-sampling operator nor the classifier; these are a 2x2x2 stride-2 transposed convolution, a
+ * channel concatenation with the skip tensor and a 1x1x1 convolution.  Pooling / up-convolution
+ * windows never straddle tiles, so none of these needs a halo; unless stated otherwise they read
+ * and write tile interiors only and leave margins as they are.  "Fine" geometry `gf` = the
+ * higher-resolution side (pool input, up-conv output); the coarse side has extents d/2, h/2, w/2 on
+ * the same tile grid.  SP_EGEOM if a fine tile extent is odd. -------------------------------------- */
+
+/* y[v,c] = max over the 2x2x2 window of Px starting at 2v.  Px fine [..][c], Py coarse [..][c]. */
+int sp_maxpool2_fwd(const void *Px, void *Py, const sp_geom_t *gf, int c, sp_dtype_t dt, void *stream);
+/* Pdx (fine) = Pdy (coarse) routed to the FIRST maximum of each window in (d,h,w) scan order, zero
+ * for the other seven voxels.  Px is the pooling input. */
+int sp_maxpool2_bwd(const void *Px, const void *Pdy, void *Pdx, const sp_geom_t *gf, int c,
+                    sp_dtype_t dt, void *stream);
+
+/* y[2v+(a,b,c), co] = bias[co] + sum_ci Px[v,ci] * u[a][b][c][ci][co];  u[2][2][2][Cin][Cout] in the
+ * tensor dtype, bias float or NULL.  Px coarse [..][Cin], Py fine [..][Cout]. */
+int sp_upconv2_fwd(const void *Px, const void *u, const float *bias, void *Py, const sp_geom_t *gf,
+                   int cin, int cout, sp_dtype_t dt, void *stream);
+/* dx[v,ci] = sum_{a,b,c,co} Pdy[2v+(a,b,c), co] * u[a][b][c][ci][co].  Pdy fine, Pdx coarse. */
+int sp_upconv2_dgrad(const void *Pdy, const void *u, void *Pdx, const sp_geom_t *gf, int cin, int cout,
+                     sp_dtype_t dt, void *stream);
+/* du[a][b][c][ci][co] = sum_v Px[v,ci] * Pdy[2v+(a,b,c), co];  db[co] = sum Pdy (NULL to skip).
+ * float outputs, overwritten; fixed-order reduction through `ws` (SP_OP_UPCONV_WGRAD). */
+int sp_upconv2_wgrad(const void *Px, const void *Pdy, float *du, float *db, const sp_geom_t *gf,
+                     int cin, int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream);
+
+/* 1x1x1 convolution: y[v,co] = bias[co] + sum_ci Px[v,ci] * p[ci][co] (SP_FLAG_RELU allowed), its data
+ * gradient dx[v,ci] = sum_co Pdy[v,co] * p[ci][co], and its weight / bias gradient (float, overwritten,
+ * fixed-order reduction through `ws`, SP_OP_POINTWISE_WGRAD).  g is the geometry of both sides. */
+int sp_pointwise_fwd(const void *Px, const void *p, const float *bias, void *Py, const sp_geom_t *g,
+                     int cin, int cout, sp_dtype_t dt, uint32_t flags, void *stream);
+int sp_pointwise_dgrad(const void *Pdy, const void *p, void *Pdx, const sp_geom_t *g, int cin, int cout,
+                       sp_dtype_t dt, void *stream);
+int sp_pointwise_wgrad(const void *Px, const void *Pdy, float *dp, float *db, const sp_geom_t *g,
+                       int cin, int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream);
+
+/* Channel concatenation Pout[..][ca+cb] = Pa[..][ca] ++ Pb[..][cb] and its inverse, over ALL voxels of
+ * the padded arrays (margins included).  Bit-exact copies. */
+int sp_concat(const void *Pa, int ca, const void *Pb, int cb, void *Pout, const sp_geom_t *g,
+              sp_dtype_t dt, void *stream);
+int sp_split(const void *Pin, void *Pa, int ca, void *Pb, int cb, const sp_geom_t *g, sp_dtype_t dt,
+             void *stream);
 
 #ifdef __cplusplus
 }

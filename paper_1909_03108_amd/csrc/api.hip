@@ -107,6 +107,13 @@ size_t sp_workspace_bytes(int op, const sp_geom_t *g, int cin, int cout, sp_dtyp
     case SP_OP_WGRAD:
         return wgrad_mfma_supported(o, cin, cout, dt) ? wgrad_mfma_ws_bytes(o, cin, cout)
                                                       : wgrad_direct_ws_bytes(o, cin, cout);
+    case SP_OP_UPCONV_WGRAD: {
+        Geo c;
+        if (make_coarse(o, &c) != SP_OK) return static_cast<size_t>(-1);
+        return upconv2_wgrad_ws_bytes(c, cin, cout);
+    }
+    case SP_OP_POINTWISE_WGRAD:
+        return wgrad_direct_ws_bytes(o, cin, cout, 1);
     default:
         return static_cast<size_t>(-1);
     }
@@ -256,6 +263,108 @@ int sp_relu_bwd(const void *Pdy, const void *Py, void *Pdz, const sp_geom_t *g, 
     if (!aligned16(Pdy) || !aligned16(Py) || !aligned16(Pdz)) return SP_EINVAL;
     return launch_relu_bwd(Pdy, Py, Pdz, static_cast<size_t>(o.ntiles) * o.tile_vox * c, dt,
                            static_cast<hipStream_t>(stream));
+}
+
+// ---- U-Net glue ---------------------------------------------------------------------------------
+
+static int check_glue(const void *a, const void *b, const void *c, const sp_geom_t *g, int c1, int c2,
+                      sp_dtype_t dt, Geo *fine, Geo *coarse) {
+    if (!a || !b || !c) return SP_EINVAL;
+    int rc = make_geo(g, fine);
+    if (rc != SP_OK) return rc;
+    if (c1 <= 0 || c2 <= 0) return SP_EINVAL;
+    if (!dtype_ok(dt) || !chan_ok(c1) || !chan_ok(c2)) return SP_EUNSUPPORTED;
+    if (!aligned16(a) || !aligned16(b) || !aligned16(c)) return SP_EINVAL;
+    if (coarse) return make_coarse(*fine, coarse);
+    return SP_OK;
+}
+
+int sp_maxpool2_fwd(const void *Px, void *Py, const sp_geom_t *gf, int c, sp_dtype_t dt, void *stream) {
+    Geo f, k;
+    int rc = check_glue(Px, Py, Py, gf, c, c, dt, &f, &k);
+    if (rc != SP_OK) return rc;
+    return launch_maxpool2(Px, nullptr, Py, f, k, c, dt, false, static_cast<hipStream_t>(stream));
+}
+
+int sp_maxpool2_bwd(const void *Px, const void *Pdy, void *Pdx, const sp_geom_t *gf, int c, sp_dtype_t dt,
+                    void *stream) {
+    Geo f, k;
+    int rc = check_glue(Px, Pdy, Pdx, gf, c, c, dt, &f, &k);
+    if (rc != SP_OK) return rc;
+    return launch_maxpool2(Px, Pdy, Pdx, f, k, c, dt, true, static_cast<hipStream_t>(stream));
+}
+
+int sp_upconv2_fwd(const void *Px, const void *u, const float *bias, void *Py, const sp_geom_t *gf, int cin,
+                   int cout, sp_dtype_t dt, void *stream) {
+    Geo f, k;
+    int rc = check_glue(Px, u, Py, gf, cin, cout, dt, &f, &k);
+    if (rc != SP_OK) return rc;
+    return launch_upconv2_fwd(Px, u, bias, Py, f, k, cin, cout, dt, static_cast<hipStream_t>(stream));
+}
+
+int sp_upconv2_dgrad(const void *Pdy, const void *u, void *Pdx, const sp_geom_t *gf, int cin, int cout,
+                     sp_dtype_t dt, void *stream) {
+    Geo f, k;
+    int rc = check_glue(Pdy, u, Pdx, gf, cin, cout, dt, &f, &k);
+    if (rc != SP_OK) return rc;
+    return launch_upconv2_dgrad(Pdy, u, Pdx, f, k, cin, cout, dt, static_cast<hipStream_t>(stream));
+}
+
+int sp_upconv2_wgrad(const void *Px, const void *Pdy, float *du, float *db, const sp_geom_t *gf, int cin,
+                     int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream) {
+    Geo f, k;
+    int rc = check_glue(Px, Pdy, du, gf, cin, cout, dt, &f, &k);
+    if (rc != SP_OK) return rc;
+    const size_t need = upconv2_wgrad_ws_bytes(k, cin, cout);
+    if (!ws || ws_bytes < need || !aligned16(ws)) return SP_EWORKSPACE;
+    return launch_upconv2_wgrad(Px, Pdy, du, db, f, k, cin, cout, dt, ws, static_cast<hipStream_t>(stream));
+}
+
+int sp_pointwise_fwd(const void *Px, const void *p, const float *bias, void *Py, const sp_geom_t *g, int cin,
+                     int cout, sp_dtype_t dt, uint32_t flags, void *stream) {
+    Geo o;
+    int rc = check_glue(Px, p, Py, g, cin, cout, dt, &o, nullptr);
+    if (rc != SP_OK) return rc;
+    if (flags & ~static_cast<uint32_t>(SP_FLAG_RELU)) return SP_EINVAL;
+    return launch_conv_direct(Px, p, bias, Py, o, cin, cout, dt, flags & SP_FLAG_RELU, false,
+                              static_cast<hipStream_t>(stream), 1);
+}
+
+int sp_pointwise_dgrad(const void *Pdy, const void *p, void *Pdx, const sp_geom_t *g, int cin, int cout,
+                       sp_dtype_t dt, void *stream) {
+    Geo o;
+    int rc = check_glue(Pdy, p, Pdx, g, cin, cout, dt, &o, nullptr);
+    if (rc != SP_OK) return rc;
+    return launch_conv_direct(Pdy, p, nullptr, Pdx, o, cout, cin, dt, false, true,
+                              static_cast<hipStream_t>(stream), 1);
+}
+
+int sp_pointwise_wgrad(const void *Px, const void *Pdy, float *dp, float *db, const sp_geom_t *g, int cin,
+                       int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream) {
+    Geo o;
+    int rc = check_glue(Px, Pdy, dp, g, cin, cout, dt, &o, nullptr);
+    if (rc != SP_OK) return rc;
+    const size_t need = wgrad_direct_ws_bytes(o, cin, cout, 1);
+    if (!ws || ws_bytes < need || !aligned16(ws)) return SP_EWORKSPACE;
+    return launch_wgrad_direct(Px, Pdy, dp, db, o, cin, cout, dt, ws, static_cast<hipStream_t>(stream), 1);
+}
+
+int sp_concat(const void *Pa, int ca, const void *Pb, int cb, void *Pout, const sp_geom_t *g, sp_dtype_t dt,
+              void *stream) {
+    Geo o;
+    int rc = check_glue(Pa, Pb, Pout, g, ca, cb, dt, &o, nullptr);
+    if (rc != SP_OK) return rc;
+    return launch_concat(Pa, ca, Pb, cb, Pout, static_cast<size_t>(o.ntiles) * o.tile_vox, dt, false,
+                         static_cast<hipStream_t>(stream));
+}
+
+int sp_split(const void *Pin, void *Pa, int ca, void *Pb, int cb, const sp_geom_t *g, sp_dtype_t dt,
+             void *stream) {
+    Geo o;
+    int rc = check_glue(Pin, Pa, Pb, g, ca, cb, dt, &o, nullptr);
+    if (rc != SP_OK) return rc;
+    return launch_concat(Pa, ca, Pb, cb, const_cast<void *>(Pin), static_cast<size_t>(o.ntiles) * o.tile_vox,
+                         dt, true, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

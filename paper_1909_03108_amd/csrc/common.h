@@ -46,11 +46,26 @@ int launch_halo_unpack(void *P, const void *msg, const Geo &g, int c, sp_dtype_t
 int launch_relu_bwd(const void *dy, const void *y, void *dz, size_t elems, sp_dtype_t dt,
                     hipStream_t s);
 
+// ks = kernel extent per axis (3, or 1 for the 1x1x1 convolution)
 int launch_conv_direct(const void *Pin, const void *w, const float *bias, void *Pout, const Geo &g,
-                       int cin, int cout, sp_dtype_t dt, bool relu, bool dgrad, hipStream_t s);
-size_t wgrad_direct_ws_bytes(const Geo &g, int cin, int cout);
+                       int cin, int cout, sp_dtype_t dt, bool relu, bool dgrad, hipStream_t s, int ks = 3);
+size_t wgrad_direct_ws_bytes(const Geo &g, int cin, int cout, int ks = 3);
 int launch_wgrad_direct(const void *Px, const void *Pdz, float *dw, float *db, const Geo &g,
-                        int cin, int cout, sp_dtype_t dt, void *ws, hipStream_t s);
+                        int cin, int cout, sp_dtype_t dt, void *ws, hipStream_t s, int ks = 3);
+
+// U-Net glue (glue_kernels.hip).  gf = geometry of the fine (higher-resolution) volume.
+int make_coarse(const Geo &gf, Geo *gc);     // SP_OK, or SP_EGEOM if a tile extent is odd
+int launch_maxpool2(const void *Px, const void *Pdy, void *Pout, const Geo &gf, const Geo &gc, int c,
+                    sp_dtype_t dt, bool backward, hipStream_t s);
+int launch_upconv2_fwd(const void *Px, const void *u, const float *bias, void *Py, const Geo &gf,
+                       const Geo &gc, int cin, int cout, sp_dtype_t dt, hipStream_t s);
+int launch_upconv2_dgrad(const void *Pdy, const void *u, void *Pdx, const Geo &gf, const Geo &gc, int cin,
+                         int cout, sp_dtype_t dt, hipStream_t s);
+size_t upconv2_wgrad_ws_bytes(const Geo &gc, int cin, int cout);
+int launch_upconv2_wgrad(const void *Px, const void *Pdy, float *du, float *db, const Geo &gf, const Geo &gc,
+                         int cin, int cout, sp_dtype_t dt, void *ws, hipStream_t s);
+int launch_concat(const void *Pa, int ca, const void *Pb, int cb, void *Pc, size_t voxels, sp_dtype_t dt,
+                  bool split, hipStream_t s);
 
 int launch_reduce_partials(const float *part, float *out, int nparts, long long n, hipStream_t s);
 

@@ -22,7 +22,8 @@ template <> __device__ __forceinline__ void stf<uint16_t>(uint16_t *p, long long
 
 // One thread per (interior voxel, output channel).  With DGRAD the taps are mirrored and the weight
 // tensor is read as w[tap][ko][ki] (ko = this kernel's output channel = the layer's input channel).
-template <typename E, bool DGRAD>
+// KS = kernel extent per axis: 3 (the 3x3x3 convolution) or 1 (the 1x1x1 classifier).
+template <typename E, bool DGRAD, int KS>
 __global__ __launch_bounds__(kThreads) void conv_direct_kernel(const E *__restrict__ Pin,
                                                                const E *__restrict__ w,
                                                                const float *__restrict__ bias,
@@ -38,13 +39,14 @@ __global__ __launch_bounds__(kThreads) void conv_direct_kernel(const E *__restri
     const unsigned ld = r / thw, lh = (r % thw) / g.tw, lw = r % g.tw;
     const long long base = tile * g.tile_vox;
     float acc = bias ? bias[co] : 0.f;
-    for (int kd = 0; kd < 3; ++kd)
-        for (int kh = 0; kh < 3; ++kh)
-            for (int kw = 0; kw < 3; ++kw) {
-                const long long pv = base + (1LL * (ld + kd) * g.ph + lh + kh) * g.pw + lw + kw;
+    constexpr int O = 1 - KS / 2;     // tap 0 reads padded coordinate (interior coordinate + O), halo = 1
+    for (int kd = 0; kd < KS; ++kd)
+        for (int kh = 0; kh < KS; ++kh)
+            for (int kw = 0; kw < KS; ++kw) {
+                const long long pv = base + (1LL * (ld + kd + O) * g.ph + lh + kh + O) * g.pw + lw + kw + O;
                 const E *xin = Pin + pv * ki;
-                const int tap = DGRAD ? ((2 - kd) * 3 + (2 - kh)) * 3 + (2 - kw)
-                                      : (kd * 3 + kh) * 3 + kw;
+                const int tap = DGRAD ? ((KS - 1 - kd) * KS + (KS - 1 - kh)) * KS + (KS - 1 - kw)
+                                      : (kd * KS + kh) * KS + kw;
                 if (DGRAD) {
                     const E *wt = w + (1LL * tap * ko + co) * ki;      // w[tap][ci=co][co'=c]
                     for (int c = 0; c < ki; ++c) acc = fmaf(ldf<E>(xin, c), ldf<E>(wt, c), acc);
@@ -54,7 +56,7 @@ __global__ __launch_bounds__(kThreads) void conv_direct_kernel(const E *__restri
                         acc = fmaf(ldf<E>(xin, c), ldf<E>(wt, 1LL * c * ko), acc);
                 }
             }
-    if (relu && !(acc > 0.f)) acc = 0.f;
+    if (relu && acc < 0.f) acc = 0.f;
     const long long ov = base + (1LL * (ld + g.halo) * g.ph + lh + g.halo) * g.pw + lw + g.halo;
     stf<E>(Pout, ov * ko + co, acc);
 }
@@ -62,7 +64,7 @@ __global__ __launch_bounds__(kThreads) void conv_direct_kernel(const E *__restri
 // Weight gradient, stage 1.  Block (tap*cin + ci, chunk, co-group): threads are laid out as
 // [voxel lane][co]; each thread sums its voxels of the chunk in index order, then the voxel lanes
 // are added in lane order by one thread per co.  Partial sums go to ws[chunk][tap][ci][co].
-template <typename E>
+template <typename E, int KS>
 __global__ __launch_bounds__(kThreads) void wgrad_direct_kernel(const E *__restrict__ Px,
                                                                 const E *__restrict__ Pdz,
                                                                 float *__restrict__ part, Geo g,
@@ -72,7 +74,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_direct_kernel(const E *__restr
     __shared__ float red[kThreads];
     const int tapci = blockIdx.x, chunk = blockIdx.y;
     const int tap = tapci / cin, ci = tapci % cin;
-    const int kd = tap / 9, kh = (tap / 3) % 3, kw = tap % 3;
+    constexpr int O = 1 - KS / 2;
+    const int kd = tap / (KS * KS) + O, kh = (tap / KS) % KS + O, kw = tap % KS + O;
     const int nvl = kThreads / cw;
     const int col = threadIdx.x % cw, vl = threadIdx.x / cw;
     const int co = blockIdx.z * cw + col;
@@ -96,7 +99,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_direct_kernel(const E *__restr
     if (vl == 0 && co < cout) {
         float s = 0.f;
         for (int l = 0; l < nvl; ++l) s += red[l * cw + col];
-        part[(1LL * chunk * 27 * cin + tapci) * cout + co] = s;
+        part[(1LL * chunk * KS * KS * KS * cin + tapci) * cout + co] = s;
     }
 }
 
@@ -154,20 +157,22 @@ int launch_reduce_partials(const float *part, float *out, int nparts, long long 
 }
 
 int launch_conv_direct(const void *Pin, const void *w, const float *bias, void *Pout, const Geo &g,
-                       int ki, int ko, sp_dtype_t dt, bool relu, bool dgrad, hipStream_t s) {
+                       int ki, int ko, sp_dtype_t dt, bool relu, bool dgrad, hipStream_t s, int ks) {
     const long long total = 1LL * g.ntiles * g.int_vox * ko;
     const long long blocks = (total + kThreads - 1) / kThreads;
     if (blocks > 0x7fffffffLL) return SP_EGEOM;
     dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
-#define SP3D_LAUNCH(E, DG)                                                                         \
-    hipLaunchKernelGGL((conv_direct_kernel<E, DG>), grid, block, 0, s, static_cast<const E *>(Pin), \
-                       static_cast<const E *>(w), bias, static_cast<E *>(Pout), g, ki, ko,         \
+#define SP3D_LAUNCH(E, DG, KS)                                                                         \
+    hipLaunchKernelGGL((conv_direct_kernel<E, DG, KS>), grid, block, 0, s, static_cast<const E *>(Pin), \
+                       static_cast<const E *>(w), bias, static_cast<E *>(Pout), g, ki, ko,             \
                        relu ? 1 : 0, total)
+#define SP3D_LAUNCH_KS(E, DG) do { if (ks == 1) SP3D_LAUNCH(E, DG, 1); else SP3D_LAUNCH(E, DG, 3); } while (0)
     if (dt == SP_BF16) {
-        if (dgrad) SP3D_LAUNCH(uint16_t, true); else SP3D_LAUNCH(uint16_t, false);
+        if (dgrad) SP3D_LAUNCH_KS(uint16_t, true); else SP3D_LAUNCH_KS(uint16_t, false);
     } else {
-        if (dgrad) SP3D_LAUNCH(float, true); else SP3D_LAUNCH(float, false);
+        if (dgrad) SP3D_LAUNCH_KS(float, true); else SP3D_LAUNCH_KS(float, false);
     }
+#undef SP3D_LAUNCH_KS
 #undef SP3D_LAUNCH
     return record_hip(hipGetLastError());
 }
@@ -182,41 +187,53 @@ static void wgrad_direct_plan(const Geo &g, int *nchunks, long long *chunk_vox) 
     *chunk_vox = cv;
 }
 
-size_t wgrad_direct_ws_bytes(const Geo &g, int cin, int cout) {
+size_t wgrad_direct_ws_bytes(const Geo &g, int cin, int cout, int ks) {
     int nc; long long cv;
     wgrad_direct_plan(g, &nc, &cv);
-    return (static_cast<size_t>(nc) * 27 * cin * cout + static_cast<size_t>(nc) * cout) * sizeof(float);
+    const size_t taps = static_cast<size_t>(ks) * ks * ks;
+    return (static_cast<size_t>(nc) * taps * cin * cout + static_cast<size_t>(nc) * cout) * sizeof(float);
 }
 
 int launch_wgrad_direct(const void *Px, const void *Pdz, float *dw, float *db, const Geo &g, int cin,
-                        int cout, sp_dtype_t dt, void *ws, hipStream_t s) {
+                        int cout, sp_dtype_t dt, void *ws, hipStream_t s, int ks) {
     int nc; long long cv;
     wgrad_direct_plan(g, &nc, &cv);
     const long long total = 1LL * g.ntiles * g.int_vox;
+    const int taps = ks * ks * ks;
     float *part_w = static_cast<float *>(ws);
-    float *part_b = part_w + static_cast<size_t>(nc) * 27 * cin * cout;
+    float *part_b = part_w + static_cast<size_t>(nc) * taps * cin * cout;
     const int cw = cout < kThreads ? cout : kThreads;
     const int zg = (cout + cw - 1) / cw;
-    if (27LL * cin > 0x7fffffffLL || nc > 65535 || zg > 65535) return SP_EUNSUPPORTED;
-    dim3 block(kThreads), gw_(27 * cin, nc, zg), gb_(1, nc, zg);
+    if (nc > 65535 || zg > 65535) return SP_EUNSUPPORTED;
+    dim3 block(kThreads), gw_(taps * cin, nc, zg), gb_(1, nc, zg);
     if (dt == SP_BF16) {
-        hipLaunchKernelGGL(wgrad_direct_kernel<uint16_t>, gw_, block, 0, s,
-                           static_cast<const uint16_t *>(Px), static_cast<const uint16_t *>(Pdz),
-                           part_w, g, cin, cout, cw, cv, total);
+        if (ks == 1)
+            hipLaunchKernelGGL((wgrad_direct_kernel<uint16_t, 1>), gw_, block, 0, s,
+                               static_cast<const uint16_t *>(Px), static_cast<const uint16_t *>(Pdz),
+                               part_w, g, cin, cout, cw, cv, total);
+        else
+            hipLaunchKernelGGL((wgrad_direct_kernel<uint16_t, 3>), gw_, block, 0, s,
+                               static_cast<const uint16_t *>(Px), static_cast<const uint16_t *>(Pdz),
+                               part_w, g, cin, cout, cw, cv, total);
         if (db)
             hipLaunchKernelGGL(bgrad_direct_kernel<uint16_t>, gb_, block, 0, s,
                                static_cast<const uint16_t *>(Pdz), part_b, g, cout, cw, cv, total);
     } else {
-        hipLaunchKernelGGL(wgrad_direct_kernel<float>, gw_, block, 0, s,
-                           static_cast<const float *>(Px), static_cast<const float *>(Pdz), part_w, g,
-                           cin, cout, cw, cv, total);
+        if (ks == 1)
+            hipLaunchKernelGGL((wgrad_direct_kernel<float, 1>), gw_, block, 0, s,
+                               static_cast<const float *>(Px), static_cast<const float *>(Pdz), part_w, g,
+                               cin, cout, cw, cv, total);
+        else
+            hipLaunchKernelGGL((wgrad_direct_kernel<float, 3>), gw_, block, 0, s,
+                               static_cast<const float *>(Px), static_cast<const float *>(Pdz), part_w, g,
+                               cin, cout, cw, cv, total);
         if (db)
             hipLaunchKernelGGL(bgrad_direct_kernel<float>, gb_, block, 0, s,
                                static_cast<const float *>(Pdz), part_b, g, cout, cw, cv, total);
     }
     int rc = record_hip(hipGetLastError());
     if (rc != SP_OK) return rc;
-    rc = launch_reduce_partials(part_w, dw, nc, 27LL * cin * cout, s);
+    rc = launch_reduce_partials(part_w, dw, nc, 1LL * taps * cin * cout, s);
     if (rc != SP_OK) return rc;
     if (db) rc = launch_reduce_partials(part_b, db, nc, cout, s);
     return rc;

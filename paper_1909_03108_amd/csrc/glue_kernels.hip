@@ -1,0 +1,325 @@
+// U-Net glue on padded tiles: 2x2x2 max pooling (forward / backward), 2x2x2 stride-2 transposed
+// convolution (forward / data gradient / weight gradient), channel concatenation and split.
+// Pooling and up-convolution windows never straddle tiles (tile extents are even), so these
+// operations need no halo; they read and write tile interiors only.  "Fine" is the higher-resolution
+// side (pool input, up-conv output), "coarse" the other; both live on the same tile grid.
+// All arithmetic is fp32 (fused multiply-add), inputs f32 or bf16, one rounding on store.
+#include "common.h"
+
+namespace sp3d {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+template <typename E> __device__ __forceinline__ float ldf(const E *p, long long i);
+template <> __device__ __forceinline__ float ldf<float>(const float *p, long long i) { return p[i]; }
+template <> __device__ __forceinline__ float ldf<uint16_t>(const uint16_t *p, long long i) {
+    return bf16_to_f32(p[i]);
+}
+template <typename E> __device__ __forceinline__ void stf(E *p, long long i, float v);
+template <> __device__ __forceinline__ void stf<float>(float *p, long long i, float v) { p[i] = v; }
+template <> __device__ __forceinline__ void stf<uint16_t>(uint16_t *p, long long i, float v) {
+    p[i] = f32_to_bf16(v);
+}
+
+// Thread layout shared by the kernels below: a block covers kThreads/cw voxels x cw channel lanes
+// (cw = power of two >= min(C, 256)); channels beyond cw are looped over.
+struct Lay {
+    int cw, cshift;          // channel lanes per voxel and log2
+    unsigned nvox;           // voxels to cover (interior voxels of all tiles of the indexing geometry)
+    FastDiv int_vox, hw, w;  // decode voxel -> (tile, ld, lh, lw) of the indexing geometry
+};
+
+Lay make_lay(const Geo &g, int c) {
+    Lay l;
+    l.cw = 1; l.cshift = 0;
+    while (l.cw < c && l.cw < kThreads) { l.cw <<= 1; ++l.cshift; }
+    l.nvox = static_cast<unsigned>(1LL * g.ntiles * g.int_vox);
+    l.int_vox = make_fastdiv(static_cast<uint32_t>(g.int_vox));
+    l.hw = make_fastdiv(static_cast<uint32_t>(g.th) * g.tw);
+    l.w = make_fastdiv(g.tw);
+    return l;
+}
+
+struct Vox { unsigned tile, ld, lh, lw; };
+__device__ __forceinline__ Vox decode(unsigned v, const Lay &l) {
+    Vox o;
+    o.tile = fdiv(v, l.int_vox);
+    const unsigned r = fmod_(v, o.tile, l.int_vox);
+    o.ld = fdiv(r, l.hw);
+    const unsigned q = fmod_(r, o.ld, l.hw);
+    o.lh = fdiv(q, l.w);
+    o.lw = fmod_(q, o.lh, l.w);
+    return o;
+}
+// padded voxel index of interior voxel (ld, lh, lw) of a tile (halo = 1)
+__device__ __forceinline__ long long pidx(const Geo &g, unsigned tile, unsigned ld, unsigned lh, unsigned lw) {
+    return tile * g.tile_vox + (1LL * (ld + 1) * g.ph + lh + 1) * g.pw + lw + 1;
+}
+
+// ---- max pooling -------------------------------------------------------------------------------
+// One thread per (coarse voxel, channel).  Forward: y = max of the 8 window values.  Backward: dx of
+// the FIRST maximum in (d,h,w) scan order receives dy, the other seven receive 0.
+template <typename E, bool BWD>
+__global__ __launch_bounds__(kThreads) void maxpool2_kernel(const E *__restrict__ x, const E *__restrict__ dy,
+                                                            E *__restrict__ out, Geo gf, Geo gc, Lay l, int C) {
+    const unsigned v = blockIdx.x * (kThreads >> l.cshift) + (threadIdx.x >> l.cshift);
+    if (v >= l.nvox) return;
+    const Vox o = decode(v, l);
+    const long long pc = pidx(gc, o.tile, o.ld, o.lh, o.lw);
+    long long pf[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+        pf[k] = pidx(gf, o.tile, 2 * o.ld + (k >> 2), 2 * o.lh + ((k >> 1) & 1), 2 * o.lw + (k & 1));
+    for (int c = threadIdx.x & (l.cw - 1); c < C; c += l.cw) {
+        float best = ldf<E>(x, pf[0] * C + c);
+        int arg = 0;
+#pragma unroll
+        for (int k = 1; k < 8; ++k) {
+            const float t = ldf<E>(x, pf[k] * C + c);
+            if (t > best) { best = t; arg = k; }
+        }
+        if (BWD) {
+            const E g = dy[pc * C + c];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) out[pf[k] * C + c] = k == arg ? g : E(0);
+        } else {
+            stf<E>(out, pc * C + c, best);
+        }
+    }
+}
+
+// ---- transposed convolution 2x2x2, stride 2 ----------------------------------------------------------
+// Forward: one thread per (fine voxel, co): y = bias + sum_ci x[coarse][ci] * u[a][b][c][ci][co].
+template <typename E>
+__global__ __launch_bounds__(kThreads) void upconv2_fwd_kernel(const E *__restrict__ x, const E *__restrict__ u,
+                                                               const float *__restrict__ bias, E *__restrict__ y,
+                                                               Geo gf, Geo gc, Lay l, int cin, int cout) {
+    const unsigned v = blockIdx.x * (kThreads >> l.cshift) + (threadIdx.x >> l.cshift);
+    if (v >= l.nvox) return;
+    const Vox o = decode(v, l);                                     // fine voxel
+    const int k = ((o.ld & 1) << 2) | ((o.lh & 1) << 1) | (o.lw & 1);
+    const E *xin = x + pidx(gc, o.tile, o.ld >> 1, o.lh >> 1, o.lw >> 1) * cin;
+    const E *uk = u + 1LL * k * cin * cout;
+    const long long po = pidx(gf, o.tile, o.ld, o.lh, o.lw);
+    for (int co = threadIdx.x & (l.cw - 1); co < cout; co += l.cw) {
+        float acc = bias ? bias[co] : 0.f;
+        for (int ci = 0; ci < cin; ++ci) acc = fmaf(ldf<E>(xin, ci), ldf<E>(uk, 1LL * ci * cout + co), acc);
+        stf<E>(y, po * cout + co, acc);
+    }
+}
+
+// Data gradient: one thread per (coarse voxel, ci): dx = sum_{window k, co} dy[fine k][co] * u[k][ci][co].
+template <typename E>
+__global__ __launch_bounds__(kThreads) void upconv2_dgrad_kernel(const E *__restrict__ dy, const E *__restrict__ u,
+                                                                 E *__restrict__ dx, Geo gf, Geo gc, Lay l,
+                                                                 int cin, int cout) {
+    const unsigned v = blockIdx.x * (kThreads >> l.cshift) + (threadIdx.x >> l.cshift);
+    if (v >= l.nvox) return;
+    const Vox o = decode(v, l);                                     // coarse voxel
+    const long long po = pidx(gc, o.tile, o.ld, o.lh, o.lw);
+    for (int ci = threadIdx.x & (l.cw - 1); ci < cin; ci += l.cw) {
+        float acc = 0.f;
+        for (int k = 0; k < 8; ++k) {
+            const E *g = dy + pidx(gf, o.tile, 2 * o.ld + (k >> 2), 2 * o.lh + ((k >> 1) & 1), 2 * o.lw + (k & 1)) * cout;
+            const E *uk = u + (1LL * k * cin + ci) * cout;
+            for (int co = 0; co < cout; ++co) acc = fmaf(ldf<E>(g, co), ldf<E>(uk, co), acc);
+        }
+        stf<E>(dx, po * cin + ci, acc);
+    }
+}
+
+// Weight gradient, stage 1 (same scheme as the direct 3x3x3 weight gradient): block (k*cin + ci, chunk of
+// coarse voxels, co group); threads [voxel lane][co]; fixed-order sums; partials to ws[chunk][k][ci][co].
+template <typename E>
+__global__ __launch_bounds__(kThreads) void upconv2_wgrad_kernel(const E *__restrict__ x, const E *__restrict__ dy,
+                                                                 float *__restrict__ part, Geo gf, Geo gc, Lay l,
+                                                                 int cin, int cout, int cw, unsigned chunk_vox) {
+    __shared__ float red[kThreads];
+    const int kci = blockIdx.x, chunk = blockIdx.y;
+    const int k = kci / cin, ci = kci % cin;
+    const int nvl = kThreads / cw;
+    const int col = threadIdx.x % cw, vl = threadIdx.x / cw;
+    const int co = blockIdx.z * cw + col;
+    float acc = 0.f;
+    unsigned v1 = (chunk + 1u) * chunk_vox;
+    if (v1 > l.nvox) v1 = l.nvox;
+    if (vl < nvl && co < cout) {
+        for (unsigned v = chunk * chunk_vox + vl; v < v1; v += nvl) {
+            const Vox o = decode(v, l);                             // coarse voxel
+            const long long px = pidx(gc, o.tile, o.ld, o.lh, o.lw);
+            const long long pz = pidx(gf, o.tile, 2 * o.ld + (k >> 2), 2 * o.lh + ((k >> 1) & 1), 2 * o.lw + (k & 1));
+            acc = fmaf(ldf<E>(x, px * cin + ci), ldf<E>(dy, pz * cout + co), acc);
+        }
+    }
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    if (vl == 0 && co < cout) {
+        float s = 0.f;
+        for (int i = 0; i < nvl; ++i) s += red[i * cw + col];
+        part[(1LL * chunk * 8 * cin + kci) * cout + co] = s;
+    }
+}
+
+// Bias gradient of the up-convolution, stage 1: sum of dy over chunks of FINE interior voxels.
+template <typename E>
+__global__ __launch_bounds__(kThreads) void bsum_kernel(const E *__restrict__ dy, float *__restrict__ part, Geo g,
+                                                        Lay l, int cout, int cw, unsigned chunk_vox) {
+    __shared__ float red[kThreads];
+    const int chunk = blockIdx.y;
+    const int nvl = kThreads / cw;
+    const int col = threadIdx.x % cw, vl = threadIdx.x / cw;
+    const int co = blockIdx.z * cw + col;
+    float acc = 0.f;
+    unsigned v1 = (chunk + 1u) * chunk_vox;
+    if (v1 > l.nvox) v1 = l.nvox;
+    if (vl < nvl && co < cout) {
+        for (unsigned v = chunk * chunk_vox + vl; v < v1; v += nvl) {
+            const Vox o = decode(v, l);
+            acc += ldf<E>(dy, pidx(g, o.tile, o.ld, o.lh, o.lw) * cout + co);
+        }
+    }
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    if (vl == 0 && co < cout) {
+        float s = 0.f;
+        for (int i = 0; i < nvl; ++i) s += red[i * cw + col];
+        part[1LL * chunk * cout + co] = s;
+    }
+}
+
+// ---- channel concat / split: one thread per (padded voxel, channel of the wide tensor) --------------
+template <typename E, bool SPLIT>
+__global__ __launch_bounds__(kThreads) void concat_kernel(E *__restrict__ a, int ca, E *__restrict__ b, int cb,
+                                                          E *__restrict__ c, size_t total) {
+    const size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (i >= total) return;
+    const int cc = ca + cb;
+    const size_t v = i / cc;
+    const int ch = static_cast<int>(i % cc);
+    E *narrow = ch < ca ? a + v * ca + ch : b + v * cb + (ch - ca);
+    if (SPLIT) *narrow = c[i]; else c[i] = *narrow;
+}
+
+void reduction_plan(unsigned nvox, int *nchunks, unsigned *chunk_vox) {
+    unsigned cv = 8192;
+    unsigned nc = (nvox + cv - 1) / cv;
+    if (nc > 256) { nc = 256; cv = (nvox + nc - 1) / nc; nc = (nvox + cv - 1) / cv; }
+    *nchunks = static_cast<int>(nc);
+    *chunk_vox = cv;
+}
+
+}  // namespace
+
+int make_coarse(const Geo &gf, Geo *gc) {
+    if ((gf.td | gf.th | gf.tw) & 1) return SP_EGEOM;
+    Geo o = gf;
+    o.td = gf.td / 2; o.th = gf.th / 2; o.tw = gf.tw / 2;
+    o.pd = o.td + 2; o.ph = o.th + 2; o.pw = o.tw + 2;
+    o.tile_vox = 1LL * o.pd * o.ph * o.pw;
+    o.int_vox = 1LL * o.td * o.th * o.tw;
+    o.msg_vox = o.tile_vox - o.int_vox;
+    *gc = o;
+    return SP_OK;
+}
+
+#define SP3D_BY_DTYPE(call_bf16, call_f32) do { if (dt == SP_BF16) { call_bf16; } else { call_f32; } } while (0)
+
+int launch_maxpool2(const void *Px, const void *Pdy, void *Pout, const Geo &gf, const Geo &gc, int c,
+                    sp_dtype_t dt, bool backward, hipStream_t s) {
+    if (1LL * gc.ntiles * gc.int_vox > 0xffffff00LL) return SP_EGEOM;
+    const Lay l = make_lay(gc, c);
+    const unsigned vpb = kThreads >> l.cshift;
+    dim3 grid((l.nvox + vpb - 1) / vpb), block(kThreads);
+#define SP3D_POOL(E, B)                                                                              \
+    hipLaunchKernelGGL((maxpool2_kernel<E, B>), grid, block, 0, s, static_cast<const E *>(Px),       \
+                       static_cast<const E *>(Pdy), static_cast<E *>(Pout), gf, gc, l, c)
+    if (backward) SP3D_BY_DTYPE(SP3D_POOL(uint16_t, true), SP3D_POOL(float, true));
+    else SP3D_BY_DTYPE(SP3D_POOL(uint16_t, false), SP3D_POOL(float, false));
+#undef SP3D_POOL
+    return record_hip(hipGetLastError());
+}
+
+int launch_upconv2_fwd(const void *Px, const void *u, const float *bias, void *Py, const Geo &gf,
+                       const Geo &gc, int cin, int cout, sp_dtype_t dt, hipStream_t s) {
+    if (1LL * gf.ntiles * gf.int_vox > 0xffffff00LL) return SP_EGEOM;
+    const Lay l = make_lay(gf, cout);
+    const unsigned vpb = kThreads >> l.cshift;
+    dim3 grid((l.nvox + vpb - 1) / vpb), block(kThreads);
+#define SP3D_UP(E)                                                                                   \
+    hipLaunchKernelGGL(upconv2_fwd_kernel<E>, grid, block, 0, s, static_cast<const E *>(Px),         \
+                       static_cast<const E *>(u), bias, static_cast<E *>(Py), gf, gc, l, cin, cout)
+    SP3D_BY_DTYPE(SP3D_UP(uint16_t), SP3D_UP(float));
+#undef SP3D_UP
+    return record_hip(hipGetLastError());
+}
+
+int launch_upconv2_dgrad(const void *Pdy, const void *u, void *Pdx, const Geo &gf, const Geo &gc, int cin,
+                         int cout, sp_dtype_t dt, hipStream_t s) {
+    if (1LL * gf.ntiles * gf.int_vox > 0xffffff00LL) return SP_EGEOM;
+    const Lay l = make_lay(gc, cin);
+    const unsigned vpb = kThreads >> l.cshift;
+    dim3 grid((l.nvox + vpb - 1) / vpb), block(kThreads);
+#define SP3D_UPD(E)                                                                                  \
+    hipLaunchKernelGGL(upconv2_dgrad_kernel<E>, grid, block, 0, s, static_cast<const E *>(Pdy),      \
+                       static_cast<const E *>(u), static_cast<E *>(Pdx), gf, gc, l, cin, cout)
+    SP3D_BY_DTYPE(SP3D_UPD(uint16_t), SP3D_UPD(float));
+#undef SP3D_UPD
+    return record_hip(hipGetLastError());
+}
+
+size_t upconv2_wgrad_ws_bytes(const Geo &gc, int cin, int cout) {
+    int ncw; unsigned cvw;
+    reduction_plan(static_cast<unsigned>(1LL * gc.ntiles * gc.int_vox), &ncw, &cvw);
+    int ncb; unsigned cvb;
+    reduction_plan(static_cast<unsigned>(8LL * gc.ntiles * gc.int_vox), &ncb, &cvb);
+    return (static_cast<size_t>(ncw) * 8 * cin * cout + static_cast<size_t>(ncb) * cout) * sizeof(float);
+}
+
+int launch_upconv2_wgrad(const void *Px, const void *Pdy, float *du, float *db, const Geo &gf, const Geo &gc,
+                         int cin, int cout, sp_dtype_t dt, void *ws, hipStream_t s) {
+    if (1LL * gf.ntiles * gf.int_vox > 0xffffff00LL) return SP_EGEOM;
+    const Lay lc = make_lay(gc, cout), lf = make_lay(gf, cout);
+    int ncw, ncb; unsigned cvw, cvb;
+    reduction_plan(lc.nvox, &ncw, &cvw);
+    reduction_plan(lf.nvox, &ncb, &cvb);
+    float *part_w = static_cast<float *>(ws);
+    float *part_b = part_w + static_cast<size_t>(ncw) * 8 * cin * cout;
+    const int cw = cout < kThreads ? cout : kThreads;
+    const int zg = (cout + cw - 1) / cw;
+    dim3 block(kThreads), gw_(8 * cin, ncw, zg), gb_(1, ncb, zg);
+#define SP3D_UPW(E)                                                                                  \
+    do {                                                                                             \
+        hipLaunchKernelGGL(upconv2_wgrad_kernel<E>, gw_, block, 0, s, static_cast<const E *>(Px),    \
+                           static_cast<const E *>(Pdy), part_w, gf, gc, lc, cin, cout, cw, cvw);     \
+        if (db)                                                                                      \
+            hipLaunchKernelGGL(bsum_kernel<E>, gb_, block, 0, s, static_cast<const E *>(Pdy), part_b, gf, lf, \
+                               cout, cw, cvb);                                                       \
+    } while (0)
+    SP3D_BY_DTYPE(SP3D_UPW(uint16_t), SP3D_UPW(float));
+#undef SP3D_UPW
+    int rc = record_hip(hipGetLastError());
+    if (rc != SP_OK) return rc;
+    rc = launch_reduce_partials(part_w, du, ncw, 8LL * cin * cout, s);
+    if (rc != SP_OK) return rc;
+    if (db) rc = launch_reduce_partials(part_b, db, ncb, cout, s);
+    return rc;
+}
+
+int launch_concat(const void *Pa, int ca, const void *Pb, int cb, void *Pc, size_t voxels, sp_dtype_t dt,
+                  bool split, hipStream_t s) {
+    const size_t total = voxels * (ca + cb);
+    const size_t blocks = (total + kThreads - 1) / kThreads;
+    if (blocks > 0x7fffffffULL) return SP_EGEOM;
+    dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
+#define SP3D_CAT(E, S)                                                                               \
+    hipLaunchKernelGGL((concat_kernel<E, S>), grid, block, 0, s, static_cast<E *>(const_cast<void *>(Pa)), ca, \
+                       static_cast<E *>(const_cast<void *>(Pb)), cb, static_cast<E *>(Pc), total)
+    if (split) SP3D_BY_DTYPE(SP3D_CAT(uint16_t, true), SP3D_CAT(float, true));
+    else SP3D_BY_DTYPE(SP3D_CAT(uint16_t, false), SP3D_CAT(float, false));
+#undef SP3D_CAT
+    return record_hip(hipGetLastError());
+}
+
+}  // namespace sp3d

@@ -9,13 +9,15 @@ import os
 SP_F32, SP_BF16 = 0, 1
 SP_OK, SP_EINVAL, SP_EGEOM, SP_EUNSUPPORTED, SP_EWORKSPACE, SP_ELAUNCH = 0, -1, -2, -3, -4, -5
 SP_FLAG_RELU = 1
-SP_OP_FWD, SP_OP_DGRAD, SP_OP_WGRAD = 0, 1, 2
+SP_OP_FWD, SP_OP_DGRAD, SP_OP_WGRAD, SP_OP_UPCONV_WGRAD, SP_OP_POINTWISE_WGRAD = 0, 1, 2, 3, 4
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsp3d.so")
 
 EXPORTS = ["sp_padded_elems", "sp_msg_elems", "sp_workspace_bytes", "sp_check_geom", "sp_strerror",
            "sp_last_hip_error", "sp_partition", "sp_unpartition", "halo_pack", "halo_unpack",
-           "conv3d_fwd", "conv3d_dgrad", "conv3d_wgrad", "sp_relu_bwd"]
+           "conv3d_fwd", "conv3d_dgrad", "conv3d_wgrad", "sp_relu_bwd",
+           "sp_maxpool2_fwd", "sp_maxpool2_bwd", "sp_upconv2_fwd", "sp_upconv2_dgrad", "sp_upconv2_wgrad",
+           "sp_pointwise_fwd", "sp_pointwise_dgrad", "sp_pointwise_wgrad", "sp_concat", "sp_split"]
 
 
 class Geom(ctypes.Structure):
@@ -68,6 +70,16 @@ def lib():
         L.conv3d_dgrad.argtypes, L.conv3d_dgrad.restype = [P, P, P, G, I, I, I, P, Z, P], I
         L.conv3d_wgrad.argtypes, L.conv3d_wgrad.restype = [P, P, P, P, G, I, I, I, P, Z, P], I
         L.sp_relu_bwd.argtypes, L.sp_relu_bwd.restype = [P, P, P, G, I, I, P], I
+        L.sp_maxpool2_fwd.argtypes, L.sp_maxpool2_fwd.restype = [P, P, G, I, I, P], I
+        L.sp_maxpool2_bwd.argtypes, L.sp_maxpool2_bwd.restype = [P, P, P, G, I, I, P], I
+        L.sp_upconv2_fwd.argtypes, L.sp_upconv2_fwd.restype = [P, P, P, P, G, I, I, I, P], I
+        L.sp_upconv2_dgrad.argtypes, L.sp_upconv2_dgrad.restype = [P, P, P, G, I, I, I, P], I
+        L.sp_upconv2_wgrad.argtypes, L.sp_upconv2_wgrad.restype = [P, P, P, P, G, I, I, I, P, Z, P], I
+        L.sp_pointwise_fwd.argtypes, L.sp_pointwise_fwd.restype = [P, P, P, P, G, I, I, I, U, P], I
+        L.sp_pointwise_dgrad.argtypes, L.sp_pointwise_dgrad.restype = [P, P, P, G, I, I, I, P], I
+        L.sp_pointwise_wgrad.argtypes, L.sp_pointwise_wgrad.restype = [P, P, P, P, G, I, I, I, P, Z, P], I
+        L.sp_concat.argtypes, L.sp_concat.restype = [P, I, P, I, P, G, I, P], I
+        L.sp_split.argtypes, L.sp_split.restype = [P, P, I, P, I, G, I, P], I
         _lib = L
     return _lib
 
@@ -155,6 +167,62 @@ def conv3d_wgrad(Px, Pdz, dw, db, g, cin, cout, dt, ws=None, stream=None):
 def sp_relu_bwd(Pdy, Py, Pdz, g, c, dt, stream=None):
     _check(lib().sp_relu_bwd(_ptr(Pdy), _ptr(Py), _ptr(Pdz), ctypes.byref(g), c, dt, _stream(stream)),
            "sp_relu_bwd")
+
+
+def sp_maxpool2_fwd(Px, Py, gf, c, dt, stream=None):
+    _check(lib().sp_maxpool2_fwd(_ptr(Px), _ptr(Py), ctypes.byref(gf), c, dt, _stream(stream)), "sp_maxpool2_fwd")
+
+
+def sp_maxpool2_bwd(Px, Pdy, Pdx, gf, c, dt, stream=None):
+    _check(lib().sp_maxpool2_bwd(_ptr(Px), _ptr(Pdy), _ptr(Pdx), ctypes.byref(gf), c, dt, _stream(stream)),
+           "sp_maxpool2_bwd")
+
+
+def sp_upconv2_fwd(Px, u, bias, Py, gf, cin, cout, dt, stream=None):
+    _check(lib().sp_upconv2_fwd(_ptr(Px), _ptr(u), _ptr(bias), _ptr(Py), ctypes.byref(gf), cin, cout, dt,
+                                _stream(stream)), "sp_upconv2_fwd")
+
+
+def sp_upconv2_dgrad(Pdy, u, Pdx, gf, cin, cout, dt, stream=None):
+    _check(lib().sp_upconv2_dgrad(_ptr(Pdy), _ptr(u), _ptr(Pdx), ctypes.byref(gf), cin, cout, dt,
+                                  _stream(stream)), "sp_upconv2_dgrad")
+
+
+def sp_upconv2_wgrad(Px, Pdy, du, db, gf, cin, cout, dt, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib().sp_upconv2_wgrad(_ptr(Px), _ptr(Pdy), _ptr(du), _ptr(db), ctypes.byref(gf), cin, cout, dt,
+                                  wp, wb, _stream(stream)), "sp_upconv2_wgrad")
+
+
+def sp_pointwise_fwd(Px, p, bias, Py, g, cin, cout, dt, flags=0, stream=None):
+    _check(lib().sp_pointwise_fwd(_ptr(Px), _ptr(p), _ptr(bias), _ptr(Py), ctypes.byref(g), cin, cout, dt,
+                                  flags, _stream(stream)), "sp_pointwise_fwd")
+
+
+def sp_pointwise_dgrad(Pdy, p, Pdx, g, cin, cout, dt, stream=None):
+    _check(lib().sp_pointwise_dgrad(_ptr(Pdy), _ptr(p), _ptr(Pdx), ctypes.byref(g), cin, cout, dt,
+                                    _stream(stream)), "sp_pointwise_dgrad")
+
+
+def sp_pointwise_wgrad(Px, Pdy, dp, db, g, cin, cout, dt, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib().sp_pointwise_wgrad(_ptr(Px), _ptr(Pdy), _ptr(dp), _ptr(db), ctypes.byref(g), cin, cout, dt,
+                                    wp, wb, _stream(stream)), "sp_pointwise_wgrad")
+
+
+def sp_concat(Pa, ca, Pb, cb, Pout, g, dt, stream=None):
+    _check(lib().sp_concat(_ptr(Pa), ca, _ptr(Pb), cb, _ptr(Pout), ctypes.byref(g), dt, _stream(stream)),
+           "sp_concat")
+
+
+def sp_split(Pin, Pa, ca, Pb, cb, g, dt, stream=None):
+    _check(lib().sp_split(_ptr(Pin), _ptr(Pa), ca, _ptr(Pb), cb, ctypes.byref(g), dt, _stream(stream)),
+           "sp_split")
+
+
+def coarse_geom(gf):
+    """Geometry of the half-resolution side of a pooling / up-convolution on the same tile grid."""
+    return Geom(gf.n, (gf.d // 2, gf.h // 2, gf.w // 2), (gf.gd, gf.gh, gf.gw), gf.halo)
 
 
 # ---- plumbing helpers (device memory only; no arithmetic) ---------------------------------------
