@@ -178,6 +178,10 @@ int sp_concat(const void *Pa, int ca, const void *Pb, int cb, void *Pout, const 
               sp_dtype_t dt, void *stream);
 int sp_split(const void *Pin, void *Pa, int ca, void *Pb, int cb, const sp_geom_t *g, sp_dtype_t dt,
              void *stream);
+/* Pout = Pa + Pb element-wise over all voxels of the padded arrays (the two gradient paths that meet
+ * at a skip connection); fp32 addition, one rounding to the tensor dtype.  Pout may alias Pa or Pb. */
+int sp_add(const void *Pa, const void *Pb, void *Pout, const sp_geom_t *g, int c, sp_dtype_t dt,
+           void *stream);
 
 #ifdef __cplusplus
 }

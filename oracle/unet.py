@@ -1,0 +1,94 @@
+"""fp64 oracle of the U-Net convolution stack on the unpartitioned volume (test infrastructure only).
+
+Composes the direct-convolution oracle and the glue oracle in the order of the paper's network
+(Sec. 3, first paragraph) as fixed by the workload list: per level two 3x3x3 conv + ReLU, 2x2x2
+max-pool between levels, decoder = transposed conv, concat (skip, up), two conv + ReLU, final 1x1x1
+conv.  Biases are zero.  All arithmetic is fp64.  With `store=None` activations stay fp64 throughout;
+with `store=round_bf16` every tensor that the path keeps in memory (each layer output, each
+propagated gradient) is rounded to the bf16 storage type first, so that the decisions the path takes
+on stored values -- the ReLU mask and the max-pool argmax -- are taken on the same kind of value
+as on the device (the workload list fixes bf16 storage with fp32 accumulation).
+"""
+import numpy as np
+
+from . import conv3d, unet_ops as U
+
+
+def round_bf16(a):
+    """fp64 -> nearest bf16 (ties to even), returned as fp64."""
+    u = np.asarray(a, dtype=np.float64).astype(np.float32).view(np.uint32)
+    r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) & np.uint32(0xFFFF0000)
+    return r.view(np.float32).astype(np.float64)
+
+
+def forward(x, w, channels, keep=None, store=None):
+    """x [N,D,H,W,Cin] fp64; w: name -> fp64 weights.  Returns logits; fills `keep` with activations."""
+    L = len(channels)
+    A = {} if keep is None else keep
+    q = store if store is not None else (lambda a: a)
+    h = np.asarray(x, dtype=np.float64)
+    for i in range(L):
+        if i > 0:
+            h = U.maxpool2_fwd(h)
+        A["enc%d_a.x" % i] = h
+        h = q(conv3d.conv3d_fwd(h, w["enc%d_a" % i], relu=True))
+        A["enc%d_b.x" % i] = h
+        h = q(conv3d.conv3d_fwd(h, w["enc%d_b" % i], relu=True))
+        A["enc%d.y" % i] = h
+    for i in range(L - 2, -1, -1):
+        A["up%d.x" % i] = h
+        up = q(U.upconv2_fwd(h, w["up%d" % i]))
+        h = U.concat(A["enc%d.y" % i], up)
+        A["dec%d_a.x" % i] = h
+        h = q(conv3d.conv3d_fwd(h, w["dec%d_a" % i], relu=True))
+        A["dec%d_b.x" % i] = h
+        h = q(conv3d.conv3d_fwd(h, w["dec%d_b" % i], relu=True))
+        A["dec%d.y" % i] = h
+    A["head.x"] = h
+    p = w["head"]
+    return q(U.pointwise_fwd(h, p.reshape(p.shape[-2], p.shape[-1])))
+
+
+def backward(dlogits, w, channels, A, store=None, trace=None):
+    """Gradients of <logits, dlogits> with respect to every weight tensor and the input.
+    `trace`, if given, receives the stored tensors of the backward pass by name
+    ("<layer>.dy" incoming gradient, "<layer>.dx" outgoing gradient, "pool<i>.dy", "skip<i>")."""
+    L = len(channels)
+    grads = {}
+    T = {} if trace is None else trace
+    q = store if store is not None else (lambda a: a)
+    p = w["head"].reshape(w["head"].shape[-2], w["head"].shape[-1])
+    dp, _ = U.pointwise_wgrad(A["head.x"], dlogits)
+    grads["head"] = dp.reshape(w["head"].shape)
+    g = q(U.pointwise_dgrad(dlogits, p))
+    T["head.dx"] = g
+
+    def conv_bwd(name, x, y, dy):
+        T[name + ".dy"] = dy
+        dz = conv3d.relu_bwd(dy, y)
+        grads[name] = conv3d.conv3d_wgrad(x, dz)
+        dx = q(conv3d.conv3d_dgrad(dz, w[name]))
+        T[name + ".dx"] = dx
+        return dx
+
+    skip = {}
+    for i in range(0, L - 1):
+        c = channels[i]
+        g = conv_bwd("dec%d_b" % i, A["dec%d_b.x" % i], A["dec%d.y" % i], g)
+        g = conv_bwd("dec%d_a" % i, A["dec%d_a.x" % i], A["dec%d_b.x" % i], g)
+        skip[i], gu = U.split(g, c)
+        T["skip%d" % i], T["up%d.dy" % i] = skip[i], gu
+        grads["up%d" % i], _ = U.upconv2_wgrad(A["up%d.x" % i], gu)
+        g = q(U.upconv2_dgrad(gu, w["up%d" % i]))
+        T["up%d.dx" % i] = g
+    for i in range(L - 1, -1, -1):
+        if i in skip:
+            T["add%d.a" % i] = g
+            g = q(g + skip[i])
+        g = conv_bwd("enc%d_b" % i, A["enc%d_b.x" % i], A["enc%d.y" % i], g)
+        g = conv_bwd("enc%d_a" % i, A["enc%d_a.x" % i], A["enc%d_b.x" % i], g)
+        if i > 0:
+            T["pool%d.dy" % i] = g
+            g = U.maxpool2_bwd(A["enc%d.y" % (i - 1)], g)
+            T["pool%d.dx" % i] = g
+    return grads, g

@@ -367,4 +367,12 @@ int sp_split(const void *Pin, void *Pa, int ca, void *Pb, int cb, const sp_geom_
                          dt, true, static_cast<hipStream_t>(stream));
 }
 
+int sp_add(const void *Pa, const void *Pb, void *Pout, const sp_geom_t *g, int c, sp_dtype_t dt, void *stream) {
+    Geo o;
+    int rc = check_glue(Pa, Pb, Pout, g, c, c, dt, &o, nullptr);
+    if (rc != SP_OK) return rc;
+    return launch_add(Pa, Pb, Pout, static_cast<size_t>(o.ntiles) * o.tile_vox * c, dt,
+                      static_cast<hipStream_t>(stream));
+}
+
 }  // extern "C"

@@ -202,6 +202,13 @@ __global__ __launch_bounds__(kThreads) void concat_kernel(E *__restrict__ a, int
     if (SPLIT) *narrow = c[i]; else c[i] = *narrow;
 }
 
+template <typename E>
+__global__ __launch_bounds__(kThreads) void add_kernel(const E *__restrict__ a, const E *__restrict__ b,
+                                                       E *__restrict__ o, size_t n) {
+    const size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (i < n) stf<E>(o, i, ldf<E>(a, i) + ldf<E>(b, i));
+}
+
 void reduction_plan(unsigned nvox, int *nchunks, unsigned *chunk_vox) {
     unsigned cv = 8192;
     unsigned nc = (nvox + cv - 1) / cv;
@@ -305,6 +312,17 @@ int launch_upconv2_wgrad(const void *Px, const void *Pdy, float *du, float *db, 
     if (rc != SP_OK) return rc;
     if (db) rc = launch_reduce_partials(part_b, db, ncb, cout, s);
     return rc;
+}
+
+int launch_add(const void *Pa, const void *Pb, void *Pout, size_t elems, sp_dtype_t dt, hipStream_t s) {
+    const size_t blocks = (elems + kThreads - 1) / kThreads;
+    if (blocks > 0x7fffffffULL) return SP_EGEOM;
+    dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
+    SP3D_BY_DTYPE(hipLaunchKernelGGL(add_kernel<uint16_t>, grid, block, 0, s, static_cast<const uint16_t *>(Pa),
+                                     static_cast<const uint16_t *>(Pb), static_cast<uint16_t *>(Pout), elems),
+                  hipLaunchKernelGGL(add_kernel<float>, grid, block, 0, s, static_cast<const float *>(Pa),
+                                     static_cast<const float *>(Pb), static_cast<float *>(Pout), elems));
+    return record_hip(hipGetLastError());
 }
 
 int launch_concat(const void *Pa, int ca, const void *Pb, int cb, void *Pc, size_t voxels, sp_dtype_t dt,

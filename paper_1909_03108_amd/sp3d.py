@@ -17,7 +17,7 @@ EXPORTS = ["sp_padded_elems", "sp_msg_elems", "sp_workspace_bytes", "sp_check_ge
            "sp_last_hip_error", "sp_partition", "sp_unpartition", "halo_pack", "halo_unpack",
            "conv3d_fwd", "conv3d_dgrad", "conv3d_wgrad", "sp_relu_bwd",
            "sp_maxpool2_fwd", "sp_maxpool2_bwd", "sp_upconv2_fwd", "sp_upconv2_dgrad", "sp_upconv2_wgrad",
-           "sp_pointwise_fwd", "sp_pointwise_dgrad", "sp_pointwise_wgrad", "sp_concat", "sp_split"]
+           "sp_pointwise_fwd", "sp_pointwise_dgrad", "sp_pointwise_wgrad", "sp_concat", "sp_split", "sp_add"]
 
 
 class Geom(ctypes.Structure):
@@ -80,6 +80,7 @@ def lib():
         L.sp_pointwise_wgrad.argtypes, L.sp_pointwise_wgrad.restype = [P, P, P, P, G, I, I, I, P, Z, P], I
         L.sp_concat.argtypes, L.sp_concat.restype = [P, I, P, I, P, G, I, P], I
         L.sp_split.argtypes, L.sp_split.restype = [P, P, I, P, I, G, I, P], I
+        L.sp_add.argtypes, L.sp_add.restype = [P, P, P, G, I, I, P], I
         _lib = L
     return _lib
 
@@ -218,6 +219,10 @@ def sp_concat(Pa, ca, Pb, cb, Pout, g, dt, stream=None):
 def sp_split(Pin, Pa, ca, Pb, cb, g, dt, stream=None):
     _check(lib().sp_split(_ptr(Pin), _ptr(Pa), ca, _ptr(Pb), cb, ctypes.byref(g), dt, _stream(stream)),
            "sp_split")
+
+
+def sp_add(Pa, Pb, Pout, g, c, dt, stream=None):
+    _check(lib().sp_add(_ptr(Pa), _ptr(Pb), _ptr(Pout), ctypes.byref(g), c, dt, _stream(stream)), "sp_add")
 
 
 def coarse_geom(gf):

@@ -1,0 +1,179 @@
+"""Forward + backward of the 3D U-Net convolution stack on a tile grid, as a sequence of C-ABI calls.
+
+Plumbing only: this module allocates device buffers (torch) and orders the library calls; every
+operation -- partition, halo exchange, the convolutions, pooling, up-convolution, concat, the
+element-wise masks and adds -- runs in the HIP kernels of libsp3d.
+
+Architecture (the paper's Sec. 3 network in the shape the workload list fixes): encoder levels with
+channels `channels`, two 3x3x3 conv + ReLU per level, 2x2x2 max-pool between levels; the last level
+is the bottleneck; decoder levels mirror the encoder: 2x2x2 stride-2 transposed conv halving the
+channels, concat (skip, up), two 3x3x3 conv + ReLU; a final 1x1x1 conv to `classes`.  Biases are
+zero and not passed.  Every 3x3x3 conv input is halo-exchanged (pack + unpack) first.
+"""
+import numpy as np
+import torch
+
+from . import sp3d
+
+
+def layer_plan(channels=(32, 64, 128, 256), in_ch=1, classes=3):
+    """Names and shapes of all weight tensors, in forward order."""
+    plan = []
+    prev = in_ch
+    for i, c in enumerate(channels):
+        plan += [("enc%d_a" % i, (3, 3, 3, prev, c)), ("enc%d_b" % i, (3, 3, 3, c, c))]
+        prev = c
+    for i in range(len(channels) - 2, -1, -1):
+        c = channels[i]
+        plan += [("up%d" % i, (2, 2, 2, prev, c)), ("dec%d_a" % i, (3, 3, 3, 2 * c, c)),
+                 ("dec%d_b" % i, (3, 3, 3, c, c))]
+        prev = c
+    plan.append(("head", (1, 1, 1, prev, classes)))
+    return plan
+
+
+class UNet:
+    def __init__(self, n, dhw, grid, weights, channels=(32, 64, 128, 256), in_ch=1, classes=3,
+                 dt=sp3d.SP_BF16):
+        self.channels, self.in_ch, self.classes, self.dt = tuple(channels), in_ch, classes, dt
+        self.L = len(channels)
+        self.g = [sp3d.Geom(n, tuple(e >> i for e in dhw), grid) for i in range(self.L)]
+        for g in self.g:
+            assert sp3d.sp_check_geom(g) == sp3d.SP_OK
+        self.w = weights                      # name -> device tensor
+        self.msg = {}
+        self.ws_cache = {}
+
+    # ---- small helpers -------------------------------------------------------------------------
+    def _ws(self, op, g, cin, cout):
+        nbytes = sp3d.sp_workspace_bytes(op, g, cin, cout, self.dt)
+        key = max(nbytes, 16)
+        cur = self.ws_cache.get("buf")
+        if cur is None or cur.numel() < key:
+            cur = sp3d.alloc_ws(key)
+            self.ws_cache["buf"] = cur
+        return cur
+
+    def _exchange(self, P, g, c):
+        need = sp3d.sp_msg_elems(g, c)
+        m = self.msg.get("buf")
+        if m is None or m.numel() < need:
+            m = torch.empty((need,), dtype=sp3d.torch_dtype(self.dt), device="cuda")
+            self.msg["buf"] = m
+        sp3d.halo_pack(P, m, g, c, self.dt)
+        sp3d.halo_unpack(P, m, g, c, self.dt)
+
+    def _conv(self, Px, name, g, cin, cout):
+        """Px must hold its halos.  Returns relu(conv(Px)) as padded tiles (margins zero)."""
+        Py = sp3d.alloc_padded(g, cout, self.dt)
+        sp3d.conv3d_fwd(Px, self.w[name], None, Py, g, cin, cout, self.dt, sp3d.SP_FLAG_RELU,
+                        self._ws(sp3d.SP_OP_FWD, g, cin, cout))
+        return Py
+
+    # ---- forward ----------------------------------------------------------------------------------
+    def forward(self, x_vol):
+        """x_vol: device volume [n,d,h,w,in_ch].  Returns the logits volume; keeps what backward needs."""
+        dt, ch = self.dt, self.channels
+        A = {}                                   # saved activations (padded, halos exchanged where needed)
+        P = sp3d.alloc_padded(self.g[0], self.in_ch, dt)
+        sp3d.sp_partition(x_vol, P, self.g[0], self.in_ch, dt)
+        prev = self.in_ch
+        for i in range(self.L):
+            g, c = self.g[i], ch[i]
+            if i > 0:
+                Pp = sp3d.alloc_padded(g, prev, dt)
+                sp3d.sp_maxpool2_fwd(P, Pp, self.g[i - 1], prev, dt)
+                P = Pp
+            self._exchange(P, g, prev)
+            A["enc%d_a.x" % i] = P
+            P = self._conv(P, "enc%d_a" % i, g, prev, c)
+            self._exchange(P, g, c)
+            A["enc%d_b.x" % i] = P
+            P = self._conv(P, "enc%d_b" % i, g, c, c)
+            A["enc%d.y" % i] = P                 # level output: pool input / skip / ReLU mask
+            prev = c
+        for i in range(self.L - 2, -1, -1):
+            g, c = self.g[i], ch[i]
+            A["up%d.x" % i] = P
+            Pu = sp3d.alloc_padded(g, c, dt)
+            sp3d.sp_upconv2_fwd(P, self.w["up%d" % i], None, Pu, g, prev, c, dt)
+            Pc = sp3d.alloc_padded(g, 2 * c, dt)
+            sp3d.sp_concat(A["enc%d.y" % i], c, Pu, c, Pc, g, dt)
+            self._exchange(Pc, g, 2 * c)
+            A["dec%d_a.x" % i] = Pc
+            P = self._conv(Pc, "dec%d_a" % i, g, 2 * c, c)
+            self._exchange(P, g, c)
+            A["dec%d_b.x" % i] = P
+            P = self._conv(P, "dec%d_b" % i, g, c, c)
+            A["dec%d.y" % i] = P
+            prev = c
+        A["head.x"] = P
+        Pl = sp3d.alloc_padded(self.g[0], self.classes, dt)
+        sp3d.sp_pointwise_fwd(P, self.w["head"], None, Pl, self.g[0], prev, self.classes, dt)
+        self.A = A
+        g0 = self.g[0]
+        out = torch.empty((g0.n, g0.d, g0.h, g0.w, self.classes), dtype=Pl.dtype, device="cuda")
+        sp3d.sp_unpartition(Pl, out, g0, self.classes, dt)
+        return out
+
+    # ---- backward ---------------------------------------------------------------------------------
+    def _conv_bwd(self, name, Px, Py, Pdy, g, cin, cout, grads, need_dx=True):
+        """Backward of y = relu(conv(x)): Pdy is d/dy (interiors valid).  Returns d/dx (padded)."""
+        dt = self.dt
+        sp3d.sp_relu_bwd(Pdy, Py, Pdy, g, cout, dt)                   # dz in place
+        dw = torch.empty((3, 3, 3, cin, cout), dtype=torch.float32, device="cuda")
+        sp3d.conv3d_wgrad(Px, Pdy, dw, None, g, cin, cout, dt, self._ws(sp3d.SP_OP_WGRAD, g, cin, cout))
+        grads[name] = dw
+        if not need_dx:
+            return None
+        self._exchange(Pdy, g, cout)
+        Pdx = sp3d.alloc_padded(g, cin, dt)
+        sp3d.conv3d_dgrad(Pdy, self.w[name], Pdx, g, cin, cout, dt, self._ws(sp3d.SP_OP_DGRAD, g, cin, cout))
+        return Pdx
+
+    def backward(self, dlogits_vol, input_grad=True):
+        """dlogits_vol: device volume [n,d,h,w,classes].  Returns (grads by layer name, dx volume or None)."""
+        dt, ch, A = self.dt, self.channels, self.A
+        grads = {}
+        g0 = self.g[0]
+        Pd = sp3d.alloc_padded(g0, self.classes, dt)
+        sp3d.sp_partition(dlogits_vol, Pd, g0, self.classes, dt)
+        c0 = ch[0]
+        dp = torch.empty((1, 1, 1, c0, self.classes), dtype=torch.float32, device="cuda")
+        sp3d.sp_pointwise_wgrad(A["head.x"], Pd, dp, None, g0, c0, self.classes, dt,
+                                self._ws(sp3d.SP_OP_POINTWISE_WGRAD, g0, c0, self.classes))
+        grads["head"] = dp
+        Pg = sp3d.alloc_padded(g0, c0, dt)
+        sp3d.sp_pointwise_dgrad(Pd, self.w["head"], Pg, g0, c0, self.classes, dt)
+        skip_grad = {}
+        for i in range(0, self.L - 1):
+            g, c = self.g[i], ch[i]
+            up_in = ch[i + 1]
+            Pg = self._conv_bwd("dec%d_b" % i, A["dec%d_b.x" % i], A["dec%d.y" % i], Pg, g, c, c, grads)
+            Pg = self._conv_bwd("dec%d_a" % i, A["dec%d_a.x" % i], A["dec%d_b.x" % i], Pg, g, 2 * c, c, grads)
+            Ps, Pu = sp3d.alloc_padded(g, c, dt), sp3d.alloc_padded(g, c, dt)
+            sp3d.sp_split(Pg, Ps, c, Pu, c, g, dt)
+            skip_grad[i] = Ps
+            du = torch.empty((2, 2, 2, up_in, c), dtype=torch.float32, device="cuda")
+            sp3d.sp_upconv2_wgrad(A["up%d.x" % i], Pu, du, None, g, up_in, c, dt,
+                                  self._ws(sp3d.SP_OP_UPCONV_WGRAD, g, up_in, c))
+            grads["up%d" % i] = du
+            Pg = sp3d.alloc_padded(self.g[i + 1], up_in, dt)
+            sp3d.sp_upconv2_dgrad(Pu, self.w["up%d" % i], Pg, g, up_in, c, dt)
+        for i in range(self.L - 1, -1, -1):
+            g, c = self.g[i], ch[i]
+            cin = self.in_ch if i == 0 else ch[i - 1]
+            if i in skip_grad:                                        # gradient through the skip connection
+                sp3d.sp_add(Pg, skip_grad[i], Pg, g, c, dt)
+            Pg = self._conv_bwd("enc%d_b" % i, A["enc%d_b.x" % i], A["enc%d.y" % i], Pg, g, c, c, grads)
+            Pg = self._conv_bwd("enc%d_a" % i, A["enc%d_a.x" % i], A["enc%d_b.x" % i], Pg, g, cin, c, grads,
+                                need_dx=(i > 0 or input_grad))
+            if i > 0:
+                Pf = sp3d.alloc_padded(self.g[i - 1], cin, dt)
+                sp3d.sp_maxpool2_bwd(A["enc%d.y" % (i - 1)], Pg, Pf, self.g[i - 1], cin, dt)
+                Pg = Pf
+        dx = None
+        if input_grad:
+            dx = torch.empty((g0.n, g0.d, g0.h, g0.w, self.in_ch), dtype=Pg.dtype, device="cuda")
+            sp3d.sp_unpartition(Pg, dx, g0, self.in_ch, dt)
+        return grads, dx

@@ -1,0 +1,171 @@
+"""The whole U-Net convolution stack (configuration 5's architecture: 4 levels, channels 32/64/128/256,
+two conv+ReLU per level, 2x2x2 max-pool, 2x2x2 transposed conv, skip concat, 1x1x1 head, grid 4x4x1)
+on the GPU against the composed oracle, at a volume size the fp64 oracle finishes in seconds.  Tile
+extents shrink to 1x1x4 voxels at the bottleneck, which exercises the smallest legal tiles.
+
+The oracle runs in its storage-aware mode (every stored tensor rounded to bf16, arithmetic in fp64).
+Three checks:
+ 1. free-running forward (the GPU consumes its own intermediates): logits within 3e-2 element-wise and
+    1e-2 in relative rms of the oracle chain (15 stored layers, one bf16 rounding each);
+ 2. teacher-forced: every operation of the forward and backward pass, at its real shape in the stack,
+    is run on the GPU from the ORACLE's stored inputs and compared element-wise to 1e-2 (exact for the
+    selects: ReLU mask, pooling routes, concat / split);
+ 3. free-running backward: wiring check only.  A pre-activation within the forward error of zero takes
+    the other ReLU branch on about 0.1 % of the voxels, and each flip changes a gradient element by its
+    full size, so two correct implementations differ by several per cent in rms here; the chain is held
+    to 0.25 in relative rms (a wiring mistake gives ~1).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import unet as OU
+from paper_1909_03108_amd import sp3d, synth, unet as PU
+from gpu_util import f64, rel_err, to_dev, widen
+
+pytestmark = pytest.mark.gpu
+DT = sp3d.SP_BF16
+
+
+def rel_rms(got, ref):
+    return float(np.sqrt(np.mean((got - ref) ** 2)) / np.sqrt(np.mean(ref ** 2)))
+
+
+def bf16_bits(a64):
+    """fp64 array holding bf16-representable values -> uint16 bit patterns"""
+    return (np.asarray(a64, dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+
+
+class Dev:
+    """host fp64 volume (bf16-representable) <-> padded device tiles"""
+
+    def __init__(self, net):
+        self.net = net
+
+    def up(self, g, a64, exchange=False):
+        c = a64.shape[-1]
+        P = sp3d.alloc_padded(g, c, DT)
+        sp3d.sp_partition(to_dev(bf16_bits(a64)), P, g, c, DT)
+        if exchange:
+            self.net._exchange(P, g, c)
+        return P
+
+    def down(self, g, P):
+        c = P.shape[-1]
+        V = torch.empty((g.n, g.d, g.h, g.w, c), dtype=P.dtype, device="cuda")
+        sp3d.sp_unpartition(P, V, g, c, DT)
+        return f64(V)
+
+
+@pytest.mark.timeout(900)
+def test_unet_stack_reduced_size():
+    channels, in_ch, classes = (32, 64, 128, 256), 1, 3
+    n, dhw, grid = 1, (32, 32, 32), (4, 4, 1)
+    L = len(channels)
+    plan = PU.layer_plan(channels, in_ch, classes)
+    x = synth.ct_like_volume((n,) + dhw + (in_ch,), synth.seed_for(5, synth.T_INPUT), "bf16")
+    w_h = {name: synth.weights(shape[3], shape[4], synth.seed_for(5, synth.T_WEIGHT0 + k), "bf16",
+                               taps=shape[:3]) for k, (name, shape) in enumerate(plan)}
+    dl = synth.normal_volume((n,) + dhw + (classes,), synth.seed_for(5, synth.T_UPSTREAM), "bf16")
+    w64 = {k: widen(v) for k, v in w_h.items()}
+    A, T = {}, {}
+    ref_logits = OU.forward(widen(x), w64, channels, keep=A, store=OU.round_bf16)
+    ref_grads, ref_dx = OU.backward(widen(dl), w64, channels, A, store=OU.round_bf16, trace=T)
+
+    net = PU.UNet(n, dhw, grid, {k: to_dev(v) for k, v in w_h.items()}, channels, in_ch, classes)
+    dev = Dev(net)
+
+    # ---- 1. free-running forward ------------------------------------------------------------------
+    logits = f64(net.forward(to_dev(x)))
+    assert rel_err(logits, ref_logits) <= 3e-2 and rel_rms(logits, ref_logits) <= 1e-2
+
+    # ---- 3. free-running backward (wiring) ----------------------------------------------------------
+    grads, dx = net.backward(to_dev(dl))
+    worst = max([rel_rms(f64(grads[k]), ref_grads[k]) for k, _ in plan] + [rel_rms(f64(dx), ref_dx)])
+    print("free-running backward: worst relative rms %.3f" % worst)
+    assert worst <= 0.25
+    del grads, dx
+
+    # ---- 2. teacher-forced, operation by operation ----------------------------------------------------
+    tol = 1e-2
+    errs = {}
+
+    def conv_layer(name, lvl):
+        g = net.g[lvl]
+        cin, cout = w_h[name].shape[3], w_h[name].shape[4]
+        ykey = {"a": name[:-2] + "_b.x", "b": name[:-2] + ".y"}[name[-1]]
+        Px = dev.up(g, A[name + ".x"], exchange=True)
+        Py = net._conv(Px, name, g, cin, cout)
+        errs[name + ".fwd"] = rel_err(dev.down(g, Py), A[ykey])
+        # backward of the same layer from the oracle's stored y and dy
+        Py_o = dev.up(g, A[ykey])
+        Pdy = dev.up(g, T[name + ".dy"])
+        sp3d.sp_relu_bwd(Pdy, Py_o, Pdy, g, cout, DT)
+        dz_ref = np.where(A[ykey] > 0, T[name + ".dy"], 0.0)
+        assert np.array_equal(dev.down(g, Pdy), dz_ref), name
+        dw = torch.empty((3, 3, 3, cin, cout), dtype=torch.float32, device="cuda")
+        sp3d.conv3d_wgrad(Px, Pdy, dw, None, g, cin, cout, DT, net._ws(sp3d.SP_OP_WGRAD, g, cin, cout))
+        errs[name + ".wgrad"] = rel_err(f64(dw), ref_grads[name])
+        net._exchange(Pdy, g, cout)
+        Pdx = sp3d.alloc_padded(g, cin, DT)
+        sp3d.conv3d_dgrad(Pdy, net.w[name], Pdx, g, cin, cout, DT, net._ws(sp3d.SP_OP_DGRAD, g, cin, cout))
+        errs[name + ".dgrad"] = rel_err(dev.down(g, Pdx), T[name + ".dx"])
+
+    for i in range(L):
+        conv_layer("enc%d_a" % i, i)
+        conv_layer("enc%d_b" % i, i)
+        if i > 0:
+            gf, gc = net.g[i - 1], net.g[i]
+            c = channels[i - 1]
+            Pf = dev.up(gf, A["enc%d.y" % (i - 1)])
+            Pc = sp3d.alloc_padded(gc, c, DT)
+            sp3d.sp_maxpool2_fwd(Pf, Pc, gf, c, DT)
+            assert np.array_equal(dev.down(gc, Pc), A["enc%d_a.x" % i])
+            Pdx = sp3d.alloc_padded(gf, c, DT)
+            sp3d.sp_maxpool2_bwd(Pf, dev.up(gc, T["pool%d.dy" % i]), Pdx, gf, c, DT)
+            assert np.array_equal(dev.down(gf, Pdx), T["pool%d.dx" % i])
+    for i in range(L - 2, -1, -1):
+        gf, gc = net.g[i], net.g[i + 1]
+        cin, c = channels[i + 1], channels[i]
+        Px = dev.up(gc, A["up%d.x" % i])
+        Pu = sp3d.alloc_padded(gf, c, DT)
+        sp3d.sp_upconv2_fwd(Px, net.w["up%d" % i], None, Pu, gf, cin, c, DT)
+        Pcat = sp3d.alloc_padded(gf, 2 * c, DT)
+        sp3d.sp_concat(dev.up(gf, A["enc%d.y" % i]), c, Pu, c, Pcat, gf, DT)
+        got = dev.down(gf, Pcat)
+        assert np.array_equal(got[..., :c], A["dec%d_a.x" % i][..., :c])
+        errs["up%d.fwd" % i] = rel_err(got[..., c:], A["dec%d_a.x" % i][..., c:])
+        Pdy = dev.up(gf, T["up%d.dy" % i])
+        du = torch.empty((2, 2, 2, cin, c), dtype=torch.float32, device="cuda")
+        sp3d.sp_upconv2_wgrad(Px, Pdy, du, None, gf, cin, c, DT, net._ws(sp3d.SP_OP_UPCONV_WGRAD, gf, cin, c))
+        errs["up%d.wgrad" % i] = rel_err(f64(du), ref_grads["up%d" % i])
+        Pdx = sp3d.alloc_padded(gc, cin, DT)
+        sp3d.sp_upconv2_dgrad(Pdy, net.w["up%d" % i], Pdx, gf, cin, c, DT)
+        errs["up%d.dgrad" % i] = rel_err(dev.down(gc, Pdx), T["up%d.dx" % i])
+        conv_layer("dec%d_a" % i, i)
+        conv_layer("dec%d_b" % i, i)
+        # skip-connection add and split
+        Pa = dev.up(gf, T["add%d.a" % i])
+        sp3d.sp_add(Pa, dev.up(gf, T["skip%d" % i]), Pa, gf, c, DT)
+        errs["add%d" % i] = rel_err(dev.down(gf, Pa), T["enc%d_b.dy" % i])
+        Ps, Pu2 = sp3d.alloc_padded(gf, c, DT), sp3d.alloc_padded(gf, c, DT)
+        sp3d.sp_split(dev.up(gf, T["dec%d_a.dx" % i]), Ps, c, Pu2, c, gf, DT)
+        assert np.array_equal(dev.down(gf, Ps), T["skip%d" % i])
+        assert np.array_equal(dev.down(gf, Pu2), T["up%d.dy" % i])
+    g0 = net.g[0]
+    Ph = dev.up(g0, A["head.x"])
+    Pl = sp3d.alloc_padded(g0, classes, DT)
+    sp3d.sp_pointwise_fwd(Ph, net.w["head"], None, Pl, g0, channels[0], classes, DT)
+    errs["head.fwd"] = rel_err(dev.down(g0, Pl), ref_logits)
+    Pd = dev.up(g0, widen(dl))
+    dp = torch.empty((1, 1, 1, channels[0], classes), dtype=torch.float32, device="cuda")
+    sp3d.sp_pointwise_wgrad(Ph, Pd, dp, None, g0, channels[0], classes, DT,
+                            net._ws(sp3d.SP_OP_POINTWISE_WGRAD, g0, channels[0], classes))
+    errs["head.wgrad"] = rel_err(f64(dp), ref_grads["head"])
+    Pdx = sp3d.alloc_padded(g0, channels[0], DT)
+    sp3d.sp_pointwise_dgrad(Pd, net.w["head"], Pdx, g0, channels[0], classes, DT)
+    errs["head.dgrad"] = rel_err(dev.down(g0, Pdx), T["head.dx"])
+
+    print({k: "%.1e" % v for k, v in errs.items()})
+    bad = {k: v for k, v in errs.items() if v > tol}
+    assert not bad, bad

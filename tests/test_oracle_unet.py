@@ -1,0 +1,49 @@
+"""The composed U-Net oracle against torch autograd in float64 on a tiny network (CPU)."""
+import numpy as np
+import pytest
+
+from oracle import unet as OU
+from paper_1909_03108_amd import unet as PU
+
+torch = pytest.importorskip("torch")
+F = torch.nn.functional
+
+
+def test_unet_oracle_matches_torch_autograd(rng):
+    channels, in_ch, classes = (2, 3, 4), 1, 2
+    plan = PU.layer_plan(channels, in_ch, classes)
+    w = {name: rng.standard_normal(shape) * 0.4 for name, shape in plan}
+    x = rng.standard_normal((1, 4, 8, 4, in_ch))
+    dl = rng.standard_normal((1, 4, 8, 4, classes))
+
+    A = {}
+    logits = OU.forward(x, w, channels, keep=A)
+    grads, dx = OU.backward(dl, w, channels, A)
+
+    tw = {k: torch.from_numpy(v).clone().requires_grad_(True) for k, v in w.items()}
+    xt = torch.from_numpy(x).permute(0, 4, 1, 2, 3).clone().requires_grad_(True)
+
+    def conv(h, name):
+        return F.relu(F.conv3d(h, tw[name].permute(4, 3, 0, 1, 2), padding=1))
+
+    h, skips = xt, []
+    for i in range(len(channels)):
+        if i > 0:
+            h = F.max_pool3d(h, 2)
+        h = conv(conv(h, "enc%d_a" % i), "enc%d_b" % i)
+        skips.append(h)
+    for i in range(len(channels) - 2, -1, -1):
+        up = F.conv_transpose3d(h, tw["up%d" % i].permute(3, 4, 0, 1, 2), stride=2)
+        h = conv(conv(torch.cat([skips[i], up], dim=1), "dec%d_a" % i), "dec%d_b" % i)
+    out = F.conv3d(h, tw["head"].permute(4, 3, 0, 1, 2))
+    np.testing.assert_allclose(logits, out.detach().permute(0, 2, 3, 4, 1).numpy(), atol=1e-10)
+    out.backward(torch.from_numpy(dl).permute(0, 4, 1, 2, 3))
+    np.testing.assert_allclose(dx, xt.grad.permute(0, 2, 3, 4, 1).numpy(), atol=1e-10)
+    for name, _ in plan:
+        np.testing.assert_allclose(grads[name], tw[name].grad.numpy(), atol=1e-10, err_msg=name)
+
+
+def test_round_bf16_matches_torch():
+    a = np.random.default_rng(3).standard_normal(5000) * 13
+    ref = torch.from_numpy(a).float().to(torch.bfloat16).double().numpy()
+    assert np.array_equal(OU.round_bf16(a), ref)
