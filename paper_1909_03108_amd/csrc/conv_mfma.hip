@@ -1,6 +1,11 @@
-// bf16 implicit-GEMM 3x3x3 convolution on padded tiles for Cin = Cout = 32, on the gfx950 matrix
-// cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation).  Serves conv3d_fwd and, with mirrored taps
-// and swapped channel roles, conv3d_dgrad.
+// bf16 implicit-GEMM 3x3x3 convolution on padded tiles for channel counts that are multiples of 32,
+// on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation).  Serves conv3d_fwd and,
+// with mirrored taps and swapped channel roles, conv3d_dgrad.
+//
+// The kernel proper contracts ONE 32-channel input chunk into one 32-channel output block.  Wider
+// layers run it once per input chunk (one launch each, every output block in the same launch): the
+// first chunk writes fp32 partial sums to the workspace, later chunks add to them, the last one adds,
+// applies ReLU and stores bf16.  The order of the additions is fixed, so results are reproducible.
 //
 // Work decomposition.  A workgroup (4 waves, one per SIMD) owns an output patch of 8 rows (H) x 32
 // columns (W) of one tile and marches along D.  Each input plane (10 x 34 voxels x 32 channels) is
@@ -51,28 +56,45 @@ constexpr int PLANE_BYTES = 4 * CH_STRIDE;          // 21888 bytes
 constexpr int LDS_BYTES = NBUF * PLANE_BYTES;       // 87552 bytes
 __device__ __forceinline__ int lds_off(int v, int c) { return c * CH_STRIDE + v * 16; }
 
+// How a launch treats the fp32 partial sums of a layer with several input chunks.
+enum Mode { kSingle = 0,   // only chunk: bias, ReLU, store bf16
+            kFirst = 1,    // first chunk: bias, store fp32 partial
+            kMiddle = 2,   // add partial, store fp32 partial
+            kLast = 3 };   // add partial, ReLU, store bf16
+
 struct ConvArgs {
-    const uint16_t *in;
-    const uint4 *wpack;     // [27][2][64] fragments of 16 bytes
-    const float *bias;
-    uint16_t *out;
+    const uint16_t *in;     // input tensor; this launch reads channels [in_co, in_co + 32) of in_cs
+    const uint4 *wpack;     // fragments of this input chunk: [nco][27][2][64] x 16 bytes
+    const float *bias;      // bias of all output channels or NULL
+    uint16_t *out;          // output tensor (out_cs channels per voxel)
+    float *part;            // fp32 partial sums, indexed like `out`
     Geo g;
+    int in_cs, in_co, out_cs;
+    int nco;                // output blocks of 32 channels (all handled by this launch)
     int dchunk;             // output planes per workgroup
     int nd, nh, nw;         // patches per tile along D, H, W
     int nblocks;            // real workgroups (grid is rounded up to a multiple of 8)
-    int relu;
 };
 
-// Pre-swizzle the weights into MFMA A-fragment order: wpack[tap][half][lane] = the 8 input
-// channels k = 16*half + 8*(lane/32) + j of output channel m = lane%32.
-// Forward reads w[tap][k][m]; data-grad reads w[26-tap][m][k] (taps mirrored, roles swapped).
+// Pre-swizzle the weights into MFMA A-fragment order.  wpack[chunk i][block j][tap][half][lane] = the 8
+// input channels k = 32i + 16*half + 8*(lane/32) + e of output channel m = 32j + lane%32.
+// Forward reads w[tap][k][m]; data-grad reads w[26-tap][m][k] (taps mirrored, roles swapped), where
+// the kernel's input channels are the layer's output channels.  ki / ko = channel counts as the
+// kernel sees them (ki in, ko out).
 __global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t *__restrict__ w,
-                                                           uint16_t *__restrict__ wpack, int dgrad) {
-    const int i = blockIdx.x * 256 + threadIdx.x;     // over 27*2*64*8 elements
-    if (i >= NFRAG * 64 * 8) return;
-    const int j = i & 7, lane = (i >> 3) & 63, half = (i >> 9) & 1, tap = i >> 10;
-    const int m = lane & 31, k = 16 * half + 8 * (lane >> 5) + j;
-    wpack[i] = dgrad ? w[((26 - tap) * C + m) * C + k] : w[(tap * C + k) * C + m];
+                                                           uint16_t *__restrict__ wpack, int ki, int ko,
+                                                           int dgrad) {
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    const int per_pair = NFRAG * 64 * 8;
+    const int pairs = (ki / C) * (ko / C);
+    if (idx >= per_pair * pairs) return;
+    const int pair = idx / per_pair, i = idx % per_pair;
+    const int ci = pair / (ko / C), cj = pair % (ko / C);
+    const int e = i & 7, lane = (i >> 3) & 63, half = (i >> 9) & 1, tap = i >> 10;
+    const int m = C * cj + (lane & 31), k = C * ci + 16 * half + 8 * (lane >> 5) + e;
+    // forward: w[tap][cin = k][cout = m] (row length ko); dgrad: w[26-tap][cin = m][cout = k] (row length ki)
+    wpack[idx] = dgrad ? w[(static_cast<size_t>(26 - tap) * ko + m) * ki + k]
+                       : w[(static_cast<size_t>(tap) * ki + k) * ko + m];
 }
 
 // two floats -> packed bf16, round to nearest even (one v_cvt_pk_bf16_f32 on gfx950)
@@ -85,13 +107,14 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
 // Per-wave state of the march that the side work of a step needs.
 template <bool HAS_BIAS>
 struct Ctx {
-    const uint16_t *tin0;       // first padded input plane of this workgroup's D chunk
-    size_t plane_elems;         // elements per padded plane of the tile
+    const uint16_t *tin0;       // first padded input plane of this workgroup's D chunk (at the chunk's channels)
+    size_t plane_elems;         // input elements per padded plane of the tile
     int nplanes;                // input planes of the chunk (output planes + 2)
     int goff[LOADS];            // per-lane source offsets of the staging loads (elements)
     char *lds_stage;            // LDS chunk plane this wave fills (ring slot 0)
     uint16_t *obase;            // output address of (plane 0, first row of the wave, this lane)
-    size_t orow;                // elements per padded row
+    float *pbase;               // same position in the fp32 partial-sum buffer
+    size_t oplane, orow;        // output elements per padded plane / per padded row
     bool okrow[RH];             // row/column of this lane lies inside the tile interior
     float bv[HAS_BIAS ? 16 : 1];
 };
@@ -108,17 +131,35 @@ __device__ __forceinline__ void stage(const Ctx<HAS_BIAS> &c, int dplane, int j,
                                          (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
 }
 
-// Convert and store 4 channels (8 bytes) of row h of a finished plane: channels 8q + 4*(lane/32) .. +3.
-template <bool RELU, bool FULL, bool HAS_BIAS>
-__device__ __forceinline__ void store_unit(const Ctx<HAS_BIAS> &c, int d, const f32x16 (&s)[RH], int h, int q) {
+// Partial sums of 4 channels of row h of plane d written by the previous input chunk.
+template <bool FULL, bool HAS_BIAS>
+__device__ __forceinline__ float4 load_partial(const Ctx<HAS_BIAS> &c, int d, int h, int q) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (FULL || c.okrow[h]) v = *reinterpret_cast<const float4 *>(c.pbase + d * c.oplane + h * c.orow + 8 * q);
+    return v;
+}
+
+// Finish 4 channels of row h of a finished plane (channels 8q + 4*(lane/32) .. +3 of this output block):
+// add the earlier chunks' partial sums if there are any, then either store the new partial (fp32) or
+// apply ReLU, convert and store bf16 (8 bytes).
+template <int MODE, bool RELU, bool FULL, bool HAS_BIAS>
+__device__ __forceinline__ void store_unit(const Ctx<HAS_BIAS> &c, int d, const f32x16 (&s)[RH],
+                                           const float4 (&pin)[RH][4], int h, int q) {
     float v0 = s[h][4 * q], v1 = s[h][4 * q + 1], v2 = s[h][4 * q + 2], v3 = s[h][4 * q + 3];
+    if (MODE == kMiddle || MODE == kLast) {
+        v0 += pin[h][q].x; v1 += pin[h][q].y; v2 += pin[h][q].z; v3 += pin[h][q].w;
+    }
+    const size_t at = d * c.oplane + h * c.orow + 8 * q;
+    if (MODE == kFirst || MODE == kMiddle) {
+        if (FULL || c.okrow[h]) *reinterpret_cast<float4 *>(c.pbase + at) = make_float4(v0, v1, v2, v3);
+        return;
+    }
     if (RELU) {
         v0 = v0 < 0.f ? 0.f : v0; v1 = v1 < 0.f ? 0.f : v1;
         v2 = v2 < 0.f ? 0.f : v2; v3 = v3 < 0.f ? 0.f : v3;
     }
     const uint2 pk = make_uint2(pack2(v0, v1), pack2(v2, v3));
-    uint2 *o = reinterpret_cast<uint2 *>(c.obase + d * c.plane_elems + h * c.orow + 8 * q);
-    if (FULL || c.okrow[h]) *o = pk;
+    if (FULL || c.okrow[h]) *reinterpret_cast<uint2 *>(c.obase + at) = pk;
 }
 
 // All MFMAs of one staged input plane Dp, with the step's side work spread over the six MFMA groups:
@@ -129,12 +170,19 @@ __device__ __forceinline__ void store_unit(const Ctx<HAS_BIAS> &c, int d, const 
 // consume them.  P = Dp mod 4: output plane Dp-kd lives in slot (P-kd) mod 4, plane Dp-3 in slot (P+1) mod 4.
 // FULL: the patch lies completely inside the tile interior, so stores need no mask (no branches in
 // the step, which lets the scheduler weave the side work between the MFMAs).
-template <int P, bool EPI, bool RELU, bool FULL, bool HAS_BIAS>
+template <int P, bool EPI, int MODE, bool RELU, bool FULL, bool HAS_BIAS>
 __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, int lane, const char *lbase,
                                            const bf16x8 (&wf)[NFRAG], f32x16 (&acc)[4][RH]) {
     constexpr int NR = RH + 2;
     constexpr int DONE = (P + 1) & 3;
     bf16x8 b[2][NR];
+    float4 pin[RH][4];      // partial sums of the plane being finished (chunks after the first)
+    if (EPI && (MODE == kMiddle || MODE == kLast)) {
+#pragma unroll
+        for (int h = 0; h < RH; ++h)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) pin[h][q] = load_partial<FULL>(c, Dp - 3, h, q);
+    }
 #pragma unroll
     for (int r = 0; r < NR; ++r)
         b[0][r] = *reinterpret_cast<const bf16x8 *>(lbase + (r * LCOLS) * 16);
@@ -154,8 +202,8 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, int l
         stage(c, Dp + DIST, gi, lane);
         if (gi < 4) {
             if (EPI) {
-                store_unit<RELU, FULL>(c, Dp - 3, acc[DONE], 0, gi);
-                store_unit<RELU, FULL>(c, Dp - 3, acc[DONE], 1, gi);
+                store_unit<MODE, RELU, FULL>(c, Dp - 3, acc[DONE], pin, 0, gi);
+                store_unit<MODE, RELU, FULL>(c, Dp - 3, acc[DONE], pin, 1, gi);
             }
         } else {
 #pragma unroll
@@ -184,7 +232,7 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, int l
     }
 }
 
-template <bool HAS_BIAS, bool RELU>
+template <int MODE, bool HAS_BIAS, bool RELU>
 __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];   // NBUF planes of PLANE_BYTES
     const Geo &g = a.g;
@@ -194,6 +242,8 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
     const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (logical >= a.nblocks) return;
     int t = logical;
+    const int cj = t % a.nco; t /= a.nco;          // output block: fastest, so that the workgroups that
+                                                    // share an input patch run together
     const int pw_i = t % a.nw; t /= a.nw;
     const int ph_i = t % a.nh; t /= a.nh;
     const int pd_i = t % a.nd; t /= a.nd;
@@ -207,13 +257,13 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
     bf16x8 wf[NFRAG];
 #pragma unroll
     for (int f = 0; f < NFRAG; ++f) {
-        const uint4 q = a.wpack[f * 64 + lane];
+        const uint4 q = a.wpack[(cj * NFRAG + f) * 64 + lane];
         wf[f] = *reinterpret_cast<const bf16x8 *>(&q);
     }
 
     Ctx<HAS_BIAS> c;
-    c.plane_elems = static_cast<size_t>(g.ph) * g.pw * C;
-    c.tin0 = a.in + static_cast<size_t>(tile) * g.tile_vox * C + d0 * c.plane_elems;
+    c.plane_elems = static_cast<size_t>(g.ph) * g.pw * a.in_cs;
+    c.tin0 = a.in + static_cast<size_t>(tile) * g.tile_vox * a.in_cs + d0 * c.plane_elems + a.in_co;
     c.nplanes = dn + 2;
     // Wave w fills chunk plane w (channels 8w..8w+7 of every voxel); load j covers patch-local voxels
     // 64j..64j+63.  Voxels outside the padded tile (ragged patches) are clamped to a valid address;
@@ -222,19 +272,23 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
     for (int j = 0; j < LOADS; ++j) {
         const int v = 64 * j + lane;
         const int row = min(h0 + v / LCOLS, g.ph - 1), colv = min(w0 + v % LCOLS, g.pw - 1);
-        c.goff[j] = (row * g.pw + colv) * C + wave * 8;
+        c.goff[j] = (row * g.pw + colv) * a.in_cs + wave * 8;
     }
     c.lds_stage = lds + wave * CH_STRIDE;
-    c.orow = static_cast<size_t>(g.pw) * C;
-    c.obase = a.out + static_cast<size_t>(tile) * g.tile_vox * C +
-              ((static_cast<size_t>(d0 + 1) * g.ph + h0 + wave * RH + 1) * g.pw + w0 + col + 1) * C + 4 * hi;
+    c.orow = static_cast<size_t>(g.pw) * a.out_cs;
+    c.oplane = static_cast<size_t>(g.ph) * c.orow;
+    const size_t opos = static_cast<size_t>(tile) * g.tile_vox * a.out_cs +
+                        ((static_cast<size_t>(d0 + 1) * g.ph + h0 + wave * RH + 1) * g.pw + w0 + col + 1) * a.out_cs +
+                        C * cj + 4 * hi;
+    c.obase = a.out + opos;
+    c.pbase = a.part + opos;
 #pragma unroll
     for (int h = 0; h < RH; ++h) c.okrow[h] = h0 + wave * RH + h < g.th && w0 + col < g.tw;
     // the bias is folded into the accumulators: a slot starts from the bias instead of zero
     // (without a bias the slots start from the constant zero and no registers are spent on it)
     if (HAS_BIAS) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) c.bv[HAS_BIAS ? i : 0] = a.bias[8 * (i >> 2) + 4 * hi + (i & 3)];
+        for (int i = 0; i < 16; ++i) c.bv[HAS_BIAS ? i : 0] = a.bias[C * cj + 8 * (i >> 2) + 4 * hi + (i & 3)];
     }
     f32x16 acc[4][RH];
 #pragma unroll
@@ -269,16 +323,16 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
     auto march = [&](auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
         // the first three steps have no finished plane to store (nplanes >= 3 always)
-        plane_step<0, false, RELU, FULL>(c, 0, lane, lbase, wf, acc);
+        plane_step<0, false, MODE, RELU, FULL>(c, 0, lane, lbase, wf, acc);
         SP3D_STEP_END();
-        plane_step<1, false, RELU, FULL>(c, 1, lane, lbase + PLANE_BYTES, wf, acc);
+        plane_step<1, false, MODE, RELU, FULL>(c, 1, lane, lbase + PLANE_BYTES, wf, acc);
         SP3D_STEP_END();
-        plane_step<2, false, RELU, FULL>(c, 2, lane, lbase + 2 * PLANE_BYTES, wf, acc);
+        plane_step<2, false, MODE, RELU, FULL>(c, 2, lane, lbase + 2 * PLANE_BYTES, wf, acc);
         SP3D_STEP_END();
         // steps 3, 4, 5, 6, 7, ...: planes mod 4 = 3, 0, 1, 2, 3, ...
 #define SP3D_MAIN_STEP(OFF, PHASE)                                                                   \
     if (D + (OFF) < nplanes) {                                                                       \
-        plane_step<PHASE, true, RELU, FULL>(c, D + (OFF), lane, lbase + (PHASE) * PLANE_BYTES, wf, acc); \
+        plane_step<PHASE, true, MODE, RELU, FULL>(c, D + (OFF), lane, lbase + (PHASE) * PLANE_BYTES, wf, acc); \
         SP3D_STEP_END();                                                                             \
     }
         for (int D = 3; D < nplanes; D += 4) {
@@ -290,13 +344,20 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
 #undef SP3D_MAIN_STEP
         // the last output plane (dn-1) finished in the last step; it sits in slot (dn-1) mod 4
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        float4 pin[RH][4];
+        if (MODE == kMiddle || MODE == kLast) {
+#pragma unroll
+            for (int h = 0; h < RH; ++h)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) pin[h][q] = load_partial<FULL>(c, dn - 1, h, q);
+        }
 #pragma unroll
         for (int s = 0; s < 4; ++s)
             if (s == ((dn - 1) & 3)) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    store_unit<RELU, FULL>(c, dn - 1, acc[s], 0, q);
-                    store_unit<RELU, FULL>(c, dn - 1, acc[s], 1, q);
+                    store_unit<MODE, RELU, FULL>(c, dn - 1, acc[s], pin, 0, q);
+                    store_unit<MODE, RELU, FULL>(c, dn - 1, acc[s], pin, 1, q);
                 }
             }
     };
@@ -308,28 +369,43 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
 }  // namespace
 
 bool conv_mfma_supported(const Geo &g, int ki, int ko, sp_dtype_t dt) {
-    return dt == SP_BF16 && ki == C && ko == C && 1LL * g.ph * g.pw * C < 0x7fffffffLL;
+    return dt == SP_BF16 && ki % C == 0 && ko % C == 0 && ki <= 1024 && ko <= 1024 &&
+           1LL * g.ph * g.pw * (ki > ko ? ki : ko) < 0x7fffffffLL;
 }
 
-size_t conv_mfma_ws_bytes(const Geo &, int, int) { return static_cast<size_t>(NFRAG) * 64 * 16; }
+static size_t pack_bytes(int ki, int ko) {
+    return static_cast<size_t>(ki / C) * (ko / C) * NFRAG * 64 * 16;
+}
+
+// workspace: packed weight fragments, then (layers with several input chunks) fp32 partial sums laid
+// out like the output tensor
+size_t conv_mfma_ws_bytes(const Geo &g, int ki, int ko) {
+    size_t n = pack_bytes(ki, ko);
+    if (ki > C) n += static_cast<size_t>(g.ntiles) * g.tile_vox * ko * sizeof(float);
+    return n;
+}
 
 int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Pout, const Geo &g,
                      int ki, int ko, bool relu, bool dgrad, void *ws, hipStream_t s) {
-    (void)ki; (void)ko;
-    hipLaunchKernelGGL(pack_weights_kernel, dim3((NFRAG * 64 * 8 + 255) / 256), dim3(256), 0, s,
-                       static_cast<const uint16_t *>(w), static_cast<uint16_t *>(ws), dgrad ? 1 : 0);
+    const int nci = ki / C, nco = ko / C;
+    const int pack_elems = nci * nco * NFRAG * 64 * 8;
+    hipLaunchKernelGGL(pack_weights_kernel, dim3((pack_elems + 255) / 256), dim3(256), 0, s,
+                       static_cast<const uint16_t *>(w), static_cast<uint16_t *>(ws), ki, ko, dgrad ? 1 : 0);
     int rc = record_hip(hipGetLastError());
     if (rc != SP_OK) return rc;
     ConvArgs a;
     a.in = static_cast<const uint16_t *>(Pin);
-    a.wpack = static_cast<const uint4 *>(ws);
     a.bias = bias;
     a.out = static_cast<uint16_t *>(Pout);
+    a.part = reinterpret_cast<float *>(static_cast<char *>(ws) + pack_bytes(ki, ko));
     a.g = g;
+    a.in_cs = ki;
+    a.out_cs = ko;
+    a.nco = nco;
     a.nh = (g.th + PH - 1) / PH;
     a.nw = (g.tw + PW - 1) / PW;
     // D chunk: whole tile depth unless that leaves the chip short of workgroups
-    long long base = 1LL * g.ntiles * a.nh * a.nw;
+    long long base = 1LL * g.ntiles * a.nh * a.nw * nco;
     int dchunk = g.td;
     while (base * ((g.td + dchunk - 1) / dchunk) < 1024 && dchunk > 16) dchunk = (dchunk + 1) / 2;
     a.dchunk = dchunk;
@@ -337,23 +413,38 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
     const long long nb = base * a.nd;
     if (nb > 0x7ffffff0LL) return SP_EGEOM;
     a.nblocks = static_cast<int>(nb);
-    a.relu = relu ? 1 : 0;
     const unsigned grid = static_cast<unsigned>((nb + 7) / 8 * 8);
-    // more than 64 KB of dynamic LDS has to be requested explicitly
     using Kern = void (*)(ConvArgs);
-    static const Kern kern[2][2] = {{conv_mfma_kernel<false, false>, conv_mfma_kernel<false, true>},
-                                    {conv_mfma_kernel<true, false>, conv_mfma_kernel<true, true>}};
+    // [mode][bias][relu]; combinations that cannot occur (bias after the first chunk, ReLU before the last)
+    // reuse the plain variant
+    static const Kern kern[4][2][2] = {
+        {{conv_mfma_kernel<kSingle, false, false>, conv_mfma_kernel<kSingle, false, true>},
+         {conv_mfma_kernel<kSingle, true, false>, conv_mfma_kernel<kSingle, true, true>}},
+        {{conv_mfma_kernel<kFirst, false, false>, conv_mfma_kernel<kFirst, false, false>},
+         {conv_mfma_kernel<kFirst, true, false>, conv_mfma_kernel<kFirst, true, false>}},
+        {{conv_mfma_kernel<kMiddle, false, false>, conv_mfma_kernel<kMiddle, false, false>},
+         {conv_mfma_kernel<kMiddle, false, false>, conv_mfma_kernel<kMiddle, false, false>}},
+        {{conv_mfma_kernel<kLast, false, false>, conv_mfma_kernel<kLast, false, true>},
+         {conv_mfma_kernel<kLast, false, false>, conv_mfma_kernel<kLast, false, true>}}};
+    // more than 64 KB of dynamic LDS has to be requested explicitly
     static const hipError_t attr = [] {
-        for (int i = 0; i < 4; ++i) {
-            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern[i >> 1][i & 1]),
+        for (int i = 0; i < 16; ++i) {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern[i >> 2][(i >> 1) & 1][i & 1]),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
             if (e != hipSuccess) return e;
         }
         return hipSuccess;
     }();
     if (attr != hipSuccess) return record_hip(attr);
-    hipLaunchKernelGGL(kern[bias ? 1 : 0][relu ? 1 : 0], dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
-    return record_hip(hipGetLastError());
+    for (int ci = 0; ci < nci; ++ci) {
+        const int mode = nci == 1 ? kSingle : (ci == 0 ? kFirst : (ci == nci - 1 ? kLast : kMiddle));
+        a.in_co = C * ci;
+        a.wpack = static_cast<const uint4 *>(ws) + static_cast<size_t>(ci) * nco * NFRAG * 64;
+        hipLaunchKernelGGL(kern[mode][bias ? 1 : 0][relu ? 1 : 0], dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
+        rc = record_hip(hipGetLastError());
+        if (rc != SP_OK) return rc;
+    }
+    return SP_OK;
 }
 
 }  // namespace sp3d

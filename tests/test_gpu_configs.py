@@ -169,3 +169,65 @@ def test_configuration_4_sampled():
     dw2 = torch.empty_like(dw)
     sp3d.conv3d_wgrad(Px, Pdy, dw2, None, g, 32, 32, dt, wsp[2])
     assert torch.equal(dw, dw2)
+
+
+@pytest.mark.timeout(900)
+def test_configuration_3_first_level_256():
+    """256^3 CT-like single-channel volume, 1 -> 32 -> 32 with ReLU after each conv, grid 4x4x2
+    (64x64x128 tiles).  Layer 1 is compared in full (its fp64 pass is cheap).  Everything behind it is
+    run on the GPU from stored inputs that do not come from the GPU -- the oracle's layer-1 output, and
+    seeded stand-ins for tensors whose true values would need a full 0.9 TFLOP fp64 pass (y2 for the
+    ReLU mask, the gradient arriving at layer 1) -- and compared on sampled boxes / sampled entries."""
+    c = synth.CONFIGS[3]
+    n, dhw, grid = c["n"], c["dhw"], c["grid"]
+    x, (w1, w2), dy = synth.config_tensors(3)
+    W1, W2 = widen(w1), widen(w2)
+    tol = TOL["bf16"]
+    L1 = Layer(n, dhw, grid, 1, 32, "bf16")
+    L2 = Layer(n, dhw, grid, 32, 32, "bf16")
+    g = L2.g
+    rng = np.random.default_rng(3)
+    boxes = sample_boxes(dhw, g.tile, rng, nrandom=16)
+    boxes += [(60, 68, 60, 68, 120, 136), (124, 132, 188, 196, 122, 134)]      # across the W split
+
+    def on_boxes(vol_dev, fn):
+        worst = 0.0
+        for bx in boxes:
+            d0, d1, h0, h1, w0, w1_ = bx
+            worst = max(worst, rel_err(f64(vol_dev[:, d0:d1, h0:h1, w0:w1_]), fn(bx)))
+        return worst
+
+    # layer 1 forward, full
+    y1_g = L1.fwd(x, w1, None, relu=True)
+    y1_o = conv3d.conv3d_fwd(x, W1, relu=True)
+    assert rel_err(f64(y1_g), y1_o) <= tol
+    y1_s = synth.f32_to_bf16_bits(y1_o.astype(np.float32))
+    del y1_g, y1_o
+    # layer 2 forward from the oracle's stored y1
+    y2_g = L2.fwd(y1_s, w2, None, relu=True)
+    assert on_boxes(y2_g, lambda bx: conv3d.conv3d_fwd(y1_s, W2, relu=True, box=bx)) <= tol
+    del y2_g
+    # layer 2 backward: mask from a seeded stand-in for y2 (post-ReLU shaped: half zeros)
+    y2_s = synth.normal_volume((n,) + dhw + (32,), synth.seed_for(3, 60), "bf16")
+    y2_s = np.where(widen(y2_s) > 0, y2_s, np.uint16(0))
+    dz2 = np.where(widen(y2_s) > 0, dy, np.uint16(0))
+    Pdy, Py2 = L2.padded(dy, 32), L2.padded(y2_s, 32)
+    sp3d.sp_relu_bwd(Pdy, Py2, Pdy, g, 32, L2.dt)
+    # padded() exchanged halos of dy and of y2 alike, so the mask also holds on the margins
+    assert np.array_equal(bits(L2.volume(Pdy, 32)), dz2)
+    del Pdy, Py2
+    dy1_g = L2.dgrad(dz2, w2)
+    assert on_boxes(dy1_g, lambda bx: conv3d.conv3d_dgrad(dz2, W2, box=bx)) <= tol
+    del dy1_g
+    sel = np.unique(rng.integers(0, 27 * 32 * 32, 24))
+    dw2, db2 = L2.wgrad(y1_s, dz2)
+    assert rel_err(f64(dw2).ravel()[sel], conv3d.conv3d_wgrad(y1_s, dz2, sel=sel)) <= tol
+    assert rel_err(f64(db2), conv3d.bias_grad(dz2)) <= tol
+    # layer 1 backward from a seeded stand-in for the gradient arriving at y1
+    dy1_s = synth.normal_volume((n,) + dhw + (32,), synth.seed_for(3, 61), "bf16")
+    dz1 = np.where(widen(y1_s) > 0, dy1_s, np.uint16(0))
+    dw1, db1 = L1.wgrad(x, dz1)
+    assert rel_err(f64(dw1), conv3d.conv3d_wgrad(x, dz1)) <= tol            # all 27 x 1 x 32 entries
+    assert rel_err(f64(db1), conv3d.bias_grad(dz1)) <= tol
+    dx_g = L1.dgrad(dz1, w1)                                                # gradient w.r.t. the image
+    assert on_boxes(dx_g, lambda bx: conv3d.conv3d_dgrad(dz1, W1, box=bx)) <= tol
