@@ -1,5 +1,7 @@
-// bf16 weight gradient of the 3x3x3 convolution for Cin = Cout = 32 on the gfx950 matrix cores
-// (v_mfma_f32_16x16x32_bf16, fp32 accumulation), plus the bias gradient.
+// bf16 weight gradient of the 3x3x3 convolution for channel counts that are multiples of 32 on the
+// gfx950 matrix cores (v_mfma_f32_16x16x32_bf16, fp32 accumulation), plus the bias gradient.
+// The kernel proper handles one (32 input channels) x (32 output channels) pair; wider layers give
+// every pair its own set of workgroups in the same launch (the pairs are independent).
 //
 //   dw[tap][ci][co] = sum over tiles and interior voxels v of  Px[v + tap][ci] * Pdz[v + (1,1,1)][co]
 //
@@ -51,9 +53,12 @@ struct WgradArgs {
     float *part_w;        // [ngroups][27][32][32]
     float *part_b;        // [ngroups][32]
     Geo g;
+    int x_cs, dz_cs;      // channels per voxel of x and dz
+    int nco;              // output blocks; pair p = (input chunk p / nco, output block p % nco)
+    int gpp;              // workgroups per pair
     int dchunk, nd, nh, nw;
-    int nitems;
-    int ngroups;          // real workgroups; grid is rounded up to a multiple of 8
+    int nitems;           // work items per pair
+    int ngroups;          // real workgroups = pairs * gpp; grid is rounded up to a multiple of 8
 };
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -109,6 +114,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
     const int per_xcd = gridDim.x >> 3;
     const int group = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (group >= a.ngroups) return;
+    const int pair = group / a.gpp, gsub = group % a.gpp;
+    const int x_co = C * (pair / a.nco), dz_co = C * (pair % a.nco);   // channel offsets of this pair
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int qi = (wave >> 1) & 1, qo = wave & 1;   // ci half, co half of this wave's quadrant
     const int kg = wave >> 2;                         // row group: dz rows [GR*kg, GR*kg + GR)
@@ -139,10 +146,10 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) bsum[j] = 0.f;
 
-    const size_t plane_elems = static_cast<size_t>(g.ph) * g.pw * C;
-    const int row_elems = g.pw * C;
+    const size_t xplane = static_cast<size_t>(g.ph) * g.pw * a.x_cs, zplane = static_cast<size_t>(g.ph) * g.pw * a.dz_cs;
+    const int xrow_elems = g.pw * a.x_cs, zrow_elems = g.pw * a.dz_cs;
 
-    for (int item = group; item < a.nitems; item += a.ngroups) {
+    for (int item = gsub; item < a.nitems; item += a.gpp) {
         int t = item;
         const int pw_i = t % a.nw; t /= a.nw;
         const int ph_i = t % a.nh; t /= a.nh;
@@ -150,13 +157,13 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
         const int tile = t;
         const int d0 = pd_i * a.dchunk, h0 = ph_i * PH, w0 = pw_i * PW;
         const int dn = min(a.dchunk, g.td - d0);
-        const uint16_t *tx = a.x + static_cast<size_t>(tile) * g.tile_vox * C;
-        const uint16_t *tz = a.dz + static_cast<size_t>(tile) * g.tile_vox * C;
+        const uint16_t *tx = a.x + static_cast<size_t>(tile) * g.tile_vox * a.x_cs + x_co;
+        const uint16_t *tz = a.dz + static_cast<size_t>(tile) * g.tile_vox * a.dz_cs + dz_co;
 
         // source offsets inside a plane and validity (x: inside the padded tile; dz: tile interior)
-        const int xsrc0 = ((h0 + sr) * g.pw + w0 + sv) * C + c4 * 8;
-        const int xsrce = ((h0 + er) * g.pw + w0 + ev) * C + c4 * 8;
-        const int zsrc0 = ((h0 + sr + 1) * g.pw + w0 + sv + 1) * C + c4 * 8;
+        const int xsrc0 = ((h0 + sr) * g.pw + w0 + sv) * a.x_cs + c4 * 8;
+        const int xsrce = ((h0 + er) * g.pw + w0 + ev) * a.x_cs + c4 * 8;
+        const int zsrc0 = ((h0 + sr + 1) * g.pw + w0 + sv + 1) * a.dz_cs + c4 * 8;
         bool xok[3], zok[2];
 #pragma unroll
         for (int i = 0; i < 3; ++i)
@@ -172,15 +179,15 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
 #define SP3D_LDG(ok, ptr) ((ok) ? *reinterpret_cast<const uint4 *>(ptr) : zero4)
 #define SP3D_FETCH(D)                                                                  \
     do {                                                                               \
-        const uint16_t *px = tx + (d0 + (D)) * plane_elems;                            \
+        const uint16_t *px = tx + (d0 + (D)) * xplane;                                 \
         xs0 = SP3D_LDG(xok[0], px + xsrc0);                                            \
-        xs1 = SP3D_LDG(xok[1], px + xsrc0 + 4 * row_elems);                            \
-        xs2 = SP3D_LDG(xok[2], px + xsrc0 + 8 * row_elems);                            \
+        xs1 = SP3D_LDG(xok[1], px + xsrc0 + 4 * xrow_elems);                           \
+        xs2 = SP3D_LDG(xok[2], px + xsrc0 + 8 * xrow_elems);                           \
         xs3 = SP3D_LDG(eok, px + xsrce);                                               \
         const bool zreal = (D) < dn;                                                   \
-        const uint16_t *pz = tz + (d0 + (D) + 1) * plane_elems;                        \
+        const uint16_t *pz = tz + (d0 + (D) + 1) * zplane;                             \
         zs0 = SP3D_LDG(zreal && zok[0], pz + zsrc0);                                   \
-        zs1 = SP3D_LDG(zreal && zok[1], pz + zsrc0 + 4 * row_elems);                   \
+        zs1 = SP3D_LDG(zreal && zok[1], pz + zsrc0 + 4 * zrow_elems);                  \
     } while (0)
 #define SP3D_BSUM(V_)                                                                  \
     do {                                                                               \
@@ -274,37 +281,74 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
     }
 }
 
-void plan(const Geo &g, WgradArgs *a) {
+void plan(const Geo &g, int cin, int cout, WgradArgs *a) {
+    const int npairs = (cin / C) * (cout / C);
+    a->x_cs = cin;
+    a->dz_cs = cout;
+    a->nco = cout / C;
     a->nh = (g.th + PH - 1) / PH;
     a->nw = (g.tw + PW - 1) / PW;
+    int gpp = kMaxGroups / npairs;                    // about one workgroup per CU in total
+    if (gpp < 1) gpp = 1;
     const long long base = 1LL * g.ntiles * a->nh * a->nw;
     int dchunk = g.td;
-    while (base * ((g.td + dchunk - 1) / dchunk) < kMaxGroups && dchunk > 16) dchunk = (dchunk + 1) / 2;
+    while (base * ((g.td + dchunk - 1) / dchunk) < gpp && dchunk > 16) dchunk = (dchunk + 1) / 2;
     a->dchunk = dchunk;
     a->nd = (g.td + dchunk - 1) / dchunk;
     const long long items = base * a->nd;
     a->nitems = static_cast<int>(items);
-    a->ngroups = static_cast<int>(items < kMaxGroups ? items : kMaxGroups);
+    a->gpp = static_cast<int>(items < gpp ? items : gpp);
+    a->ngroups = a->gpp * npairs;
+}
+
+// dw[tap][ci][co] = sum over the workgroups of pair (ci/32, co/32), in workgroup order, of their partial
+// [tap][ci%32][co%32]; db[co] likewise from the pairs of input chunk 0.
+__global__ __launch_bounds__(256) void reduce_wgrad_kernel(const float *__restrict__ part_w,
+                                                           const float *__restrict__ part_b,
+                                                           float *__restrict__ dw, float *__restrict__ db,
+                                                           int cin, int cout, int gpp) {
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    const int nw_ = 27 * cin * cout;
+    if (e < nw_) {
+        const int co = e % cout, ci = (e / cout) % cin, tap = e / (cout * cin);
+        const int pair = (ci / C) * (cout / C) + co / C;
+        const float *p = part_w + (static_cast<size_t>(pair) * gpp * 27 + tap) * C * C + (ci % C) * C + co % C;
+        float s = 0.f;
+        int k = 0;
+        for (; k + 4 <= gpp; k += 4) {          // loads issued together, additions kept in order
+            const float p0 = p[static_cast<size_t>(k) * 27 * C * C], p1 = p[static_cast<size_t>(k + 1) * 27 * C * C];
+            const float p2 = p[static_cast<size_t>(k + 2) * 27 * C * C], p3 = p[static_cast<size_t>(k + 3) * 27 * C * C];
+            s = (((s + p0) + p1) + p2) + p3;
+        }
+        for (; k < gpp; ++k) s += p[static_cast<size_t>(k) * 27 * C * C];
+        dw[e] = s;
+    } else if (db && e < nw_ + cout) {
+        const int co = e - nw_;
+        const float *p = part_b + static_cast<size_t>(co / C) * gpp * C + co % C;     // pairs (0, co/32)
+        float s = 0.f;
+        for (int k = 0; k < gpp; ++k) s += p[k * C];
+        db[co] = s;
+    }
 }
 
 }  // namespace
 
 bool wgrad_mfma_supported(const Geo &g, int cin, int cout, sp_dtype_t dt) {
-    if (!(dt == SP_BF16 && cin == C && cout == C)) return false;
+    if (!(dt == SP_BF16 && cin % C == 0 && cout % C == 0 && cin <= 1024 && cout <= 1024)) return false;
     const long long base = 1LL * g.ntiles * ((g.th + PH - 1) / PH) * ((g.tw + PW - 1) / PW);
-    return base * g.td < 0x7fffffffLL && 1LL * g.ph * g.pw * C < 0x7fffffffLL;
+    return base * g.td < 0x7fffffffLL && 1LL * g.ph * g.pw * (cin > cout ? cin : cout) < 0x7fffffffLL;
 }
 
-size_t wgrad_mfma_ws_bytes(const Geo &g, int, int) {
+size_t wgrad_mfma_ws_bytes(const Geo &g, int cin, int cout) {
     WgradArgs a;
-    plan(g, &a);
+    plan(g, cin, cout, &a);
     return static_cast<size_t>(a.ngroups) * (27 * C * C + C) * sizeof(float);
 }
 
-int launch_wgrad_mfma(const void *Px, const void *Pdz, float *dw, float *db, const Geo &g, int, int,
+int launch_wgrad_mfma(const void *Px, const void *Pdz, float *dw, float *db, const Geo &g, int cin, int cout,
                       void *ws, hipStream_t s) {
     WgradArgs a;
-    plan(g, &a);
+    plan(g, cin, cout, &a);
     a.x = static_cast<const uint16_t *>(Px);
     a.dz = static_cast<const uint16_t *>(Pdz);
     a.part_w = static_cast<float *>(ws);
@@ -318,10 +362,10 @@ int launch_wgrad_mfma(const void *Px, const void *Pdz, float *dw, float *db, con
     hipLaunchKernelGGL(wgrad_mfma_kernel, dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
     int rc = record_hip(hipGetLastError());
     if (rc != SP_OK) return rc;
-    rc = launch_reduce_partials(a.part_w, dw, a.ngroups, 27LL * C * C, s);
-    if (rc != SP_OK) return rc;
-    if (db) rc = launch_reduce_partials(a.part_b, db, a.ngroups, C, s);
-    return rc;
+    const int n = 27 * cin * cout + cout;
+    hipLaunchKernelGGL(reduce_wgrad_kernel, dim3((n + 255) / 256), dim3(256), 0, s, a.part_w, a.part_b, dw, db,
+                       cin, cout, a.gpp);
+    return record_hip(hipGetLastError());
 }
 
 }  // namespace sp3d
