@@ -130,6 +130,37 @@ __global__ __launch_bounds__(kThreads) void upconv2_dgrad_kernel(const E *__rest
     }
 }
 
+// Data gradient, bf16 with cout a multiple of 8: same thread layout, but dy and the weight row
+// u[k][ci][.] are read 8 channels (16 bytes) at a time.
+__global__ __launch_bounds__(kThreads) void upconv2_dgrad_bf16x8_kernel(const uint16_t *__restrict__ dy,
+                                                                        const uint16_t *__restrict__ u,
+                                                                        uint16_t *__restrict__ dx, Geo gf, Geo gc,
+                                                                        Lay l, int cin, int cout) {
+    const unsigned v = blockIdx.x * (kThreads >> l.cshift) + (threadIdx.x >> l.cshift);
+    if (v >= l.nvox) return;
+    const Vox o = decode(v, l);                                     // coarse voxel
+    const long long po = pidx(gc, o.tile, o.ld, o.lh, o.lw);
+    for (int ci = threadIdx.x & (l.cw - 1); ci < cin; ci += l.cw) {
+        float acc = 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const uint4 *g = reinterpret_cast<const uint4 *>(
+                dy + pidx(gf, o.tile, 2 * o.ld + (k >> 2), 2 * o.lh + ((k >> 1) & 1), 2 * o.lw + (k & 1)) * cout);
+            const uint4 *uk = reinterpret_cast<const uint4 *>(u + (1LL * k * cin + ci) * cout);
+            for (int c8 = 0; c8 < cout / 8; ++c8) {
+                const uint4 a = g[c8], b = uk[c8];
+                const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    acc = fmaf(__uint_as_float(aw[e] << 16), __uint_as_float(bw[e] << 16), acc);
+                    acc = fmaf(__uint_as_float(aw[e] & 0xffff0000u), __uint_as_float(bw[e] & 0xffff0000u), acc);
+                }
+            }
+        }
+        dx[po * cin + ci] = f32_to_bf16(acc);
+    }
+}
+
 // Weight gradient, stage 1 (same scheme as the direct 3x3x3 weight gradient): block (k*cin + ci, chunk of
 // coarse voxels, co group); threads [voxel lane][co]; fixed-order sums; partials to ws[chunk][k][ci][co].
 template <typename E>
@@ -159,6 +190,48 @@ __global__ __launch_bounds__(kThreads) void upconv2_wgrad_kernel(const E *__rest
         float s = 0.f;
         for (int i = 0; i < nvl; ++i) s += red[i * cw + col];
         part[(1LL * chunk * 8 * cin + kci) * cout + co] = s;
+    }
+}
+
+// Weight gradient, stage 1, bf16 with cout/8 a power of two <= 256: thread (ci, group of 8 co) keeps the
+// 8 window positions x 8 channels of its du entries in registers and walks over the chunk's coarse
+// voxels in index order (one 2-byte x load and eight 16-byte dy loads per 64 multiply-adds).
+__global__ __launch_bounds__(kThreads) void upconv2_wgrad_bf16x8_kernel(const uint16_t *__restrict__ x,
+                                                                        const uint16_t *__restrict__ dy,
+                                                                        float *__restrict__ part, Geo gf, Geo gc,
+                                                                        Lay l, int cin, int cout, int co8_shift,
+                                                                        unsigned chunk_vox) {
+    const int co8 = threadIdx.x & ((1 << co8_shift) - 1);
+    const int ci = blockIdx.x * (kThreads >> co8_shift) + (threadIdx.x >> co8_shift);
+    const int chunk = blockIdx.y;
+    if (ci >= cin) return;
+    float acc[8][8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[k][e] = 0.f;
+    unsigned v1 = (chunk + 1u) * chunk_vox;
+    if (v1 > l.nvox) v1 = l.nvox;
+    for (unsigned v = chunk * chunk_vox; v < v1; ++v) {
+        const Vox o = decode(v, l);                                 // coarse voxel
+        const float xv = bf16_to_f32(x[pidx(gc, o.tile, o.ld, o.lh, o.lw) * cin + ci]);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const uint4 g = *reinterpret_cast<const uint4 *>(
+                dy + pidx(gf, o.tile, 2 * o.ld + (k >> 2), 2 * o.lh + ((k >> 1) & 1), 2 * o.lw + (k & 1)) * cout + 8 * co8);
+            const uint32_t gw[4] = {g.x, g.y, g.z, g.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc[k][2 * e] = fmaf(xv, __uint_as_float(gw[e] << 16), acc[k][2 * e]);
+                acc[k][2 * e + 1] = fmaf(xv, __uint_as_float(gw[e] & 0xffff0000u), acc[k][2 * e + 1]);
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        float *p = part + ((1LL * chunk * 8 + k) * cin + ci) * cout + 8 * co8;
+        *reinterpret_cast<float4 *>(p) = make_float4(acc[k][0], acc[k][1], acc[k][2], acc[k][3]);
+        *reinterpret_cast<float4 *>(p + 4) = make_float4(acc[k][4], acc[k][5], acc[k][6], acc[k][7]);
     }
 }
 
@@ -271,6 +344,11 @@ int launch_upconv2_dgrad(const void *Pdy, const void *u, void *Pdx, const Geo &g
 #define SP3D_UPD(E)                                                                                  \
     hipLaunchKernelGGL(upconv2_dgrad_kernel<E>, grid, block, 0, s, static_cast<const E *>(Pdy),      \
                        static_cast<const E *>(u), static_cast<E *>(Pdx), gf, gc, l, cin, cout)
+    if (dt == SP_BF16 && cout % 8 == 0) {
+        hipLaunchKernelGGL(upconv2_dgrad_bf16x8_kernel, grid, block, 0, s, static_cast<const uint16_t *>(Pdy),
+                           static_cast<const uint16_t *>(u), static_cast<uint16_t *>(Pdx), gf, gc, l, cin, cout);
+        return record_hip(hipGetLastError());
+    }
     SP3D_BY_DTYPE(SP3D_UPD(uint16_t), SP3D_UPD(float));
 #undef SP3D_UPD
     return record_hip(hipGetLastError());
@@ -296,6 +374,26 @@ int launch_upconv2_wgrad(const void *Px, const void *Pdy, float *du, float *db, 
     const int cw = cout < kThreads ? cout : kThreads;
     const int zg = (cout + cw - 1) / cw;
     dim3 block(kThreads), gw_(8 * cin, ncw, zg), gb_(1, ncb, zg);
+    int co8_shift = -1;
+    if (dt == SP_BF16 && cout % 8 == 0 && cout <= 8 * kThreads && ((cout / 8) & (cout / 8 - 1)) == 0) {
+        co8_shift = 0;
+        while ((1 << co8_shift) < cout / 8) ++co8_shift;
+    }
+    if (co8_shift >= 0) {
+        const int cipb = kThreads >> co8_shift;
+        hipLaunchKernelGGL(upconv2_wgrad_bf16x8_kernel, dim3((cin + cipb - 1) / cipb, ncw), block, 0, s,
+                           static_cast<const uint16_t *>(Px), static_cast<const uint16_t *>(Pdy), part_w, gf, gc, lc,
+                           cin, cout, co8_shift, cvw);
+        if (db)
+            hipLaunchKernelGGL(bsum_kernel<uint16_t>, gb_, block, 0, s, static_cast<const uint16_t *>(Pdy), part_b,
+                               gf, lf, cout, cw, cvb);
+        int rc2 = record_hip(hipGetLastError());
+        if (rc2 != SP_OK) return rc2;
+        rc2 = launch_reduce_partials(part_w, du, ncw, 8LL * cin * cout, s);
+        if (rc2 != SP_OK) return rc2;
+        if (db) rc2 = launch_reduce_partials(part_b, db, ncb, cout, s);
+        return rc2;
+    }
 #define SP3D_UPW(E)                                                                                  \
     do {                                                                                             \
         hipLaunchKernelGGL(upconv2_wgrad_kernel<E>, gw_, block, 0, s, static_cast<const E *>(Px),    \
