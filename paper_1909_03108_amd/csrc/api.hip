@@ -105,6 +105,7 @@ size_t sp_workspace_bytes(int op, const sp_geom_t *g, int cin, int cout, sp_dtyp
         return conv_mfma_supported(o, ki, ko, dt) ? conv_mfma_ws_bytes(o, ki, ko) : 0;
     }
     case SP_OP_WGRAD:
+        if (conv_c1_supported(o, cin, cout, dt)) return wgrad_c1_ws_bytes(o, cout);
         return wgrad_mfma_supported(o, cin, cout, dt) ? wgrad_mfma_ws_bytes(o, cin, cout)
                                                       : wgrad_direct_ws_bytes(o, cin, cout);
     case SP_OP_UPCONV_WGRAD: {
@@ -217,6 +218,7 @@ int conv3d_fwd(const void *Px, const void *w, const float *bias, void *Py, const
         if (need && (!ws || ws_bytes < need || !aligned16(ws))) return SP_EWORKSPACE;
         return launch_conv_mfma(Px, w, bias, Py, o, cin, cout, relu, false, ws, s);
     }
+    if (conv_c1_supported(o, cin, cout, dt)) return launch_conv_c1_fwd(Px, w, bias, Py, o, cout, relu, s);
     return launch_conv_direct(Px, w, bias, Py, o, cin, cout, dt, relu, false, s);
 }
 
@@ -245,9 +247,12 @@ int conv3d_wgrad(const void *Px, const void *Pdz, float *dw, float *db, const sp
     if (rc != SP_OK) return rc;
     if (db && (reinterpret_cast<uintptr_t>(db) & 3u)) return SP_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const bool mfma = wgrad_mfma_supported(o, cin, cout, dt);
-    const size_t need = mfma ? wgrad_mfma_ws_bytes(o, cin, cout) : wgrad_direct_ws_bytes(o, cin, cout);
+    const bool c1 = conv_c1_supported(o, cin, cout, dt);
+    const bool mfma = !c1 && wgrad_mfma_supported(o, cin, cout, dt);
+    const size_t need = c1 ? wgrad_c1_ws_bytes(o, cout)
+                           : (mfma ? wgrad_mfma_ws_bytes(o, cin, cout) : wgrad_direct_ws_bytes(o, cin, cout));
     if (need && (!ws || ws_bytes < need || !aligned16(ws))) return SP_EWORKSPACE;
+    if (c1) return launch_wgrad_c1(Px, Pdz, dw, db, o, cout, ws, s);
     if (mfma) return launch_wgrad_mfma(Px, Pdz, dw, db, o, cin, cout, ws, s);
     return launch_wgrad_direct(Px, Pdz, dw, db, o, cin, cout, dt, ws, s);
 }

@@ -75,6 +75,14 @@ size_t conv_mfma_ws_bytes(const Geo &g, int cin, int cout);
 int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Pout, const Geo &g,
                      int cin, int cout, bool relu, bool dgrad, void *ws, hipStream_t s);
 
+// single-input-channel first layer (conv_c1.hip)
+bool conv_c1_supported(const Geo &g, int cin, int cout, sp_dtype_t dt);
+int launch_conv_c1_fwd(const void *Px, const void *w, const float *bias, void *Py, const Geo &g, int cout,
+                       bool relu, hipStream_t s);
+size_t wgrad_c1_ws_bytes(const Geo &g, int cout);
+int launch_wgrad_c1(const void *Px, const void *Pdz, float *dw, float *db, const Geo &g, int cout, void *ws,
+                    hipStream_t s);
+
 bool wgrad_mfma_supported(const Geo &g, int cin, int cout, sp_dtype_t dt);
 size_t wgrad_mfma_ws_bytes(const Geo &g, int cin, int cout);
 int launch_wgrad_mfma(const void *Px, const void *Pdz, float *dw, float *db, const Geo &g,

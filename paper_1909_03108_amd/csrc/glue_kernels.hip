@@ -282,6 +282,21 @@ __global__ __launch_bounds__(kThreads) void add_kernel(const E *__restrict__ a, 
     if (i < n) stf<E>(o, i, ldf<E>(a, i) + ldf<E>(b, i));
 }
 
+// chunking of the coarse voxels for the up-convolution weight gradient: short chunks (many
+// workgroups) as long as the partial sums stay below 256 MB
+void upconv_wgrad_plan(unsigned nvox, int cin, int cout, int *nchunks, unsigned *chunk_vox) {
+    const size_t per_chunk = 8ull * cin * cout * sizeof(float);
+    size_t cap = (256ull << 20) / per_chunk;
+    if (cap < 1) cap = 1;
+    if (cap > 4096) cap = 4096;
+    size_t want = (nvox + 1023) / 1024;
+    if (want < 1) want = 1;
+    const unsigned nc = static_cast<unsigned>(want < cap ? want : cap);
+    const unsigned cv = (nvox + nc - 1) / nc;
+    *nchunks = static_cast<int>((nvox + cv - 1) / cv);
+    *chunk_vox = cv;
+}
+
 void reduction_plan(unsigned nvox, int *nchunks, unsigned *chunk_vox) {
     unsigned cv = 8192;
     unsigned nc = (nvox + cv - 1) / cv;
@@ -356,7 +371,7 @@ int launch_upconv2_dgrad(const void *Pdy, const void *u, void *Pdx, const Geo &g
 
 size_t upconv2_wgrad_ws_bytes(const Geo &gc, int cin, int cout) {
     int ncw; unsigned cvw;
-    reduction_plan(static_cast<unsigned>(1LL * gc.ntiles * gc.int_vox), &ncw, &cvw);
+    upconv_wgrad_plan(static_cast<unsigned>(1LL * gc.ntiles * gc.int_vox), cin, cout, &ncw, &cvw);
     int ncb; unsigned cvb;
     reduction_plan(static_cast<unsigned>(8LL * gc.ntiles * gc.int_vox), &ncb, &cvb);
     return (static_cast<size_t>(ncw) * 8 * cin * cout + static_cast<size_t>(ncb) * cout) * sizeof(float);
@@ -367,7 +382,7 @@ int launch_upconv2_wgrad(const void *Px, const void *Pdy, float *du, float *db, 
     if (1LL * gf.ntiles * gf.int_vox > 0xffffff00LL) return SP_EGEOM;
     const Lay lc = make_lay(gc, cout), lf = make_lay(gf, cout);
     int ncw, ncb; unsigned cvw, cvb;
-    reduction_plan(lc.nvox, &ncw, &cvw);
+    upconv_wgrad_plan(lc.nvox, cin, cout, &ncw, &cvw);
     reduction_plan(lf.nvox, &ncb, &cvb);
     float *part_w = static_cast<float *>(ws);
     float *part_b = part_w + static_cast<size_t>(ncw) * 8 * cin * cout;
