@@ -36,10 +36,66 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--size", type=int, default=512, help="volume edge (512 = headline workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", default="c4", choices=["c4", "c5"],
+                    help="c4 = headline single-layer workload (default); c5 = the whole U-Net convolution "
+                         "stack of the workload list (256^3, channels 32/64/128/256), forward + backward")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (torch copy_) so that profiler "
                          "byte counters can be scaled against a kernel of known traffic")
     return ap.parse_args()
+
+
+def bench_unet(args):
+    """Secondary workload: the U-Net convolution stack (configuration 5), one step = forward + backward."""
+    import numpy as np
+    import torch
+    from paper_1909_03108_amd import sp3d, synth, unet
+
+    torch.cuda.set_device(0)
+    S = 256 if args.size == 512 else args.size
+    channels, in_ch, classes = (32, 64, 128, 256), 1, 3
+    n, dhw, grid = 1, (S, S, S), (4, 4, 1)
+    plan = unet.layer_plan(channels, in_ch, classes)
+
+    def dev(a):
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+
+    x = dev(synth.ct_like_volume((n,) + dhw + (in_ch,), synth.seed_for(5, synth.T_INPUT), "bf16"))
+    w = {name: dev(synth.weights(shape[3], shape[4], synth.seed_for(5, synth.T_WEIGHT0 + k), "bf16",
+                                 taps=shape[:3])) for k, (name, shape) in enumerate(plan)}
+    dl = dev(synth.normal_volume((n,) + dhw + (classes,), synth.seed_for(5, synth.T_UPSTREAM), "bf16"))
+    net = unet.UNet(n, dhw, grid, w, channels, in_ch, classes)
+
+    def step():
+        net.forward(x)
+        net.backward(dl, input_grad=False)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    vox = n * S * S * S
+    flop = 0.0
+    for name, shape in plan:
+        lvl_vox = vox
+        if name[:3] in ("enc", "dec"):
+            lvl_vox = vox >> (3 * int(name[3]))
+        elif name[:2] == "up":
+            lvl_vox = vox >> (3 * int(name[2]))
+        taps = shape[0] * shape[1] * shape[2]
+        per = 2.0 * shape[3] * shape[4] * lvl_vox * (taps if taps != 8 else 1)   # up-conv: 1 tap per output voxel
+        flop += 3 * per
+    flop -= 2.0 * 27 * in_ch * channels[0] * vox                    # no image gradient
+    print(json.dumps({
+        "metric": "U-Net conv stack fwd+bwd TFLOP/s (bf16), secondary workload", "value": round(flop / ms / 1e9, 2),
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "c5_unet_%d^3: channels 32/64/128/256, grid 4x4x1, halo 1, forward + backward "
+                               "(weight and data gradients, no image gradient)" % S}}))
 
 
 def main():
@@ -48,6 +104,8 @@ def main():
         print("bench.py: this build runs on one GPU only (all tiles of the grid live in one HBM); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
+    if args.workload == "c5":
+        return bench_unet(args)
 
     import numpy as np
     import torch

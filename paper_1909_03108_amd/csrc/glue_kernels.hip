@@ -284,6 +284,36 @@ __global__ __launch_bounds__(kThreads) void add_kernel(const E *__restrict__ a, 
 
 // chunking of the coarse voxels for the up-convolution weight gradient: short chunks (many
 // workgroups) as long as the partial sums stay below 256 MB
+// concat / split in 16-byte chunks (bf16, both channel counts multiples of 8)
+template <bool SPLIT>
+__global__ __launch_bounds__(kThreads) void concat_x8_kernel(uint4 *__restrict__ a, int ca8, uint4 *__restrict__ b,
+                                                             int cb8, uint4 *__restrict__ c, size_t total) {
+    const size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (i >= total) return;
+    const int cc = ca8 + cb8;
+    const size_t v = i / cc;
+    const int ch = static_cast<int>(i % cc);
+    uint4 *narrow = ch < ca8 ? a + v * ca8 + ch : b + v * cb8 + (ch - ca8);
+    if (SPLIT) *narrow = c[i]; else c[i] = *narrow;
+}
+
+// element-wise sum, bf16, 8 elements per thread
+__global__ __launch_bounds__(kThreads) void add_bf16x8_kernel(const uint4 *__restrict__ a, const uint4 *__restrict__ b,
+                                                              uint4 *__restrict__ o, size_t nvec) {
+    const size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (i >= nvec) return;
+    const uint4 x = a[i], y = b[i];
+    const uint32_t xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
+    uint32_t r[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const float lo = __uint_as_float(xs[k] << 16) + __uint_as_float(ys[k] << 16);
+        const float hi = __uint_as_float(xs[k] & 0xffff0000u) + __uint_as_float(ys[k] & 0xffff0000u);
+        r[k] = static_cast<uint32_t>(f32_to_bf16(lo)) | (static_cast<uint32_t>(f32_to_bf16(hi)) << 16);
+    }
+    o[i] = make_uint4(r[0], r[1], r[2], r[3]);
+}
+
 void upconv_wgrad_plan(unsigned nvox, int cin, int cout, int *nchunks, unsigned *chunk_vox) {
     const size_t per_chunk = 8ull * cin * cout * sizeof(float);
     size_t cap = (256ull << 20) / per_chunk;
@@ -428,6 +458,13 @@ int launch_upconv2_wgrad(const void *Px, const void *Pdy, float *du, float *db, 
 }
 
 int launch_add(const void *Pa, const void *Pb, void *Pout, size_t elems, sp_dtype_t dt, hipStream_t s) {
+    if (dt == SP_BF16 && elems % 8 == 0 && (elems / 8 + kThreads - 1) / kThreads <= 0x7fffffffULL) {
+        const size_t nvec = elems / 8;
+        hipLaunchKernelGGL(add_bf16x8_kernel, dim3(static_cast<unsigned>((nvec + kThreads - 1) / kThreads)),
+                           dim3(kThreads), 0, s, static_cast<const uint4 *>(Pa), static_cast<const uint4 *>(Pb),
+                           static_cast<uint4 *>(Pout), nvec);
+        return record_hip(hipGetLastError());
+    }
     const size_t blocks = (elems + kThreads - 1) / kThreads;
     if (blocks > 0x7fffffffULL) return SP_EGEOM;
     dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
@@ -440,6 +477,20 @@ int launch_add(const void *Pa, const void *Pb, void *Pout, size_t elems, sp_dtyp
 
 int launch_concat(const void *Pa, int ca, const void *Pb, int cb, void *Pc, size_t voxels, sp_dtype_t dt,
                   bool split, hipStream_t s) {
+    if (dt == SP_BF16 && ca % 8 == 0 && cb % 8 == 0) {
+        const size_t total8 = voxels * ((ca + cb) / 8);
+        const size_t blocks8 = (total8 + kThreads - 1) / kThreads;
+        if (blocks8 > 0x7fffffffULL) return SP_EGEOM;
+        dim3 grid8(static_cast<unsigned>(blocks8)), block8(kThreads);
+        uint4 *pa = static_cast<uint4 *>(const_cast<void *>(Pa)), *pb = static_cast<uint4 *>(const_cast<void *>(Pb));
+        if (split)
+            hipLaunchKernelGGL(concat_x8_kernel<true>, grid8, block8, 0, s, pa, ca / 8, pb, cb / 8,
+                               static_cast<uint4 *>(Pc), total8);
+        else
+            hipLaunchKernelGGL(concat_x8_kernel<false>, grid8, block8, 0, s, pa, ca / 8, pb, cb / 8,
+                               static_cast<uint4 *>(Pc), total8);
+        return record_hip(hipGetLastError());
+    }
     const size_t total = voxels * (ca + cb);
     const size_t blocks = (total + kThreads - 1) / kThreads;
     if (blocks > 0x7fffffffULL) return SP_EGEOM;

@@ -187,6 +187,23 @@ __global__ __launch_bounds__(kThreads) void relu_bwd_kernel(const E *__restrict_
         dz[i] = positive<E>(y[i]) ? dy[i] : E(0);
 }
 
+// 16-byte variant for bf16 (8 elements per thread): mask built from the sign/zero test of each half word
+__global__ __launch_bounds__(kThreads) void relu_bwd_bf16x8_kernel(const u32x4 *__restrict__ dy,
+                                                                   const u32x4 *__restrict__ y,
+                                                                   u32x4 *__restrict__ dz, size_t nvec) {
+    const size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (i >= nvec) return;
+    const u32x4 g = dy[i], v = y[i];
+    u32x4 o;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t lo = positive<uint16_t>(static_cast<uint16_t>(v[k] & 0xffffu)) ? 0x0000ffffu : 0u;
+        const uint32_t hi = positive<uint16_t>(static_cast<uint16_t>(v[k] >> 16)) ? 0xffff0000u : 0u;
+        o[k] = g[k] & (lo | hi);
+    }
+    dz[i] = o;
+}
+
 }  // namespace
 
 int launch_partition(const void *vol, void *P, const Geo &g, int c, sp_dtype_t dt, bool inverse,
@@ -247,6 +264,13 @@ int launch_halo_unpack(void *P, const void *msg, const Geo &g, int c, sp_dtype_t
 int launch_relu_bwd(const void *dy, const void *y, void *dz, size_t elems, sp_dtype_t dt,
                     hipStream_t s) {
     if (elems == 0) return SP_OK;
+    if (dt == SP_BF16 && elems % 8 == 0 && elems / 8 <= 0x7fffffffULL * kThreads) {
+        const size_t nvec = elems / 8;
+        hipLaunchKernelGGL(relu_bwd_bf16x8_kernel, dim3(static_cast<unsigned>((nvec + kThreads - 1) / kThreads)),
+                           dim3(kThreads), 0, s, static_cast<const u32x4 *>(dy), static_cast<const u32x4 *>(y),
+                           static_cast<u32x4 *>(dz), nvec);
+        return record_hip(hipGetLastError());
+    }
     size_t blocks = (elems + kThreads - 1) / kThreads;
     if (blocks > 65536) blocks = 65536;
     dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
