@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 # HBM traffic per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (see profiles/ and the design doc for the scaling against a plain copy kernel); None = not measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {512: 18.61e9}      # profiles/bench_512_hbm_traffic.md
 
 
 def parse():
