@@ -91,3 +91,51 @@ def test_error_strings():
     seen = {L.sp_strerror(c) for c in range(-5, 1)}
     assert len(seen) == 6 and all(s for s in seen)
     assert L.sp_last_hip_error() == 0
+
+
+def test_glue_calls_reject_bad_arguments_before_launching():
+    L = sp3d.lib()
+    g = sp3d.Geom(1, (8, 8, 8), (2, 2, 2))
+    odd = sp3d.Geom(1, (6, 8, 8), (2, 2, 2))            # tile depth 3: cannot be pooled
+    gp, op = ctypes.byref(g), ctypes.byref(odd)
+    A, B, C = FAKE, FAKE * 2, FAKE * 4
+    assert L.sp_maxpool2_fwd(A, None, gp, 4, sp3d.SP_BF16, None) == sp3d.SP_EINVAL
+    assert L.sp_maxpool2_fwd(A, B, op, 4, sp3d.SP_BF16, None) == sp3d.SP_EGEOM
+    assert L.sp_maxpool2_bwd(A, B, C + 4, gp, 4, sp3d.SP_BF16, None) == sp3d.SP_EINVAL     # misaligned
+    assert L.sp_upconv2_fwd(A, B, None, C, op, 8, 4, sp3d.SP_BF16, None) == sp3d.SP_EGEOM
+    assert L.sp_upconv2_fwd(A, B, None, C, gp, 0, 4, sp3d.SP_BF16, None) == sp3d.SP_EINVAL
+    assert L.sp_upconv2_dgrad(A, B, C, gp, 8, 4, 9, None) == sp3d.SP_EUNSUPPORTED
+    need = sp3d.sp_workspace_bytes(sp3d.SP_OP_UPCONV_WGRAD, g, 8, 4, sp3d.SP_BF16)
+    assert need > 0
+    assert L.sp_upconv2_wgrad(A, B, C, None, gp, 8, 4, sp3d.SP_BF16, None, 0, None) == sp3d.SP_EWORKSPACE
+    assert L.sp_upconv2_wgrad(A, B, C, None, gp, 8, 4, sp3d.SP_BF16, FAKE * 8, need - 1, None) == sp3d.SP_EWORKSPACE
+    assert L.sp_pointwise_fwd(A, B, None, C, gp, 8, 3, sp3d.SP_BF16, 4, None) == sp3d.SP_EINVAL         # bad flag
+    assert L.sp_pointwise_dgrad(A, None, C, gp, 8, 3, sp3d.SP_BF16, None) == sp3d.SP_EINVAL
+    needp = sp3d.sp_workspace_bytes(sp3d.SP_OP_POINTWISE_WGRAD, g, 8, 3, sp3d.SP_BF16)
+    assert L.sp_pointwise_wgrad(A, B, C, None, gp, 8, 3, sp3d.SP_BF16, FAKE * 8, needp - 1, None) == sp3d.SP_EWORKSPACE
+    assert L.sp_concat(A, 4, B, 0, C, gp, sp3d.SP_BF16, None) == sp3d.SP_EINVAL
+    assert L.sp_split(A, B, 4, None, 4, gp, sp3d.SP_BF16, None) == sp3d.SP_EINVAL
+    assert L.sp_add(A, B, None, gp, 4, sp3d.SP_BF16, None) == sp3d.SP_EINVAL
+    assert L.sp_workspace_bytes(sp3d.SP_OP_UPCONV_WGRAD, op, 8, 4, sp3d.SP_BF16) == ctypes.c_size_t(-1).value
+
+
+def test_workspace_sizes_of_the_kernel_families():
+    """Which kernel family a call will use is visible through its workspace size (host logic only)."""
+    g = sp3d.Geom(1, (128, 128, 128), (4, 4, 1))
+    frag = 27 * 2 * 64 * 16                                    # packed weight fragments of one 32x32 pair
+    assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 32, 32, sp3d.SP_BF16) == frag
+    assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 32, 64, sp3d.SP_BF16) == 2 * frag      # one input chunk: no partials
+    padded64 = sp3d.sp_padded_elems(g, 64)
+    assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 64, 64, sp3d.SP_BF16) == 4 * frag + 4 * padded64
+    assert sp3d.sp_workspace_bytes(sp3d.SP_OP_DGRAD, g, 32, 64, sp3d.SP_BF16) == 2 * frag + 4 * sp3d.sp_padded_elems(g, 32)
+    assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 1, 32, sp3d.SP_BF16) == 0               # first-layer kernel
+    assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 8, 16, sp3d.SP_F32) == 0                # direct kernel
+    for cin, cout in ((32, 32), (64, 128), (1, 32), (3, 5)):
+        assert sp3d.sp_workspace_bytes(sp3d.SP_OP_WGRAD, g, cin, cout, sp3d.SP_BF16) > 0
+
+
+def test_geometry_limits():
+    # per-tile voxel indices must stay 32-bit
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (2048, 2048, 2048), (1, 1, 1))) == sp3d.SP_EGEOM
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (2048, 2048, 2048), (2, 2, 2))) == sp3d.SP_OK
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (7, 8, 8), (7, 1, 1))) == sp3d.SP_OK
