@@ -69,6 +69,16 @@ __device__ __forceinline__ s16x4 tr_read(const char *p) {
         (lds_s16x4 *)(__attribute__((address_space(3))) char *)(p));
 }
 
+// Masked 16-byte chunk: the load goes to a safe address when the chunk is outside the plane ...
+__device__ __forceinline__ uint4 ldg_clamped(bool ok, const uint16_t *p, const uint16_t *safe) {
+    return *reinterpret_cast<const uint4 *>(ok ? p : safe);
+}
+// ... and the value is zeroed where it is consumed (after the plane's MFMAs), so that nothing waits
+// for the load earlier than that.
+__device__ __forceinline__ uint4 keep_if(bool ok, const uint4 &v) {
+    return make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
+}
+
 // One operand fragment (32 voxels x 16 channels): voxels 0..15 then 16..31 of a row.
 __device__ __forceinline__ bf16x8 frag(const char *p) {
     union { struct { s16x4 lo, hi; } s; bf16x8 v; } u;
@@ -81,17 +91,28 @@ __device__ __forceinline__ bf16x8 frag(const char *p) {
 // of this wave's row group; xlane / zlane already point at the group's first row.
 template <int P>   // P = D mod 4
 __device__ __forceinline__ void plane_step(const char *xlane, const char *zlane, f32x4 (&acc)[27]) {
-    bf16x8 zf[3][3];   // [kd][row mod 3]
+    // Software pipeline over the x rows: the fragments of row R + 1 are requested before the MFMAs
+    // of row R are issued, and the scheduling barriers keep the compiler from sinking the reads
+    // back down to their first use (which would expose the LDS latency once per row).
+    bf16x8 zf[3][4];   // [kd][row mod 4]: rows R, R-1, R-2 in use, R+1 in flight
+    bf16x8 xf[2][3];   // [row parity][kw]
+#pragma unroll
+    for (int kw = 0; kw < 3; ++kw) xf[0][kw] = frag(xlane + kw * 32);
+#pragma unroll
+    for (int kd = 0; kd < 3; ++kd) zf[kd][0] = frag(zlane + ((P - kd + 4) % 4) * Z_PLANE);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int R = 0; R < GR + 2; ++R) {
-        bf16x8 xf[3];
+        if (R + 1 < GR + 2) {
 #pragma unroll
-        for (int kw = 0; kw < 3; ++kw) xf[kw] = frag(xlane + (R * XC + kw) * 32);
-        if (R < GR) {
+            for (int kw = 0; kw < 3; ++kw) xf[(R + 1) & 1][kw] = frag(xlane + ((R + 1) * XC + kw) * 32);
+        }
+        if (R + 1 < GR) {
 #pragma unroll
             for (int kd = 0; kd < 3; ++kd)
-                zf[kd][R % 3] = frag(zlane + ((P - kd + 4) % 4) * Z_PLANE + R * PW * 32);
+                zf[kd][(R + 1) & 3] = frag(zlane + ((P - kd + 4) % 4) * Z_PLANE + (R + 1) * PW * 32);
         }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int kh = 0; kh < 3; ++kh) {
             const int h = R - kh;
@@ -101,10 +122,11 @@ __device__ __forceinline__ void plane_step(const char *xlane, const char *zlane,
 #pragma unroll
                 for (int kw = 0; kw < 3; ++kw) {
                     const int tap = (kd * 3 + kh) * 3 + kw;
-                    acc[tap] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[kw], zf[kd][h % 3], acc[tap],
+                    acc[tap] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[R & 1][kw], zf[kd][h & 3], acc[tap],
                                                                        0, 0, 0);
                 }
         }
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -175,19 +197,18 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
         // staged chunks travel in registers from the global loads (issued before a plane's MFMAs)
         // to the LDS writes (after them)
         uint4 xs0, xs1, xs2, xs3, zs0, zs1;
-        const uint4 zero4 = make_uint4(0, 0, 0, 0);
-#define SP3D_LDG(ok, ptr) ((ok) ? *reinterpret_cast<const uint4 *>(ptr) : zero4)
+#define SP3D_LDG(ok, ptr, safe) ldg_clamped(ok, ptr, safe)
 #define SP3D_FETCH(D)                                                                  \
     do {                                                                               \
         const uint16_t *px = tx + (d0 + (D)) * xplane;                                 \
-        xs0 = SP3D_LDG(xok[0], px + xsrc0);                                            \
-        xs1 = SP3D_LDG(xok[1], px + xsrc0 + 4 * xrow_elems);                           \
-        xs2 = SP3D_LDG(xok[2], px + xsrc0 + 8 * xrow_elems);                           \
-        xs3 = SP3D_LDG(eok, px + xsrce);                                               \
+        xs0 = SP3D_LDG(xok[0], px + xsrc0, tx);                                        \
+        xs1 = SP3D_LDG(xok[1], px + xsrc0 + 4 * xrow_elems, tx);                       \
+        xs2 = SP3D_LDG(xok[2], px + xsrc0 + 8 * xrow_elems, tx);                       \
+        xs3 = SP3D_LDG(eok, px + xsrce, tx);                                           \
         const bool zreal = (D) < dn;                                                   \
         const uint16_t *pz = tz + (d0 + (D) + 1) * zplane;                             \
-        zs0 = SP3D_LDG(zreal && zok[0], pz + zsrc0);                                   \
-        zs1 = SP3D_LDG(zreal && zok[1], pz + zsrc0 + 4 * zrow_elems);                  \
+        zs0 = SP3D_LDG(zreal && zok[0], pz + zsrc0, tz);                               \
+        zs1 = SP3D_LDG(zreal && zok[1], pz + zsrc0 + 4 * zrow_elems, tz);              \
     } while (0)
 #define SP3D_BSUM(V_)                                                                  \
     do {                                                                               \
@@ -198,6 +219,10 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
     } while (0)
 #define SP3D_COMMIT(D)                                                                 \
     do {                                                                               \
+        const bool zreal = (D) < dn;                                                   \
+        xs0 = keep_if(xok[0], xs0); xs1 = keep_if(xok[1], xs1);                        \
+        xs2 = keep_if(xok[2], xs2); xs3 = keep_if(eok, xs3);                           \
+        zs0 = keep_if(zreal && zok[0], zs0); zs1 = keep_if(zreal && zok[1], zs1);      \
         char *xp = xbuf + ((D) & 1) * X_BYTES;                                         \
         *reinterpret_cast<uint4 *>(xp + xdst0) = xs0;                                  \
         *reinterpret_cast<uint4 *>(xp + xdst0 + 4 * XC * 32) = xs1;                    \
@@ -214,8 +239,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
         __syncthreads();   // every wave is done reading the previous item's planes
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            *reinterpret_cast<uint4 *>(zbuf + 2 * Z_PLANE + zdst0 + 4 * i * PW * 32) = zero4;
-            *reinterpret_cast<uint4 *>(zbuf + 3 * Z_PLANE + zdst0 + 4 * i * PW * 32) = zero4;
+            *reinterpret_cast<uint4 *>(zbuf + 2 * Z_PLANE + zdst0 + 4 * i * PW * 32) = make_uint4(0, 0, 0, 0);
+            *reinterpret_cast<uint4 *>(zbuf + 3 * Z_PLANE + zdst0 + 4 * i * PW * 32) = make_uint4(0, 0, 0, 0);
         }
         SP3D_FETCH(0);
         SP3D_COMMIT(0);
@@ -279,6 +304,233 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
         for (int k = chunk; k < kThreads; k += 4) s += red[k * 8 + j];
         a.part_b[group * C + tid] = s;
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Variant for tiles whose interior is a whole number of 8 x 32 patches: every staged chunk is real
+// data, so the planes go from global memory straight into LDS (global_load_lds: lane l's 16 bytes
+// land at LDS base + 16*l) two planes ahead of their use, and no registers, LDS writes or VALU work
+// are spent on staging.  What the staging registers did for free moves elsewhere:
+//  - dz planes outside the D chunk (D - kd < 0 or >= dn) are not zero-filled in LDS; the fragments
+//    read for such a plane are and-ed with a wave-uniform zero mask instead, so stale LDS contents
+//    (any bit pattern) never reach the matrix cores;
+//  - the bias gradient is one more MFMA per dz row with an all-ones A operand (every row of the
+//    result is the column sum), issued by one wave per SIMD.
+constexpr int NXB = 3, NZB = 5;               // ring slots: x planes D..D+2, dz planes D-2..D+2
+constexpr int XG = (XVOX + 31) / 32;          // 11 groups of 32 voxels per x plane; the last one is padded
+constexpr int XD_HALF = XG * 32 * 32 + 64;    // 11328: room for the padding voxels of the last group
+constexpr int XD_BYTES = 2 * XD_HALF;
+constexpr int DMA_STAGE_BYTES = NXB * XD_BYTES + NZB * Z_PLANE;       // 150528
+constexpr int DMA_LDS_BYTES = DMA_STAGE_BYTES > RED_BYTES ? DMA_STAGE_BYTES : RED_BYTES;
+static_assert(DMA_LDS_BYTES <= 160 * 1024, "LDS of one CU");
+// Wave loads per plane pair: 2 halves x 11 groups for x, 2 halves x 8 groups for dz.  Each of the 8
+// waves issues 3 x loads (24 slots for 22 loads: the last two waves repeat one of theirs) and 2 dz loads.
+constexpr int DMA_X = 3, DMA_Z = 2, DMA_PER_WAVE = DMA_X + DMA_Z;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// 16 bytes per lane from global memory straight into LDS: lane l's data lands at dst + 16*l (dst is
+// wave-uniform and travels in M0).  Written as assembly because the compiler, when it knows of such a
+// load, waits for ALL outstanding ones before every transposing LDS read, which would undo the
+// two-plane prefetch; the kernel waits for exactly the loads it needs with explicit s_waitcnt vmcnt.
+__device__ __forceinline__ void dma16(const uint16_t *src, char *dst) {
+    const uint32_t l = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+        (__attribute__((address_space(3))) char *)dst));
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(src), "s"(l)
+                 : "memory");
+}
+
+__device__ __forceinline__ bf16x8 frag_masked(const char *p, uint32_t m) {
+    union { struct { s16x4 lo, hi; } s; u32x4 w; bf16x8 v; } u;
+    u.s.lo = tr_read(p);
+    u.s.hi = tr_read(p + 16 * 32);
+    u.w &= m;
+    return u.v;
+}
+
+// Same march as plane_step, with run-time ring slots: z[kd] points at dz plane D - kd, m[kd] is
+// all ones if that plane exists and zero otherwise.
+__device__ __forceinline__ void plane_step_dma(const char *xl, const char *z0, const char *z1, const char *z2,
+                                               uint32_t m0, uint32_t m1, uint32_t m2, bool bias_wave,
+                                               f32x4 (&acc)[27], f32x4 &accb) {
+    const char *z[3] = {z0, z1, z2};
+    const uint32_t m[3] = {m0, m1, m2};
+    union { uint32_t w[4]; bf16x8 v; } ones;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ones.w[i] = 0x3f803f80u;     // bf16 1.0 pairs
+    bf16x8 zf[3][4];
+    bf16x8 xf[2][3];
+#pragma unroll
+    for (int kw = 0; kw < 3; ++kw) xf[0][kw] = frag(xl + kw * 32);
+#pragma unroll
+    for (int kd = 0; kd < 3; ++kd) zf[kd][0] = frag_masked(z[kd], m[kd]);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int R = 0; R < GR + 2; ++R) {
+        if (R + 1 < GR + 2) {
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) xf[(R + 1) & 1][kw] = frag(xl + ((R + 1) * XC + kw) * 32);
+        }
+        if (R + 1 < GR) {
+#pragma unroll
+            for (int kd = 0; kd < 3; ++kd) zf[kd][(R + 1) & 3] = frag_masked(z[kd] + (R + 1) * PW * 32, m[kd]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (bias_wave && R < GR)      // wave-uniform
+            accb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones.v, zf[0][R & 3], accb, 0, 0, 0);
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh) {
+            const int h = R - kh;
+            if (h < 0 || h >= GR) continue;
+#pragma unroll
+            for (int kd = 0; kd < 3; ++kd)
+#pragma unroll
+                for (int kw = 0; kw < 3; ++kw) {
+                    const int tap = (kd * 3 + kh) * 3 + kw;
+                    acc[tap] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[R & 1][kw], zf[kd][h & 3], acc[tap],
+                                                                       0, 0, 0);
+                }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void wgrad_mfma_dma_kernel(WgradArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const Geo &g = a.g;
+    const int per_xcd = gridDim.x >> 3;
+    const int group = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (group >= a.ngroups) return;
+    const int pair = group / a.gpp, gsub = group % a.gpp;
+    const int x_co = C * (pair / a.nco), dz_co = C * (pair % a.nco);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform: scalar control flow below
+    // Waves w and w + 4 share a SIMD: give them different ci halves, so that each SIMD hosts exactly one
+    // of the four waves (ci half 0) that also accumulate the bias gradient.
+    const int kg = wave >> 2;
+    const int qo = wave & 1, qi = ((wave >> 1) & 1) ^ kg;
+    const bool bias_wave = qi == 0;
+    char *xbuf = lds;
+    char *zbuf = lds + NXB * XD_BYTES;
+    const int G = lane >> 4, p = lane & 15;
+    const int lane_off = (4 * G + (p >> 2)) * 32 + (p & 3) * 8;
+    const char *xlane = xbuf + qi * XD_HALF + lane_off + kg * GR * XC * 32;
+    const char *zlane = zbuf + qo * Z_HALF + lane_off + kg * GR * PW * 32;
+
+    // Staging loads of this wave: x loads u = 2*wave, 2*wave + 1 and 16 + wave (waves 6, 7 repeat their
+    // second one), dz loads 2*wave, 2*wave + 1.  Load u covers half u / groups, voxel group u % groups;
+    // lane l fetches chunk l & 1 of voxel 32*group + l/2.  Voxels past the end of the x plane (last
+    // group) re-fetch its last voxel into the padding.
+    int gx[DMA_X], gz[DMA_Z];        // source offsets (elements) inside the item's plane
+    int lx[DMA_X], lz[DMA_Z];        // LDS byte offsets inside ring slot 0
+#pragma unroll
+    for (int j = 0; j < DMA_X; ++j) {
+        const int u = j < 2 ? 2 * wave + j : (wave < 6 ? 16 + wave : 2 * wave + 1);
+        const int half = u / XG, vg = u % XG;
+        const int v = min(vg * 32 + (lane >> 1), XVOX - 1);
+        gx[j] = ((v / XC) * g.pw + v % XC) * a.x_cs + half * 16 + (lane & 1) * 8;
+        lx[j] = half * XD_HALF + vg * 1024;
+    }
+#pragma unroll
+    for (int j = 0; j < DMA_Z; ++j) {
+        const int u = 2 * wave + j;
+        const int half = u / (ZVOX / 32), vg = u % (ZVOX / 32);
+        const int v = vg * 32 + (lane >> 1);
+        gz[j] = ((v / PW + 1) * g.pw + v % PW + 1) * a.dz_cs + half * 16 + (lane & 1) * 8;
+        lz[j] = NXB * XD_BYTES + half * Z_HALF + vg * 1024;
+    }
+
+    f32x4 acc[27];
+#pragma unroll
+    for (int t = 0; t < 27; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    f32x4 accb = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const size_t xplane = static_cast<size_t>(g.ph) * g.pw * a.x_cs, zplane = static_cast<size_t>(g.ph) * g.pw * a.dz_cs;
+
+    for (int item = gsub; item < a.nitems; item += a.gpp) {
+        int t = item;
+        const int pw_i = t % a.nw; t /= a.nw;
+        const int ph_i = t % a.nh; t /= a.nh;
+        const int pd_i = t % a.nd; t /= a.nd;
+        const int tile = t;
+        const int d0 = pd_i * a.dchunk, h0 = ph_i * PH, w0 = pw_i * PW;
+        const int dn = min(a.dchunk, g.td - d0);
+        // padded plane d0 of the tile, at the patch's first voxel and the pair's channels
+        const uint16_t *tx = a.x + (static_cast<size_t>(tile) * g.tile_vox + static_cast<size_t>(d0) * g.ph * g.pw +
+                                    h0 * g.pw + w0) * a.x_cs + x_co;
+        const uint16_t *tz = a.dz + (static_cast<size_t>(tile) * g.tile_vox + static_cast<size_t>(d0 + 1) * g.ph * g.pw +
+                                     h0 * g.pw + w0) * a.dz_cs + dz_co;
+
+        // Stage planes D of x and dz into ring slots sx, sz.  Planes past the last one are clamped to it:
+        // their slots are either never read or masked, and every call issues exactly DMA_PER_WAVE loads.
+#define SP3D_STAGE(D, sx, sz)                                                                      \
+    do {                                                                                           \
+        const uint16_t *px = tx + min((D), dn + 1) * xplane;                                       \
+        const uint16_t *pz = tz + min((D), dn - 1) * zplane;                                       \
+        _Pragma("unroll") for (int j = 0; j < DMA_X; ++j) dma16(px + gx[j], lds + lx[j] + (sx) * XD_BYTES); \
+        _Pragma("unroll") for (int j = 0; j < DMA_Z; ++j) dma16(pz + gz[j], lds + lz[j] + (sz) * Z_PLANE);  \
+    } while (0)
+
+        // every wave has left the previous item's last plane (the barrier that ended it)
+        SP3D_STAGE(0, 0, 0);
+        SP3D_STAGE(1, 1, 1);
+        asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+
+        const int nplanes = dn + 2;
+        int sx = 0, sz = 0;                   // ring slots of planes D
+        for (int D = 0; D < nplanes; ++D) {
+            {
+                const int sx2 = sx + 2 >= NXB ? sx + 2 - NXB : sx + 2;
+                const int sz2 = sz + 2 >= NZB ? sz + 2 - NZB : sz + 2;
+                SP3D_STAGE(D + 2, sx2, sz2);
+            }
+            const int sz1 = sz == 0 ? NZB - 1 : sz - 1;
+            const int sz2m = sz1 == 0 ? NZB - 1 : sz1 - 1;
+            const uint32_t m0 = D < dn ? 0xffffffffu : 0u;
+            const uint32_t m1 = (D >= 1 && D - 1 < dn) ? 0xffffffffu : 0u;
+            const uint32_t m2 = D >= 2 ? 0xffffffffu : 0u;
+            plane_step_dma(xlane + sx * XD_BYTES, zlane + sz * Z_PLANE, zlane + sz1 * Z_PLANE,
+                           zlane + sz2m * Z_PLANE, m0, m1, m2, bias_wave, acc, accb);
+            // plane D + 1 (staged one step ago) has landed once at most this step's loads are in flight
+            asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            sx = sx + 1 == NXB ? 0 : sx + 1;
+            sz = sz + 1 == NZB ? 0 : sz + 1;
+        }
+    }
+#undef SP3D_STAGE
+
+    // The clamped loads of the last item may still be writing LDS: drain them before the staging area is
+    // reused for the reductions.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    float *red = reinterpret_cast<float *>(lds);
+    const int quad = qi * 2 + qo;
+    if (kg == 1) {
+#pragma unroll
+        for (int t = 0; t < 27; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) red[((quad * 27 + t) * 4 + i) * 64 + lane] = acc[t][i];
+    }
+    __syncthreads();
+    if (kg == 0) {
+        float *pw = a.part_w + static_cast<size_t>(group) * 27 * C * C;
+#pragma unroll
+        for (int t = 0; t < 27; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                pw[(t * C + 16 * qi + 4 * G + i) * C + 16 * qo + p] =
+                    acc[t][i] + red[((quad * 27 + t) * 4 + i) * 64 + lane];
+    }
+    // bias partial: row 0 of the ones-product (lanes 0..15, register 0) holds the column sums of the
+    // wave's co half and row group
+    __syncthreads();
+    if (bias_wave && lane < 16) red[(kg * 2 + qo) * 16 + lane] = accb[0];
+    __syncthreads();
+    if (tid < C) a.part_b[group * C + tid] = red[tid] + red[C + tid];
 }
 
 void plan(const Geo &g, int cin, int cout, WgradArgs *a) {
@@ -358,8 +610,15 @@ int launch_wgrad_mfma(const void *Px, const void *Pdz, float *dw, float *db, con
     // more than 64 KB of dynamic LDS has to be requested explicitly
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(wgrad_mfma_kernel),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    static const hipError_t attr_dma = hipFuncSetAttribute(reinterpret_cast<const void *>(wgrad_mfma_dma_kernel),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, DMA_LDS_BYTES);
     if (attr != hipSuccess) return record_hip(attr);
-    hipLaunchKernelGGL(wgrad_mfma_kernel, dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
+    if (attr_dma != hipSuccess) return record_hip(attr_dma);
+    // whole patches only: the direct-to-LDS loads cannot zero-fill a ragged edge
+    if (g.th % PH == 0 && g.tw % PW == 0)
+        hipLaunchKernelGGL(wgrad_mfma_dma_kernel, dim3(grid), dim3(kThreads), DMA_LDS_BYTES, s, a);
+    else
+        hipLaunchKernelGGL(wgrad_mfma_kernel, dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
     int rc = record_hip(hipGetLastError());
     if (rc != SP_OK) return rc;
     const int n = 27 * cin * cout + cout;
