@@ -33,8 +33,8 @@ template <typename T> __device__ __forceinline__ void st_stream(T *p, T v) { __b
 
 // ---------------------------------------------------------------------------------------------
 // partition / unpartition.  A "row" is the run of tw voxels of one tile at fixed (ld, lh); it is
-// contiguous both in the volume and in the padded tile.  One vector per thread (many small
-// workgroups stream best on this chip); a block covers 256 vectors of one row, or several short rows.
+// contiguous both in the volume and in the padded tile.  Many small workgroups stream
+// best on this chip; a block covers kVpt chunks of 256 vectors of a row (or of several short rows).
 struct PartArgs {
     Geo g;
     int rowvecs;       // vectors per row
@@ -45,52 +45,66 @@ struct PartArgs {
     FastDiv rows_per_tile, th, gw, gh, gd;
 };
 
-template <typename T, bool INVERSE>
+// Vectors per thread in the streaming kernels below: the loads of all of them are issued before the
+// first store, which keeps more bytes in flight per wave (two measured best; one or four are slower).
+constexpr int kVpt = 2;
+
+template <typename T, bool INVERSE, int VPT>
 __global__ __launch_bounds__(kThreads) void partition_kernel(const T *__restrict__ src,
                                                              T *__restrict__ dst, PartArgs a) {
     const Geo &g = a.g;
-    const unsigned rpb = kThreads / a.tpr;                  // row chunks per block
-    const unsigned rc = blockIdx.x * rpb + threadIdx.x / a.tpr;   // row chunk index
-    if (rc >= a.nchunks) return;
-    const unsigned row = fdiv(rc, a.cpr);
-    const unsigned j = fmod_(rc, row, a.cpr) * a.tpr + threadIdx.x % a.tpr;
-    if (j >= static_cast<unsigned>(a.rowvecs)) return;
-    // row -> (tile, ld, lh)
-    const unsigned tile = fdiv(row, a.rows_per_tile);
-    const unsigned r = fmod_(row, tile, a.rows_per_tile);
-    const unsigned ld = fdiv(r, a.th), lh = fmod_(r, ld, a.th);
-    // tile -> (n, a, b, c)
-    const unsigned t1 = fdiv(tile, a.gw), tc = fmod_(tile, t1, a.gw);
-    const unsigned t2 = fdiv(t1, a.gh), tb = fmod_(t1, t2, a.gh);
-    const unsigned tn = fdiv(t2, a.gd), ta = fmod_(t2, tn, a.gd);
+    const unsigned rpb = kThreads / a.tpr;                  // row chunks per block and pass
     const long long D = 1LL * g.gd * g.td, H = 1LL * g.gh * g.th, W = 1LL * g.gw * g.tw;
-    const long long vvox = ((tn * D + ta * g.td + ld) * H + tb * g.th + lh) * W + 1LL * tc * g.tw;
-    const long long pvox = tile * g.tile_vox +
-                           (1LL * (ld + g.halo) * g.ph + lh + g.halo) * g.pw + g.halo;
-    if (INVERSE)
-        st_stream(dst + vvox * a.vpv_num + j, ld_stream(src + pvox * a.vpv_num + j));
-    else
-        st_stream(dst + pvox * a.vpv_num + j, ld_stream(src + vvox * a.vpv_num + j));
+    T v[VPT];
+    long long so[VPT], do_[VPT];
+    bool ok[VPT];
+#pragma unroll
+    for (int k = 0; k < VPT; ++k) {
+        const unsigned rc = (blockIdx.x * VPT + k) * rpb + threadIdx.x / a.tpr;   // row chunk index
+        const unsigned rcc = rc < a.nchunks ? rc : 0;
+        const unsigned row = fdiv(rcc, a.cpr);
+        const unsigned j = fmod_(rcc, row, a.cpr) * a.tpr + threadIdx.x % a.tpr;
+        ok[k] = rc < a.nchunks && j < static_cast<unsigned>(a.rowvecs);
+        // row -> (tile, ld, lh)
+        const unsigned tile = fdiv(row, a.rows_per_tile);
+        const unsigned r = fmod_(row, tile, a.rows_per_tile);
+        const unsigned ld = fdiv(r, a.th), lh = fmod_(r, ld, a.th);
+        // tile -> (n, a, b, c)
+        const unsigned t1 = fdiv(tile, a.gw), tc = fmod_(tile, t1, a.gw);
+        const unsigned t2 = fdiv(t1, a.gh), tb = fmod_(t1, t2, a.gh);
+        const unsigned tn = fdiv(t2, a.gd), ta = fmod_(t2, tn, a.gd);
+        const long long vvox = ((tn * D + ta * g.td + ld) * H + tb * g.th + lh) * W + 1LL * tc * g.tw;
+        const long long pvox = tile * g.tile_vox +
+                               (1LL * (ld + g.halo) * g.ph + lh + g.halo) * g.pw + g.halo;
+        so[k] = (INVERSE ? pvox : vvox) * a.vpv_num + j;
+        do_[k] = (INVERSE ? vvox : pvox) * a.vpv_num + j;
+        if (ok[k]) v[k] = ld_stream(src + so[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < VPT; ++k)
+        if (ok[k]) st_stream(dst + do_[k], v[k]);
 }
 
 template <int VB>
 int partition_dispatch(const void *vol, void *P, const PartArgs &a, bool inverse, hipStream_t s) {
     using T = typename VecT<VB>::type;
-    const unsigned rpb = kThreads / a.tpr;
+    // measured: gathering from the padded tiles gains from two vectors per thread, scattering into them
+    // does not
+    const unsigned rpb = (kThreads / a.tpr) * (inverse ? kVpt : 1);
     const unsigned blocks = (a.nchunks + rpb - 1) / rpb;
     dim3 grid(blocks), block(kThreads);
     if (inverse)
-        hipLaunchKernelGGL((partition_kernel<T, true>), grid, block, 0, s,
+        hipLaunchKernelGGL((partition_kernel<T, true, kVpt>), grid, block, 0, s,
                            static_cast<const T *>(P), static_cast<T *>(const_cast<void *>(vol)), a);
     else
-        hipLaunchKernelGGL((partition_kernel<T, false>), grid, block, 0, s,
+        hipLaunchKernelGGL((partition_kernel<T, false, 1>), grid, block, 0, s,
                            static_cast<const T *>(vol), static_cast<T *>(P), a);
     return record_hip(hipGetLastError());
 }
 
 // ---------------------------------------------------------------------------------------------
 // halo pack / unpack.  One block serves a chunk of one region of one tile.
-constexpr int kHaloChunk = kThreads;   // vectors per block: one per thread
+constexpr int kHaloChunk = kThreads * kVpt;   // vectors per block
 
 struct HaloArgs {
     Geo g;
@@ -111,8 +125,7 @@ __global__ __launch_bounds__(kThreads) void halo_kernel(const T *__restrict__ sr
     const Region &r = a.t.r[ri];
     const unsigned chunk = rem - a.blk_prefix[ri];
     const unsigned nvec = static_cast<unsigned>(r.ext[0]) * r.ext[1] * r.ext[2] * a.vpv.d;
-    const unsigned j = chunk * kHaloChunk + threadIdx.x;
-    if (j >= nvec) return;
+    if (chunk * kHaloChunk >= nvec) return;   // uniform; cannot happen with the block counts of halo_dispatch
 
     long long nb_msg = -1;   // UNPACK: voxel offset of the neighbour's message region, -1 = none
     if (UNPACK) {
@@ -127,17 +140,27 @@ __global__ __launch_bounds__(kThreads) void halo_kernel(const T *__restrict__ sr
         }
     }
     const int *org = UNPACK ? r.recv : r.send;
-    const unsigned vox = fdiv(j, a.vpv), cv = fmod_(j, vox, a.vpv);
-    const unsigned ld = fdiv(vox, a.ehw[ri]), q = fmod_(vox, ld, a.ehw[ri]);
-    const unsigned lh = fdiv(q, a.ew[ri]), lw = fmod_(q, lh, a.ew[ri]);
-    const long long pvox = tile * g.tile_vox + (1LL * (org[0] + ld) * g.ph + org[1] + lh) * g.pw + org[2] + lw;
-    if (UNPACK) {
-        T v = zero_vec<T>();
-        if (nb_msg >= 0) v = ld_stream(src + (nb_msg + vox) * a.vpv.d + cv);
-        st_stream(dst + pvox * a.vpv.d + cv, v);
-    } else {
-        st_stream(dst + (tile * g.msg_vox + r.off + vox) * a.vpv.d + cv, ld_stream(src + pvox * a.vpv.d + cv));
+    const long long msg0 = UNPACK ? nb_msg : tile * g.msg_vox + r.off;   // message region of this block
+    T v[kVpt];
+    long long mo[kVpt], po[kVpt];   // vector offsets in the message and in the padded tensor
+    bool ok[kVpt];
+#pragma unroll
+    for (int k = 0; k < kVpt; ++k) {
+        const unsigned j = chunk * kHaloChunk + k * kThreads + threadIdx.x;
+        ok[k] = j < nvec;
+        const unsigned jj = ok[k] ? j : 0;
+        const unsigned vox = fdiv(jj, a.vpv), cv = fmod_(jj, vox, a.vpv);
+        const unsigned ld = fdiv(vox, a.ehw[ri]), q = fmod_(vox, ld, a.ehw[ri]);
+        const unsigned lh = fdiv(q, a.ew[ri]), lw = fmod_(q, lh, a.ew[ri]);
+        const long long pvox = tile * g.tile_vox + (1LL * (org[0] + ld) * g.ph + org[1] + lh) * g.pw + org[2] + lw;
+        po[k] = pvox * a.vpv.d + cv;
+        mo[k] = (msg0 + vox) * a.vpv.d + cv;
+        v[k] = zero_vec<T>();
+        if (ok[k] && (!UNPACK || nb_msg >= 0)) v[k] = ld_stream(src + (UNPACK ? mo[k] : po[k]));
     }
+#pragma unroll
+    for (int k = 0; k < kVpt; ++k)
+        if (ok[k]) st_stream(dst + (UNPACK ? po[k] : mo[k]), v[k]);
 }
 
 template <int VB>
@@ -221,7 +244,7 @@ int launch_partition(const void *vol, void *P, const Geo &g, int c, sp_dtype_t d
     a.tpr = tpr;
     const long long cpr = (a.rowvecs + tpr - 1) / tpr;
     const long long nchunks = 1LL * g.ntiles * g.td * g.th * cpr;
-    if (nchunks > 0xffffff00LL) return SP_EGEOM;
+    if (nchunks > 0xfffffc00LL) return SP_EGEOM;   // room for the rounding up to whole blocks
     a.nchunks = static_cast<unsigned>(nchunks);
     a.cpr = make_fastdiv(static_cast<uint32_t>(cpr));
     a.rows_per_tile = make_fastdiv(static_cast<uint32_t>(g.td) * g.th);
