@@ -368,6 +368,7 @@ int launch_maxpool2(const void *Px, const void *Pdy, void *Pout, const Geo &gf, 
 
 int launch_upconv2_fwd(const void *Px, const void *u, const float *bias, void *Py, const Geo &gf,
                        const Geo &gc, int cin, int cout, sp_dtype_t dt, hipStream_t s) {
+    if (upconv_mfma_supported(gf, gc, cin, cout, dt)) return launch_upconv_fwd_mfma(Px, u, bias, Py, gf, gc, cin, cout, s);
     if (1LL * gf.ntiles * gf.int_vox > 0xffffff00LL) return SP_EGEOM;
     const Lay l = make_lay(gf, cout);
     const unsigned vpb = kThreads >> l.cshift;
@@ -382,6 +383,7 @@ int launch_upconv2_fwd(const void *Px, const void *u, const float *bias, void *P
 
 int launch_upconv2_dgrad(const void *Pdy, const void *u, void *Pdx, const Geo &gf, const Geo &gc, int cin,
                          int cout, sp_dtype_t dt, hipStream_t s) {
+    if (upconv_mfma_supported(gf, gc, cin, cout, dt)) return launch_upconv_dgrad_mfma(Pdy, u, Pdx, gf, gc, cin, cout, s);
     if (1LL * gf.ntiles * gf.int_vox > 0xffffff00LL) return SP_EGEOM;
     const Lay l = make_lay(gc, cin);
     const unsigned vpb = kThreads >> l.cshift;

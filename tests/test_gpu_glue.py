@@ -32,6 +32,7 @@ CASES = [  # n, fine dhw, grid, dtype
     (1, (8, 8, 16), (4, 4, 1), "bf16"),      # coarse tiles 1x1x8
     (2, (4, 12, 8), (2, 3, 2), "f32"),
     (1, (16, 8, 64), (2, 2, 1), "bf16"),
+    (1, (4, 8, 80), (1, 2, 1), "bf16"),      # coarse rows of 40 voxels: one whole and one ragged 32-voxel segment
 ]
 
 
@@ -60,7 +61,7 @@ def test_maxpool_forward_and_backward_bit_exact(n, dhw, grid, dtype, c):
 
 
 @pytest.mark.parametrize("n,dhw,grid,dtype", CASES)
-@pytest.mark.parametrize("cin,cout", [(8, 4), (64, 32), (5, 3)])
+@pytest.mark.parametrize("cin,cout", [(8, 4), (64, 32), (5, 3), (128, 64), (32, 96), (256, 128)])
 def test_upconv_fwd_dgrad_wgrad(n, dhw, grid, dtype, cin, cout):
     gf = sp3d.Geom(n, dhw, grid)
     gc = sp3d.coarse_geom(gf)
