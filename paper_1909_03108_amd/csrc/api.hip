@@ -111,7 +111,7 @@ size_t sp_workspace_bytes(int op, const sp_geom_t *g, int cin, int cout, sp_dtyp
     case SP_OP_UPCONV_WGRAD: {
         Geo c;
         if (make_coarse(o, &c) != SP_OK) return static_cast<size_t>(-1);
-        return upconv2_wgrad_ws_bytes(c, cin, cout);
+        return upconv2_wgrad_ws_bytes(o, c, cin, cout, dt);
     }
     case SP_OP_POINTWISE_WGRAD:
         return wgrad_direct_ws_bytes(o, cin, cout, 1);
@@ -320,7 +320,7 @@ int sp_upconv2_wgrad(const void *Px, const void *Pdy, float *du, float *db, cons
     Geo f, k;
     int rc = check_glue(Px, Pdy, du, gf, cin, cout, dt, &f, &k);
     if (rc != SP_OK) return rc;
-    const size_t need = upconv2_wgrad_ws_bytes(k, cin, cout);
+    const size_t need = upconv2_wgrad_ws_bytes(f, k, cin, cout, dt);
     if (!ws || ws_bytes < need || !aligned16(ws)) return SP_EWORKSPACE;
     return launch_upconv2_wgrad(Px, Pdy, du, db, f, k, cin, cout, dt, ws, static_cast<hipStream_t>(stream));
 }

@@ -61,7 +61,7 @@ int launch_upconv2_fwd(const void *Px, const void *u, const float *bias, void *P
                        const Geo &gc, int cin, int cout, sp_dtype_t dt, hipStream_t s);
 int launch_upconv2_dgrad(const void *Pdy, const void *u, void *Pdx, const Geo &gf, const Geo &gc, int cin,
                          int cout, sp_dtype_t dt, hipStream_t s);
-size_t upconv2_wgrad_ws_bytes(const Geo &gc, int cin, int cout);
+size_t upconv2_wgrad_ws_bytes(const Geo &gf, const Geo &gc, int cin, int cout, sp_dtype_t dt);
 int launch_upconv2_wgrad(const void *Px, const void *Pdy, float *du, float *db, const Geo &gf, const Geo &gc,
                          int cin, int cout, sp_dtype_t dt, void *ws, hipStream_t s);
 // matrix-core variants of the transposed convolution (upconv_mfma.hip); bf16, channels in multiples of 32
@@ -70,6 +70,9 @@ int launch_upconv_fwd_mfma(const void *Px, const void *u, const float *bias, voi
                            const Geo &gc, int cin, int cout, hipStream_t s);
 int launch_upconv_dgrad_mfma(const void *Pdy, const void *u, void *Pdx, const Geo &gf, const Geo &gc, int cin,
                              int cout, hipStream_t s);
+size_t upconv_wgrad_mfma_ws_bytes(const Geo &gc, int cin, int cout);
+int launch_upconv_wgrad_mfma(const void *Px, const void *Pdy, float *du, float *db, const Geo &gf, const Geo &gc,
+                             int cin, int cout, void *ws, hipStream_t s);
 int launch_add(const void *Pa, const void *Pb, void *Pout, size_t elems, sp_dtype_t dt, hipStream_t s);
 int launch_concat(const void *Pa, int ca, const void *Pb, int cb, void *Pc, size_t voxels, sp_dtype_t dt,
                   bool split, hipStream_t s);

@@ -401,7 +401,8 @@ int launch_upconv2_dgrad(const void *Pdy, const void *u, void *Pdx, const Geo &g
     return record_hip(hipGetLastError());
 }
 
-size_t upconv2_wgrad_ws_bytes(const Geo &gc, int cin, int cout) {
+size_t upconv2_wgrad_ws_bytes(const Geo &gf, const Geo &gc, int cin, int cout, sp_dtype_t dt) {
+    if (upconv_mfma_supported(gf, gc, cin, cout, dt)) return upconv_wgrad_mfma_ws_bytes(gc, cin, cout);
     int ncw; unsigned cvw;
     upconv_wgrad_plan(static_cast<unsigned>(1LL * gc.ntiles * gc.int_vox), cin, cout, &ncw, &cvw);
     int ncb; unsigned cvb;
@@ -411,6 +412,8 @@ size_t upconv2_wgrad_ws_bytes(const Geo &gc, int cin, int cout) {
 
 int launch_upconv2_wgrad(const void *Px, const void *Pdy, float *du, float *db, const Geo &gf, const Geo &gc,
                          int cin, int cout, sp_dtype_t dt, void *ws, hipStream_t s) {
+    if (upconv_mfma_supported(gf, gc, cin, cout, dt))
+        return launch_upconv_wgrad_mfma(Px, Pdy, du, db, gf, gc, cin, cout, ws, s);
     if (1LL * gf.ntiles * gf.int_vox > 0xffffff00LL) return SP_EGEOM;
     const Lay lc = make_lay(gc, cout), lf = make_lay(gf, cout);
     int ncw, ncb; unsigned cvw, cvb;

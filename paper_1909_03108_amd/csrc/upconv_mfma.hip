@@ -50,13 +50,13 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
 }
 
 struct Item { int tile, d, h, w0; };
-__device__ __forceinline__ Item decode_item(int item, const UpArgs &a) {
+__device__ __forceinline__ Item decode_item(int item, int nseg, const Geo &gc) {
     Item o;
-    o.w0 = (item % a.nseg) * SEG;
-    int t = item / a.nseg;
-    o.h = t % a.gc.th; t /= a.gc.th;
-    o.d = t % a.gc.td;
-    o.tile = t / a.gc.td;
+    o.w0 = (item % nseg) * SEG;
+    int t = item / nseg;
+    o.h = t % gc.th; t /= gc.th;
+    o.d = t % gc.td;
+    o.tile = t / gc.td;
     return o;
 }
 // padded voxel index of interior voxel (d, h, w) of a tile
@@ -98,14 +98,14 @@ __global__ __launch_bounds__(kT) void upconv_fwd_mfma_kernel(UpArgs a) {
     bf16x8 b0[NKS], b1[NKS];
     auto fetch = [&](int item, bf16x8 (&b)[NKS]) {
         if (item >= a.nitems) return;
-        const Item o = decode_item(item, a);
+        const Item o = decode_item(item, a.nseg, a.gc);
         const int w = min(o.w0 + m, a.gc.tw - 1);
         const uint16_t *px = a.in + pvox(a.gc, o.tile, o.d, o.h, w) * CIN + 8 * kh;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) b[ks] = *reinterpret_cast<const bf16x8 *>(px + 16 * ks);
     };
     auto compute = [&](int item, const bf16x8 (&b)[NKS]) {
-        const Item o = decode_item(item, a);
+        const Item o = decode_item(item, a.nseg, a.gc);
         const int w = o.w0 + m;
         const bool ok = w < a.gc.tw;
 #pragma unroll 1
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(kT) void upconv_dgrad_mfma_kernel(UpArgs a) {
 
 #pragma unroll 1
     for (int item = sub * (kT / 64) + wave; item < a.nitems; item += a.wpb * (kT / 64)) {
-        const Item o = decode_item(item, a);
+        const Item o = decode_item(item, a.nseg, a.gc);
         const int w = o.w0 + m;
         const bool ok = w < a.gc.tw;
         const int wl = ok ? w : a.gc.tw - 1;
@@ -208,6 +208,184 @@ __global__ __launch_bounds__(kT) void upconv_dgrad_mfma_kernel(UpArgs a) {
                         make_uint2(pack2(acc[g][4 * q], acc[g][4 * q + 1]), pack2(acc[g][4 * q + 2], acc[g][4 * q + 3]));
         }
     }
+}
+
+// ---- weight gradient -----------------------------------------------------------------------------------
+//   du[t][ci][co] = sum_v x[v][ci] * dy[2v + t][co],   db[co] = sum over fine voxels of dy[.][co]
+// The reduction runs over voxels while memory keeps channels contiguous, so both operands go through LDS
+// and are read back with the transposing load (4 voxels of one channel per lane and read).  Wave t of a
+// workgroup owns tap t: it stages, for every 32-voxel segment, its own copy of the x rows (NCI blocks of
+// 32 input channels) and the dy rows of its tap (one block of 32 output channels) with direct-to-LDS
+// loads into a private three-slot ring, two segments ahead, and multiplies them - the waves of a
+// workgroup never synchronise.  LDS records are voxel-major, 64 bytes (32 channels) per voxel.
+// Each workgroup writes its partial sums; a second kernel adds them in workgroup order.
+constexpr int WG_NST = 3;                     // ring slots per wave
+
+struct UpWArgs {
+    const uint16_t *x, *dy;
+    float *part_w;           // [workgroup][8][32 NCI][32]
+    float *part_b;           // [workgroup][8][32]
+    Geo gf, gc;
+    int cin, cout;
+    int nco;                 // output-channel blocks; channel group = (ci group) * nco + co block
+    int ngroups, wpg;        // channel groups, workgroups per group
+    int nseg, nitems;
+};
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// 16 bytes per lane from global memory to LDS address dst + 16 * lane (dst wave-uniform, in M0).  The wait
+// on lgkmcnt makes sure that this wave's earlier reads of the ring slot have returned before it is refilled.
+__device__ __forceinline__ void dma16_after_reads(const uint16_t *src, const char *dst) {
+    const uint32_t l = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+        (const __attribute__((address_space(3))) char *)dst));
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(src), "s"(l)
+                 : "memory");
+}
+
+// One 32x32x16 operand (32 channels x 16 voxels) from 16 voxel records at p (p includes the lane part).
+// Lane l gets channel l % 32 and voxels 8 (l/32) + {0..7}; `nvalid` voxels of the 16 are real, the others
+// are forced to zero (FULL: all are real).
+template <bool FULL>
+__device__ __forceinline__ bf16x8 tr_frag(const char *p, int lane, int nvalid) {
+    union { struct { s16x4 lo, hi; } s; u32x4 w; bf16x8 v; } u;
+    u.s.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(__attribute__((address_space(3))) char *)(p));
+    u.s.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(__attribute__((address_space(3))) char *)(p + 4 * 64));
+    if (!FULL) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int c = nvalid - (8 * (lane >> 5) + 4 * r);        // real voxels among this read's four
+            u.w[2 * r] &= c >= 2 ? 0xffffffffu : (c == 1 ? 0x0000ffffu : 0u);
+            u.w[2 * r + 1] &= c >= 4 ? 0xffffffffu : (c == 3 ? 0x0000ffffu : 0u);
+        }
+    }
+    return u.v;
+}
+
+template <int NCI, bool FULL>
+__global__ __launch_bounds__(kT) void upconv_wgrad_mfma_kernel(UpWArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    constexpr int STAGE = (NCI + 1) * 2048;          // x blocks, then the dy block: 32 voxels x 64 bytes each
+    constexpr int DM = 2 * (NCI + 1);                // staging loads per segment and wave
+    const int group = blockIdx.x % a.ngroups, sub = blockIdx.x / a.ngroups;
+    const int cg = group / a.nco, cb = group % a.nco;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int tap = __builtin_amdgcn_readfirstlane(tid >> 6);
+    char *ring = lds + tap * (WG_NST * STAGE);
+    // transposing-read address of this lane inside a 16-voxel group of records
+    const int p16 = lane & 15;
+    const int tr_off = (8 * (lane >> 5) + (p16 >> 2)) * 64 + (16 * ((lane >> 4) & 1) + 4 * (p16 & 3)) * 2;
+    const int sv = lane >> 2, sc = lane & 3;         // staging: voxel within a 16-voxel group, 16-byte chunk
+
+    f32x16 acc[NCI], accb;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        accb[i] = 0.f;
+#pragma unroll
+        for (int b = 0; b < NCI; ++b) acc[b][i] = 0.f;
+    }
+    union { uint32_t w[4]; bf16x8 v; } ones;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ones.w[i] = 0x3f803f80u;
+    const bool bias_group = cg == 0;
+
+    auto stage = [&](int item, int slot) {
+        const Item o = decode_item(item, a.nseg, a.gc);
+        char *dst = ring + slot * STAGE;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int w = min(o.w0 + 16 * q + sv, a.gc.tw - 1);
+            const uint16_t *px = a.x + pvox(a.gc, o.tile, o.d, o.h, w) * a.cin + C * cg * NCI + 8 * sc;
+#pragma unroll
+            for (int b = 0; b < NCI; ++b) dma16_after_reads(px + C * b, dst + b * 2048 + q * 1024);
+            const uint16_t *pz = a.dy + pvox(a.gf, o.tile, 2 * o.d + (tap >> 2), 2 * o.h + ((tap >> 1) & 1),
+                                             2 * w + (tap & 1)) * a.cout + C * cb + 8 * sc;
+            dma16_after_reads(pz, dst + NCI * 2048 + q * 1024);
+        }
+    };
+
+    // items sub, sub + wpg, ...; past the end the last item is staged again (its slot is never read), so
+    // that every wave always has the same number of loads in flight
+    const int first = sub, last = first + ((a.nitems - 1 - first) / a.wpg) * a.wpg;
+    stage(first, 0);
+    stage(min(first + a.wpg, last), 1);
+    int slot = 0;
+#pragma unroll 1
+    for (int item = first; item <= last; item += a.wpg) {
+        const int nxt = item + 2 * a.wpg;
+        stage(nxt <= last ? nxt : last, slot >= 1 ? slot - 1 : slot + 2);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * DM) : "memory");      // this item's loads have landed
+        const char *st = ring + slot * STAGE + tr_off;
+        const int nvalid = FULL ? 32 : a.gc.tw - (item % a.nseg) * SEG;    // real voxels of the segment
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const bf16x8 zf = tr_frag<FULL>(st + NCI * 2048 + ks * 1024, lane, nvalid - 16 * ks);
+#pragma unroll
+            for (int b = 0; b < NCI; ++b) {
+                const bf16x8 xf = tr_frag<FULL>(st + b * 2048 + ks * 1024, lane, nvalid - 16 * ks);
+                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, zf, acc[b], 0, 0, 0);
+            }
+            if (bias_group) accb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones.v, zf, accb, 0, 0, 0);
+        }
+        slot = slot == WG_NST - 1 ? 0 : slot + 1;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+    // lane l holds column co = l % 32 and rows ci = 8 (i/4) + 4 (l/32) + i % 4
+    const int wg = group * a.wpg + sub;
+    float *pw = a.part_w + (static_cast<size_t>(wg) * 8 + tap) * (NCI * C * C);
+#pragma unroll
+    for (int b = 0; b < NCI; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            pw[(C * b + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3)) * C + (lane & 31)] = acc[b][i];
+    // every row of the ones-product is the column sum; row 0 sits in register 0 of lanes 0..31
+    if (lane < C) a.part_b[(static_cast<size_t>(wg) * 8 + tap) * C + lane] = accb[0];
+}
+
+// du[t][ci][co] = sum over the workgroups of (ci, co)'s channel group, in workgroup order; db[co] likewise
+// over the workgroups of ci group 0 and the 8 taps.
+__global__ __launch_bounds__(256) void upconv_wgrad_reduce_kernel(const float *__restrict__ part_w,
+                                                                  const float *__restrict__ part_b,
+                                                                  float *__restrict__ du, float *__restrict__ db,
+                                                                  int cin, int cout, int nci, int wpg) {
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    const int nw = 8 * cin * cout;
+    const int nco = cout / C, gci = C * nci;
+    if (e < nw) {
+        const int co = e % cout, ci = (e / cout) % cin, tap = e / (cout * cin);
+        const int group = (ci / gci) * nco + co / C;
+        const float *p = part_w + ((static_cast<size_t>(group) * wpg * 8 + tap) * gci + ci % gci) * C + co % C;
+        float s = 0.f;
+        for (int k = 0; k < wpg; ++k) s += p[static_cast<size_t>(k) * 8 * gci * C];
+        du[e] = s;
+    } else if (db && e < nw + cout) {
+        const int co = e - nw;
+        const float *p = part_b + static_cast<size_t>(co / C) * wpg * 8 * C + co % C;      // ci group 0
+        float s = 0.f;
+        for (int k = 0; k < wpg * 8; ++k) s += p[k * C];
+        db[co] = s;
+    }
+}
+
+int wgrad_plan(const Geo &gc, int cin, int cout, UpWArgs *a, int *nci) {
+    *nci = cin % (2 * C) == 0 ? 2 : 1;
+    a->cin = cin; a->cout = cout;
+    a->nco = cout / C;
+    a->ngroups = (cin / (C * *nci)) * a->nco;
+    a->nseg = (gc.tw + SEG - 1) / SEG;
+    const long long items = 1LL * gc.ntiles * gc.td * gc.th * a->nseg;
+    if (items > 0x7fff0000LL) return SP_EGEOM;
+    a->nitems = static_cast<int>(items);
+    int wpg = kGroups / a->ngroups;
+    if (wpg < 1) wpg = 1;
+    if (wpg > items) wpg = static_cast<int>(items);
+    a->wpg = wpg;
+    return SP_OK;
 }
 
 int dgrad_gci(int cin, int cout) {
@@ -296,6 +474,47 @@ int launch_upconv_dgrad_mfma(const void *Pdy, const void *u, void *Pdx, const Ge
     default: return SP_EUNSUPPORTED;
     }
 #undef SP3D_DG
+}
+
+size_t upconv_wgrad_mfma_ws_bytes(const Geo &gc, int cin, int cout) {
+    UpWArgs a;
+    int nci;
+    if (wgrad_plan(gc, cin, cout, &a, &nci) != SP_OK) return 0;
+    return static_cast<size_t>(a.ngroups) * a.wpg * 8 * (nci * C * C + C) * sizeof(float);
+}
+
+int launch_upconv_wgrad_mfma(const void *Px, const void *Pdy, float *du, float *db, const Geo &gf, const Geo &gc,
+                             int cin, int cout, void *ws, hipStream_t s) {
+    UpWArgs a;
+    int nci;
+    int rc = wgrad_plan(gc, cin, cout, &a, &nci);
+    if (rc != SP_OK) return rc;
+    a.x = static_cast<const uint16_t *>(Px);
+    a.dy = static_cast<const uint16_t *>(Pdy);
+    a.gf = gf; a.gc = gc;
+    a.part_w = static_cast<float *>(ws);
+    a.part_b = a.part_w + static_cast<size_t>(a.ngroups) * a.wpg * 8 * nci * C * C;
+    const bool full = gc.tw % SEG == 0;
+    const int lds_bytes = 8 * WG_NST * (nci + 1) * 2048;
+    hipError_t e = hipSuccess;
+    const dim3 grid(a.ngroups * a.wpg), block(kT);
+#define SP3D_UW(NCI, FULL)                                                                              \
+    do {                                                                                                \
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(upconv_wgrad_mfma_kernel<NCI, FULL>),    \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);                 \
+        if (e == hipSuccess)                                                                            \
+            hipLaunchKernelGGL((upconv_wgrad_mfma_kernel<NCI, FULL>), grid, block, lds_bytes, s, a);    \
+    } while (0)
+    if (nci == 2) { if (full) SP3D_UW(2, true); else SP3D_UW(2, false); }
+    else { if (full) SP3D_UW(1, true); else SP3D_UW(1, false); }
+#undef SP3D_UW
+    if (e != hipSuccess) return record_hip(e);
+    rc = record_hip(hipGetLastError());
+    if (rc != SP_OK) return rc;
+    const int n = 8 * cin * cout + cout;
+    hipLaunchKernelGGL(upconv_wgrad_reduce_kernel, dim3((n + 255) / 256), dim3(256), 0, s, a.part_w, a.part_b, du,
+                       db, cin, cout, nci, a.wpg);
+    return record_hip(hipGetLastError());
 }
 
 }  // namespace sp3d
