@@ -114,7 +114,8 @@ size_t sp_workspace_bytes(int op, const sp_geom_t *g, int cin, int cout, sp_dtyp
         return upconv2_wgrad_ws_bytes(o, c, cin, cout, dt);
     }
     case SP_OP_POINTWISE_WGRAD:
-        return wgrad_direct_ws_bytes(o, cin, cout, 1);
+        return pointwise_small_supported(o, cin, cout, dt) ? pointwise_small_wgrad_ws_bytes(o, cin, cout)
+                                                           : wgrad_direct_ws_bytes(o, cin, cout, 1);
     default:
         return static_cast<size_t>(-1);
     }
@@ -331,6 +332,9 @@ int sp_pointwise_fwd(const void *Px, const void *p, const float *bias, void *Py,
     int rc = check_glue(Px, p, Py, g, cin, cout, dt, &o, nullptr);
     if (rc != SP_OK) return rc;
     if (flags & ~static_cast<uint32_t>(SP_FLAG_RELU)) return SP_EINVAL;
+    if (pointwise_small_supported(o, cin, cout, dt))
+        return launch_pointwise_small_fwd(Px, p, bias, Py, o, cin, cout, flags & SP_FLAG_RELU,
+                                          static_cast<hipStream_t>(stream));
     return launch_conv_direct(Px, p, bias, Py, o, cin, cout, dt, flags & SP_FLAG_RELU, false,
                               static_cast<hipStream_t>(stream), 1);
 }
@@ -340,6 +344,8 @@ int sp_pointwise_dgrad(const void *Pdy, const void *p, void *Pdx, const sp_geom_
     Geo o;
     int rc = check_glue(Pdy, p, Pdx, g, cin, cout, dt, &o, nullptr);
     if (rc != SP_OK) return rc;
+    if (pointwise_small_supported(o, cin, cout, dt))
+        return launch_pointwise_small_dgrad(Pdy, p, Pdx, o, cin, cout, static_cast<hipStream_t>(stream));
     return launch_conv_direct(Pdy, p, nullptr, Pdx, o, cout, cin, dt, false, true,
                               static_cast<hipStream_t>(stream), 1);
 }
@@ -349,8 +355,11 @@ int sp_pointwise_wgrad(const void *Px, const void *Pdy, float *dp, float *db, co
     Geo o;
     int rc = check_glue(Px, Pdy, dp, g, cin, cout, dt, &o, nullptr);
     if (rc != SP_OK) return rc;
-    const size_t need = wgrad_direct_ws_bytes(o, cin, cout, 1);
+    const bool small = pointwise_small_supported(o, cin, cout, dt);
+    const size_t need = small ? pointwise_small_wgrad_ws_bytes(o, cin, cout) : wgrad_direct_ws_bytes(o, cin, cout, 1);
     if (!ws || ws_bytes < need || !aligned16(ws)) return SP_EWORKSPACE;
+    if (small)
+        return launch_pointwise_small_wgrad(Px, Pdy, dp, db, o, cin, cout, ws, static_cast<hipStream_t>(stream));
     return launch_wgrad_direct(Px, Pdy, dp, db, o, cin, cout, dt, ws, static_cast<hipStream_t>(stream), 1);
 }
 

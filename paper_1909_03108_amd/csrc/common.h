@@ -73,6 +73,15 @@ int launch_upconv_dgrad_mfma(const void *Pdy, const void *u, void *Pdx, const Ge
 size_t upconv_wgrad_mfma_ws_bytes(const Geo &gc, int cin, int cout);
 int launch_upconv_wgrad_mfma(const void *Px, const void *Pdy, float *du, float *db, const Geo &gf, const Geo &gc,
                              int cin, int cout, void *ws, hipStream_t s);
+// 1x1x1 convolution with at most 4 output channels (segmentation head), bf16 (glue_kernels.hip)
+bool pointwise_small_supported(const Geo &g, int cin, int cout, sp_dtype_t dt);
+int launch_pointwise_small_fwd(const void *Px, const void *p, const float *bias, void *Py, const Geo &g, int cin,
+                               int cout, bool relu, hipStream_t s);
+int launch_pointwise_small_dgrad(const void *Pdy, const void *p, void *Pdx, const Geo &g, int cin, int cout,
+                                 hipStream_t s);
+size_t pointwise_small_wgrad_ws_bytes(const Geo &g, int cin, int cout);
+int launch_pointwise_small_wgrad(const void *Px, const void *Pdy, float *dp, float *db, const Geo &g, int cin,
+                                 int cout, void *ws, hipStream_t s);
 int launch_add(const void *Pa, const void *Pb, void *Pout, size_t elems, sp_dtype_t dt, hipStream_t s);
 int launch_concat(const void *Pa, int ca, const void *Pb, int cb, void *Pc, size_t voxels, sp_dtype_t dt,
                   bool split, hipStream_t s);

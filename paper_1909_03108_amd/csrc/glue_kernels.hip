@@ -314,6 +314,149 @@ __global__ __launch_bounds__(kThreads) void add_bf16x8_kernel(const uint4 *__res
     o[i] = make_uint4(r[0], r[1], r[2], r[3]);
 }
 
+// ---- 1x1x1 convolution with a few output channels (the segmentation head), bf16 ----------------------
+// These are bound by HBM traffic: every voxel record is read (or written) once with 16-byte accesses,
+// the cin x CO weights sit in LDS as floats and are read as broadcasts.  One thread per interior voxel.
+constexpr int kPwMaxCin = 256;
+
+template <int CO>
+__global__ __launch_bounds__(kThreads) void pointwise_small_fwd_kernel(const uint16_t *__restrict__ x,
+                                                                       const uint16_t *__restrict__ p,
+                                                                       const float *__restrict__ bias,
+                                                                       uint16_t *__restrict__ y, Geo g, Lay l,
+                                                                       int cin, int relu) {
+    __shared__ float w[kPwMaxCin * CO];
+    for (int i = threadIdx.x; i < cin * CO; i += kThreads) w[i] = bf16_to_f32(p[i]);
+    __syncthreads();
+    const unsigned v = blockIdx.x * kThreads + threadIdx.x;
+    if (v >= l.nvox) return;
+    const Vox o = decode(v, l);
+    const long long pv = pidx(g, o.tile, o.ld, o.lh, o.lw);
+    float acc[CO];
+#pragma unroll
+    for (int co = 0; co < CO; ++co) acc[co] = bias ? bias[co] : 0.f;
+    const uint4 *px = reinterpret_cast<const uint4 *>(x + pv * cin);
+    for (int c8 = 0; c8 < cin / 8; ++c8) {
+        const uint4 q = px[c8];
+        const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float xv = __uint_as_float((e & 1) ? (qw[e >> 1] & 0xffff0000u) : (qw[e >> 1] << 16));
+#pragma unroll
+            for (int co = 0; co < CO; ++co) acc[co] = fmaf(xv, w[(8 * c8 + e) * CO + co], acc[co]);
+        }
+    }
+#pragma unroll
+    for (int co = 0; co < CO; ++co) y[pv * CO + co] = f32_to_bf16(relu ? fmaxf(acc[co], 0.f) : acc[co]);
+}
+
+// dx[v][ci] = sum_co dy[v][co] * p[ci][co]
+template <int CO>
+__global__ __launch_bounds__(kThreads) void pointwise_small_dgrad_kernel(const uint16_t *__restrict__ dy,
+                                                                         const uint16_t *__restrict__ p,
+                                                                         uint16_t *__restrict__ dx, Geo g, Lay l,
+                                                                         int cin) {
+    __shared__ float w[kPwMaxCin * CO];
+    for (int i = threadIdx.x; i < cin * CO; i += kThreads) w[i] = bf16_to_f32(p[i]);
+    __syncthreads();
+    const unsigned v = blockIdx.x * kThreads + threadIdx.x;
+    if (v >= l.nvox) return;
+    const Vox o = decode(v, l);
+    const long long pv = pidx(g, o.tile, o.ld, o.lh, o.lw);
+    float gv[CO];
+#pragma unroll
+    for (int co = 0; co < CO; ++co) gv[co] = bf16_to_f32(dy[pv * CO + co]);
+    uint4 *px = reinterpret_cast<uint4 *>(dx + pv * cin);
+    for (int c8 = 0; c8 < cin / 8; ++c8) {
+        uint32_t r[4];
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+            float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+            for (int co = 0; co < CO; ++co) {
+                s0 = fmaf(gv[co], w[(8 * c8 + 2 * e2) * CO + co], s0);
+                s1 = fmaf(gv[co], w[(8 * c8 + 2 * e2 + 1) * CO + co], s1);
+            }
+            r[e2] = static_cast<uint32_t>(f32_to_bf16(s0)) | (static_cast<uint32_t>(f32_to_bf16(s1)) << 16);
+        }
+        px[c8] = make_uint4(r[0], r[1], r[2], r[3]);
+    }
+}
+
+// dp[ci][co] = sum_v x[v][ci] * dy[v][co], db[co] = sum_v dy[v][co]: a block walks over a chunk of voxels
+// with kThreads / (cin/8) voxel lanes x cin/8 channel groups (8 channels = one 16-byte load per thread);
+// the voxel lanes are then added in lane order and the block's partial goes to ws[chunk][cin*CO (+CO)].
+template <int CO>
+__global__ __launch_bounds__(kThreads) void pointwise_small_wgrad_kernel(const uint16_t *__restrict__ x,
+                                                                         const uint16_t *__restrict__ dy,
+                                                                         float *__restrict__ part_w,
+                                                                         float *__restrict__ part_b, Geo g, Lay l,
+                                                                         int cin, int cg_shift, unsigned chunk_vox) {
+    __shared__ float red[kThreads * (8 * CO)];
+    const int cg = threadIdx.x & ((1 << cg_shift) - 1), vl = threadIdx.x >> cg_shift;
+    const int nvl = kThreads >> cg_shift;
+    float acc[8][CO], accb[CO];
+#pragma unroll
+    for (int co = 0; co < CO; ++co) {
+        accb[co] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e][co] = 0.f;
+    }
+    const unsigned v0 = blockIdx.x * chunk_vox;
+    unsigned v1 = v0 + chunk_vox;
+    if (v1 > l.nvox) v1 = l.nvox;
+    for (unsigned v = v0 + vl; v < v1; v += nvl) {
+        const Vox o = decode(v, l);
+        const long long pv = pidx(g, o.tile, o.ld, o.lh, o.lw);
+        const uint4 q = *reinterpret_cast<const uint4 *>(x + pv * cin + 8 * cg);
+        const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
+        float gv[CO];
+#pragma unroll
+        for (int co = 0; co < CO; ++co) {
+            gv[co] = bf16_to_f32(dy[pv * CO + co]);
+            accb[co] += gv[co];
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float xv = __uint_as_float((e & 1) ? (qw[e >> 1] & 0xffff0000u) : (qw[e >> 1] << 16));
+#pragma unroll
+            for (int co = 0; co < CO; ++co) acc[e][co] = fmaf(xv, gv[co], acc[e][co]);
+        }
+    }
+    // red[vl][ci][co]
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+#pragma unroll
+        for (int co = 0; co < CO; ++co) red[(vl * cin + 8 * cg + e) * CO + co] = acc[e][co];
+    __syncthreads();
+    for (int i = threadIdx.x; i < cin * CO; i += kThreads) {
+        float s = 0.f;
+        for (int k = 0; k < nvl; ++k) s += red[k * cin * CO + i];
+        part_w[static_cast<size_t>(blockIdx.x) * cin * CO + i] = s;
+    }
+    if (part_b) {
+        __syncthreads();
+        if (cg == 0) {
+#pragma unroll
+            for (int co = 0; co < CO; ++co) red[vl * CO + co] = accb[co];
+        }
+        __syncthreads();
+        if (threadIdx.x < CO) {
+            float s = 0.f;
+            for (int k = 0; k < nvl; ++k) s += red[k * CO + threadIdx.x];
+            part_b[static_cast<size_t>(blockIdx.x) * CO + threadIdx.x] = s;
+        }
+    }
+}
+
+void pointwise_wgrad_plan(unsigned nvox, int *nchunks, unsigned *chunk_vox) {
+    unsigned cv = 4096;
+    unsigned nc = (nvox + cv - 1) / cv;
+    if (nc > 2048) { nc = 2048; cv = (nvox + nc - 1) / nc; nc = (nvox + cv - 1) / cv; }
+    *nchunks = static_cast<int>(nc);
+    *chunk_vox = cv;
+}
+
 void upconv_wgrad_plan(unsigned nvox, int cin, int cout, int *nchunks, unsigned *chunk_vox) {
     const size_t per_chunk = 8ull * cin * cout * sizeof(float);
     size_t cap = (256ull << 20) / per_chunk;
@@ -508,5 +651,64 @@ int launch_concat(const void *Pa, int ca, const void *Pb, int cb, void *Pc, size
 #undef SP3D_CAT
     return record_hip(hipGetLastError());
 }
+
+bool pointwise_small_supported(const Geo &g, int cin, int cout, sp_dtype_t dt) {
+    if (dt != SP_BF16 || cout < 1 || cout > 4 || cin % 8 != 0 || cin > kPwMaxCin) return false;
+    const int cg = cin / 8;
+    return (cg & (cg - 1)) == 0 && 1LL * g.ntiles * g.int_vox <= 0xffffff00LL;
+}
+
+#define SP3D_BY_CO(KERNEL, ...)                                                                      \
+    switch (cout) {                                                                                  \
+    case 1: hipLaunchKernelGGL(KERNEL<1>, __VA_ARGS__); break;                                       \
+    case 2: hipLaunchKernelGGL(KERNEL<2>, __VA_ARGS__); break;                                       \
+    case 3: hipLaunchKernelGGL(KERNEL<3>, __VA_ARGS__); break;                                       \
+    default: hipLaunchKernelGGL(KERNEL<4>, __VA_ARGS__); break;                                      \
+    }
+
+int launch_pointwise_small_fwd(const void *Px, const void *p, const float *bias, void *Py, const Geo &g, int cin,
+                               int cout, bool relu, hipStream_t s) {
+    const Lay l = make_lay(g, 1);
+    dim3 grid((l.nvox + kThreads - 1) / kThreads), block(kThreads);
+    SP3D_BY_CO(pointwise_small_fwd_kernel, grid, block, 0, s, static_cast<const uint16_t *>(Px),
+               static_cast<const uint16_t *>(p), bias, static_cast<uint16_t *>(Py), g, l, cin, relu ? 1 : 0)
+    return record_hip(hipGetLastError());
+}
+
+int launch_pointwise_small_dgrad(const void *Pdy, const void *p, void *Pdx, const Geo &g, int cin, int cout,
+                                 hipStream_t s) {
+    const Lay l = make_lay(g, 1);
+    dim3 grid((l.nvox + kThreads - 1) / kThreads), block(kThreads);
+    SP3D_BY_CO(pointwise_small_dgrad_kernel, grid, block, 0, s, static_cast<const uint16_t *>(Pdy),
+               static_cast<const uint16_t *>(p), static_cast<uint16_t *>(Pdx), g, l, cin)
+    return record_hip(hipGetLastError());
+}
+
+size_t pointwise_small_wgrad_ws_bytes(const Geo &g, int cin, int cout) {
+    int nc; unsigned cv;
+    pointwise_wgrad_plan(static_cast<unsigned>(1LL * g.ntiles * g.int_vox), &nc, &cv);
+    return static_cast<size_t>(nc) * (cin * cout + cout) * sizeof(float);
+}
+
+int launch_pointwise_small_wgrad(const void *Px, const void *Pdy, float *dp, float *db, const Geo &g, int cin,
+                                 int cout, void *ws, hipStream_t s) {
+    const Lay l = make_lay(g, 1);
+    int nc; unsigned cv;
+    pointwise_wgrad_plan(l.nvox, &nc, &cv);
+    float *part_w = static_cast<float *>(ws);
+    float *part_b = db ? part_w + static_cast<size_t>(nc) * cin * cout : nullptr;
+    int cg_shift = 0;
+    while ((1 << cg_shift) < cin / 8) ++cg_shift;
+    dim3 grid(nc), block(kThreads);
+    SP3D_BY_CO(pointwise_small_wgrad_kernel, grid, block, 0, s, static_cast<const uint16_t *>(Px),
+               static_cast<const uint16_t *>(Pdy), part_w, part_b, g, l, cin, cg_shift, cv)
+    int rc = record_hip(hipGetLastError());
+    if (rc != SP_OK) return rc;
+    rc = launch_reduce_partials(part_w, dp, nc, 1LL * cin * cout, s);
+    if (rc != SP_OK) return rc;
+    if (db) rc = launch_reduce_partials(part_b, db, nc, cout, s);
+    return rc;
+}
+#undef SP3D_BY_CO
 
 }  // namespace sp3d

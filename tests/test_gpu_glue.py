@@ -90,7 +90,7 @@ def test_upconv_fwd_dgrad_wgrad(n, dhw, grid, dtype, cin, cout):
 
 
 @pytest.mark.parametrize("n,dhw,grid,dtype", CASES)
-@pytest.mark.parametrize("cin,cout", [(32, 3), (7, 5)])
+@pytest.mark.parametrize("cin,cout", [(32, 3), (7, 5), (64, 4), (8, 1), (256, 2)])
 def test_pointwise_fwd_dgrad_wgrad(n, dhw, grid, dtype, cin, cout):
     g = sp3d.Geom(n, dhw, grid)
     dt, tol = DT[dtype], TOL[dtype]
