@@ -43,6 +43,19 @@ class UNet:
         self.w = weights                      # name -> device tensor
         self.msg = {}
         self.ws_cache = {}
+        self.pool = {}                        # name -> padded tensor, allocated (zeroed) once and reused
+
+    def _buf(self, name, g, c):
+        """Padded tensor owned by `name`.  It is zeroed only when first allocated: later steps overwrite the
+        interiors, and margins are either rewritten by the halo exchange before anything reads them or
+        never read (pooling, up-convolution, 1x1x1 convolution and the element-wise ops use interiors or
+        pass margins through)."""
+        key = (name, g.padded_shape, c)
+        t = self.pool.get(key)
+        if t is None:
+            t = sp3d.alloc_padded(g, c, self.dt)
+            self.pool[key] = t
+        return t
 
     # ---- small helpers -------------------------------------------------------------------------
     def _ws(self, op, g, cin, cout):
@@ -65,7 +78,7 @@ class UNet:
 
     def _conv(self, Px, name, g, cin, cout):
         """Px must hold its halos.  Returns relu(conv(Px)) as padded tiles (margins zero)."""
-        Py = sp3d.alloc_padded(g, cout, self.dt)
+        Py = self._buf(name + ".y", g, cout)
         sp3d.conv3d_fwd(Px, self.w[name], None, Py, g, cin, cout, self.dt, sp3d.SP_FLAG_RELU,
                         self._ws(sp3d.SP_OP_FWD, g, cin, cout))
         return Py
@@ -75,13 +88,13 @@ class UNet:
         """x_vol: device volume [n,d,h,w,in_ch].  Returns the logits volume; keeps what backward needs."""
         dt, ch = self.dt, self.channels
         A = {}                                   # saved activations (padded, halos exchanged where needed)
-        P = sp3d.alloc_padded(self.g[0], self.in_ch, dt)
+        P = self._buf("input", self.g[0], self.in_ch)
         sp3d.sp_partition(x_vol, P, self.g[0], self.in_ch, dt)
         prev = self.in_ch
         for i in range(self.L):
             g, c = self.g[i], ch[i]
             if i > 0:
-                Pp = sp3d.alloc_padded(g, prev, dt)
+                Pp = self._buf("pool%d" % i, g, prev)
                 sp3d.sp_maxpool2_fwd(P, Pp, self.g[i - 1], prev, dt)
                 P = Pp
             self._exchange(P, g, prev)
@@ -95,9 +108,9 @@ class UNet:
         for i in range(self.L - 2, -1, -1):
             g, c = self.g[i], ch[i]
             A["up%d.x" % i] = P
-            Pu = sp3d.alloc_padded(g, c, dt)
+            Pu = self._buf("up%d.y" % i, g, c)
             sp3d.sp_upconv2_fwd(P, self.w["up%d" % i], None, Pu, g, prev, c, dt)
-            Pc = sp3d.alloc_padded(g, 2 * c, dt)
+            Pc = self._buf("cat%d" % i, g, 2 * c)
             sp3d.sp_concat(A["enc%d.y" % i], c, Pu, c, Pc, g, dt)
             self._exchange(Pc, g, 2 * c)
             A["dec%d_a.x" % i] = Pc
@@ -108,7 +121,7 @@ class UNet:
             A["dec%d.y" % i] = P
             prev = c
         A["head.x"] = P
-        Pl = sp3d.alloc_padded(self.g[0], self.classes, dt)
+        Pl = self._buf("logits", self.g[0], self.classes)
         sp3d.sp_pointwise_fwd(P, self.w["head"], None, Pl, self.g[0], prev, self.classes, dt)
         self.A = A
         g0 = self.g[0]
@@ -127,7 +140,7 @@ class UNet:
         if not need_dx:
             return None
         self._exchange(Pdy, g, cout)
-        Pdx = sp3d.alloc_padded(g, cin, dt)
+        Pdx = self._buf(name + ".dx", g, cin)
         sp3d.conv3d_dgrad(Pdy, self.w[name], Pdx, g, cin, cout, dt, self._ws(sp3d.SP_OP_DGRAD, g, cin, cout))
         return Pdx
 
@@ -136,14 +149,14 @@ class UNet:
         dt, ch, A = self.dt, self.channels, self.A
         grads = {}
         g0 = self.g[0]
-        Pd = sp3d.alloc_padded(g0, self.classes, dt)
+        Pd = self._buf("dlogits", g0, self.classes)
         sp3d.sp_partition(dlogits_vol, Pd, g0, self.classes, dt)
         c0 = ch[0]
         dp = torch.empty((1, 1, 1, c0, self.classes), dtype=torch.float32, device="cuda")
         sp3d.sp_pointwise_wgrad(A["head.x"], Pd, dp, None, g0, c0, self.classes, dt,
                                 self._ws(sp3d.SP_OP_POINTWISE_WGRAD, g0, c0, self.classes))
         grads["head"] = dp
-        Pg = sp3d.alloc_padded(g0, c0, dt)
+        Pg = self._buf("head.dx", g0, c0)
         sp3d.sp_pointwise_dgrad(Pd, self.w["head"], Pg, g0, c0, self.classes, dt)
         skip_grad = {}
         for i in range(0, self.L - 1):
@@ -151,14 +164,14 @@ class UNet:
             up_in = ch[i + 1]
             Pg = self._conv_bwd("dec%d_b" % i, A["dec%d_b.x" % i], A["dec%d.y" % i], Pg, g, c, c, grads)
             Pg = self._conv_bwd("dec%d_a" % i, A["dec%d_a.x" % i], A["dec%d_b.x" % i], Pg, g, 2 * c, c, grads)
-            Ps, Pu = sp3d.alloc_padded(g, c, dt), sp3d.alloc_padded(g, c, dt)
+            Ps, Pu = self._buf("skip%d.d" % i, g, c), self._buf("up%d.dy" % i, g, c)
             sp3d.sp_split(Pg, Ps, c, Pu, c, g, dt)
             skip_grad[i] = Ps
             du = torch.empty((2, 2, 2, up_in, c), dtype=torch.float32, device="cuda")
             sp3d.sp_upconv2_wgrad(A["up%d.x" % i], Pu, du, None, g, up_in, c, dt,
                                   self._ws(sp3d.SP_OP_UPCONV_WGRAD, g, up_in, c))
             grads["up%d" % i] = du
-            Pg = sp3d.alloc_padded(self.g[i + 1], up_in, dt)
+            Pg = self._buf("up%d.dx" % i, self.g[i + 1], up_in)
             sp3d.sp_upconv2_dgrad(Pu, self.w["up%d" % i], Pg, g, up_in, c, dt)
         for i in range(self.L - 1, -1, -1):
             g, c = self.g[i], ch[i]
@@ -169,7 +182,7 @@ class UNet:
             Pg = self._conv_bwd("enc%d_a" % i, A["enc%d_a.x" % i], A["enc%d_b.x" % i], Pg, g, cin, c, grads,
                                 need_dx=(i > 0 or input_grad))
             if i > 0:
-                Pf = sp3d.alloc_padded(self.g[i - 1], cin, dt)
+                Pf = self._buf("pool%d.dx" % i, self.g[i - 1], cin)
                 sp3d.sp_maxpool2_bwd(A["enc%d.y" % (i - 1)], Pg, Pf, self.g[i - 1], cin, dt)
                 Pg = Pf
         dx = None

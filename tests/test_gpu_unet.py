@@ -84,7 +84,15 @@ def test_unet_stack_reduced_size():
     worst = max([rel_rms(f64(grads[k]), ref_grads[k]) for k, _ in plan] + [rel_rms(f64(dx), ref_dx)])
     print("free-running backward: worst relative rms %.3f" % worst)
     assert worst <= 0.25
-    del grads, dx
+
+    # ---- 3b. a second step on the same object reuses every buffer and must reproduce the first bit by bit
+    logits2 = net.forward(to_dev(x))
+    assert np.array_equal(f64(logits2), logits)
+    grads2, dx2 = net.backward(to_dev(dl))
+    for k, _ in plan:
+        assert torch.equal(grads2[k], grads[k]), k
+    assert torch.equal(dx2, dx)
+    del grads, dx, grads2, dx2, logits2
 
     # ---- 2. teacher-forced, operation by operation ----------------------------------------------------
     tol = 1e-2
