@@ -42,6 +42,10 @@ def parse():
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (torch copy_) so that profiler "
                          "byte counters can be scaled against a kernel of known traffic")
+    ap.add_argument("--calib-gemm", action="store_true",
+                    help="also time the vendor library's dense bf16 GEMM (torch.matmul, 8192^3, normal "
+                         "data) on this box and report it as `library_gemm_tflops`: context for what a "
+                         "matrix-core-bound kernel sustains here, not part of the step")
     return ap.parse_args()
 
 
@@ -183,6 +187,33 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
 
+    gemm_tflops = None
+    if args.calib_gemm:
+        ga = torch.randn(8192, 8192, device="cuda").bfloat16()
+        gb = torch.randn(8192, 8192, device="cuda").bfloat16()
+        for _ in range(3):
+            gc_ = ga @ gb
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            gc_ = ga @ gb
+        e1.record()
+        torch.cuda.synchronize()
+        gemm_tflops = 20 * 2.0 * 8192 ** 3 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        del ga, gb, gc_
+
+    # outside the timed step: the one-pass exchange (what a one-GPU caller would use instead of pack + unpack)
+    ex = []
+    for _ in range(10):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        sp3d.sp_halo_exchange(Px, g, c, dt, stream)
+        e1.record(stream)
+        ex.append((e0, e1))
+    torch.cuda.synchronize()
+    exchange_ms = sorted(a.elapsed_time(b) for a, b in ex)[len(ex) // 2]
+
     per = {}
     for name, e0, e1 in events:
         per.setdefault(name, []).append(e0.elapsed_time(e1))
@@ -233,6 +264,8 @@ def main():
         "paper_context": "paper reports ~5% of training time for partitioning+reshaping+halo exchange "
                          "on TPU pods (its own hardware; not a target)",
         "ms_per_launch": {k: round(v, 4) for k, v in avg_ms.items()},
+        "halo_exchange_fused_ms": round(exchange_ms, 4),
+        "library_gemm_tflops": None if gemm_tflops is None else round(gemm_tflops, 1),
         "roofline": roofline,
         "roofline_other": other,
     }

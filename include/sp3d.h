@@ -99,6 +99,11 @@ int halo_pack(const void *P, void *msg, const sp_geom_t *g, int c, sp_dtype_t dt
  * neighbour is outside the grid (zero 'same' padding at the volume border).  Writes margins
  * only; interiors are untouched.  P is updated in place.  Bit-exact. */
 int halo_unpack(void *P, const void *msg, const sp_geom_t *g, int c, sp_dtype_t dt, void *stream);
+/* halo_pack + delivery + halo_unpack in one pass for the case that all tiles live in one memory
+ * (Sec. 2, Fig. 1b with the sending and the receiving device being the same): every margin region
+ * of P is filled from the interior of the neighbour tile (zeros at the volume border), with no
+ * message buffer.  Leaves P exactly as halo_pack followed by halo_unpack would.  In place. */
+int sp_halo_exchange(void *P, const sp_geom_t *g, int c, sp_dtype_t dt, void *stream);
 
 /* ---- convolution on padded tiles (Sec. 2: "finally apply convolution"; Sec. 3: fwd + bwd) --- */
 

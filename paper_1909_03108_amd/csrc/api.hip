@@ -191,6 +191,13 @@ int halo_unpack(void *P, const void *msg, const sp_geom_t *g, int c, sp_dtype_t 
     return launch_halo_unpack(P, msg, o, c, dt, static_cast<hipStream_t>(stream));
 }
 
+int sp_halo_exchange(void *P, const sp_geom_t *g, int c, sp_dtype_t dt, void *stream) {
+    Geo o;
+    int rc = check_copy_args(P, P, g, c, dt, &o);
+    if (rc != SP_OK) return rc;
+    return launch_halo_exchange(P, o, c, dt, static_cast<hipStream_t>(stream));
+}
+
 static int check_conv_args(const void *a, const void *b, const void *c, const sp_geom_t *g, int cin,
                            int cout, sp_dtype_t dt, Geo *o) {
     if (!a || !b || !c) return SP_EINVAL;

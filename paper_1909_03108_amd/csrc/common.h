@@ -43,6 +43,7 @@ int launch_partition(const void *vol, void *P, const Geo &g, int c, sp_dtype_t d
                      hipStream_t s);
 int launch_halo_pack(const void *P, void *msg, const Geo &g, int c, sp_dtype_t dt, hipStream_t s);
 int launch_halo_unpack(void *P, const void *msg, const Geo &g, int c, sp_dtype_t dt, hipStream_t s);
+int launch_halo_exchange(void *P, const Geo &g, int c, sp_dtype_t dt, hipStream_t s);
 int launch_relu_bwd(const void *dy, const void *y, void *dz, size_t elems, sp_dtype_t dt,
                     hipStream_t s);
 

@@ -115,9 +115,15 @@ struct HaloArgs {
     FastDiv bpt, gw, gh, gd;
 };
 
-template <typename T, bool UNPACK>
-__global__ __launch_bounds__(kThreads) void halo_kernel(const T *__restrict__ src, T *__restrict__ dst,
-                                                        HaloArgs a) {
+// MODE: kPack = tile interiors -> messages; kUnpack = neighbours' messages -> margins (zeros where the
+// neighbour is outside the grid); kExchange = both at once when all tiles share one memory: every margin
+// region is read straight from the neighbour's interior (src and dst are then the same tensor; the
+// reads touch interiors only and the writes margins only).
+enum HaloMode { kPack = 0, kUnpack = 1, kExchange = 2 };
+
+template <typename T, int MODE>
+__global__ __launch_bounds__(kThreads) void halo_kernel(const T *src, T *dst, HaloArgs a) {
+    constexpr bool UNPACK = MODE != kPack;
     const Geo &g = a.g;
     const unsigned tile = fdiv(blockIdx.x, a.bpt), rem = fmod_(blockIdx.x, tile, a.bpt);
     int ri = 0;
@@ -136,10 +142,11 @@ __global__ __launch_bounds__(kThreads) void halo_kernel(const T *__restrict__ sr
         const int nc = static_cast<int>(tc) + r.delta[2];
         if (na >= 0 && na < g.gd && nb >= 0 && nb < g.gh && nc >= 0 && nc < g.gw) {
             const long long ntile = ((1LL * tn * g.gd + na) * g.gh + nb) * g.gw + nc;
-            nb_msg = ntile * g.msg_vox + a.t.r[r.opposite].off;
+            nb_msg = MODE == kExchange ? ntile : ntile * g.msg_vox + a.t.r[r.opposite].off;
         }
     }
     const int *org = UNPACK ? r.recv : r.send;
+    const int *nsend = a.t.r[r.opposite].send;     // kExchange: the box the neighbour would have packed
     const long long msg0 = UNPACK ? nb_msg : tile * g.msg_vox + r.off;   // message region of this block
     T v[kVpt];
     long long mo[kVpt], po[kVpt];   // vector offsets in the message and in the padded tensor
@@ -154,7 +161,11 @@ __global__ __launch_bounds__(kThreads) void halo_kernel(const T *__restrict__ sr
         const unsigned lh = fdiv(q, a.ew[ri]), lw = fmod_(q, lh, a.ew[ri]);
         const long long pvox = tile * g.tile_vox + (1LL * (org[0] + ld) * g.ph + org[1] + lh) * g.pw + org[2] + lw;
         po[k] = pvox * a.vpv.d + cv;
-        mo[k] = (msg0 + vox) * a.vpv.d + cv;
+        if (MODE == kExchange)
+            mo[k] = (nb_msg * g.tile_vox + (1LL * (nsend[0] + ld) * g.ph + nsend[1] + lh) * g.pw + nsend[2] + lw) *
+                        a.vpv.d + cv;
+        else
+            mo[k] = (msg0 + vox) * a.vpv.d + cv;
         v[k] = zero_vec<T>();
         if (ok[k] && (!UNPACK || nb_msg >= 0)) v[k] = ld_stream(src + (UNPACK ? mo[k] : po[k]));
     }
@@ -164,7 +175,7 @@ __global__ __launch_bounds__(kThreads) void halo_kernel(const T *__restrict__ sr
 }
 
 template <int VB>
-int halo_dispatch(const void *src, void *dst, HaloArgs &a, bool unpack, hipStream_t s) {
+int halo_dispatch(const void *src, void *dst, HaloArgs &a, int mode, hipStream_t s) {
     using T = typename VecT<VB>::type;
     int acc = 0;
     for (int i = 0; i < 26; ++i) {
@@ -183,11 +194,14 @@ int halo_dispatch(const void *src, void *dst, HaloArgs &a, bool unpack, hipStrea
     const long long blocks = 1LL * acc * a.g.ntiles;
     if (blocks > 0x7fffffffLL) return SP_EGEOM;
     dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
-    if (unpack)
-        hipLaunchKernelGGL((halo_kernel<T, true>), grid, block, 0, s, static_cast<const T *>(src),
+    if (mode == kUnpack)
+        hipLaunchKernelGGL((halo_kernel<T, kUnpack>), grid, block, 0, s, static_cast<const T *>(src),
+                           static_cast<T *>(dst), a);
+    else if (mode == kExchange)
+        hipLaunchKernelGGL((halo_kernel<T, kExchange>), grid, block, 0, s, static_cast<const T *>(src),
                            static_cast<T *>(dst), a);
     else
-        hipLaunchKernelGGL((halo_kernel<T, false>), grid, block, 0, s, static_cast<const T *>(src),
+        hipLaunchKernelGGL((halo_kernel<T, kPack>), grid, block, 0, s, static_cast<const T *>(src),
                            static_cast<T *>(dst), a);
     return record_hip(hipGetLastError());
 }
@@ -260,7 +274,7 @@ int launch_partition(const void *vol, void *P, const Geo &g, int c, sp_dtype_t d
     }
 }
 
-static int halo_launch(const void *src, void *dst, const Geo &g, int c, sp_dtype_t dt, bool unpack,
+static int halo_launch(const void *src, void *dst, const Geo &g, int c, sp_dtype_t dt, int mode,
                        hipStream_t s) {
     const size_t rec = static_cast<size_t>(c) * elem_size(dt);
     const int vb = vec_bytes(rec);
@@ -269,19 +283,23 @@ static int halo_launch(const void *src, void *dst, const Geo &g, int c, sp_dtype
     make_regions(g, &a.t);
     a.vpv = make_fastdiv(static_cast<uint32_t>(rec / vb));
     switch (vb) {
-    case 16: return halo_dispatch<16>(src, dst, a, unpack, s);
-    case 8: return halo_dispatch<8>(src, dst, a, unpack, s);
-    case 4: return halo_dispatch<4>(src, dst, a, unpack, s);
-    default: return halo_dispatch<2>(src, dst, a, unpack, s);
+    case 16: return halo_dispatch<16>(src, dst, a, mode, s);
+    case 8: return halo_dispatch<8>(src, dst, a, mode, s);
+    case 4: return halo_dispatch<4>(src, dst, a, mode, s);
+    default: return halo_dispatch<2>(src, dst, a, mode, s);
     }
 }
 
 int launch_halo_pack(const void *P, void *msg, const Geo &g, int c, sp_dtype_t dt, hipStream_t s) {
-    return halo_launch(P, msg, g, c, dt, false, s);
+    return halo_launch(P, msg, g, c, dt, kPack, s);
 }
 
 int launch_halo_unpack(void *P, const void *msg, const Geo &g, int c, sp_dtype_t dt, hipStream_t s) {
-    return halo_launch(msg, P, g, c, dt, true, s);
+    return halo_launch(msg, P, g, c, dt, kUnpack, s);
+}
+
+int launch_halo_exchange(void *P, const Geo &g, int c, sp_dtype_t dt, hipStream_t s) {
+    return halo_launch(P, P, g, c, dt, kExchange, s);
 }
 
 int launch_relu_bwd(const void *dy, const void *y, void *dz, size_t elems, sp_dtype_t dt,

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsp3d.so"
 
 EXPORTS = ["sp_padded_elems", "sp_msg_elems", "sp_workspace_bytes", "sp_check_geom", "sp_strerror",
            "sp_last_hip_error", "sp_partition", "sp_unpartition", "halo_pack", "halo_unpack",
+           "sp_halo_exchange",
            "conv3d_fwd", "conv3d_dgrad", "conv3d_wgrad", "sp_relu_bwd",
            "sp_maxpool2_fwd", "sp_maxpool2_bwd", "sp_upconv2_fwd", "sp_upconv2_dgrad", "sp_upconv2_wgrad",
            "sp_pointwise_fwd", "sp_pointwise_dgrad", "sp_pointwise_wgrad", "sp_concat", "sp_split", "sp_add"]
@@ -66,6 +67,7 @@ def lib():
         for name in ("sp_partition", "sp_unpartition", "halo_pack", "halo_unpack"):
             f = getattr(L, name)
             f.argtypes, f.restype = [P, P, G, I, I, P], I
+        L.sp_halo_exchange.argtypes, L.sp_halo_exchange.restype = [P, G, I, I, P], I
         L.conv3d_fwd.argtypes, L.conv3d_fwd.restype = [P, P, P, P, G, I, I, I, U, P, Z, P], I
         L.conv3d_dgrad.argtypes, L.conv3d_dgrad.restype = [P, P, P, G, I, I, I, P, Z, P], I
         L.conv3d_wgrad.argtypes, L.conv3d_wgrad.restype = [P, P, P, P, G, I, I, I, P, Z, P], I
@@ -145,6 +147,10 @@ def halo_pack(P, msg, g, c, dt, stream=None):
 
 def halo_unpack(P, msg, g, c, dt, stream=None):
     _check(lib().halo_unpack(_ptr(P), _ptr(msg), ctypes.byref(g), c, dt, _stream(stream)), "halo_unpack")
+
+
+def sp_halo_exchange(P, g, c, dt, stream=None):
+    _check(lib().sp_halo_exchange(_ptr(P), ctypes.byref(g), c, dt, _stream(stream)), "sp_halo_exchange")
 
 
 def conv3d_fwd(Px, w, bias, Py, g, cin, cout, dt, flags=0, ws=None, stream=None):

@@ -8,7 +8,7 @@ Architecture (the paper's Sec. 3 network in the shape the workload list fixes): 
 channels `channels`, two 3x3x3 conv + ReLU per level, 2x2x2 max-pool between levels; the last level
 is the bottleneck; decoder levels mirror the encoder: 2x2x2 stride-2 transposed conv halving the
 channels, concat (skip, up), two 3x3x3 conv + ReLU; a final 1x1x1 conv to `classes`.  Biases are
-zero and not passed.  Every 3x3x3 conv input is halo-exchanged (pack + unpack) first.
+zero and not passed.  Every 3x3x3 conv input is halo-exchanged first (sp_halo_exchange: pack, delivery and unpack in one pass).
 """
 import numpy as np
 import torch
@@ -41,7 +41,6 @@ class UNet:
         for g in self.g:
             assert sp3d.sp_check_geom(g) == sp3d.SP_OK
         self.w = weights                      # name -> device tensor
-        self.msg = {}
         self.ws_cache = {}
         self.pool = {}                        # name -> padded tensor, allocated (zeroed) once and reused
 
@@ -68,13 +67,8 @@ class UNet:
         return cur
 
     def _exchange(self, P, g, c):
-        need = sp3d.sp_msg_elems(g, c)
-        m = self.msg.get("buf")
-        if m is None or m.numel() < need:
-            m = torch.empty((need,), dtype=sp3d.torch_dtype(self.dt), device="cuda")
-            self.msg["buf"] = m
-        sp3d.halo_pack(P, m, g, c, self.dt)
-        sp3d.halo_unpack(P, m, g, c, self.dt)
+        """All tiles share this GPU's memory, so margins are filled straight from the neighbours' interiors."""
+        sp3d.sp_halo_exchange(P, g, c, self.dt)
 
     def _conv(self, Px, name, g, cin, cout):
         """Px must hold its halos.  Returns relu(conv(Px)) as padded tiles (margins zero)."""

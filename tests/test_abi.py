@@ -71,6 +71,9 @@ def test_calls_reject_bad_arguments_before_launching():
     assert L.sp_unpartition(FAKE, FAKE * 16, gp, 0, sp3d.SP_BF16, None) == sp3d.SP_EINVAL
     assert L.halo_pack(FAKE, FAKE * 16, gp, 4, 7, None) == sp3d.SP_EUNSUPPORTED
     assert L.halo_unpack(FAKE, None, gp, 4, sp3d.SP_BF16, None) == sp3d.SP_EINVAL
+    assert L.sp_halo_exchange(None, gp, 4, sp3d.SP_BF16, None) == sp3d.SP_EINVAL
+    assert L.sp_halo_exchange(FAKE, bp, 4, sp3d.SP_BF16, None) == sp3d.SP_EGEOM
+    assert L.sp_halo_exchange(FAKE + 4, gp, 4, sp3d.SP_BF16, None) == sp3d.SP_EINVAL
     assert L.conv3d_fwd(FAKE, FAKE * 2, None, FAKE * 16, bp, 4, 4, sp3d.SP_F32, 0, None, 0, None) == sp3d.SP_EGEOM
     assert L.conv3d_fwd(FAKE, FAKE * 2, None, FAKE * 16, gp, 4, 4, sp3d.SP_F32, 2, None, 0, None) == sp3d.SP_EINVAL
     assert L.conv3d_fwd(FAKE, FAKE * 2, None, FAKE, gp, 4, 4, sp3d.SP_F32, 0, None, 0, None) == sp3d.SP_EINVAL

@@ -65,6 +65,13 @@ def test_partition_pack_unpack_unpartition_bit_exact(n, dhw, grid, c, dtype):
     assert np.array_equal(tiling.halo_unpack(ref_P, ref_M), ref_full)
     assert guards_intact(pbuf, fill)
 
+    # the one-pass exchange on a freshly partitioned tensor gives the same padded tiles, margins included
+    qbuf, Q = guard_alloc(g.padded_shape + (c,), tdt, fill)
+    sp3d.sp_partition(to_dev(V), Q, g, c, dt)
+    sp3d.sp_halo_exchange(Q, g, c, dt)
+    assert np.array_equal(bits(Q), ref_full)
+    assert guards_intact(qbuf, fill)
+
     # unpartition
     vbuf, V2 = guard_alloc((n,) + dhw + (c,), tdt, fill)
     sp3d.sp_unpartition(P, V2, g, c, dt)
