@@ -150,7 +150,31 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
     out[e] = s;
 }
 
+// Same sum for few outputs and many partials (one serial chain per output would be latency-bound): a block
+// per output; thread t adds the partials t, t + 256, ... in order, then the 256 thread sums are combined
+// by a fixed binary tree.  The grouping depends only on nparts, so the result is still reproducible.
+__global__ __launch_bounds__(256) void reduce_partials_wide_kernel(const float *__restrict__ part,
+                                                                   float *__restrict__ out, int nparts,
+                                                                   long long n) {
+    __shared__ float red[256];
+    const long long e = blockIdx.x;
+    float s = 0.f;
+    for (int p = threadIdx.x; p < nparts; p += 256) s += part[1LL * p * n + e];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if (threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[e] = red[0];
+}
+
 int launch_reduce_partials(const float *part, float *out, int nparts, long long n, hipStream_t s) {
+    if (nparts >= 512 && n <= 16384) {
+        hipLaunchKernelGGL(reduce_partials_wide_kernel, dim3(static_cast<unsigned>(n)), dim3(256), 0, s, part, out,
+                           nparts, n);
+        return record_hip(hipGetLastError());
+    }
     dim3 grid(static_cast<unsigned>((n + 255) / 256)), block(256);
     hipLaunchKernelGGL(reduce_partials_kernel, grid, block, 0, s, part, out, nparts, n);
     return record_hip(hipGetLastError());

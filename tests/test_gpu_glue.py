@@ -114,6 +114,28 @@ def test_pointwise_fwd_dgrad_wgrad(n, dhw, grid, dtype, cin, cout):
     assert rel_err(f64(dp), ref_dp) <= tol and rel_err(f64(db), ref_db) <= tol
 
 
+def test_pointwise_wgrad_many_partials():
+    """Head-sized 1x1x1 weight gradient on a volume large enough for hundreds of per-block partial sums
+    (the second-stage reduction then takes its wide, tree-shaped path); run twice: same bits."""
+    n, dhw, grid, cin, cout = 1, (96, 128, 192), (2, 4, 1), 32, 3
+    g = sp3d.Geom(n, dhw, grid)
+    dt, tol = DT["bf16"], TOL["bf16"]
+    x = draw("bf16", (n,) + dhw + (cin,), 16)
+    dy = draw("bf16", (n,) + dhw + (cout,), 17)
+    Px, Pdy = padded(g, x, cin, dt), padded(g, dy, cout, dt)
+    ws = sp3d.alloc_ws(sp3d.sp_workspace_bytes(sp3d.SP_OP_POINTWISE_WGRAD, g, cin, cout, dt))
+    assert ws.numel() >= 512 * (cin * cout + cout) * 4
+    out = []
+    for _ in range(2):
+        dp = torch.empty((cin, cout), dtype=torch.float32, device="cuda")
+        db = torch.empty((cout,), dtype=torch.float32, device="cuda")
+        sp3d.sp_pointwise_wgrad(Px, Pdy, dp, db, g, cin, cout, dt, ws)
+        out.append((dp, db))
+    ref_dp, ref_db = U.pointwise_wgrad(widen(x), widen(dy))
+    assert rel_err(f64(out[0][0]), ref_dp) <= tol and rel_err(f64(out[0][1]), ref_db) <= tol
+    assert torch.equal(out[0][0], out[1][0]) and torch.equal(out[0][1], out[1][1])
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_concat_and_split_bit_exact(dtype):
     g = sp3d.Geom(1, (4, 6, 8), (2, 3, 1))
