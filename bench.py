@@ -8,9 +8,11 @@ One "step" is one pass of the whole path over one synthetic 512^3 x 32-channel b
     partition dy -> halo pack -> halo unpack -> conv3d_dgrad -> unpartition dx
     conv3d_wgrad (dw, db)
 
-Inputs are resident in HBM before the timed region.  Prints ONE JSON line (see the design doc for the
-meaning of every field).  `value` is 3 conv passes' FLOPs divided by the whole step time, i.e. it
-is charged for partitioning and halo exchange too.
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.  `value` is 3 conv passes'
+FLOPs divided by the whole step time, i.e. it is charged for partitioning and halo exchange too;
+`roofline` rates the dominant kernel (algorithmic FLOPs of one launch / its HIP-event time) against the
+dense bf16 peak, `cpu_baseline` is the fp64 oracle timed on the host cores on a corner box of the same
+tensors.
 """
 import argparse
 import json
@@ -24,9 +26,10 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
-# HBM traffic per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (see profiles/ and the design doc for the scaling against a plain copy kernel); None = not measured.
-MEASURED_TRAFFIC_BYTES = {512: 18.61e9}      # profiles/bench_512_hbm_traffic.md
+# HBM traffic per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script with --calib-copy (each counter scaled by what it reads for the plain 1 GiB copy of known size:
+# FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); None = not measured at that size.
+MEASURED_TRAFFIC_BYTES = {512: 18.61e9}
 
 
 def parse():
