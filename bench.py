@@ -267,6 +267,12 @@ def main():
         "paper_context": "paper reports ~5% of training time for partitioning+reshaping+halo exchange "
                          "on TPU pods (its own hardware; not a target)",
         "ms_per_launch": {k: round(v, 4) for k, v in avg_ms.items()},
+        "conv_stack": {"what": "conv3d_fwd + conv3d_dgrad + conv3d_wgrad launches alone",
+                       "tflops": round(3 * flop_pass / ((avg_ms["conv3d_fwd"] + avg_ms["conv3d_dgrad"]
+                                                          + avg_ms["conv3d_wgrad"]) * 1e-3) / 1e12, 1),
+                       "frac_of_bf16_peak": round(3 * flop_pass / ((avg_ms["conv3d_fwd"] + avg_ms["conv3d_dgrad"]
+                                                                   + avg_ms["conv3d_wgrad"]) * 1e-3) / 1e12
+                                                  / PEAK_BF16_TFLOPS, 4)},
         "halo_exchange_fused_ms": round(exchange_ms, 4),
         "library_gemm_tflops": None if gemm_tflops is None else round(gemm_tflops, 1),
         "roofline": roofline,

@@ -553,33 +553,44 @@ void plan(const Geo &g, int cin, int cout, WgradArgs *a) {
     a->ngroups = a->gpp * npairs;
 }
 
-// dw[tap][ci][co] = sum over the workgroups of pair (ci/32, co/32), in workgroup order, of their partial
-// [tap][ci%32][co%32]; db[co] likewise from the pairs of input chunk 0.
+// dw[tap][ci][co] = sum over the workgroups of pair (ci/32, co/32) of their partial [tap][ci%32][co%32];
+// db[co] likewise from the pairs of input chunk 0.  Eight neighbouring lanes share one output: lane s adds
+// the contiguous run of workgroups [s*gpp/8, (s+1)*gpp/8) in order, and the eight run sums are combined by
+// a fixed three-level tree, so the grouping depends only on gpp and the result is reproducible.  (One
+// serial chain of gpp dependent loads per output was latency-bound: 72 us for 28 MB of partials.)
+constexpr int RSPLIT = 8;
 __global__ __launch_bounds__(256) void reduce_wgrad_kernel(const float *__restrict__ part_w,
                                                            const float *__restrict__ part_b,
                                                            float *__restrict__ dw, float *__restrict__ db,
                                                            int cin, int cout, int gpp) {
-    const int e = blockIdx.x * 256 + threadIdx.x;
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    const int e = t / RSPLIT, sub = t % RSPLIT;
     const int nw_ = 27 * cin * cout;
+    const int k0 = static_cast<int>(1LL * sub * gpp / RSPLIT), k1 = static_cast<int>(1LL * (sub + 1) * gpp / RSPLIT);
+    float s = 0.f;
     if (e < nw_) {
         const int co = e % cout, ci = (e / cout) % cin, tap = e / (cout * cin);
         const int pair = (ci / C) * (cout / C) + co / C;
         const float *p = part_w + (static_cast<size_t>(pair) * gpp * 27 + tap) * C * C + (ci % C) * C + co % C;
-        float s = 0.f;
-        int k = 0;
-        for (; k + 4 <= gpp; k += 4) {          // loads issued together, additions kept in order
+        int k = k0;
+        for (; k + 4 <= k1; k += 4) {          // loads issued together, additions kept in order
             const float p0 = p[static_cast<size_t>(k) * 27 * C * C], p1 = p[static_cast<size_t>(k + 1) * 27 * C * C];
             const float p2 = p[static_cast<size_t>(k + 2) * 27 * C * C], p3 = p[static_cast<size_t>(k + 3) * 27 * C * C];
             s = (((s + p0) + p1) + p2) + p3;
         }
-        for (; k < gpp; ++k) s += p[static_cast<size_t>(k) * 27 * C * C];
-        dw[e] = s;
-    } else if (db && e < nw_ + cout) {
+        for (; k < k1; ++k) s += p[static_cast<size_t>(k) * 27 * C * C];
+    } else if (e < nw_ + cout) {
         const int co = e - nw_;
         const float *p = part_b + static_cast<size_t>(co / C) * gpp * C + co % C;     // pairs (0, co/32)
-        float s = 0.f;
-        for (int k = 0; k < gpp; ++k) s += p[k * C];
-        db[co] = s;
+        for (int k = k0; k < k1; ++k) s += p[k * C];
+    }
+    // lanes 8j .. 8j+7 hold the run sums of one output (every lane of the wave takes part in the shuffles)
+    s += __shfl_xor(s, 1);
+    s += __shfl_xor(s, 2);
+    s += __shfl_xor(s, 4);
+    if (sub == 0) {
+        if (e < nw_) dw[e] = s;
+        else if (db && e < nw_ + cout) db[e - nw_] = s;
     }
 }
 
@@ -621,9 +632,9 @@ int launch_wgrad_mfma(const void *Px, const void *Pdz, float *dw, float *db, con
         hipLaunchKernelGGL(wgrad_mfma_kernel, dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
     int rc = record_hip(hipGetLastError());
     if (rc != SP_OK) return rc;
-    const int n = 27 * cin * cout + cout;
-    hipLaunchKernelGGL(reduce_wgrad_kernel, dim3((n + 255) / 256), dim3(256), 0, s, a.part_w, a.part_b, dw, db,
-                       cin, cout, a.gpp);
+    const long long n = (27LL * cin * cout + cout) * RSPLIT;
+    hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, s, a.part_w,
+                       a.part_b, dw, db, cin, cout, a.gpp);
     return record_hip(hipGetLastError());
 }
 
