@@ -366,6 +366,347 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
 #undef SP3D_STEP_END
 }
 
+// =============================================================================================
+// Two input chunks per launch (layers with Cin a multiple of 64).  With one chunk per launch every extra
+// chunk costs a round trip of the fp32 partial sums through HBM (8 bytes per output value), which makes
+// wide layers bandwidth-bound.  Here a workgroup contracts 64 input channels at once and adds the two
+// halves on chip: the patch is 4 rows x 32 columns, waves 0, 1 take input chunk 0 and waves 2, 3 chunk 1
+// of the pair, each for one row group of 2 rows, with the same register-resident weights, D march and
+// fragment reuse as above.  When an output plane is complete, the chunk-1 wave writes its 2 x 16
+// accumulators to a small LDS buffer (during the next step, between its MFMAs); one step later, after the
+// step barrier, the chunk-0 wave of the same rows adds them to its own, converts and stores.  A plane
+// therefore lives in an accumulator slot for five steps (three contributing, one being handed over, one
+// being stored), hence five slots.  Layers with more than one pair still go through fp32 partial sums, but
+// half as often.
+namespace wide {
+
+constexpr int NRG = 2;                      // row groups
+constexpr int PH = RH * NRG;                // 4 patch rows
+constexpr int LROWS = PH + 2;               // 6
+constexpr int PLANE_VOX = LROWS * LCOLS;    // 204 voxels of one chunk's plane
+constexpr int CP_LOADS = (PLANE_VOX + 63) / 64;      // 4 wave loads per 16-byte chunk plane
+constexpr int LOADS = 2 * CP_LOADS;         // a wave fills two of the four chunk planes of its input chunk
+constexpr int NSLOT = 5;
+constexpr int CH_STRIDE = (PLANE_VOX + 2) * 16;      // 3296
+constexpr int CHUNK_BYTES = 4 * CH_STRIDE;           // 13184: one input chunk's plane
+constexpr int PLANE_BYTES = 2 * CHUNK_BYTES;         // both chunks of the pair
+constexpr int RING_BYTES = NBUF * PLANE_BYTES;       // 105472
+constexpr int RED_BYTES = NRG * RH * 4 * 64 * 16;    // 16384: one plane's hand-over (float4 per lane and unit)
+constexpr int LDS_BYTES = RING_BYTES + 2 * RED_BYTES;   // 138240
+static_assert(LDS_BYTES <= 160 * 1024, "LDS of one CU");
+
+// direct-to-LDS load as in wgrad_mfma.hip: written as assembly so that the compiler neither tracks it nor
+// drains it before unrelated LDS accesses; the kernel counts the loads itself (s_waitcnt vmcnt)
+__device__ __forceinline__ void dma16(const uint16_t *src, const char *dst) {
+    const uint32_t l = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+        (const __attribute__((address_space(3))) char *)dst));
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(l) : "memory");
+}
+
+template <bool HAS_BIAS>
+struct Ctx {
+    const uint16_t *tin0;       // first padded input plane of the D chunk, at this wave's input chunk
+    size_t plane_elems;
+    int nplanes;
+    int goff[LOADS];            // source offsets of the staging loads (elements)
+    bool tail_lane;             // lane has a voxel in the last (partial) load of a chunk plane
+    char *lds_stage;            // first chunk plane this wave fills, ring slot 0
+    char *red;                  // hand-over buffer of this wave's row group (buffer 0), lane part included
+    uint16_t *obase;
+    float *pbase;
+    size_t oplane, orow;
+    bool okrow[RH];
+    float bv[HAS_BIAS ? 16 : 1];
+};
+
+// staging load j (0..7) of plane `dplane`: chunk plane j / 4 of this wave's two, voxels 64 (j % 4) ..
+template <bool HAS_BIAS>
+__device__ __forceinline__ void stage(const Ctx<HAS_BIAS> &c, int dplane, int j) {
+    const uint16_t *p = c.tin0 + min(dplane, c.nplanes - 1) * c.plane_elems;
+    const char *dst = c.lds_stage + (dplane % NBUF) * PLANE_BYTES + (j / CP_LOADS) * CH_STRIDE + (j % CP_LOADS) * 1024;
+    // only the last load of a chunk plane is partial (204 = 3 x 64 + 12 voxels); j is a compile-time constant
+    // at every call site, so the other loads carry no predicate
+    if (j % CP_LOADS != CP_LOADS - 1 || c.tail_lane) dma16(p + c.goff[j], dst);
+}
+
+template <bool FULL, bool HAS_BIAS>
+__device__ __forceinline__ float4 load_partial(const Ctx<HAS_BIAS> &c, int d, int h, int q) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (FULL || c.okrow[h]) v = *reinterpret_cast<const float4 *>(c.pbase + d * c.oplane + h * c.orow + 8 * q);
+    return v;
+}
+
+// chunk-0 wave: finish 4 channels of row h of plane d: own sum + the partner's (from LDS) + earlier pairs'
+// partial sums (pin, fetched at the start of the step), then store the new partial (fp32) or ReLU /
+// convert / store bf16
+template <int MODE, bool RELU, bool FULL, bool HAS_BIAS>
+__device__ __forceinline__ void finish_unit(const Ctx<HAS_BIAS> &c, int d, const f32x16 (&s)[RH], const char *red,
+                                            const float4 (&pin)[RH][4], int h, int q) {
+    const float4 o = *reinterpret_cast<const float4 *>(red + (h * 4 + q) * 1024);
+    float v0 = s[h][4 * q] + o.x, v1 = s[h][4 * q + 1] + o.y, v2 = s[h][4 * q + 2] + o.z, v3 = s[h][4 * q + 3] + o.w;
+    if (MODE == kMiddle || MODE == kLast) {
+        v0 += pin[h][q].x; v1 += pin[h][q].y; v2 += pin[h][q].z; v3 += pin[h][q].w;
+    }
+    const size_t at = d * c.oplane + h * c.orow + 8 * q;
+    if (MODE == kFirst || MODE == kMiddle) {
+        if (FULL || c.okrow[h]) *reinterpret_cast<float4 *>(c.pbase + at) = make_float4(v0, v1, v2, v3);
+        return;
+    }
+    if (RELU) {
+        v0 = v0 < 0.f ? 0.f : v0; v1 = v1 < 0.f ? 0.f : v1;
+        v2 = v2 < 0.f ? 0.f : v2; v3 = v3 < 0.f ? 0.f : v3;
+    }
+    const uint2 pk = make_uint2(pack2(v0, v1), pack2(v2, v3));
+    if (FULL || c.okrow[h]) *reinterpret_cast<uint2 *>(c.obase + at) = pk;
+}
+
+// chunk-1 wave: hand 4 channels of row h of a complete plane over to the chunk-0 wave
+__device__ __forceinline__ void give_unit(const f32x16 (&s)[RH], char *red, int h, int q) {
+    *reinterpret_cast<float4 *>(red + (h * 4 + q) * 1024) =
+        make_float4(s[h][4 * q], s[h][4 * q + 1], s[h][4 * q + 2], s[h][4 * q + 3]);
+}
+
+// One staged input plane Dp.  P = Dp mod 5: output plane Dp - kd accumulates in slot (P - kd) mod 5.
+// ROLE 1 (chunk 1): GIVE = plane Dp - 3 (slot (P + 2) mod 5) goes to the hand-over buffer Dp & 1 and its
+// slot is cleared.  ROLE 0 (chunk 0): FIN = plane Dp - 4 (slot (P + 1) mod 5) is finished from the buffer
+// written in the previous step, (Dp - 1) & 1, and its slot returns to the bias.
+template <int P, int ROLE, bool GIVE, bool FIN, int MODE, bool RELU, bool FULL, bool HAS_BIAS>
+__device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const char *lbase,
+                                           const bf16x8 (&wf)[NFRAG], f32x16 (&acc)[NSLOT][RH]) {
+    constexpr int NR = RH + 2;
+    constexpr int SIDE = ROLE == 1 ? (P + 2) % NSLOT : (P + 1) % NSLOT;     // slot of the side work
+    constexpr int NEXT = (P + 1) % NSLOT;      // slot of output plane Dp + 1: must be clean when this step ends
+    constexpr bool ACTIVE = ROLE == 1 ? GIVE : FIN;
+    bf16x8 b[2][NR];
+    char *red_w = c.red + (Dp & 1) * RED_BYTES;
+    const char *red_r = c.red + ((Dp - 1) & 1) * RED_BYTES;
+    float4 pin[RH][4];
+    if (ROLE == 0 && FIN && (MODE == kMiddle || MODE == kLast)) {
+#pragma unroll
+        for (int h = 0; h < RH; ++h)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) pin[h][q] = load_partial<FULL>(c, Dp - 4, h, q);
+    }
+#pragma unroll
+    for (int r = 0; r < NR; ++r) b[0][r] = *reinterpret_cast<const bf16x8 *>(lbase + (r * LCOLS) * 16);
+#pragma unroll
+    for (int gi = 0; gi < NG; ++gi) {
+        const int kw = gi >> 1, half = gi & 1;
+        if (gi + 1 < NG) {
+            const int kw2 = (gi + 1) >> 1, half2 = (gi + 1) & 1;
+#pragma unroll
+            for (int r = 0; r < NR; ++r)
+                b[(gi + 1) & 1][r] = *reinterpret_cast<const bf16x8 *>(
+                    lbase + half2 * 2 * CH_STRIDE + (r * LCOLS + kw2) * 16);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // eight staging loads over six groups
+        stage(c, Dp + DIST, gi);
+        if (gi < 2) stage(c, Dp + DIST, NG + gi);
+        if (gi < 4) {
+            if (ACTIVE) {
+                if (ROLE == 1) {
+                    give_unit(acc[SIDE], red_w, 0, gi);
+                    give_unit(acc[SIDE], red_w, 1, gi);
+                } else {
+                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SIDE], red_r, pin, 0, gi);
+                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SIDE], red_r, pin, 1, gi);
+                }
+            }
+        } else {
+            // the slot of the next output plane starts from the bias (chunk 0) or zero (chunk 1); in the first
+            // steps it holds sums for planes that do not exist.  A handed-over slot is cleared as well.
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                acc[NEXT][gi - 4][i] = (ROLE == 0 && HAS_BIAS) ? c.bv[HAS_BIAS ? i : 0] : 0.f;
+                if (ROLE == 1 && GIVE) acc[SIDE][gi - 4][i] = 0.f;
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh) {
+                const int h = r - kh;
+                if (h < 0 || h >= RH) continue;
+#pragma unroll
+                for (int kd = 0; kd < 3; ++kd) {
+                    const int slot = (P - kd + NSLOT) % NSLOT;
+                    acc[slot][h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        wf[((kd * 3 + kh) * 3 + kw) * 2 + half], b[gi & 1][r], acc[slot][h], 0, 0, 0);
+                }
+            }
+#pragma unroll
+        for (int i = 0; i < 3 * (RH + 1) * 2; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x006, 3, 0);   // up to three VALU / SALU
+            if (i % 6 == 2) __builtin_amdgcn_sched_group_barrier(0x060, 1, 0);   // a vector memory op
+        }
+    }
+}
+
+// The two steps after the last input plane: only the side work is left.  Dp = nplanes: chunk 1 hands over
+// the last output plane (Dp - 3 = dn - 1), chunk 0 finishes plane Dp - 4; Dp = nplanes + 1: chunk 0 finishes
+// the last plane.  Same slot arithmetic as plane_step, so every accumulator index stays a constant.
+template <int P, int ROLE, bool GIVE, bool FIN, int MODE, bool RELU, bool FULL, bool HAS_BIAS>
+__device__ __forceinline__ void drain_step(const Ctx<HAS_BIAS> &c, int Dp, f32x16 (&acc)[NSLOT][RH]) {
+    constexpr int SIDE = ROLE == 1 ? (P + 2) % NSLOT : (P + 1) % NSLOT;
+    if (ROLE == 1) {
+        if (GIVE && Dp == c.nplanes) {
+            char *red_w = c.red + (Dp & 1) * RED_BYTES;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                give_unit(acc[SIDE], red_w, 0, q);
+                give_unit(acc[SIDE], red_w, 1, q);
+            }
+        }
+    } else if (FIN) {
+        const char *red_r = c.red + ((Dp - 1) & 1) * RED_BYTES;
+        float4 pin[RH][4];
+        if (MODE == kMiddle || MODE == kLast) {
+#pragma unroll
+            for (int h = 0; h < RH; ++h)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) pin[h][q] = load_partial<FULL>(c, Dp - 4, h, q);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SIDE], red_r, pin, 0, q);
+            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SIDE], red_r, pin, 1, q);
+        }
+    }
+}
+
+template <int ROLE, int MODE, bool HAS_BIAS, bool RELU>
+__device__ __forceinline__ void run(const ConvArgs &a, char *lds, int tile, int d0, int h0, int w0, int dn, int cj,
+                                    int rg) {
+    const Geo &g = a.g;
+    const int lane = threadIdx.x & 63;
+    const int col = lane & 31, hi = lane >> 5;
+
+    bf16x8 wf[NFRAG];
+    {
+        const uint4 *wp = a.wpack + static_cast<size_t>(ROLE) * a.nco * NFRAG * 64;     // chunk ROLE of the pair
+#pragma unroll
+        for (int f = 0; f < NFRAG; ++f) {
+            const uint4 q = wp[(cj * NFRAG + f) * 64 + lane];
+            wf[f] = *reinterpret_cast<const bf16x8 *>(&q);
+        }
+    }
+
+    Ctx<HAS_BIAS> c;
+    c.plane_elems = static_cast<size_t>(g.ph) * g.pw * a.in_cs;
+    c.tin0 = a.in + static_cast<size_t>(tile) * g.tile_vox * a.in_cs + d0 * c.plane_elems + a.in_co + C * ROLE;
+    c.nplanes = dn + 2;
+    // this wave fills chunk planes 2 rg and 2 rg + 1 (channels 16 rg .. 16 rg + 15) of its input chunk
+#pragma unroll
+    for (int j = 0; j < LOADS; ++j) {
+        const int v = 64 * (j % CP_LOADS) + lane;
+        const int row = min(h0 + v / LCOLS, g.ph - 1), colv = min(w0 + v % LCOLS, g.pw - 1);
+        c.goff[j] = (row * g.pw + colv) * a.in_cs + (2 * rg + j / CP_LOADS) * 8;      // clamped: always addressable
+    }
+    c.tail_lane = 64 * (CP_LOADS - 1) + lane < PLANE_VOX;
+    c.lds_stage = lds + ROLE * CHUNK_BYTES + 2 * rg * CH_STRIDE;
+    c.red = lds + RING_BYTES + rg * (RH * 4 * 1024) + lane * 16;
+    c.orow = static_cast<size_t>(g.pw) * a.out_cs;
+    c.oplane = static_cast<size_t>(g.ph) * c.orow;
+    const size_t opos = static_cast<size_t>(tile) * g.tile_vox * a.out_cs +
+                        ((static_cast<size_t>(d0 + 1) * g.ph + h0 + rg * RH + 1) * g.pw + w0 + col + 1) * a.out_cs +
+                        C * cj + 4 * hi;
+    c.obase = a.out + opos;
+    c.pbase = a.part + opos;
+#pragma unroll
+    for (int h = 0; h < RH; ++h) c.okrow[h] = h0 + rg * RH + h < g.th && w0 + col < g.tw;
+    if (HAS_BIAS) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) c.bv[HAS_BIAS ? i : 0] = a.bias[C * cj + 8 * (i >> 2) + 4 * hi + (i & 3)];
+    }
+    // the bias is folded into the chunk-0 accumulators; chunk-1 accumulators start from zero
+    f32x16 acc[NSLOT][RH];
+#pragma unroll
+    for (int s = 0; s < NSLOT; ++s)
+#pragma unroll
+        for (int h = 0; h < RH; ++h)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[s][h][i] = (ROLE == 0 && HAS_BIAS) ? c.bv[HAS_BIAS ? i : 0] : 0.f;
+
+    const char *lbase = lds + ROLE * CHUNK_BYTES + hi * CH_STRIDE + (rg * RH * LCOLS + col) * 16;
+    const int nplanes = c.nplanes;
+
+#pragma unroll
+    for (int i = 0; i < DIST; ++i)
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) stage(c, i, j);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+
+    // End of a step: plane Dp + 1 has landed when at most the loads of planes Dp + 2, Dp + 3 are in flight
+    // (loads complete in order; stores share the counter and only make the wait stricter), and this wave's
+    // hand-over writes have reached LDS.
+#define SP3D_STEP_END()                                                                        \
+    do {                                                                                       \
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((DIST - 1) * LOADS) : "memory");   \
+        __builtin_amdgcn_s_barrier();                                                          \
+    } while (0)
+
+    auto march = [&](auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        plane_step<0, ROLE, false, false, MODE, RELU, FULL>(c, 0, lbase, wf, acc);
+        SP3D_STEP_END();
+        plane_step<1, ROLE, false, false, MODE, RELU, FULL>(c, 1, lbase + PLANE_BYTES, wf, acc);
+        SP3D_STEP_END();
+        plane_step<2, ROLE, false, false, MODE, RELU, FULL>(c, 2, lbase + 2 * PLANE_BYTES, wf, acc);
+        SP3D_STEP_END();
+        // Steps 3, 4, ... with slot phase Dp mod 5 as a compile-time constant (the ring slot Dp mod 4 is a
+        // run-time offset: a period of 20 steps would be needed to make both constants).  The march runs two
+        // steps past the last input plane; those only hand over / finish what is left.
+#define SP3D_STEP(DP, PHASE, GIVE_EN, FIN_EN)                                                              \
+    if ((DP) < nplanes) {                                                                                  \
+        plane_step<PHASE, ROLE, GIVE_EN, FIN_EN, MODE, RELU, FULL>(c, (DP), lbase + ((DP) % NBUF) * PLANE_BYTES, \
+                                                                   wf, acc);                              \
+        SP3D_STEP_END();                                                                                   \
+    } else if ((DP) < nplanes + 2) {                                                                       \
+        drain_step<PHASE, ROLE, GIVE_EN, FIN_EN, MODE, RELU, FULL>(c, (DP), acc);                          \
+        SP3D_STEP_END();                                                                                   \
+    }
+        SP3D_STEP(3, 3, true, false)
+        for (int D = 4; D < nplanes + 2; D += NSLOT) {
+            SP3D_STEP(D, 4, true, true)
+            SP3D_STEP(D + 1, 0, true, true)
+            SP3D_STEP(D + 2, 1, true, true)
+            SP3D_STEP(D + 3, 2, true, true)
+            SP3D_STEP(D + 4, 3, true, true)
+        }
+#undef SP3D_STEP
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // clamped staging loads of the last steps
+    };
+    if (h0 + PH <= g.th && w0 + PW <= g.tw) march(std::true_type{});
+    else march(std::false_type{});
+#undef SP3D_STEP_END
+}
+
+template <int MODE, bool HAS_BIAS, bool RELU>
+__global__ __launch_bounds__(kThreads, 1) void conv_mfma_pair_kernel(ConvArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const Geo &g = a.g;
+    const int per_xcd = gridDim.x >> 3;
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= a.nblocks) return;
+    int t = logical;
+    const int cj = t % a.nco; t /= a.nco;
+    const int pw_i = t % a.nw; t /= a.nw;
+    const int ph_i = t % a.nh; t /= a.nh;
+    const int pd_i = t % a.nd; t /= a.nd;
+    const int tile = t;
+    const int d0 = pd_i * a.dchunk, h0 = ph_i * PH, w0 = pw_i * PW;
+    const int dn = min(a.dchunk, g.td - d0);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // two copies of the march, one per role, so that each is straight-line code for the scheduler
+    if (wave < 2) run<0, MODE, HAS_BIAS, RELU>(a, lds, tile, d0, h0, w0, dn, cj, wave & 1);
+    else run<1, MODE, HAS_BIAS, RELU>(a, lds, tile, d0, h0, w0, dn, cj, wave & 1);
+}
+
+}  // namespace wide
+
 }  // namespace
 
 bool conv_mfma_supported(const Geo &g, int ki, int ko, sp_dtype_t dt) {
@@ -402,7 +743,10 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
     a.in_cs = ki;
     a.out_cs = ko;
     a.nco = nco;
-    a.nh = (g.th + PH - 1) / PH;
+    // input channels in multiples of 64: two chunks per launch, summed on chip (4-row patches)
+    const bool pairs = ki % (2 * C) == 0;
+    const int ph = pairs ? wide::PH : PH;
+    a.nh = (g.th + ph - 1) / ph;
     a.nw = (g.tw + PW - 1) / PW;
     // D chunk: whole tile depth unless that leaves the chip short of workgroups
     long long base = 1LL * g.ntiles * a.nh * a.nw * nco;
@@ -426,21 +770,38 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
          {conv_mfma_kernel<kMiddle, false, false>, conv_mfma_kernel<kMiddle, false, false>}},
         {{conv_mfma_kernel<kLast, false, false>, conv_mfma_kernel<kLast, false, true>},
          {conv_mfma_kernel<kLast, false, false>, conv_mfma_kernel<kLast, false, true>}}};
+    static const Kern kern2[4][2][2] = {
+        {{wide::conv_mfma_pair_kernel<kSingle, false, false>, wide::conv_mfma_pair_kernel<kSingle, false, true>},
+         {wide::conv_mfma_pair_kernel<kSingle, true, false>, wide::conv_mfma_pair_kernel<kSingle, true, true>}},
+        {{wide::conv_mfma_pair_kernel<kFirst, false, false>, wide::conv_mfma_pair_kernel<kFirst, false, false>},
+         {wide::conv_mfma_pair_kernel<kFirst, true, false>, wide::conv_mfma_pair_kernel<kFirst, true, false>}},
+        {{wide::conv_mfma_pair_kernel<kMiddle, false, false>, wide::conv_mfma_pair_kernel<kMiddle, false, false>},
+         {wide::conv_mfma_pair_kernel<kMiddle, false, false>, wide::conv_mfma_pair_kernel<kMiddle, false, false>}},
+        {{wide::conv_mfma_pair_kernel<kLast, false, false>, wide::conv_mfma_pair_kernel<kLast, false, true>},
+         {wide::conv_mfma_pair_kernel<kLast, false, false>, wide::conv_mfma_pair_kernel<kLast, false, true>}}};
     // more than 64 KB of dynamic LDS has to be requested explicitly
     static const hipError_t attr = [] {
         for (int i = 0; i < 16; ++i) {
-            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern[i >> 2][(i >> 1) & 1][i & 1]),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern[i >> 2][(i >> 1) & 1][i & 1]),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+            if (e != hipSuccess) return e;
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern2[i >> 2][(i >> 1) & 1][i & 1]),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, wide::LDS_BYTES);
             if (e != hipSuccess) return e;
         }
         return hipSuccess;
     }();
     if (attr != hipSuccess) return record_hip(attr);
-    for (int ci = 0; ci < nci; ++ci) {
-        const int mode = nci == 1 ? kSingle : (ci == 0 ? kFirst : (ci == nci - 1 ? kLast : kMiddle));
-        a.in_co = C * ci;
-        a.wpack = static_cast<const uint4 *>(ws) + static_cast<size_t>(ci) * nco * NFRAG * 64;
-        hipLaunchKernelGGL(kern[mode][bias ? 1 : 0][relu ? 1 : 0], dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
+    const int nsteps = pairs ? nci / 2 : nci;          // launches: input chunks, or pairs of them
+    for (int ci = 0; ci < nsteps; ++ci) {
+        const int mode = nsteps == 1 ? kSingle : (ci == 0 ? kFirst : (ci == nsteps - 1 ? kLast : kMiddle));
+        a.in_co = (pairs ? 2 * C : C) * ci;
+        a.wpack = static_cast<const uint4 *>(ws) + static_cast<size_t>(pairs ? 2 * ci : ci) * nco * NFRAG * 64;
+        if (pairs)
+            hipLaunchKernelGGL(kern2[mode][bias ? 1 : 0][relu ? 1 : 0], dim3(grid), dim3(kThreads), wide::LDS_BYTES,
+                               s, a);
+        else
+            hipLaunchKernelGGL(kern[mode][bias ? 1 : 0][relu ? 1 : 0], dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
         rc = record_hip(hipGetLastError());
         if (rc != SP_OK) return rc;
     }

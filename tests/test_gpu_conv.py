@@ -82,6 +82,12 @@ SMALL = [
     (1, (4, 8, 16), (1, 2, 2), 64, 32, "bf16"),
     (1, (4, 8, 16), (1, 2, 2), 32, 64, "bf16"),
     (1, (5, 3, 7), (1, 1, 1), 16, 48, "bf16"),
+    # input channels in multiples of 64: two chunks per launch, summed on chip (4 x 32 patches)
+    (1, (16, 8, 64), (1, 2, 1), 64, 64, "bf16"),      # whole patches, 16 planes: every slot phase
+    (1, (6, 8, 32), (6, 1, 1), 64, 32, "bf16"),       # one output plane per tile
+    (1, (4, 12, 40), (2, 1, 1), 128, 64, "bf16"),     # two pairs (first / last), two planes, ragged
+    (1, (3, 4, 32), (1, 1, 1), 192, 32, "bf16"),      # three pairs (first / middle / last), three planes
+    (1, (7, 5, 33), (1, 1, 1), 64, 32, "bf16"),       # seven planes, ragged rows and columns
 ]
 
 
