@@ -39,9 +39,11 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--size", type=int, default=512, help="volume edge (512 = headline workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="c4", choices=["c4", "c5"],
+    ap.add_argument("--workload", default="c4", choices=["c4", "c5", "paper512"],
                     help="c4 = headline single-layer workload (default); c5 = the whole U-Net convolution "
-                         "stack of the workload list (256^3, channels 32/64/128/256), forward + backward")
+                         "stack of the workload list (256^3, channels 32/64/128/256), forward + backward; "
+                         "paper512 = the network the paper trains at 512^3 (six blocks of four convolutions, "
+                         "32 ... 1024 filters), forward + backward, all 16 tiles in this GPU's HBM")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (torch copy_) so that profiler "
                          "byte counters can be scaled against a kernel of known traffic")
@@ -59,10 +61,12 @@ def bench_unet(args):
     from paper_1909_03108_amd import sp3d, synth, unet
 
     torch.cuda.set_device(0)
-    S = 256 if args.size == 512 else args.size
-    channels, in_ch, classes = (32, 64, 128, 256), 1, 3
+    paper = args.workload == "paper512"
+    S = args.size if (paper or args.size != 512) else 256
+    channels, in_ch, classes = ((32, 64, 128, 256, 512, 1024) if paper else (32, 64, 128, 256)), 1, 3
+    convs = 4 if paper else 2
     n, dhw, grid = 1, (S, S, S), (4, 4, 1)
-    plan = unet.layer_plan(channels, in_ch, classes)
+    plan = unet.layer_plan(channels, in_ch, classes, convs)
 
     def dev(a):
         return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
@@ -71,7 +75,7 @@ def bench_unet(args):
     w = {name: dev(synth.weights(shape[3], shape[4], synth.seed_for(5, synth.T_WEIGHT0 + k), "bf16",
                                  taps=shape[:3])) for k, (name, shape) in enumerate(plan)}
     dl = dev(synth.normal_volume((n,) + dhw + (classes,), synth.seed_for(5, synth.T_UPSTREAM), "bf16"))
-    net = unet.UNet(n, dhw, grid, w, channels, in_ch, classes)
+    net = unet.UNet(n, dhw, grid, w, channels, in_ch, classes, convs=convs)
 
     def step():
         net.forward(x)
@@ -97,12 +101,16 @@ def bench_unet(args):
         per = 2.0 * shape[3] * shape[4] * lvl_vox * (taps if taps != 8 else 1)   # up-conv: 1 tap per output voxel
         flop += 3 * per
     flop -= 2.0 * 27 * in_ch * channels[0] * vox                    # no image gradient
+    name = ("paper512_unet_%d^3: six blocks of four 3x3x3 convolutions, 32/64/128/256/512/1024 filters"
+            if paper else "c5_unet_%d^3: channels 32/64/128/256") % S
     print(json.dumps({
         "metric": "U-Net conv stack fwd+bwd TFLOP/s (bf16), secondary workload", "value": round(flop / ms / 1e9, 2),
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "c5_unet_%d^3: channels 32/64/128/256, grid 4x4x1, halo 1, forward + backward "
-                               "(weight and data gradients, no image gradient)" % S}}))
+        "config": {"workload": name + ", grid 4x4x1, halo 1, forward + backward (weight and data gradients, "
+                                      "no image gradient)",
+                   "tflop_per_step": round(flop / 1e12, 2),
+                   "hbm_allocated_gb": round(torch.cuda.max_memory_allocated() / 1e9, 1)}}))
 
 
 def main():
@@ -111,7 +119,7 @@ def main():
         print("bench.py: this build runs on one GPU only (all tiles of the grid live in one HBM); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
-    if args.workload == "c5":
+    if args.workload in ("c5", "paper512"):
         return bench_unet(args)
 
     import numpy as np

@@ -1,9 +1,9 @@
 """fp64 oracle of the U-Net convolution stack on the unpartitioned volume (test infrastructure only).
 
 Composes the direct-convolution oracle and the glue oracle in the order of the paper's network
-(Sec. 3, first paragraph) as fixed by the workload list: per level two 3x3x3 conv + ReLU, 2x2x2
-max-pool between levels, decoder = transposed conv, concat (skip, up), two conv + ReLU, final 1x1x1
-conv.  Biases are zero.  All arithmetic is fp64.  With `store=None` activations stay fp64 throughout;
+(Sec. 3, first paragraph) as fixed by the workload list: per level `convs` 3x3x3 conv + ReLU (two in
+the workload list, four in the paper's own blocks), 2x2x2 max-pool between levels, decoder = transposed
+conv, concat (skip, up), `convs` conv + ReLU, final 1x1x1 conv.  Biases are zero.  All arithmetic is fp64.  With `store=None` activations stay fp64 throughout;
 with `store=round_bf16` every tensor that the path keeps in memory (each layer output, each
 propagated gradient) is rounded to the bf16 storage type first, so that the decisions the path takes
 on stored values -- the ReLU mask and the max-pool argmax -- are taken on the same kind of value
@@ -21,7 +21,10 @@ def round_bf16(a):
     return r.view(np.float32).astype(np.float64)
 
 
-def forward(x, w, channels, keep=None, store=None):
+LETTERS = "abcdefgh"
+
+
+def forward(x, w, channels, keep=None, store=None, convs=2):
     """x [N,D,H,W,Cin] fp64; w: name -> fp64 weights.  Returns logits; fills `keep` with activations."""
     L = len(channels)
     A = {} if keep is None else keep
@@ -30,26 +33,26 @@ def forward(x, w, channels, keep=None, store=None):
     for i in range(L):
         if i > 0:
             h = U.maxpool2_fwd(h)
-        A["enc%d_a.x" % i] = h
-        h = q(conv3d.conv3d_fwd(h, w["enc%d_a" % i], relu=True))
-        A["enc%d_b.x" % i] = h
-        h = q(conv3d.conv3d_fwd(h, w["enc%d_b" % i], relu=True))
+        for k in range(convs):
+            name = "enc%d_%s" % (i, LETTERS[k])
+            A[name + ".x"] = h
+            h = q(conv3d.conv3d_fwd(h, w[name], relu=True))
         A["enc%d.y" % i] = h
     for i in range(L - 2, -1, -1):
         A["up%d.x" % i] = h
         up = q(U.upconv2_fwd(h, w["up%d" % i]))
         h = U.concat(A["enc%d.y" % i], up)
-        A["dec%d_a.x" % i] = h
-        h = q(conv3d.conv3d_fwd(h, w["dec%d_a" % i], relu=True))
-        A["dec%d_b.x" % i] = h
-        h = q(conv3d.conv3d_fwd(h, w["dec%d_b" % i], relu=True))
+        for k in range(convs):
+            name = "dec%d_%s" % (i, LETTERS[k])
+            A[name + ".x"] = h
+            h = q(conv3d.conv3d_fwd(h, w[name], relu=True))
         A["dec%d.y" % i] = h
     A["head.x"] = h
     p = w["head"]
     return q(U.pointwise_fwd(h, p.reshape(p.shape[-2], p.shape[-1])))
 
 
-def backward(dlogits, w, channels, A, store=None, trace=None):
+def backward(dlogits, w, channels, A, store=None, trace=None, convs=2):
     """Gradients of <logits, dlogits> with respect to every weight tensor and the input.
     `trace`, if given, receives the stored tensors of the backward pass by name
     ("<layer>.dy" incoming gradient, "<layer>.dx" outgoing gradient, "pool<i>.dy", "skip<i>")."""
@@ -71,11 +74,18 @@ def backward(dlogits, w, channels, A, store=None, trace=None):
         T[name + ".dx"] = dx
         return dx
 
+    def block_bwd(block, g):
+        """the `convs` layers of a block, last to first; layer k's output is layer k + 1's input"""
+        for k in range(convs - 1, -1, -1):
+            name = "%s_%s" % (block, LETTERS[k])
+            y = A[block + ".y"] if k == convs - 1 else A["%s_%s.x" % (block, LETTERS[k + 1])]
+            g = conv_bwd(name, A[name + ".x"], y, g)
+        return g
+
     skip = {}
     for i in range(0, L - 1):
         c = channels[i]
-        g = conv_bwd("dec%d_b" % i, A["dec%d_b.x" % i], A["dec%d.y" % i], g)
-        g = conv_bwd("dec%d_a" % i, A["dec%d_a.x" % i], A["dec%d_b.x" % i], g)
+        g = block_bwd("dec%d" % i, g)
         skip[i], gu = U.split(g, c)
         T["skip%d" % i], T["up%d.dy" % i] = skip[i], gu
         grads["up%d" % i], _ = U.upconv2_wgrad(A["up%d.x" % i], gu)
@@ -85,8 +95,7 @@ def backward(dlogits, w, channels, A, store=None, trace=None):
         if i in skip:
             T["add%d.a" % i] = g
             g = q(g + skip[i])
-        g = conv_bwd("enc%d_b" % i, A["enc%d_b.x" % i], A["enc%d.y" % i], g)
-        g = conv_bwd("enc%d_a" % i, A["enc%d_a.x" % i], A["enc%d_b.x" % i], g)
+        g = block_bwd("enc%d" % i, g)
         if i > 0:
             T["pool%d.dy" % i] = g
             g = U.maxpool2_bwd(A["enc%d.y" % (i - 1)], g)

@@ -718,11 +718,13 @@ static size_t pack_bytes(int ki, int ko) {
     return static_cast<size_t>(ki / C) * (ko / C) * NFRAG * 64 * 16;
 }
 
-// workspace: packed weight fragments, then (layers with several input chunks) fp32 partial sums laid
-// out like the output tensor
+// workspace: packed weight fragments, then (layers that need more than one launch: more than one input
+// chunk, or more than one pair of chunks when Cin is a multiple of 64) fp32 partial sums laid out like the
+// output tensor
 size_t conv_mfma_ws_bytes(const Geo &g, int ki, int ko) {
     size_t n = pack_bytes(ki, ko);
-    if (ki > C) n += static_cast<size_t>(g.ntiles) * g.tile_vox * ko * sizeof(float);
+    const int launches = ki % (2 * C) == 0 ? ki / (2 * C) : ki / C;
+    if (launches > 1) n += static_cast<size_t>(g.ntiles) * g.tile_vox * ko * sizeof(float);
     return n;
 }
 

@@ -5,9 +5,10 @@ operation -- partition, halo exchange, the convolutions, pooling, up-convolution
 element-wise masks and adds -- runs in the HIP kernels of libsp3d.
 
 Architecture (the paper's Sec. 3 network in the shape the workload list fixes): encoder levels with
-channels `channels`, two 3x3x3 conv + ReLU per level, 2x2x2 max-pool between levels; the last level
-is the bottleneck; decoder levels mirror the encoder: 2x2x2 stride-2 transposed conv halving the
-channels, concat (skip, up), two 3x3x3 conv + ReLU; a final 1x1x1 conv to `classes`.  Biases are
+channels `channels`, `convs` 3x3x3 conv + ReLU per level (two in the workload list, four in the paper's
+own blocks), 2x2x2 max-pool between levels; the last level is the bottleneck; decoder levels mirror the
+encoder: 2x2x2 stride-2 transposed conv halving the channels, concat (skip, up), `convs` 3x3x3 conv +
+ReLU; a final 1x1x1 conv to `classes`.  Biases are
 zero and not passed.  Every 3x3x3 conv input is halo-exchanged first (sp_halo_exchange: pack, delivery and unpack in one pass).
 """
 import numpy as np
@@ -16,17 +17,22 @@ import torch
 from . import sp3d
 
 
-def layer_plan(channels=(32, 64, 128, 256), in_ch=1, classes=3):
+LETTERS = "abcdefgh"
+
+
+def layer_plan(channels=(32, 64, 128, 256), in_ch=1, classes=3, convs=2):
     """Names and shapes of all weight tensors, in forward order."""
     plan = []
     prev = in_ch
     for i, c in enumerate(channels):
-        plan += [("enc%d_a" % i, (3, 3, 3, prev, c)), ("enc%d_b" % i, (3, 3, 3, c, c))]
+        for k in range(convs):
+            plan.append(("enc%d_%s" % (i, LETTERS[k]), (3, 3, 3, prev if k == 0 else c, c)))
         prev = c
     for i in range(len(channels) - 2, -1, -1):
         c = channels[i]
-        plan += [("up%d" % i, (2, 2, 2, prev, c)), ("dec%d_a" % i, (3, 3, 3, 2 * c, c)),
-                 ("dec%d_b" % i, (3, 3, 3, c, c))]
+        plan.append(("up%d" % i, (2, 2, 2, prev, c)))
+        for k in range(convs):
+            plan.append(("dec%d_%s" % (i, LETTERS[k]), (3, 3, 3, 2 * c if k == 0 else c, c)))
         prev = c
     plan.append(("head", (1, 1, 1, prev, classes)))
     return plan
@@ -34,8 +40,10 @@ def layer_plan(channels=(32, 64, 128, 256), in_ch=1, classes=3):
 
 class UNet:
     def __init__(self, n, dhw, grid, weights, channels=(32, 64, 128, 256), in_ch=1, classes=3,
-                 dt=sp3d.SP_BF16):
+                 dt=sp3d.SP_BF16, convs=2):
         self.channels, self.in_ch, self.classes, self.dt = tuple(channels), in_ch, classes, dt
+        self.convs = convs
+        self.free = {}                        # (padded shape, channels) -> released gradient buffers
         self.L = len(channels)
         self.g = [sp3d.Geom(n, tuple(e >> i for e in dhw), grid) for i in range(self.L)]
         for g in self.g:
@@ -77,6 +85,37 @@ class UNet:
                         self._ws(sp3d.SP_OP_FWD, g, cin, cout))
         return Py
 
+    def _block_fwd(self, block, P, g, cin, c, A):
+        """`convs` conv + ReLU layers; saves every layer input (with halos) and the block output in A."""
+        for k in range(self.convs):
+            name = "%s_%s" % (block, LETTERS[k])
+            self._exchange(P, g, cin if k == 0 else c)
+            A[name + ".x"] = P
+            P = self._conv(P, name, g, cin if k == 0 else c, c)
+        A[block + ".y"] = P
+        return P
+
+    def _block_bwd(self, block, Pg, g, cin, c, grads, need_dx=True):
+        """backward of a block, last layer first; layer k's output is layer k + 1's input"""
+        A = self.A
+        for k in range(self.convs - 1, -1, -1):
+            name = "%s_%s" % (block, LETTERS[k])
+            Py = A[block + ".y"] if k == self.convs - 1 else A["%s_%s.x" % (block, LETTERS[k + 1])]
+            Pg = self._conv_bwd(name, A[name + ".x"], Py, Pg, g, cin if k == 0 else c, c, grads,
+                                need_dx=(need_dx or k > 0))
+        return Pg
+
+    # gradient buffers are short-lived: they come from a free list keyed by shape and go back to it as
+    # soon as their consumer has run, so the backward pass needs a few of the largest tensors, not one per
+    # layer
+    def _tmp(self, g, c):
+        key = (g.padded_shape, c)
+        lst = self.free.setdefault(key, [])
+        return lst.pop() if lst else sp3d.alloc_padded(g, c, self.dt)
+
+    def _release(self, t, g, c):
+        self.free.setdefault((g.padded_shape, c), []).append(t)
+
     # ---- forward ----------------------------------------------------------------------------------
     def forward(self, x_vol):
         """x_vol: device volume [n,d,h,w,in_ch].  Returns the logits volume; keeps what backward needs."""
@@ -91,13 +130,7 @@ class UNet:
                 Pp = self._buf("pool%d" % i, g, prev)
                 sp3d.sp_maxpool2_fwd(P, Pp, self.g[i - 1], prev, dt)
                 P = Pp
-            self._exchange(P, g, prev)
-            A["enc%d_a.x" % i] = P
-            P = self._conv(P, "enc%d_a" % i, g, prev, c)
-            self._exchange(P, g, c)
-            A["enc%d_b.x" % i] = P
-            P = self._conv(P, "enc%d_b" % i, g, c, c)
-            A["enc%d.y" % i] = P                 # level output: pool input / skip / ReLU mask
+            P = self._block_fwd("enc%d" % i, P, g, prev, c, A)   # level output: pool input / skip / ReLU mask
             prev = c
         for i in range(self.L - 2, -1, -1):
             g, c = self.g[i], ch[i]
@@ -106,13 +139,7 @@ class UNet:
             sp3d.sp_upconv2_fwd(P, self.w["up%d" % i], None, Pu, g, prev, c, dt)
             Pc = self._buf("cat%d" % i, g, 2 * c)
             sp3d.sp_concat(A["enc%d.y" % i], c, Pu, c, Pc, g, dt)
-            self._exchange(Pc, g, 2 * c)
-            A["dec%d_a.x" % i] = Pc
-            P = self._conv(Pc, "dec%d_a" % i, g, 2 * c, c)
-            self._exchange(P, g, c)
-            A["dec%d_b.x" % i] = P
-            P = self._conv(P, "dec%d_b" % i, g, c, c)
-            A["dec%d.y" % i] = P
+            P = self._block_fwd("dec%d" % i, Pc, g, 2 * c, c, A)
             prev = c
         A["head.x"] = P
         Pl = self._buf("logits", self.g[0], self.classes)
@@ -131,11 +158,12 @@ class UNet:
         dw = torch.empty((3, 3, 3, cin, cout), dtype=torch.float32, device="cuda")
         sp3d.conv3d_wgrad(Px, Pdy, dw, None, g, cin, cout, dt, self._ws(sp3d.SP_OP_WGRAD, g, cin, cout))
         grads[name] = dw
-        if not need_dx:
-            return None
-        self._exchange(Pdy, g, cout)
-        Pdx = self._buf(name + ".dx", g, cin)
-        sp3d.conv3d_dgrad(Pdy, self.w[name], Pdx, g, cin, cout, dt, self._ws(sp3d.SP_OP_DGRAD, g, cin, cout))
+        Pdx = None
+        if need_dx:
+            self._exchange(Pdy, g, cout)
+            Pdx = self._tmp(g, cin)
+            sp3d.conv3d_dgrad(Pdy, self.w[name], Pdx, g, cin, cout, dt, self._ws(sp3d.SP_OP_DGRAD, g, cin, cout))
+        self._release(Pdy, g, cout)
         return Pdx
 
     def backward(self, dlogits_vol, input_grad=True):
@@ -150,37 +178,39 @@ class UNet:
         sp3d.sp_pointwise_wgrad(A["head.x"], Pd, dp, None, g0, c0, self.classes, dt,
                                 self._ws(sp3d.SP_OP_POINTWISE_WGRAD, g0, c0, self.classes))
         grads["head"] = dp
-        Pg = self._buf("head.dx", g0, c0)
+        Pg = self._tmp(g0, c0)
         sp3d.sp_pointwise_dgrad(Pd, self.w["head"], Pg, g0, c0, self.classes, dt)
         skip_grad = {}
         for i in range(0, self.L - 1):
             g, c = self.g[i], ch[i]
             up_in = ch[i + 1]
-            Pg = self._conv_bwd("dec%d_b" % i, A["dec%d_b.x" % i], A["dec%d.y" % i], Pg, g, c, c, grads)
-            Pg = self._conv_bwd("dec%d_a" % i, A["dec%d_a.x" % i], A["dec%d_b.x" % i], Pg, g, 2 * c, c, grads)
-            Ps, Pu = self._buf("skip%d.d" % i, g, c), self._buf("up%d.dy" % i, g, c)
+            Pg = self._block_bwd("dec%d" % i, Pg, g, 2 * c, c, grads)          # gradient of concat(skip, up)
+            Ps, Pu = self._tmp(g, c), self._tmp(g, c)
             sp3d.sp_split(Pg, Ps, c, Pu, c, g, dt)
+            self._release(Pg, g, 2 * c)
             skip_grad[i] = Ps
             du = torch.empty((2, 2, 2, up_in, c), dtype=torch.float32, device="cuda")
             sp3d.sp_upconv2_wgrad(A["up%d.x" % i], Pu, du, None, g, up_in, c, dt,
                                   self._ws(sp3d.SP_OP_UPCONV_WGRAD, g, up_in, c))
             grads["up%d" % i] = du
-            Pg = self._buf("up%d.dx" % i, self.g[i + 1], up_in)
+            Pg = self._tmp(self.g[i + 1], up_in)
             sp3d.sp_upconv2_dgrad(Pu, self.w["up%d" % i], Pg, g, up_in, c, dt)
+            self._release(Pu, g, c)
         for i in range(self.L - 1, -1, -1):
             g, c = self.g[i], ch[i]
             cin = self.in_ch if i == 0 else ch[i - 1]
             if i in skip_grad:                                        # gradient through the skip connection
                 sp3d.sp_add(Pg, skip_grad[i], Pg, g, c, dt)
-            Pg = self._conv_bwd("enc%d_b" % i, A["enc%d_b.x" % i], A["enc%d.y" % i], Pg, g, c, c, grads)
-            Pg = self._conv_bwd("enc%d_a" % i, A["enc%d_a.x" % i], A["enc%d_b.x" % i], Pg, g, cin, c, grads,
-                                need_dx=(i > 0 or input_grad))
+                self._release(skip_grad[i], g, c)
+            Pg = self._block_bwd("enc%d" % i, Pg, g, cin, c, grads, need_dx=(i > 0 or input_grad))
             if i > 0:
-                Pf = self._buf("pool%d.dx" % i, self.g[i - 1], cin)
+                Pf = self._tmp(self.g[i - 1], cin)
                 sp3d.sp_maxpool2_bwd(A["enc%d.y" % (i - 1)], Pg, Pf, self.g[i - 1], cin, dt)
+                self._release(Pg, g, cin)
                 Pg = Pf
         dx = None
         if input_grad:
             dx = torch.empty((g0.n, g0.d, g0.h, g0.w, self.in_ch), dtype=Pg.dtype, device="cuda")
             sp3d.sp_unpartition(Pg, dx, g0, self.in_ch, dt)
+            self._release(Pg, g0, self.in_ch)
         return grads, dx

@@ -129,8 +129,10 @@ def test_workspace_sizes_of_the_kernel_families():
     assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 32, 32, sp3d.SP_BF16) == frag
     assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 32, 64, sp3d.SP_BF16) == 2 * frag      # one input chunk: no partials
     padded64 = sp3d.sp_padded_elems(g, 64)
-    assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 64, 64, sp3d.SP_BF16) == 4 * frag + 4 * padded64
-    assert sp3d.sp_workspace_bytes(sp3d.SP_OP_DGRAD, g, 32, 64, sp3d.SP_BF16) == 2 * frag + 4 * sp3d.sp_padded_elems(g, 32)
+    assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 64, 64, sp3d.SP_BF16) == 4 * frag              # one pair of chunks
+    assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 96, 64, sp3d.SP_BF16) == 6 * frag + 4 * padded64   # three launches
+    assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 128, 64, sp3d.SP_BF16) == 8 * frag + 4 * padded64  # two pairs
+    assert sp3d.sp_workspace_bytes(sp3d.SP_OP_DGRAD, g, 32, 64, sp3d.SP_BF16) == 2 * frag           # the kernel's input is dz
     assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 1, 32, sp3d.SP_BF16) == 0               # first-layer kernel
     assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 8, 16, sp3d.SP_F32) == 0                # direct kernel
     for cin, cout in ((32, 32), (64, 128), (1, 32), (3, 5)):

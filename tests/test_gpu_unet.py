@@ -177,3 +177,37 @@ def test_unet_stack_reduced_size():
     print({k: "%.1e" % v for k, v in errs.items()})
     bad = {k: v for k, v in errs.items() if v > tol}
     assert not bad, bad
+
+
+@pytest.mark.timeout(600)
+def test_unet_four_convs_per_block():
+    """The paper's own block shape (Sec. 3: four convolutions and one max-pool per block) on a small volume:
+    free-running forward within the accumulated storage-rounding bound, backward wiring, and bit-identical
+    repetition (gradient buffers come from a free list and change owners between steps)."""
+    channels, in_ch, classes, convs = (32, 64, 128), 1, 3, 4
+    n, dhw, grid = 1, (16, 16, 32), (2, 2, 1)
+    plan = PU.layer_plan(channels, in_ch, classes, convs)
+    assert len(plan) == 3 * 4 + 2 * (1 + 4) + 1
+    x = synth.ct_like_volume((n,) + dhw + (in_ch,), synth.seed_for(6, synth.T_INPUT), "bf16")
+    w_h = {name: synth.weights(shape[3], shape[4], synth.seed_for(6, synth.T_WEIGHT0 + k), "bf16",
+                               taps=shape[:3]) for k, (name, shape) in enumerate(plan)}
+    dl = synth.normal_volume((n,) + dhw + (classes,), synth.seed_for(6, synth.T_UPSTREAM), "bf16")
+    w64 = {k: widen(v) for k, v in w_h.items()}
+    A = {}
+    ref_logits = OU.forward(widen(x), w64, channels, keep=A, store=OU.round_bf16, convs=convs)
+    ref_grads, ref_dx = OU.backward(widen(dl), w64, channels, A, store=OU.round_bf16, convs=convs)
+
+    net = PU.UNet(n, dhw, grid, {k: to_dev(v) for k, v in w_h.items()}, channels, in_ch, classes, convs=convs)
+    logits_t = net.forward(to_dev(x))
+    logits = f64(logits_t)
+    print("4-conv blocks: forward relative rms %.4f max %.4f" % (rel_rms(logits, ref_logits), rel_err(logits, ref_logits)))
+    assert rel_rms(logits, ref_logits) <= 2e-2
+    grads, dx = net.backward(to_dev(dl))
+    worst = max([rel_rms(f64(grads[k]), ref_grads[k]) for k, _ in plan] + [rel_rms(f64(dx), ref_dx)])
+    print("4-conv blocks: free-running backward worst relative rms %.3f" % worst)
+    assert worst <= 0.35
+    logits2 = net.forward(to_dev(x))
+    grads2, dx2 = net.backward(to_dev(dl))
+    assert torch.equal(logits2, logits_t) and torch.equal(dx2, dx)
+    for k, _ in plan:
+        assert torch.equal(grads2[k], grads[k]), k

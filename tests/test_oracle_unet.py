@@ -9,16 +9,17 @@ torch = pytest.importorskip("torch")
 F = torch.nn.functional
 
 
-def test_unet_oracle_matches_torch_autograd(rng):
+@pytest.mark.parametrize("convs", [2, 4, 1])
+def test_unet_oracle_matches_torch_autograd(rng, convs):
     channels, in_ch, classes = (2, 3, 4), 1, 2
-    plan = PU.layer_plan(channels, in_ch, classes)
+    plan = PU.layer_plan(channels, in_ch, classes, convs)
     w = {name: rng.standard_normal(shape) * 0.4 for name, shape in plan}
     x = rng.standard_normal((1, 4, 8, 4, in_ch))
     dl = rng.standard_normal((1, 4, 8, 4, classes))
 
     A = {}
-    logits = OU.forward(x, w, channels, keep=A)
-    grads, dx = OU.backward(dl, w, channels, A)
+    logits = OU.forward(x, w, channels, keep=A, convs=convs)
+    grads, dx = OU.backward(dl, w, channels, A, convs=convs)
 
     tw = {k: torch.from_numpy(v).clone().requires_grad_(True) for k, v in w.items()}
     xt = torch.from_numpy(x).permute(0, 4, 1, 2, 3).clone().requires_grad_(True)
@@ -30,11 +31,14 @@ def test_unet_oracle_matches_torch_autograd(rng):
     for i in range(len(channels)):
         if i > 0:
             h = F.max_pool3d(h, 2)
-        h = conv(conv(h, "enc%d_a" % i), "enc%d_b" % i)
+        for k in range(convs):
+            h = conv(h, "enc%d_%s" % (i, "abcd"[k]))
         skips.append(h)
     for i in range(len(channels) - 2, -1, -1):
         up = F.conv_transpose3d(h, tw["up%d" % i].permute(3, 4, 0, 1, 2), stride=2)
-        h = conv(conv(torch.cat([skips[i], up], dim=1), "dec%d_a" % i), "dec%d_b" % i)
+        h = torch.cat([skips[i], up], dim=1)
+        for k in range(convs):
+            h = conv(h, "dec%d_%s" % (i, "abcd"[k]))
     out = F.conv3d(h, tw["head"].permute(4, 3, 0, 1, 2))
     np.testing.assert_allclose(logits, out.detach().permute(0, 2, 3, 4, 1).numpy(), atol=1e-10)
     out.backward(torch.from_numpy(dl).permute(0, 4, 1, 2, 3))
