@@ -388,6 +388,117 @@ int wgrad_plan(const Geo &gc, int cin, int cout, UpWArgs *a, int *nci) {
     return SP_OK;
 }
 
+// ---- wide layers (more than 256 channels on the reduction side) -----------------------------------------
+// The bottom of a deep U-Net has few voxels and many channels: the weight fragments of all 8 taps no longer
+// fit LDS, and the tensors are small enough to be re-read from L2.  Forward: a workgroup serves ONE tap of
+// one output block (its fragments: Cin / 16 KB <= 64 KB) and walks over the segments with a single
+// accumulator, fetching the x fragments 8 reduction steps at a time.  Data gradient: the weight fragments
+// are contiguous 16-byte pieces of u, so they are read straight from global memory (L2) next to the dy
+// fragments.
+template <int UNUSED = 0>
+__global__ __launch_bounds__(kT) void upconv_fwd_mfma_big_kernel(UpArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int blk = blockIdx.x % a.nblk, sub = blockIdx.x / a.nblk;
+    const int tap = blk & 7, cb = blk >> 3;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nks = a.cin >> 4;
+    for (int e = tid; e < a.cin * 4; e += kT) {
+        const int c8 = e & 3, ci = e >> 2;
+        const uint4 v = *reinterpret_cast<const uint4 *>(a.u + (static_cast<size_t>(tap) * a.cin + ci) * a.cout +
+                                                         C * cb + 8 * c8);
+        char *dst = lds + (ci >> 4) * 1024 + ((ci >> 3) & 1) * 512 + (ci & 7) * 2 + 8 * c8 * 16;
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            *reinterpret_cast<uint16_t *>(dst + j * 16) = static_cast<uint16_t>(w[j >> 1] >> (16 * (j & 1)));
+    }
+    __syncthreads();
+    const int m = lane & 31, kh = lane >> 5;
+    float bv[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) bv[i] = a.bias ? a.bias[C * cb + 8 * (i >> 2) + 4 * kh + (i & 3)] : 0.f;
+#pragma unroll 1
+    for (int item = sub * (kT / 64) + wave; item < a.nitems; item += a.wpb * (kT / 64)) {
+        const Item o = decode_item(item, a.nseg, a.gc);
+        const int w = o.w0 + m;
+        const bool ok = w < a.gc.tw;
+        const uint16_t *px = a.in + pvox(a.gc, o.tile, o.d, o.h, ok ? w : a.gc.tw - 1) * a.cin + 8 * kh;
+        f32x16 acc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = bv[i];
+#pragma unroll 1
+        for (int k0 = 0; k0 < nks; k0 += 8) {          // nks is a multiple of 2; the chunk may be short
+            bf16x8 b[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (k0 + k < nks) b[k] = *reinterpret_cast<const bf16x8 *>(px + 16 * (k0 + k));
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (k0 + k < nks) {
+                    const bf16x8 af = *reinterpret_cast<const bf16x8 *>(lds + (k0 + k) * 1024 + lane * 16);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, b[k], acc, 0, 0, 0);
+                }
+        }
+        if (ok) {
+            uint16_t *py = a.out + pvox(a.gf, o.tile, 2 * o.d + (tap >> 2), 2 * o.h + ((tap >> 1) & 1),
+                                        2 * w + (tap & 1)) * a.cout + C * cb + 4 * kh;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<uint2 *>(py + 8 * q) = make_uint2(pack2(acc[4 * q], acc[4 * q + 1]),
+                                                                   pack2(acc[4 * q + 2], acc[4 * q + 3]));
+        }
+    }
+}
+
+template <int UNUSED = 0>
+__global__ __launch_bounds__(kT) void upconv_dgrad_mfma_big_kernel(UpArgs a) {
+    const int cg = blockIdx.x % a.nblk, sub = blockIdx.x / a.nblk;      // one input-channel block per workgroup
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nks = a.cout >> 4;
+    const int m = lane & 31, kh = lane >> 5;
+    // this lane's row of u: input channel 32 cg + lane % 32, reduction offset 8 (lane / 32)
+    const uint16_t *urow = a.u + static_cast<size_t>(C * cg + m) * a.cout + 8 * kh;
+    const size_t utap = static_cast<size_t>(a.cin) * a.cout;
+#pragma unroll 1
+    for (int item = sub * (kT / 64) + wave; item < a.nitems; item += a.wpb * (kT / 64)) {
+        const Item o = decode_item(item, a.nseg, a.gc);
+        const int w = o.w0 + m;
+        const bool ok = w < a.gc.tw;
+        const int wl = ok ? w : a.gc.tw - 1;
+        f32x16 acc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll 1
+        for (int tap = 0; tap < 8; ++tap) {
+            const uint16_t *pdy = a.in + pvox(a.gf, o.tile, 2 * o.d + (tap >> 2), 2 * o.h + ((tap >> 1) & 1),
+                                              2 * wl + (tap & 1)) * a.cout + 8 * kh;
+            const uint16_t *pu = urow + tap * utap;
+#pragma unroll 1
+            for (int k0 = 0; k0 < nks; k0 += 8) {
+                bf16x8 b[8], af[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (k0 + k < nks) {
+                        b[k] = *reinterpret_cast<const bf16x8 *>(pdy + 16 * (k0 + k));
+                        af[k] = *reinterpret_cast<const bf16x8 *>(pu + 16 * (k0 + k));
+                    }
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (k0 + k < nks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[k], b[k], acc, 0, 0, 0);
+            }
+        }
+        if (ok) {
+            uint16_t *px = a.out + pvox(a.gc, o.tile, o.d, o.h, w) * a.cin + C * cg + 4 * kh;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<uint2 *>(px + 8 * q) = make_uint2(pack2(acc[4 * q], acc[4 * q + 1]),
+                                                                   pack2(acc[4 * q + 2], acc[4 * q + 3]));
+        }
+    }
+}
+
 int dgrad_gci(int cin, int cout) {
     int g = 4;
     while (g > 1 && (g * 8 * (cout / 16) > kMaxFragKB || (cin / C) % g != 0)) g >>= 1;
@@ -422,7 +533,7 @@ int launch(K kernel, const UpArgs &a, int lds_bytes, hipStream_t s) {
 }  // namespace
 
 bool upconv_mfma_supported(const Geo &gf, const Geo &gc, int cin, int cout, sp_dtype_t dt) {
-    if (dt != SP_BF16 || cin % C != 0 || cout % C != 0 || cin > 256 || cout > 256) return false;
+    if (dt != SP_BF16 || cin % C != 0 || cout % C != 0 || cin > 1024 || cout > 1024) return false;
     // element offsets of a voxel inside the tensors stay far below 2^63; segment counts are checked in plan()
     return 1LL * gc.ntiles * gc.td * gc.th * ((gc.tw + SEG - 1) / SEG) <= 0x7fff0000LL;
 }
@@ -435,6 +546,11 @@ int launch_upconv_fwd_mfma(const void *Px, const void *u, const float *bias, voi
     a.bias = bias;
     a.out = static_cast<uint16_t *>(Py);
     a.gf = gf; a.gc = gc; a.cin = cin; a.cout = cout;
+    if (cin > 256) {                 // one tap per workgroup: 8 x (cout / 32) kinds of workgroups
+        int rc = plan(gc, 8 * (cout / C), &a);
+        if (rc != SP_OK) return rc;
+        return launch(upconv_fwd_mfma_big_kernel<0>, a, (cin / 16) * 1024, s);
+    }
     int rc = plan(gc, cout / C, &a);
     if (rc != SP_OK) return rc;
     const int lds_bytes = 8 * (cin / 16) * 1024;
@@ -459,6 +575,12 @@ int launch_upconv_dgrad_mfma(const void *Pdy, const void *u, void *Pdx, const Ge
     a.bias = nullptr;
     a.out = static_cast<uint16_t *>(Pdx);
     a.gf = gf; a.gc = gc; a.cin = cin; a.cout = cout;
+    if (cout > 256) {                // weight fragments straight from global memory
+        int rc = plan(gc, cin / C, &a);
+        if (rc != SP_OK) return rc;
+        hipLaunchKernelGGL(upconv_dgrad_mfma_big_kernel<0>, dim3(a.nblk * a.wpb), dim3(kT), 0, s, a);
+        return record_hip(hipGetLastError());
+    }
     const int gci = dgrad_gci(cin, cout);
     int rc = plan(gc, cin / C / gci, &a);
     if (rc != SP_OK) return rc;

@@ -61,7 +61,7 @@ def test_maxpool_forward_and_backward_bit_exact(n, dhw, grid, dtype, c):
 
 
 @pytest.mark.parametrize("n,dhw,grid,dtype", CASES)
-@pytest.mark.parametrize("cin,cout", [(8, 4), (64, 32), (5, 3), (128, 64), (32, 96), (256, 128)])
+@pytest.mark.parametrize("cin,cout", [(8, 4), (64, 32), (5, 3), (128, 64), (32, 96), (256, 128), (288, 320), (512, 64)])
 def test_upconv_fwd_dgrad_wgrad(n, dhw, grid, dtype, cin, cout):
     gf = sp3d.Geom(n, dhw, grid)
     gc = sp3d.coarse_geom(gf)
