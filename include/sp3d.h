@@ -125,6 +125,13 @@ int conv3d_fwd(const void *Px, const void *w, const float *bias, void *Py, const
  * interiors of Pdx [..][Cin].  Precision as conv3d_fwd. */
 int conv3d_dgrad(const void *Pdz, const void *w, void *Pdx, const sp_geom_t *g, int cin, int cout,
                  sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream);
+/* Data gradient followed by the backward of the ReLU that produced this layer's input (Sec. 3: the
+ * backward pass of a conv + ReLU stack):  Pdx[v,ci] = dx[v,ci] if Px[v,ci] > 0 else 0, with dx as in
+ * conv3d_dgrad and Px [..][Cin] the layer's forward input (the previous layer's ReLU output).  Same
+ * bits as conv3d_dgrad followed by sp_relu_bwd(Pdx, Px, Pdx), in one pass over Pdx.  Px must not
+ * overlap Pdx. */
+int conv3d_dgrad_relu(const void *Pdz, const void *w, const void *Px, void *Pdx, const sp_geom_t *g,
+                      int cin, int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream);
 
 /* Weight gradient.  dw[kd][kh][kw][ci][co] = sum over tiles and interior voxels v of
  * Px[v + (kd,kh,kw)][ci] * Pdz[v + (1,1,1)][co];  db[co] = sum of Pdz interiors (db may be NULL).

@@ -230,22 +230,36 @@ int conv3d_fwd(const void *Px, const void *w, const float *bias, void *Py, const
     return launch_conv_direct(Px, w, bias, Py, o, cin, cout, dt, relu, false, s);
 }
 
-int conv3d_dgrad(const void *Pdz, const void *w, void *Pdx, const sp_geom_t *g, int cin, int cout,
-                 sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream) {
+static int dgrad_impl(const void *Pdz, const void *w, const void *Pmask, void *Pdx, const sp_geom_t *g, int cin,
+                      int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream) {
     Geo o;
     int rc = check_conv_args(Pdz, w, Pdx, g, cin, cout, dt, &o);
     if (rc != SP_OK) return rc;
     const size_t es = elem_size(dt);
     const size_t pv = static_cast<size_t>(o.ntiles) * o.tile_vox;
     if (overlap(Pdz, pv * cout * es, Pdx, pv * cin * es)) return SP_EINVAL;
+    if (Pmask && (!aligned16(Pmask) || overlap(Pmask, pv * cin * es, Pdx, pv * cin * es))) return SP_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     // the kernel's "input channels" are cout and its "output channels" are cin
     if (conv_mfma_supported(o, cout, cin, dt)) {
         const size_t need = conv_mfma_ws_bytes(o, cout, cin);
         if (need && (!ws || ws_bytes < need || !aligned16(ws))) return SP_EWORKSPACE;
-        return launch_conv_mfma(Pdz, w, nullptr, Pdx, o, cout, cin, false, true, ws, s);
+        return launch_conv_mfma(Pdz, w, nullptr, Pdx, o, cout, cin, false, true, ws, s, Pmask);
     }
-    return launch_conv_direct(Pdz, w, nullptr, Pdx, o, cout, cin, dt, false, true, s);
+    rc = launch_conv_direct(Pdz, w, nullptr, Pdx, o, cout, cin, dt, false, true, s);
+    if (rc != SP_OK || !Pmask) return rc;
+    return launch_relu_bwd(Pdx, Pmask, Pdx, pv * cin, dt, s);      // element-wise, in place
+}
+
+int conv3d_dgrad(const void *Pdz, const void *w, void *Pdx, const sp_geom_t *g, int cin, int cout,
+                 sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream) {
+    return dgrad_impl(Pdz, w, nullptr, Pdx, g, cin, cout, dt, ws, ws_bytes, stream);
+}
+
+int conv3d_dgrad_relu(const void *Pdz, const void *w, const void *Px, void *Pdx, const sp_geom_t *g, int cin,
+                      int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream) {
+    if (!Px) return SP_EINVAL;
+    return dgrad_impl(Pdz, w, Px, Pdx, g, cin, cout, dt, ws, ws_bytes, stream);
 }
 
 int conv3d_wgrad(const void *Px, const void *Pdz, float *dw, float *db, const sp_geom_t *g, int cin,

@@ -91,8 +91,10 @@ int launch_reduce_partials(const float *part, float *out, int nparts, long long 
 
 bool conv_mfma_supported(const Geo &g, int cin, int cout, sp_dtype_t dt);
 size_t conv_mfma_ws_bytes(const Geo &g, int cin, int cout);
+// mask (optional, data gradient): tensor laid out like Pout; results are zeroed where it is not positive
 int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Pout, const Geo &g,
-                     int cin, int cout, bool relu, bool dgrad, void *ws, hipStream_t s);
+                     int cin, int cout, bool relu, bool dgrad, void *ws, hipStream_t s,
+                     const void *mask = nullptr);
 
 // single-input-channel first layer (conv_c1.hip)
 bool conv_c1_supported(const Geo &g, int cin, int cout, sp_dtype_t dt);

@@ -67,6 +67,7 @@ struct ConvArgs {
     const uint4 *wpack;     // fragments of this input chunk: [nco][27][2][64] x 16 bytes
     const float *bias;      // bias of all output channels or NULL
     uint16_t *out;          // output tensor (out_cs channels per voxel)
+    const uint16_t *mask;   // RELU == 2: tensor laid out like `out`; results are zeroed where it is not positive
     float *part;            // fp32 partial sums, indexed like `out`
     Geo g;
     int in_cs, in_co, out_cs;
@@ -104,6 +105,17 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
     return r.u;
 }
 
+// What happens to a finished output value (template parameter RELU of the kernels below).
+enum Epilogue { kNone = 0, kRelu = 1,   // max(z, 0): forward with SP_FLAG_RELU
+                kMask = 2 };            // z where the mask tensor is positive, else 0: the data gradient followed
+                                        // by the backward of the ReLU that produced the layer's input
+
+// two bf16 in a word -> 0xffff in each half whose value is positive (not zero, not negative, not NaN)
+__device__ __forceinline__ uint32_t positive_halves(uint32_t v) {
+    const uint32_t lo = v & 0xffffu, hi = v >> 16;
+    return ((lo - 1u) < 0x7f80u ? 0x0000ffffu : 0u) | ((hi - 1u) < 0x7f80u ? 0xffff0000u : 0u);
+}
+
 // Per-wave state of the march that the side work of a step needs.
 template <bool HAS_BIAS>
 struct Ctx {
@@ -113,6 +125,7 @@ struct Ctx {
     int goff[LOADS];            // per-lane source offsets of the staging loads (elements)
     char *lds_stage;            // LDS chunk plane this wave fills (ring slot 0)
     uint16_t *obase;            // output address of (plane 0, first row of the wave, this lane)
+    const uint16_t *mbase;      // same position in the mask tensor
     float *pbase;               // same position in the fp32 partial-sum buffer
     size_t oplane, orow;        // output elements per padded plane / per padded row
     bool okrow[RH];             // row/column of this lane lies inside the tile interior
@@ -139,12 +152,20 @@ __device__ __forceinline__ float4 load_partial(const Ctx<HAS_BIAS> &c, int d, in
     return v;
 }
 
+// The 4 mask values that belong to one store unit (fetched at the start of the step, like the partial sums).
+template <bool FULL, bool HAS_BIAS>
+__device__ __forceinline__ uint2 load_mask(const Ctx<HAS_BIAS> &c, int d, int h, int q) {
+    uint2 v = make_uint2(0u, 0u);
+    if (FULL || c.okrow[h]) v = *reinterpret_cast<const uint2 *>(c.mbase + d * c.oplane + h * c.orow + 8 * q);
+    return v;
+}
+
 // Finish 4 channels of row h of a finished plane (channels 8q + 4*(lane/32) .. +3 of this output block):
 // add the earlier chunks' partial sums if there are any, then either store the new partial (fp32) or
 // apply ReLU, convert and store bf16 (8 bytes).
-template <int MODE, bool RELU, bool FULL, bool HAS_BIAS>
+template <int MODE, int RELU, bool FULL, bool HAS_BIAS>
 __device__ __forceinline__ void store_unit(const Ctx<HAS_BIAS> &c, int d, const f32x16 (&s)[RH],
-                                           const float4 (&pin)[RH][4], int h, int q) {
+                                           const float4 (&pin)[RH][4], const uint2 (&mk)[RH][4], int h, int q) {
     float v0 = s[h][4 * q], v1 = s[h][4 * q + 1], v2 = s[h][4 * q + 2], v3 = s[h][4 * q + 3];
     if (MODE == kMiddle || MODE == kLast) {
         v0 += pin[h][q].x; v1 += pin[h][q].y; v2 += pin[h][q].z; v3 += pin[h][q].w;
@@ -154,11 +175,15 @@ __device__ __forceinline__ void store_unit(const Ctx<HAS_BIAS> &c, int d, const 
         if (FULL || c.okrow[h]) *reinterpret_cast<float4 *>(c.pbase + at) = make_float4(v0, v1, v2, v3);
         return;
     }
-    if (RELU) {
+    if (RELU == kRelu) {
         v0 = v0 < 0.f ? 0.f : v0; v1 = v1 < 0.f ? 0.f : v1;
         v2 = v2 < 0.f ? 0.f : v2; v3 = v3 < 0.f ? 0.f : v3;
     }
-    const uint2 pk = make_uint2(pack2(v0, v1), pack2(v2, v3));
+    uint2 pk = make_uint2(pack2(v0, v1), pack2(v2, v3));
+    if (RELU == kMask) {
+        pk.x &= positive_halves(mk[h][q].x);
+        pk.y &= positive_halves(mk[h][q].y);
+    }
     if (FULL || c.okrow[h]) *reinterpret_cast<uint2 *>(c.obase + at) = pk;
 }
 
@@ -170,18 +195,25 @@ __device__ __forceinline__ void store_unit(const Ctx<HAS_BIAS> &c, int d, const 
 // consume them.  P = Dp mod 4: output plane Dp-kd lives in slot (P-kd) mod 4, plane Dp-3 in slot (P+1) mod 4.
 // FULL: the patch lies completely inside the tile interior, so stores need no mask (no branches in
 // the step, which lets the scheduler weave the side work between the MFMAs).
-template <int P, bool EPI, int MODE, bool RELU, bool FULL, bool HAS_BIAS>
+template <int P, bool EPI, int MODE, int RELU, bool FULL, bool HAS_BIAS>
 __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, int lane, const char *lbase,
                                            const bf16x8 (&wf)[NFRAG], f32x16 (&acc)[4][RH]) {
     constexpr int NR = RH + 2;
     constexpr int DONE = (P + 1) & 3;
     bf16x8 b[2][NR];
     float4 pin[RH][4];      // partial sums of the plane being finished (chunks after the first)
+    uint2 mk[RH][4];        // mask values of the plane being finished (RELU == kMask)
     if (EPI && (MODE == kMiddle || MODE == kLast)) {
 #pragma unroll
         for (int h = 0; h < RH; ++h)
 #pragma unroll
             for (int q = 0; q < 4; ++q) pin[h][q] = load_partial<FULL>(c, Dp - 3, h, q);
+    }
+    if (EPI && RELU == kMask && (MODE == kSingle || MODE == kLast)) {
+#pragma unroll
+        for (int h = 0; h < RH; ++h)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) mk[h][q] = load_mask<FULL>(c, Dp - 3, h, q);
     }
 #pragma unroll
     for (int r = 0; r < NR; ++r)
@@ -202,8 +234,8 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, int l
         stage(c, Dp + DIST, gi, lane);
         if (gi < 4) {
             if (EPI) {
-                store_unit<MODE, RELU, FULL>(c, Dp - 3, acc[DONE], pin, 0, gi);
-                store_unit<MODE, RELU, FULL>(c, Dp - 3, acc[DONE], pin, 1, gi);
+                store_unit<MODE, RELU, FULL>(c, Dp - 3, acc[DONE], pin, mk, 0, gi);
+                store_unit<MODE, RELU, FULL>(c, Dp - 3, acc[DONE], pin, mk, 1, gi);
             }
         } else {
 #pragma unroll
@@ -232,7 +264,7 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, int l
     }
 }
 
-template <int MODE, bool HAS_BIAS, bool RELU>
+template <int MODE, bool HAS_BIAS, int RELU>
 __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];   // NBUF planes of PLANE_BYTES
     const Geo &g = a.g;
@@ -281,6 +313,7 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
                         ((static_cast<size_t>(d0 + 1) * g.ph + h0 + wave * RH + 1) * g.pw + w0 + col + 1) * a.out_cs +
                         C * cj + 4 * hi;
     c.obase = a.out + opos;
+    c.mbase = a.mask + opos;
     c.pbase = a.part + opos;
 #pragma unroll
     for (int h = 0; h < RH; ++h) c.okrow[h] = h0 + wave * RH + h < g.th && w0 + col < g.tw;
@@ -345,19 +378,26 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
         // the last output plane (dn-1) finished in the last step; it sits in slot (dn-1) mod 4
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         float4 pin[RH][4];
+        uint2 mk[RH][4];
         if (MODE == kMiddle || MODE == kLast) {
 #pragma unroll
             for (int h = 0; h < RH; ++h)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) pin[h][q] = load_partial<FULL>(c, dn - 1, h, q);
         }
+        if (RELU == kMask && (MODE == kSingle || MODE == kLast)) {
+#pragma unroll
+            for (int h = 0; h < RH; ++h)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) mk[h][q] = load_mask<FULL>(c, dn - 1, h, q);
+        }
 #pragma unroll
         for (int s = 0; s < 4; ++s)
             if (s == ((dn - 1) & 3)) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    store_unit<MODE, RELU, FULL>(c, dn - 1, acc[s], pin, 0, q);
-                    store_unit<MODE, RELU, FULL>(c, dn - 1, acc[s], pin, 1, q);
+                    store_unit<MODE, RELU, FULL>(c, dn - 1, acc[s], pin, mk, 0, q);
+                    store_unit<MODE, RELU, FULL>(c, dn - 1, acc[s], pin, mk, 1, q);
                 }
             }
     };
@@ -413,6 +453,7 @@ struct Ctx {
     char *lds_stage;            // first chunk plane this wave fills, ring slot 0
     char *red;                  // hand-over buffer of this wave's row group (buffer 0), lane part included
     uint16_t *obase;
+    const uint16_t *mbase;
     float *pbase;
     size_t oplane, orow;
     bool okrow[RH];
@@ -436,12 +477,19 @@ __device__ __forceinline__ float4 load_partial(const Ctx<HAS_BIAS> &c, int d, in
     return v;
 }
 
+template <bool FULL, bool HAS_BIAS>
+__device__ __forceinline__ uint2 load_mask(const Ctx<HAS_BIAS> &c, int d, int h, int q) {
+    uint2 v = make_uint2(0u, 0u);
+    if (FULL || c.okrow[h]) v = *reinterpret_cast<const uint2 *>(c.mbase + d * c.oplane + h * c.orow + 8 * q);
+    return v;
+}
+
 // chunk-0 wave: finish 4 channels of row h of plane d: own sum + the partner's (from LDS) + earlier pairs'
 // partial sums (pin, fetched at the start of the step), then store the new partial (fp32) or ReLU /
 // convert / store bf16
-template <int MODE, bool RELU, bool FULL, bool HAS_BIAS>
+template <int MODE, int RELU, bool FULL, bool HAS_BIAS>
 __device__ __forceinline__ void finish_unit(const Ctx<HAS_BIAS> &c, int d, const f32x16 (&s)[RH], const char *red,
-                                            const float4 (&pin)[RH][4], int h, int q) {
+                                            const float4 (&pin)[RH][4], const uint2 (&mk)[RH][4], int h, int q) {
     const float4 o = *reinterpret_cast<const float4 *>(red + (h * 4 + q) * 1024);
     float v0 = s[h][4 * q] + o.x, v1 = s[h][4 * q + 1] + o.y, v2 = s[h][4 * q + 2] + o.z, v3 = s[h][4 * q + 3] + o.w;
     if (MODE == kMiddle || MODE == kLast) {
@@ -452,11 +500,15 @@ __device__ __forceinline__ void finish_unit(const Ctx<HAS_BIAS> &c, int d, const
         if (FULL || c.okrow[h]) *reinterpret_cast<float4 *>(c.pbase + at) = make_float4(v0, v1, v2, v3);
         return;
     }
-    if (RELU) {
+    if (RELU == kRelu) {
         v0 = v0 < 0.f ? 0.f : v0; v1 = v1 < 0.f ? 0.f : v1;
         v2 = v2 < 0.f ? 0.f : v2; v3 = v3 < 0.f ? 0.f : v3;
     }
-    const uint2 pk = make_uint2(pack2(v0, v1), pack2(v2, v3));
+    uint2 pk = make_uint2(pack2(v0, v1), pack2(v2, v3));
+    if (RELU == kMask) {
+        pk.x &= positive_halves(mk[h][q].x);
+        pk.y &= positive_halves(mk[h][q].y);
+    }
     if (FULL || c.okrow[h]) *reinterpret_cast<uint2 *>(c.obase + at) = pk;
 }
 
@@ -470,7 +522,7 @@ __device__ __forceinline__ void give_unit(const f32x16 (&s)[RH], char *red, int 
 // ROLE 1 (chunk 1): GIVE = plane Dp - 3 (slot (P + 2) mod 5) goes to the hand-over buffer Dp & 1 and its
 // slot is cleared.  ROLE 0 (chunk 0): FIN = plane Dp - 4 (slot (P + 1) mod 5) is finished from the buffer
 // written in the previous step, (Dp - 1) & 1, and its slot returns to the bias.
-template <int P, int ROLE, bool GIVE, bool FIN, int MODE, bool RELU, bool FULL, bool HAS_BIAS>
+template <int P, int ROLE, bool GIVE, bool FIN, int MODE, int RELU, bool FULL, bool HAS_BIAS>
 __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const char *lbase,
                                            const bf16x8 (&wf)[NFRAG], f32x16 (&acc)[NSLOT][RH]) {
     constexpr int NR = RH + 2;
@@ -481,11 +533,18 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const
     char *red_w = c.red + (Dp & 1) * RED_BYTES;
     const char *red_r = c.red + ((Dp - 1) & 1) * RED_BYTES;
     float4 pin[RH][4];
+    uint2 mk[RH][4];
     if (ROLE == 0 && FIN && (MODE == kMiddle || MODE == kLast)) {
 #pragma unroll
         for (int h = 0; h < RH; ++h)
 #pragma unroll
             for (int q = 0; q < 4; ++q) pin[h][q] = load_partial<FULL>(c, Dp - 4, h, q);
+    }
+    if (ROLE == 0 && FIN && RELU == kMask && (MODE == kSingle || MODE == kLast)) {
+#pragma unroll
+        for (int h = 0; h < RH; ++h)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) mk[h][q] = load_mask<FULL>(c, Dp - 4, h, q);
     }
 #pragma unroll
     for (int r = 0; r < NR; ++r) b[0][r] = *reinterpret_cast<const bf16x8 *>(lbase + (r * LCOLS) * 16);
@@ -509,8 +568,8 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const
                     give_unit(acc[SIDE], red_w, 0, gi);
                     give_unit(acc[SIDE], red_w, 1, gi);
                 } else {
-                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SIDE], red_r, pin, 0, gi);
-                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SIDE], red_r, pin, 1, gi);
+                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SIDE], red_r, pin, mk, 0, gi);
+                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SIDE], red_r, pin, mk, 1, gi);
                 }
             }
         } else {
@@ -547,7 +606,7 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const
 // The two steps after the last input plane: only the side work is left.  Dp = nplanes: chunk 1 hands over
 // the last output plane (Dp - 3 = dn - 1), chunk 0 finishes plane Dp - 4; Dp = nplanes + 1: chunk 0 finishes
 // the last plane.  Same slot arithmetic as plane_step, so every accumulator index stays a constant.
-template <int P, int ROLE, bool GIVE, bool FIN, int MODE, bool RELU, bool FULL, bool HAS_BIAS>
+template <int P, int ROLE, bool GIVE, bool FIN, int MODE, int RELU, bool FULL, bool HAS_BIAS>
 __device__ __forceinline__ void drain_step(const Ctx<HAS_BIAS> &c, int Dp, f32x16 (&acc)[NSLOT][RH]) {
     constexpr int SIDE = ROLE == 1 ? (P + 2) % NSLOT : (P + 1) % NSLOT;
     if (ROLE == 1) {
@@ -562,21 +621,28 @@ __device__ __forceinline__ void drain_step(const Ctx<HAS_BIAS> &c, int Dp, f32x1
     } else if (FIN) {
         const char *red_r = c.red + ((Dp - 1) & 1) * RED_BYTES;
         float4 pin[RH][4];
+        uint2 mk[RH][4];
         if (MODE == kMiddle || MODE == kLast) {
 #pragma unroll
             for (int h = 0; h < RH; ++h)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) pin[h][q] = load_partial<FULL>(c, Dp - 4, h, q);
         }
+        if (RELU == kMask && (MODE == kSingle || MODE == kLast)) {
+#pragma unroll
+            for (int h = 0; h < RH; ++h)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) mk[h][q] = load_mask<FULL>(c, Dp - 4, h, q);
+        }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SIDE], red_r, pin, 0, q);
-            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SIDE], red_r, pin, 1, q);
+            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SIDE], red_r, pin, mk, 0, q);
+            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SIDE], red_r, pin, mk, 1, q);
         }
     }
 }
 
-template <int ROLE, int MODE, bool HAS_BIAS, bool RELU>
+template <int ROLE, int MODE, bool HAS_BIAS, int RELU>
 __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int tile, int d0, int h0, int w0, int dn, int cj,
                                     int rg) {
     const Geo &g = a.g;
@@ -613,6 +679,7 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int tile, int 
                         ((static_cast<size_t>(d0 + 1) * g.ph + h0 + rg * RH + 1) * g.pw + w0 + col + 1) * a.out_cs +
                         C * cj + 4 * hi;
     c.obase = a.out + opos;
+    c.mbase = a.mask + opos;
     c.pbase = a.part + opos;
 #pragma unroll
     for (int h = 0; h < RH; ++h) c.okrow[h] = h0 + rg * RH + h < g.th && w0 + col < g.tw;
@@ -684,7 +751,7 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int tile, int 
 #undef SP3D_STEP_END
 }
 
-template <int MODE, bool HAS_BIAS, bool RELU>
+template <int MODE, bool HAS_BIAS, int RELU>
 __global__ __launch_bounds__(kThreads, 1) void conv_mfma_pair_kernel(ConvArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const Geo &g = a.g;
@@ -729,7 +796,7 @@ size_t conv_mfma_ws_bytes(const Geo &g, int ki, int ko) {
 }
 
 int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Pout, const Geo &g,
-                     int ki, int ko, bool relu, bool dgrad, void *ws, hipStream_t s) {
+                     int ki, int ko, bool relu, bool dgrad, void *ws, hipStream_t s, const void *mask) {
     const int nci = ki / C, nco = ko / C;
     const int pack_elems = nci * nco * NFRAG * 64 * 8;
     hipLaunchKernelGGL(pack_weights_kernel, dim3((pack_elems + 255) / 256), dim3(256), 0, s,
@@ -740,6 +807,7 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
     a.in = static_cast<const uint16_t *>(Pin);
     a.bias = bias;
     a.out = static_cast<uint16_t *>(Pout);
+    a.mask = static_cast<const uint16_t *>(mask);
     a.part = reinterpret_cast<float *>(static_cast<char *>(ws) + pack_bytes(ki, ko));
     a.g = g;
     a.in_cs = ki;
@@ -761,33 +829,28 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
     a.nblocks = static_cast<int>(nb);
     const unsigned grid = static_cast<unsigned>((nb + 7) / 8 * 8);
     using Kern = void (*)(ConvArgs);
-    // [mode][bias][relu]; combinations that cannot occur (bias after the first chunk, ReLU before the last)
-    // reuse the plain variant
-    static const Kern kern[4][2][2] = {
-        {{conv_mfma_kernel<kSingle, false, false>, conv_mfma_kernel<kSingle, false, true>},
-         {conv_mfma_kernel<kSingle, true, false>, conv_mfma_kernel<kSingle, true, true>}},
-        {{conv_mfma_kernel<kFirst, false, false>, conv_mfma_kernel<kFirst, false, false>},
-         {conv_mfma_kernel<kFirst, true, false>, conv_mfma_kernel<kFirst, true, false>}},
-        {{conv_mfma_kernel<kMiddle, false, false>, conv_mfma_kernel<kMiddle, false, false>},
-         {conv_mfma_kernel<kMiddle, false, false>, conv_mfma_kernel<kMiddle, false, false>}},
-        {{conv_mfma_kernel<kLast, false, false>, conv_mfma_kernel<kLast, false, true>},
-         {conv_mfma_kernel<kLast, false, false>, conv_mfma_kernel<kLast, false, true>}}};
-    static const Kern kern2[4][2][2] = {
-        {{wide::conv_mfma_pair_kernel<kSingle, false, false>, wide::conv_mfma_pair_kernel<kSingle, false, true>},
-         {wide::conv_mfma_pair_kernel<kSingle, true, false>, wide::conv_mfma_pair_kernel<kSingle, true, true>}},
-        {{wide::conv_mfma_pair_kernel<kFirst, false, false>, wide::conv_mfma_pair_kernel<kFirst, false, false>},
-         {wide::conv_mfma_pair_kernel<kFirst, true, false>, wide::conv_mfma_pair_kernel<kFirst, true, false>}},
-        {{wide::conv_mfma_pair_kernel<kMiddle, false, false>, wide::conv_mfma_pair_kernel<kMiddle, false, false>},
-         {wide::conv_mfma_pair_kernel<kMiddle, false, false>, wide::conv_mfma_pair_kernel<kMiddle, false, false>}},
-        {{wide::conv_mfma_pair_kernel<kLast, false, false>, wide::conv_mfma_pair_kernel<kLast, false, true>},
-         {wide::conv_mfma_pair_kernel<kLast, false, false>, wide::conv_mfma_pair_kernel<kLast, false, true>}}};
+    // [mode][bias][epilogue]; combinations that cannot occur (bias after the first launch, ReLU or mask before
+    // the last, bias together with a mask) reuse the plain variant
+#define SP3D_TABLE(K)                                                                                      \
+    {{{K<kSingle, false, kNone>, K<kSingle, false, kRelu>, K<kSingle, false, kMask>},                        \
+      {K<kSingle, true, kNone>, K<kSingle, true, kRelu>, K<kSingle, false, kMask>}},                         \
+     {{K<kFirst, false, kNone>, K<kFirst, false, kNone>, K<kFirst, false, kNone>},                           \
+      {K<kFirst, true, kNone>, K<kFirst, true, kNone>, K<kFirst, true, kNone>}},                             \
+     {{K<kMiddle, false, kNone>, K<kMiddle, false, kNone>, K<kMiddle, false, kNone>},                        \
+      {K<kMiddle, false, kNone>, K<kMiddle, false, kNone>, K<kMiddle, false, kNone>}},                       \
+     {{K<kLast, false, kNone>, K<kLast, false, kRelu>, K<kLast, false, kMask>},                              \
+      {K<kLast, false, kNone>, K<kLast, false, kRelu>, K<kLast, false, kMask>}}}
+    static const Kern kern[4][2][3] = SP3D_TABLE(conv_mfma_kernel);
+    static const Kern kern2[4][2][3] = SP3D_TABLE(wide::conv_mfma_pair_kernel);
+#undef SP3D_TABLE
+    const int epi = mask ? kMask : (relu ? kRelu : kNone);
     // more than 64 KB of dynamic LDS has to be requested explicitly
     static const hipError_t attr = [] {
-        for (int i = 0; i < 16; ++i) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern[i >> 2][(i >> 1) & 1][i & 1]),
+        for (int i = 0; i < 24; ++i) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern[i / 6][(i / 3) & 1][i % 3]),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
             if (e != hipSuccess) return e;
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern2[i >> 2][(i >> 1) & 1][i & 1]),
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern2[i / 6][(i / 3) & 1][i % 3]),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, wide::LDS_BYTES);
             if (e != hipSuccess) return e;
         }
@@ -800,10 +863,9 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
         a.in_co = (pairs ? 2 * C : C) * ci;
         a.wpack = static_cast<const uint4 *>(ws) + static_cast<size_t>(pairs ? 2 * ci : ci) * nco * NFRAG * 64;
         if (pairs)
-            hipLaunchKernelGGL(kern2[mode][bias ? 1 : 0][relu ? 1 : 0], dim3(grid), dim3(kThreads), wide::LDS_BYTES,
-                               s, a);
+            hipLaunchKernelGGL(kern2[mode][bias ? 1 : 0][epi], dim3(grid), dim3(kThreads), wide::LDS_BYTES, s, a);
         else
-            hipLaunchKernelGGL(kern[mode][bias ? 1 : 0][relu ? 1 : 0], dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
+            hipLaunchKernelGGL(kern[mode][bias ? 1 : 0][epi], dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
         rc = record_hip(hipGetLastError());
         if (rc != SP_OK) return rc;
     }

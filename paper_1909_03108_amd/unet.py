@@ -101,8 +101,9 @@ class UNet:
         for k in range(self.convs - 1, -1, -1):
             name = "%s_%s" % (block, LETTERS[k])
             Py = A[block + ".y"] if k == self.convs - 1 else A["%s_%s.x" % (block, LETTERS[k + 1])]
+            # layer k > 0 reads the ReLU output of layer k - 1: its data gradient applies that mask itself
             Pg = self._conv_bwd(name, A[name + ".x"], Py, Pg, g, cin if k == 0 else c, c, grads,
-                                need_dx=(need_dx or k > 0))
+                                need_dx=(need_dx or k > 0), masked=(k < self.convs - 1), mask_next=(k > 0))
         return Pg
 
     # gradient buffers are short-lived: they come from a free list keyed by shape and go back to it as
@@ -151,10 +152,13 @@ class UNet:
         return out
 
     # ---- backward ---------------------------------------------------------------------------------
-    def _conv_bwd(self, name, Px, Py, Pdy, g, cin, cout, grads, need_dx=True):
-        """Backward of y = relu(conv(x)): Pdy is d/dy (interiors valid).  Returns d/dx (padded)."""
+    def _conv_bwd(self, name, Px, Py, Pdy, g, cin, cout, grads, need_dx=True, masked=False, mask_next=False):
+        """Backward of y = relu(conv(x)): Pdy is d/dy (interiors valid), or already d/dz if `masked`.
+        Returns d/dx (padded); with `mask_next` (x is itself a ReLU output) the ReLU mask of x is applied
+        in the same pass, so the result is the previous layer's d/dz."""
         dt = self.dt
-        sp3d.sp_relu_bwd(Pdy, Py, Pdy, g, cout, dt)                   # dz in place
+        if not masked:
+            sp3d.sp_relu_bwd(Pdy, Py, Pdy, g, cout, dt)               # dz in place
         dw = torch.empty((3, 3, 3, cin, cout), dtype=torch.float32, device="cuda")
         sp3d.conv3d_wgrad(Px, Pdy, dw, None, g, cin, cout, dt, self._ws(sp3d.SP_OP_WGRAD, g, cin, cout))
         grads[name] = dw
@@ -162,7 +166,12 @@ class UNet:
         if need_dx:
             self._exchange(Pdy, g, cout)
             Pdx = self._tmp(g, cin)
-            sp3d.conv3d_dgrad(Pdy, self.w[name], Pdx, g, cin, cout, dt, self._ws(sp3d.SP_OP_DGRAD, g, cin, cout))
+            if mask_next:
+                sp3d.conv3d_dgrad_relu(Pdy, self.w[name], Px, Pdx, g, cin, cout, dt,
+                                       self._ws(sp3d.SP_OP_DGRAD, g, cin, cout))
+            else:
+                sp3d.conv3d_dgrad(Pdy, self.w[name], Pdx, g, cin, cout, dt,
+                                  self._ws(sp3d.SP_OP_DGRAD, g, cin, cout))
         self._release(Pdy, g, cout)
         return Pdx
 

@@ -79,6 +79,8 @@ def test_calls_reject_bad_arguments_before_launching():
     assert L.conv3d_fwd(FAKE, FAKE * 2, None, FAKE, gp, 4, 4, sp3d.SP_F32, 0, None, 0, None) == sp3d.SP_EINVAL
     assert L.conv3d_dgrad(FAKE, None, FAKE * 16, gp, 4, 4, sp3d.SP_F32, None, 0, None) == sp3d.SP_EINVAL
     assert L.conv3d_dgrad(FAKE, FAKE * 2, FAKE * 16, gp, -1, 4, sp3d.SP_F32, None, 0, None) == sp3d.SP_EINVAL
+    assert L.conv3d_dgrad_relu(FAKE, FAKE * 2, None, FAKE * 16, gp, 4, 4, sp3d.SP_F32, None, 0, None) == sp3d.SP_EINVAL
+    assert L.conv3d_dgrad_relu(FAKE, FAKE * 2, FAKE * 16, FAKE * 16, gp, 4, 4, sp3d.SP_F32, None, 0, None) == sp3d.SP_EINVAL
     # weight gradient always needs scratch for its fixed-order reduction
     need = sp3d.sp_workspace_bytes(sp3d.SP_OP_WGRAD, g, 4, 4, sp3d.SP_F32)
     assert need > 0

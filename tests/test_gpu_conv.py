@@ -54,6 +54,16 @@ class Layer:
                           self.ws[sp3d.SP_OP_DGRAD])
         return self.volume(Pdx, self.cin)
 
+    def dgrad_relu(self, dz, w, xmask):
+        """data gradient with the ReLU mask of the layer input applied in the same pass"""
+        Pz = self.padded(dz, self.cout)
+        Pm = sp3d.alloc_padded(self.g, self.cin, self.dt)
+        sp3d.sp_partition(to_dev(xmask), Pm, self.g, self.cin, self.dt)
+        Pdx = sp3d.alloc_padded(self.g, self.cin, self.dt)
+        sp3d.conv3d_dgrad_relu(Pz, to_dev(w), Pm, Pdx, self.g, self.cin, self.cout, self.dt,
+                               self.ws[sp3d.SP_OP_DGRAD])
+        return self.volume(Pdx, self.cin)
+
     def wgrad(self, x, dz, want_db=True):
         Px = self.padded(x, self.cin)
         Pz = sp3d.alloc_padded(self.g, self.cout, self.dt)
@@ -166,3 +176,19 @@ def test_configuration_1_fp32_full():
     L = Layer(c["n"], c["dhw"], c["grid"], 8, 16, "f32")
     y = L.fwd(x, ws[0], np.zeros(16, dtype=np.float32))
     assert rel_err(f64(y), conv3d.conv3d_fwd(x, widen(ws[0]))) <= TOL["f32"]
+
+
+@pytest.mark.parametrize("n,dhw,grid,cin,cout,dtype", [c for c in SMALL if c[3] > 1])
+def test_dgrad_with_relu_mask_equals_dgrad_then_mask(n, dhw, grid, cin, cout, dtype):
+    """conv3d_dgrad_relu = conv3d_dgrad followed by the ReLU backward on the layer input, bit for bit
+    (every kernel family: one chunk, pairs, several launches, the fp32 / odd-channel direct kernel)."""
+    L = Layer(n, dhw, grid, cin, cout, dtype)
+    dz = draw(dtype, (n,) + dhw + (cout,), 21)
+    w = synth.weights(cin, cout, 22, dtype)
+    x = draw(dtype, (n,) + dhw + (cin,), 23)
+    xr = np.where(widen(x) > 0, x, np.zeros_like(x))           # a ReLU output: about half zeros
+    plain = L.dgrad(dz, w)
+    fused = L.dgrad_relu(dz, w, xr)
+    expect = torch.where(to_dev(xr).float() > 0, plain, torch.zeros_like(plain))
+    assert torch.equal(fused, expect)
+    assert rel_err(f64(fused), np.where(widen(xr) > 0, conv3d.conv3d_dgrad(dz, widen(w)), 0.0)) <= TOL[dtype]
