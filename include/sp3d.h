@@ -141,6 +141,22 @@ int conv3d_dgrad_relu(const void *Pdz, const void *w, const void *Px, void *Pdx,
 int conv3d_wgrad(const void *Px, const void *Pdz, float *dw, float *db, const sp_geom_t *g,
                  int cin, int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream);
 
+/* The three passes on a channel-wise concatenation that is never materialised (the decoder of the
+ * U-Net of Sec. 3 convolves concat(skip, up)): the layer's input channels [0, ca) live in tensor a
+ * [..][ca] and [ca, ca + cb) in tensor b [..][cb]; w, dw are [3][3][3][ca + cb][Cout].  Results are
+ * bit-identical to concatenating first and calling conv3d_fwd / conv3d_dgrad (+ split) / conv3d_wgrad.
+ * bf16 with ca, cb, Cout multiples of 32 only (SP_EUNSUPPORTED otherwise: concatenate instead).
+ * Workspace as for the single-tensor call with Cin = ca + cb.  Both inputs must hold their halos
+ * (forward, weight gradient); conv3d_dgrad2 writes the interiors of both gradient tensors. */
+int conv3d_fwd2(const void *Pxa, int ca, const void *Pxb, int cb, const void *w, const float *bias,
+                void *Py, const sp_geom_t *g, int cout, sp_dtype_t dt, uint32_t flags, void *ws,
+                size_t ws_bytes, void *stream);
+int conv3d_dgrad2(const void *Pdz, const void *w, void *Pdxa, int ca, void *Pdxb, int cb,
+                  const sp_geom_t *g, int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream);
+int conv3d_wgrad2(const void *Pxa, int ca, const void *Pxb, int cb, const void *Pdz, float *dw,
+                  float *db, const sp_geom_t *g, int cout, sp_dtype_t dt, void *ws, size_t ws_bytes,
+                  void *stream);
+
 /* Element-wise ReLU backward on padded tiles: Pdz = Pdy where Py > 0, else 0 (all elements,
  * margins included; the derivative at 0 is taken as 0).  Pdz may alias Pdy. */
 int sp_relu_bwd(const void *Pdy, const void *Py, void *Pdz, const sp_geom_t *g, int c,

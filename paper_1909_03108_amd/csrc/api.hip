@@ -279,6 +279,65 @@ int conv3d_wgrad(const void *Px, const void *Pdz, float *dw, float *db, const sp
     return launch_wgrad_direct(Px, Pdz, dw, db, o, cin, cout, dt, ws, s);
 }
 
+// ---- the same three passes on a channel-wise concatenation that is never materialised ----------------
+
+static int check_pair(const void *a, int ca, const void *b, int cb, sp_dtype_t dt) {
+    if (!a || !b) return SP_EINVAL;
+    if (ca <= 0 || cb <= 0) return SP_EINVAL;
+    if (dt != SP_BF16 || ca % 32 != 0 || cb % 32 != 0) return SP_EUNSUPPORTED;
+    if (!aligned16(a) || !aligned16(b)) return SP_EINVAL;
+    return SP_OK;
+}
+
+int conv3d_fwd2(const void *Pxa, int ca, const void *Pxb, int cb, const void *w, const float *bias, void *Py,
+                const sp_geom_t *g, int cout, sp_dtype_t dt, uint32_t flags, void *ws, size_t ws_bytes,
+                void *stream) {
+    Geo o;
+    int rc = check_conv_args(Pxa, w, Py, g, ca + cb, cout, dt, &o);
+    if (rc != SP_OK) return rc;
+    if ((rc = check_pair(Pxa, ca, Pxb, cb, dt)) != SP_OK) return rc;
+    if (flags & ~static_cast<uint32_t>(SP_FLAG_RELU)) return SP_EINVAL;
+    if (!conv_mfma_supported(o, ca + cb, cout, dt)) return SP_EUNSUPPORTED;
+    const size_t pv = static_cast<size_t>(o.ntiles) * o.tile_vox;
+    if (overlap(Pxa, pv * ca * 2, Py, pv * cout * 2) || overlap(Pxb, pv * cb * 2, Py, pv * cout * 2)) return SP_EINVAL;
+    const size_t need = conv_mfma_ws_bytes(o, ca + cb, cout);
+    if (need && (!ws || ws_bytes < need || !aligned16(ws))) return SP_EWORKSPACE;
+    const ConvSplit sp{Pxb, ca, nullptr, 0};
+    return launch_conv_mfma(Pxa, w, bias, Py, o, ca + cb, cout, flags & SP_FLAG_RELU, false, ws,
+                            static_cast<hipStream_t>(stream), nullptr, &sp);
+}
+
+int conv3d_dgrad2(const void *Pdz, const void *w, void *Pdxa, int ca, void *Pdxb, int cb, const sp_geom_t *g,
+                  int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream) {
+    Geo o;
+    int rc = check_conv_args(Pdz, w, Pdxa, g, ca + cb, cout, dt, &o);
+    if (rc != SP_OK) return rc;
+    if ((rc = check_pair(Pdxa, ca, Pdxb, cb, dt)) != SP_OK) return rc;
+    if (!conv_mfma_supported(o, cout, ca + cb, dt)) return SP_EUNSUPPORTED;
+    const size_t pv = static_cast<size_t>(o.ntiles) * o.tile_vox;
+    if (overlap(Pdz, pv * cout * 2, Pdxa, pv * ca * 2) || overlap(Pdz, pv * cout * 2, Pdxb, pv * cb * 2) ||
+        overlap(Pdxa, pv * ca * 2, Pdxb, pv * cb * 2))
+        return SP_EINVAL;
+    const size_t need = conv_mfma_ws_bytes(o, cout, ca + cb);
+    if (need && (!ws || ws_bytes < need || !aligned16(ws))) return SP_EWORKSPACE;
+    const ConvSplit sp{nullptr, 0, Pdxb, ca};
+    return launch_conv_mfma(Pdz, w, nullptr, Pdxa, o, cout, ca + cb, false, true, ws,
+                            static_cast<hipStream_t>(stream), nullptr, &sp);
+}
+
+int conv3d_wgrad2(const void *Pxa, int ca, const void *Pxb, int cb, const void *Pdz, float *dw, float *db,
+                  const sp_geom_t *g, int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream) {
+    Geo o;
+    int rc = check_conv_args(Pxa, Pdz, dw, g, ca + cb, cout, dt, &o);
+    if (rc != SP_OK) return rc;
+    if ((rc = check_pair(Pxa, ca, Pxb, cb, dt)) != SP_OK) return rc;
+    if (db && (reinterpret_cast<uintptr_t>(db) & 3u)) return SP_EINVAL;
+    if (!wgrad_mfma_supported(o, ca + cb, cout, dt)) return SP_EUNSUPPORTED;
+    const size_t need = wgrad_mfma_ws_bytes(o, ca + cb, cout);
+    if (!ws || ws_bytes < need || !aligned16(ws)) return SP_EWORKSPACE;
+    return launch_wgrad_mfma(Pxa, Pdz, dw, db, o, ca + cb, cout, ws, static_cast<hipStream_t>(stream), Pxb, ca);
+}
+
 int sp_relu_bwd(const void *Pdy, const void *Py, void *Pdz, const sp_geom_t *g, int c, sp_dtype_t dt,
                 void *stream) {
     Geo o;

@@ -91,10 +91,17 @@ int launch_reduce_partials(const float *part, float *out, int nparts, long long 
 
 bool conv_mfma_supported(const Geo &g, int cin, int cout, sp_dtype_t dt);
 size_t conv_mfma_ws_bytes(const Geo &g, int cin, int cout);
+// Channel-wise concatenation without a copy: the kernel's input channels [in_ca, cin) may live in a second
+// tensor in2 (cin - in_ca channels per voxel, Pin then has in_ca), and its output channels [out_ca, cout) may
+// go to a second tensor out2 (cout - out_ca per voxel, Pout then has out_ca).  Null pointers = not split.
+struct ConvSplit {
+    const void *in2; int in_ca;
+    void *out2; int out_ca;
+};
 // mask (optional, data gradient): tensor laid out like Pout; results are zeroed where it is not positive
 int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Pout, const Geo &g,
                      int cin, int cout, bool relu, bool dgrad, void *ws, hipStream_t s,
-                     const void *mask = nullptr);
+                     const void *mask = nullptr, const ConvSplit *split = nullptr);
 
 // single-input-channel first layer (conv_c1.hip)
 bool conv_c1_supported(const Geo &g, int cin, int cout, sp_dtype_t dt);
@@ -106,8 +113,9 @@ int launch_wgrad_c1(const void *Px, const void *Pdz, float *dw, float *db, const
 
 bool wgrad_mfma_supported(const Geo &g, int cin, int cout, sp_dtype_t dt);
 size_t wgrad_mfma_ws_bytes(const Geo &g, int cin, int cout);
+// Px2 (optional): the input channels [ca, cin) live in a second tensor of cin - ca channels per voxel
 int launch_wgrad_mfma(const void *Px, const void *Pdz, float *dw, float *db, const Geo &g,
-                      int cin, int cout, void *ws, hipStream_t s);
+                      int cin, int cout, void *ws, hipStream_t s, const void *Px2 = nullptr, int ca = 0);
 
 // Division of a 32-bit index by a launch-time constant without the ~25-instruction software divide:
 // multiply-high by a precomputed reciprocal, with the one-bit-wider "add" form where the 32-bit

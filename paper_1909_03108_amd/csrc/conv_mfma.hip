@@ -64,9 +64,13 @@ enum Mode { kSingle = 0,   // only chunk: bias, ReLU, store bf16
 
 struct ConvArgs {
     const uint16_t *in;     // input tensor; this launch reads channels [in_co, in_co + 32) of in_cs
+    const uint16_t *in2;    // pair kernel: tensor, channels per voxel and offset of the pair's second chunk
+    int in2_cs, in2_co;     //   (the same tensor 32 channels further on, or a second input tensor)
     const uint4 *wpack;     // fragments of this input chunk: [nco][27][2][64] x 16 bytes
     const float *bias;      // bias of all output channels or NULL
     uint16_t *out;          // output tensor (out_cs channels per voxel)
+    uint16_t *out2;         // optional second output tensor (out2_cs channels per voxel): output channels
+    int out_ca, out2_cs;    //   [out_ca, ko) go there, [0, out_ca) to `out`; partial sums are split alike
     const uint16_t *mask;   // RELU == 2: tensor laid out like `out`; results are zeroed where it is not positive
     float *part;            // fp32 partial sums, indexed like `out`
     Geo g;
@@ -103,6 +107,16 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
     union { bf16x2 v; uint32_t u; } r;
     r.v = __builtin_convertvector(f32x2{a, b}, bf16x2);
     return r.u;
+}
+
+// Where output block cj goes: tensor, its channels per voxel, channel offset, and the offset of that tensor's
+// part of the fp32 partial-sum buffer (the buffer holds one region per output tensor, each laid out like it).
+struct OutDst { uint16_t *base; int cs, co; size_t part_off; };
+__device__ __forceinline__ OutDst out_dest(const ConvArgs &a, int cj) {
+    if (a.out2 && C * cj >= a.out_ca)
+        return OutDst{a.out2, a.out2_cs, C * cj - a.out_ca,
+                      static_cast<size_t>(a.g.ntiles) * a.g.tile_vox * a.out_cs};
+    return OutDst{a.out, a.out_cs, C * cj, 0};
 }
 
 // What happens to a finished output value (template parameter RELU of the kernels below).
@@ -307,14 +321,15 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
         c.goff[j] = (row * g.pw + colv) * a.in_cs + wave * 8;
     }
     c.lds_stage = lds + wave * CH_STRIDE;
-    c.orow = static_cast<size_t>(g.pw) * a.out_cs;
+    const OutDst od = out_dest(a, cj);
+    c.orow = static_cast<size_t>(g.pw) * od.cs;
     c.oplane = static_cast<size_t>(g.ph) * c.orow;
-    const size_t opos = static_cast<size_t>(tile) * g.tile_vox * a.out_cs +
-                        ((static_cast<size_t>(d0 + 1) * g.ph + h0 + wave * RH + 1) * g.pw + w0 + col + 1) * a.out_cs +
-                        C * cj + 4 * hi;
-    c.obase = a.out + opos;
+    const size_t opos = static_cast<size_t>(tile) * g.tile_vox * od.cs +
+                        ((static_cast<size_t>(d0 + 1) * g.ph + h0 + wave * RH + 1) * g.pw + w0 + col + 1) * od.cs +
+                        od.co + 4 * hi;
+    c.obase = od.base + opos;
     c.mbase = a.mask + opos;
-    c.pbase = a.part + opos;
+    c.pbase = a.part + od.part_off + opos;
 #pragma unroll
     for (int h = 0; h < RH; ++h) c.okrow[h] = h0 + wave * RH + h < g.th && w0 + col < g.tw;
     // the bias is folded into the accumulators: a slot starts from the bias instead of zero
@@ -660,27 +675,30 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int tile, int 
     }
 
     Ctx<HAS_BIAS> c;
-    c.plane_elems = static_cast<size_t>(g.ph) * g.pw * a.in_cs;
-    c.tin0 = a.in + static_cast<size_t>(tile) * g.tile_vox * a.in_cs + d0 * c.plane_elems + a.in_co + C * ROLE;
+    const uint16_t *src = ROLE ? a.in2 : a.in;
+    const int src_cs = ROLE ? a.in2_cs : a.in_cs, src_co = ROLE ? a.in2_co : a.in_co;
+    c.plane_elems = static_cast<size_t>(g.ph) * g.pw * src_cs;
+    c.tin0 = src + static_cast<size_t>(tile) * g.tile_vox * src_cs + d0 * c.plane_elems + src_co;
     c.nplanes = dn + 2;
     // this wave fills chunk planes 2 rg and 2 rg + 1 (channels 16 rg .. 16 rg + 15) of its input chunk
 #pragma unroll
     for (int j = 0; j < LOADS; ++j) {
         const int v = 64 * (j % CP_LOADS) + lane;
         const int row = min(h0 + v / LCOLS, g.ph - 1), colv = min(w0 + v % LCOLS, g.pw - 1);
-        c.goff[j] = (row * g.pw + colv) * a.in_cs + (2 * rg + j / CP_LOADS) * 8;      // clamped: always addressable
+        c.goff[j] = (row * g.pw + colv) * src_cs + (2 * rg + j / CP_LOADS) * 8;       // clamped: always addressable
     }
     c.tail_lane = 64 * (CP_LOADS - 1) + lane < PLANE_VOX;
     c.lds_stage = lds + ROLE * CHUNK_BYTES + 2 * rg * CH_STRIDE;
     c.red = lds + RING_BYTES + rg * (RH * 4 * 1024) + lane * 16;
-    c.orow = static_cast<size_t>(g.pw) * a.out_cs;
+    const OutDst od = out_dest(a, cj);
+    c.orow = static_cast<size_t>(g.pw) * od.cs;
     c.oplane = static_cast<size_t>(g.ph) * c.orow;
-    const size_t opos = static_cast<size_t>(tile) * g.tile_vox * a.out_cs +
-                        ((static_cast<size_t>(d0 + 1) * g.ph + h0 + rg * RH + 1) * g.pw + w0 + col + 1) * a.out_cs +
-                        C * cj + 4 * hi;
-    c.obase = a.out + opos;
+    const size_t opos = static_cast<size_t>(tile) * g.tile_vox * od.cs +
+                        ((static_cast<size_t>(d0 + 1) * g.ph + h0 + rg * RH + 1) * g.pw + w0 + col + 1) * od.cs +
+                        od.co + 4 * hi;
+    c.obase = od.base + opos;
     c.mbase = a.mask + opos;
-    c.pbase = a.part + opos;
+    c.pbase = a.part + od.part_off + opos;
 #pragma unroll
     for (int h = 0; h < RH; ++h) c.okrow[h] = h0 + rg * RH + h < g.th && w0 + col < g.tw;
     if (HAS_BIAS) {
@@ -796,7 +814,8 @@ size_t conv_mfma_ws_bytes(const Geo &g, int ki, int ko) {
 }
 
 int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Pout, const Geo &g,
-                     int ki, int ko, bool relu, bool dgrad, void *ws, hipStream_t s, const void *mask) {
+                     int ki, int ko, bool relu, bool dgrad, void *ws, hipStream_t s, const void *mask,
+                     const ConvSplit *split) {
     const int nci = ki / C, nco = ko / C;
     const int pack_elems = nci * nco * NFRAG * 64 * 8;
     hipLaunchKernelGGL(pack_weights_kernel, dim3((pack_elems + 255) / 256), dim3(256), 0, s,
@@ -807,12 +826,34 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
     a.in = static_cast<const uint16_t *>(Pin);
     a.bias = bias;
     a.out = static_cast<uint16_t *>(Pout);
+    a.out2 = nullptr;
+    a.out_ca = ko;
+    a.out2_cs = 0;
+    // two-tensor input: kernel channels [0, in_ca) come from Pin (in_ca per voxel), the rest from split->in2
+    const uint16_t *in_a = static_cast<const uint16_t *>(Pin), *in_b = nullptr;
+    int in_ca = ki;
+    if (split && split->in2) {
+        in_b = static_cast<const uint16_t *>(split->in2);
+        in_ca = split->in_ca;
+    }
+    if (split && split->out2) {
+        a.out2 = static_cast<uint16_t *>(split->out2);
+        a.out_ca = split->out_ca;
+        a.out2_cs = ko - split->out_ca;
+    }
+    // channels per voxel of the first output tensor (the whole output if there is no second one)
+    const int out_cs_a = a.out2 ? a.out_ca : ko;
     a.mask = static_cast<const uint16_t *>(mask);
     a.part = reinterpret_cast<float *>(static_cast<char *>(ws) + pack_bytes(ki, ko));
     a.g = g;
-    a.in_cs = ki;
-    a.out_cs = ko;
+    a.out_cs = out_cs_a;
     a.nco = nco;
+    // source of input chunk c (32 channels from channel 32 c of the concatenated input)
+    auto chunk_src = [&](int cchunk, const uint16_t **base, int *cs, int *co) {
+        const int c0 = C * cchunk;
+        if (in_b && c0 >= in_ca) { *base = in_b; *cs = ki - in_ca; *co = c0 - in_ca; }
+        else { *base = in_a; *cs = in_b ? in_ca : ki; *co = c0; }
+    };
     // input channels in multiples of 64: two chunks per launch, summed on chip (4-row patches)
     const bool pairs = ki % (2 * C) == 0;
     const int ph = pairs ? wide::PH : PH;
@@ -860,7 +901,8 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
     const int nsteps = pairs ? nci / 2 : nci;          // launches: input chunks, or pairs of them
     for (int ci = 0; ci < nsteps; ++ci) {
         const int mode = nsteps == 1 ? kSingle : (ci == 0 ? kFirst : (ci == nsteps - 1 ? kLast : kMiddle));
-        a.in_co = (pairs ? 2 * C : C) * ci;
+        chunk_src(pairs ? 2 * ci : ci, &a.in, &a.in_cs, &a.in_co);
+        if (pairs) chunk_src(2 * ci + 1, &a.in2, &a.in2_cs, &a.in2_co);
         a.wpack = static_cast<const uint4 *>(ws) + static_cast<size_t>(pairs ? 2 * ci : ci) * nco * NFRAG * 64;
         if (pairs)
             hipLaunchKernelGGL(kern2[mode][bias ? 1 : 0][epi], dim3(grid), dim3(kThreads), wide::LDS_BYTES, s, a);

@@ -48,12 +48,14 @@ static_assert(kThreads * 8 * 4 <= LDS_BYTES, "bias reduction scratch must fit");
 constexpr int kMaxGroups = 256;               // workgroups (= partial results); one per CU
 
 struct WgradArgs {
-    const uint16_t *x;
+    const uint16_t *x;       // input tensor holding the first x_ca input channels (all of them if x2 is null)
+    const uint16_t *x2;      // tensor holding the remaining input channels (x2_cs per voxel), or null
     const uint16_t *dz;
     float *part_w;        // [ngroups][27][32][32]
     float *part_b;        // [ngroups][32]
     Geo g;
     int x_cs, dz_cs;      // channels per voxel of x and dz
+    int x_ca, x2_cs;      // two-tensor input: channels [0, x_ca) come from x, [x_ca, cin) from x2
     int nco;              // output blocks; pair p = (input chunk p / nco, output block p % nco)
     int gpp;              // workgroups per pair
     int dchunk, nd, nh, nw;
@@ -62,6 +64,13 @@ struct WgradArgs {
 };
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+// Where input channels [ci0, ci0 + 32) live: tensor base, its channels per voxel and the offset inside it.
+struct XSrc { const uint16_t *base; int cs, co; };
+__device__ __forceinline__ XSrc x_source(const WgradArgs &a, int ci0) {
+    if (a.x2 && ci0 >= a.x_ca) return XSrc{a.x2, a.x2_cs, ci0 - a.x_ca};
+    return XSrc{a.x, a.x_cs, ci0};
+}
 
 // Transposing LDS read of one MFMA operand half: 16 voxels x 16 channels -> 4 voxels per lane.
 __device__ __forceinline__ s16x4 tr_read(const char *p) {
@@ -137,7 +146,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
     const int group = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (group >= a.ngroups) return;
     const int pair = group / a.gpp, gsub = group % a.gpp;
-    const int x_co = C * (pair / a.nco), dz_co = C * (pair % a.nco);   // channel offsets of this pair
+    const XSrc xs = x_source(a, C * (pair / a.nco));
+    const int x_co = xs.co, dz_co = C * (pair % a.nco);   // channel offsets of this pair
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int qi = (wave >> 1) & 1, qo = wave & 1;   // ci half, co half of this wave's quadrant
     const int kg = wave >> 2;                         // row group: dz rows [GR*kg, GR*kg + GR)
@@ -168,8 +178,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) bsum[j] = 0.f;
 
-    const size_t xplane = static_cast<size_t>(g.ph) * g.pw * a.x_cs, zplane = static_cast<size_t>(g.ph) * g.pw * a.dz_cs;
-    const int xrow_elems = g.pw * a.x_cs, zrow_elems = g.pw * a.dz_cs;
+    const size_t xplane = static_cast<size_t>(g.ph) * g.pw * xs.cs, zplane = static_cast<size_t>(g.ph) * g.pw * a.dz_cs;
+    const int xrow_elems = g.pw * xs.cs, zrow_elems = g.pw * a.dz_cs;
 
     for (int item = gsub; item < a.nitems; item += a.gpp) {
         int t = item;
@@ -179,12 +189,12 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
         const int tile = t;
         const int d0 = pd_i * a.dchunk, h0 = ph_i * PH, w0 = pw_i * PW;
         const int dn = min(a.dchunk, g.td - d0);
-        const uint16_t *tx = a.x + static_cast<size_t>(tile) * g.tile_vox * a.x_cs + x_co;
+        const uint16_t *tx = xs.base + static_cast<size_t>(tile) * g.tile_vox * xs.cs + x_co;
         const uint16_t *tz = a.dz + static_cast<size_t>(tile) * g.tile_vox * a.dz_cs + dz_co;
 
         // source offsets inside a plane and validity (x: inside the padded tile; dz: tile interior)
-        const int xsrc0 = ((h0 + sr) * g.pw + w0 + sv) * a.x_cs + c4 * 8;
-        const int xsrce = ((h0 + er) * g.pw + w0 + ev) * a.x_cs + c4 * 8;
+        const int xsrc0 = ((h0 + sr) * g.pw + w0 + sv) * xs.cs + c4 * 8;
+        const int xsrce = ((h0 + er) * g.pw + w0 + ev) * xs.cs + c4 * 8;
         const int zsrc0 = ((h0 + sr + 1) * g.pw + w0 + sv + 1) * a.dz_cs + c4 * 8;
         bool xok[3], zok[2];
 #pragma unroll
@@ -404,7 +414,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_dma_kernel(WgradArgs a) {
     const int group = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (group >= a.ngroups) return;
     const int pair = group / a.gpp, gsub = group % a.gpp;
-    const int x_co = C * (pair / a.nco), dz_co = C * (pair % a.nco);
+    const XSrc xs = x_source(a, C * (pair / a.nco));
+    const int x_co = xs.co, dz_co = C * (pair % a.nco);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform: scalar control flow below
     // Waves w and w + 4 share a SIMD: give them different ci halves, so that each SIMD hosts exactly one
@@ -430,7 +441,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_dma_kernel(WgradArgs a) {
         const int u = j < 2 ? 2 * wave + j : (wave < 6 ? 16 + wave : 2 * wave + 1);
         const int half = u / XG, vg = u % XG;
         const int v = min(vg * 32 + (lane >> 1), XVOX - 1);
-        gx[j] = ((v / XC) * g.pw + v % XC) * a.x_cs + half * 16 + (lane & 1) * 8;
+        gx[j] = ((v / XC) * g.pw + v % XC) * xs.cs + half * 16 + (lane & 1) * 8;
         lx[j] = half * XD_HALF + vg * 1024;
     }
 #pragma unroll
@@ -447,7 +458,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_dma_kernel(WgradArgs a) {
     for (int t = 0; t < 27; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
     f32x4 accb = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const size_t xplane = static_cast<size_t>(g.ph) * g.pw * a.x_cs, zplane = static_cast<size_t>(g.ph) * g.pw * a.dz_cs;
+    const size_t xplane = static_cast<size_t>(g.ph) * g.pw * xs.cs, zplane = static_cast<size_t>(g.ph) * g.pw * a.dz_cs;
 
     for (int item = gsub; item < a.nitems; item += a.gpp) {
         int t = item;
@@ -458,8 +469,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_dma_kernel(WgradArgs a) {
         const int d0 = pd_i * a.dchunk, h0 = ph_i * PH, w0 = pw_i * PW;
         const int dn = min(a.dchunk, g.td - d0);
         // padded plane d0 of the tile, at the patch's first voxel and the pair's channels
-        const uint16_t *tx = a.x + (static_cast<size_t>(tile) * g.tile_vox + static_cast<size_t>(d0) * g.ph * g.pw +
-                                    h0 * g.pw + w0) * a.x_cs + x_co;
+        const uint16_t *tx = xs.base + (static_cast<size_t>(tile) * g.tile_vox + static_cast<size_t>(d0) * g.ph * g.pw +
+                                        h0 * g.pw + w0) * xs.cs + x_co;
         const uint16_t *tz = a.dz + (static_cast<size_t>(tile) * g.tile_vox + static_cast<size_t>(d0 + 1) * g.ph * g.pw +
                                      h0 * g.pw + w0) * a.dz_cs + dz_co;
 
@@ -609,10 +620,13 @@ size_t wgrad_mfma_ws_bytes(const Geo &g, int cin, int cout) {
 }
 
 int launch_wgrad_mfma(const void *Px, const void *Pdz, float *dw, float *db, const Geo &g, int cin, int cout,
-                      void *ws, hipStream_t s) {
+                      void *ws, hipStream_t s, const void *Px2, int ca) {
     WgradArgs a;
     plan(g, cin, cout, &a);
     a.x = static_cast<const uint16_t *>(Px);
+    a.x2 = static_cast<const uint16_t *>(Px2);
+    if (Px2) { a.x_cs = ca; a.x_ca = ca; a.x2_cs = cin - ca; }
+    else { a.x_ca = cin; a.x2_cs = 0; }
     a.dz = static_cast<const uint16_t *>(Pdz);
     a.part_w = static_cast<float *>(ws);
     a.part_b = a.part_w + static_cast<size_t>(a.ngroups) * 27 * C * C;

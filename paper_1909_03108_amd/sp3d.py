@@ -16,7 +16,8 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsp3d.so"
 EXPORTS = ["sp_padded_elems", "sp_msg_elems", "sp_workspace_bytes", "sp_check_geom", "sp_strerror",
            "sp_last_hip_error", "sp_partition", "sp_unpartition", "halo_pack", "halo_unpack",
            "sp_halo_exchange",
-           "conv3d_fwd", "conv3d_dgrad", "conv3d_dgrad_relu", "conv3d_wgrad", "sp_relu_bwd",
+           "conv3d_fwd", "conv3d_dgrad", "conv3d_dgrad_relu", "conv3d_wgrad", "conv3d_fwd2", "conv3d_dgrad2",
+           "conv3d_wgrad2", "sp_relu_bwd",
            "sp_maxpool2_fwd", "sp_maxpool2_bwd", "sp_upconv2_fwd", "sp_upconv2_dgrad", "sp_upconv2_wgrad",
            "sp_pointwise_fwd", "sp_pointwise_dgrad", "sp_pointwise_wgrad", "sp_concat", "sp_split", "sp_add"]
 
@@ -72,6 +73,9 @@ def lib():
         L.conv3d_dgrad.argtypes, L.conv3d_dgrad.restype = [P, P, P, G, I, I, I, P, Z, P], I
         L.conv3d_dgrad_relu.argtypes, L.conv3d_dgrad_relu.restype = [P, P, P, P, G, I, I, I, P, Z, P], I
         L.conv3d_wgrad.argtypes, L.conv3d_wgrad.restype = [P, P, P, P, G, I, I, I, P, Z, P], I
+        L.conv3d_fwd2.argtypes, L.conv3d_fwd2.restype = [P, I, P, I, P, P, P, G, I, I, U, P, Z, P], I
+        L.conv3d_dgrad2.argtypes, L.conv3d_dgrad2.restype = [P, P, P, I, P, I, G, I, I, P, Z, P], I
+        L.conv3d_wgrad2.argtypes, L.conv3d_wgrad2.restype = [P, I, P, I, P, P, P, G, I, I, P, Z, P], I
         L.sp_relu_bwd.argtypes, L.sp_relu_bwd.restype = [P, P, P, G, I, I, P], I
         L.sp_maxpool2_fwd.argtypes, L.sp_maxpool2_fwd.restype = [P, P, G, I, I, P], I
         L.sp_maxpool2_bwd.argtypes, L.sp_maxpool2_bwd.restype = [P, P, P, G, I, I, P], I
@@ -170,6 +174,24 @@ def conv3d_dgrad_relu(Pdz, w, Px, Pdx, g, cin, cout, dt, ws=None, stream=None):
     wp, wb = _ws(ws)
     _check(lib().conv3d_dgrad_relu(_ptr(Pdz), _ptr(w), _ptr(Px), _ptr(Pdx), ctypes.byref(g), cin, cout, dt, wp, wb,
                                    _stream(stream)), "conv3d_dgrad_relu")
+
+
+def conv3d_fwd2(Pxa, ca, Pxb, cb, w, bias, Py, g, cout, dt, flags=0, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib().conv3d_fwd2(_ptr(Pxa), ca, _ptr(Pxb), cb, _ptr(w), _ptr(bias), _ptr(Py), ctypes.byref(g), cout, dt,
+                             flags, wp, wb, _stream(stream)), "conv3d_fwd2")
+
+
+def conv3d_dgrad2(Pdz, w, Pdxa, ca, Pdxb, cb, g, cout, dt, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib().conv3d_dgrad2(_ptr(Pdz), _ptr(w), _ptr(Pdxa), ca, _ptr(Pdxb), cb, ctypes.byref(g), cout, dt, wp, wb,
+                               _stream(stream)), "conv3d_dgrad2")
+
+
+def conv3d_wgrad2(Pxa, ca, Pxb, cb, Pdz, dw, db, g, cout, dt, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib().conv3d_wgrad2(_ptr(Pxa), ca, _ptr(Pxb), cb, _ptr(Pdz), _ptr(dw), _ptr(db), ctypes.byref(g), cout, dt,
+                               wp, wb, _stream(stream)), "conv3d_wgrad2")
 
 
 def conv3d_wgrad(Px, Pdz, dw, db, g, cin, cout, dt, ws=None, stream=None):

@@ -74,6 +74,10 @@ class UNet:
             self.ws_cache["buf"] = cur
         return cur
 
+    def _two_tensor(self, c):
+        """the two-tensor convolution entry points need bf16 and channel counts in multiples of 32"""
+        return self.dt == sp3d.SP_BF16 and c % 32 == 0
+
     def _exchange(self, P, g, c):
         """All tiles share this GPU's memory, so margins are filled straight from the neighbours' interiors."""
         sp3d.sp_halo_exchange(P, g, c, self.dt)
@@ -85,10 +89,21 @@ class UNet:
                         self._ws(sp3d.SP_OP_FWD, g, cin, cout))
         return Py
 
-    def _block_fwd(self, block, P, g, cin, c, A):
-        """`convs` conv + ReLU layers; saves every layer input (with halos) and the block output in A."""
+    def _block_fwd(self, block, P, g, cin, c, A, P2=None):
+        """`convs` conv + ReLU layers; saves every layer input (with halos) and the block output in A.
+        With P2 the block input is concat(P, P2) (cin / 2 channels each), never materialised."""
         for k in range(self.convs):
             name = "%s_%s" % (block, LETTERS[k])
+            if k == 0 and P2 is not None:
+                ca = cin // 2
+                self._exchange(P, g, ca)
+                self._exchange(P2, g, ca)
+                A[name + ".x"] = (P, P2)
+                Py = self._buf(name + ".y", g, c)
+                sp3d.conv3d_fwd2(P, ca, P2, ca, self.w[name], None, Py, g, c, self.dt, sp3d.SP_FLAG_RELU,
+                                 self._ws(sp3d.SP_OP_FWD, g, cin, c))
+                P = Py
+                continue
             self._exchange(P, g, cin if k == 0 else c)
             A[name + ".x"] = P
             P = self._conv(P, name, g, cin if k == 0 else c, c)
@@ -138,9 +153,12 @@ class UNet:
             A["up%d.x" % i] = P
             Pu = self._buf("up%d.y" % i, g, c)
             sp3d.sp_upconv2_fwd(P, self.w["up%d" % i], None, Pu, g, prev, c, dt)
-            Pc = self._buf("cat%d" % i, g, 2 * c)
-            sp3d.sp_concat(A["enc%d.y" % i], c, Pu, c, Pc, g, dt)
-            P = self._block_fwd("dec%d" % i, Pc, g, 2 * c, c, A)
+            if self._two_tensor(c):                  # convolve concat(skip, up) without building it
+                P = self._block_fwd("dec%d" % i, A["enc%d.y" % i], g, 2 * c, c, A, P2=Pu)
+            else:
+                Pc = self._buf("cat%d" % i, g, 2 * c)
+                sp3d.sp_concat(A["enc%d.y" % i], c, Pu, c, Pc, g, dt)
+                P = self._block_fwd("dec%d" % i, Pc, g, 2 * c, c, A)
             prev = c
         A["head.x"] = P
         Pl = self._buf("logits", self.g[0], self.classes)
@@ -160,6 +178,17 @@ class UNet:
         if not masked:
             sp3d.sp_relu_bwd(Pdy, Py, Pdy, g, cout, dt)               # dz in place
         dw = torch.empty((3, 3, 3, cin, cout), dtype=torch.float32, device="cuda")
+        if isinstance(Px, tuple):                 # x = concat(Px[0], Px[1]): gradients go to two tensors
+            ca = cin // 2
+            sp3d.conv3d_wgrad2(Px[0], ca, Px[1], ca, Pdy, dw, None, g, cout, dt,
+                               self._ws(sp3d.SP_OP_WGRAD, g, cin, cout))
+            grads[name] = dw
+            self._exchange(Pdy, g, cout)
+            Pa, Pb = self._tmp(g, ca), self._tmp(g, ca)
+            sp3d.conv3d_dgrad2(Pdy, self.w[name], Pa, ca, Pb, ca, g, cout, dt,
+                               self._ws(sp3d.SP_OP_DGRAD, g, cin, cout))
+            self._release(Pdy, g, cout)
+            return (Pa, Pb)
         sp3d.conv3d_wgrad(Px, Pdy, dw, None, g, cin, cout, dt, self._ws(sp3d.SP_OP_WGRAD, g, cin, cout))
         grads[name] = dw
         Pdx = None
@@ -194,9 +223,12 @@ class UNet:
             g, c = self.g[i], ch[i]
             up_in = ch[i + 1]
             Pg = self._block_bwd("dec%d" % i, Pg, g, 2 * c, c, grads)          # gradient of concat(skip, up)
-            Ps, Pu = self._tmp(g, c), self._tmp(g, c)
-            sp3d.sp_split(Pg, Ps, c, Pu, c, g, dt)
-            self._release(Pg, g, 2 * c)
+            if isinstance(Pg, tuple):
+                Ps, Pu = Pg
+            else:
+                Ps, Pu = self._tmp(g, c), self._tmp(g, c)
+                sp3d.sp_split(Pg, Ps, c, Pu, c, g, dt)
+                self._release(Pg, g, 2 * c)
             skip_grad[i] = Ps
             du = torch.empty((2, 2, 2, up_in, c), dtype=torch.float32, device="cuda")
             sp3d.sp_upconv2_wgrad(A["up%d.x" % i], Pu, du, None, g, up_in, c, dt,

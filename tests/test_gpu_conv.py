@@ -192,3 +192,60 @@ def test_dgrad_with_relu_mask_equals_dgrad_then_mask(n, dhw, grid, cin, cout, dt
     expect = torch.where(to_dev(xr).float() > 0, plain, torch.zeros_like(plain))
     assert torch.equal(fused, expect)
     assert rel_err(f64(fused), np.where(widen(xr) > 0, conv3d.conv3d_dgrad(dz, widen(w)), 0.0)) <= TOL[dtype]
+
+
+SPLIT = [  # n, dhw, grid, ca, cb, cout
+    (1, (8, 8, 64), (2, 1, 1), 32, 32, 32),       # one pair whose two chunks come from different tensors
+    (1, (6, 12, 40), (1, 2, 1), 64, 64, 64),      # two pairs, one per tensor; ragged patches
+    (1, (4, 8, 32), (1, 1, 1), 32, 64, 32),       # 96 input channels: one chunk per launch, three launches
+    (2, (4, 4, 32), (2, 1, 1), 128, 128, 64),     # four pairs, batch 2
+]
+
+
+@pytest.mark.parametrize("n,dhw,grid,ca,cb,cout", SPLIT)
+def test_two_tensor_variants_equal_concat_bit_for_bit(n, dhw, grid, ca, cb, cout):
+    """conv3d_fwd2 / conv3d_dgrad2 / conv3d_wgrad2 work on concat(a, b) without materialising it: same bits as
+    concatenating (or splitting) on the device and calling the single-tensor entry points."""
+    g = sp3d.Geom(n, dhw, grid)
+    dt, cin = sp3d.SP_BF16, ca + cb
+    L = Layer(n, dhw, grid, cin, cout, "bf16")
+    xa, xb = draw("bf16", (n,) + dhw + (ca,), 31), draw("bf16", (n,) + dhw + (cb,), 32)
+    dz = draw("bf16", (n,) + dhw + (cout,), 33)
+    w_h = synth.weights(cin, cout, 34, "bf16")
+    w = to_dev(w_h)
+    Pa, Pb, Pz = L.padded(xa, ca), L.padded(xb, cb), L.padded(dz, cout)
+    Pc = sp3d.alloc_padded(g, cin, dt)
+    sp3d.sp_concat(Pa, ca, Pb, cb, Pc, g, dt)
+    ws = {op: sp3d.alloc_ws(sp3d.sp_workspace_bytes(op, g, cin, cout, dt)) for op in (0, 1, 2)}
+    bias = torch.linspace(-0.5, 0.5, cout, device="cuda")
+    # forward
+    y1, y2 = sp3d.alloc_padded(g, cout, dt), sp3d.alloc_padded(g, cout, dt)
+    sp3d.conv3d_fwd(Pc, w, bias, y1, g, cin, cout, dt, sp3d.SP_FLAG_RELU, ws[0])
+    sp3d.conv3d_fwd2(Pa, ca, Pb, cb, w, bias, y2, g, cout, dt, sp3d.SP_FLAG_RELU, ws[0])
+    assert torch.equal(y1, y2)
+    ref = conv3d.conv3d_fwd(np.concatenate([xa, xb], axis=-1), widen(w_h), bias.double().cpu().numpy(), True)
+    assert rel_err(f64(L.volume(y2, cout)), ref) <= TOL["bf16"]
+    # data gradient into two tensors
+    dc = sp3d.alloc_padded(g, cin, dt)
+    sp3d.conv3d_dgrad(Pz, w, dc, g, cin, cout, dt, ws[1])
+    da, db_ = sp3d.alloc_padded(g, ca, dt), sp3d.alloc_padded(g, cb, dt)
+    sp3d.conv3d_dgrad2(Pz, w, da, ca, db_, cb, g, cout, dt, ws[1])
+    ea, eb = sp3d.alloc_padded(g, ca, dt), sp3d.alloc_padded(g, cb, dt)
+    sp3d.sp_split(dc, ea, ca, eb, cb, g, dt)
+    assert torch.equal(L.volume(da, ca), L.volume(ea, ca)) and torch.equal(L.volume(db_, cb), L.volume(eb, cb))
+    # weight gradient
+    dw1 = torch.empty((3, 3, 3, cin, cout), dtype=torch.float32, device="cuda")
+    dw2, b1, b2 = torch.empty_like(dw1), torch.empty(cout, device="cuda"), torch.empty(cout, device="cuda")
+    sp3d.conv3d_wgrad(Pc, Pz, dw1, b1, g, cin, cout, dt, ws[2])
+    sp3d.conv3d_wgrad2(Pa, ca, Pb, cb, Pz, dw2, b2, g, cout, dt, ws[2])
+    assert torch.equal(dw1, dw2) and torch.equal(b1, b2)
+
+
+def test_two_tensor_variants_reject_what_they_cannot_do():
+    g = sp3d.Geom(1, (4, 4, 8), (1, 1, 1))
+    a = sp3d.alloc_padded(g, 16, sp3d.SP_BF16)
+    y = sp3d.alloc_padded(g, 32, sp3d.SP_BF16)
+    w = torch.zeros((3, 3, 3, 32, 32), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sp3d.Sp3dError) as e:
+        sp3d.conv3d_fwd2(a, 16, a, 16, w, None, y, g, 32, sp3d.SP_BF16, 0, None)
+    assert e.value.code == sp3d.SP_EUNSUPPORTED
