@@ -44,6 +44,9 @@ def parse():
                          "stack of the workload list (256^3, channels 32/64/128/256), forward + backward; "
                          "paper512 = the network the paper trains at 512^3 (six blocks of four convolutions, "
                          "32 ... 1024 filters), forward + backward, all 16 tiles in this GPU's HBM")
+    ap.add_argument("--loss", action="store_true",
+                    help="U-Net workloads: compute the upstream gradient with sp_dice_ce_loss on seeded labels "
+                         "instead of the N(0,1) stand-in of the workload list (adds the loss passes to the step)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (torch copy_) so that profiler "
                          "byte counters can be scaled against a kernel of known traffic")
@@ -77,9 +80,18 @@ def bench_unet(args):
     dl = dev(synth.normal_volume((n,) + dhw + (classes,), synth.seed_for(5, synth.T_UPSTREAM), "bf16"))
     net = unet.UNet(n, dhw, grid, w, channels, in_ch, classes, convs=convs)
 
+    labels = None
+    if args.loss:
+        lab = np.random.default_rng(synth.seed_for(5, synth.T_UPSTREAM)).integers(0, classes, size=(n,) + dhw + (1,))
+        labels = dev(synth.f32_to_bf16_bits(lab.astype(np.float32)))
+
     def step():
         net.forward(x)
-        net.backward(dl, input_grad=False)
+        if labels is not None:
+            net.loss(labels)
+            net.backward(None, input_grad=False)
+        else:
+            net.backward(dl, input_grad=False)
 
     for _ in range(args.warmup):
         step()
@@ -108,7 +120,8 @@ def bench_unet(args):
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": name + ", grid 4x4x1, halo 1, forward + backward (weight and data gradients, "
-                                      "no image gradient)",
+                                      "no image gradient)" + (", upstream gradient from the Dice + CE loss"
+                                                              if args.loss else ""),
                    "tflop_per_step": round(flop / 1e12, 2),
                    "hbm_allocated_gb": round(torch.cuda.max_memory_allocated() / 1e9, 1)}}))
 

@@ -63,7 +63,8 @@ enum { SP_FLAG_RELU = 1 };                                /* conv3d_fwd: y = max
 enum {                                                    /* sp_workspace_bytes `op`   */
     SP_OP_FWD = 0, SP_OP_DGRAD = 1, SP_OP_WGRAD = 2,      /* the 3x3x3 convolution     */
     SP_OP_UPCONV_WGRAD = 3,                               /* sp_upconv2_wgrad          */
-    SP_OP_POINTWISE_WGRAD = 4                             /* sp_pointwise_wgrad        */
+    SP_OP_POINTWISE_WGRAD = 4,                            /* sp_pointwise_wgrad        */
+    SP_OP_LOSS = 5                                        /* sp_dice_ce_loss: cin = classes, cout = 1 */
 };
 
 /* ---- host-only helpers (no GPU needed) --------------------------------------------------- */
@@ -210,6 +211,21 @@ int sp_split(const void *Pin, void *Pa, int ca, void *Pb, int cb, const sp_geom_
  * at a skip connection); fp32 addition, one rounding to the tensor dtype.  Pout may alias Pa or Pb. */
 int sp_add(const void *Pa, const void *Pb, void *Pout, const sp_geom_t *g, int c, sp_dtype_t dt,
            void *stream);
+
+/* ---- loss (Sec. 3, training set-up: 0.9 x Dice + 0.1 x cross-entropy; the paper gives no formula,
+ *      the soft form of both terms is used) --------------------------------------------------------
+ * p[v,:] = softmax of the logits of voxel v;  y = one-hot label;  V = all interior voxels of all tiles.
+ *   Dice_c = (2 sum_v p[v,c] y[v,c] + eps) / (sum_v p[v,c] + sum_v y[v,c] + eps)
+ *   loss   = w_dice (1 - mean_c Dice_c) - w_ce (1/V) sum_v log p[v, label v]
+ * Plogits [..][classes] padded tiles; Plabels [..][1] padded tiles of the same dtype holding the class
+ * index of every voxel (values outside [0, classes) are clamped); only interiors are read.
+ * Outputs (each may be NULL, not all): Pdlogits [..][classes] = d loss / d logits, interiors written;
+ * loss = 1 float; stats = 3*classes + 1 floats: sum p y, sum p, sum y per class, then -sum log p[label]
+ * (the cross-tile sums; taken in a fixed order, so reproducible).  loss and stats are device pointers.
+ * classes 2..4.  Workspace: sp_workspace_bytes(SP_OP_LOSS, g, classes, 1, dt). */
+int sp_dice_ce_loss(const void *Plogits, const void *Plabels, void *Pdlogits, float *loss, float *stats,
+                    const sp_geom_t *g, int classes, sp_dtype_t dt, float w_dice, float w_ce, float eps,
+                    void *ws, size_t ws_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -113,6 +113,8 @@ size_t sp_workspace_bytes(int op, const sp_geom_t *g, int cin, int cout, sp_dtyp
         if (make_coarse(o, &c) != SP_OK) return static_cast<size_t>(-1);
         return upconv2_wgrad_ws_bytes(o, c, cin, cout, dt);
     }
+    case SP_OP_LOSS:
+        return loss_supported(o, cin) ? loss_ws_bytes(o, cin) : static_cast<size_t>(-1);
     case SP_OP_POINTWISE_WGRAD:
         return pointwise_small_supported(o, cin, cout, dt) ? pointwise_small_wgrad_ws_bytes(o, cin, cout)
                                                            : wgrad_direct_ws_bytes(o, cin, cout, 1);
@@ -441,6 +443,26 @@ int sp_pointwise_wgrad(const void *Px, const void *Pdy, float *dp, float *db, co
     if (small)
         return launch_pointwise_small_wgrad(Px, Pdy, dp, db, o, cin, cout, ws, static_cast<hipStream_t>(stream));
     return launch_wgrad_direct(Px, Pdy, dp, db, o, cin, cout, dt, ws, static_cast<hipStream_t>(stream), 1);
+}
+
+int sp_dice_ce_loss(const void *Plogits, const void *Plabels, void *Pdlogits, float *loss, float *stats,
+                    const sp_geom_t *g, int classes, sp_dtype_t dt, float w_dice, float w_ce, float eps, void *ws,
+                    size_t ws_bytes, void *stream) {
+    if (!Plogits || !Plabels || (!Pdlogits && !loss && !stats)) return SP_EINVAL;
+    Geo o;
+    int rc = make_geo(g, &o);
+    if (rc != SP_OK) return rc;
+    if (!dtype_ok(dt)) return SP_EUNSUPPORTED;
+    if (classes < 2) return SP_EINVAL;
+    if (!loss_supported(o, classes)) return SP_EUNSUPPORTED;
+    if (!aligned16(Plogits) || !aligned16(Plabels) || (Pdlogits && !aligned16(Pdlogits))) return SP_EINVAL;
+    if ((loss && (reinterpret_cast<uintptr_t>(loss) & 3u)) || (stats && (reinterpret_cast<uintptr_t>(stats) & 3u)))
+        return SP_EINVAL;
+    if (!(eps >= 0.f) || !(w_dice >= 0.f) || !(w_ce >= 0.f)) return SP_EINVAL;
+    const size_t need = loss_ws_bytes(o, classes);
+    if (!ws || ws_bytes < need || !aligned16(ws)) return SP_EWORKSPACE;
+    return launch_loss(Plogits, Plabels, Pdlogits, loss, stats, o, classes, dt, w_dice, w_ce, eps, ws,
+                       static_cast<hipStream_t>(stream));
 }
 
 int sp_concat(const void *Pa, int ca, const void *Pb, int cb, void *Pout, const sp_geom_t *g, sp_dtype_t dt,

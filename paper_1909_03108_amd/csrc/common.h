@@ -83,6 +83,11 @@ int launch_pointwise_small_dgrad(const void *Pdy, const void *p, void *Pdx, cons
 size_t pointwise_small_wgrad_ws_bytes(const Geo &g, int cin, int cout);
 int launch_pointwise_small_wgrad(const void *Px, const void *Pdy, float *dp, float *db, const Geo &g, int cin,
                                  int cout, void *ws, hipStream_t s);
+// soft Dice + cross-entropy over the class logits and its gradient (loss_kernels.hip)
+bool loss_supported(const Geo &g, int classes);
+size_t loss_ws_bytes(const Geo &g, int classes);
+int launch_loss(const void *Pz, const void *Plab, void *Pdz, float *loss, float *stats, const Geo &g, int classes,
+                sp_dtype_t dt, float w_dice, float w_ce, float eps, void *ws, hipStream_t s);
 int launch_add(const void *Pa, const void *Pb, void *Pout, size_t elems, sp_dtype_t dt, hipStream_t s);
 int launch_concat(const void *Pa, int ca, const void *Pb, int cb, void *Pc, size_t voxels, sp_dtype_t dt,
                   bool split, hipStream_t s);

@@ -1,0 +1,181 @@
+// Segmentation loss on padded tiles: soft Dice + cross-entropy over the class logits, and its gradient
+// with respect to the logits.  Two passes over the voxels, both bound by HBM traffic (a few bytes per voxel):
+//
+//   pass 1  per class c:  I_c = sum_v p[v,c] y[v,c],  P_c = sum_v p[v,c],  Y_c = sum_v y[v,c];  N = -sum_v log p[v, label v]
+//           p = softmax of the voxel's logits, y = one-hot label.  The sums run over the interiors of ALL tiles
+//           (the cross-tile reduction of the path): per-thread fp32 sums, a fixed tree per block, then the
+//           fixed-order second stage shared with the weight gradients, so the result is reproducible.
+//   pass 2  loss = w_dice (1 - mean_c (2 I_c + eps) / (P_c + Y_c + eps)) + w_ce N / V
+//           dz[v,k] = p_k (g_k - sum_c g_c p_c) + w_ce (p_k - y_k) / V,
+//           g_c = -(w_dice / C) (2 y_c S_c - (2 I_c + eps)) / S_c^2,  S_c = P_c + Y_c + eps
+//
+// Labels are a one-channel padded tensor of the logits' dtype holding the class index of every voxel.
+#include "common.h"
+
+namespace sp3d {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr unsigned kChunk = 4096;         // voxels per block in pass 1
+
+template <typename E> __device__ __forceinline__ float ldv(const E *p, long long i);
+template <> __device__ __forceinline__ float ldv<float>(const float *p, long long i) { return p[i]; }
+template <> __device__ __forceinline__ float ldv<uint16_t>(const uint16_t *p, long long i) { return bf16_to_f32(p[i]); }
+template <typename E> __device__ __forceinline__ void stv(E *p, long long i, float v);
+template <> __device__ __forceinline__ void stv<float>(float *p, long long i, float v) { p[i] = v; }
+template <> __device__ __forceinline__ void stv<uint16_t>(uint16_t *p, long long i, float v) { p[i] = f32_to_bf16(v); }
+
+struct LossGeo {
+    Geo g;
+    unsigned nvox;                 // interior voxels of all tiles
+    FastDiv int_vox, hw, w;
+};
+
+__device__ __forceinline__ long long padded_index(const LossGeo &l, unsigned v) {
+    const unsigned tile = fdiv(v, l.int_vox), r = fmod_(v, tile, l.int_vox);
+    const unsigned ld = fdiv(r, l.hw), q = fmod_(r, ld, l.hw);
+    const unsigned lh = fdiv(q, l.w), lw = fmod_(q, lh, l.w);
+    return tile * l.g.tile_vox + (1LL * (ld + 1) * l.g.ph + lh + 1) * l.g.pw + lw + 1;
+}
+
+// softmax of one voxel; returns the label (clamped into range: the host cannot check every voxel)
+template <typename E, int C>
+__device__ __forceinline__ int voxel_softmax(const E *z, const E *lab, long long pv, float (&p)[C]) {
+    float m = -3.0e38f;
+#pragma unroll
+    for (int c = 0; c < C; ++c) { p[c] = ldv<E>(z, pv * C + c); m = fmaxf(m, p[c]); }
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < C; ++c) { p[c] = __expf(p[c] - m); s += p[c]; }
+    const float inv = 1.f / s;
+#pragma unroll
+    for (int c = 0; c < C; ++c) p[c] *= inv;
+    const int k = static_cast<int>(ldv<E>(lab, pv));
+    return k < 0 ? 0 : (k >= C ? C - 1 : k);
+}
+
+// pass 1: part[block][0..C) = I, [C..2C) = P, [2C..3C) = Y, [3C] = N
+template <typename E, int C>
+__global__ __launch_bounds__(kThreads) void loss_stats_kernel(const E *__restrict__ z, const E *__restrict__ lab,
+                                                              float *__restrict__ part, LossGeo l) {
+    __shared__ float red[kThreads];
+    float acc[3 * C + 1];
+#pragma unroll
+    for (int i = 0; i < 3 * C + 1; ++i) acc[i] = 0.f;
+    const unsigned v0 = blockIdx.x * kChunk;
+    const unsigned v1 = v0 + kChunk < l.nvox ? v0 + kChunk : l.nvox;
+    for (unsigned v = v0 + threadIdx.x; v < v1; v += kThreads) {
+        const long long pv = padded_index(l, v);
+        float p[C];
+        const int k = voxel_softmax<E, C>(z, lab, pv, p);
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            acc[C + c] += p[c];
+            if (c == k) { acc[c] += p[c]; acc[2 * C + c] += 1.f; acc[3 * C] -= __logf(fmaxf(p[c], 1e-38f)); }
+        }
+    }
+    // one fixed tree per statistic
+    for (int i = 0; i < 3 * C + 1; ++i) {
+        red[threadIdx.x] = acc[i];
+        __syncthreads();
+        for (int w = kThreads / 2; w > 0; w >>= 1) {
+            if (threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) part[static_cast<size_t>(blockIdx.x) * (3 * C + 1) + i] = red[0];
+        __syncthreads();
+    }
+}
+
+// pass 2: gradient (dz may be null) and the loss value (written by block 0)
+template <typename E, int C>
+__global__ __launch_bounds__(kThreads) void loss_grad_kernel(const E *__restrict__ z, const E *__restrict__ lab,
+                                                             const float *__restrict__ stats, E *__restrict__ dz,
+                                                             float *__restrict__ loss, LossGeo l, float w_dice,
+                                                             float w_ce, float eps) {
+    float S[C], T[C];          // S_c = P_c + Y_c + eps, T_c = 2 I_c + eps
+    float dice = 0.f;
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        S[c] = stats[C + c] + stats[2 * C + c] + eps;
+        T[c] = 2.f * stats[c] + eps;
+        dice += T[c] / S[c];
+    }
+    const float invV = 1.f / static_cast<float>(l.nvox);
+    if (loss && blockIdx.x == 0 && threadIdx.x == 0)
+        loss[0] = w_dice * (1.f - dice / C) + w_ce * stats[3 * C] * invV;
+    if (!dz) return;
+    const unsigned v = blockIdx.x * kThreads + threadIdx.x;
+    if (v >= l.nvox) return;
+    const long long pv = padded_index(l, v);
+    float p[C];
+    const int k = voxel_softmax<E, C>(z, lab, pv, p);
+    float g[C], gp = 0.f;
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        const float y = c == k ? 1.f : 0.f;
+        g[c] = -(w_dice / C) * (2.f * y * S[c] - T[c]) / (S[c] * S[c]);
+        gp += g[c] * p[c];
+    }
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        const float y = c == k ? 1.f : 0.f;
+        stv<E>(dz, pv * C + c, p[c] * (g[c] - gp) + w_ce * (p[c] - y) * invV);
+    }
+}
+
+LossGeo make_loss_geo(const Geo &g) {
+    LossGeo l;
+    l.g = g;
+    l.nvox = static_cast<unsigned>(1LL * g.ntiles * g.int_vox);
+    l.int_vox = make_fastdiv(static_cast<uint32_t>(g.int_vox));
+    l.hw = make_fastdiv(static_cast<uint32_t>(g.th) * g.tw);
+    l.w = make_fastdiv(g.tw);
+    return l;
+}
+
+template <typename E, int C>
+int run_loss(const void *Pz, const void *Plab, void *Pdz, float *loss, float *stats, const Geo &g, float w_dice,
+             float w_ce, float eps, void *ws, hipStream_t s) {
+    const LossGeo l = make_loss_geo(g);
+    const unsigned nblk = (l.nvox + kChunk - 1) / kChunk;
+    float *part = static_cast<float *>(ws);
+    float *st = stats ? stats : part + static_cast<size_t>(nblk) * (3 * C + 1);
+    hipLaunchKernelGGL((loss_stats_kernel<E, C>), dim3(nblk), dim3(kThreads), 0, s, static_cast<const E *>(Pz),
+                       static_cast<const E *>(Plab), part, l);
+    int rc = record_hip(hipGetLastError());
+    if (rc != SP_OK) return rc;
+    rc = launch_reduce_partials(part, st, static_cast<int>(nblk), 3 * C + 1, s);
+    if (rc != SP_OK) return rc;
+    const unsigned gblk = Pdz ? (l.nvox + kThreads - 1) / kThreads : 1;
+    hipLaunchKernelGGL((loss_grad_kernel<E, C>), dim3(gblk), dim3(kThreads), 0, s, static_cast<const E *>(Pz),
+                       static_cast<const E *>(Plab), st, static_cast<E *>(Pdz), loss, l, w_dice, w_ce, eps);
+    return record_hip(hipGetLastError());
+}
+
+}  // namespace
+
+bool loss_supported(const Geo &g, int classes) {
+    return classes >= 2 && classes <= 4 && 1LL * g.ntiles * g.int_vox <= 0xffffff00LL;
+}
+
+size_t loss_ws_bytes(const Geo &g, int classes) {
+    const size_t nblk = (static_cast<size_t>(g.ntiles) * g.int_vox + kChunk - 1) / kChunk;
+    return (nblk + 1) * (3 * classes + 1) * sizeof(float);
+}
+
+int launch_loss(const void *Pz, const void *Plab, void *Pdz, float *loss, float *stats, const Geo &g, int classes,
+                sp_dtype_t dt, float w_dice, float w_ce, float eps, void *ws, hipStream_t s) {
+#define SP3D_LOSS(E)                                                                                         \
+    switch (classes) {                                                                                       \
+    case 2: return run_loss<E, 2>(Pz, Plab, Pdz, loss, stats, g, w_dice, w_ce, eps, ws, s);                  \
+    case 3: return run_loss<E, 3>(Pz, Plab, Pdz, loss, stats, g, w_dice, w_ce, eps, ws, s);                  \
+    default: return run_loss<E, 4>(Pz, Plab, Pdz, loss, stats, g, w_dice, w_ce, eps, ws, s);                 \
+    }
+    if (dt == SP_BF16) { SP3D_LOSS(uint16_t) }
+    SP3D_LOSS(float)
+#undef SP3D_LOSS
+}
+
+}  // namespace sp3d

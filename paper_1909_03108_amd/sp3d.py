@@ -9,7 +9,7 @@ import os
 SP_F32, SP_BF16 = 0, 1
 SP_OK, SP_EINVAL, SP_EGEOM, SP_EUNSUPPORTED, SP_EWORKSPACE, SP_ELAUNCH = 0, -1, -2, -3, -4, -5
 SP_FLAG_RELU = 1
-SP_OP_FWD, SP_OP_DGRAD, SP_OP_WGRAD, SP_OP_UPCONV_WGRAD, SP_OP_POINTWISE_WGRAD = 0, 1, 2, 3, 4
+SP_OP_FWD, SP_OP_DGRAD, SP_OP_WGRAD, SP_OP_UPCONV_WGRAD, SP_OP_POINTWISE_WGRAD, SP_OP_LOSS = 0, 1, 2, 3, 4, 5
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsp3d.so")
 
@@ -19,7 +19,8 @@ EXPORTS = ["sp_padded_elems", "sp_msg_elems", "sp_workspace_bytes", "sp_check_ge
            "conv3d_fwd", "conv3d_dgrad", "conv3d_dgrad_relu", "conv3d_wgrad", "conv3d_fwd2", "conv3d_dgrad2",
            "conv3d_wgrad2", "sp_relu_bwd",
            "sp_maxpool2_fwd", "sp_maxpool2_bwd", "sp_upconv2_fwd", "sp_upconv2_dgrad", "sp_upconv2_wgrad",
-           "sp_pointwise_fwd", "sp_pointwise_dgrad", "sp_pointwise_wgrad", "sp_concat", "sp_split", "sp_add"]
+           "sp_pointwise_fwd", "sp_pointwise_dgrad", "sp_pointwise_wgrad", "sp_concat", "sp_split", "sp_add",
+           "sp_dice_ce_loss"]
 
 
 class Geom(ctypes.Structure):
@@ -88,6 +89,8 @@ def lib():
         L.sp_concat.argtypes, L.sp_concat.restype = [P, I, P, I, P, G, I, P], I
         L.sp_split.argtypes, L.sp_split.restype = [P, P, I, P, I, G, I, P], I
         L.sp_add.argtypes, L.sp_add.restype = [P, P, P, G, I, I, P], I
+        F = ctypes.c_float
+        L.sp_dice_ce_loss.argtypes, L.sp_dice_ce_loss.restype = [P, P, P, P, P, G, I, I, F, F, F, P, Z, P], I
         _lib = L
     return _lib
 
@@ -287,3 +290,11 @@ def alloc_msg(g, c, dt, device="cuda"):
 def alloc_ws(nbytes, device="cuda"):
     import torch
     return torch.empty((max(int(nbytes), 16),), dtype=torch.uint8, device=device)
+
+
+def sp_dice_ce_loss(Plogits, Plabels, Pdlogits, loss, stats, g, classes, dt, w_dice=0.9, w_ce=0.1, eps=1.0, ws=None,
+                    stream=None):
+    wp, wb = _ws(ws)
+    _check(lib().sp_dice_ce_loss(_ptr(Plogits), _ptr(Plabels), _ptr(Pdlogits), _ptr(loss), _ptr(stats),
+                                 ctypes.byref(g), classes, dt, w_dice, w_ce, eps, wp, wb, _stream(stream)),
+           "sp_dice_ce_loss")

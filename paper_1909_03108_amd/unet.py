@@ -204,13 +204,33 @@ class UNet:
         self._release(Pdy, g, cout)
         return Pdx
 
+    def loss(self, labels_vol, w_dice=0.9, w_ce=0.1, eps=1.0):
+        """Soft Dice + cross-entropy of the logits of the last forward() against labels_vol (device volume
+        [n,d,h,w,1] of the tensor dtype holding class indices).  Returns a 1-element device tensor and leaves
+        d loss / d logits in the padded gradient buffer that backward(None) starts from."""
+        g0, dt = self.g[0], self.dt
+        Pl = self._buf("logits", g0, self.classes)
+        Plab = self._buf("labels", g0, 1)
+        sp3d.sp_partition(labels_vol, Plab, g0, 1, dt)
+        Pd = self._buf("dlogits", g0, self.classes)
+        out = torch.empty(1, dtype=torch.float32, device="cuda")
+        nbytes = sp3d.sp_workspace_bytes(sp3d.SP_OP_LOSS, g0, self.classes, 1, dt)
+        cur = self.ws_cache.get("buf")
+        if cur is None or cur.numel() < nbytes:
+            cur = sp3d.alloc_ws(nbytes)
+            self.ws_cache["buf"] = cur
+        sp3d.sp_dice_ce_loss(Pl, Plab, Pd, out, None, g0, self.classes, dt, w_dice, w_ce, eps, cur)
+        return out
+
     def backward(self, dlogits_vol, input_grad=True):
-        """dlogits_vol: device volume [n,d,h,w,classes].  Returns (grads by layer name, dx volume or None)."""
+        """dlogits_vol: device volume [n,d,h,w,classes], or None to start from the gradient loss() left.
+        Returns (grads by layer name, dx volume or None)."""
         dt, ch, A = self.dt, self.channels, self.A
         grads = {}
         g0 = self.g[0]
         Pd = self._buf("dlogits", g0, self.classes)
-        sp3d.sp_partition(dlogits_vol, Pd, g0, self.classes, dt)
+        if dlogits_vol is not None:
+            sp3d.sp_partition(dlogits_vol, Pd, g0, self.classes, dt)
         c0 = ch[0]
         dp = torch.empty((1, 1, 1, c0, self.classes), dtype=torch.float32, device="cuda")
         sp3d.sp_pointwise_wgrad(A["head.x"], Pd, dp, None, g0, c0, self.classes, dt,

@@ -141,6 +141,23 @@ def test_workspace_sizes_of_the_kernel_families():
         assert sp3d.sp_workspace_bytes(sp3d.SP_OP_WGRAD, g, cin, cout, sp3d.SP_BF16) > 0
 
 
+def test_loss_call_rejects_bad_arguments_before_launching():
+    L = sp3d.lib()
+    g = sp3d.Geom(1, (8, 8, 8), (2, 2, 2))
+    gp = ctypes.byref(g)
+    need = sp3d.sp_workspace_bytes(sp3d.SP_OP_LOSS, g, 3, 1, sp3d.SP_BF16)
+    assert 0 < need < 1 << 20
+    A, B, C, W = FAKE, FAKE * 2, FAKE * 4, FAKE * 8
+    f = L.sp_dice_ce_loss
+    assert f(A, None, C, None, None, gp, 3, sp3d.SP_BF16, 0.9, 0.1, 1.0, W, need, None) == sp3d.SP_EINVAL
+    assert f(A, B, None, None, None, gp, 3, sp3d.SP_BF16, 0.9, 0.1, 1.0, W, need, None) == sp3d.SP_EINVAL   # no output
+    assert f(A, B, C, None, None, gp, 1, sp3d.SP_BF16, 0.9, 0.1, 1.0, W, need, None) == sp3d.SP_EINVAL
+    assert f(A, B, C, None, None, gp, 5, sp3d.SP_BF16, 0.9, 0.1, 1.0, W, need, None) == sp3d.SP_EUNSUPPORTED
+    assert f(A, B, C, None, None, gp, 3, sp3d.SP_BF16, -1.0, 0.1, 1.0, W, need, None) == sp3d.SP_EINVAL
+    assert f(A, B, C, None, None, gp, 3, sp3d.SP_BF16, 0.9, 0.1, 1.0, W, need - 1, None) == sp3d.SP_EWORKSPACE
+    assert f(A, B, C, FAKE + 2, None, gp, 3, sp3d.SP_BF16, 0.9, 0.1, 1.0, W, need, None) == sp3d.SP_EINVAL
+
+
 def test_geometry_limits():
     # per-tile voxel indices must stay 32-bit
     assert sp3d.sp_check_geom(sp3d.Geom(1, (2048, 2048, 2048), (1, 1, 1))) == sp3d.SP_EGEOM

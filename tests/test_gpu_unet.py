@@ -211,3 +211,32 @@ def test_unet_four_convs_per_block():
     assert torch.equal(logits2, logits_t) and torch.equal(dx2, dx)
     for k, _ in plan:
         assert torch.equal(grads2[k], grads[k]), k
+
+
+@pytest.mark.timeout(600)
+def test_unet_with_loss_end_to_end():
+    """forward -> soft Dice + cross-entropy -> backward, against the oracle chain (free-running, storage-aware)."""
+    from oracle import loss as OL
+    channels, in_ch, classes = (32, 64), 1, 3
+    n, dhw, grid = 1, (8, 16, 32), (2, 2, 1)
+    plan = PU.layer_plan(channels, in_ch, classes)
+    x = synth.ct_like_volume((n,) + dhw + (in_ch,), synth.seed_for(7, synth.T_INPUT), "bf16")
+    w_h = {name: synth.weights(shape[3], shape[4], synth.seed_for(7, synth.T_WEIGHT0 + k), "bf16",
+                               taps=shape[:3]) for k, (name, shape) in enumerate(plan)}
+    lab = np.random.default_rng(synth.seed_for(7, synth.T_UPSTREAM)).integers(0, classes, size=(n,) + dhw)
+    w64 = {k: widen(v) for k, v in w_h.items()}
+    A = {}
+    ref_logits = OU.forward(widen(x), w64, channels, keep=A, store=OU.round_bf16)
+    ref_loss = OL.loss(ref_logits, lab)
+    ref_dl = OU.round_bf16(OL.gradient(ref_logits, lab))
+    ref_grads, _ = OU.backward(ref_dl, w64, channels, A, store=OU.round_bf16)
+
+    net = PU.UNet(n, dhw, grid, {k: to_dev(v) for k, v in w_h.items()}, channels, in_ch, classes)
+    net.forward(to_dev(x))
+    lab_dev = to_dev(synth.f32_to_bf16_bits(lab.astype(np.float32))[..., None])
+    loss = net.loss(lab_dev)
+    assert abs(loss.item() - ref_loss) <= 5e-3 * abs(ref_loss)
+    grads, _ = net.backward(None, input_grad=False)
+    worst = max(rel_rms(f64(grads[k]), ref_grads[k]) for k, _ in plan)
+    print("with loss: free-running backward worst relative rms %.3f" % worst)
+    assert worst <= 0.05          # the loss gradient is smooth, so few ReLU decisions flip (measured: 0.003)
