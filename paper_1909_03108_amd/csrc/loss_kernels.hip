@@ -17,7 +17,7 @@ namespace sp3d {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr unsigned kChunk = 4096;         // voxels per block in pass 1
+constexpr unsigned kChunk = 8192;         // voxels per block in pass 1
 
 template <typename E> __device__ __forceinline__ float ldv(const E *p, long long i);
 template <> __device__ __forceinline__ float ldv<float>(const float *p, long long i) { return p[i]; }
@@ -75,16 +75,24 @@ __global__ __launch_bounds__(kThreads) void loss_stats_kernel(const E *__restric
             if (c == k) { acc[c] += p[c]; acc[2 * C + c] += 1.f; acc[3 * C] -= __logf(fmaxf(p[c], 1e-38f)); }
         }
     }
-    // one fixed tree per statistic
+    // a fixed tree per statistic: butterfly inside each wave, then the four wave sums in wave order
+#pragma unroll
     for (int i = 0; i < 3 * C + 1; ++i) {
-        red[threadIdx.x] = acc[i];
-        __syncthreads();
-        for (int w = kThreads / 2; w > 0; w >>= 1) {
-            if (threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
-            __syncthreads();
-        }
-        if (threadIdx.x == 0) part[static_cast<size_t>(blockIdx.x) * (3 * C + 1) + i] = red[0];
-        __syncthreads();
+        float v = acc[i];
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) v += __shfl_xor(v, m);
+        acc[i] = v;
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) {
+#pragma unroll
+        for (int i = 0; i < 3 * C + 1; ++i) red[wave * (3 * C + 1) + i] = acc[i];
+    }
+    __syncthreads();
+    if (threadIdx.x < 3 * C + 1) {
+        float t = 0.f;
+        for (int w = 0; w < kThreads / 64; ++w) t += red[w * (3 * C + 1) + threadIdx.x];
+        part[static_cast<size_t>(blockIdx.x) * (3 * C + 1) + threadIdx.x] = t;
     }
 }
 
