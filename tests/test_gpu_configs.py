@@ -231,3 +231,58 @@ def test_configuration_3_first_level_256():
     assert rel_err(f64(db1), conv3d.bias_grad(dz1)) <= tol
     dx_g = L1.dgrad(dz1, w1)                                                # gradient w.r.t. the image
     assert on_boxes(dx_g, lambda bx: conv3d.conv3d_dgrad(dz1, W1, box=bx)) <= tol
+
+
+@pytest.mark.timeout(900)
+def test_configuration_5_decoder_layer_256_sampled():
+    """The widest layer of the U-Net stack at its real size: concat(skip, up) 64 -> 32 on 256^3, grid 4x4x1
+    (64 x 64 x 256 tiles), through the two-tensor entry points (chunk pairs summed on chip).  Inputs are seeded
+    stand-ins of the right shape and distribution (ReLU outputs: half zeros), compared on sampled boxes /
+    entries as for configuration 4; the masked data gradient of the following 32 -> 32 layer likewise."""
+    n, dhw, grid = 1, (256, 256, 256), (4, 4, 1)
+    g = sp3d.Geom(n, dhw, grid)
+    dt, tol = sp3d.SP_BF16, TOL["bf16"]
+    relu = lambda a: np.where(widen(a) > 0, a, np.zeros_like(a))
+    skip = relu(synth.normal_volume((n,) + dhw + (32,), synth.seed_for(5, 60), "bf16"))
+    up = synth.normal_volume((n,) + dhw + (32,), synth.seed_for(5, 61), "bf16")
+    dz = synth.normal_volume((n,) + dhw + (32,), synth.seed_for(5, 62), "bf16")
+    w = synth.weights(64, 32, synth.seed_for(5, 63), "bf16")
+    w2 = synth.weights(32, 32, synth.seed_for(5, 64), "bf16")
+    Wd, W2d = widen(w), widen(w2)
+    x_cat = np.concatenate([skip, up], axis=-1)
+    rng = np.random.default_rng(5)
+    boxes = sample_boxes(dhw, g.tile, rng, nrandom=12)
+    vol = torch.empty((n,) + dhw + (32,), dtype=torch.bfloat16, device="cuda")
+
+    def exchanged(v, c):
+        P = sp3d.alloc_padded(g, c, dt)
+        sp3d.sp_partition(to_dev(v), P, g, c, dt)
+        sp3d.sp_halo_exchange(P, g, c, dt)
+        return P
+
+    def check(P_out, fn, what):
+        sp3d.sp_unpartition(P_out, vol, g, 32, dt)
+        worst = max(rel_err(f64(vol[:, b[0]:b[1], b[2]:b[3], b[4]:b[5]]), fn(b)) for b in boxes)
+        assert worst <= tol, (what, worst)
+
+    ws = {op: sp3d.alloc_ws(sp3d.sp_workspace_bytes(op, g, 64, 32, dt)) for op in (0, 1, 2)}
+    Ps, Pu, Pz = exchanged(skip, 32), exchanged(up, 32), exchanged(dz, 32)
+    Py = sp3d.alloc_padded(g, 32, dt)
+    sp3d.conv3d_fwd2(Ps, 32, Pu, 32, to_dev(w), None, Py, g, 32, dt, sp3d.SP_FLAG_RELU, ws[0])
+    check(Py, lambda b: conv3d.conv3d_fwd(x_cat, Wd, relu=True, box=b), "fwd2")
+    # data gradient into the two tensors
+    Pa, Pb = sp3d.alloc_padded(g, 32, dt), sp3d.alloc_padded(g, 32, dt)
+    sp3d.conv3d_dgrad2(Pz, to_dev(w), Pa, 32, Pb, 32, g, 32, dt, ws[1])
+    check(Pa, lambda b: conv3d.conv3d_dgrad(dz, Wd, box=b)[..., :32], "dgrad2 a")
+    check(Pb, lambda b: conv3d.conv3d_dgrad(dz, Wd, box=b)[..., 32:], "dgrad2 b")
+    # weight gradient, sampled entries
+    dw = torch.empty((3, 3, 3, 64, 32), dtype=torch.float32, device="cuda")
+    sp3d.conv3d_wgrad2(Ps, 32, Pu, 32, Pz, dw, None, g, 32, dt, ws[2])
+    sel = np.array([0, 13 * 2048 + 5 * 32 + 7, 26 * 2048 + 63 * 32 + 31, 2 * 2048 + 40 * 32 + 3, 9 * 2048 + 33 * 32 + 1,
+                    18 * 2048 + 30 * 32, 22 * 2048 + 47 * 32 + 16, 24 * 2048 + 15])
+    assert rel_err(f64(dw).ravel()[sel], conv3d.conv3d_wgrad(x_cat, dz, sel=sel)) <= tol
+    # the following 32 -> 32 layer: its data gradient with the ReLU mask of its input (here: skip) applied
+    ws1 = sp3d.alloc_ws(sp3d.sp_workspace_bytes(sp3d.SP_OP_DGRAD, g, 32, 32, dt))
+    sp3d.conv3d_dgrad_relu(Pz, to_dev(w2), Ps, Pa, g, 32, 32, dt, ws1)
+    check(Pa, lambda b: np.where(widen(skip[:, b[0]:b[1], b[2]:b[3], b[4]:b[5]]) > 0,
+                                 conv3d.conv3d_dgrad(dz, W2d, box=b), 0.0), "dgrad_relu")
