@@ -19,12 +19,24 @@ namespace {
 constexpr int kThreads = 256;
 constexpr unsigned kChunk = 8192;         // voxels per block in pass 1
 
-template <typename E> __device__ __forceinline__ float ldv(const E *p, long long i);
-template <> __device__ __forceinline__ float ldv<float>(const float *p, long long i) { return p[i]; }
-template <> __device__ __forceinline__ float ldv<uint16_t>(const uint16_t *p, long long i) { return bf16_to_f32(p[i]); }
-template <typename E> __device__ __forceinline__ void stv(E *p, long long i, float v);
-template <> __device__ __forceinline__ void stv<float>(float *p, long long i, float v) { p[i] = v; }
-template <> __device__ __forceinline__ void stv<uint16_t>(uint16_t *p, long long i, float v) { p[i] = f32_to_bf16(v); }
+template <typename E> __device__ __forceinline__ float widen(E v);
+template <> __device__ __forceinline__ float widen<float>(float v) { return v; }
+template <> __device__ __forceinline__ float widen<uint16_t>(uint16_t v) { return bf16_to_f32(v); }
+template <typename E> __device__ __forceinline__ E narrow(float v);
+template <> __device__ __forceinline__ float narrow<float>(float v) { return v; }
+template <> __device__ __forceinline__ uint16_t narrow<uint16_t>(float v) { return f32_to_bf16(v); }
+
+// A thread works on VPT consecutive voxels of a W row (VPT divides the tile's W extent, so a group never
+// leaves its row) and moves their records as one block: with 3 classes of bf16 a voxel is 6 bytes, and
+// 8 voxels make three 16-byte accesses per lane where single voxels would make 2-byte ones.  The copies
+// below have only the element's alignment; the compiler turns them into full-width global accesses.
+template <typename E, int N> struct __attribute__((packed, aligned(sizeof(E)))) Rec { E e[N]; };
+template <typename E, int N> __device__ __forceinline__ void load_rec(const E *p, Rec<E, N> &r) {
+    __builtin_memcpy(&r, p, sizeof(r));
+}
+template <typename E, int N> __device__ __forceinline__ void store_rec(E *p, const Rec<E, N> &r) {
+    __builtin_memcpy(p, &r, sizeof(r));
+}
 
 struct LossGeo {
     Geo g;
@@ -39,24 +51,25 @@ __device__ __forceinline__ long long padded_index(const LossGeo &l, unsigned v) 
     return tile * l.g.tile_vox + (1LL * (ld + 1) * l.g.ph + lh + 1) * l.g.pw + lw + 1;
 }
 
-// softmax of one voxel; returns the label (clamped into range: the host cannot check every voxel)
+// softmax of one voxel from its stored logits; returns the label (clamped into range: the host cannot check
+// every voxel)
 template <typename E, int C>
-__device__ __forceinline__ int voxel_softmax(const E *z, const E *lab, long long pv, float (&p)[C]) {
+__device__ __forceinline__ int voxel_softmax(const E *zr, E labv, float (&p)[C]) {
     float m = -3.0e38f;
 #pragma unroll
-    for (int c = 0; c < C; ++c) { p[c] = ldv<E>(z, pv * C + c); m = fmaxf(m, p[c]); }
+    for (int c = 0; c < C; ++c) { p[c] = widen<E>(zr[c]); m = fmaxf(m, p[c]); }
     float s = 0.f;
 #pragma unroll
     for (int c = 0; c < C; ++c) { p[c] = __expf(p[c] - m); s += p[c]; }
     const float inv = 1.f / s;
 #pragma unroll
     for (int c = 0; c < C; ++c) p[c] *= inv;
-    const int k = static_cast<int>(ldv<E>(lab, pv));
+    const int k = static_cast<int>(widen<E>(labv));
     return k < 0 ? 0 : (k >= C ? C - 1 : k);
 }
 
 // pass 1: part[block][0..C) = I, [C..2C) = P, [2C..3C) = Y, [3C] = N
-template <typename E, int C>
+template <typename E, int C, int VPT>
 __global__ __launch_bounds__(kThreads) void loss_stats_kernel(const E *__restrict__ z, const E *__restrict__ lab,
                                                               float *__restrict__ part, LossGeo l) {
     __shared__ float red[kThreads];
@@ -65,14 +78,21 @@ __global__ __launch_bounds__(kThreads) void loss_stats_kernel(const E *__restric
     for (int i = 0; i < 3 * C + 1; ++i) acc[i] = 0.f;
     const unsigned v0 = blockIdx.x * kChunk;
     const unsigned v1 = v0 + kChunk < l.nvox ? v0 + kChunk : l.nvox;
-    for (unsigned v = v0 + threadIdx.x; v < v1; v += kThreads) {
+    for (unsigned v = v0 + threadIdx.x * VPT; v < v1; v += kThreads * VPT) {   // kChunk and nvox are multiples of VPT
         const long long pv = padded_index(l, v);
-        float p[C];
-        const int k = voxel_softmax<E, C>(z, lab, pv, p);
+        Rec<E, VPT * C> zr;
+        Rec<E, VPT> lr;
+        load_rec(z + pv * C, zr);
+        load_rec(lab + pv, lr);
 #pragma unroll
-        for (int c = 0; c < C; ++c) {
-            acc[C + c] += p[c];
-            if (c == k) { acc[c] += p[c]; acc[2 * C + c] += 1.f; acc[3 * C] -= __logf(fmaxf(p[c], 1e-38f)); }
+        for (int i = 0; i < VPT; ++i) {
+            float p[C];
+            const int k = voxel_softmax<E, C>(zr.e + i * C, lr.e[i], p);
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                acc[C + c] += p[c];
+                if (c == k) { acc[c] += p[c]; acc[2 * C + c] += 1.f; acc[3 * C] -= __logf(fmaxf(p[c], 1e-38f)); }
+            }
         }
     }
     // a fixed tree per statistic: butterfly inside each wave, then the four wave sums in wave order
@@ -97,7 +117,7 @@ __global__ __launch_bounds__(kThreads) void loss_stats_kernel(const E *__restric
 }
 
 // pass 2: gradient (dz may be null) and the loss value (written by block 0)
-template <typename E, int C>
+template <typename E, int C, int VPT>
 __global__ __launch_bounds__(kThreads) void loss_grad_kernel(const E *__restrict__ z, const E *__restrict__ lab,
                                                              const float *__restrict__ stats, E *__restrict__ dz,
                                                              float *__restrict__ loss, LossGeo l, float w_dice,
@@ -114,23 +134,31 @@ __global__ __launch_bounds__(kThreads) void loss_grad_kernel(const E *__restrict
     if (loss && blockIdx.x == 0 && threadIdx.x == 0)
         loss[0] = w_dice * (1.f - dice / C) + w_ce * stats[3 * C] * invV;
     if (!dz) return;
-    const unsigned v = blockIdx.x * kThreads + threadIdx.x;
-    if (v >= l.nvox) return;
-    const long long pv = padded_index(l, v);
-    float p[C];
-    const int k = voxel_softmax<E, C>(z, lab, pv, p);
-    float g[C], gp = 0.f;
+    const unsigned long long v64 = (static_cast<unsigned long long>(blockIdx.x) * kThreads + threadIdx.x) * VPT;
+    if (v64 >= l.nvox) return;
+    const long long pv = padded_index(l, static_cast<unsigned>(v64));
+    Rec<E, VPT * C> zr, out;
+    Rec<E, VPT> lr;
+    load_rec(z + pv * C, zr);
+    load_rec(lab + pv, lr);
 #pragma unroll
-    for (int c = 0; c < C; ++c) {
-        const float y = c == k ? 1.f : 0.f;
-        g[c] = -(w_dice / C) * (2.f * y * S[c] - T[c]) / (S[c] * S[c]);
-        gp += g[c] * p[c];
-    }
+    for (int i = 0; i < VPT; ++i) {
+        float p[C];
+        const int k = voxel_softmax<E, C>(zr.e + i * C, lr.e[i], p);
+        float g[C], gp = 0.f;
 #pragma unroll
-    for (int c = 0; c < C; ++c) {
-        const float y = c == k ? 1.f : 0.f;
-        stv<E>(dz, pv * C + c, p[c] * (g[c] - gp) + w_ce * (p[c] - y) * invV);
+        for (int c = 0; c < C; ++c) {
+            const float y = c == k ? 1.f : 0.f;
+            g[c] = -(w_dice / C) * (2.f * y * S[c] - T[c]) / (S[c] * S[c]);
+            gp += g[c] * p[c];
+        }
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const float y = c == k ? 1.f : 0.f;
+            out.e[i * C + c] = narrow<E>(p[c] * (g[c] - gp) + w_ce * (p[c] - y) * invV);
+        }
     }
+    store_rec(dz + pv * C, out);
 }
 
 LossGeo make_loss_geo(const Geo &g) {
@@ -143,23 +171,30 @@ LossGeo make_loss_geo(const Geo &g) {
     return l;
 }
 
-template <typename E, int C>
-int run_loss(const void *Pz, const void *Plab, void *Pdz, float *loss, float *stats, const Geo &g, float w_dice,
+template <typename E, int C, int VPT>
+int run_loss_vpt(const void *Pz, const void *Plab, void *Pdz, float *loss, float *stats, const Geo &g, float w_dice,
              float w_ce, float eps, void *ws, hipStream_t s) {
     const LossGeo l = make_loss_geo(g);
     const unsigned nblk = (l.nvox + kChunk - 1) / kChunk;
     float *part = static_cast<float *>(ws);
     float *st = stats ? stats : part + static_cast<size_t>(nblk) * (3 * C + 1);
-    hipLaunchKernelGGL((loss_stats_kernel<E, C>), dim3(nblk), dim3(kThreads), 0, s, static_cast<const E *>(Pz),
+    hipLaunchKernelGGL((loss_stats_kernel<E, C, VPT>), dim3(nblk), dim3(kThreads), 0, s, static_cast<const E *>(Pz),
                        static_cast<const E *>(Plab), part, l);
     int rc = record_hip(hipGetLastError());
     if (rc != SP_OK) return rc;
     rc = launch_reduce_partials(part, st, static_cast<int>(nblk), 3 * C + 1, s);
     if (rc != SP_OK) return rc;
-    const unsigned gblk = Pdz ? (l.nvox + kThreads - 1) / kThreads : 1;
-    hipLaunchKernelGGL((loss_grad_kernel<E, C>), dim3(gblk), dim3(kThreads), 0, s, static_cast<const E *>(Pz),
+    const unsigned gblk = Pdz ? (l.nvox / VPT + kThreads - 1) / kThreads : 1;
+    hipLaunchKernelGGL((loss_grad_kernel<E, C, VPT>), dim3(gblk), dim3(kThreads), 0, s, static_cast<const E *>(Pz),
                        static_cast<const E *>(Plab), st, static_cast<E *>(Pdz), loss, l, w_dice, w_ce, eps);
     return record_hip(hipGetLastError());
+}
+
+template <typename E, int C>
+int run_loss(const void *Pz, const void *Plab, void *Pdz, float *loss, float *stats, const Geo &g, float w_dice,
+             float w_ce, float eps, void *ws, hipStream_t s) {
+    if (g.tw % 8 == 0) return run_loss_vpt<E, C, 8>(Pz, Plab, Pdz, loss, stats, g, w_dice, w_ce, eps, ws, s);
+    return run_loss_vpt<E, C, 1>(Pz, Plab, Pdz, loss, stats, g, w_dice, w_ce, eps, ws, s);
 }
 
 }  // namespace

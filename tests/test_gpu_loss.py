@@ -14,6 +14,8 @@ CASES = [  # n, dhw, grid, classes, dtype
     (2, (6, 4, 10), (3, 2, 5), 2, "f32"),            # batch 2, 1-voxel-thin tiles along W
     (1, (32, 48, 64), (2, 2, 1), 3, "bf16"),          # 98 304 voxels: 24 blocks in the first pass
     (1, (16, 16, 16), (1, 1, 1), 4, "f32"),
+    (1, (8, 10, 24), (2, 1, 1), 3, "bf16"),           # rows of 24 voxels: three 8-voxel groups per row
+    (1, (4, 6, 12), (1, 2, 1), 3, "bf16"),            # rows not a multiple of 8: one voxel per thread
 ]
 
 
