@@ -54,3 +54,39 @@ def tiled_wgrad(V, dZ, grid=(1, 1, 1), h=1):
                                   np.ascontiguousarray(Pz[:, a, b, c, h:-h, h:-h, h:-h, :]),
                                   pad=0)
     return dw
+
+
+def _grown(idx, ngrid, t, h, e):
+    """Padded-coordinate range of a tile's own voxels grown by e towards the neighbours it has."""
+    return h - (e if idx > 0 else 0), h + t + (e if idx < ngrid - 1 else 0)
+
+
+def tiled_block_fwd(V, ws, bs=None, grid=(1, 1, 1), stop_at_border=True):
+    """k = len(ws) stacked conv + ReLU layers after ONE exchange of k-wide margins: the overlapping-patch
+    idea of Sec. 1 (each device works on a patch that overlaps its neighbours and so needs nothing from
+    them while it runs) applied to a short stack.  Layer i (1-based) is computed by every tile on its own
+    voxels plus the k - i voxels around them that the following layers will read; where a tile has no
+    neighbour that surround lies beyond the volume, where every layer's output is zero padding, so the box
+    does not grow there.  Returns the k layer outputs as whole volumes.
+    stop_at_border=False plants the mistake of growing there as well (tests only)."""
+    k = len(ws)
+    bs = bs or [None] * k
+    h = k
+    P = tiling.exchange(tiling.partition(V, grid, h), h)
+    N, gd, gh, gw, pd, ph, pw, _ = P.shape
+    tile = (pd - 2 * h, ph - 2 * h, pw - 2 * h)
+    outs = []
+    for i, (w, b) in enumerate(zip(ws, bs), 1):
+        e = k - i
+        Y = np.zeros((N, gd, gh, gw, pd, ph, pw, w.shape[4]), dtype=np.float64)
+        for a, bb, c in _per_tile(P):
+            if stop_at_border:
+                (d0, d1), (h0, h1), (w0, w1) = (_grown(i_, n_, t_, h, e)
+                                                for i_, n_, t_ in zip((a, bb, c), (gd, gh, gw), tile))
+            else:
+                (d0, d1), (h0, h1), (w0, w1) = ((h - e, h + t_ + e) for t_ in tile)
+            window = np.ascontiguousarray(P[:, a, bb, c, d0 - 1:d1 + 1, h0 - 1:h1 + 1, w0 - 1:w1 + 1, :])
+            Y[:, a, bb, c, d0:d1, h0:h1, w0:w1, :] = conv3d.conv3d_fwd(window, w, b, True, pad=0)
+        outs.append(tiling.unpartition(Y, h))
+        P = Y
+    return outs

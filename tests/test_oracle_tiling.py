@@ -140,3 +140,40 @@ def test_paper_size_arithmetic():
         a, b, dp, sp = facts[key]
         assert a * b * facts["cores_per_tpu"][0] == dp * sp
     assert int(facts["kernel_size"][0] * facts["halo_fraction_of_kernel"][0]) == 1
+
+
+@pytest.mark.parametrize("dhw,grid,k", [((6, 6, 4), (2, 3, 1), 2), ((6, 6, 6), (2, 2, 2), 3), ((8, 4, 4), (2, 1, 1), 4),
+                                        ((4, 4, 4), (1, 1, 1), 2)])
+def test_block_after_one_wide_exchange_equals_the_unpartitioned_stack(rng, dhw, grid, k):
+    """k conv + ReLU layers after one exchange of k-wide margins (the overlap of Sec. 1 for a short stack):
+    every layer's output equals the whole-volume one, provided the redundantly computed surround stops at the
+    volume border, where each layer sees zero padding."""
+    x = vol(rng, dhw, 2)
+    ws = [rng.standard_normal((3, 3, 3, 2, 2)) * 0.3 for _ in range(k)]
+    bs = [rng.standard_normal(2) for _ in range(k)]
+    ref, y = [], x
+    for w, b in zip(ws, bs):
+        y = conv3d.conv3d_fwd(y, w, b, relu=True)
+        ref.append(y)
+    got = tiled.tiled_block_fwd(x, ws, bs, grid)
+    for r, g_ in zip(ref, got):
+        np.testing.assert_allclose(g_, r, rtol=0, atol=1e-12)
+    if max(grid) > 1 or k > 1:
+        # planted mistake: convolving beyond the volume border as well changes the last layer near the border
+        wrong = tiled.tiled_block_fwd(x, ws, bs, grid, stop_at_border=False)
+        assert not np.allclose(wrong[-1], ref[-1])
+
+
+WIDE = [((4, 4, 4), (1, 1, 1), 2), ((4, 4, 4), (2, 2, 2), 2), ((6, 4, 8), (2, 1, 4), 2), ((6, 6, 3), (2, 2, 1), 3),
+        ((8, 4, 4), (2, 1, 1), 4)]
+
+
+@pytest.mark.parametrize("dhw,grid,h", WIDE)
+def test_wider_margins_reproduce_wider_windows(rng, dhw, grid, h):
+    """Margins of width h > 1 (several layers per exchange): same invariants as for h = 1."""
+    V = vol(rng, dhw, 2, n=2)
+    P = tiling.partition(V, grid, h)
+    assert np.count_nonzero(P) == np.count_nonzero(V) and np.array_equal(tiling.unpartition(P, h), V)
+    assert np.array_equal(tiling.exchange(P, h), tiling.padded_reference(V, grid, h))
+    tile = tiling.tile_extents(dhw, grid)
+    assert sum(tiling.region_sizes(tile, h)) == tiling.margin_voxels(tile, h) == tiling.halo_pack(P, h).shape[4]
