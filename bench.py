@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--loss", action="store_true",
                     help="U-Net workloads: compute the upstream gradient with sp_dice_ce_loss on seeded labels "
                          "instead of the N(0,1) stand-in of the workload list (adds the loss passes to the step)")
+    ap.add_argument("--halo", type=int, default=1, choices=[1, 2],
+                    help="U-Net workloads: margin width of the layout; 2 = two layers of a block share one exchange "
+                         "(the first also computes the voxel shell the second reads)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (torch copy_) so that profiler "
                          "byte counters can be scaled against a kernel of known traffic")
@@ -78,7 +81,7 @@ def bench_unet(args):
     w = {name: dev(synth.weights(shape[3], shape[4], synth.seed_for(5, synth.T_WEIGHT0 + k), "bf16",
                                  taps=shape[:3])) for k, (name, shape) in enumerate(plan)}
     dl = dev(synth.normal_volume((n,) + dhw + (classes,), synth.seed_for(5, synth.T_UPSTREAM), "bf16"))
-    net = unet.UNet(n, dhw, grid, w, channels, in_ch, classes, convs=convs)
+    net = unet.UNet(n, dhw, grid, w, channels, in_ch, classes, convs=convs, halo=args.halo)
 
     labels = None
     if args.loss:
@@ -119,8 +122,8 @@ def bench_unet(args):
         "metric": "U-Net conv stack fwd+bwd TFLOP/s (bf16), secondary workload", "value": round(flop / ms / 1e9, 2),
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": name + ", grid 4x4x1, halo 1, forward + backward (weight and data gradients, "
-                                      "no image gradient)" + (", upstream gradient from the Dice + CE loss"
+        "config": {"workload": name + (", grid 4x4x1, halo %d, forward + backward (weight and data gradients, "
+                                       "no image gradient)" % args.halo) + (", upstream gradient from the Dice + CE loss"
                                                               if args.loss else ""),
                    "tflop_per_step": round(flop / 1e12, 2),
                    "hbm_allocated_gb": round(torch.cuda.max_memory_allocated() / 1e9, 1)}}))

@@ -17,8 +17,14 @@
  *     synchronising.
  *   - Return value: SP_OK (0) or a negative error code; on error nothing has been enqueued.
  *   - Geometry: volume extents (n, d, h, w); tile grid (gd, gh, gw) over the D, H, W axes, which
- *     must divide d, h, w; halo width `halo` (only 1 = floor(3/2) is supported).  Tile extents
+ *     must divide d, h, w; margin width `halo` of the padded layout.  Tile extents
  *     td = d/gd, th = h/gh, tw = w/gw; padded tile extents pd = td + 2*halo, etc.
+ *     halo = 1 = floor(3/2) is what one 3x3x3 convolution needs (Sec. 2).  A wider margin lets a
+ *     block of k <= halo convolutions run after ONE exchange of `halo`-wide margins, the overlap
+ *     idea of Sec. 1 applied to a few layers: layer i of the block (i = 1..k) is called with
+ *     grow = k - i and also computes the `grow` voxels around the interior that its successors
+ *     read, instead of receiving them (redundant arithmetic in exchange for fewer exchanges).
+ *     The grown box stops at the volume border: what lies beyond is zero padding at every layer.
  *
  * Layouts (C = channels, fastest)
  *   volume        V[n][d][h][w][C]
@@ -45,8 +51,11 @@ extern "C" {
 typedef struct sp_geom {
     int32_t n, d, h, w;   /* whole-volume extents in voxels                     */
     int32_t gd, gh, gw;   /* tile grid over D, H, W; must divide d, h, w        */
-    int32_t halo;         /* margin width; 1 for the 3x3x3 kernel               */
+    int32_t halo;         /* margin width of the layout, 1..SP_MAX_HALO          */
+    int32_t grow;         /* conv3d_fwd*, conv3d_dgrad*: 0 <= grow < halo, see below; ignored elsewhere */
 } sp_geom_t;
+
+enum { SP_MAX_HALO = 4 };
 
 typedef enum sp_dtype { SP_F32 = 0, SP_BF16 = 1 } sp_dtype_t;
 
@@ -54,7 +63,7 @@ enum {
     SP_OK = 0,
     SP_EINVAL = -1,        /* null pointer, misaligned pointer, non-positive extent/channels */
     SP_EGEOM = -2,         /* grid does not divide the volume, or a tile is thinner than halo */
-    SP_EUNSUPPORTED = -3,  /* halo != 1, unknown dtype, channel count with no kernel          */
+    SP_EUNSUPPORTED = -3,  /* halo > SP_MAX_HALO, unknown dtype, channel count with no kernel */
     SP_EWORKSPACE = -4,    /* workspace missing or smaller than sp_workspace_bytes says       */
     SP_ELAUNCH = -5        /* HIP reported an error; see sp_last_hip_error()                  */
 };
@@ -114,6 +123,10 @@ int sp_halo_exchange(void *P, const sp_geom_t *g, int c, sp_dtype_t dt, void *st
  * zero-padded 'same' convolution of the whole volume once halo_unpack has run on Px.
  * Writes y = z (or max(z,0) with SP_FLAG_RELU) into the interiors of Py; Py's margins are left
  * as they are.  bias may be NULL.  Px [..][Cin], Py [..][Cout] must not overlap.
+ * With g->grow = e > 0 the output box of a tile is its interior plus e voxels on every side on which
+ * the tile has a neighbour in the grid (the voxels the next e layers of a block read, computed here
+ * instead of exchanged); Px must be valid e + 1 voxels around the interior.  The rest of Py's
+ * margins is still left as it is: keep it zero beyond the volume border (a zeroed buffer stays so).
  * bf16: products of bf16 values accumulated in fp32, result rounded to nearest-even bf16.
  * f32: fp32 throughout. */
 int conv3d_fwd(const void *Px, const void *w, const float *bias, void *Py, const sp_geom_t *g,
@@ -123,7 +136,7 @@ int conv3d_fwd(const void *Px, const void *w, const float *bias, void *Py, const
 /* Data gradient.  dx[v,ci] = sum_{kd,kh,kw,co} Pdz[v + (2-kd,2-kh,2-kw)][co] * w[kd][kh][kw][ci][co]
  * over interior voxels v, i.e. the same correlation with the taps mirrored and the channel roles
  * swapped, reading halo-exchanged dz (run halo_pack/halo_unpack on Pdz first).  Writes the
- * interiors of Pdx [..][Cin].  Precision as conv3d_fwd. */
+ * interiors of Pdx [..][Cin] (with g->grow the grown box, as conv3d_fwd).  Precision as conv3d_fwd. */
 int conv3d_dgrad(const void *Pdz, const void *w, void *Pdx, const sp_geom_t *g, int cin, int cout,
                  sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream);
 /* Data gradient followed by the backward of the ReLU that produced this layer's input (Sec. 3: the

@@ -17,14 +17,15 @@ int record_hip(hipError_t e) {
 int make_geo(const sp_geom_t *g, Geo *out) {
     if (!g) return SP_EINVAL;
     if (g->n <= 0 || g->d <= 0 || g->h <= 0 || g->w <= 0 || g->gd <= 0 || g->gh <= 0 ||
-        g->gw <= 0 || g->halo < 0)
+        g->gw <= 0 || g->halo < 0 || g->grow < 0 || (g->grow > 0 && g->grow >= g->halo))
         return SP_EINVAL;
     if (g->d % g->gd || g->h % g->gh || g->w % g->gw) return SP_EGEOM;
-    if (g->halo != 1) return SP_EUNSUPPORTED;
+    if (g->halo < 1 || g->halo > SP_MAX_HALO) return SP_EUNSUPPORTED;
     Geo o;
     o.n = g->n; o.gd = g->gd; o.gh = g->gh; o.gw = g->gw;
     o.td = g->d / g->gd; o.th = g->h / g->gh; o.tw = g->w / g->gw;
     o.halo = g->halo;
+    o.grow = g->grow;
     if (o.td < o.halo || o.th < o.halo || o.tw < o.halo) return SP_EGEOM;
     o.pd = o.td + 2 * o.halo; o.ph = o.th + 2 * o.halo; o.pw = o.tw + 2 * o.halo;
     long long nt = 1LL * o.n * o.gd * o.gh * o.gw;
@@ -228,7 +229,8 @@ int conv3d_fwd(const void *Px, const void *w, const float *bias, void *Py, const
         if (need && (!ws || ws_bytes < need || !aligned16(ws))) return SP_EWORKSPACE;
         return launch_conv_mfma(Px, w, bias, Py, o, cin, cout, relu, false, ws, s);
     }
-    if (conv_c1_supported(o, cin, cout, dt)) return launch_conv_c1_fwd(Px, w, bias, Py, o, cout, relu, s);
+    if (o.grow == 0 && conv_c1_supported(o, cin, cout, dt))
+        return launch_conv_c1_fwd(shifted(Px, o, 1, dt), w, bias, shifted(Py, o, cout, dt), o, cout, relu, s);
     return launch_conv_direct(Px, w, bias, Py, o, cin, cout, dt, relu, false, s);
 }
 
@@ -248,9 +250,7 @@ static int dgrad_impl(const void *Pdz, const void *w, const void *Pmask, void *P
         if (need && (!ws || ws_bytes < need || !aligned16(ws))) return SP_EWORKSPACE;
         return launch_conv_mfma(Pdz, w, nullptr, Pdx, o, cout, cin, false, true, ws, s, Pmask);
     }
-    rc = launch_conv_direct(Pdz, w, nullptr, Pdx, o, cout, cin, dt, false, true, s);
-    if (rc != SP_OK || !Pmask) return rc;
-    return launch_relu_bwd(Pdx, Pmask, Pdx, pv * cin, dt, s);      // element-wise, in place
+    return launch_conv_direct(Pdz, w, nullptr, Pdx, o, cout, cin, dt, false, true, s, 3, Pmask);
 }
 
 int conv3d_dgrad(const void *Pdz, const void *w, void *Pdx, const sp_geom_t *g, int cin, int cout,
@@ -276,8 +276,9 @@ int conv3d_wgrad(const void *Px, const void *Pdz, float *dw, float *db, const sp
     const size_t need = c1 ? wgrad_c1_ws_bytes(o, cout)
                            : (mfma ? wgrad_mfma_ws_bytes(o, cin, cout) : wgrad_direct_ws_bytes(o, cin, cout));
     if (need && (!ws || ws_bytes < need || !aligned16(ws))) return SP_EWORKSPACE;
-    if (c1) return launch_wgrad_c1(Px, Pdz, dw, db, o, cout, ws, s);
-    if (mfma) return launch_wgrad_mfma(Px, Pdz, dw, db, o, cin, cout, ws, s);
+    if (c1) return launch_wgrad_c1(shifted(Px, o, 1, dt), shifted(Pdz, o, cout, dt), dw, db, o, cout, ws, s);
+    if (mfma)
+        return launch_wgrad_mfma(shifted(Px, o, cin, dt), shifted(Pdz, o, cout, dt), dw, db, o, cin, cout, ws, s);
     return launch_wgrad_direct(Px, Pdz, dw, db, o, cin, cout, dt, ws, s);
 }
 
@@ -337,7 +338,8 @@ int conv3d_wgrad2(const void *Pxa, int ca, const void *Pxb, int cb, const void *
     if (!wgrad_mfma_supported(o, ca + cb, cout, dt)) return SP_EUNSUPPORTED;
     const size_t need = wgrad_mfma_ws_bytes(o, ca + cb, cout);
     if (!ws || ws_bytes < need || !aligned16(ws)) return SP_EWORKSPACE;
-    return launch_wgrad_mfma(Pxa, Pdz, dw, db, o, ca + cb, cout, ws, static_cast<hipStream_t>(stream), Pxb, ca);
+    return launch_wgrad_mfma(shifted(Pxa, o, ca, dt), shifted(Pdz, o, cout, dt), dw, db, o, ca + cb, cout, ws,
+                             static_cast<hipStream_t>(stream), shifted(Pxb, o, cb, dt), ca);
 }
 
 int sp_relu_bwd(const void *Pdy, const void *Py, void *Pdz, const sp_geom_t *g, int c, sp_dtype_t dt,
@@ -363,6 +365,7 @@ static int check_glue(const void *a, const void *b, const void *c, const sp_geom
     if (c1 <= 0 || c2 <= 0) return SP_EINVAL;
     if (!dtype_ok(dt) || !chan_ok(c1) || !chan_ok(c2)) return SP_EUNSUPPORTED;
     if (!aligned16(a) || !aligned16(b) || !aligned16(c)) return SP_EINVAL;
+    fine->grow = 0;            // these operations work on interiors only
     if (coarse) return make_coarse(*fine, coarse);
     return SP_OK;
 }
@@ -371,7 +374,8 @@ int sp_maxpool2_fwd(const void *Px, void *Py, const sp_geom_t *gf, int c, sp_dty
     Geo f, k;
     int rc = check_glue(Px, Py, Py, gf, c, c, dt, &f, &k);
     if (rc != SP_OK) return rc;
-    return launch_maxpool2(Px, nullptr, Py, f, k, c, dt, false, static_cast<hipStream_t>(stream));
+    return launch_maxpool2(shifted(Px, f, c, dt), nullptr, shifted(Py, k, c, dt), f, k, c, dt, false,
+                           static_cast<hipStream_t>(stream));
 }
 
 int sp_maxpool2_bwd(const void *Px, const void *Pdy, void *Pdx, const sp_geom_t *gf, int c, sp_dtype_t dt,
@@ -379,7 +383,8 @@ int sp_maxpool2_bwd(const void *Px, const void *Pdy, void *Pdx, const sp_geom_t 
     Geo f, k;
     int rc = check_glue(Px, Pdy, Pdx, gf, c, c, dt, &f, &k);
     if (rc != SP_OK) return rc;
-    return launch_maxpool2(Px, Pdy, Pdx, f, k, c, dt, true, static_cast<hipStream_t>(stream));
+    return launch_maxpool2(shifted(Px, f, c, dt), shifted(Pdy, k, c, dt), shifted(Pdx, f, c, dt), f, k, c, dt, true,
+                           static_cast<hipStream_t>(stream));
 }
 
 int sp_upconv2_fwd(const void *Px, const void *u, const float *bias, void *Py, const sp_geom_t *gf, int cin,
@@ -387,7 +392,8 @@ int sp_upconv2_fwd(const void *Px, const void *u, const float *bias, void *Py, c
     Geo f, k;
     int rc = check_glue(Px, u, Py, gf, cin, cout, dt, &f, &k);
     if (rc != SP_OK) return rc;
-    return launch_upconv2_fwd(Px, u, bias, Py, f, k, cin, cout, dt, static_cast<hipStream_t>(stream));
+    return launch_upconv2_fwd(shifted(Px, k, cin, dt), u, bias, shifted(Py, f, cout, dt), f, k, cin, cout, dt,
+                              static_cast<hipStream_t>(stream));
 }
 
 int sp_upconv2_dgrad(const void *Pdy, const void *u, void *Pdx, const sp_geom_t *gf, int cin, int cout,
@@ -395,7 +401,8 @@ int sp_upconv2_dgrad(const void *Pdy, const void *u, void *Pdx, const sp_geom_t 
     Geo f, k;
     int rc = check_glue(Pdy, u, Pdx, gf, cin, cout, dt, &f, &k);
     if (rc != SP_OK) return rc;
-    return launch_upconv2_dgrad(Pdy, u, Pdx, f, k, cin, cout, dt, static_cast<hipStream_t>(stream));
+    return launch_upconv2_dgrad(shifted(Pdy, f, cout, dt), u, shifted(Pdx, k, cin, dt), f, k, cin, cout, dt,
+                                static_cast<hipStream_t>(stream));
 }
 
 int sp_upconv2_wgrad(const void *Px, const void *Pdy, float *du, float *db, const sp_geom_t *gf, int cin,
@@ -405,7 +412,8 @@ int sp_upconv2_wgrad(const void *Px, const void *Pdy, float *du, float *db, cons
     if (rc != SP_OK) return rc;
     const size_t need = upconv2_wgrad_ws_bytes(f, k, cin, cout, dt);
     if (!ws || ws_bytes < need || !aligned16(ws)) return SP_EWORKSPACE;
-    return launch_upconv2_wgrad(Px, Pdy, du, db, f, k, cin, cout, dt, ws, static_cast<hipStream_t>(stream));
+    return launch_upconv2_wgrad(shifted(Px, k, cin, dt), shifted(Pdy, f, cout, dt), du, db, f, k, cin, cout, dt, ws,
+                                static_cast<hipStream_t>(stream));
 }
 
 int sp_pointwise_fwd(const void *Px, const void *p, const float *bias, void *Py, const sp_geom_t *g, int cin,
@@ -415,8 +423,8 @@ int sp_pointwise_fwd(const void *Px, const void *p, const float *bias, void *Py,
     if (rc != SP_OK) return rc;
     if (flags & ~static_cast<uint32_t>(SP_FLAG_RELU)) return SP_EINVAL;
     if (pointwise_small_supported(o, cin, cout, dt))
-        return launch_pointwise_small_fwd(Px, p, bias, Py, o, cin, cout, flags & SP_FLAG_RELU,
-                                          static_cast<hipStream_t>(stream));
+        return launch_pointwise_small_fwd(shifted(Px, o, cin, dt), p, bias, shifted(Py, o, cout, dt), o, cin, cout,
+                                          flags & SP_FLAG_RELU, static_cast<hipStream_t>(stream));
     return launch_conv_direct(Px, p, bias, Py, o, cin, cout, dt, flags & SP_FLAG_RELU, false,
                               static_cast<hipStream_t>(stream), 1);
 }
@@ -427,7 +435,8 @@ int sp_pointwise_dgrad(const void *Pdy, const void *p, void *Pdx, const sp_geom_
     int rc = check_glue(Pdy, p, Pdx, g, cin, cout, dt, &o, nullptr);
     if (rc != SP_OK) return rc;
     if (pointwise_small_supported(o, cin, cout, dt))
-        return launch_pointwise_small_dgrad(Pdy, p, Pdx, o, cin, cout, static_cast<hipStream_t>(stream));
+        return launch_pointwise_small_dgrad(shifted(Pdy, o, cout, dt), p, shifted(Pdx, o, cin, dt), o, cin, cout,
+                                            static_cast<hipStream_t>(stream));
     return launch_conv_direct(Pdy, p, nullptr, Pdx, o, cout, cin, dt, false, true,
                               static_cast<hipStream_t>(stream), 1);
 }
@@ -441,7 +450,8 @@ int sp_pointwise_wgrad(const void *Px, const void *Pdy, float *dp, float *db, co
     const size_t need = small ? pointwise_small_wgrad_ws_bytes(o, cin, cout) : wgrad_direct_ws_bytes(o, cin, cout, 1);
     if (!ws || ws_bytes < need || !aligned16(ws)) return SP_EWORKSPACE;
     if (small)
-        return launch_pointwise_small_wgrad(Px, Pdy, dp, db, o, cin, cout, ws, static_cast<hipStream_t>(stream));
+        return launch_pointwise_small_wgrad(shifted(Px, o, cin, dt), shifted(Pdy, o, cout, dt), dp, db, o, cin, cout, ws,
+                                            static_cast<hipStream_t>(stream));
     return launch_wgrad_direct(Px, Pdy, dp, db, o, cin, cout, dt, ws, static_cast<hipStream_t>(stream), 1);
 }
 
@@ -461,8 +471,8 @@ int sp_dice_ce_loss(const void *Plogits, const void *Plabels, void *Pdlogits, fl
     if (!(eps >= 0.f) || !(w_dice >= 0.f) || !(w_ce >= 0.f)) return SP_EINVAL;
     const size_t need = loss_ws_bytes(o, classes);
     if (!ws || ws_bytes < need || !aligned16(ws)) return SP_EWORKSPACE;
-    return launch_loss(Plogits, Plabels, Pdlogits, loss, stats, o, classes, dt, w_dice, w_ce, eps, ws,
-                       static_cast<hipStream_t>(stream));
+    return launch_loss(shifted(Plogits, o, classes, dt), shifted(Plabels, o, 1, dt), shifted(Pdlogits, o, classes, dt),
+                       loss, stats, o, classes, dt, w_dice, w_ce, eps, ws, static_cast<hipStream_t>(stream));
 }
 
 int sp_concat(const void *Pa, int ca, const void *Pb, int cb, void *Pout, const sp_geom_t *g, sp_dtype_t dt,

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <type_traits>
 #include "sp3d.h"
 
 namespace sp3d {
@@ -13,6 +14,8 @@ struct Geo {
     int td, th, tw;          // tile extents
     int pd, ph, pw;          // padded tile extents (t + 2*halo)
     int halo;
+    int grow;                // conv3d_fwd / conv3d_dgrad: output box = interior grown by this many voxels
+                             // towards every neighbouring tile (0 <= grow < halo); other operations ignore it
     int ntiles;              // n * gd * gh * gw
     long long tile_vox;      // pd * ph * pw   (voxels per padded tile)
     long long int_vox;       // td * th * tw   (interior voxels per tile)
@@ -20,6 +23,14 @@ struct Geo {
 };
 
 int make_geo(const sp_geom_t *g, Geo *out);       // SP_OK or error code
+// Kernels that touch tile interiors only are written for a one-voxel margin: interior voxel (i, j, k) at
+// padded coordinates (i + 1, j + 1, k + 1), strides ph * pw and pw.  A tensor with a wider margin is handed
+// to them through this offset (in voxels) on its base pointer: the strides stay those of the real layout.
+inline long long interior_shift(const Geo &g) { return (g.halo - 1) * (1LL * g.ph * g.pw + g.pw + 1); }
+template <typename T> inline T *shifted(T *p, const Geo &g, int c, sp_dtype_t dt) {
+    typedef typename std::conditional<std::is_const<T>::value, const char, char>::type B;
+    return p ? reinterpret_cast<T *>(reinterpret_cast<B *>(p) + interior_shift(g) * c * (dt == SP_BF16 ? 2 : 4)) : p;
+}
 int record_hip(hipError_t e);                      // stores e, returns SP_ELAUNCH if e != success
 inline size_t elem_size(sp_dtype_t dt) { return dt == SP_BF16 ? 2 : 4; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -47,9 +58,11 @@ int launch_halo_exchange(void *P, const Geo &g, int c, sp_dtype_t dt, hipStream_
 int launch_relu_bwd(const void *dy, const void *y, void *dz, size_t elems, sp_dtype_t dt,
                     hipStream_t s);
 
-// ks = kernel extent per axis (3, or 1 for the 1x1x1 convolution)
+// ks = kernel extent per axis (3, or 1 for the 1x1x1 convolution); mask (optional): tensor laid out like Pout,
+// results are zeroed where it is not positive
 int launch_conv_direct(const void *Pin, const void *w, const float *bias, void *Pout, const Geo &g,
-                       int cin, int cout, sp_dtype_t dt, bool relu, bool dgrad, hipStream_t s, int ks = 3);
+                       int cin, int cout, sp_dtype_t dt, bool relu, bool dgrad, hipStream_t s, int ks = 3,
+                       const void *mask = nullptr);
 size_t wgrad_direct_ws_bytes(const Geo &g, int cin, int cout, int ks = 3);
 int launch_wgrad_direct(const void *Px, const void *Pdz, float *dw, float *db, const Geo &g,
                         int cin, int cout, sp_dtype_t dt, void *ws, hipStream_t s, int ks = 3);
@@ -151,6 +164,32 @@ __device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv &f) {
 __device__ __forceinline__ uint32_t fmod_(uint32_t n, uint32_t q, const FastDiv &f) { return n - q * f.d; }
 
 // device helpers ------------------------------------------------------------------------------
+// Output box of a convolution on one tile: the interior, grown by g.grow voxels on every side where the tile
+// has a neighbour in the grid (so the box never leaves the volume: beyond the volume border an activation is
+// zero padding, not a convolution result).  org = voxel offset, inside the padded tile, of the corner one
+// voxel before the box on every axis: a kernel written for a one-voxel margin sees the box as the interior
+// of a padded tile that starts there.
+struct TileBox {
+    int bd, bh, bw;
+    long long org;
+};
+__device__ __forceinline__ TileBox tile_box(const Geo &g, int tile) {
+    TileBox b;
+    int ld = g.halo, lh = g.halo, lw = g.halo;
+    b.bd = g.td; b.bh = g.th; b.bw = g.tw;
+    if (g.grow > 0) {
+        const int tc = tile % g.gw, t1 = tile / g.gw;
+        const int tb = t1 % g.gh, ta = (t1 / g.gh) % g.gd;
+        if (ta > 0) { ld -= g.grow; b.bd += g.grow; }
+        if (ta < g.gd - 1) b.bd += g.grow;
+        if (tb > 0) { lh -= g.grow; b.bh += g.grow; }
+        if (tb < g.gh - 1) b.bh += g.grow;
+        if (tc > 0) { lw -= g.grow; b.bw += g.grow; }
+        if (tc < g.gw - 1) b.bw += g.grow;
+    }
+    b.org = (1LL * (ld - 1) * g.ph + lh - 1) * g.pw + lw - 1;
+    return b;
+}
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) {
     return __uint_as_float(static_cast<uint32_t>(b) << 16);
 }

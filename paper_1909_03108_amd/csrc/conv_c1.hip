@@ -49,8 +49,8 @@ __device__ __forceinline__ int tap_off(int t) {
     return t < 27 ? ((t / 9) * XH + (t / 3) % 3) * XW + t % 3 : 0;
 }
 
-// Stage the input voxels around brick (tile, d0, h0, w0) (interior coordinates).  Positions outside
-// the padded tile (ragged bricks) are staged as zero.
+// Stage the input voxels around brick (tile, d0, h0, w0) (interior coordinates).  Positions beyond the
+// interior and the one voxel around it (ragged bricks) are staged as zero.
 __device__ __forceinline__ void stage_x(const C1Args &a, uint16_t *lx, int tile, int d0, int h0, int w0) {
     const Geo &g = a.g;
     const uint16_t *tx = a.x + static_cast<size_t>(tile) * g.tile_vox;
@@ -59,7 +59,7 @@ __device__ __forceinline__ void stage_x(const C1Args &a, uint16_t *lx, int tile,
         const int e = threadIdx.x + i * kThreads;
         if (e < XVOX) {
             const int pd = e / (XH * XW), r = e % (XH * XW), ph = r / XW, pc = r % XW;
-            const bool ok = d0 + pd < g.pd && h0 + ph < g.ph && w0 + pc < g.pw;
+            const bool ok = d0 + pd < g.td + 2 && h0 + ph < g.th + 2 && w0 + pc < g.tw + 2;
             lx[e] = ok ? tx[(static_cast<size_t>(d0 + pd) * g.ph + h0 + ph) * g.pw + w0 + pc] : uint16_t(0);
         }
     }

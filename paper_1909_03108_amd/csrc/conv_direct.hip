@@ -20,30 +20,45 @@ template <> __device__ __forceinline__ void stf<uint16_t>(uint16_t *p, long long
     p[i] = f32_to_bf16(v);
 }
 
-// One thread per (interior voxel, output channel).  With DGRAD the taps are mirrored and the weight
+// One thread per (voxel of the output box, output channel).  With DGRAD the taps are mirrored and the weight
 // tensor is read as w[tap][ko][ki] (ko = this kernel's output channel = the layer's input channel).
 // KS = kernel extent per axis: 3 (the 3x3x3 convolution) or 1 (the 1x1x1 classifier).
+// The threads cover the interior grown by g.grow on every side; a thread whose voxel lies beyond a side on
+// which its tile has no neighbour (beyond the volume) has nothing to do.
 template <typename E, bool DGRAD, int KS>
 __global__ __launch_bounds__(kThreads) void conv_direct_kernel(const E *__restrict__ Pin,
                                                                const E *__restrict__ w,
                                                                const float *__restrict__ bias,
                                                                E *__restrict__ Pout, Geo g, int ki,
-                                                               int ko, int relu, long long total) {
+                                                               int ko, int relu, long long total,
+                                                               const E *__restrict__ mask) {
     const long long idx = 1LL * blockIdx.x * kThreads + threadIdx.x;
     if (idx >= total) return;
     const int co = static_cast<int>(idx % ko);
-    const long long v = idx / ko;                       // interior voxel over all tiles
-    const long long tile = v / g.int_vox;
-    const unsigned r = static_cast<unsigned>(v % g.int_vox);
-    const unsigned thw = static_cast<unsigned>(g.th) * g.tw;
-    const unsigned ld = r / thw, lh = (r % thw) / g.tw, lw = r % g.tw;
+    const long long v = idx / ko;                       // voxel of the grown boxes of all tiles
+    const int ed = g.td + 2 * g.grow, eh = g.th + 2 * g.grow, ew = g.tw + 2 * g.grow;
+    const long long box_vox = 1LL * ed * eh * ew;
+    const long long tile = v / box_vox;
+    const unsigned r = static_cast<unsigned>(v % box_vox);
+    const unsigned ehw = static_cast<unsigned>(eh) * ew;
+    // padded coordinates of the output voxel
+    const int pd = static_cast<int>(r / ehw) + g.halo - g.grow, ph = static_cast<int>((r % ehw) / ew) + g.halo - g.grow,
+              pw = static_cast<int>(r % ew) + g.halo - g.grow;
+    if (g.grow > 0) {
+        const int tc = static_cast<int>(tile % g.gw), tb = static_cast<int>((tile / g.gw) % g.gh),
+                  ta = static_cast<int>((tile / (1LL * g.gw * g.gh)) % g.gd);
+        if ((pd < g.halo && ta == 0) || (pd >= g.halo + g.td && ta == g.gd - 1) || (ph < g.halo && tb == 0) ||
+            (ph >= g.halo + g.th && tb == g.gh - 1) || (pw < g.halo && tc == 0) ||
+            (pw >= g.halo + g.tw && tc == g.gw - 1))
+            return;
+    }
     const long long base = tile * g.tile_vox;
     float acc = bias ? bias[co] : 0.f;
-    constexpr int O = 1 - KS / 2;     // tap 0 reads padded coordinate (interior coordinate + O), halo = 1
+    constexpr int O = KS / 2;         // tap k reads the input voxel at output coordinate + k - O
     for (int kd = 0; kd < KS; ++kd)
         for (int kh = 0; kh < KS; ++kh)
             for (int kw = 0; kw < KS; ++kw) {
-                const long long pv = base + (1LL * (ld + kd + O) * g.ph + lh + kh + O) * g.pw + lw + kw + O;
+                const long long pv = base + (1LL * (pd + kd - O) * g.ph + ph + kh - O) * g.pw + pw + kw - O;
                 const E *xin = Pin + pv * ki;
                 const int tap = DGRAD ? ((KS - 1 - kd) * KS + (KS - 1 - kh)) * KS + (KS - 1 - kw)
                                       : (kd * KS + kh) * KS + kw;
@@ -57,7 +72,8 @@ __global__ __launch_bounds__(kThreads) void conv_direct_kernel(const E *__restri
                 }
             }
     if (relu && acc < 0.f) acc = 0.f;
-    const long long ov = base + (1LL * (ld + g.halo) * g.ph + lh + g.halo) * g.pw + lw + g.halo;
+    const long long ov = base + (1LL * pd * g.ph + ph) * g.pw + pw;
+    if (mask && !(ldf<E>(mask, ov * ko + co) > 0.f)) acc = 0.f;      // backward of the ReLU that produced the input
     stf<E>(Pout, ov * ko + co, acc);
 }
 
@@ -74,7 +90,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_direct_kernel(const E *__restr
     __shared__ float red[kThreads];
     const int tapci = blockIdx.x, chunk = blockIdx.y;
     const int tap = tapci / cin, ci = tapci % cin;
-    constexpr int O = 1 - KS / 2;
+    const int O = g.halo - KS / 2;    // tap k reads padded coordinate (interior coordinate + k + O)
     const int kd = tap / (KS * KS) + O, kh = (tap / KS) % KS + O, kw = tap % KS + O;
     const int nvl = kThreads / cw;
     const int col = threadIdx.x % cw, vl = threadIdx.x / cw;
@@ -181,15 +197,16 @@ int launch_reduce_partials(const float *part, float *out, int nparts, long long 
 }
 
 int launch_conv_direct(const void *Pin, const void *w, const float *bias, void *Pout, const Geo &g,
-                       int ki, int ko, sp_dtype_t dt, bool relu, bool dgrad, hipStream_t s, int ks) {
-    const long long total = 1LL * g.ntiles * g.int_vox * ko;
+                       int ki, int ko, sp_dtype_t dt, bool relu, bool dgrad, hipStream_t s, int ks,
+                       const void *mask) {
+    const long long total = 1LL * g.ntiles * (g.td + 2 * g.grow) * (g.th + 2 * g.grow) * (g.tw + 2 * g.grow) * ko;
     const long long blocks = (total + kThreads - 1) / kThreads;
     if (blocks > 0x7fffffffLL) return SP_EGEOM;
     dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
 #define SP3D_LAUNCH(E, DG, KS)                                                                         \
     hipLaunchKernelGGL((conv_direct_kernel<E, DG, KS>), grid, block, 0, s, static_cast<const E *>(Pin), \
                        static_cast<const E *>(w), bias, static_cast<E *>(Pout), g, ki, ko,             \
-                       relu ? 1 : 0, total)
+                       relu ? 1 : 0, total, static_cast<const E *>(mask))
 #define SP3D_LAUNCH_KS(E, DG) do { if (ks == 1) SP3D_LAUNCH(E, DG, 1); else SP3D_LAUNCH(E, DG, 3); } while (0)
     if (dt == SP_BF16) {
         if (dgrad) SP3D_LAUNCH_KS(uint16_t, true); else SP3D_LAUNCH_KS(uint16_t, false);

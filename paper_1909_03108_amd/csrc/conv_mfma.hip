@@ -294,8 +294,11 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
     const int ph_i = t % a.nh; t /= a.nh;
     const int pd_i = t % a.nd; t /= a.nd;
     const int tile = t;
-    const int d0 = pd_i * a.dchunk, h0 = ph_i * PH, w0 = pw_i * PW;      // interior coordinates
-    const int dn = min(a.dchunk, g.td - d0);                            // output planes to produce
+    const int d0 = pd_i * a.dchunk, h0 = ph_i * PH, w0 = pw_i * PW;      // coordinates inside the output box
+    const TileBox bx = tile_box(g, tile);
+    const int dn = min(a.dchunk, bx.bd - d0);                           // output planes to produce
+    // the patches are laid out for the largest box of the grid; a tile at the volume border has a smaller one
+    if (dn <= 0 || h0 >= bx.bh || w0 >= bx.bw) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, hi = lane >> 5;
 
@@ -309,29 +312,29 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
 
     Ctx<HAS_BIAS> c;
     c.plane_elems = static_cast<size_t>(g.ph) * g.pw * a.in_cs;
-    c.tin0 = a.in + static_cast<size_t>(tile) * g.tile_vox * a.in_cs + d0 * c.plane_elems + a.in_co;
+    c.tin0 = a.in + (static_cast<size_t>(tile) * g.tile_vox + bx.org) * a.in_cs + d0 * c.plane_elems + a.in_co;
     c.nplanes = dn + 2;
     // Wave w fills chunk plane w (channels 8w..8w+7 of every voxel); load j covers patch-local voxels
-    // 64j..64j+63.  Voxels outside the padded tile (ragged patches) are clamped to a valid address;
-    // they only feed outputs that are never stored.
+    // 64j..64j+63.  Voxels beyond the box and its one-voxel surround (ragged patches) are clamped to a valid
+    // address; they only feed outputs that are never stored.
 #pragma unroll
     for (int j = 0; j < LOADS; ++j) {
         const int v = 64 * j + lane;
-        const int row = min(h0 + v / LCOLS, g.ph - 1), colv = min(w0 + v % LCOLS, g.pw - 1);
+        const int row = min(h0 + v / LCOLS, bx.bh + 1), colv = min(w0 + v % LCOLS, bx.bw + 1);
         c.goff[j] = (row * g.pw + colv) * a.in_cs + wave * 8;
     }
     c.lds_stage = lds + wave * CH_STRIDE;
     const OutDst od = out_dest(a, cj);
     c.orow = static_cast<size_t>(g.pw) * od.cs;
     c.oplane = static_cast<size_t>(g.ph) * c.orow;
-    const size_t opos = static_cast<size_t>(tile) * g.tile_vox * od.cs +
+    const size_t opos = (static_cast<size_t>(tile) * g.tile_vox + bx.org) * od.cs +
                         ((static_cast<size_t>(d0 + 1) * g.ph + h0 + wave * RH + 1) * g.pw + w0 + col + 1) * od.cs +
                         od.co + 4 * hi;
     c.obase = od.base + opos;
     c.mbase = a.mask + opos;
     c.pbase = a.part + od.part_off + opos;
 #pragma unroll
-    for (int h = 0; h < RH; ++h) c.okrow[h] = h0 + wave * RH + h < g.th && w0 + col < g.tw;
+    for (int h = 0; h < RH; ++h) c.okrow[h] = h0 + wave * RH + h < bx.bh && w0 + col < bx.bw;
     // the bias is folded into the accumulators: a slot starts from the bias instead of zero
     // (without a bias the slots start from the constant zero and no registers are spent on it)
     if (HAS_BIAS) {
@@ -416,7 +419,7 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
                 }
             }
     };
-    if (h0 + PH <= g.th && w0 + PW <= g.tw) march(std::true_type{});
+    if (h0 + PH <= bx.bh && w0 + PW <= bx.bw) march(std::true_type{});
     else march(std::false_type{});
 #undef SP3D_STEP_END
 }
@@ -658,8 +661,8 @@ __device__ __forceinline__ void drain_step(const Ctx<HAS_BIAS> &c, int Dp, f32x1
 }
 
 template <int ROLE, int MODE, bool HAS_BIAS, int RELU>
-__device__ __forceinline__ void run(const ConvArgs &a, char *lds, int tile, int d0, int h0, int w0, int dn, int cj,
-                                    int rg) {
+__device__ __forceinline__ void run(const ConvArgs &a, char *lds, int tile, const TileBox &bx, int d0, int h0, int w0,
+                                    int dn, int cj, int rg) {
     const Geo &g = a.g;
     const int lane = threadIdx.x & 63;
     const int col = lane & 31, hi = lane >> 5;
@@ -678,13 +681,13 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int tile, int 
     const uint16_t *src = ROLE ? a.in2 : a.in;
     const int src_cs = ROLE ? a.in2_cs : a.in_cs, src_co = ROLE ? a.in2_co : a.in_co;
     c.plane_elems = static_cast<size_t>(g.ph) * g.pw * src_cs;
-    c.tin0 = src + static_cast<size_t>(tile) * g.tile_vox * src_cs + d0 * c.plane_elems + src_co;
+    c.tin0 = src + (static_cast<size_t>(tile) * g.tile_vox + bx.org) * src_cs + d0 * c.plane_elems + src_co;
     c.nplanes = dn + 2;
     // this wave fills chunk planes 2 rg and 2 rg + 1 (channels 16 rg .. 16 rg + 15) of its input chunk
 #pragma unroll
     for (int j = 0; j < LOADS; ++j) {
         const int v = 64 * (j % CP_LOADS) + lane;
-        const int row = min(h0 + v / LCOLS, g.ph - 1), colv = min(w0 + v % LCOLS, g.pw - 1);
+        const int row = min(h0 + v / LCOLS, bx.bh + 1), colv = min(w0 + v % LCOLS, bx.bw + 1);
         c.goff[j] = (row * g.pw + colv) * src_cs + (2 * rg + j / CP_LOADS) * 8;       // clamped: always addressable
     }
     c.tail_lane = 64 * (CP_LOADS - 1) + lane < PLANE_VOX;
@@ -693,14 +696,14 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int tile, int 
     const OutDst od = out_dest(a, cj);
     c.orow = static_cast<size_t>(g.pw) * od.cs;
     c.oplane = static_cast<size_t>(g.ph) * c.orow;
-    const size_t opos = static_cast<size_t>(tile) * g.tile_vox * od.cs +
+    const size_t opos = (static_cast<size_t>(tile) * g.tile_vox + bx.org) * od.cs +
                         ((static_cast<size_t>(d0 + 1) * g.ph + h0 + rg * RH + 1) * g.pw + w0 + col + 1) * od.cs +
                         od.co + 4 * hi;
     c.obase = od.base + opos;
     c.mbase = a.mask + opos;
     c.pbase = a.part + od.part_off + opos;
 #pragma unroll
-    for (int h = 0; h < RH; ++h) c.okrow[h] = h0 + rg * RH + h < g.th && w0 + col < g.tw;
+    for (int h = 0; h < RH; ++h) c.okrow[h] = h0 + rg * RH + h < bx.bh && w0 + col < bx.bw;
     if (HAS_BIAS) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) c.bv[HAS_BIAS ? i : 0] = a.bias[C * cj + 8 * (i >> 2) + 4 * hi + (i & 3)];
@@ -764,7 +767,7 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int tile, int 
 #undef SP3D_STEP
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // clamped staging loads of the last steps
     };
-    if (h0 + PH <= g.th && w0 + PW <= g.tw) march(std::true_type{});
+    if (h0 + PH <= bx.bh && w0 + PW <= bx.bw) march(std::true_type{});
     else march(std::false_type{});
 #undef SP3D_STEP_END
 }
@@ -783,11 +786,13 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_pair_kernel(ConvArgs a)
     const int pd_i = t % a.nd; t /= a.nd;
     const int tile = t;
     const int d0 = pd_i * a.dchunk, h0 = ph_i * PH, w0 = pw_i * PW;
-    const int dn = min(a.dchunk, g.td - d0);
+    const TileBox bx = tile_box(g, tile);
+    const int dn = min(a.dchunk, bx.bd - d0);
+    if (dn <= 0 || h0 >= bx.bh || w0 >= bx.bw) return;     // patch of the largest box that this tile's box lacks
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // two copies of the march, one per role, so that each is straight-line code for the scheduler
-    if (wave < 2) run<0, MODE, HAS_BIAS, RELU>(a, lds, tile, d0, h0, w0, dn, cj, wave & 1);
-    else run<1, MODE, HAS_BIAS, RELU>(a, lds, tile, d0, h0, w0, dn, cj, wave & 1);
+    if (wave < 2) run<0, MODE, HAS_BIAS, RELU>(a, lds, tile, bx, d0, h0, w0, dn, cj, wave & 1);
+    else run<1, MODE, HAS_BIAS, RELU>(a, lds, tile, bx, d0, h0, w0, dn, cj, wave & 1);
 }
 
 }  // namespace wide
@@ -857,14 +862,16 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
     // input channels in multiples of 64: two chunks per launch, summed on chip (4-row patches)
     const bool pairs = ki % (2 * C) == 0;
     const int ph = pairs ? wide::PH : PH;
-    a.nh = (g.th + ph - 1) / ph;
-    a.nw = (g.tw + PW - 1) / PW;
-    // D chunk: whole tile depth unless that leaves the chip short of workgroups
+    // patches cover the largest output box of the grid (the interior grown on both sides)
+    const int ed = g.td + 2 * g.grow, eh = g.th + 2 * g.grow, ew = g.tw + 2 * g.grow;
+    a.nh = (eh + ph - 1) / ph;
+    a.nw = (ew + PW - 1) / PW;
+    // D chunk: whole box depth unless that leaves the chip short of workgroups
     long long base = 1LL * g.ntiles * a.nh * a.nw * nco;
-    int dchunk = g.td;
-    while (base * ((g.td + dchunk - 1) / dchunk) < 1024 && dchunk > 16) dchunk = (dchunk + 1) / 2;
+    int dchunk = ed;
+    while (base * ((ed + dchunk - 1) / dchunk) < 1024 && dchunk > 16) dchunk = (dchunk + 1) / 2;
     a.dchunk = dchunk;
-    a.nd = (g.td + dchunk - 1) / dchunk;
+    a.nd = (ed + dchunk - 1) / dchunk;
     const long long nb = base * a.nd;
     if (nb > 0x7ffffff0LL) return SP_EGEOM;
     a.nblocks = static_cast<int>(nb);

@@ -484,7 +484,8 @@ int make_coarse(const Geo &gf, Geo *gc) {
     if ((gf.td | gf.th | gf.tw) & 1) return SP_EGEOM;
     Geo o = gf;
     o.td = gf.td / 2; o.th = gf.th / 2; o.tw = gf.tw / 2;
-    o.pd = o.td + 2; o.ph = o.th + 2; o.pw = o.tw + 2;
+    if (o.td < o.halo || o.th < o.halo || o.tw < o.halo) return SP_EGEOM;
+    o.pd = o.td + 2 * o.halo; o.ph = o.th + 2 * o.halo; o.pw = o.tw + 2 * o.halo;
     o.tile_vox = 1LL * o.pd * o.ph * o.pw;
     o.int_vox = 1LL * o.td * o.th * o.tw;
     o.msg_vox = o.tile_vox - o.int_vox;

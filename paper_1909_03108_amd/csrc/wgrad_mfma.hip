@@ -192,15 +192,15 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
         const uint16_t *tx = xs.base + static_cast<size_t>(tile) * g.tile_vox * xs.cs + x_co;
         const uint16_t *tz = a.dz + static_cast<size_t>(tile) * g.tile_vox * a.dz_cs + dz_co;
 
-        // source offsets inside a plane and validity (x: inside the padded tile; dz: tile interior)
+        // source offsets inside a plane and validity (x: the interior and one voxel around it; dz: tile interior)
         const int xsrc0 = ((h0 + sr) * g.pw + w0 + sv) * xs.cs + c4 * 8;
         const int xsrce = ((h0 + er) * g.pw + w0 + ev) * xs.cs + c4 * 8;
         const int zsrc0 = ((h0 + sr + 1) * g.pw + w0 + sv + 1) * a.dz_cs + c4 * 8;
         bool xok[3], zok[2];
 #pragma unroll
         for (int i = 0; i < 3; ++i)
-            xok[i] = sr + 4 * i < XR && h0 + sr + 4 * i < g.ph && w0 + sv < g.pw;
-        const bool eok = tid < 8 * XR && h0 + er < g.ph && w0 + ev < g.pw;
+            xok[i] = sr + 4 * i < XR && h0 + sr + 4 * i < g.th + 2 && w0 + sv < g.tw + 2;
+        const bool eok = tid < 8 * XR && h0 + er < g.th + 2 && w0 + ev < g.tw + 2;
 #pragma unroll
         for (int i = 0; i < 2; ++i) zok[i] = h0 + sr + 4 * i < g.th && w0 + sv < g.tw;
 

@@ -24,11 +24,16 @@ EXPORTS = ["sp_padded_elems", "sp_msg_elems", "sp_workspace_bytes", "sp_check_ge
 
 
 class Geom(ctypes.Structure):
-    """sp_geom_t: volume extents, tile grid (D,H,W order) and halo width."""
-    _fields_ = [(k, ctypes.c_int32) for k in ("n", "d", "h", "w", "gd", "gh", "gw", "halo")]
+    """sp_geom_t: volume extents, tile grid (D,H,W order), margin width of the layout, and by how much the
+    convolutions grow their output box beyond the interior (0 unless several layers share one exchange)."""
+    _fields_ = [(k, ctypes.c_int32) for k in ("n", "d", "h", "w", "gd", "gh", "gw", "halo", "grow")]
 
-    def __init__(self, n, dhw, grid, halo=1):
-        super().__init__(n, dhw[0], dhw[1], dhw[2], grid[0], grid[1], grid[2], halo)
+    def __init__(self, n, dhw, grid, halo=1, grow=0):
+        super().__init__(n, dhw[0], dhw[1], dhw[2], grid[0], grid[1], grid[2], halo, grow)
+
+    def grown(self, grow):
+        """The same geometry with another `grow`."""
+        return Geom(self.n, (self.d, self.h, self.w), (self.gd, self.gh, self.gw), self.halo, grow)
 
     @property
     def tile(self):

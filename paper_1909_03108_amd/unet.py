@@ -10,6 +10,11 @@ own blocks), 2x2x2 max-pool between levels; the last level is the bottleneck; de
 encoder: 2x2x2 stride-2 transposed conv halving the channels, concat (skip, up), `convs` 3x3x3 conv +
 ReLU; a final 1x1x1 conv to `classes`.  Biases are
 zero and not passed.  Every 3x3x3 conv input is halo-exchanged first (sp_halo_exchange: pack, delivery and unpack in one pass).
+
+With `halo` = 2 the tensors carry margins that wide and two consecutive layers of a block share
+one exchange (the overlap idea of the paper's Sec. 1 applied to a short stack): the first layer of such a group
+also computes the voxels around the tile that the later ones read (`grow`), and the backward pass does the same
+with the gradients.  The results are bit for bit those of `halo` = 1.
 """
 import numpy as np
 import torch
@@ -40,12 +45,17 @@ def layer_plan(channels=(32, 64, 128, 256), in_ch=1, classes=3, convs=2):
 
 class UNet:
     def __init__(self, n, dhw, grid, weights, channels=(32, 64, 128, 256), in_ch=1, classes=3,
-                 dt=sp3d.SP_BF16, convs=2):
+                 dt=sp3d.SP_BF16, convs=2, halo=1):
         self.channels, self.in_ch, self.classes, self.dt = tuple(channels), in_ch, classes, dt
         self.convs = convs
+        # Runs of more than two layers would need ReLU masks further around the tiles in the backward pass than
+        # the forward pass produces (layer j of a run needs its input's mask j voxels out, the forward pass
+        # leaves it run length - j voxels out).
+        assert 1 <= halo <= 2
+        self.halo = halo
         self.free = {}                        # (padded shape, channels) -> released gradient buffers
         self.L = len(channels)
-        self.g = [sp3d.Geom(n, tuple(e >> i for e in dhw), grid) for i in range(self.L)]
+        self.g = [sp3d.Geom(n, tuple(e >> i for e in dhw), grid, halo) for i in range(self.L)]
         for g in self.g:
             assert sp3d.sp_check_geom(g) == sp3d.SP_OK
         self.w = weights                      # name -> device tensor
@@ -78,47 +88,80 @@ class UNet:
         """the two-tensor convolution entry points need bf16 and channel counts in multiples of 32"""
         return self.dt == sp3d.SP_BF16 and c % 32 == 0
 
+    def _can_grow(self, cin, cout):
+        """kernels that compute a grown box: the matrix-core ones (bf16, channels in multiples of 32) and the
+        generic fp32 one"""
+        return self.dt != sp3d.SP_BF16 or (cin % 32 == 0 and cout % 32 == 0)
+
+    def _groups(self, cin, c):
+        """Split the block's layers into runs that share one exchange: [(first layer, number of layers)]."""
+        out, k = [], 0
+        while k < self.convs:
+            s = min(self.halo, self.convs - k) if self._can_grow(cin if k == 0 else c, c) and self._can_grow(c, c) else 1
+            out.append((k, s))
+            k += s
+        return out
+
+    def _plan(self, cin, c):
+        """per layer: (exchange before the forward pass, forward grow, position j in its group, group size)"""
+        plan = {}
+        for k0, s in self._groups(cin, c):
+            for j in range(s):
+                plan[k0 + j] = (j == 0, s - 1 - j, j, s)
+        return plan
+
     def _exchange(self, P, g, c):
         """All tiles share this GPU's memory, so margins are filled straight from the neighbours' interiors."""
         sp3d.sp_halo_exchange(P, g, c, self.dt)
 
-    def _conv(self, Px, name, g, cin, cout):
-        """Px must hold its halos.  Returns relu(conv(Px)) as padded tiles (margins zero)."""
+    def _conv(self, Px, name, g, cin, cout, grow=0):
+        """Px must hold its halos.  Returns relu(conv(Px)) as padded tiles (written: the interiors and `grow`
+        voxels around them)."""
         Py = self._buf(name + ".y", g, cout)
-        sp3d.conv3d_fwd(Px, self.w[name], None, Py, g, cin, cout, self.dt, sp3d.SP_FLAG_RELU,
-                        self._ws(sp3d.SP_OP_FWD, g, cin, cout))
+        gg = g.grown(grow) if grow else g
+        sp3d.conv3d_fwd(Px, self.w[name], None, Py, gg, cin, cout, self.dt, sp3d.SP_FLAG_RELU,
+                        self._ws(sp3d.SP_OP_FWD, gg, cin, cout))
         return Py
 
     def _block_fwd(self, block, P, g, cin, c, A, P2=None):
         """`convs` conv + ReLU layers; saves every layer input (with halos) and the block output in A.
         With P2 the block input is concat(P, P2) (cin / 2 channels each), never materialised."""
+        plan = self._plan(cin, c)
         for k in range(self.convs):
             name = "%s_%s" % (block, LETTERS[k])
+            exch, grow = plan[k][0], plan[k][1]
             if k == 0 and P2 is not None:
                 ca = cin // 2
                 self._exchange(P, g, ca)
                 self._exchange(P2, g, ca)
                 A[name + ".x"] = (P, P2)
                 Py = self._buf(name + ".y", g, c)
-                sp3d.conv3d_fwd2(P, ca, P2, ca, self.w[name], None, Py, g, c, self.dt, sp3d.SP_FLAG_RELU,
-                                 self._ws(sp3d.SP_OP_FWD, g, cin, c))
+                gg = g.grown(grow) if grow else g
+                sp3d.conv3d_fwd2(P, ca, P2, ca, self.w[name], None, Py, gg, c, self.dt, sp3d.SP_FLAG_RELU,
+                                 self._ws(sp3d.SP_OP_FWD, gg, cin, c))
                 P = Py
                 continue
-            self._exchange(P, g, cin if k == 0 else c)
+            if exch:
+                self._exchange(P, g, cin if k == 0 else c)
             A[name + ".x"] = P
-            P = self._conv(P, name, g, cin if k == 0 else c, c)
+            P = self._conv(P, name, g, cin if k == 0 else c, c, grow)
         A[block + ".y"] = P
         return P
 
     def _block_bwd(self, block, Pg, g, cin, c, grads, need_dx=True):
         """backward of a block, last layer first; layer k's output is layer k + 1's input"""
         A = self.A
+        plan = self._plan(cin, c)
         for k in range(self.convs - 1, -1, -1):
             name = "%s_%s" % (block, LETTERS[k])
             Py = A[block + ".y"] if k == self.convs - 1 else A["%s_%s.x" % (block, LETTERS[k + 1])]
-            # layer k > 0 reads the ReLU output of layer k - 1: its data gradient applies that mask itself
+            # Layer k > 0 reads the ReLU output of layer k - 1: its data gradient applies that mask itself.
+            # Inside a run of layers that share one exchange only the last layer's d/dz is exchanged; layer j of
+            # the run then also produces the j voxels of d/dx around the tile that layer j - 1 reads.
+            j, s = plan[k][2], plan[k][3]
             Pg = self._conv_bwd(name, A[name + ".x"], Py, Pg, g, cin if k == 0 else c, c, grads,
-                                need_dx=(need_dx or k > 0), masked=(k < self.convs - 1), mask_next=(k > 0))
+                                need_dx=(need_dx or k > 0), masked=(k < self.convs - 1), mask_next=(k > 0),
+                                exchange=(j == s - 1), grow=j)
         return Pg
 
     # gradient buffers are short-lived: they come from a free list keyed by shape and go back to it as
@@ -170,7 +213,8 @@ class UNet:
         return out
 
     # ---- backward ---------------------------------------------------------------------------------
-    def _conv_bwd(self, name, Px, Py, Pdy, g, cin, cout, grads, need_dx=True, masked=False, mask_next=False):
+    def _conv_bwd(self, name, Px, Py, Pdy, g, cin, cout, grads, need_dx=True, masked=False, mask_next=False,
+                  exchange=True, grow=0):
         """Backward of y = relu(conv(x)): Pdy is d/dy (interiors valid), or already d/dz if `masked`.
         Returns d/dx (padded); with `mask_next` (x is itself a ReLU output) the ReLU mask of x is applied
         in the same pass, so the result is the previous layer's d/dz."""
@@ -183,24 +227,27 @@ class UNet:
             sp3d.conv3d_wgrad2(Px[0], ca, Px[1], ca, Pdy, dw, None, g, cout, dt,
                                self._ws(sp3d.SP_OP_WGRAD, g, cin, cout))
             grads[name] = dw
-            self._exchange(Pdy, g, cout)
+            if exchange:
+                self._exchange(Pdy, g, cout)
             Pa, Pb = self._tmp(g, ca), self._tmp(g, ca)
             sp3d.conv3d_dgrad2(Pdy, self.w[name], Pa, ca, Pb, ca, g, cout, dt,
-                               self._ws(sp3d.SP_OP_DGRAD, g, cin, cout))
+                               self._ws(sp3d.SP_OP_DGRAD, g, cin, cout))          # first layer of its run: no grow
             self._release(Pdy, g, cout)
             return (Pa, Pb)
         sp3d.conv3d_wgrad(Px, Pdy, dw, None, g, cin, cout, dt, self._ws(sp3d.SP_OP_WGRAD, g, cin, cout))
         grads[name] = dw
         Pdx = None
         if need_dx:
-            self._exchange(Pdy, g, cout)
+            if exchange:
+                self._exchange(Pdy, g, cout)
             Pdx = self._tmp(g, cin)
+            gg = g.grown(grow) if grow else g
             if mask_next:
-                sp3d.conv3d_dgrad_relu(Pdy, self.w[name], Px, Pdx, g, cin, cout, dt,
-                                       self._ws(sp3d.SP_OP_DGRAD, g, cin, cout))
+                sp3d.conv3d_dgrad_relu(Pdy, self.w[name], Px, Pdx, gg, cin, cout, dt,
+                                       self._ws(sp3d.SP_OP_DGRAD, gg, cin, cout))
             else:
-                sp3d.conv3d_dgrad(Pdy, self.w[name], Pdx, g, cin, cout, dt,
-                                  self._ws(sp3d.SP_OP_DGRAD, g, cin, cout))
+                sp3d.conv3d_dgrad(Pdy, self.w[name], Pdx, gg, cin, cout, dt,
+                                  self._ws(sp3d.SP_OP_DGRAD, gg, cin, cout))
         self._release(Pdy, g, cout)
         return Pdx
 

@@ -52,7 +52,21 @@ def test_margin_voxel_counts_of_the_workload_configurations():
 def test_geometry_errors():
     assert sp3d.sp_check_geom(sp3d.Geom(1, (8, 8, 8), (2, 2, 2))) == sp3d.SP_OK
     assert sp3d.sp_check_geom(sp3d.Geom(1, (8, 8, 8), (3, 2, 2))) == sp3d.SP_EGEOM
-    assert sp3d.sp_check_geom(sp3d.Geom(1, (8, 8, 8), (2, 2, 2), halo=2)) == sp3d.SP_EUNSUPPORTED
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (8, 8, 8), (2, 2, 2), halo=2)) == sp3d.SP_OK
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (8, 8, 8), (2, 2, 2), halo=4)) == sp3d.SP_OK
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (8, 8, 8), (2, 2, 2), halo=5)) == sp3d.SP_EUNSUPPORTED
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (8, 8, 8), (2, 2, 2), halo=0)) == sp3d.SP_EUNSUPPORTED
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (8, 8, 8), (2, 2, 2), halo=-1)) == sp3d.SP_EINVAL
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (8, 8, 8), (4, 2, 2), halo=3)) == sp3d.SP_EGEOM     # 2-voxel tiles, 3-wide margin
+    # grow: the convolutions' output box may grow by less than the margin width
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (8, 8, 8), (2, 2, 2), halo=2, grow=1)) == sp3d.SP_OK
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (8, 8, 8), (2, 2, 2), halo=2, grow=2)) == sp3d.SP_EINVAL
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (8, 8, 8), (2, 2, 2), halo=1, grow=1)) == sp3d.SP_EINVAL
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (8, 8, 8), (2, 2, 2), grow=-1)) == sp3d.SP_EINVAL
+    g2 = sp3d.Geom(1, (8, 8, 8), (2, 2, 2), halo=2)
+    assert sp3d.sp_padded_elems(g2, 3) == 8 * 8 * 8 * 8 * 3 and g2.padded_shape == (1, 2, 2, 2, 8, 8, 8)
+    assert sp3d.sp_msg_elems(g2, 1) == 8 * (8 * 8 * 8 - 4 * 4 * 4)
+    assert g2.grown(1).grow == 1 and g2.grown(1).halo == 2
     assert sp3d.sp_check_geom(sp3d.Geom(0, (8, 8, 8), (2, 2, 2))) == sp3d.SP_EINVAL
     assert sp3d.sp_check_geom(sp3d.Geom(1, (8, 8, 8), (2, 0, 2))) == sp3d.SP_EINVAL
     assert sp3d.sp_check_geom(sp3d.Geom(1, (2, 2, 2), (2, 2, 2))) == sp3d.SP_OK     # 1-voxel tiles are legal

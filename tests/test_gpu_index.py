@@ -21,6 +21,14 @@ CASES = [
     (1, (24, 40, 72), (2, 2, 1), 32, "bf16"),      # rows longer than one block pass, ragged
     (1, (4, 6, 260), (2, 3, 2), 16, "f32"),
 ]
+# margins wider than one voxel (several layers per exchange): n, dhw, grid, c, dtype, halo
+WIDE = [
+    (1, (16, 16, 64), (4, 4, 1), 32, "bf16", 2),
+    (1, (8, 8, 12), (4, 4, 2), 1, "bf16", 2),      # tiles exactly as thick as the margin
+    (2, (6, 6, 9), (2, 1, 3), 3, "f32", 3),
+    (1, (8, 12, 40), (2, 1, 1), 32, "bf16", 4),
+    (1, (5, 7, 9), (1, 1, 1), 4, "bf16", 2),
+]
 
 
 def make_volume(n, dhw, c, dtype, seed):
@@ -30,9 +38,9 @@ def make_volume(n, dhw, c, dtype, seed):
     return rng.standard_normal((n,) + dhw + (c,)).astype(np.float32)
 
 
-@pytest.mark.parametrize("n,dhw,grid,c,dtype", CASES)
-def test_partition_pack_unpack_unpartition_bit_exact(n, dhw, grid, c, dtype):
-    g = sp3d.Geom(n, dhw, grid)
+@pytest.mark.parametrize("n,dhw,grid,c,dtype,h", [k + (1,) for k in CASES] + WIDE)
+def test_partition_pack_unpack_unpartition_bit_exact(n, dhw, grid, c, dtype, h):
+    g = sp3d.Geom(n, dhw, grid, h)
     dt = DT[dtype]
     V = make_volume(n, dhw, c, dtype, 11)
     tdt = sp3d.torch_dtype(dt)
@@ -42,9 +50,9 @@ def test_partition_pack_unpack_unpartition_bit_exact(n, dhw, grid, c, dtype):
     # partition: interiors written, margins untouched (still the fill value)
     pbuf, P = guard_alloc(g.padded_shape + (c,), tdt, fill)
     sp3d.sp_partition(to_dev(V), P, g, c, dt)
-    ref_P = tiling.partition(V, grid)
+    ref_P = tiling.partition(V, grid, h)
     got = bits(P)
-    inner = (slice(None),) * 4 + (slice(1, -1),) * 3
+    inner = (slice(None),) * 4 + (slice(h, -h),) * 3
     assert np.array_equal(got[inner], ref_P[inner])
     mask = np.ones(got.shape, dtype=bool)
     mask[inner] = False
@@ -54,15 +62,15 @@ def test_partition_pack_unpack_unpartition_bit_exact(n, dhw, grid, c, dtype):
     # pack
     mbuf, M = guard_alloc((sp3d.sp_msg_elems(g, c),), tdt, fill)
     sp3d.halo_pack(P, M, g, c, dt)
-    ref_M = tiling.halo_pack(ref_P)
+    ref_M = tiling.halo_pack(ref_P, h)
     assert np.array_equal(bits(M).reshape(ref_M.shape), ref_M)
     assert guards_intact(mbuf, fill)
 
     # unpack: margins from neighbours or zero; interior untouched
     sp3d.halo_unpack(P, M, g, c, dt)
-    ref_full = tiling.padded_reference(V, grid)
+    ref_full = tiling.padded_reference(V, grid, h)
     assert np.array_equal(bits(P), ref_full)
-    assert np.array_equal(tiling.halo_unpack(ref_P, ref_M), ref_full)
+    assert np.array_equal(tiling.halo_unpack(ref_P, ref_M, h), ref_full)
     assert guards_intact(pbuf, fill)
 
     # the one-pass exchange on a freshly partitioned tensor gives the same padded tiles, margins included

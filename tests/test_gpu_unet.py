@@ -240,3 +240,40 @@ def test_unet_with_loss_end_to_end():
     worst = max(rel_rms(f64(grads[k]), ref_grads[k]) for k, _ in plan)
     print("with loss: free-running backward worst relative rms %.3f" % worst)
     assert worst <= 0.05          # the loss gradient is smooth, so few ReLU decisions flip (measured: 0.003)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("convs", [2, 4])
+def test_unet_two_layers_per_exchange_bit_identical(convs):
+    """Margins two voxels wide, two layers per exchange (the overlap of Sec. 1 for a short stack; the first layer
+    of a pair also computes the voxel shell its successor reads, the data gradients likewise): every output is
+    bit for bit that of the one-exchange-per-layer path, whose parity with the oracle the tests above establish,
+    with fewer exchanges."""
+    channels, in_ch, classes = (32, 64, 128), 1, 3
+    n, dhw, grid = 1, (16, 16, 32), (2, 2, 1)
+    plan = PU.layer_plan(channels, in_ch, classes, convs)
+    x = to_dev(synth.ct_like_volume((n,) + dhw + (in_ch,), synth.seed_for(8, synth.T_INPUT), "bf16"))
+    w_d = {name: to_dev(synth.weights(shape[3], shape[4], synth.seed_for(8, synth.T_WEIGHT0 + k), "bf16",
+                                      taps=shape[:3])) for k, (name, shape) in enumerate(plan)}
+    dl = to_dev(synth.normal_volume((n,) + dhw + (classes,), synth.seed_for(8, synth.T_UPSTREAM), "bf16"))
+    res, count = [], []
+    for halo in (1, 2):
+        net = PU.UNet(n, dhw, grid, w_d, channels, in_ch, classes, convs=convs, halo=halo)
+        calls = [0]
+        inner = net._exchange
+
+        def counted(P, g, c, inner=inner, calls=calls):
+            calls[0] += 1
+            inner(P, g, c)
+        net._exchange = counted
+        for _ in range(2):                       # the second step runs on recycled buffers
+            logits = net.forward(x)
+            grads, dx = net.backward(dl)
+        res.append((logits, grads, dx))
+        count.append(calls[0])
+    (l1, g1, d1), (l2, g2, d2) = res
+    assert torch.equal(l1, l2) and torch.equal(d1, d2)
+    for k, _ in plan:
+        assert torch.equal(g1[k], g2[k]), k
+    print("exchanges per two steps: one per layer %d, two layers per exchange %d" % tuple(count))
+    assert count[1] < count[0]
