@@ -4,8 +4,9 @@
 // the arithmetic free: the 27 taps, padded to 32, are the GEMM K (forward) or M (weight gradient)
 // dimension of a v_mfma_f32_32x32x16_bf16.
 //
-// Both kernels work on bricks of 4 (D) x 8 (H) x 32 (W) output voxels: the 6 x 10 x 34 input voxels
-// around a brick (4 KB) are staged in LDS and every wave owns one plane of the brick.
+// Both kernels stage the input voxels around a brick of output voxels in LDS (2-byte elements, gathered per
+// tap): the weight gradient works on bricks of 4 (D) x 8 (H) x 32 (W) with one plane per wave, the forward pass
+// on bricks of 1 x 32 x 32 with 8 rows per wave.
 #include "common.h"
 
 namespace sp3d {
@@ -44,53 +45,105 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
     return r.u;
 }
 
-// element offset inside the staged input brick of tap t relative to an output voxel (0 for the padding taps)
-__device__ __forceinline__ int tap_off(int t) {
-    return t < 27 ? ((t / 9) * XH + (t / 3) % 3) * XW + t % 3 : 0;
+// ReLU on two packed bf16 values: a bf16 with its sign bit set is a negative 16-bit integer, so the signed
+// integer maximum with 0 clears exactly the negative values (and -0); one v_pk_max_i16 per pair
+__device__ __forceinline__ uint32_t relu2(uint32_t p) {
+    typedef short s16x2 __attribute__((ext_vector_type(2)));
+    union { uint32_t u; s16x2 v; } a, r;
+    a.u = p;
+    r.v = __builtin_elementwise_max(a.v, s16x2{0, 0});
+    return r.u;
 }
 
-// Stage the input voxels around brick (tile, d0, h0, w0) (interior coordinates).  Positions beyond the
-// interior and the one voxel around it (ragged bricks) are staged as zero.
-__device__ __forceinline__ void stage_x(const C1Args &a, uint16_t *lx, int tile, int d0, int h0, int w0) {
-    const Geo &g = a.g;
-    const uint16_t *tx = a.x + static_cast<size_t>(tile) * g.tile_vox;
-#pragma unroll
-    for (int i = 0; i < XLOADS; ++i) {
-        const int e = threadIdx.x + i * kThreads;
-        if (e < XVOX) {
-            const int pd = e / (XH * XW), r = e % (XH * XW), ph = r / XW, pc = r % XW;
-            const bool ok = d0 + pd < g.td + 2 && h0 + ph < g.th + 2 && w0 + pc < g.tw + 2;
-            lx[e] = ok ? tx[(static_cast<size_t>(d0 + pd) * g.ph + h0 + ph) * g.pw + w0 + pc] : uint16_t(0);
-        }
-    }
+// element offset inside the staged input brick of tap t relative to an output voxel (0 for the padding taps)
+__host__ __device__ constexpr int tap_off(int t) {
+    return t < 27 ? ((t / 9) * XH + (t / 3) % 3) * XW + t % 3 : 0;
 }
 
 // ---- forward ------------------------------------------------------------------------------------------
 // D[co][voxel] = sum_tap W[co][tap] * X[tap][voxel]: A = weights (lane: channel lane%32, taps 8*(lane/32)+e of
 // each 16-tap half), B = gathered input (lane: voxel lane%32 of a row, the same taps).
-__global__ __launch_bounds__(kThreads) void conv_c1_fwd_kernel(C1Args a) {
-    __shared__ __attribute__((aligned(16))) uint16_t lx[XVOX + 8];
+// The kernel is bound by its 64 bytes of output per voxel, so the stores are shaped for the memory system: a
+// finished row (32 voxels x 64 bytes) goes through a wave-private LDS buffer, in which lane (voxel, half) writes
+// its four 8-byte pieces and from which lane l reads the 16 contiguous bytes l % 4 of voxel l / 4, so that one
+// store instruction writes 1 KB of consecutive memory (sixteen whole voxel records) instead of 8-byte pieces
+// 64 bytes apart.  Two rows are in flight at a time so that the second row's MFMAs cover the first row's epilogue.
+constexpr int YROW = 72;                              // LDS bytes per voxel record: 64 + 8 of padding (8-byte writes
+                                                      // 72 bytes apart fall into 32 different bank pairs)
+constexpr int YBUF = 32 * YROW;                       // one row
+// Forward bricks are one plane thick: 32 rows (8 per wave) x 32 voxels along W, so that a workgroup writes a
+// compact block of adjacent rows while it walks along W (with bricks four planes thick the same stores ran
+// slower: the four waves then wrote into planes megabytes apart).
+constexpr int FH = 32, FXD = 3, FXH = FH + 2;         // brick rows; input planes and rows around a brick
+constexpr int FXROWS = FXD * FXH;                     // 102 staged rows of XW voxels
+constexpr int FXVOX = FXROWS * XW;                    // 3468
+constexpr int FRW = (FXROWS + 3) / 4;                 // rows per wave when staging: 26
+
+__host__ __device__ constexpr int fwd_tap_off(int t) {
+    return t < 27 ? ((t / 9) * FXH + (t / 3) % 3) * XW + t % 3 : 0;
+}
+
+// A workgroup walks along W over the bricks of one (tile, plane, group of 32 rows): while it computes a brick,
+// the input voxels of the next one are already on their way into registers (wave w fetches rows w, w + 4, ...;
+// lanes 0..33 one voxel each), and they are written to the other half of a double-buffered LDS array afterwards,
+// so neither the memory latency nor more than one barrier per brick lies on the critical path.
+template <bool RELU, bool HAS_BIAS>
+__global__ __launch_bounds__(kThreads) void conv_c1_fwd_kernel(C1Args a, int nhg) {
+    __shared__ __attribute__((aligned(16))) uint16_t lx[2][FXVOX + 8];
+    __shared__ __attribute__((aligned(16))) char ly[kThreads / 64][2][YBUF];
     const Geo &g = a.g;
     int t = blockIdx.x;
-    const int bw_i = t % a.nw; t /= a.nw;
-    const int bh_i = t % a.nh; t /= a.nh;
-    const int bd_i = t % a.nd; t /= a.nd;
+    const int bh_i = t % nhg; t /= nhg;
+    const int od = t % g.td; t /= g.td;               // output plane (interior coordinate)
     const int tile = t;
-    const int d0 = bd_i * BD, h0 = bh_i * BH, w0 = bw_i * BW;
+    const int h0 = bh_i * FH;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 31, hi = lane >> 5;
-    stage_x(a, lx, tile, d0, h0, w0);
+    const uint16_t *tx = a.x + static_cast<size_t>(tile) * g.tile_vox;
+    uint16_t *ty = a.y + static_cast<size_t>(tile) * g.tile_vox * a.cout;
+
+    // staging: element offsets of this lane's voxel in each of its rows (-1: beyond the interior and the one
+    // voxel around it, staged as zero); the W position advances by BW per brick
+    int xsrc[FRW];
+#pragma unroll
+    for (int i = 0; i < FRW; ++i) {
+        const int row = wave + 4 * i, pd = row / FXH, ph = row % FXH;
+        const bool ok = row < FXROWS && lane < XW && h0 + ph < g.th + 2;
+        xsrc[i] = ok ? ((od + pd) * g.ph + h0 + ph) * g.pw + lane : -1;
+    }
+    uint16_t xr[FRW];
+    auto fetch = [&](int w0) {
+#pragma unroll
+        for (int i = 0; i < FRW; ++i) {
+            const bool ok = xsrc[i] >= 0 && w0 + lane < g.tw + 2;
+            xr[i] = ok ? tx[xsrc[i] + w0] : uint16_t(0);
+        }
+    };
+    auto commit = [&](uint16_t *dst) {
+#pragma unroll
+        for (int i = 0; i < FRW; ++i)
+            if (wave + 4 * i < FXROWS && lane < XW) dst[(wave + 4 * i) * XW + lane] = xr[i];
+    };
+    fetch(0);
+    commit(lx[0]);
+
     int off[2][8];
 #pragma unroll
     for (int half = 0; half < 2; ++half)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) off[half][e] = tap_off(16 * half + 8 * hi + e);
-    __syncthreads();
-    const int od = d0 + wave;                         // this wave's output plane
-    if (od >= g.td) return;
-    uint16_t *ty = a.y + static_cast<size_t>(tile) * g.tile_vox * a.cout;
-    for (int cb = 0; cb < a.cout / 32; ++cb) {
-        union { bf16x8 v; uint16_t u[8]; } wf[2];
+        for (int e = 0; e < 8; ++e) off[half][e] = hi ? fwd_tap_off(16 * half + 8 + e) : fwd_tap_off(16 * half + e);
+    const int r0 = wave * (FH / 4);                   // this wave's rows of the brick: r0 .. r0 + 7
+    const bool rows_ok = h0 + r0 < g.th;
+    char *wy = &ly[wave][0][0];
+    char *wr_at = wy + col * YROW + 8 * hi;           // this lane's pieces: + 16 q
+    const int rv = lane >> 2, rp = lane & 3;          // read back: voxel rv (+16), 16-byte piece rp
+    const char *rd_at = wy + rv * YROW + 16 * rp;
+    // weights and bias of the (first) output block; wider layers reload them per block inside the loop
+    const int ncb = a.cout / 32;
+    union WF { bf16x8 v; uint16_t u[8]; };
+    WF wf[2];
+    f32x16 bv;
+    auto load_weights = [&](int cb) {
 #pragma unroll
         for (int half = 0; half < 2; ++half)
 #pragma unroll
@@ -98,35 +151,69 @@ __global__ __launch_bounds__(kThreads) void conv_c1_fwd_kernel(C1Args a) {
                 const int tap = 16 * half + 8 * hi + e;
                 wf[half].u[e] = tap < 27 ? a.w[tap * a.cout + 32 * cb + col] : uint16_t(0);
             }
-        float bv[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) bv[i] = a.bias ? a.bias[32 * cb + 8 * (i >> 2) + 4 * hi + (i & 3)] : 0.f;
-        for (int r = 0; r < BH; ++r) {
-            const int base = (wave * XH + r) * XW + col;
-            union { bf16x8 v; uint16_t u[8]; } xf[2];
+        for (int i = 0; i < 16; ++i) bv[i] = HAS_BIAS ? a.bias[32 * cb + 8 * (i >> 2) + 4 * hi + (i & 3)] : 0.f;
+    };
+    load_weights(0);
+    __syncthreads();
+
+    for (int bw_i = 0; bw_i < a.nw; ++bw_i) {
+        const int w0 = bw_i * BW;
+        const uint16_t *cur = lx[bw_i & 1];
+        if (bw_i + 1 < a.nw) fetch(w0 + BW);
+        if (rows_ok) {
+            for (int cb = 0; cb < ncb; ++cb) {
+                if (ncb > 1) load_weights(cb);
+#pragma unroll 1
+                for (int r = 0; r < FH / 4; r += 2) {
+                    WF xf[2][2];
 #pragma unroll
-            for (int half = 0; half < 2; ++half)
+                    for (int k = 0; k < 2; ++k) {
+                        const int base = (r0 + r + k) * XW + col;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) xf[half].u[e] = lx[base + off[half][e]];
-            f32x16 acc;
+                        for (int half = 0; half < 2; ++half)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[i] = bv[i];
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[0].v, xf[0].v, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[1].v, xf[1].v, acc, 0, 0, 0);
-            const int oh = h0 + r, ow = w0 + col;
-            if (oh < g.th && ow < g.tw) {
-                uint16_t *o = ty + ((static_cast<size_t>(od + 1) * g.ph + oh + 1) * g.pw + ow + 1) * a.cout + 32 * cb + 4 * hi;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float v0 = acc[4 * q], v1 = acc[4 * q + 1], v2 = acc[4 * q + 2], v3 = acc[4 * q + 3];
-                    if (a.relu) {
-                        v0 = v0 < 0.f ? 0.f : v0; v1 = v1 < 0.f ? 0.f : v1;
-                        v2 = v2 < 0.f ? 0.f : v2; v3 = v3 < 0.f ? 0.f : v3;
+                            for (int e = 0; e < 8; ++e) xf[k][half].u[e] = cur[base + off[half][e]];
                     }
-                    *reinterpret_cast<uint2 *>(o + 8 * q) = make_uint2(pack2(v0, v1), pack2(v2, v3));
+                    f32x16 acc[2];
+#pragma unroll
+                    for (int k = 0; k < 2; ++k)
+                        acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[0].v, xf[k][0].v, bv, 0, 0, 0);
+#pragma unroll
+                    for (int k = 0; k < 2; ++k)
+                        acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[1].v, xf[k][1].v, acc[k], 0, 0, 0);
+#pragma unroll
+                    for (int k = 0; k < 2; ++k) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            uint32_t p0 = pack2(acc[k][4 * q], acc[k][4 * q + 1]), p1 = pack2(acc[k][4 * q + 2], acc[k][4 * q + 3]);
+                            if (RELU) { p0 = relu2(p0); p1 = relu2(p1); }
+                            *reinterpret_cast<uint2 *>(wr_at + k * YBUF + 16 * q) = make_uint2(p0, p1);
+                        }
+                    }
+                    // the LDS unit serves a wave's accesses in order, so the reads below see the writes above
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+#pragma unroll
+                    for (int k = 0; k < 2; ++k) {
+                        const int oh = h0 + r0 + r + k;
+                        uint16_t *orow = ty + ((static_cast<size_t>(od + 1) * g.ph + oh + 1) * g.pw + w0 + 1) * a.cout +
+                                         32 * cb + 8 * rp;
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            const int v = rv + 16 * j;
+                            const uint2 lo = *reinterpret_cast<const uint2 *>(rd_at + k * YBUF + 16 * j * YROW);
+                            const uint2 hi2 = *reinterpret_cast<const uint2 *>(rd_at + k * YBUF + 16 * j * YROW + 8);
+                            if (oh < g.th && w0 + v < g.tw)
+                                *reinterpret_cast<uint4 *>(orow + static_cast<size_t>(v) * a.cout) =
+                                    make_uint4(lo.x, lo.y, hi2.x, hi2.y);
+                        }
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
                 }
             }
         }
+        if (bw_i + 1 < a.nw) commit(lx[(bw_i + 1) & 1]);
+        __syncthreads();
     }
 }
 
@@ -143,6 +230,13 @@ __device__ __forceinline__ s16x4 tr_read(const char *p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(__attribute__((address_space(3))) char *)(p));
 }
 
+constexpr int XROWS = XD * XH;                        // 60 input rows of XW voxels around a brick
+constexpr int XRW = (XROWS + 3) / 4;                  // rows per wave when staging: 15
+constexpr int ZLD = ZVOX * 4 / kThreads;              // 16-byte pieces of dz per thread and brick: 16
+
+// The loads of a workgroup's next brick (x: wave w takes rows w, w + 4, ..., lanes 0..33 one voxel each; dz: four
+// lanes per voxel, 16 bytes each) are issued before the MFMAs of the current brick and land in registers while
+// those run; they go to LDS between two barriers afterwards.
 __global__ __launch_bounds__(kThreads, 2) void wgrad_c1_kernel(C1Args a, int cb) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     uint16_t *lx = reinterpret_cast<uint16_t *>(lds);
@@ -160,28 +254,51 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_c1_kernel(C1Args a, int cb)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 
-    for (int brick = group; brick < a.nbricks; brick += a.ngroups) {
+    uint16_t xr[XRW];
+    uint4 zr[ZLD];
+    auto fetch = [&](int brick) {
         int t = brick;
         const int bw_i = t % a.nw; t /= a.nw;
         const int bh_i = t % a.nh; t /= a.nh;
         const int bd_i = t % a.nd; t /= a.nd;
         const int tile = t;
         const int d0 = bd_i * BD, h0 = bh_i * BH, w0 = bw_i * BW;
-        __syncthreads();                              // the previous brick's readers are done
-        stage_x(a, lx, tile, d0, h0, w0);
+        const uint16_t *tx = a.x + static_cast<size_t>(tile) * g.tile_vox;
+#pragma unroll
+        for (int i = 0; i < XRW; ++i) {
+            const int row = wave + 4 * i, pd = row / XH, ph = row % XH;
+            // beyond the interior and the one voxel around it (ragged bricks): zero
+            const bool ok = row < XROWS && lane < XW && d0 + pd < g.td + 2 && h0 + ph < g.th + 2 && w0 + lane < g.tw + 2;
+            xr[i] = ok ? tx[(static_cast<size_t>(d0 + pd) * g.ph + h0 + ph) * g.pw + w0 + lane] : uint16_t(0);
+        }
         const uint16_t *tz = a.dz + static_cast<size_t>(tile) * g.tile_vox * a.cout + 32 * cb + 8 * c4;
 #pragma unroll
-        for (int i = 0; i < ZVOX * 4 / kThreads; ++i) {
+        for (int i = 0; i < ZLD; ++i) {
             const int v = (threadIdx.x + i * kThreads) >> 2;            // brick-local voxel
             const int vd = v / (BH * BW), vh = (v / BW) % BH, vw = v % BW;
             const bool ok = d0 + vd < g.td && h0 + vh < g.th && w0 + vw < g.tw;     // tile interior only
-            uint4 q = make_uint4(0, 0, 0, 0);
+            zr[i] = make_uint4(0, 0, 0, 0);
             if (ok)
-                q = *reinterpret_cast<const uint4 *>(
+                zr[i] = *reinterpret_cast<const uint4 *>(
                     tz + ((static_cast<size_t>(d0 + vd + 1) * g.ph + h0 + vh + 1) * g.pw + w0 + vw + 1) * a.cout);
-            *reinterpret_cast<uint4 *>(lz + (c4 >> 1) * Z_HALF + v * 32 + (c4 & 1) * 16) = q;
         }
+    };
+    auto commit = [&]() {
+#pragma unroll
+        for (int i = 0; i < XRW; ++i)
+            if (wave + 4 * i < XROWS && lane < XW) lx[(wave + 4 * i) * XW + lane] = xr[i];
+#pragma unroll
+        for (int i = 0; i < ZLD; ++i) {
+            const int v = (threadIdx.x + i * kThreads) >> 2;
+            *reinterpret_cast<uint4 *>(lz + (c4 >> 1) * Z_HALF + v * 32 + (c4 & 1) * 16) = zr[i];
+        }
+    };
+
+    if (group < a.nbricks) fetch(group);
+    for (int brick = group; brick < a.nbricks; brick += a.ngroups) {
+        commit();
         __syncthreads();
+        if (brick + a.ngroups < a.nbricks) fetch(brick + a.ngroups);
         for (int r = 0; r < BH; ++r)
 #pragma unroll
             for (int step = 0; step < 2; ++step) {
@@ -195,6 +312,7 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_c1_kernel(C1Args a, int cb)
                 zf.s.hi = tr_read(zp + 4 * 32);
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf.v, zf.v, acc, 0, 0, 0);
             }
+        __syncthreads();                              // this brick's readers are done before the next commit
     }
     // combine the four waves in a fixed order and write this workgroup's partial [32 taps][32 channels]
     __syncthreads();
@@ -240,7 +358,7 @@ void plan(const Geo &g, C1Args *a) {
 
 bool conv_c1_supported(const Geo &g, int cin, int cout, sp_dtype_t dt) {
     return dt == SP_BF16 && cin == 1 && cout % 32 == 0 && cout <= 1024 &&
-           1LL * g.ntiles * ((g.td + BD - 1) / BD) * ((g.th + BH - 1) / BH) * ((g.tw + BW - 1) / BW) < 0x7fffffffLL;
+           1LL * g.ntiles * g.td * ((g.th + BH - 1) / BH) * ((g.tw + BW - 1) / BW) < 0x7fffffffLL;
 }
 
 int launch_conv_c1_fwd(const void *Px, const void *w, const float *bias, void *Py, const Geo &g, int cout,
@@ -254,7 +372,15 @@ int launch_conv_c1_fwd(const void *Px, const void *w, const float *bias, void *P
     a.cout = cout;
     a.relu = relu ? 1 : 0;
     plan(g, &a);
-    hipLaunchKernelGGL(conv_c1_fwd_kernel, dim3(a.nbricks), dim3(kThreads), 0, s, a);
+    const int nhg = (g.th + FH - 1) / FH;
+    const dim3 grid(static_cast<unsigned>(1LL * g.ntiles * g.td * nhg)), block(kThreads);
+    if (relu) {
+        if (bias) hipLaunchKernelGGL((conv_c1_fwd_kernel<true, true>), grid, block, 0, s, a, nhg);
+        else hipLaunchKernelGGL((conv_c1_fwd_kernel<true, false>), grid, block, 0, s, a, nhg);
+    } else {
+        if (bias) hipLaunchKernelGGL((conv_c1_fwd_kernel<false, true>), grid, block, 0, s, a, nhg);
+        else hipLaunchKernelGGL((conv_c1_fwd_kernel<false, false>), grid, block, 0, s, a, nhg);
+    }
     return record_hip(hipGetLastError());
 }
 
