@@ -191,6 +191,15 @@ int sp_maxpool2_fwd(const void *Px, void *Py, const sp_geom_t *gf, int c, sp_dty
  * for the other seven voxels.  Px is the pooling input. */
 int sp_maxpool2_bwd(const void *Px, const void *Pdy, void *Pdx, const sp_geom_t *gf, int c,
                     sp_dtype_t dt, void *stream);
+/* The backward pass of an encoder level of the network of Sec. 3 in one sweep.  The level's last ReLU
+ * output Px (fine) feeds both the pooling and, as the skip tensor, the decoder; the gradient that
+ * reaches the level's last convolution is therefore
+ *     Pdz = [Px > 0] * (maxpool_bwd(Px, Pdy) + Pskip)
+ * with Pdy (coarse) the gradient of the pooled tensor and Pskip (fine) the gradient that arrived through
+ * the skip connection.  Same bits as sp_maxpool2_bwd, sp_add and sp_relu_bwd in that order (the sum in
+ * fp32, rounded once).  Pskip may be the same tensor as Pdz; Px must not overlap Pdz. */
+int sp_maxpool2_bwd_join(const void *Px, const void *Pdy, const void *Pskip, void *Pdz, const sp_geom_t *gf,
+                         int c, sp_dtype_t dt, void *stream);
 
 /* y[2v+(a,b,c), co] = bias[co] + sum_ci Px[v,ci] * u[a][b][c][ci][co];  u[2][2][2][Cin][Cout] in the
  * tensor dtype, bias float or NULL.  Px coarse [..][Cin], Py fine [..][Cout]. */
@@ -211,6 +220,10 @@ int sp_pointwise_fwd(const void *Px, const void *p, const float *bias, void *Py,
                      int cin, int cout, sp_dtype_t dt, uint32_t flags, void *stream);
 int sp_pointwise_dgrad(const void *Pdy, const void *p, void *Pdx, const sp_geom_t *g, int cin, int cout,
                        sp_dtype_t dt, void *stream);
+/* sp_pointwise_dgrad followed by the backward of the ReLU that produced the layer input Px [..][Cin]:
+ * Pdx[v,ci] = dx[v,ci] if Px[v,ci] > 0 else 0, in one pass.  Px must not overlap Pdx. */
+int sp_pointwise_dgrad_relu(const void *Pdy, const void *p, const void *Px, void *Pdx, const sp_geom_t *g,
+                            int cin, int cout, sp_dtype_t dt, void *stream);
 int sp_pointwise_wgrad(const void *Px, const void *Pdy, float *dp, float *db, const sp_geom_t *g,
                        int cin, int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream);
 

@@ -387,6 +387,19 @@ int sp_maxpool2_bwd(const void *Px, const void *Pdy, void *Pdx, const sp_geom_t 
                            static_cast<hipStream_t>(stream));
 }
 
+int sp_maxpool2_bwd_join(const void *Px, const void *Pdy, const void *Pskip, void *Pdz, const sp_geom_t *gf, int c,
+                         sp_dtype_t dt, void *stream) {
+    Geo f, k;
+    int rc = check_glue(Px, Pdy, Pdz, gf, c, c, dt, &f, &k);
+    if (rc != SP_OK) return rc;
+    if (!Pskip || !aligned16(Pskip)) return SP_EINVAL;
+    const size_t bytes = static_cast<size_t>(f.ntiles) * f.tile_vox * c * elem_size(dt);
+    if (overlap(Px, bytes, Pdz, bytes)) return SP_EINVAL;
+    if (Pskip != Pdz && overlap(Pskip, bytes, Pdz, bytes)) return SP_EINVAL;
+    return launch_maxpool2(shifted(Px, f, c, dt), shifted(Pdy, k, c, dt), shifted(Pdz, f, c, dt), f, k, c, dt, true,
+                           static_cast<hipStream_t>(stream), shifted(Pskip, f, c, dt));
+}
+
 int sp_upconv2_fwd(const void *Px, const void *u, const float *bias, void *Py, const sp_geom_t *gf, int cin,
                    int cout, sp_dtype_t dt, void *stream) {
     Geo f, k;
@@ -429,16 +442,31 @@ int sp_pointwise_fwd(const void *Px, const void *p, const float *bias, void *Py,
                               static_cast<hipStream_t>(stream), 1);
 }
 
-int sp_pointwise_dgrad(const void *Pdy, const void *p, void *Pdx, const sp_geom_t *g, int cin, int cout,
-                       sp_dtype_t dt, void *stream) {
+static int pointwise_dgrad_impl(const void *Pdy, const void *p, const void *Pmask, void *Pdx, const sp_geom_t *g,
+                                int cin, int cout, sp_dtype_t dt, void *stream) {
     Geo o;
     int rc = check_glue(Pdy, p, Pdx, g, cin, cout, dt, &o, nullptr);
     if (rc != SP_OK) return rc;
+    if (Pmask) {
+        const size_t bytes = static_cast<size_t>(o.ntiles) * o.tile_vox * cin * elem_size(dt);
+        if (!aligned16(Pmask) || overlap(Pmask, bytes, Pdx, bytes)) return SP_EINVAL;
+    }
     if (pointwise_small_supported(o, cin, cout, dt))
         return launch_pointwise_small_dgrad(shifted(Pdy, o, cout, dt), p, shifted(Pdx, o, cin, dt), o, cin, cout,
-                                            static_cast<hipStream_t>(stream));
+                                            static_cast<hipStream_t>(stream), shifted(Pmask, o, cin, dt));
     return launch_conv_direct(Pdy, p, nullptr, Pdx, o, cout, cin, dt, false, true,
-                              static_cast<hipStream_t>(stream), 1);
+                              static_cast<hipStream_t>(stream), 1, Pmask);
+}
+
+int sp_pointwise_dgrad(const void *Pdy, const void *p, void *Pdx, const sp_geom_t *g, int cin, int cout,
+                       sp_dtype_t dt, void *stream) {
+    return pointwise_dgrad_impl(Pdy, p, nullptr, Pdx, g, cin, cout, dt, stream);
+}
+
+int sp_pointwise_dgrad_relu(const void *Pdy, const void *p, const void *Px, void *Pdx, const sp_geom_t *g, int cin,
+                            int cout, sp_dtype_t dt, void *stream) {
+    if (!Px) return SP_EINVAL;
+    return pointwise_dgrad_impl(Pdy, p, Px, Pdx, g, cin, cout, dt, stream);
 }
 
 int sp_pointwise_wgrad(const void *Px, const void *Pdy, float *dp, float *db, const sp_geom_t *g, int cin,

@@ -69,8 +69,9 @@ int launch_wgrad_direct(const void *Px, const void *Pdz, float *dw, float *db, c
 
 // U-Net glue (glue_kernels.hip).  gf = geometry of the fine (higher-resolution) volume.
 int make_coarse(const Geo &gf, Geo *gc);     // SP_OK, or SP_EGEOM if a tile extent is odd
+// backward with Pskip: Pout = [Px > 0] * (maxpool_bwd(Px, Pdy) + Pskip)   (Pskip may be Pout)
 int launch_maxpool2(const void *Px, const void *Pdy, void *Pout, const Geo &gf, const Geo &gc, int c,
-                    sp_dtype_t dt, bool backward, hipStream_t s);
+                    sp_dtype_t dt, bool backward, hipStream_t s, const void *Pskip = nullptr);
 int launch_upconv2_fwd(const void *Px, const void *u, const float *bias, void *Py, const Geo &gf,
                        const Geo &gc, int cin, int cout, sp_dtype_t dt, hipStream_t s);
 int launch_upconv2_dgrad(const void *Pdy, const void *u, void *Pdx, const Geo &gf, const Geo &gc, int cin,
@@ -91,8 +92,9 @@ int launch_upconv_wgrad_mfma(const void *Px, const void *Pdy, float *du, float *
 bool pointwise_small_supported(const Geo &g, int cin, int cout, sp_dtype_t dt);
 int launch_pointwise_small_fwd(const void *Px, const void *p, const float *bias, void *Py, const Geo &g, int cin,
                                int cout, bool relu, hipStream_t s);
+// Pmask (optional): laid out like Pdx; results are zeroed where it is not positive
 int launch_pointwise_small_dgrad(const void *Pdy, const void *p, void *Pdx, const Geo &g, int cin, int cout,
-                                 hipStream_t s);
+                                 hipStream_t s, const void *Pmask = nullptr);
 size_t pointwise_small_wgrad_ws_bytes(const Geo &g, int cin, int cout);
 int launch_pointwise_small_wgrad(const void *Px, const void *Pdy, float *dp, float *db, const Geo &g, int cin,
                                  int cout, void *ws, hipStream_t s);

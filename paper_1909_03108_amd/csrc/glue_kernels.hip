@@ -42,6 +42,12 @@ Lay make_lay(const Geo &g, int c) {
     return l;
 }
 
+// two bf16 in a word -> 0xffff in each half whose value is positive (not zero, not negative, not NaN)
+__device__ __forceinline__ uint32_t positive_halves(uint32_t v) {
+    const uint32_t lo = v & 0xffffu, hi = v >> 16;
+    return ((lo - 1u) < 0x7f80u ? 0x0000ffffu : 0u) | ((hi - 1u) < 0x7f80u ? 0xffff0000u : 0u);
+}
+
 struct Vox { unsigned tile, ld, lh, lw; };
 __device__ __forceinline__ Vox decode(unsigned v, const Lay &l) {
     Vox o;
@@ -61,9 +67,15 @@ __device__ __forceinline__ long long pidx(const Geo &g, unsigned tile, unsigned 
 // ---- max pooling -------------------------------------------------------------------------------
 // One thread per (coarse voxel, channel).  Forward: y = max of the 8 window values.  Backward: dx of
 // the FIRST maximum in (d,h,w) scan order receives dy, the other seven receive 0.
-template <typename E, bool BWD>
+// MODE kPoolBwdJoin: the backward pass of an encoder level in one sweep.  The pooled tensor x is also the
+// level's ReLU output that the decoder took as its skip input, so the gradient that reaches the level's last
+// convolution is  dz = [x > 0] * (maxpool_bwd(x, dy) + skip_grad);  `skip` may be the same tensor as `out`
+// (a thread reads its eight positions before it writes them).  The sum is taken in fp32 and rounded once,
+// as sp_add does.
+enum PoolMode { kPoolFwd = 0, kPoolBwd = 1, kPoolBwdJoin = 2 };
+template <typename E, int MODE>
 __global__ __launch_bounds__(kThreads) void maxpool2_kernel(const E *__restrict__ x, const E *__restrict__ dy,
-                                                            E *__restrict__ out, Geo gf, Geo gc, Lay l, int C) {
+                                                            const E *skip, E *out, Geo gf, Geo gc, Lay l, int C) {
     const unsigned v = blockIdx.x * (kThreads >> l.cshift) + (threadIdx.x >> l.cshift);
     if (v >= l.nvox) return;
     const Vox o = decode(v, l);
@@ -73,17 +85,25 @@ __global__ __launch_bounds__(kThreads) void maxpool2_kernel(const E *__restrict_
     for (int k = 0; k < 8; ++k)
         pf[k] = pidx(gf, o.tile, 2 * o.ld + (k >> 2), 2 * o.lh + ((k >> 1) & 1), 2 * o.lw + (k & 1));
     for (int c = threadIdx.x & (l.cw - 1); c < C; c += l.cw) {
-        float best = ldf<E>(x, pf[0] * C + c);
+        float xv[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) xv[k] = ldf<E>(x, pf[k] * C + c);
+        float best = xv[0];
         int arg = 0;
 #pragma unroll
-        for (int k = 1; k < 8; ++k) {
-            const float t = ldf<E>(x, pf[k] * C + c);
-            if (t > best) { best = t; arg = k; }
-        }
-        if (BWD) {
+        for (int k = 1; k < 8; ++k)
+            if (xv[k] > best) { best = xv[k]; arg = k; }
+        if (MODE == kPoolBwd) {
             const E g = dy[pc * C + c];
 #pragma unroll
             for (int k = 0; k < 8; ++k) out[pf[k] * C + c] = k == arg ? g : E(0);
+        } else if (MODE == kPoolBwdJoin) {
+            const float g = ldf<E>(dy, pc * C + c);
+            float sk[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) sk[k] = ldf<E>(skip, pf[k] * C + c);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) stf<E>(out, pf[k] * C + c, xv[k] > 0.f ? (k == arg ? g : 0.f) + sk[k] : 0.f);
         } else {
             stf<E>(out, pc * C + c, best);
         }
@@ -355,7 +375,7 @@ template <int CO>
 __global__ __launch_bounds__(kThreads) void pointwise_small_dgrad_kernel(const uint16_t *__restrict__ dy,
                                                                          const uint16_t *__restrict__ p,
                                                                          uint16_t *__restrict__ dx, Geo g, Lay l,
-                                                                         int cin) {
+                                                                         int cin, const uint16_t *__restrict__ mask) {
     __shared__ float w[kPwMaxCin * CO];
     for (int i = threadIdx.x; i < cin * CO; i += kThreads) w[i] = bf16_to_f32(p[i]);
     __syncthreads();
@@ -367,6 +387,7 @@ __global__ __launch_bounds__(kThreads) void pointwise_small_dgrad_kernel(const u
 #pragma unroll
     for (int co = 0; co < CO; ++co) gv[co] = bf16_to_f32(dy[pv * CO + co]);
     uint4 *px = reinterpret_cast<uint4 *>(dx + pv * cin);
+    const uint4 *pm = reinterpret_cast<const uint4 *>(mask + pv * cin);      // read only if mask != nullptr
     for (int c8 = 0; c8 < cin / 8; ++c8) {
         uint32_t r[4];
 #pragma unroll
@@ -378,6 +399,11 @@ __global__ __launch_bounds__(kThreads) void pointwise_small_dgrad_kernel(const u
                 s1 = fmaf(gv[co], w[(8 * c8 + 2 * e2 + 1) * CO + co], s1);
             }
             r[e2] = static_cast<uint32_t>(f32_to_bf16(s0)) | (static_cast<uint32_t>(f32_to_bf16(s1)) << 16);
+        }
+        if (mask) {      // backward of the ReLU that produced the layer input: keep dx where that input is positive
+            const uint4 mv = pm[c8];
+            r[0] &= positive_halves(mv.x); r[1] &= positive_halves(mv.y);
+            r[2] &= positive_halves(mv.z); r[3] &= positive_halves(mv.w);
         }
         px[c8] = make_uint4(r[0], r[1], r[2], r[3]);
     }
@@ -496,16 +522,17 @@ int make_coarse(const Geo &gf, Geo *gc) {
 #define SP3D_BY_DTYPE(call_bf16, call_f32) do { if (dt == SP_BF16) { call_bf16; } else { call_f32; } } while (0)
 
 int launch_maxpool2(const void *Px, const void *Pdy, void *Pout, const Geo &gf, const Geo &gc, int c,
-                    sp_dtype_t dt, bool backward, hipStream_t s) {
+                    sp_dtype_t dt, bool backward, hipStream_t s, const void *Pskip) {
     if (1LL * gc.ntiles * gc.int_vox > 0xffffff00LL) return SP_EGEOM;
     const Lay l = make_lay(gc, c);
     const unsigned vpb = kThreads >> l.cshift;
     dim3 grid((l.nvox + vpb - 1) / vpb), block(kThreads);
 #define SP3D_POOL(E, B)                                                                              \
     hipLaunchKernelGGL((maxpool2_kernel<E, B>), grid, block, 0, s, static_cast<const E *>(Px),       \
-                       static_cast<const E *>(Pdy), static_cast<E *>(Pout), gf, gc, l, c)
-    if (backward) SP3D_BY_DTYPE(SP3D_POOL(uint16_t, true), SP3D_POOL(float, true));
-    else SP3D_BY_DTYPE(SP3D_POOL(uint16_t, false), SP3D_POOL(float, false));
+                       static_cast<const E *>(Pdy), static_cast<const E *>(Pskip), static_cast<E *>(Pout), gf, gc, l, c)
+    if (backward && Pskip) SP3D_BY_DTYPE(SP3D_POOL(uint16_t, kPoolBwdJoin), SP3D_POOL(float, kPoolBwdJoin));
+    else if (backward) SP3D_BY_DTYPE(SP3D_POOL(uint16_t, kPoolBwd), SP3D_POOL(float, kPoolBwd));
+    else SP3D_BY_DTYPE(SP3D_POOL(uint16_t, kPoolFwd), SP3D_POOL(float, kPoolFwd));
 #undef SP3D_POOL
     return record_hip(hipGetLastError());
 }
@@ -677,11 +704,12 @@ int launch_pointwise_small_fwd(const void *Px, const void *p, const float *bias,
 }
 
 int launch_pointwise_small_dgrad(const void *Pdy, const void *p, void *Pdx, const Geo &g, int cin, int cout,
-                                 hipStream_t s) {
+                                 hipStream_t s, const void *Pmask) {
     const Lay l = make_lay(g, 1);
     dim3 grid((l.nvox + kThreads - 1) / kThreads), block(kThreads);
     SP3D_BY_CO(pointwise_small_dgrad_kernel, grid, block, 0, s, static_cast<const uint16_t *>(Pdy),
-               static_cast<const uint16_t *>(p), static_cast<uint16_t *>(Pdx), g, l, cin)
+               static_cast<const uint16_t *>(p), static_cast<uint16_t *>(Pdx), g, l, cin,
+               static_cast<const uint16_t *>(Pmask))
     return record_hip(hipGetLastError());
 }
 

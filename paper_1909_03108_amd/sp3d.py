@@ -18,8 +18,8 @@ EXPORTS = ["sp_padded_elems", "sp_msg_elems", "sp_workspace_bytes", "sp_check_ge
            "sp_halo_exchange",
            "conv3d_fwd", "conv3d_dgrad", "conv3d_dgrad_relu", "conv3d_wgrad", "conv3d_fwd2", "conv3d_dgrad2",
            "conv3d_wgrad2", "sp_relu_bwd",
-           "sp_maxpool2_fwd", "sp_maxpool2_bwd", "sp_upconv2_fwd", "sp_upconv2_dgrad", "sp_upconv2_wgrad",
-           "sp_pointwise_fwd", "sp_pointwise_dgrad", "sp_pointwise_wgrad", "sp_concat", "sp_split", "sp_add",
+           "sp_maxpool2_fwd", "sp_maxpool2_bwd", "sp_maxpool2_bwd_join", "sp_upconv2_fwd", "sp_upconv2_dgrad", "sp_upconv2_wgrad",
+           "sp_pointwise_fwd", "sp_pointwise_dgrad", "sp_pointwise_dgrad_relu", "sp_pointwise_wgrad", "sp_concat", "sp_split", "sp_add",
            "sp_dice_ce_loss"]
 
 
@@ -85,11 +85,13 @@ def lib():
         L.sp_relu_bwd.argtypes, L.sp_relu_bwd.restype = [P, P, P, G, I, I, P], I
         L.sp_maxpool2_fwd.argtypes, L.sp_maxpool2_fwd.restype = [P, P, G, I, I, P], I
         L.sp_maxpool2_bwd.argtypes, L.sp_maxpool2_bwd.restype = [P, P, P, G, I, I, P], I
+        L.sp_maxpool2_bwd_join.argtypes, L.sp_maxpool2_bwd_join.restype = [P, P, P, P, G, I, I, P], I
         L.sp_upconv2_fwd.argtypes, L.sp_upconv2_fwd.restype = [P, P, P, P, G, I, I, I, P], I
         L.sp_upconv2_dgrad.argtypes, L.sp_upconv2_dgrad.restype = [P, P, P, G, I, I, I, P], I
         L.sp_upconv2_wgrad.argtypes, L.sp_upconv2_wgrad.restype = [P, P, P, P, G, I, I, I, P, Z, P], I
         L.sp_pointwise_fwd.argtypes, L.sp_pointwise_fwd.restype = [P, P, P, P, G, I, I, I, U, P], I
         L.sp_pointwise_dgrad.argtypes, L.sp_pointwise_dgrad.restype = [P, P, P, G, I, I, I, P], I
+        L.sp_pointwise_dgrad_relu.argtypes, L.sp_pointwise_dgrad_relu.restype = [P, P, P, P, G, I, I, I, P], I
         L.sp_pointwise_wgrad.argtypes, L.sp_pointwise_wgrad.restype = [P, P, P, P, G, I, I, I, P, Z, P], I
         L.sp_concat.argtypes, L.sp_concat.restype = [P, I, P, I, P, G, I, P], I
         L.sp_split.argtypes, L.sp_split.restype = [P, P, I, P, I, G, I, P], I
@@ -222,6 +224,11 @@ def sp_maxpool2_bwd(Px, Pdy, Pdx, gf, c, dt, stream=None):
            "sp_maxpool2_bwd")
 
 
+def sp_maxpool2_bwd_join(Px, Pdy, Pskip, Pdz, gf, c, dt, stream=None):
+    _check(lib().sp_maxpool2_bwd_join(_ptr(Px), _ptr(Pdy), _ptr(Pskip), _ptr(Pdz), ctypes.byref(gf), c, dt,
+                                      _stream(stream)), "sp_maxpool2_bwd_join")
+
+
 def sp_upconv2_fwd(Px, u, bias, Py, gf, cin, cout, dt, stream=None):
     _check(lib().sp_upconv2_fwd(_ptr(Px), _ptr(u), _ptr(bias), _ptr(Py), ctypes.byref(gf), cin, cout, dt,
                                 _stream(stream)), "sp_upconv2_fwd")
@@ -246,6 +253,11 @@ def sp_pointwise_fwd(Px, p, bias, Py, g, cin, cout, dt, flags=0, stream=None):
 def sp_pointwise_dgrad(Pdy, p, Pdx, g, cin, cout, dt, stream=None):
     _check(lib().sp_pointwise_dgrad(_ptr(Pdy), _ptr(p), _ptr(Pdx), ctypes.byref(g), cin, cout, dt,
                                     _stream(stream)), "sp_pointwise_dgrad")
+
+
+def sp_pointwise_dgrad_relu(Pdy, p, Px, Pdx, g, cin, cout, dt, stream=None):
+    _check(lib().sp_pointwise_dgrad_relu(_ptr(Pdy), _ptr(p), _ptr(Px), _ptr(Pdx), ctypes.byref(g), cin, cout, dt,
+                                         _stream(stream)), "sp_pointwise_dgrad_relu")
 
 
 def sp_pointwise_wgrad(Px, Pdy, dp, db, g, cin, cout, dt, ws=None, stream=None):

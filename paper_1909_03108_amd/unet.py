@@ -148,8 +148,9 @@ class UNet:
         A[block + ".y"] = P
         return P
 
-    def _block_bwd(self, block, Pg, g, cin, c, grads, need_dx=True):
-        """backward of a block, last layer first; layer k's output is layer k + 1's input"""
+    def _block_bwd(self, block, Pg, g, cin, c, grads, need_dx=True, masked_last=False):
+        """backward of a block, last layer first; layer k's output is layer k + 1's input.  masked_last: Pg is
+        already d/dz of the last layer (its producer applied the ReLU mask of the block output)."""
         A = self.A
         plan = self._plan(cin, c)
         for k in range(self.convs - 1, -1, -1):
@@ -160,7 +161,8 @@ class UNet:
             # the run then also produces the j voxels of d/dx around the tile that layer j - 1 reads.
             j, s = plan[k][2], plan[k][3]
             Pg = self._conv_bwd(name, A[name + ".x"], Py, Pg, g, cin if k == 0 else c, c, grads,
-                                need_dx=(need_dx or k > 0), masked=(k < self.convs - 1), mask_next=(k > 0),
+                                need_dx=(need_dx or k > 0), masked=(k < self.convs - 1 or masked_last),
+                                mask_next=(k > 0),
                                 exchange=(j == s - 1), grow=j)
         return Pg
 
@@ -284,12 +286,13 @@ class UNet:
                                 self._ws(sp3d.SP_OP_POINTWISE_WGRAD, g0, c0, self.classes))
         grads["head"] = dp
         Pg = self._tmp(g0, c0)
-        sp3d.sp_pointwise_dgrad(Pd, self.w["head"], Pg, g0, c0, self.classes, dt)
+        # the head reads the ReLU output of the last decoder block: its data gradient applies that mask
+        sp3d.sp_pointwise_dgrad_relu(Pd, self.w["head"], A["head.x"], Pg, g0, c0, self.classes, dt)
         skip_grad = {}
         for i in range(0, self.L - 1):
             g, c = self.g[i], ch[i]
             up_in = ch[i + 1]
-            Pg = self._block_bwd("dec%d" % i, Pg, g, 2 * c, c, grads)          # gradient of concat(skip, up)
+            Pg = self._block_bwd("dec%d" % i, Pg, g, 2 * c, c, grads, masked_last=(i == 0))   # -> d concat(skip, up)
             if isinstance(Pg, tuple):
                 Ps, Pu = Pg
             else:
@@ -304,18 +307,18 @@ class UNet:
             Pg = self._tmp(self.g[i + 1], up_in)
             sp3d.sp_upconv2_dgrad(Pu, self.w["up%d" % i], Pg, g, up_in, c, dt)
             self._release(Pu, g, c)
+        joined = False            # Pg already is d/dz of the level's last layer (pool backward + skip + ReLU mask)
         for i in range(self.L - 1, -1, -1):
             g, c = self.g[i], ch[i]
             cin = self.in_ch if i == 0 else ch[i - 1]
-            if i in skip_grad:                                        # gradient through the skip connection
-                sp3d.sp_add(Pg, skip_grad[i], Pg, g, c, dt)
-                self._release(skip_grad[i], g, c)
-            Pg = self._block_bwd("enc%d" % i, Pg, g, cin, c, grads, need_dx=(i > 0 or input_grad))
+            Pg = self._block_bwd("enc%d" % i, Pg, g, cin, c, grads, need_dx=(i > 0 or input_grad), masked_last=joined)
             if i > 0:
-                Pf = self._tmp(self.g[i - 1], cin)
-                sp3d.sp_maxpool2_bwd(A["enc%d.y" % (i - 1)], Pg, Pf, self.g[i - 1], cin, dt)
+                # the level above: gradient through its pooling, plus the one that came through its skip
+                # connection, masked by the ReLU of its output (which is the pooling input), in one sweep
+                Ps = skip_grad.pop(i - 1)
+                sp3d.sp_maxpool2_bwd_join(A["enc%d.y" % (i - 1)], Pg, Ps, Ps, self.g[i - 1], cin, dt)
                 self._release(Pg, g, cin)
-                Pg = Pf
+                Pg, joined = Ps, True
         dx = None
         if input_grad:
             dx = torch.empty((g0.n, g0.d, g0.h, g0.w, self.in_ch), dtype=Pg.dtype, device="cuda")

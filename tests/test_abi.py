@@ -121,6 +121,11 @@ def test_glue_calls_reject_bad_arguments_before_launching():
     assert L.sp_maxpool2_fwd(A, None, gp, 4, sp3d.SP_BF16, None) == sp3d.SP_EINVAL
     assert L.sp_maxpool2_fwd(A, B, op, 4, sp3d.SP_BF16, None) == sp3d.SP_EGEOM
     assert L.sp_maxpool2_bwd(A, B, C + 4, gp, 4, sp3d.SP_BF16, None) == sp3d.SP_EINVAL     # misaligned
+    far = FAKE * 64
+    assert L.sp_maxpool2_bwd_join(A, B, None, far, gp, 4, sp3d.SP_BF16, None) == sp3d.SP_EINVAL      # no skip gradient
+    assert L.sp_maxpool2_bwd_join(A, B, far, A, gp, 4, sp3d.SP_BF16, None) == sp3d.SP_EINVAL         # output over the input
+    assert L.sp_maxpool2_bwd_join(A, B, far + 16, far, gp, 4, sp3d.SP_BF16, None) == sp3d.SP_EINVAL  # skip overlaps, not equal
+    assert L.sp_maxpool2_bwd_join(A, B, far, far, op, 4, sp3d.SP_BF16, None) == sp3d.SP_EGEOM
     assert L.sp_upconv2_fwd(A, B, None, C, op, 8, 4, sp3d.SP_BF16, None) == sp3d.SP_EGEOM
     assert L.sp_upconv2_fwd(A, B, None, C, gp, 0, 4, sp3d.SP_BF16, None) == sp3d.SP_EINVAL
     assert L.sp_upconv2_dgrad(A, B, C, gp, 8, 4, 9, None) == sp3d.SP_EUNSUPPORTED
@@ -130,6 +135,8 @@ def test_glue_calls_reject_bad_arguments_before_launching():
     assert L.sp_upconv2_wgrad(A, B, C, None, gp, 8, 4, sp3d.SP_BF16, FAKE * 8, need - 1, None) == sp3d.SP_EWORKSPACE
     assert L.sp_pointwise_fwd(A, B, None, C, gp, 8, 3, sp3d.SP_BF16, 4, None) == sp3d.SP_EINVAL         # bad flag
     assert L.sp_pointwise_dgrad(A, None, C, gp, 8, 3, sp3d.SP_BF16, None) == sp3d.SP_EINVAL
+    assert L.sp_pointwise_dgrad_relu(A, B, None, far, gp, 8, 3, sp3d.SP_BF16, None) == sp3d.SP_EINVAL
+    assert L.sp_pointwise_dgrad_relu(A, B, far, far, gp, 8, 3, sp3d.SP_BF16, None) == sp3d.SP_EINVAL   # mask over the output
     needp = sp3d.sp_workspace_bytes(sp3d.SP_OP_POINTWISE_WGRAD, g, 8, 3, sp3d.SP_BF16)
     assert L.sp_pointwise_wgrad(A, B, C, None, gp, 8, 3, sp3d.SP_BF16, FAKE * 8, needp - 1, None) == sp3d.SP_EWORKSPACE
     assert L.sp_concat(A, 4, B, 0, C, gp, sp3d.SP_BF16, None) == sp3d.SP_EINVAL

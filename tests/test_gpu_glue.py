@@ -56,8 +56,26 @@ def test_maxpool_forward_and_backward_bit_exact(n, dhw, grid, dtype, c):
     mask[(slice(None),) * 4 + (slice(1, -1),) * 3] = False
     assert np.all(got[mask] == 9.0)                       # margins untouched
     Pdx = sp3d.alloc_padded(gf, c, dt)
-    sp3d.sp_maxpool2_bwd(Px, padded(gc, dy, c, dt), Pdx, gf, c, dt)
+    Pdy = padded(gc, dy, c, dt)
+    sp3d.sp_maxpool2_bwd(Px, Pdy, Pdx, gf, c, dt)
     assert np.array_equal(f64(volume(gf, Pdx, c, dt)), U.maxpool2_bwd(widen(x), widen(dy)))
+    # the encoder level's whole backward join, [x > 0] * (pool backward + skip gradient): the oracle's three
+    # steps composed (exact selects and one rounded sum), and bit for bit the three separate calls; in place too
+    skip = draw(dtype, (n,) + dhw + (c,), 3)
+    Ps = padded(gf, skip, c, dt)
+    Pj = torch.full(gf.padded_shape + (c,), 9.0, dtype=Px.dtype, device="cuda")
+    sp3d.sp_maxpool2_bwd_join(Px, Pdy, Ps, Pj, gf, c, dt)
+    ref = np.where(widen(x) > 0, U.maxpool2_bwd(widen(x), widen(dy)) + widen(skip), 0.0)
+    assert rel_err(f64(volume(gf, Pj, c, dt)), ref) <= (2.0 ** -8 if dtype == "bf16" else 1e-6)
+    got = f64(Pj)
+    maskf = np.ones(got.shape, dtype=bool)
+    maskf[(slice(None),) * 4 + (slice(1, -1),) * 3] = False
+    assert np.all(got[maskf] == 9.0)                      # margins untouched
+    sp3d.sp_add(Pdx, Ps, Pdx, gf, c, dt)
+    sp3d.sp_relu_bwd(Pdx, Px, Pdx, gf, c, dt)
+    assert torch.equal(volume(gf, Pdx, c, dt), volume(gf, Pj, c, dt))
+    sp3d.sp_maxpool2_bwd_join(Px, Pdy, Ps, Ps, gf, c, dt)
+    assert torch.equal(volume(gf, Ps, c, dt), volume(gf, Pj, c, dt))
 
 
 @pytest.mark.parametrize("n,dhw,grid,dtype", CASES)
@@ -106,6 +124,13 @@ def test_pointwise_fwd_dgrad_wgrad(n, dhw, grid, dtype, cin, cout):
     Pdx = sp3d.alloc_padded(g, cin, dt)
     sp3d.sp_pointwise_dgrad(Pdy, to_dev(p), Pdx, g, cin, cout, dt)
     assert rel_err(f64(volume(g, Pdx, cin, dt)), U.pointwise_dgrad(widen(dy), pw)) <= tol
+    # with the ReLU mask of the layer input (x clipped at zero stands for a ReLU output)
+    xr = np.where(widen(x) > 0, x, np.zeros_like(x))
+    Pm, Pdm = padded(g, xr, cin, dt), sp3d.alloc_padded(g, cin, dt)
+    sp3d.sp_pointwise_dgrad_relu(Pdy, to_dev(p), Pm, Pdm, g, cin, cout, dt)
+    assert rel_err(f64(volume(g, Pdm, cin, dt)), np.where(widen(xr) > 0, U.pointwise_dgrad(widen(dy), pw), 0.0)) <= tol
+    sp3d.sp_relu_bwd(Pdx, Pm, Pdx, g, cin, dt)
+    assert torch.equal(volume(g, Pdx, cin, dt), volume(g, Pdm, cin, dt))
     dp = torch.empty((cin, cout), dtype=torch.float32, device="cuda")
     db = torch.empty((cout,), dtype=torch.float32, device="cuda")
     ws = sp3d.alloc_ws(sp3d.sp_workspace_bytes(sp3d.SP_OP_POINTWISE_WGRAD, g, cin, cout, dt))
