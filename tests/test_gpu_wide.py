@@ -233,6 +233,9 @@ def test_glue_operations_on_a_wide_margin_layout(n, dhw, grid, cin, cout, dtype,
         Pdyc, Pdf = exchanged(gc, dyc, cin, dt), sp3d.alloc_padded(gf, cin, dt)
         sp3d.sp_maxpool2_bwd(Pf, Pdyc, Pdf, gf, cin, dt)
         r.append(volume(gf, Pdf, cin, dt))
+        Pj = sp3d.alloc_padded(gf, cin, dt)
+        sp3d.sp_maxpool2_bwd_join(Pf, Pdyc, Pdf, Pj, gf, cin, dt)          # skip gradient: any fine tensor
+        r.append(volume(gf, Pj, cin, dt))
         u = to_dev(synth.weights(cin, cout, 3, dtype, taps=(2, 2, 2)))
         Pu = sp3d.alloc_padded(gf, cout, dt)
         sp3d.sp_upconv2_fwd(Pdyc, u, None, Pu, gf, cin, cout, dt)
@@ -261,6 +264,8 @@ def test_glue_operations_on_a_wide_margin_layout(n, dhw, grid, cin, cout, dtype,
         r.append(volume(gf, Pdl, 3, dt))
         Pdh = sp3d.alloc_padded(gf, cin, dt)
         sp3d.sp_pointwise_dgrad(Pdl, p, Pdh, gf, cin, 3, dt)
+        r.append(volume(gf, Pdh, cin, dt))
+        sp3d.sp_pointwise_dgrad_relu(Pdl, p, Pf, Pdh, gf, cin, 3, dt)
         r.append(volume(gf, Pdh, cin, dt))
         dp = torch.empty((1, 1, 1, cin, 3), dtype=torch.float32, device="cuda")
         sp3d.sp_pointwise_wgrad(Pf, Pdl, dp, None, gf, cin, 3, dt,
