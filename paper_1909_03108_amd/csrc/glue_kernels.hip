@@ -370,43 +370,42 @@ __global__ __launch_bounds__(kThreads) void pointwise_small_fwd_kernel(const uin
     for (int co = 0; co < CO; ++co) y[pv * CO + co] = f32_to_bf16(relu ? fmaxf(acc[co], 0.f) : acc[co]);
 }
 
-// dx[v][ci] = sum_co dy[v][co] * p[ci][co]
+// dx[v][ci] = sum_co dy[v][co] * p[ci][co].  cin / 8 consecutive lanes share a voxel, 8 channels (16 bytes) each,
+// so that a wave's store (and its mask load) covers whole voxel records back to back.
 template <int CO>
 __global__ __launch_bounds__(kThreads) void pointwise_small_dgrad_kernel(const uint16_t *__restrict__ dy,
                                                                          const uint16_t *__restrict__ p,
                                                                          uint16_t *__restrict__ dx, Geo g, Lay l,
-                                                                         int cin, const uint16_t *__restrict__ mask) {
+                                                                         int cin, int cg_shift,
+                                                                         const uint16_t *__restrict__ mask) {
     __shared__ float w[kPwMaxCin * CO];
     for (int i = threadIdx.x; i < cin * CO; i += kThreads) w[i] = bf16_to_f32(p[i]);
     __syncthreads();
-    const unsigned v = blockIdx.x * kThreads + threadIdx.x;
+    const unsigned long long t = static_cast<unsigned long long>(blockIdx.x) * kThreads + threadIdx.x;
+    const unsigned v = static_cast<unsigned>(t >> cg_shift), c8 = static_cast<unsigned>(t) & ((1u << cg_shift) - 1);
     if (v >= l.nvox) return;
     const Vox o = decode(v, l);
     const long long pv = pidx(g, o.tile, o.ld, o.lh, o.lw);
     float gv[CO];
 #pragma unroll
     for (int co = 0; co < CO; ++co) gv[co] = bf16_to_f32(dy[pv * CO + co]);
-    uint4 *px = reinterpret_cast<uint4 *>(dx + pv * cin);
-    const uint4 *pm = reinterpret_cast<const uint4 *>(mask + pv * cin);      // read only if mask != nullptr
-    for (int c8 = 0; c8 < cin / 8; ++c8) {
-        uint32_t r[4];
+    uint32_t r[4];
 #pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2) {
-            float s0 = 0.f, s1 = 0.f;
+    for (int e2 = 0; e2 < 4; ++e2) {
+        float s0 = 0.f, s1 = 0.f;
 #pragma unroll
-            for (int co = 0; co < CO; ++co) {
-                s0 = fmaf(gv[co], w[(8 * c8 + 2 * e2) * CO + co], s0);
-                s1 = fmaf(gv[co], w[(8 * c8 + 2 * e2 + 1) * CO + co], s1);
-            }
-            r[e2] = static_cast<uint32_t>(f32_to_bf16(s0)) | (static_cast<uint32_t>(f32_to_bf16(s1)) << 16);
+        for (int co = 0; co < CO; ++co) {
+            s0 = fmaf(gv[co], w[(8 * c8 + 2 * e2) * CO + co], s0);
+            s1 = fmaf(gv[co], w[(8 * c8 + 2 * e2 + 1) * CO + co], s1);
         }
-        if (mask) {      // backward of the ReLU that produced the layer input: keep dx where that input is positive
-            const uint4 mv = pm[c8];
-            r[0] &= positive_halves(mv.x); r[1] &= positive_halves(mv.y);
-            r[2] &= positive_halves(mv.z); r[3] &= positive_halves(mv.w);
-        }
-        px[c8] = make_uint4(r[0], r[1], r[2], r[3]);
+        r[e2] = static_cast<uint32_t>(f32_to_bf16(s0)) | (static_cast<uint32_t>(f32_to_bf16(s1)) << 16);
     }
+    if (mask) {      // backward of the ReLU that produced the layer input: keep dx where that input is positive
+        const uint4 mv = *reinterpret_cast<const uint4 *>(mask + pv * cin + 8 * c8);
+        r[0] &= positive_halves(mv.x); r[1] &= positive_halves(mv.y);
+        r[2] &= positive_halves(mv.z); r[3] &= positive_halves(mv.w);
+    }
+    *reinterpret_cast<uint4 *>(dx + pv * cin + 8 * c8) = make_uint4(r[0], r[1], r[2], r[3]);
 }
 
 // dp[ci][co] = sum_v x[v][ci] * dy[v][co], db[co] = sum_v dy[v][co]: a block walks over a chunk of voxels
@@ -706,9 +705,14 @@ int launch_pointwise_small_fwd(const void *Px, const void *p, const float *bias,
 int launch_pointwise_small_dgrad(const void *Pdy, const void *p, void *Pdx, const Geo &g, int cin, int cout,
                                  hipStream_t s, const void *Pmask) {
     const Lay l = make_lay(g, 1);
-    dim3 grid((l.nvox + kThreads - 1) / kThreads), block(kThreads);
+    int cg_shift = 0;
+    while ((1 << cg_shift) < cin / 8) ++cg_shift;
+    const unsigned long long threads = static_cast<unsigned long long>(l.nvox) << cg_shift;
+    const unsigned long long blocks = (threads + kThreads - 1) / kThreads;
+    if (blocks > 0x7fffffffULL) return SP_EGEOM;
+    dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
     SP3D_BY_CO(pointwise_small_dgrad_kernel, grid, block, 0, s, static_cast<const uint16_t *>(Pdy),
-               static_cast<const uint16_t *>(p), static_cast<uint16_t *>(Pdx), g, l, cin,
+               static_cast<const uint16_t *>(p), static_cast<uint16_t *>(Pdx), g, l, cin, cg_shift,
                static_cast<const uint16_t *>(Pmask))
     return record_hip(hipGetLastError());
 }
