@@ -24,12 +24,19 @@ template <> struct VecT<4> { using type = uint32_t; };
 template <> struct VecT<8> { using type = u32x2; };
 template <> struct VecT<16> { using type = u32x4; };
 
+// 16 bytes at an address that is only aligned to the element (2 or 4 bytes): rows of voxel records whose size
+// does not divide 16 (3 channels of bf16 = 6 bytes) are still contiguous runs of bytes, and the hardware
+// serves wide accesses at any alignment
+struct __attribute__((packed, aligned(2))) Bytes16 { uint32_t w[4]; };
+
 template <typename T> __device__ __forceinline__ T zero_vec() { return T(0); }
 
 // Streaming accesses: every byte is touched exactly once, so bypass-friendly (non-temporal) loads and
 // stores are used; measured copy ceiling on MI355X: 6.5 TB/s against 6.1 TB/s with plain accesses.
 template <typename T> __device__ __forceinline__ T ld_stream(const T *p) { return __builtin_nontemporal_load(p); }
 template <typename T> __device__ __forceinline__ void st_stream(T *p, T v) { __builtin_nontemporal_store(v, p); }
+template <> __device__ __forceinline__ Bytes16 ld_stream<Bytes16>(const Bytes16 *p) { return *p; }
+template <> __device__ __forceinline__ void st_stream<Bytes16>(Bytes16 *p, Bytes16 v) { *p = v; }
 
 // ---------------------------------------------------------------------------------------------
 // partition / unpartition.  A "row" is the run of tw voxels of one tile at fixed (ld, lh); it is
@@ -40,7 +47,7 @@ struct PartArgs {
     int rowvecs;       // vectors per row
     int tpr;           // threads per row chunk (power of two, <= 256)
     unsigned nchunks;  // rows * cpr (row chunks in total; checked to fit 32 bits)
-    int vpv_num;       // vectors per voxel: rec / vec  (rows are addressed in vectors)
+    int vpv_num;       // vectors per voxel: rec / vec  (rows are addressed in vectors); Bytes16 rows: bytes per voxel
     FastDiv cpr;       // chunks of tpr vectors per row
     FastDiv rows_per_tile, th, gw, gh, gd;
 };
@@ -48,6 +55,14 @@ struct PartArgs {
 // Vectors per thread in the streaming kernels below: the loads of all of them are issued before the
 // first store, which keeps more bytes in flight per wave (two measured best; one or four are slower).
 constexpr int kVpt = 2;
+
+template <typename T> __device__ __forceinline__ T *at(T *p, long long off) { return p + off; }
+template <> __device__ __forceinline__ const Bytes16 *at<const Bytes16>(const Bytes16 *p, long long off) {
+    return reinterpret_cast<const Bytes16 *>(reinterpret_cast<const char *>(p) + off);
+}
+template <> __device__ __forceinline__ Bytes16 *at<Bytes16>(Bytes16 *p, long long off) {
+    return reinterpret_cast<Bytes16 *>(reinterpret_cast<char *>(p) + off);
+}
 
 template <typename T, bool INVERSE, int VPT>
 __global__ __launch_bounds__(kThreads) void partition_kernel(const T *__restrict__ src,
@@ -76,18 +91,19 @@ __global__ __launch_bounds__(kThreads) void partition_kernel(const T *__restrict
         const long long vvox = ((tn * D + ta * g.td + ld) * H + tb * g.th + lh) * W + 1LL * tc * g.tw;
         const long long pvox = tile * g.tile_vox +
                                (1LL * (ld + g.halo) * g.ph + lh + g.halo) * g.pw + g.halo;
-        so[k] = (INVERSE ? pvox : vvox) * a.vpv_num + j;
-        do_[k] = (INVERSE ? vvox : pvox) * a.vpv_num + j;
-        if (ok[k]) v[k] = ld_stream(src + so[k]);
+        // offsets in vectors; rows of Bytes16 start at any even byte, so those are kept in bytes
+        constexpr long long JS = std::is_same<T, Bytes16>::value ? 16 : 1;
+        so[k] = (INVERSE ? pvox : vvox) * a.vpv_num + j * JS;
+        do_[k] = (INVERSE ? vvox : pvox) * a.vpv_num + j * JS;
+        if (ok[k]) v[k] = ld_stream(at(src, so[k]));
     }
 #pragma unroll
     for (int k = 0; k < VPT; ++k)
-        if (ok[k]) st_stream(dst + do_[k], v[k]);
+        if (ok[k]) st_stream(at(dst, do_[k]), v[k]);
 }
 
-template <int VB>
+template <typename T>
 int partition_dispatch(const void *vol, void *P, const PartArgs &a, bool inverse, hipStream_t s) {
-    using T = typename VecT<VB>::type;
     // measured: gathering from the padded tiles gains from two vectors per thread, scattering into them
     // does not
     const unsigned rpb = (kThreads / a.tpr) * (inverse ? kVpt : 1);
@@ -246,11 +262,14 @@ __global__ __launch_bounds__(kThreads) void relu_bwd_bf16x8_kernel(const u32x4 *
 int launch_partition(const void *vol, void *P, const Geo &g, int c, sp_dtype_t dt, bool inverse,
                      hipStream_t s) {
     const size_t rec = static_cast<size_t>(c) * elem_size(dt);
-    const int vb = vec_bytes(rec);
+    int vb = vec_bytes(rec);
+    // narrow records whose rows are still whole multiples of 16 bytes: copy the rows as bytes, 16 at a time
+    const bool as_bytes = vb < 16 && (static_cast<size_t>(g.tw) * rec) % 16 == 0;
+    if (as_bytes) vb = 16;
     PartArgs a;
     a.g = g;
-    a.vpv_num = static_cast<int>(rec / vb);
-    const long long rowvecs = 1LL * g.tw * a.vpv_num;
+    a.vpv_num = as_bytes ? static_cast<int>(rec) : static_cast<int>(rec / vb);
+    const long long rowvecs = as_bytes ? static_cast<long long>(g.tw * rec / 16) : 1LL * g.tw * a.vpv_num;
     if (rowvecs > 0x7fffffffLL) return SP_EGEOM;
     a.rowvecs = static_cast<int>(rowvecs);
     int tpr = 1;
@@ -266,11 +285,12 @@ int launch_partition(const void *vol, void *P, const Geo &g, int c, sp_dtype_t d
     a.gw = make_fastdiv(g.gw);
     a.gh = make_fastdiv(g.gh);
     a.gd = make_fastdiv(g.gd);
+    if (as_bytes) return partition_dispatch<Bytes16>(vol, P, a, inverse, s);
     switch (vb) {
-    case 16: return partition_dispatch<16>(vol, P, a, inverse, s);
-    case 8: return partition_dispatch<8>(vol, P, a, inverse, s);
-    case 4: return partition_dispatch<4>(vol, P, a, inverse, s);
-    default: return partition_dispatch<2>(vol, P, a, inverse, s);
+    case 16: return partition_dispatch<VecT<16>::type>(vol, P, a, inverse, s);
+    case 8: return partition_dispatch<VecT<8>::type>(vol, P, a, inverse, s);
+    case 4: return partition_dispatch<VecT<4>::type>(vol, P, a, inverse, s);
+    default: return partition_dispatch<VecT<2>::type>(vol, P, a, inverse, s);
     }
 }
 

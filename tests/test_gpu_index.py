@@ -20,6 +20,11 @@ CASES = [
     (1, (5, 7, 9), (1, 1, 1), 4, "bf16"),          # single tile: every margin is zero fill
     (1, (24, 40, 72), (2, 2, 1), 32, "bf16"),      # rows longer than one block pass, ragged
     (1, (4, 6, 260), (2, 3, 2), 16, "f32"),
+    # narrow records whose rows are whole multiples of 16 bytes: rows copied as 16-byte pieces at 2- / 4-byte alignment
+    (1, (4, 6, 64), (2, 1, 2), 1, "bf16"),         # the CT volume itself: 64-byte rows
+    (1, (4, 4, 32), (1, 2, 2), 3, "bf16"),         # class logits: 6-byte records, 96-byte rows
+    (2, (4, 4, 8), (2, 1, 2), 3, "f32"),           # 12-byte records, 48-byte rows
+    (1, (2, 3, 520), (1, 1, 1), 3, "bf16"),        # rows longer than one pass of a block
 ]
 # margins wider than one voxel (several layers per exchange): n, dhw, grid, c, dtype, halo
 WIDE = [
@@ -28,6 +33,7 @@ WIDE = [
     (2, (6, 6, 9), (2, 1, 3), 3, "f32", 3),
     (1, (8, 12, 40), (2, 1, 1), 32, "bf16", 4),
     (1, (5, 7, 9), (1, 1, 1), 4, "bf16", 2),
+    (1, (4, 4, 32), (1, 1, 2), 3, "bf16", 3),
 ]
 
 
