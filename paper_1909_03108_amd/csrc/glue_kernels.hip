@@ -110,6 +110,78 @@ __global__ __launch_bounds__(kThreads) void maxpool2_kernel(const E *__restrict_
     }
 }
 
+// The same three operations for bf16 tensors whose channel count is a multiple of 8: a thread owns 8 channels
+// (16 bytes) of a coarse voxel, so every access is a full 16-byte piece and C / 8 consecutive lanes cover a
+// voxel record back to back.  Comparisons and the sum are taken on the widened values exactly as above.
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void maxpool2_x8_kernel(const uint16_t *__restrict__ x,
+                                                               const uint16_t *__restrict__ dy, const uint16_t *skip,
+                                                               uint16_t *out, Geo gf, Geo gc, Lay l, int C) {
+    const unsigned v = blockIdx.x * (kThreads >> l.cshift) + (threadIdx.x >> l.cshift);
+    if (v >= l.nvox) return;
+    const Vox o = decode(v, l);
+    const long long pc = pidx(gc, o.tile, o.ld, o.lh, o.lw);
+    long long pf[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+        pf[k] = pidx(gf, o.tile, 2 * o.ld + (k >> 2), 2 * o.lh + ((k >> 1) & 1), 2 * o.lw + (k & 1));
+    auto widen8 = [](const uint4 &q, float (&f)[8]) {
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = __uint_as_float(w[i] << 16);
+            f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    };
+    auto narrow8 = [](const float (&f)[8]) {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            w[i] = static_cast<uint32_t>(f32_to_bf16(f[2 * i])) | (static_cast<uint32_t>(f32_to_bf16(f[2 * i + 1])) << 16);
+        return make_uint4(w[0], w[1], w[2], w[3]);
+    };
+    for (int cg = threadIdx.x & (l.cw - 1); 8 * cg < C; cg += l.cw) {
+        float xv[8][8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) widen8(*reinterpret_cast<const uint4 *>(x + pf[k] * C + 8 * cg), xv[k]);
+        float best[8];
+        int arg[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            best[e] = xv[0][e];
+            arg[e] = 0;
+#pragma unroll
+            for (int k = 1; k < 8; ++k)
+                if (xv[k][e] > best[e]) { best[e] = xv[k][e]; arg[e] = k; }
+        }
+        if (MODE == kPoolFwd) {
+            *reinterpret_cast<uint4 *>(out + pc * C + 8 * cg) = narrow8(best);
+            continue;
+        }
+        float g[8];
+        widen8(*reinterpret_cast<const uint4 *>(dy + pc * C + 8 * cg), g);
+        uint4 sk[8];
+        if (MODE == kPoolBwdJoin) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) sk[k] = *reinterpret_cast<const uint4 *>(skip + pf[k] * C + 8 * cg);
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            float r[8];
+            if (MODE == kPoolBwdJoin) {
+                float s8[8];
+                widen8(sk[k], s8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) r[e] = xv[k][e] > 0.f ? (arg[e] == k ? g[e] : 0.f) + s8[e] : 0.f;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) r[e] = arg[e] == k ? g[e] : 0.f;
+            }
+            *reinterpret_cast<uint4 *>(out + pf[k] * C + 8 * cg) = narrow8(r);
+        }
+    }
+}
+
 // ---- transposed convolution 2x2x2, stride 2 ----------------------------------------------------------
 // Forward: one thread per (fine voxel, co): y = bias + sum_ci x[coarse][ci] * u[a][b][c][ci][co].
 template <typename E>
@@ -523,6 +595,20 @@ int make_coarse(const Geo &gf, Geo *gc) {
 int launch_maxpool2(const void *Px, const void *Pdy, void *Pout, const Geo &gf, const Geo &gc, int c,
                     sp_dtype_t dt, bool backward, hipStream_t s, const void *Pskip) {
     if (1LL * gc.ntiles * gc.int_vox > 0xffffff00LL) return SP_EGEOM;
+    if (dt == SP_BF16 && c % 8 == 0) {
+        const Lay l = make_lay(gc, c / 8);
+        const unsigned vpb = kThreads >> l.cshift;
+        dim3 grid((l.nvox + vpb - 1) / vpb), block(kThreads);
+#define SP3D_POOL8(M)                                                                                     \
+    hipLaunchKernelGGL(maxpool2_x8_kernel<M>, grid, block, 0, s, static_cast<const uint16_t *>(Px),       \
+                       static_cast<const uint16_t *>(Pdy), static_cast<const uint16_t *>(Pskip),          \
+                       static_cast<uint16_t *>(Pout), gf, gc, l, c)
+        if (backward && Pskip) SP3D_POOL8(kPoolBwdJoin);
+        else if (backward) SP3D_POOL8(kPoolBwd);
+        else SP3D_POOL8(kPoolFwd);
+#undef SP3D_POOL8
+        return record_hip(hipGetLastError());
+    }
     const Lay l = make_lay(gc, c);
     const unsigned vpb = kThreads >> l.cshift;
     dim3 grid((l.nvox + vpb - 1) / vpb), block(kThreads);
