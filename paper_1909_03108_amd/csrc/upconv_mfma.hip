@@ -104,6 +104,14 @@ __global__ __launch_bounds__(kT) void upconv_fwd_mfma_kernel(UpArgs a) {
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) b[ks] = *reinterpret_cast<const bf16x8 *>(px + 16 * ks);
     };
+    // Stores.  A lane of D holds 4 x 8 bytes of ONE fine voxel, and neighbouring lanes hold voxels two apart, so
+    // direct stores are 8-byte pieces scattered over 4 KB.  With room in LDS (Cin <= 128) the two taps that
+    // interleave along W are put together in a wave-private buffer first (64 fine voxels x 64 bytes, rows padded
+    // to 72 bytes) and written out as 16-byte pieces that are contiguous across the wave: 1 KB per instruction.
+    constexpr bool TR = NKS <= 8;
+    constexpr int TROW = 72;
+    char *tbuf = lds + 8 * NKS * 1024 + wave * (64 * TROW);
+    const int rv = lane >> 2, rp = lane & 3;
     auto compute = [&](int item, const bf16x8 (&b)[NKS]) {
         const Item o = decode_item(item, a.nseg, a.gc);
         const int w = o.w0 + m;
@@ -118,7 +126,29 @@ __global__ __launch_bounds__(kT) void upconv_fwd_mfma_kernel(UpArgs a) {
                 const bf16x8 af = *reinterpret_cast<const bf16x8 *>(lds + (tap * NKS + ks) * 1024 + lane * 16);
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, b[ks], acc, 0, 0, 0);
             }
-            if (ok) {
+            if (TR) {
+                char *wr = tbuf + (2 * m + (tap & 1)) * TROW + 8 * kh;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<uint2 *>(wr + 16 * q) = make_uint2(pack2(acc[4 * q], acc[4 * q + 1]),
+                                                                         pack2(acc[4 * q + 2], acc[4 * q + 3]));
+                if (tap & 1) {
+                    // both taps of this fine row are in the buffer (the LDS unit serves a wave's accesses in order)
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    uint16_t *prow = a.out + pvox(a.gf, o.tile, 2 * o.d + (tap >> 2), 2 * o.h + ((tap >> 1) & 1),
+                                                  2 * o.w0) * a.cout + C * cb + 8 * rp;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int fv = 16 * j + rv;                     // fine voxel of the 64
+                        const uint2 lo = *reinterpret_cast<const uint2 *>(tbuf + fv * TROW + 16 * rp);
+                        const uint2 hi = *reinterpret_cast<const uint2 *>(tbuf + fv * TROW + 16 * rp + 8);
+                        if (2 * o.w0 + fv < 2 * a.gc.tw)
+                            *reinterpret_cast<uint4 *>(prow + static_cast<size_t>(fv) * a.cout) =
+                                make_uint4(lo.x, lo.y, hi.x, hi.y);
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                }
+            } else if (ok) {
                 uint16_t *py = a.out + pvox(a.gf, o.tile, 2 * o.d + (tap >> 2), 2 * o.h + ((tap >> 1) & 1),
                                             2 * w + (tap & 1)) * a.cout + C * cb + 4 * kh;
 #pragma unroll
@@ -553,7 +583,8 @@ int launch_upconv_fwd_mfma(const void *Px, const void *u, const float *bias, voi
     }
     int rc = plan(gc, cout / C, &a);
     if (rc != SP_OK) return rc;
-    const int lds_bytes = 8 * (cin / 16) * 1024;
+    // weight fragments, plus (Cin <= 128) one 64-voxel store buffer per wave
+    const int lds_bytes = 8 * (cin / 16) * 1024 + (cin <= 128 ? (kT / 64) * 64 * 72 : 0);
     switch (cin / C) {
     case 1: return launch(upconv_fwd_mfma_kernel<2>, a, lds_bytes, s);
     case 2: return launch(upconv_fwd_mfma_kernel<4>, a, lds_bytes, s);
