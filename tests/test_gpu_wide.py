@@ -105,6 +105,8 @@ BLOCKS = [  # n, dhw, grid, channels of the stack (input first), dtype
     (1, (12, 20, 72), (2, 2, 1), (32, 32, 32), "bf16"),          # ragged patches, two layers
     (1, (12, 12, 48), (3, 2, 2), (32, 32, 32, 32), "bf16"),      # three layers, inner tiles grow on both sides
     (1, (8, 16, 40), (2, 2, 1), (64, 64, 32), "bf16"),           # chunk pairs
+    (1, (4, 4, 8), (2, 2, 1), (64, 64, 64), "bf16"),             # masked data gradient with grow on chunk pairs, tiny tiles
+    (1, (8, 8, 40), (2, 2, 1), (128, 128, 128), "bf16"),         # the same with partial sums between pairs
     (1, (6, 8, 32), (1, 2, 1), (128, 32, 64, 32), "bf16"),       # partial sums between pairs, grow 2 and 1
 ]
 
