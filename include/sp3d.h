@@ -25,6 +25,14 @@
  *     grow = k - i and also computes the `grow` voxels around the interior that its successors
  *     read, instead of receiving them (redundant arithmetic in exchange for fewer exchanges).
  *     The grown box stops at the volume border: what lies beyond is zero padding at every layer.
+ *   - 2-D variant (the paper's 2-D U-Net on slabs, Sec. 3: the same architecture with 2-D convolutions
+ *     and poolings): with `flat` = 1 in the geometry the D axis is a stack of independent slices.  The
+ *     convolutions then have extent 1 along D (weights w[3][3][Cin][Cout], taps (kh, kw)), the pooling
+ *     and transposed-convolution windows are 1 x 2 x 2 (u[2][2][Cin][Cout]; the coarse side has
+ *     extents d, h/2, w/2), a grown box does not grow along D, and the halo operations move only the
+ *     8 regions with dd = 0.  The layouts are unchanged: the D margins of P and the other 18 regions
+ *     of M exist but are neither read nor written.  Everything stated below for "3x3x3" / "2x2x2"
+ *     holds with the D extent of the kernel or window set to 1.
  *
  * Layouts (C = channels, fastest)
  *   volume        V[n][d][h][w][C]
@@ -35,7 +43,8 @@
  *                 without (0,0,0), each region row-major over its own (d,h,w) extents.  Region
  *                 `dir` holds the tile's own voxels nearest to the neighbour in direction `dir`:
  *                 on an axis with dir = -1 the first `halo` planes, +1 the last `halo`, 0 all.
- *   weights       w[3][3][3][Cin][Cout] in the tensor dtype; weight gradient same shape, float
+ *   weights       w[3][3][3][Cin][Cout] in the tensor dtype (flat: w[3][3][Cin][Cout]); weight gradient
+ *                 same shape, float
  *   bias          float[Cout]; bias gradient float[Cout]
  */
 #ifndef SP3D_H
@@ -53,6 +62,7 @@ typedef struct sp_geom {
     int32_t gd, gh, gw;   /* tile grid over D, H, W; must divide d, h, w        */
     int32_t halo;         /* margin width of the layout, 1..SP_MAX_HALO          */
     int32_t grow;         /* conv3d_fwd*, conv3d_dgrad*: 0 <= grow < halo, see below; ignored elsewhere */
+    int32_t flat;         /* 0: 3-D operations; 1: the 2-D variant (D = stack of slices), see above       */
 } sp_geom_t;
 
 enum { SP_MAX_HALO = 4 };

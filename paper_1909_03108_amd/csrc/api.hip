@@ -17,7 +17,8 @@ int record_hip(hipError_t e) {
 int make_geo(const sp_geom_t *g, Geo *out) {
     if (!g) return SP_EINVAL;
     if (g->n <= 0 || g->d <= 0 || g->h <= 0 || g->w <= 0 || g->gd <= 0 || g->gh <= 0 ||
-        g->gw <= 0 || g->halo < 0 || g->grow < 0 || (g->grow > 0 && g->grow >= g->halo))
+        g->gw <= 0 || g->halo < 0 || g->grow < 0 || (g->grow > 0 && g->grow >= g->halo) ||
+        (g->flat != 0 && g->flat != 1))
         return SP_EINVAL;
     if (g->d % g->gd || g->h % g->gh || g->w % g->gw) return SP_EGEOM;
     if (g->halo < 1 || g->halo > SP_MAX_HALO) return SP_EUNSUPPORTED;
@@ -26,7 +27,9 @@ int make_geo(const sp_geom_t *g, Geo *out) {
     o.td = g->d / g->gd; o.th = g->h / g->gh; o.tw = g->w / g->gw;
     o.halo = g->halo;
     o.grow = g->grow;
-    if (o.td < o.halo || o.th < o.halo || o.tw < o.halo) return SP_EGEOM;
+    o.flat = g->flat;
+    // (the 2-D variant moves nothing along D, so a tile may hold fewer slices than the margin is wide)
+    if ((!o.flat && o.td < o.halo) || o.th < o.halo || o.tw < o.halo) return SP_EGEOM;
     o.pd = o.td + 2 * o.halo; o.ph = o.th + 2 * o.halo; o.pw = o.tw + 2 * o.halo;
     long long nt = 1LL * o.n * o.gd * o.gh * o.gw;
     if (nt > 0x7fffffffLL) return SP_EGEOM;

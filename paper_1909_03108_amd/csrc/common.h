@@ -16,6 +16,7 @@ struct Geo {
     int halo;
     int grow;                // conv3d_fwd / conv3d_dgrad: output box = interior grown by this many voxels
                              // towards every neighbouring tile (0 <= grow < halo); other operations ignore it
+    int flat;                // 1: 2-D variant, D is a stack of independent slices (kernel / window extent 1 along D)
     int ntiles;              // n * gd * gh * gw
     long long tile_vox;      // pd * ph * pw   (voxels per padded tile)
     long long int_vox;       // td * th * tw   (interior voxels per tile)
@@ -32,6 +33,8 @@ template <typename T> inline T *shifted(T *p, const Geo &g, int c, sp_dtype_t dt
     return p ? reinterpret_cast<T *>(reinterpret_cast<B *>(p) + interior_shift(g) * c * (dt == SP_BF16 ? 2 : 4)) : p;
 }
 int record_hip(hipError_t e);                      // stores e, returns SP_ELAUNCH if e != success
+__host__ __device__ inline int grow_d(const Geo &g) { return g.flat ? 0 : g.grow; }      // growth of a convolution's output box along D
+__host__ __device__ inline int taps_of(const Geo &g) { return g.flat ? 9 : 27; }          // taps of the 3x3(x3) kernel
 inline size_t elem_size(sp_dtype_t dt) { return dt == SP_BF16 ? 2 : 4; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -182,8 +185,10 @@ __device__ __forceinline__ TileBox tile_box(const Geo &g, int tile) {
     if (g.grow > 0) {
         const int tc = tile % g.gw, t1 = tile / g.gw;
         const int tb = t1 % g.gh, ta = (t1 / g.gh) % g.gd;
-        if (ta > 0) { ld -= g.grow; b.bd += g.grow; }
-        if (ta < g.gd - 1) b.bd += g.grow;
+        if (!g.flat) {          // slices of the 2-D variant do not interact: nothing to grow along D
+            if (ta > 0) { ld -= g.grow; b.bd += g.grow; }
+            if (ta < g.gd - 1) b.bd += g.grow;
+        }
         if (tb > 0) { lh -= g.grow; b.bh += g.grow; }
         if (tb < g.gh - 1) b.bh += g.grow;
         if (tc > 0) { lw -= g.grow; b.bw += g.grow; }

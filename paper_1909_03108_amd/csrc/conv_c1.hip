@@ -357,7 +357,7 @@ void plan(const Geo &g, C1Args *a) {
 }  // namespace
 
 bool conv_c1_supported(const Geo &g, int cin, int cout, sp_dtype_t dt) {
-    return dt == SP_BF16 && cin == 1 && cout % 32 == 0 && cout <= 1024 &&
+    return !g.flat && dt == SP_BF16 && cin == 1 && cout % 32 == 0 && cout <= 1024 &&
            1LL * g.ntiles * g.td * ((g.th + BH - 1) / BH) * ((g.tw + BW - 1) / BW) < 0x7fffffffLL;
 }
 

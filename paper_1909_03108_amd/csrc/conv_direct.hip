@@ -22,7 +22,8 @@ template <> __device__ __forceinline__ void stf<uint16_t>(uint16_t *p, long long
 
 // One thread per (voxel of the output box, output channel).  With DGRAD the taps are mirrored and the weight
 // tensor is read as w[tap][ko][ki] (ko = this kernel's output channel = the layer's input channel).
-// KS = kernel extent per axis: 3 (the 3x3x3 convolution) or 1 (the 1x1x1 classifier).
+// KS = kernel extent per axis: 3 (the 3x3x3 convolution) or 1 (the 1x1x1 classifier); in the 2-D variant
+// (g.flat) the extent along D is 1 and the box does not grow along D.
 // The threads cover the interior grown by g.grow on every side; a thread whose voxel lies beyond a side on
 // which its tile has no neighbour (beyond the volume) has nothing to do.
 template <typename E, bool DGRAD, int KS>
@@ -36,13 +37,14 @@ __global__ __launch_bounds__(kThreads) void conv_direct_kernel(const E *__restri
     if (idx >= total) return;
     const int co = static_cast<int>(idx % ko);
     const long long v = idx / ko;                       // voxel of the grown boxes of all tiles
-    const int ed = g.td + 2 * g.grow, eh = g.th + 2 * g.grow, ew = g.tw + 2 * g.grow;
+    const int gd_ = grow_d(g);
+    const int ed = g.td + 2 * gd_, eh = g.th + 2 * g.grow, ew = g.tw + 2 * g.grow;
     const long long box_vox = 1LL * ed * eh * ew;
     const long long tile = v / box_vox;
     const unsigned r = static_cast<unsigned>(v % box_vox);
     const unsigned ehw = static_cast<unsigned>(eh) * ew;
     // padded coordinates of the output voxel
-    const int pd = static_cast<int>(r / ehw) + g.halo - g.grow, ph = static_cast<int>((r % ehw) / ew) + g.halo - g.grow,
+    const int pd = static_cast<int>(r / ehw) + g.halo - gd_, ph = static_cast<int>((r % ehw) / ew) + g.halo - g.grow,
               pw = static_cast<int>(r % ew) + g.halo - g.grow;
     if (g.grow > 0) {
         const int tc = static_cast<int>(tile % g.gw), tb = static_cast<int>((tile / g.gw) % g.gh),
@@ -55,12 +57,13 @@ __global__ __launch_bounds__(kThreads) void conv_direct_kernel(const E *__restri
     const long long base = tile * g.tile_vox;
     float acc = bias ? bias[co] : 0.f;
     constexpr int O = KS / 2;         // tap k reads the input voxel at output coordinate + k - O
-    for (int kd = 0; kd < KS; ++kd)
+    const int KD = g.flat ? 1 : KS, OD = KD / 2;
+    for (int kd = 0; kd < KD; ++kd)
         for (int kh = 0; kh < KS; ++kh)
             for (int kw = 0; kw < KS; ++kw) {
-                const long long pv = base + (1LL * (pd + kd - O) * g.ph + ph + kh - O) * g.pw + pw + kw - O;
+                const long long pv = base + (1LL * (pd + kd - OD) * g.ph + ph + kh - O) * g.pw + pw + kw - O;
                 const E *xin = Pin + pv * ki;
-                const int tap = DGRAD ? ((KS - 1 - kd) * KS + (KS - 1 - kh)) * KS + (KS - 1 - kw)
+                const int tap = DGRAD ? ((KD - 1 - kd) * KS + (KS - 1 - kh)) * KS + (KS - 1 - kw)
                                       : (kd * KS + kh) * KS + kw;
                 if (DGRAD) {
                     const E *wt = w + (1LL * tap * ko + co) * ki;      // w[tap][ci=co][co'=c]
@@ -91,7 +94,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_direct_kernel(const E *__restr
     const int tapci = blockIdx.x, chunk = blockIdx.y;
     const int tap = tapci / cin, ci = tapci % cin;
     const int O = g.halo - KS / 2;    // tap k reads padded coordinate (interior coordinate + k + O)
-    const int kd = tap / (KS * KS) + O, kh = (tap / KS) % KS + O, kw = tap % KS + O;
+    // 2-D variant: KS * KS taps, all in the voxel's own slice
+    const int kd = g.flat ? g.halo : tap / (KS * KS) + O, kh = (tap / KS) % KS + O, kw = tap % KS + O;
     const int nvl = kThreads / cw;
     const int col = threadIdx.x % cw, vl = threadIdx.x / cw;
     const int co = blockIdx.z * cw + col;
@@ -115,7 +119,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_direct_kernel(const E *__restr
     if (vl == 0 && co < cout) {
         float s = 0.f;
         for (int l = 0; l < nvl; ++l) s += red[l * cw + col];
-        part[(1LL * chunk * KS * KS * KS * cin + tapci) * cout + co] = s;
+        part[(1LL * chunk * gridDim.x + tapci) * cout + co] = s;
     }
 }
 
@@ -199,7 +203,7 @@ int launch_reduce_partials(const float *part, float *out, int nparts, long long 
 int launch_conv_direct(const void *Pin, const void *w, const float *bias, void *Pout, const Geo &g,
                        int ki, int ko, sp_dtype_t dt, bool relu, bool dgrad, hipStream_t s, int ks,
                        const void *mask) {
-    const long long total = 1LL * g.ntiles * (g.td + 2 * g.grow) * (g.th + 2 * g.grow) * (g.tw + 2 * g.grow) * ko;
+    const long long total = 1LL * g.ntiles * (g.td + 2 * grow_d(g)) * (g.th + 2 * g.grow) * (g.tw + 2 * g.grow) * ko;
     const long long blocks = (total + kThreads - 1) / kThreads;
     if (blocks > 0x7fffffffLL) return SP_EGEOM;
     dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
@@ -231,7 +235,7 @@ static void wgrad_direct_plan(const Geo &g, int *nchunks, long long *chunk_vox) 
 size_t wgrad_direct_ws_bytes(const Geo &g, int cin, int cout, int ks) {
     int nc; long long cv;
     wgrad_direct_plan(g, &nc, &cv);
-    const size_t taps = static_cast<size_t>(ks) * ks * ks;
+    const size_t taps = static_cast<size_t>(g.flat ? 1 : ks) * ks * ks;
     return (static_cast<size_t>(nc) * taps * cin * cout + static_cast<size_t>(nc) * cout) * sizeof(float);
 }
 
@@ -240,7 +244,7 @@ int launch_wgrad_direct(const void *Px, const void *Pdz, float *dw, float *db, c
     int nc; long long cv;
     wgrad_direct_plan(g, &nc, &cv);
     const long long total = 1LL * g.ntiles * g.int_vox;
-    const int taps = ks * ks * ks;
+    const int taps = (g.flat ? 1 : ks) * ks * ks;
     float *part_w = static_cast<float *>(ws);
     float *part_b = part_w + static_cast<size_t>(nc) * taps * cin * cout;
     const int cw = cout < kThreads ? cout : kThreads;

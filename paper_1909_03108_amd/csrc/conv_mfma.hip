@@ -17,6 +17,10 @@
 // the MFMA stream of the current step.  All 27 x 2 weight fragments (32 x 16 each) live in
 // registers for the whole march.
 //
+// 2-D variant (template parameter KD = 1; geometry flag `flat`): the kernel has extent 1 along D, so a staged
+// plane feeds only its own output plane (tap kd = 1 of the scheme above; the MFMAs of kd = 0, 2 and their
+// weight fragments are left out).  The march, the ring and the epilogue timing are unchanged.
+//
 // MFMA operand roles: A = weights [M = Cout][K = 16 input channels], B = voxels [K][N = 32 voxels
 // along W], D[M = Cout][N = voxel].  Lane l of B supplies voxel l%32, channels 8*(l/32)..+7 of the
 // 16-channel half; lane l of D holds voxel l%32, channels 8*(i/4) + 4*(l/32) + i%4 for i = 0..15.
@@ -88,7 +92,7 @@ struct ConvArgs {
 // kernel sees them (ki in, ko out).
 __global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t *__restrict__ w,
                                                            uint16_t *__restrict__ wpack, int ki, int ko,
-                                                           int dgrad) {
+                                                           int dgrad, int flat) {
     const int idx = blockIdx.x * 256 + threadIdx.x;
     const int per_pair = NFRAG * 64 * 8;
     const int pairs = (ki / C) * (ko / C);
@@ -98,6 +102,15 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t *__res
     const int e = i & 7, lane = (i >> 3) & 63, half = (i >> 9) & 1, tap = i >> 10;
     const int m = C * cj + (lane & 31), k = C * ci + 16 * half + 8 * (lane >> 5) + e;
     // forward: w[tap][cin = k][cout = m] (row length ko); dgrad: w[26-tap][cin = m][cout = k] (row length ki)
+    if (flat) {
+        // w[3][3][..][..]: its 9 taps are the kernel's taps 9..17 (kd = 1); the other fragments are never loaded
+        const int t9 = tap - 9;
+        uint16_t v = 0;
+        if (t9 >= 0 && t9 < 9)
+            v = dgrad ? w[(static_cast<size_t>(8 - t9) * ko + m) * ki + k] : w[(static_cast<size_t>(t9) * ki + k) * ko + m];
+        wpack[idx] = v;
+        return;
+    }
     wpack[idx] = dgrad ? w[(static_cast<size_t>(26 - tap) * ko + m) * ki + k]
                        : w[(static_cast<size_t>(tap) * ki + k) * ko + m];
 }
@@ -209,7 +222,7 @@ __device__ __forceinline__ void store_unit(const Ctx<HAS_BIAS> &c, int d, const 
 // consume them.  P = Dp mod 4: output plane Dp-kd lives in slot (P-kd) mod 4, plane Dp-3 in slot (P+1) mod 4.
 // FULL: the patch lies completely inside the tile interior, so stores need no mask (no branches in
 // the step, which lets the scheduler weave the side work between the MFMAs).
-template <int P, bool EPI, int MODE, int RELU, bool FULL, bool HAS_BIAS>
+template <int P, bool EPI, int MODE, int RELU, bool FULL, int KD, bool HAS_BIAS>
 __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, int lane, const char *lbase,
                                            const bf16x8 (&wf)[NFRAG], f32x16 (&acc)[4][RH]) {
     constexpr int NR = RH + 2;
@@ -263,6 +276,7 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, int l
                 if (h < 0 || h >= RH) continue;
 #pragma unroll
                 for (int kd = 0; kd < 3; ++kd) {
+                    if (KD == 1 && kd != 1) continue;
                     const int slot = (P - kd + 4) & 3;
                     acc[slot][h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                         wf[((kd * 3 + kh) * 3 + kw) * 2 + half], b[gi & 1][r], acc[slot][h], 0, 0, 0);
@@ -270,7 +284,7 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, int l
             }
         // weave: after each MFMA let a few of the side-work instructions issue while it executes
 #pragma unroll
-        for (int i = 0; i < 3 * (RH + 1) * 2; ++i) {
+        for (int i = 0; i < KD * (RH + 1) * 2; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
             __builtin_amdgcn_sched_group_barrier(0x006, 3, 0);   // up to three VALU / SALU
             if (i % 6 == 2) __builtin_amdgcn_sched_group_barrier(0x060, 1, 0);   // a vector memory op
@@ -278,7 +292,7 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, int l
     }
 }
 
-template <int MODE, bool HAS_BIAS, int RELU>
+template <int MODE, bool HAS_BIAS, int RELU, int KD>
 __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];   // NBUF planes of PLANE_BYTES
     const Geo &g = a.g;
@@ -306,6 +320,7 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
     bf16x8 wf[NFRAG];
 #pragma unroll
     for (int f = 0; f < NFRAG; ++f) {
+        if (KD == 1 && f / 18 != 1) continue;        // 2-D variant: only the taps with kd = 1 exist
         const uint4 q = a.wpack[(cj * NFRAG + f) * 64 + lane];
         wf[f] = *reinterpret_cast<const bf16x8 *>(&q);
     }
@@ -374,16 +389,16 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
     auto march = [&](auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
         // the first three steps have no finished plane to store (nplanes >= 3 always)
-        plane_step<0, false, MODE, RELU, FULL>(c, 0, lane, lbase, wf, acc);
+        plane_step<0, false, MODE, RELU, FULL, KD>(c, 0, lane, lbase, wf, acc);
         SP3D_STEP_END();
-        plane_step<1, false, MODE, RELU, FULL>(c, 1, lane, lbase + PLANE_BYTES, wf, acc);
+        plane_step<1, false, MODE, RELU, FULL, KD>(c, 1, lane, lbase + PLANE_BYTES, wf, acc);
         SP3D_STEP_END();
-        plane_step<2, false, MODE, RELU, FULL>(c, 2, lane, lbase + 2 * PLANE_BYTES, wf, acc);
+        plane_step<2, false, MODE, RELU, FULL, KD>(c, 2, lane, lbase + 2 * PLANE_BYTES, wf, acc);
         SP3D_STEP_END();
         // steps 3, 4, 5, 6, 7, ...: planes mod 4 = 3, 0, 1, 2, 3, ...
 #define SP3D_MAIN_STEP(OFF, PHASE)                                                                   \
     if (D + (OFF) < nplanes) {                                                                       \
-        plane_step<PHASE, true, MODE, RELU, FULL>(c, D + (OFF), lane, lbase + (PHASE) * PLANE_BYTES, wf, acc); \
+        plane_step<PHASE, true, MODE, RELU, FULL, KD>(c, D + (OFF), lane, lbase + (PHASE) * PLANE_BYTES, wf, acc); \
         SP3D_STEP_END();                                                                             \
     }
         for (int D = 3; D < nplanes; D += 4) {
@@ -540,7 +555,7 @@ __device__ __forceinline__ void give_unit(const f32x16 (&s)[RH], char *red, int 
 // ROLE 1 (chunk 1): GIVE = plane Dp - 3 (slot (P + 2) mod 5) goes to the hand-over buffer Dp & 1 and its
 // slot is cleared.  ROLE 0 (chunk 0): FIN = plane Dp - 4 (slot (P + 1) mod 5) is finished from the buffer
 // written in the previous step, (Dp - 1) & 1, and its slot returns to the bias.
-template <int P, int ROLE, bool GIVE, bool FIN, int MODE, int RELU, bool FULL, bool HAS_BIAS>
+template <int P, int ROLE, bool GIVE, bool FIN, int MODE, int RELU, bool FULL, int KD, bool HAS_BIAS>
 __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const char *lbase,
                                            const bf16x8 (&wf)[NFRAG], f32x16 (&acc)[NSLOT][RH]) {
     constexpr int NR = RH + 2;
@@ -607,13 +622,14 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const
                 if (h < 0 || h >= RH) continue;
 #pragma unroll
                 for (int kd = 0; kd < 3; ++kd) {
+                    if (KD == 1 && kd != 1) continue;
                     const int slot = (P - kd + NSLOT) % NSLOT;
                     acc[slot][h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                         wf[((kd * 3 + kh) * 3 + kw) * 2 + half], b[gi & 1][r], acc[slot][h], 0, 0, 0);
                 }
             }
 #pragma unroll
-        for (int i = 0; i < 3 * (RH + 1) * 2; ++i) {
+        for (int i = 0; i < KD * (RH + 1) * 2; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
             __builtin_amdgcn_sched_group_barrier(0x006, 3, 0);   // up to three VALU / SALU
             if (i % 6 == 2) __builtin_amdgcn_sched_group_barrier(0x060, 1, 0);   // a vector memory op
@@ -660,7 +676,7 @@ __device__ __forceinline__ void drain_step(const Ctx<HAS_BIAS> &c, int Dp, f32x1
     }
 }
 
-template <int ROLE, int MODE, bool HAS_BIAS, int RELU>
+template <int ROLE, int MODE, bool HAS_BIAS, int RELU, int KD>
 __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int tile, const TileBox &bx, int d0, int h0, int w0,
                                     int dn, int cj, int rg) {
     const Geo &g = a.g;
@@ -672,6 +688,7 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int tile, cons
         const uint4 *wp = a.wpack + static_cast<size_t>(ROLE) * a.nco * NFRAG * 64;     // chunk ROLE of the pair
 #pragma unroll
         for (int f = 0; f < NFRAG; ++f) {
+            if (KD == 1 && f / 18 != 1) continue;
             const uint4 q = wp[(cj * NFRAG + f) * 64 + lane];
             wf[f] = *reinterpret_cast<const bf16x8 *>(&q);
         }
@@ -738,18 +755,18 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int tile, cons
 
     auto march = [&](auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
-        plane_step<0, ROLE, false, false, MODE, RELU, FULL>(c, 0, lbase, wf, acc);
+        plane_step<0, ROLE, false, false, MODE, RELU, FULL, KD>(c, 0, lbase, wf, acc);
         SP3D_STEP_END();
-        plane_step<1, ROLE, false, false, MODE, RELU, FULL>(c, 1, lbase + PLANE_BYTES, wf, acc);
+        plane_step<1, ROLE, false, false, MODE, RELU, FULL, KD>(c, 1, lbase + PLANE_BYTES, wf, acc);
         SP3D_STEP_END();
-        plane_step<2, ROLE, false, false, MODE, RELU, FULL>(c, 2, lbase + 2 * PLANE_BYTES, wf, acc);
+        plane_step<2, ROLE, false, false, MODE, RELU, FULL, KD>(c, 2, lbase + 2 * PLANE_BYTES, wf, acc);
         SP3D_STEP_END();
         // Steps 3, 4, ... with slot phase Dp mod 5 as a compile-time constant (the ring slot Dp mod 4 is a
         // run-time offset: a period of 20 steps would be needed to make both constants).  The march runs two
         // steps past the last input plane; those only hand over / finish what is left.
 #define SP3D_STEP(DP, PHASE, GIVE_EN, FIN_EN)                                                              \
     if ((DP) < nplanes) {                                                                                  \
-        plane_step<PHASE, ROLE, GIVE_EN, FIN_EN, MODE, RELU, FULL>(c, (DP), lbase + ((DP) % NBUF) * PLANE_BYTES, \
+        plane_step<PHASE, ROLE, GIVE_EN, FIN_EN, MODE, RELU, FULL, KD>(c, (DP), lbase + ((DP) % NBUF) * PLANE_BYTES, \
                                                                    wf, acc);                              \
         SP3D_STEP_END();                                                                                   \
     } else if ((DP) < nplanes + 2) {                                                                       \
@@ -772,7 +789,7 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int tile, cons
 #undef SP3D_STEP_END
 }
 
-template <int MODE, bool HAS_BIAS, int RELU>
+template <int MODE, bool HAS_BIAS, int RELU, int KD>
 __global__ __launch_bounds__(kThreads, 1) void conv_mfma_pair_kernel(ConvArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const Geo &g = a.g;
@@ -791,8 +808,8 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_pair_kernel(ConvArgs a)
     if (dn <= 0 || h0 >= bx.bh || w0 >= bx.bw) return;     // patch of the largest box that this tile's box lacks
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // two copies of the march, one per role, so that each is straight-line code for the scheduler
-    if (wave < 2) run<0, MODE, HAS_BIAS, RELU>(a, lds, tile, bx, d0, h0, w0, dn, cj, wave & 1);
-    else run<1, MODE, HAS_BIAS, RELU>(a, lds, tile, bx, d0, h0, w0, dn, cj, wave & 1);
+    if (wave < 2) run<0, MODE, HAS_BIAS, RELU, KD>(a, lds, tile, bx, d0, h0, w0, dn, cj, wave & 1);
+    else run<1, MODE, HAS_BIAS, RELU, KD>(a, lds, tile, bx, d0, h0, w0, dn, cj, wave & 1);
 }
 
 }  // namespace wide
@@ -824,7 +841,7 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
     const int nci = ki / C, nco = ko / C;
     const int pack_elems = nci * nco * NFRAG * 64 * 8;
     hipLaunchKernelGGL(pack_weights_kernel, dim3((pack_elems + 255) / 256), dim3(256), 0, s,
-                       static_cast<const uint16_t *>(w), static_cast<uint16_t *>(ws), ki, ko, dgrad ? 1 : 0);
+                       static_cast<const uint16_t *>(w), static_cast<uint16_t *>(ws), ki, ko, dgrad ? 1 : 0, g.flat);
     int rc = record_hip(hipGetLastError());
     if (rc != SP_OK) return rc;
     ConvArgs a;
@@ -863,7 +880,7 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
     const bool pairs = ki % (2 * C) == 0;
     const int ph = pairs ? wide::PH : PH;
     // patches cover the largest output box of the grid (the interior grown on both sides)
-    const int ed = g.td + 2 * g.grow, eh = g.th + 2 * g.grow, ew = g.tw + 2 * g.grow;
+    const int ed = g.td + 2 * grow_d(g), eh = g.th + 2 * g.grow, ew = g.tw + 2 * g.grow;
     a.nh = (eh + ph - 1) / ph;
     a.nw = (ew + PW - 1) / PW;
     // D chunk: whole box depth unless that leaves the chip short of workgroups
@@ -879,26 +896,28 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
     using Kern = void (*)(ConvArgs);
     // [mode][bias][epilogue]; combinations that cannot occur (bias after the first launch, ReLU or mask before
     // the last, bias together with a mask) reuse the plain variant
-#define SP3D_TABLE(K)                                                                                      \
-    {{{K<kSingle, false, kNone>, K<kSingle, false, kRelu>, K<kSingle, false, kMask>},                        \
-      {K<kSingle, true, kNone>, K<kSingle, true, kRelu>, K<kSingle, false, kMask>}},                         \
-     {{K<kFirst, false, kNone>, K<kFirst, false, kNone>, K<kFirst, false, kNone>},                           \
-      {K<kFirst, true, kNone>, K<kFirst, true, kNone>, K<kFirst, true, kNone>}},                             \
-     {{K<kMiddle, false, kNone>, K<kMiddle, false, kNone>, K<kMiddle, false, kNone>},                        \
-      {K<kMiddle, false, kNone>, K<kMiddle, false, kNone>, K<kMiddle, false, kNone>}},                       \
-     {{K<kLast, false, kNone>, K<kLast, false, kRelu>, K<kLast, false, kMask>},                              \
-      {K<kLast, false, kNone>, K<kLast, false, kRelu>, K<kLast, false, kMask>}}}
-    static const Kern kern[4][2][3] = SP3D_TABLE(conv_mfma_kernel);
-    static const Kern kern2[4][2][3] = SP3D_TABLE(wide::conv_mfma_pair_kernel);
+#define SP3D_TABLE(K, KD)                                                                                  \
+    {{{K<kSingle, false, kNone, KD>, K<kSingle, false, kRelu, KD>, K<kSingle, false, kMask, KD>},            \
+      {K<kSingle, true, kNone, KD>, K<kSingle, true, kRelu, KD>, K<kSingle, false, kMask, KD>}},             \
+     {{K<kFirst, false, kNone, KD>, K<kFirst, false, kNone, KD>, K<kFirst, false, kNone, KD>},               \
+      {K<kFirst, true, kNone, KD>, K<kFirst, true, kNone, KD>, K<kFirst, true, kNone, KD>}},                 \
+     {{K<kMiddle, false, kNone, KD>, K<kMiddle, false, kNone, KD>, K<kMiddle, false, kNone, KD>},            \
+      {K<kMiddle, false, kNone, KD>, K<kMiddle, false, kNone, KD>, K<kMiddle, false, kNone, KD>}},           \
+     {{K<kLast, false, kNone, KD>, K<kLast, false, kRelu, KD>, K<kLast, false, kMask, KD>},                  \
+      {K<kLast, false, kNone, KD>, K<kLast, false, kRelu, KD>, K<kLast, false, kMask, KD>}}}
+    // [2-D variant][mode][bias][epilogue]
+    static const Kern kern[2][4][2][3] = {SP3D_TABLE(conv_mfma_kernel, 3), SP3D_TABLE(conv_mfma_kernel, 1)};
+    static const Kern kern2[2][4][2][3] = {SP3D_TABLE(wide::conv_mfma_pair_kernel, 3),
+                                           SP3D_TABLE(wide::conv_mfma_pair_kernel, 1)};
 #undef SP3D_TABLE
     const int epi = mask ? kMask : (relu ? kRelu : kNone);
     // more than 64 KB of dynamic LDS has to be requested explicitly
     static const hipError_t attr = [] {
-        for (int i = 0; i < 24; ++i) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern[i / 6][(i / 3) & 1][i % 3]),
+        for (int i = 0; i < 48; ++i) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern[i / 24][(i / 6) & 3][(i / 3) & 1][i % 3]),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
             if (e != hipSuccess) return e;
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern2[i / 6][(i / 3) & 1][i % 3]),
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern2[i / 24][(i / 6) & 3][(i / 3) & 1][i % 3]),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, wide::LDS_BYTES);
             if (e != hipSuccess) return e;
         }
@@ -912,9 +931,9 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
         if (pairs) chunk_src(2 * ci + 1, &a.in2, &a.in2_cs, &a.in2_co);
         a.wpack = static_cast<const uint4 *>(ws) + static_cast<size_t>(pairs ? 2 * ci : ci) * nco * NFRAG * 64;
         if (pairs)
-            hipLaunchKernelGGL(kern2[mode][bias ? 1 : 0][epi], dim3(grid), dim3(kThreads), wide::LDS_BYTES, s, a);
+            hipLaunchKernelGGL(kern2[g.flat][mode][bias ? 1 : 0][epi], dim3(grid), dim3(kThreads), wide::LDS_BYTES, s, a);
         else
-            hipLaunchKernelGGL(kern[mode][bias ? 1 : 0][epi], dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
+            hipLaunchKernelGGL(kern[g.flat][mode][bias ? 1 : 0][epi], dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
         rc = record_hip(hipGetLastError());
         if (rc != SP_OK) return rc;
     }

@@ -64,46 +64,56 @@ __device__ __forceinline__ long long pidx(const Geo &g, unsigned tile, unsigned 
     return tile * g.tile_vox + (1LL * (ld + 1) * g.ph + lh + 1) * g.pw + lw + 1;
 }
 
+// Fine-tensor position k of the window that belongs to coarse voxel o: 2x2x2 windows, k = 4a + 2b + c for
+// offset (a, b, c); in the 2-D variant (g.flat) 1x2x2 windows inside the voxel's own slice, k = 2b + c.
+template <int NW>
+__device__ __forceinline__ long long wpos(const Geo &gf, const Vox &o, int k) {
+    if (NW == 4) return pidx(gf, o.tile, o.ld, 2 * o.lh + ((k >> 1) & 1), 2 * o.lw + (k & 1));
+    return pidx(gf, o.tile, 2 * o.ld + (k >> 2), 2 * o.lh + ((k >> 1) & 1), 2 * o.lw + (k & 1));
+}
+__device__ __forceinline__ long long wpos(const Geo &gf, const Vox &o, int k) {
+    return gf.flat ? wpos<4>(gf, o, k) : wpos<8>(gf, o, k);
+}
+
 // ---- max pooling -------------------------------------------------------------------------------
-// One thread per (coarse voxel, channel).  Forward: y = max of the 8 window values.  Backward: dx of
-// the FIRST maximum in (d,h,w) scan order receives dy, the other seven receive 0.
+// One thread per (coarse voxel, channel).  Forward: y = max of the NW window values (8, or 4 in the 2-D
+// variant).  Backward: dx of the FIRST maximum in (d,h,w) scan order receives dy, the others receive 0.
 // MODE kPoolBwdJoin: the backward pass of an encoder level in one sweep.  The pooled tensor x is also the
 // level's ReLU output that the decoder took as its skip input, so the gradient that reaches the level's last
 // convolution is  dz = [x > 0] * (maxpool_bwd(x, dy) + skip_grad);  `skip` may be the same tensor as `out`
 // (a thread reads its eight positions before it writes them).  The sum is taken in fp32 and rounded once,
 // as sp_add does.
 enum PoolMode { kPoolFwd = 0, kPoolBwd = 1, kPoolBwdJoin = 2 };
-template <typename E, int MODE>
+template <typename E, int MODE, int NW>
 __global__ __launch_bounds__(kThreads) void maxpool2_kernel(const E *__restrict__ x, const E *__restrict__ dy,
                                                             const E *skip, E *out, Geo gf, Geo gc, Lay l, int C) {
     const unsigned v = blockIdx.x * (kThreads >> l.cshift) + (threadIdx.x >> l.cshift);
     if (v >= l.nvox) return;
     const Vox o = decode(v, l);
     const long long pc = pidx(gc, o.tile, o.ld, o.lh, o.lw);
-    long long pf[8];
+    long long pf[NW];
 #pragma unroll
-    for (int k = 0; k < 8; ++k)
-        pf[k] = pidx(gf, o.tile, 2 * o.ld + (k >> 2), 2 * o.lh + ((k >> 1) & 1), 2 * o.lw + (k & 1));
+    for (int k = 0; k < NW; ++k) pf[k] = wpos<NW>(gf, o, k);
     for (int c = threadIdx.x & (l.cw - 1); c < C; c += l.cw) {
-        float xv[8];
+        float xv[NW];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) xv[k] = ldf<E>(x, pf[k] * C + c);
+        for (int k = 0; k < NW; ++k) xv[k] = ldf<E>(x, pf[k] * C + c);
         float best = xv[0];
         int arg = 0;
 #pragma unroll
-        for (int k = 1; k < 8; ++k)
+        for (int k = 1; k < NW; ++k)
             if (xv[k] > best) { best = xv[k]; arg = k; }
         if (MODE == kPoolBwd) {
             const E g = dy[pc * C + c];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) out[pf[k] * C + c] = k == arg ? g : E(0);
+            for (int k = 0; k < NW; ++k) out[pf[k] * C + c] = k == arg ? g : E(0);
         } else if (MODE == kPoolBwdJoin) {
             const float g = ldf<E>(dy, pc * C + c);
-            float sk[8];
+            float sk[NW];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) sk[k] = ldf<E>(skip, pf[k] * C + c);
+            for (int k = 0; k < NW; ++k) sk[k] = ldf<E>(skip, pf[k] * C + c);
 #pragma unroll
-            for (int k = 0; k < 8; ++k) stf<E>(out, pf[k] * C + c, xv[k] > 0.f ? (k == arg ? g : 0.f) + sk[k] : 0.f);
+            for (int k = 0; k < NW; ++k) stf<E>(out, pf[k] * C + c, xv[k] > 0.f ? (k == arg ? g : 0.f) + sk[k] : 0.f);
         } else {
             stf<E>(out, pc * C + c, best);
         }
@@ -113,7 +123,7 @@ __global__ __launch_bounds__(kThreads) void maxpool2_kernel(const E *__restrict_
 // The same three operations for bf16 tensors whose channel count is a multiple of 8: a thread owns 8 channels
 // (16 bytes) of a coarse voxel, so every access is a full 16-byte piece and C / 8 consecutive lanes cover a
 // voxel record back to back.  Comparisons and the sum are taken on the widened values exactly as above.
-template <int MODE>
+template <int MODE, int NW>
 __global__ __launch_bounds__(kThreads) void maxpool2_x8_kernel(const uint16_t *__restrict__ x,
                                                                const uint16_t *__restrict__ dy, const uint16_t *skip,
                                                                uint16_t *out, Geo gf, Geo gc, Lay l, int C) {
@@ -121,10 +131,9 @@ __global__ __launch_bounds__(kThreads) void maxpool2_x8_kernel(const uint16_t *_
     if (v >= l.nvox) return;
     const Vox o = decode(v, l);
     const long long pc = pidx(gc, o.tile, o.ld, o.lh, o.lw);
-    long long pf[8];
+    long long pf[NW];
 #pragma unroll
-    for (int k = 0; k < 8; ++k)
-        pf[k] = pidx(gf, o.tile, 2 * o.ld + (k >> 2), 2 * o.lh + ((k >> 1) & 1), 2 * o.lw + (k & 1));
+    for (int k = 0; k < NW; ++k) pf[k] = wpos<NW>(gf, o, k);
     auto widen8 = [](const uint4 &q, float (&f)[8]) {
         const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
@@ -141,9 +150,9 @@ __global__ __launch_bounds__(kThreads) void maxpool2_x8_kernel(const uint16_t *_
         return make_uint4(w[0], w[1], w[2], w[3]);
     };
     for (int cg = threadIdx.x & (l.cw - 1); 8 * cg < C; cg += l.cw) {
-        float xv[8][8];
+        float xv[NW][8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) widen8(*reinterpret_cast<const uint4 *>(x + pf[k] * C + 8 * cg), xv[k]);
+        for (int k = 0; k < NW; ++k) widen8(*reinterpret_cast<const uint4 *>(x + pf[k] * C + 8 * cg), xv[k]);
         float best[8];
         int arg[8];
 #pragma unroll
@@ -151,7 +160,7 @@ __global__ __launch_bounds__(kThreads) void maxpool2_x8_kernel(const uint16_t *_
             best[e] = xv[0][e];
             arg[e] = 0;
 #pragma unroll
-            for (int k = 1; k < 8; ++k)
+            for (int k = 1; k < NW; ++k)
                 if (xv[k][e] > best[e]) { best[e] = xv[k][e]; arg[e] = k; }
         }
         if (MODE == kPoolFwd) {
@@ -160,13 +169,13 @@ __global__ __launch_bounds__(kThreads) void maxpool2_x8_kernel(const uint16_t *_
         }
         float g[8];
         widen8(*reinterpret_cast<const uint4 *>(dy + pc * C + 8 * cg), g);
-        uint4 sk[8];
+        uint4 sk[NW];
         if (MODE == kPoolBwdJoin) {
 #pragma unroll
-            for (int k = 0; k < 8; ++k) sk[k] = *reinterpret_cast<const uint4 *>(skip + pf[k] * C + 8 * cg);
+            for (int k = 0; k < NW; ++k) sk[k] = *reinterpret_cast<const uint4 *>(skip + pf[k] * C + 8 * cg);
         }
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
+        for (int k = 0; k < NW; ++k) {
             float r[8];
             if (MODE == kPoolBwdJoin) {
                 float s8[8];
@@ -191,8 +200,8 @@ __global__ __launch_bounds__(kThreads) void upconv2_fwd_kernel(const E *__restri
     const unsigned v = blockIdx.x * (kThreads >> l.cshift) + (threadIdx.x >> l.cshift);
     if (v >= l.nvox) return;
     const Vox o = decode(v, l);                                     // fine voxel
-    const int k = ((o.ld & 1) << 2) | ((o.lh & 1) << 1) | (o.lw & 1);
-    const E *xin = x + pidx(gc, o.tile, o.ld >> 1, o.lh >> 1, o.lw >> 1) * cin;
+    const int k = (gf.flat ? 0 : (o.ld & 1) << 2) | ((o.lh & 1) << 1) | (o.lw & 1);
+    const E *xin = x + pidx(gc, o.tile, gf.flat ? o.ld : o.ld >> 1, o.lh >> 1, o.lw >> 1) * cin;
     const E *uk = u + 1LL * k * cin * cout;
     const long long po = pidx(gf, o.tile, o.ld, o.lh, o.lw);
     for (int co = threadIdx.x & (l.cw - 1); co < cout; co += l.cw) {
@@ -213,8 +222,8 @@ __global__ __launch_bounds__(kThreads) void upconv2_dgrad_kernel(const E *__rest
     const long long po = pidx(gc, o.tile, o.ld, o.lh, o.lw);
     for (int ci = threadIdx.x & (l.cw - 1); ci < cin; ci += l.cw) {
         float acc = 0.f;
-        for (int k = 0; k < 8; ++k) {
-            const E *g = dy + pidx(gf, o.tile, 2 * o.ld + (k >> 2), 2 * o.lh + ((k >> 1) & 1), 2 * o.lw + (k & 1)) * cout;
+        for (int k = 0; k < (gf.flat ? 4 : 8); ++k) {
+            const E *g = dy + wpos(gf, o, k) * cout;
             const E *uk = u + (1LL * k * cin + ci) * cout;
             for (int co = 0; co < cout; ++co) acc = fmaf(ldf<E>(g, co), ldf<E>(uk, co), acc);
         }
@@ -234,10 +243,8 @@ __global__ __launch_bounds__(kThreads) void upconv2_dgrad_bf16x8_kernel(const ui
     const long long po = pidx(gc, o.tile, o.ld, o.lh, o.lw);
     for (int ci = threadIdx.x & (l.cw - 1); ci < cin; ci += l.cw) {
         float acc = 0.f;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const uint4 *g = reinterpret_cast<const uint4 *>(
-                dy + pidx(gf, o.tile, 2 * o.ld + (k >> 2), 2 * o.lh + ((k >> 1) & 1), 2 * o.lw + (k & 1)) * cout);
+        for (int k = 0; k < (gf.flat ? 4 : 8); ++k) {
+            const uint4 *g = reinterpret_cast<const uint4 *>(dy + wpos(gf, o, k) * cout);
             const uint4 *uk = reinterpret_cast<const uint4 *>(u + (1LL * k * cin + ci) * cout);
             for (int c8 = 0; c8 < cout / 8; ++c8) {
                 const uint4 a = g[c8], b = uk[c8];
@@ -272,7 +279,7 @@ __global__ __launch_bounds__(kThreads) void upconv2_wgrad_kernel(const E *__rest
         for (unsigned v = chunk * chunk_vox + vl; v < v1; v += nvl) {
             const Vox o = decode(v, l);                             // coarse voxel
             const long long px = pidx(gc, o.tile, o.ld, o.lh, o.lw);
-            const long long pz = pidx(gf, o.tile, 2 * o.ld + (k >> 2), 2 * o.lh + ((k >> 1) & 1), 2 * o.lw + (k & 1));
+            const long long pz = wpos(gf, o, k);
             acc = fmaf(ldf<E>(x, px * cin + ci), ldf<E>(dy, pz * cout + co), acc);
         }
     }
@@ -281,7 +288,7 @@ __global__ __launch_bounds__(kThreads) void upconv2_wgrad_kernel(const E *__rest
     if (vl == 0 && co < cout) {
         float s = 0.f;
         for (int i = 0; i < nvl; ++i) s += red[i * cw + col];
-        part[(1LL * chunk * 8 * cin + kci) * cout + co] = s;
+        part[(1LL * chunk * gridDim.x + kci) * cout + co] = s;
     }
 }
 
@@ -297,6 +304,7 @@ __global__ __launch_bounds__(kThreads) void upconv2_wgrad_bf16x8_kernel(const ui
     const int ci = blockIdx.x * (kThreads >> co8_shift) + (threadIdx.x >> co8_shift);
     const int chunk = blockIdx.y;
     if (ci >= cin) return;
+    const int nk = gf.flat ? 4 : 8;          // window positions
     float acc[8][8];
 #pragma unroll
     for (int k = 0; k < 8; ++k)
@@ -309,21 +317,24 @@ __global__ __launch_bounds__(kThreads) void upconv2_wgrad_bf16x8_kernel(const ui
         const float xv = bf16_to_f32(x[pidx(gc, o.tile, o.ld, o.lh, o.lw) * cin + ci]);
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-            const uint4 g = *reinterpret_cast<const uint4 *>(
-                dy + pidx(gf, o.tile, 2 * o.ld + (k >> 2), 2 * o.lh + ((k >> 1) & 1), 2 * o.lw + (k & 1)) * cout + 8 * co8);
-            const uint32_t gw[4] = {g.x, g.y, g.z, g.w};
+            if (k < nk) {
+                const uint4 g = *reinterpret_cast<const uint4 *>(dy + wpos(gf, o, k) * cout + 8 * co8);
+                const uint32_t gw[4] = {g.x, g.y, g.z, g.w};
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                acc[k][2 * e] = fmaf(xv, __uint_as_float(gw[e] << 16), acc[k][2 * e]);
-                acc[k][2 * e + 1] = fmaf(xv, __uint_as_float(gw[e] & 0xffff0000u), acc[k][2 * e + 1]);
+                for (int e = 0; e < 4; ++e) {
+                    acc[k][2 * e] = fmaf(xv, __uint_as_float(gw[e] << 16), acc[k][2 * e]);
+                    acc[k][2 * e + 1] = fmaf(xv, __uint_as_float(gw[e] & 0xffff0000u), acc[k][2 * e + 1]);
+                }
             }
         }
     }
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-        float *p = part + ((1LL * chunk * 8 + k) * cin + ci) * cout + 8 * co8;
-        *reinterpret_cast<float4 *>(p) = make_float4(acc[k][0], acc[k][1], acc[k][2], acc[k][3]);
-        *reinterpret_cast<float4 *>(p + 4) = make_float4(acc[k][4], acc[k][5], acc[k][6], acc[k][7]);
+        if (k < nk) {
+            float *p = part + ((1LL * chunk * nk + k) * cin + ci) * cout + 8 * co8;
+            *reinterpret_cast<float4 *>(p) = make_float4(acc[k][0], acc[k][1], acc[k][2], acc[k][3]);
+            *reinterpret_cast<float4 *>(p + 4) = make_float4(acc[k][4], acc[k][5], acc[k][6], acc[k][7]);
+        }
     }
 }
 
@@ -578,10 +589,10 @@ void reduction_plan(unsigned nvox, int *nchunks, unsigned *chunk_vox) {
 }  // namespace
 
 int make_coarse(const Geo &gf, Geo *gc) {
-    if ((gf.td | gf.th | gf.tw) & 1) return SP_EGEOM;
+    if (((gf.flat ? 0 : gf.td) | gf.th | gf.tw) & 1) return SP_EGEOM;
     Geo o = gf;
-    o.td = gf.td / 2; o.th = gf.th / 2; o.tw = gf.tw / 2;
-    if (o.td < o.halo || o.th < o.halo || o.tw < o.halo) return SP_EGEOM;
+    o.td = gf.flat ? gf.td : gf.td / 2; o.th = gf.th / 2; o.tw = gf.tw / 2;
+    if ((!o.flat && o.td < o.halo) || o.th < o.halo || o.tw < o.halo) return SP_EGEOM;
     o.pd = o.td + 2 * o.halo; o.ph = o.th + 2 * o.halo; o.pw = o.tw + 2 * o.halo;
     o.tile_vox = 1LL * o.pd * o.ph * o.pw;
     o.int_vox = 1LL * o.td * o.th * o.tw;
@@ -599,26 +610,30 @@ int launch_maxpool2(const void *Px, const void *Pdy, void *Pout, const Geo &gf, 
         const Lay l = make_lay(gc, c / 8);
         const unsigned vpb = kThreads >> l.cshift;
         dim3 grid((l.nvox + vpb - 1) / vpb), block(kThreads);
-#define SP3D_POOL8(M)                                                                                     \
-    hipLaunchKernelGGL(maxpool2_x8_kernel<M>, grid, block, 0, s, static_cast<const uint16_t *>(Px),       \
+#define SP3D_POOL8N(M, NW)                                                                                \
+    hipLaunchKernelGGL((maxpool2_x8_kernel<M, NW>), grid, block, 0, s, static_cast<const uint16_t *>(Px), \
                        static_cast<const uint16_t *>(Pdy), static_cast<const uint16_t *>(Pskip),          \
                        static_cast<uint16_t *>(Pout), gf, gc, l, c)
+#define SP3D_POOL8(M) do { if (gf.flat) SP3D_POOL8N(M, 4); else SP3D_POOL8N(M, 8); } while (0)
         if (backward && Pskip) SP3D_POOL8(kPoolBwdJoin);
         else if (backward) SP3D_POOL8(kPoolBwd);
         else SP3D_POOL8(kPoolFwd);
 #undef SP3D_POOL8
+#undef SP3D_POOL8N
         return record_hip(hipGetLastError());
     }
     const Lay l = make_lay(gc, c);
     const unsigned vpb = kThreads >> l.cshift;
     dim3 grid((l.nvox + vpb - 1) / vpb), block(kThreads);
-#define SP3D_POOL(E, B)                                                                              \
-    hipLaunchKernelGGL((maxpool2_kernel<E, B>), grid, block, 0, s, static_cast<const E *>(Px),       \
+#define SP3D_POOLN(E, B, NW)                                                                         \
+    hipLaunchKernelGGL((maxpool2_kernel<E, B, NW>), grid, block, 0, s, static_cast<const E *>(Px),   \
                        static_cast<const E *>(Pdy), static_cast<const E *>(Pskip), static_cast<E *>(Pout), gf, gc, l, c)
+#define SP3D_POOL(E, B) do { if (gf.flat) SP3D_POOLN(E, B, 4); else SP3D_POOLN(E, B, 8); } while (0)
     if (backward && Pskip) SP3D_BY_DTYPE(SP3D_POOL(uint16_t, kPoolBwdJoin), SP3D_POOL(float, kPoolBwdJoin));
     else if (backward) SP3D_BY_DTYPE(SP3D_POOL(uint16_t, kPoolBwd), SP3D_POOL(float, kPoolBwd));
     else SP3D_BY_DTYPE(SP3D_POOL(uint16_t, kPoolFwd), SP3D_POOL(float, kPoolFwd));
 #undef SP3D_POOL
+#undef SP3D_POOLN
     return record_hip(hipGetLastError());
 }
 
@@ -662,8 +677,8 @@ size_t upconv2_wgrad_ws_bytes(const Geo &gf, const Geo &gc, int cin, int cout, s
     int ncw; unsigned cvw;
     upconv_wgrad_plan(static_cast<unsigned>(1LL * gc.ntiles * gc.int_vox), cin, cout, &ncw, &cvw);
     int ncb; unsigned cvb;
-    reduction_plan(static_cast<unsigned>(8LL * gc.ntiles * gc.int_vox), &ncb, &cvb);
-    return (static_cast<size_t>(ncw) * 8 * cin * cout + static_cast<size_t>(ncb) * cout) * sizeof(float);
+    reduction_plan(static_cast<unsigned>(1LL * gf.ntiles * gf.int_vox), &ncb, &cvb);
+    return (static_cast<size_t>(ncw) * (gf.flat ? 4 : 8) * cin * cout + static_cast<size_t>(ncb) * cout) * sizeof(float);
 }
 
 int launch_upconv2_wgrad(const void *Px, const void *Pdy, float *du, float *db, const Geo &gf, const Geo &gc,
@@ -676,10 +691,11 @@ int launch_upconv2_wgrad(const void *Px, const void *Pdy, float *du, float *db, 
     upconv_wgrad_plan(lc.nvox, cin, cout, &ncw, &cvw);
     reduction_plan(lf.nvox, &ncb, &cvb);
     float *part_w = static_cast<float *>(ws);
-    float *part_b = part_w + static_cast<size_t>(ncw) * 8 * cin * cout;
+    const int nk = gf.flat ? 4 : 8;          // window positions = taps of u
+    float *part_b = part_w + static_cast<size_t>(ncw) * nk * cin * cout;
     const int cw = cout < kThreads ? cout : kThreads;
     const int zg = (cout + cw - 1) / cw;
-    dim3 block(kThreads), gw_(8 * cin, ncw, zg), gb_(1, ncb, zg);
+    dim3 block(kThreads), gw_(nk * cin, ncw, zg), gb_(1, ncb, zg);
     int co8_shift = -1;
     if (dt == SP_BF16 && cout % 8 == 0 && cout <= 8 * kThreads && ((cout / 8) & (cout / 8 - 1)) == 0) {
         co8_shift = 0;
@@ -695,7 +711,7 @@ int launch_upconv2_wgrad(const void *Px, const void *Pdy, float *du, float *db, 
                                gf, lf, cout, cw, cvb);
         int rc2 = record_hip(hipGetLastError());
         if (rc2 != SP_OK) return rc2;
-        rc2 = launch_reduce_partials(part_w, du, ncw, 8LL * cin * cout, s);
+        rc2 = launch_reduce_partials(part_w, du, ncw, 1LL * nk * cin * cout, s);
         if (rc2 != SP_OK) return rc2;
         if (db) rc2 = launch_reduce_partials(part_b, db, ncb, cout, s);
         return rc2;
@@ -712,7 +728,7 @@ int launch_upconv2_wgrad(const void *Px, const void *Pdy, float *du, float *db, 
 #undef SP3D_UPW
     int rc = record_hip(hipGetLastError());
     if (rc != SP_OK) return rc;
-    rc = launch_reduce_partials(part_w, du, ncw, 8LL * cin * cout, s);
+    rc = launch_reduce_partials(part_w, du, ncw, 1LL * nk * cin * cout, s);
     if (rc != SP_OK) return rc;
     if (db) rc = launch_reduce_partials(part_b, db, ncb, cout, s);
     return rc;

@@ -200,6 +200,8 @@ int halo_dispatch(const void *src, void *dst, HaloArgs &a, int mode, hipStream_t
         if (nvec > 0xffffff00LL) return SP_EGEOM;
         a.ehw[i] = make_fastdiv(static_cast<uint32_t>(a.t.r[i].ext[1]) * a.t.r[i].ext[2]);
         a.ew[i] = make_fastdiv(a.t.r[i].ext[2]);
+        // 2-D variant: slices do not interact, the regions above and below a tile are not moved
+        if (a.g.flat && a.t.r[i].delta[0] != 0) continue;
         acc += static_cast<int>((nvec + kHaloChunk - 1) / kHaloChunk);
     }
     a.blk_prefix[26] = acc;

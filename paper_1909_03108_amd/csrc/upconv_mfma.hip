@@ -13,6 +13,8 @@
 // every 32-voxel segment.  The result lane layout - lane l holds voxel l % 32 and channels
 // 8*(i/4) + 4*(l/32) + i%4 - gives 8-byte stores.  Both kernels are bound by HBM traffic, not by the
 // matrix cores; a workgroup is persistent and its 8 waves walk over segments independently.
+// 2-D variant (geometry flag `flat`): 1x2x2 windows, 4 taps t = (b, c), u[4][cin][cout]; the fine voxel of
+// tap t lies in the coarse voxel's own slice.
 #include "common.h"
 
 namespace sp3d {
@@ -41,6 +43,7 @@ struct UpArgs {
     int wpb;                 // workgroups per channel block
     int nseg;                // segments per coarse W row
     int nitems;              // segments in total
+    int ntap;                // window positions: 8, or 4 in the 2-D variant
 };
 
 __device__ __forceinline__ uint32_t pack2(float a, float b) {
@@ -64,6 +67,11 @@ __device__ __forceinline__ size_t pvox(const Geo &g, int tile, int d, int h, int
     return static_cast<size_t>(tile) * g.tile_vox + (static_cast<size_t>(d + 1) * g.ph + h + 1) * g.pw + w + 1;
 }
 
+// padded voxel index of the fine voxel that tap t of coarse voxel (d, h, w) produces
+__device__ __forceinline__ size_t fvox(const Geo &gf, int tile, int d, int h, int w, int tap) {
+    return pvox(gf, tile, gf.flat ? d : 2 * d + (tap >> 2), 2 * h + ((tap >> 1) & 1), 2 * w + (tap & 1));
+}
+
 // ---- forward -----------------------------------------------------------------------------------------
 // NKS = Cin / 16 reduction steps.  LDS: fragment (tap, ks) at (tap * NKS + ks) KB; lane l of it holds
 // u[tap][16 ks + 8 (l/32) + j][32 cb + l % 32], j = 0..7.
@@ -75,7 +83,7 @@ __global__ __launch_bounds__(kT) void upconv_fwd_mfma_kernel(UpArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     constexpr int CIN = 16 * NKS;
     // weights: 16-byte pieces (8 output channels of one (tap, ci)) scattered to the 8 lanes that own them
-    for (int e = tid; e < 8 * CIN * 4; e += kT) {
+    for (int e = tid; e < a.ntap * CIN * 4; e += kT) {
         const int c8 = e & 3, ci = (e >> 2) % CIN, tap = (e >> 2) / CIN;
         const uint4 v = *reinterpret_cast<const uint4 *>(a.u + (static_cast<size_t>(tap) * CIN + ci) * a.cout +
                                                          C * cb + 8 * c8);
@@ -117,7 +125,7 @@ __global__ __launch_bounds__(kT) void upconv_fwd_mfma_kernel(UpArgs a) {
         const int w = o.w0 + m;
         const bool ok = w < a.gc.tw;
 #pragma unroll 1
-        for (int tap = 0; tap < 8; ++tap) {
+        for (int tap = 0; tap < a.ntap; ++tap) {
             f32x16 acc;
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[i] = bv[i];
@@ -135,8 +143,7 @@ __global__ __launch_bounds__(kT) void upconv_fwd_mfma_kernel(UpArgs a) {
                 if (tap & 1) {
                     // both taps of this fine row are in the buffer (the LDS unit serves a wave's accesses in order)
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    uint16_t *prow = a.out + pvox(a.gf, o.tile, 2 * o.d + (tap >> 2), 2 * o.h + ((tap >> 1) & 1),
-                                                  2 * o.w0) * a.cout + C * cb + 8 * rp;
+                    uint16_t *prow = a.out + fvox(a.gf, o.tile, o.d, o.h, o.w0, tap & ~1) * a.cout + C * cb + 8 * rp;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const int fv = 16 * j + rv;                     // fine voxel of the 64
@@ -149,8 +156,7 @@ __global__ __launch_bounds__(kT) void upconv_fwd_mfma_kernel(UpArgs a) {
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
                 }
             } else if (ok) {
-                uint16_t *py = a.out + pvox(a.gf, o.tile, 2 * o.d + (tap >> 2), 2 * o.h + ((tap >> 1) & 1),
-                                            2 * w + (tap & 1)) * a.cout + C * cb + 4 * kh;
+                uint16_t *py = a.out + fvox(a.gf, o.tile, o.d, o.h, w, tap) * a.cout + C * cb + 4 * kh;
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
                     *reinterpret_cast<uint2 *>(py + 8 * q) = make_uint2(pack2(acc[4 * q], acc[4 * q + 1]),
@@ -185,6 +191,7 @@ __global__ __launch_bounds__(kT) void upconv_dgrad_mfma_kernel(UpArgs a) {
     for (int e = tid; e < GCI * 8 * NKS * 64; e += kT) {
         const int l = e & 63, f = e >> 6;
         const int ks = f % NKS, tap = (f / NKS) & 7, g = f / (8 * NKS);
+        if (tap >= a.ntap) continue;
         const int ci = C * (cg * GCI + g) + (l & 31);
         *reinterpret_cast<uint4 *>(lds + e * 16) = *reinterpret_cast<const uint4 *>(
             a.u + (static_cast<size_t>(tap) * a.cin + ci) * COUT + 16 * ks + 8 * (l >> 5));
@@ -205,8 +212,7 @@ __global__ __launch_bounds__(kT) void upconv_dgrad_mfma_kernel(UpArgs a) {
         // taps in pairs: the dy fragments of the next tap are in flight while the current one is multiplied
         bf16x8 b0[NKS], b1[NKS];
         auto fetch = [&](int tap, bf16x8 (&b)[NKS]) {
-            const uint16_t *pdy = a.in + pvox(a.gf, o.tile, 2 * o.d + (tap >> 2), 2 * o.h + ((tap >> 1) & 1),
-                                              2 * wl + (tap & 1)) * COUT + 8 * kh;
+            const uint16_t *pdy = a.in + fvox(a.gf, o.tile, o.d, o.h, wl, tap) * COUT + 8 * kh;
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks) b[ks] = *reinterpret_cast<const bf16x8 *>(pdy + 16 * ks);
         };
@@ -222,10 +228,10 @@ __global__ __launch_bounds__(kT) void upconv_dgrad_mfma_kernel(UpArgs a) {
         };
         fetch(0, b0);
 #pragma unroll 1
-        for (int tap = 0; tap < 8; tap += 2) {
+        for (int tap = 0; tap < a.ntap; tap += 2) {
             fetch(tap + 1, b1);
             compute(tap, b0);
-            if (tap + 2 < 8) fetch(tap + 2, b0);
+            if (tap + 2 < a.ntap) fetch(tap + 2, b0);
             compute(tap + 1, b1);
         }
         if (ok) {
@@ -260,6 +266,7 @@ struct UpWArgs {
     int nco;                 // output-channel blocks; channel group = (ci group) * nco + co block
     int ngroups, wpg;        // channel groups, workgroups per group
     int nseg, nitems;
+    int ntap;                // window positions: 8, or 4 in the 2-D variant (waves 4..7 then have no tap)
 };
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -305,6 +312,7 @@ __global__ __launch_bounds__(kT) void upconv_wgrad_mfma_kernel(UpWArgs a) {
     const int cg = group / a.nco, cb = group % a.nco;
     const int tid = threadIdx.x, lane = tid & 63;
     const int tap = __builtin_amdgcn_readfirstlane(tid >> 6);
+    if (tap >= a.ntap) return;                       // the waves never synchronise
     char *ring = lds + tap * (WG_NST * STAGE);
     // transposing-read address of this lane inside a 16-voxel group of records
     const int p16 = lane & 15;
@@ -332,8 +340,7 @@ __global__ __launch_bounds__(kT) void upconv_wgrad_mfma_kernel(UpWArgs a) {
             const uint16_t *px = a.x + pvox(a.gc, o.tile, o.d, o.h, w) * a.cin + C * cg * NCI + 8 * sc;
 #pragma unroll
             for (int b = 0; b < NCI; ++b) dma16_after_reads(px + C * b, dst + b * 2048 + q * 1024);
-            const uint16_t *pz = a.dy + pvox(a.gf, o.tile, 2 * o.d + (tap >> 2), 2 * o.h + ((tap >> 1) & 1),
-                                             2 * w + (tap & 1)) * a.cout + C * cb + 8 * sc;
+            const uint16_t *pz = a.dy + fvox(a.gf, o.tile, o.d, o.h, w, tap) * a.cout + C * cb + 8 * sc;
             dma16_after_reads(pz, dst + NCI * 2048 + q * 1024);
         }
     };
@@ -382,9 +389,9 @@ __global__ __launch_bounds__(kT) void upconv_wgrad_mfma_kernel(UpWArgs a) {
 __global__ __launch_bounds__(256) void upconv_wgrad_reduce_kernel(const float *__restrict__ part_w,
                                                                   const float *__restrict__ part_b,
                                                                   float *__restrict__ du, float *__restrict__ db,
-                                                                  int cin, int cout, int nci, int wpg) {
+                                                                  int cin, int cout, int nci, int wpg, int ntap) {
     const int e = blockIdx.x * 256 + threadIdx.x;
-    const int nw = 8 * cin * cout;
+    const int nw = ntap * cin * cout;
     const int nco = cout / C, gci = C * nci;
     if (e < nw) {
         const int co = e % cout, ci = (e / cout) % cin, tap = e / (cout * cin);
@@ -397,7 +404,8 @@ __global__ __launch_bounds__(256) void upconv_wgrad_reduce_kernel(const float *_
         const int co = e - nw;
         const float *p = part_b + static_cast<size_t>(co / C) * wpg * 8 * C + co % C;      // ci group 0
         float s = 0.f;
-        for (int k = 0; k < wpg * 8; ++k) s += p[k * C];
+        for (int k = 0; k < wpg; ++k)
+            for (int t = 0; t < ntap; ++t) s += p[(k * 8 + t) * C];
         db[co] = s;
     }
 }
@@ -429,7 +437,7 @@ template <int UNUSED = 0>
 __global__ __launch_bounds__(kT) void upconv_fwd_mfma_big_kernel(UpArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int blk = blockIdx.x % a.nblk, sub = blockIdx.x / a.nblk;
-    const int tap = blk & 7, cb = blk >> 3;
+    const int tap = blk % a.ntap, cb = blk / a.ntap;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nks = a.cin >> 4;
@@ -471,8 +479,7 @@ __global__ __launch_bounds__(kT) void upconv_fwd_mfma_big_kernel(UpArgs a) {
                 }
         }
         if (ok) {
-            uint16_t *py = a.out + pvox(a.gf, o.tile, 2 * o.d + (tap >> 2), 2 * o.h + ((tap >> 1) & 1),
-                                        2 * w + (tap & 1)) * a.cout + C * cb + 4 * kh;
+            uint16_t *py = a.out + fvox(a.gf, o.tile, o.d, o.h, w, tap) * a.cout + C * cb + 4 * kh;
 #pragma unroll
             for (int q = 0; q < 4; ++q)
                 *reinterpret_cast<uint2 *>(py + 8 * q) = make_uint2(pack2(acc[4 * q], acc[4 * q + 1]),
@@ -501,9 +508,8 @@ __global__ __launch_bounds__(kT) void upconv_dgrad_mfma_big_kernel(UpArgs a) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll 1
-        for (int tap = 0; tap < 8; ++tap) {
-            const uint16_t *pdy = a.in + pvox(a.gf, o.tile, 2 * o.d + (tap >> 2), 2 * o.h + ((tap >> 1) & 1),
-                                              2 * wl + (tap & 1)) * a.cout + 8 * kh;
+        for (int tap = 0; tap < a.ntap; ++tap) {
+            const uint16_t *pdy = a.in + fvox(a.gf, o.tile, o.d, o.h, wl, tap) * a.cout + 8 * kh;
             const uint16_t *pu = urow + tap * utap;
 #pragma unroll 1
             for (int k0 = 0; k0 < nks; k0 += 8) {
@@ -576,8 +582,9 @@ int launch_upconv_fwd_mfma(const void *Px, const void *u, const float *bias, voi
     a.bias = bias;
     a.out = static_cast<uint16_t *>(Py);
     a.gf = gf; a.gc = gc; a.cin = cin; a.cout = cout;
-    if (cin > 256) {                 // one tap per workgroup: 8 x (cout / 32) kinds of workgroups
-        int rc = plan(gc, 8 * (cout / C), &a);
+    a.ntap = gf.flat ? 4 : 8;
+    if (cin > 256) {                 // one tap per workgroup: ntap x (cout / 32) kinds of workgroups
+        int rc = plan(gc, a.ntap * (cout / C), &a);
         if (rc != SP_OK) return rc;
         return launch(upconv_fwd_mfma_big_kernel<0>, a, (cin / 16) * 1024, s);
     }
@@ -606,6 +613,7 @@ int launch_upconv_dgrad_mfma(const void *Pdy, const void *u, void *Pdx, const Ge
     a.bias = nullptr;
     a.out = static_cast<uint16_t *>(Pdx);
     a.gf = gf; a.gc = gc; a.cin = cin; a.cout = cout;
+    a.ntap = gf.flat ? 4 : 8;
     if (cout > 256) {                // weight fragments straight from global memory
         int rc = plan(gc, cin / C, &a);
         if (rc != SP_OK) return rc;
@@ -645,6 +653,7 @@ int launch_upconv_wgrad_mfma(const void *Px, const void *Pdy, float *du, float *
     a.x = static_cast<const uint16_t *>(Px);
     a.dy = static_cast<const uint16_t *>(Pdy);
     a.gf = gf; a.gc = gc;
+    a.ntap = gf.flat ? 4 : 8;
     a.part_w = static_cast<float *>(ws);
     a.part_b = a.part_w + static_cast<size_t>(a.ngroups) * a.wpg * 8 * nci * C * C;
     const bool full = gc.tw % SEG == 0;
@@ -664,9 +673,9 @@ int launch_upconv_wgrad_mfma(const void *Px, const void *Pdy, float *du, float *
     if (e != hipSuccess) return record_hip(e);
     rc = record_hip(hipGetLastError());
     if (rc != SP_OK) return rc;
-    const int n = 8 * cin * cout + cout;
+    const int n = a.ntap * cin * cout + cout;
     hipLaunchKernelGGL(upconv_wgrad_reduce_kernel, dim3((n + 255) / 256), dim3(256), 0, s, a.part_w, a.part_b, du,
-                       db, cin, cout, nci, a.wpg);
+                       db, cin, cout, nci, a.wpg, a.ntap);
     return record_hip(hipGetLastError());
 }
 

@@ -18,6 +18,8 @@
 // rows R-1, R-2 are still in registers, so 6 fragment reads feed 27 MFMAs.
 // Each workgroup writes its partial dw / db to the workspace; a second kernel adds the partials in
 // workgroup order, so the result does not depend on scheduling.
+// 2-D variant (template parameter KD = 1; geometry flag `flat`): only the taps with kd = 1 exist (x plane D
+// meets dz plane D - 1, its own slice); dw and the partials then hold 9 taps.
 #include "common.h"
 
 namespace sp3d {
@@ -98,7 +100,7 @@ __device__ __forceinline__ bf16x8 frag(const char *p) {
 
 // x plane D (in xcur) against dz planes D, D-1, D-2 (ring slots (P - kd) mod 4) for the GR dz rows
 // of this wave's row group; xlane / zlane already point at the group's first row.
-template <int P>   // P = D mod 4
+template <int P, int KD>   // P = D mod 4
 __device__ __forceinline__ void plane_step(const char *xlane, const char *zlane, f32x4 (&acc)[27]) {
     // Software pipeline over the x rows: the fragments of row R + 1 are requested before the MFMAs
     // of row R are issued, and the scheduling barriers keep the compiler from sinking the reads
@@ -108,7 +110,8 @@ __device__ __forceinline__ void plane_step(const char *xlane, const char *zlane,
 #pragma unroll
     for (int kw = 0; kw < 3; ++kw) xf[0][kw] = frag(xlane + kw * 32);
 #pragma unroll
-    for (int kd = 0; kd < 3; ++kd) zf[kd][0] = frag(zlane + ((P - kd + 4) % 4) * Z_PLANE);
+    for (int kd = 0; kd < 3; ++kd)
+        if (KD == 3 || kd == 1) zf[kd][0] = frag(zlane + ((P - kd + 4) % 4) * Z_PLANE);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int R = 0; R < GR + 2; ++R) {
@@ -119,7 +122,8 @@ __device__ __forceinline__ void plane_step(const char *xlane, const char *zlane,
         if (R + 1 < GR) {
 #pragma unroll
             for (int kd = 0; kd < 3; ++kd)
-                zf[kd][(R + 1) & 3] = frag(zlane + ((P - kd + 4) % 4) * Z_PLANE + (R + 1) * PW * 32);
+                if (KD == 3 || kd == 1)
+                    zf[kd][(R + 1) & 3] = frag(zlane + ((P - kd + 4) % 4) * Z_PLANE + (R + 1) * PW * 32);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -130,6 +134,7 @@ __device__ __forceinline__ void plane_step(const char *xlane, const char *zlane,
             for (int kd = 0; kd < 3; ++kd)
 #pragma unroll
                 for (int kw = 0; kw < 3; ++kw) {
+                    if (KD == 1 && kd != 1) continue;
                     const int tap = (kd * 3 + kh) * 3 + kw;
                     acc[tap] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[R & 1][kw], zf[kd][h & 3], acc[tap],
                                                                        0, 0, 0);
@@ -139,7 +144,9 @@ __device__ __forceinline__ void plane_step(const char *xlane, const char *zlane,
     }
 }
 
+template <int KD>
 __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
+    constexpr int NT = KD == 1 ? 9 : 27, T0 = KD == 1 ? 9 : 0;      // taps written, first tap of acc[] among them
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const Geo &g = a.g;
     const int per_xcd = gridDim.x >> 3;
@@ -267,10 +274,13 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
                     const bool more = Dp + 1 < nplanes;
                     if (more) SP3D_FETCH(Dp + 1);
                     const char *xl = xlane + (Dp & 1) * X_BYTES;
-                    if (ph == 0) plane_step<0>(xl, zlane, acc);
-                    else if (ph == 1) plane_step<1>(xl, zlane, acc);
-                    else if (ph == 2) plane_step<2>(xl, zlane, acc);
-                    else plane_step<3>(xl, zlane, acc);
+                    // 2-D variant: x planes 0 and dn + 1 are the D margins, which hold nothing defined (and
+                    // meet no dz plane): they must not reach the matrix cores
+                    if (KD == 1 && (Dp < 1 || Dp > dn)) {
+                    } else if (ph == 0) plane_step<0, KD>(xl, zlane, acc);
+                    else if (ph == 1) plane_step<1, KD>(xl, zlane, acc);
+                    else if (ph == 2) plane_step<2, KD>(xl, zlane, acc);
+                    else plane_step<3, KD>(xl, zlane, acc);
                     if (more) SP3D_COMMIT(Dp + 1);
                     __syncthreads();
                 }
@@ -289,18 +299,18 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
     const int quad = wave & 3;
     if (kg == 1) {
 #pragma unroll
-        for (int t = 0; t < 27; ++t)
+        for (int t = T0; t < T0 + NT; ++t)
 #pragma unroll
             for (int i = 0; i < 4; ++i) red[((quad * 27 + t) * 4 + i) * 64 + lane] = acc[t][i];
     }
     __syncthreads();
     if (kg == 0) {
-        float *pw = a.part_w + static_cast<size_t>(group) * 27 * C * C;
+        float *pw = a.part_w + static_cast<size_t>(group) * NT * C * C;
 #pragma unroll
-        for (int t = 0; t < 27; ++t)
+        for (int t = T0; t < T0 + NT; ++t)
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                pw[(t * C + 16 * qi + 4 * G + i) * C + 16 * qo + p] =
+                pw[((t - T0) * C + 16 * qi + 4 * G + i) * C + 16 * qo + p] =
                     acc[t][i] + red[((quad * 27 + t) * 4 + i) * 64 + lane];
     }
     // bias partial: threads with the same chunk index hold sums of the same 8 channels
@@ -362,6 +372,7 @@ __device__ __forceinline__ bf16x8 frag_masked(const char *p, uint32_t m) {
 
 // Same march as plane_step, with run-time ring slots: z[kd] points at dz plane D - kd, m[kd] is
 // all ones if that plane exists and zero otherwise.
+template <int KD>
 __device__ __forceinline__ void plane_step_dma(const char *xl, const char *z0, const char *z1, const char *z2,
                                                uint32_t m0, uint32_t m1, uint32_t m2, bool bias_wave,
                                                f32x4 (&acc)[27], f32x4 &accb) {
@@ -375,7 +386,8 @@ __device__ __forceinline__ void plane_step_dma(const char *xl, const char *z0, c
 #pragma unroll
     for (int kw = 0; kw < 3; ++kw) xf[0][kw] = frag(xl + kw * 32);
 #pragma unroll
-    for (int kd = 0; kd < 3; ++kd) zf[kd][0] = frag_masked(z[kd], m[kd]);
+    for (int kd = 0; kd < 3; ++kd)
+        if (KD == 3 || kd == 1) zf[kd][0] = frag_masked(z[kd], m[kd]);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int R = 0; R < GR + 2; ++R) {
@@ -385,11 +397,14 @@ __device__ __forceinline__ void plane_step_dma(const char *xl, const char *z0, c
         }
         if (R + 1 < GR) {
 #pragma unroll
-            for (int kd = 0; kd < 3; ++kd) zf[kd][(R + 1) & 3] = frag_masked(z[kd] + (R + 1) * PW * 32, m[kd]);
+            for (int kd = 0; kd < 3; ++kd)
+                if (KD == 3 || kd == 1) zf[kd][(R + 1) & 3] = frag_masked(z[kd] + (R + 1) * PW * 32, m[kd]);
         }
         __builtin_amdgcn_sched_barrier(0);
+        // every dz plane passes once through each kd position (masked when it does not exist); the 2-D
+        // variant only reads position 1
         if (bias_wave && R < GR)      // wave-uniform
-            accb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones.v, zf[0][R & 3], accb, 0, 0, 0);
+            accb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones.v, zf[KD == 1 ? 1 : 0][R & 3], accb, 0, 0, 0);
 #pragma unroll
         for (int kh = 0; kh < 3; ++kh) {
             const int h = R - kh;
@@ -398,6 +413,7 @@ __device__ __forceinline__ void plane_step_dma(const char *xl, const char *z0, c
             for (int kd = 0; kd < 3; ++kd)
 #pragma unroll
                 for (int kw = 0; kw < 3; ++kw) {
+                    if (KD == 1 && kd != 1) continue;
                     const int tap = (kd * 3 + kh) * 3 + kw;
                     acc[tap] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[R & 1][kw], zf[kd][h & 3], acc[tap],
                                                                        0, 0, 0);
@@ -407,7 +423,9 @@ __device__ __forceinline__ void plane_step_dma(const char *xl, const char *z0, c
     }
 }
 
+template <int KD>
 __global__ __launch_bounds__(kThreads) void wgrad_mfma_dma_kernel(WgradArgs a) {
+    constexpr int NT = KD == 1 ? 9 : 27, T0 = KD == 1 ? 9 : 0;
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const Geo &g = a.g;
     const int per_xcd = gridDim.x >> 3;
@@ -503,7 +521,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_dma_kernel(WgradArgs a) {
             const uint32_t m0 = D < dn ? 0xffffffffu : 0u;
             const uint32_t m1 = (D >= 1 && D - 1 < dn) ? 0xffffffffu : 0u;
             const uint32_t m2 = D >= 2 ? 0xffffffffu : 0u;
-            plane_step_dma(xlane + sx * XD_BYTES, zlane + sz * Z_PLANE, zlane + sz1 * Z_PLANE,
+            // (2-D variant: x planes 0 and dn + 1 are the undefined D margins and meet no dz plane)
+            if (KD == 3 || (D >= 1 && D <= dn))
+                plane_step_dma<KD>(xlane + sx * XD_BYTES, zlane + sz * Z_PLANE, zlane + sz1 * Z_PLANE,
                            zlane + sz2m * Z_PLANE, m0, m1, m2, bias_wave, acc, accb);
             // plane D + 1 (staged one step ago) has landed once at most this step's loads are in flight
             asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
@@ -522,18 +542,18 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_dma_kernel(WgradArgs a) {
     const int quad = qi * 2 + qo;
     if (kg == 1) {
 #pragma unroll
-        for (int t = 0; t < 27; ++t)
+        for (int t = T0; t < T0 + NT; ++t)
 #pragma unroll
             for (int i = 0; i < 4; ++i) red[((quad * 27 + t) * 4 + i) * 64 + lane] = acc[t][i];
     }
     __syncthreads();
     if (kg == 0) {
-        float *pw = a.part_w + static_cast<size_t>(group) * 27 * C * C;
+        float *pw = a.part_w + static_cast<size_t>(group) * NT * C * C;
 #pragma unroll
-        for (int t = 0; t < 27; ++t)
+        for (int t = T0; t < T0 + NT; ++t)
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                pw[(t * C + 16 * qi + 4 * G + i) * C + 16 * qo + p] =
+                pw[((t - T0) * C + 16 * qi + 4 * G + i) * C + 16 * qo + p] =
                     acc[t][i] + red[((quad * 27 + t) * 4 + i) * 64 + lane];
     }
     // bias partial: row 0 of the ones-product (lanes 0..15, register 0) holds the column sums of the
@@ -573,23 +593,24 @@ constexpr int RSPLIT = 8;
 __global__ __launch_bounds__(256) void reduce_wgrad_kernel(const float *__restrict__ part_w,
                                                            const float *__restrict__ part_b,
                                                            float *__restrict__ dw, float *__restrict__ db,
-                                                           int cin, int cout, int gpp) {
+                                                           int cin, int cout, int gpp, int ntaps) {
     const int t = blockIdx.x * 256 + threadIdx.x;
     const int e = t / RSPLIT, sub = t % RSPLIT;
-    const int nw_ = 27 * cin * cout;
+    const int nw_ = ntaps * cin * cout;
+    const size_t gstride = static_cast<size_t>(ntaps) * C * C;      // partial of one workgroup
     const int k0 = static_cast<int>(1LL * sub * gpp / RSPLIT), k1 = static_cast<int>(1LL * (sub + 1) * gpp / RSPLIT);
     float s = 0.f;
     if (e < nw_) {
         const int co = e % cout, ci = (e / cout) % cin, tap = e / (cout * cin);
         const int pair = (ci / C) * (cout / C) + co / C;
-        const float *p = part_w + (static_cast<size_t>(pair) * gpp * 27 + tap) * C * C + (ci % C) * C + co % C;
+        const float *p = part_w + (static_cast<size_t>(pair) * gpp * ntaps + tap) * C * C + (ci % C) * C + co % C;
         int k = k0;
         for (; k + 4 <= k1; k += 4) {          // loads issued together, additions kept in order
-            const float p0 = p[static_cast<size_t>(k) * 27 * C * C], p1 = p[static_cast<size_t>(k + 1) * 27 * C * C];
-            const float p2 = p[static_cast<size_t>(k + 2) * 27 * C * C], p3 = p[static_cast<size_t>(k + 3) * 27 * C * C];
+            const float p0 = p[k * gstride], p1 = p[(k + 1) * gstride];
+            const float p2 = p[(k + 2) * gstride], p3 = p[(k + 3) * gstride];
             s = (((s + p0) + p1) + p2) + p3;
         }
-        for (; k < k1; ++k) s += p[static_cast<size_t>(k) * 27 * C * C];
+        for (; k < k1; ++k) s += p[k * gstride];
     } else if (e < nw_ + cout) {
         const int co = e - nw_;
         const float *p = part_b + static_cast<size_t>(co / C) * gpp * C + co % C;     // pairs (0, co/32)
@@ -616,7 +637,7 @@ bool wgrad_mfma_supported(const Geo &g, int cin, int cout, sp_dtype_t dt) {
 size_t wgrad_mfma_ws_bytes(const Geo &g, int cin, int cout) {
     WgradArgs a;
     plan(g, cin, cout, &a);
-    return static_cast<size_t>(a.ngroups) * (27 * C * C + C) * sizeof(float);
+    return static_cast<size_t>(a.ngroups) * (taps_of(g) * C * C + C) * sizeof(float);
 }
 
 int launch_wgrad_mfma(const void *Px, const void *Pdz, float *dw, float *db, const Geo &g, int cin, int cout,
@@ -629,26 +650,36 @@ int launch_wgrad_mfma(const void *Px, const void *Pdz, float *dw, float *db, con
     else { a.x_ca = cin; a.x2_cs = 0; }
     a.dz = static_cast<const uint16_t *>(Pdz);
     a.part_w = static_cast<float *>(ws);
-    a.part_b = a.part_w + static_cast<size_t>(a.ngroups) * 27 * C * C;
+    const int ntaps = taps_of(g);
+    a.part_b = a.part_w + static_cast<size_t>(a.ngroups) * ntaps * C * C;
     a.g = g;
     const unsigned grid = static_cast<unsigned>((a.ngroups + 7) / 8 * 8);
     // more than 64 KB of dynamic LDS has to be requested explicitly
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(wgrad_mfma_kernel),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    static const hipError_t attr_dma = hipFuncSetAttribute(reinterpret_cast<const void *>(wgrad_mfma_dma_kernel),
-                                                           hipFuncAttributeMaxDynamicSharedMemorySize, DMA_LDS_BYTES);
+    using Kern = void (*)(WgradArgs);
+    static const Kern plain[2] = {wgrad_mfma_kernel<3>, wgrad_mfma_kernel<1>};          // [2-D variant]
+    static const Kern dma[2] = {wgrad_mfma_dma_kernel<3>, wgrad_mfma_dma_kernel<1>};
+    static const hipError_t attr = [] {
+        for (int i = 0; i < 2; ++i) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(plain[i]),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+            if (e != hipSuccess) return e;
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(dma[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    DMA_LDS_BYTES);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }();
     if (attr != hipSuccess) return record_hip(attr);
-    if (attr_dma != hipSuccess) return record_hip(attr_dma);
     // whole patches only: the direct-to-LDS loads cannot zero-fill a ragged edge
     if (g.th % PH == 0 && g.tw % PW == 0)
-        hipLaunchKernelGGL(wgrad_mfma_dma_kernel, dim3(grid), dim3(kThreads), DMA_LDS_BYTES, s, a);
+        hipLaunchKernelGGL(dma[g.flat], dim3(grid), dim3(kThreads), DMA_LDS_BYTES, s, a);
     else
-        hipLaunchKernelGGL(wgrad_mfma_kernel, dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
+        hipLaunchKernelGGL(plain[g.flat], dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
     int rc = record_hip(hipGetLastError());
     if (rc != SP_OK) return rc;
-    const long long n = (27LL * cin * cout + cout) * RSPLIT;
+    const long long n = (1LL * ntaps * cin * cout + cout) * RSPLIT;
     hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, s, a.part_w,
-                       a.part_b, dw, db, cin, cout, a.gpp);
+                       a.part_b, dw, db, cin, cout, a.gpp, ntaps);
     return record_hip(hipGetLastError());
 }
 

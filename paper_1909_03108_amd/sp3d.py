@@ -25,15 +25,16 @@ EXPORTS = ["sp_padded_elems", "sp_msg_elems", "sp_workspace_bytes", "sp_check_ge
 
 class Geom(ctypes.Structure):
     """sp_geom_t: volume extents, tile grid (D,H,W order), margin width of the layout, and by how much the
-    convolutions grow their output box beyond the interior (0 unless several layers share one exchange)."""
-    _fields_ = [(k, ctypes.c_int32) for k in ("n", "d", "h", "w", "gd", "gh", "gw", "halo", "grow")]
+    convolutions grow their output box beyond the interior (0 unless several layers share one exchange).
+    flat = 1 selects the 2-D variant: D is a stack of independent slices (3x3 kernels, 1x2x2 windows)."""
+    _fields_ = [(k, ctypes.c_int32) for k in ("n", "d", "h", "w", "gd", "gh", "gw", "halo", "grow", "flat")]
 
-    def __init__(self, n, dhw, grid, halo=1, grow=0):
-        super().__init__(n, dhw[0], dhw[1], dhw[2], grid[0], grid[1], grid[2], halo, grow)
+    def __init__(self, n, dhw, grid, halo=1, grow=0, flat=0):
+        super().__init__(n, dhw[0], dhw[1], dhw[2], grid[0], grid[1], grid[2], halo, grow, int(flat))
 
     def grown(self, grow):
         """The same geometry with another `grow`."""
-        return Geom(self.n, (self.d, self.h, self.w), (self.gd, self.gh, self.gw), self.halo, grow)
+        return Geom(self.n, (self.d, self.h, self.w), (self.gd, self.gh, self.gw), self.halo, grow, self.flat)
 
     @property
     def tile(self):
@@ -281,8 +282,10 @@ def sp_add(Pa, Pb, Pout, g, c, dt, stream=None):
 
 
 def coarse_geom(gf):
-    """Geometry of the half-resolution side of a pooling / up-convolution on the same tile grid."""
-    return Geom(gf.n, (gf.d // 2, gf.h // 2, gf.w // 2), (gf.gd, gf.gh, gf.gw), gf.halo)
+    """Geometry of the half-resolution side of a pooling / up-convolution on the same tile grid (the 2-D
+    variant keeps D: its windows are 1x2x2)."""
+    return Geom(gf.n, (gf.d if gf.flat else gf.d // 2, gf.h // 2, gf.w // 2), (gf.gd, gf.gh, gf.gw), gf.halo, 0,
+                gf.flat)
 
 
 # ---- plumbing helpers (device memory only; no arithmetic) ---------------------------------------

@@ -15,6 +15,10 @@ With `halo` = 2 the tensors carry margins that wide and two consecutive layers o
 one exchange (the overlap idea of the paper's Sec. 1 applied to a short stack): the first layer of such a group
 also computes the voxels around the tile that the later ones read (`grow`), and the backward pass does the same
 with the gradients.  The results are bit for bit those of `halo` = 1.
+
+With `flat` the same network is the paper's 2-D U-Net (Sec. 3: same architecture, 2-D convolutions and
+poolings, trained on 512 x 512 x 5 slabs): D is a stack of independent slices, the kernels are 3x3 and the
+windows 1x2x2, and only H and W halve from level to level.
 """
 import numpy as np
 import torch
@@ -25,27 +29,28 @@ from . import sp3d
 LETTERS = "abcdefgh"
 
 
-def layer_plan(channels=(32, 64, 128, 256), in_ch=1, classes=3, convs=2):
-    """Names and shapes of all weight tensors, in forward order."""
+def layer_plan(channels=(32, 64, 128, 256), in_ch=1, classes=3, convs=2, flat=False):
+    """Names and shapes of all weight tensors, in forward order (flat: the 2-D variant's 3x3 / 2x2 / 1x1)."""
+    nd = 2 if flat else 3
     plan = []
     prev = in_ch
     for i, c in enumerate(channels):
         for k in range(convs):
-            plan.append(("enc%d_%s" % (i, LETTERS[k]), (3, 3, 3, prev if k == 0 else c, c)))
+            plan.append(("enc%d_%s" % (i, LETTERS[k]), (3,) * nd + (prev if k == 0 else c, c)))
         prev = c
     for i in range(len(channels) - 2, -1, -1):
         c = channels[i]
-        plan.append(("up%d" % i, (2, 2, 2, prev, c)))
+        plan.append(("up%d" % i, (2,) * nd + (prev, c)))
         for k in range(convs):
-            plan.append(("dec%d_%s" % (i, LETTERS[k]), (3, 3, 3, 2 * c if k == 0 else c, c)))
+            plan.append(("dec%d_%s" % (i, LETTERS[k]), (3,) * nd + (2 * c if k == 0 else c, c)))
         prev = c
-    plan.append(("head", (1, 1, 1, prev, classes)))
+    plan.append(("head", (1,) * nd + (prev, classes)))
     return plan
 
 
 class UNet:
     def __init__(self, n, dhw, grid, weights, channels=(32, 64, 128, 256), in_ch=1, classes=3,
-                 dt=sp3d.SP_BF16, convs=2, halo=1):
+                 dt=sp3d.SP_BF16, convs=2, halo=1, flat=False):
         self.channels, self.in_ch, self.classes, self.dt = tuple(channels), in_ch, classes, dt
         self.convs = convs
         # Runs of more than two layers would need ReLU masks further around the tiles in the backward pass than
@@ -55,7 +60,9 @@ class UNet:
         self.halo = halo
         self.free = {}                        # (padded shape, channels) -> released gradient buffers
         self.L = len(channels)
-        self.g = [sp3d.Geom(n, tuple(e >> i for e in dhw), grid, halo) for i in range(self.L)]
+        self.flat = bool(flat)
+        self.g = [sp3d.Geom(n, (dhw[0] if flat else dhw[0] >> i, dhw[1] >> i, dhw[2] >> i), grid, halo, 0, flat)
+                  for i in range(self.L)]
         for g in self.g:
             assert sp3d.sp_check_geom(g) == sp3d.SP_OK
         self.w = weights                      # name -> device tensor
@@ -223,7 +230,7 @@ class UNet:
         dt = self.dt
         if not masked:
             sp3d.sp_relu_bwd(Pdy, Py, Pdy, g, cout, dt)               # dz in place
-        dw = torch.empty((3, 3, 3, cin, cout), dtype=torch.float32, device="cuda")
+        dw = torch.empty(tuple(self.w[name].shape), dtype=torch.float32, device="cuda")
         if isinstance(Px, tuple):                 # x = concat(Px[0], Px[1]): gradients go to two tensors
             ca = cin // 2
             sp3d.conv3d_wgrad2(Px[0], ca, Px[1], ca, Pdy, dw, None, g, cout, dt,
@@ -281,7 +288,7 @@ class UNet:
         if dlogits_vol is not None:
             sp3d.sp_partition(dlogits_vol, Pd, g0, self.classes, dt)
         c0 = ch[0]
-        dp = torch.empty((1, 1, 1, c0, self.classes), dtype=torch.float32, device="cuda")
+        dp = torch.empty(tuple(self.w["head"].shape), dtype=torch.float32, device="cuda")
         sp3d.sp_pointwise_wgrad(A["head.x"], Pd, dp, None, g0, c0, self.classes, dt,
                                 self._ws(sp3d.SP_OP_POINTWISE_WGRAD, g0, c0, self.classes))
         grads["head"] = dp
@@ -300,7 +307,7 @@ class UNet:
                 sp3d.sp_split(Pg, Ps, c, Pu, c, g, dt)
                 self._release(Pg, g, 2 * c)
             skip_grad[i] = Ps
-            du = torch.empty((2, 2, 2, up_in, c), dtype=torch.float32, device="cuda")
+            du = torch.empty(tuple(self.w["up%d" % i].shape), dtype=torch.float32, device="cuda")
             sp3d.sp_upconv2_wgrad(A["up%d.x" % i], Pu, du, None, g, up_in, c, dt,
                                   self._ws(sp3d.SP_OP_UPCONV_WGRAD, g, up_in, c))
             grads["up%d" % i] = du
