@@ -39,11 +39,16 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--size", type=int, default=512, help="volume edge (512 = headline workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="c4", choices=["c4", "c5", "paper512"],
+    ap.add_argument("--workload", default="c4", choices=["c4", "c5", "paper512", "paper2d"],
                     help="c4 = headline single-layer workload (default); c5 = the whole U-Net convolution "
                          "stack of the workload list (256^3, channels 32/64/128/256), forward + backward; "
                          "paper512 = the network the paper trains at 512^3 (six blocks of four convolutions, "
-                         "32 ... 1024 filters), forward + backward, all 16 tiles in this GPU's HBM")
+                         "32 ... 1024 filters), forward + backward, all 16 tiles in this GPU's HBM; "
+                         "paper2d = the paper's 2-D U-Net (same architecture, 2-D operations) on a batch of "
+                         "512 x 512 x 5 slabs, grid 1x4x4")
+    ap.add_argument("--slabs", type=int, default=16, help="paper2d: slabs per step (the stack axis of the tensors)")
+    ap.add_argument("--grid", default=None,
+                    help="U-Net workloads: tile grid gd,gh,gw (default 4,4,1; paper2d: 1,2,2)")
     ap.add_argument("--loss", action="store_true",
                     help="U-Net workloads: compute the upstream gradient with sp_dice_ce_loss on seeded labels "
                          "instead of the N(0,1) stand-in of the workload list (adds the loss passes to the step)")
@@ -67,21 +72,30 @@ def bench_unet(args):
     from paper_1909_03108_amd import sp3d, synth, unet
 
     torch.cuda.set_device(0)
-    paper = args.workload == "paper512"
+    flat = args.workload == "paper2d"
+    paper = args.workload == "paper512" or flat
     S = args.size if (paper or args.size != 512) else 256
-    channels, in_ch, classes = ((32, 64, 128, 256, 512, 1024) if paper else (32, 64, 128, 256)), 1, 3
+    channels, in_ch, classes = ((32, 64, 128, 256, 512, 1024) if paper else (32, 64, 128, 256)), (5 if flat else 1), 3
     convs = 4 if paper else 2
-    n, dhw, grid = 1, (S, S, S), (4, 4, 1)
-    plan = unet.layer_plan(channels, in_ch, classes, convs)
+    n, dhw, grid = 1, ((args.slabs, S, S) if flat else (S, S, S)), ((1, 2, 2) if flat else (4, 4, 1))
+    if args.grid:
+        grid = tuple(int(v) for v in args.grid.split(","))
+        assert len(grid) == 3
+    plan = unet.layer_plan(channels, in_ch, classes, convs, flat=flat)
+    nd = 2 if flat else 3
 
     def dev(a):
         return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
 
-    x = dev(synth.ct_like_volume((n,) + dhw + (in_ch,), synth.seed_for(5, synth.T_INPUT), "bf16"))
-    w = {name: dev(synth.weights(shape[3], shape[4], synth.seed_for(5, synth.T_WEIGHT0 + k), "bf16",
-                                 taps=shape[:3])) for k, (name, shape) in enumerate(plan)}
+    if flat:     # a slab = 5 neighbouring slices as channels: five draws of the CT-like generator
+        x = dev(np.concatenate([synth.ct_like_volume((n,) + dhw + (1,), synth.seed_for(5, synth.T_INPUT) + 977 * i,
+                                                     "bf16") for i in range(in_ch)], axis=-1))
+    else:
+        x = dev(synth.ct_like_volume((n,) + dhw + (in_ch,), synth.seed_for(5, synth.T_INPUT), "bf16"))
+    w = {name: dev(synth.weights(shape[nd], shape[nd + 1], synth.seed_for(5, synth.T_WEIGHT0 + k), "bf16",
+                                 taps=shape[:nd])) for k, (name, shape) in enumerate(plan)}
     dl = dev(synth.normal_volume((n,) + dhw + (classes,), synth.seed_for(5, synth.T_UPSTREAM), "bf16"))
-    net = unet.UNet(n, dhw, grid, w, channels, in_ch, classes, convs=convs, halo=args.halo)
+    net = unet.UNet(n, dhw, grid, w, channels, in_ch, classes, convs=convs, halo=args.halo, flat=flat)
 
     labels = None
     if args.loss:
@@ -104,26 +118,30 @@ def bench_unet(args):
         step()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    vox = n * S * S * S
+    vox = n * dhw[0] * dhw[1] * dhw[2]
     flop = 0.0
     for name, shape in plan:
         lvl_vox = vox
         if name[:3] in ("enc", "dec"):
-            lvl_vox = vox >> (3 * int(name[3]))
+            lvl_vox = vox >> (nd * int(name[3]))
         elif name[:2] == "up":
-            lvl_vox = vox >> (3 * int(name[2]))
-        taps = shape[0] * shape[1] * shape[2]
-        per = 2.0 * shape[3] * shape[4] * lvl_vox * (taps if taps != 8 else 1)   # up-conv: 1 tap per output voxel
+            lvl_vox = vox >> (nd * int(name[2]))
+        taps = int(np.prod(shape[:nd]))
+        per = 2.0 * shape[nd] * shape[nd + 1] * lvl_vox * (taps if taps != 2 ** nd else 1)   # up-conv: 1 tap per output voxel
         flop += 3 * per
-    flop -= 2.0 * 27 * in_ch * channels[0] * vox                    # no image gradient
-    name = ("paper512_unet_%d^3: six blocks of four 3x3x3 convolutions, 32/64/128/256/512/1024 filters"
-            if paper else "c5_unet_%d^3: channels 32/64/128/256") % S
+    flop -= 2.0 * 3 ** nd * in_ch * channels[0] * vox               # no image gradient
+    if flat:
+        name = ("paper2d_unet_%dx%dx%d: %d slabs of %d slices as channels, six blocks of four 3x3 convolutions, "
+                "32/64/128/256/512/1024 filters" % (S, S, in_ch, args.slabs, in_ch))
+    else:
+        name = ("paper512_unet_%d^3: six blocks of four 3x3x3 convolutions, 32/64/128/256/512/1024 filters"
+                if paper else "c5_unet_%d^3: channels 32/64/128/256") % S
     print(json.dumps({
         "metric": "U-Net conv stack fwd+bwd TFLOP/s (bf16), secondary workload", "value": round(flop / ms / 1e9, 2),
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": name + (", grid 4x4x1, halo %d, forward + backward (weight and data gradients, "
-                                       "no image gradient)" % args.halo) + (", upstream gradient from the Dice + CE loss"
+        "config": {"workload": name + (", grid %dx%dx%d, halo %d, forward + backward (weight and data gradients, "
+                                       "no image gradient)" % (grid + (args.halo,))) + (", upstream gradient from the Dice + CE loss"
                                                               if args.loss else ""),
                    "tflop_per_step": round(flop / 1e12, 2),
                    "hbm_allocated_gb": round(torch.cuda.max_memory_allocated() / 1e9, 1)}}))
@@ -135,7 +153,7 @@ def main():
         print("bench.py: this build runs on one GPU only (all tiles of the grid live in one HBM); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
-    if args.workload in ("c5", "paper512"):
+    if args.workload in ("c5", "paper512", "paper2d"):
         return bench_unet(args)
 
     import numpy as np

@@ -106,12 +106,16 @@ size_t sp_workspace_bytes(int op, const sp_geom_t *g, int cin, int cout, sp_dtyp
     case SP_OP_DGRAD: {
         // dgrad swaps the channel roles of the same kernel
         const int ki = op == SP_OP_FWD ? cin : cout, ko = op == SP_OP_FWD ? cout : cin;
-        return conv_mfma_supported(o, ki, ko, dt) ? conv_mfma_ws_bytes(o, ki, ko) : 0;
+        if (conv_mfma_supported(o, ki, ko, dt)) return conv_mfma_ws_bytes(o, ki, ko);
+        if (op == SP_OP_FWD && !conv_c1_supported(o, cin, cout, dt) && chan_pad_supported(o, cin, cout, dt))
+            return chan_pad_fwd_ws_bytes(o, cin, cout);
+        return 0;
     }
     case SP_OP_WGRAD:
         if (conv_c1_supported(o, cin, cout, dt)) return wgrad_c1_ws_bytes(o, cout);
-        return wgrad_mfma_supported(o, cin, cout, dt) ? wgrad_mfma_ws_bytes(o, cin, cout)
-                                                      : wgrad_direct_ws_bytes(o, cin, cout);
+        if (wgrad_mfma_supported(o, cin, cout, dt)) return wgrad_mfma_ws_bytes(o, cin, cout);
+        if (chan_pad_supported(o, cin, cout, dt)) return chan_pad_wgrad_ws_bytes(o, cin, cout);
+        return wgrad_direct_ws_bytes(o, cin, cout);
     case SP_OP_UPCONV_WGRAD: {
         Geo c;
         if (make_coarse(o, &c) != SP_OK) return static_cast<size_t>(-1);
@@ -234,6 +238,12 @@ int conv3d_fwd(const void *Px, const void *w, const float *bias, void *Py, const
     }
     if (o.grow == 0 && conv_c1_supported(o, cin, cout, dt))
         return launch_conv_c1_fwd(shifted(Px, o, 1, dt), w, bias, shifted(Py, o, cout, dt), o, cout, relu, s);
+    // few input channels: zero-padded copies in the workspace, then the matrix-core kernel
+    if (!conv_c1_supported(o, cin, cout, dt) && chan_pad_supported(o, cin, cout, dt)) {
+        const size_t need = chan_pad_fwd_ws_bytes(o, cin, cout);
+        if (!ws || ws_bytes < need || !aligned16(ws)) return SP_EWORKSPACE;
+        return launch_conv_chan_pad_fwd(Px, w, bias, Py, o, cin, cout, relu, ws, s);
+    }
     return launch_conv_direct(Px, w, bias, Py, o, cin, cout, dt, relu, false, s);
 }
 
@@ -276,9 +286,12 @@ int conv3d_wgrad(const void *Px, const void *Pdz, float *dw, float *db, const sp
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool c1 = conv_c1_supported(o, cin, cout, dt);
     const bool mfma = !c1 && wgrad_mfma_supported(o, cin, cout, dt);
+    const bool pad = !c1 && !mfma && chan_pad_supported(o, cin, cout, dt);
     const size_t need = c1 ? wgrad_c1_ws_bytes(o, cout)
-                           : (mfma ? wgrad_mfma_ws_bytes(o, cin, cout) : wgrad_direct_ws_bytes(o, cin, cout));
+                           : (mfma ? wgrad_mfma_ws_bytes(o, cin, cout)
+                                   : (pad ? chan_pad_wgrad_ws_bytes(o, cin, cout) : wgrad_direct_ws_bytes(o, cin, cout)));
     if (need && (!ws || ws_bytes < need || !aligned16(ws))) return SP_EWORKSPACE;
+    if (pad) return launch_wgrad_chan_pad(Px, Pdz, dw, db, o, cin, cout, dt, ws, s);
     if (c1) return launch_wgrad_c1(shifted(Px, o, 1, dt), shifted(Pdz, o, cout, dt), dw, db, o, cout, ws, s);
     if (mfma)
         return launch_wgrad_mfma(shifted(Px, o, cin, dt), shifted(Pdz, o, cout, dt), dw, db, o, cin, cout, ws, s);

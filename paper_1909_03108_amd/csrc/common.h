@@ -140,6 +140,15 @@ size_t wgrad_mfma_ws_bytes(const Geo &g, int cin, int cout);
 int launch_wgrad_mfma(const void *Px, const void *Pdz, float *dw, float *db, const Geo &g,
                       int cin, int cout, void *ws, hipStream_t s, const void *Px2 = nullptr, int ca = 0);
 
+// few input channels (not a multiple of 32) on the matrix cores through zero-padded copies (chan_pad.hip)
+bool chan_pad_supported(const Geo &g, int cin, int cout, sp_dtype_t dt);
+size_t chan_pad_fwd_ws_bytes(const Geo &g, int cin, int cout);
+size_t chan_pad_wgrad_ws_bytes(const Geo &g, int cin, int cout);
+int launch_conv_chan_pad_fwd(const void *Px, const void *w, const float *bias, void *Py, const Geo &g, int cin,
+                             int cout, bool relu, void *ws, hipStream_t s);
+int launch_wgrad_chan_pad(const void *Px, const void *Pdz, float *dw, float *db, const Geo &g, int cin, int cout,
+                          sp_dtype_t dt, void *ws, hipStream_t s);
+
 // Division of a 32-bit index by a launch-time constant without the ~25-instruction software divide:
 // multiply-high by a precomputed reciprocal, with the one-bit-wider "add" form where the 32-bit
 // reciprocal is not exact (Granlund & Montgomery, "Division by invariant integers using

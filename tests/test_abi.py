@@ -73,6 +73,35 @@ def test_geometry_errors():
     assert sp3d.sp_padded_elems(sp3d.Geom(1, (8, 8, 8), (3, 2, 2)), 4) == 0
 
 
+def test_flat_geometry_of_the_2d_variant():
+    """flat = 1: D is a stack of slices.  The layout is unchanged, a tile may hold fewer slices than the margin is
+    wide, only H and W must be even for pooling, and the workspaces are sized for 9 taps / 4 window positions."""
+    flat = sp3d.Geom(1, (3, 16, 64), (1, 2, 2), flat=1)
+    full = sp3d.Geom(1, (3, 16, 64), (1, 2, 2))
+    assert sp3d.sp_check_geom(flat) == sp3d.SP_OK
+    assert sp3d.sp_padded_elems(flat, 4) == sp3d.sp_padded_elems(full, 4)
+    assert sp3d.sp_msg_elems(flat, 4) == sp3d.sp_msg_elems(full, 4)
+    assert flat.grown(0).flat == 1
+    bad = sp3d.Geom(1, (3, 16, 64), (1, 2, 2))
+    bad.flat = 2
+    assert sp3d.sp_check_geom(bad) == sp3d.SP_EINVAL
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (2, 16, 64), (2, 2, 2), halo=2, flat=1)) == sp3d.SP_OK     # 1 slice per tile
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (2, 16, 64), (2, 2, 2), halo=2)) == sp3d.SP_EGEOM
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (4, 2, 64), (1, 2, 2), halo=2, flat=1)) == sp3d.SP_EGEOM    # 1-voxel rows
+    gc = sp3d.coarse_geom(flat)
+    assert (gc.d, gc.h, gc.w, gc.flat) == (3, 8, 32, 1)
+    dt = sp3d.SP_BF16
+    # odd slice count: fine for the 1x2x2 windows, not for the 2x2x2 ones
+    assert sp3d.sp_workspace_bytes(sp3d.SP_OP_UPCONV_WGRAD, flat, 64, 32, dt) > 0
+    with pytest.raises(sp3d.Sp3dError):
+        sp3d.sp_workspace_bytes(sp3d.SP_OP_UPCONV_WGRAD, full, 64, 32, dt)
+    even_f, even = sp3d.Geom(1, (4, 16, 64), (1, 2, 2), flat=1), sp3d.Geom(1, (4, 16, 64), (1, 2, 2))
+    for op, ci, co in [(sp3d.SP_OP_WGRAD, 32, 32), (sp3d.SP_OP_WGRAD, 5, 8)]:
+        assert 0 < sp3d.sp_workspace_bytes(op, even_f, ci, co, dt) < sp3d.sp_workspace_bytes(op, even, ci, co, dt)
+    assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, even_f, 64, 64, dt) == sp3d.sp_workspace_bytes(
+        sp3d.SP_OP_FWD, even, 64, 64, dt)
+
+
 def test_calls_reject_bad_arguments_before_launching():
     L = sp3d.lib()
     g = sp3d.Geom(1, (8, 8, 8), (2, 2, 2))

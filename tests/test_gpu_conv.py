@@ -98,6 +98,9 @@ SMALL = [
     (1, (4, 12, 40), (2, 1, 1), 128, 64, "bf16"),     # two pairs (first / last), two planes, ragged
     (1, (3, 4, 32), (1, 1, 1), 192, 32, "bf16"),      # three pairs (first / middle / last), three planes
     (1, (7, 5, 33), (1, 1, 1), 64, 32, "bf16"),       # seven planes, ragged rows and columns
+    # few input channels: zero-padded copies, then the matrix-core kernels
+    (1, (6, 10, 40), (1, 2, 1), 3, 32, "bf16"),
+    (1, (4, 8, 16), (2, 1, 1), 40, 64, "bf16"),       # 40 -> 64 channels: a pair of chunks
 ]
 
 

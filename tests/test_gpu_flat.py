@@ -58,6 +58,7 @@ SMALL = [
     (1, (2, 4, 32), (1, 1, 1), 192, 32, "bf16"),       # three pairs
     (1, (7, 5, 33), (1, 1, 1), 96, 32, "bf16"),        # three single chunks (first / middle / last)
     (1, (4, 16, 64), (1, 2, 2), 32, 32, "bf16"),       # whole patches: direct-to-LDS weight gradient
+    (1, (3, 16, 40), (1, 2, 1), 5, 32, "bf16"),        # the slab input on the matrix cores (zero-padded channels)
 ]
 
 
