@@ -138,7 +138,11 @@ int sp_halo_exchange(void *P, const sp_geom_t *g, int c, sp_dtype_t dt, void *st
  * instead of exchanged); Px must be valid e + 1 voxels around the interior.  The rest of Py's
  * margins is still left as it is: keep it zero beyond the volume border (a zeroed buffer stays so).
  * bf16: products of bf16 values accumulated in fp32, result rounded to nearest-even bf16.
- * f32: fp32 throughout. */
+ * f32: fp32 throughout.
+ * bf16 layers whose Cin is not a multiple of 32 (but Cout is; Cin = 1 aside, which has kernels of its
+ * own) run on the matrix cores through copies of Px and w with the channel axis zero-padded to the next
+ * multiple of 32, held in `ws`: sp_workspace_bytes then asks for about one padded tensor of that many
+ * channels.  conv3d_wgrad does the same and drops the padding rows of dw. */
 int conv3d_fwd(const void *Px, const void *w, const float *bias, void *Py, const sp_geom_t *g,
                int cin, int cout, sp_dtype_t dt, uint32_t flags, void *ws, size_t ws_bytes,
                void *stream);

@@ -306,3 +306,36 @@ def test_flat_unet_against_the_composed_oracle(convs):
     assert torch.equal(logits3, logits) and torch.equal(dx3, dx)
     for k, _ in plan:
         assert torch.equal(grads3[k], grads[k]), k
+
+
+@pytest.mark.timeout(600)
+def test_bench_shape_first_two_layers_full():
+    """The shape `bench.py --workload paper2d` times (16 slabs of 512 x 512, grid 1x2x2): the slab layer 5 -> 32 and
+    a 32 -> 32 layer, every output element of forward, data gradient and weight gradient against the oracle."""
+    n, dhw, grid = 1, (16, 512, 512), (1, 2, 2)
+    for cin, cout in ((5, 32), (32, 32)):
+        L = Layer(n, dhw, grid, cin, cout, "bf16")
+        g, dt = L.g, L.dt
+        x = draw("bf16", (n,) + dhw + (cin,), 21)
+        dz = draw("bf16", (n,) + dhw + (cout,), 22)
+        w = synth.weights(cin, cout, 23, "bf16", taps=(3, 3))
+        Px = L.padded(x, cin)
+        Py = sp3d.alloc_padded(g, cout, dt)
+        sp3d.conv3d_fwd(Px, to_dev(w), None, Py, g, cin, cout, dt, sp3d.SP_FLAG_RELU, L.ws[sp3d.SP_OP_FWD])
+        assert rel_err(f64(L.volume(Py, cout)), O.conv_fwd(widen(x), widen(w), relu=True)) <= 1e-2, (cin, "fwd")
+        del Py
+        Pzi = L.padded(dz, cout, exchange=False)
+        dw = torch.empty((3, 3, cin, cout), dtype=torch.float32, device="cuda")
+        db = torch.empty((cout,), dtype=torch.float32, device="cuda")
+        sp3d.conv3d_wgrad(Px, Pzi, dw, db, g, cin, cout, dt, L.ws[sp3d.SP_OP_WGRAD])
+        assert rel_err(f64(dw), O.conv_wgrad(widen(x), widen(dz))) <= 1e-2, (cin, "wgrad")
+        assert rel_err(f64(db), O.bias_grad(widen(dz))) <= 1e-2
+        dw2 = torch.empty_like(dw)
+        sp3d.conv3d_wgrad(Px, Pzi, dw2, None, g, cin, cout, dt, L.ws[sp3d.SP_OP_WGRAD])
+        assert torch.equal(dw, dw2)                       # fixed reduction order
+        del Px, Pzi
+        if cin == 32:
+            Pz = L.padded(dz, cout)
+            Pdx = sp3d.alloc_padded(g, cin, dt)
+            sp3d.conv3d_dgrad(Pz, to_dev(w), Pdx, g, cin, cout, dt, L.ws[sp3d.SP_OP_DGRAD])
+            assert rel_err(f64(L.volume(Pdx, cin)), O.conv_dgrad(widen(dz), widen(w))) <= 1e-2, "dgrad"
