@@ -134,6 +134,26 @@ def test_calls_reject_bad_arguments_before_launching():
     assert L.sp_workspace_bytes(sp3d.SP_OP_FWD, bp, 4, 4, sp3d.SP_F32) == ctypes.c_size_t(-1).value
 
 
+def test_few_channel_layers_ask_for_their_padded_copies():
+    """bf16 layers with Cin not a multiple of 32 (Cout a multiple) run on zero-padded copies held in the workspace:
+    the size helper says so and the calls refuse a missing or short workspace before anything is launched."""
+    L = sp3d.lib()
+    far = FAKE * 4096
+    for g in (sp3d.Geom(1, (8, 8, 32), (2, 2, 1)), sp3d.Geom(1, (3, 8, 32), (1, 2, 1), flat=1)):
+        gp = ctypes.byref(g)
+        padded32 = sp3d.sp_padded_elems(g, 32) * 2
+        for op in (sp3d.SP_OP_FWD, sp3d.SP_OP_WGRAD):
+            need = sp3d.sp_workspace_bytes(op, g, 5, 32, sp3d.SP_BF16)
+            assert need >= padded32 + sp3d.sp_workspace_bytes(op, g, 32, 32, sp3d.SP_BF16)
+            assert need > sp3d.sp_workspace_bytes(op, g, 5, 24, sp3d.SP_BF16)          # Cout 24: the plain kernels
+        assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 5, 32, sp3d.SP_F32) == 0
+        need = sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 5, 32, sp3d.SP_BF16)
+        assert L.conv3d_fwd(FAKE, FAKE * 2, None, far, gp, 5, 32, sp3d.SP_BF16, 0, None, 0, None) == sp3d.SP_EWORKSPACE
+        assert L.conv3d_fwd(FAKE, FAKE * 2, None, far, gp, 5, 32, sp3d.SP_BF16, 0, far * 2, need - 1, None) == sp3d.SP_EWORKSPACE
+        need = sp3d.sp_workspace_bytes(sp3d.SP_OP_WGRAD, g, 5, 32, sp3d.SP_BF16)
+        assert L.conv3d_wgrad(FAKE, far, far * 2, None, gp, 5, 32, sp3d.SP_BF16, far * 4, need - 1, None) == sp3d.SP_EWORKSPACE
+
+
 def test_error_strings():
     L = sp3d.lib()
     seen = {L.sp_strerror(c) for c in range(-5, 1)}
