@@ -74,9 +74,9 @@ struct ConvArgs {
     const float *bias;      // bias of all output channels or NULL
     uint16_t *out;          // output tensor (out_cs channels per voxel)
     uint16_t *out2;         // optional second output tensor (out2_cs channels per voxel): output channels
-    int out_ca, out2_cs;    //   [out_ca, ko) go there, [0, out_ca) to `out`; partial sums are split alike
+    int out_ca, out2_cs;    //   [out_ca, ko) go there, [0, out_ca) to `out`
     const uint16_t *mask;   // RELU == 2: tensor laid out like `out`; results are zeroed where it is not positive
-    float *part;            // fp32 partial sums, indexed like `out`
+    float *part;            // fp32 partial sums in fragment order (see part_unit)
     Geo g;
     int in_cs, in_co, out_cs;
     int nco;                // output blocks of 32 channels (all handled by this launch)
@@ -122,14 +122,11 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
     return r.u;
 }
 
-// Where output block cj goes: tensor, its channels per voxel, channel offset, and the offset of that tensor's
-// part of the fp32 partial-sum buffer (the buffer holds one region per output tensor, each laid out like it).
-struct OutDst { uint16_t *base; int cs, co; size_t part_off; };
+// Where output block cj goes: tensor, its channels per voxel, channel offset.
+struct OutDst { uint16_t *base; int cs, co; };
 __device__ __forceinline__ OutDst out_dest(const ConvArgs &a, int cj) {
-    if (a.out2 && C * cj >= a.out_ca)
-        return OutDst{a.out2, a.out2_cs, C * cj - a.out_ca,
-                      static_cast<size_t>(a.g.ntiles) * a.g.tile_vox * a.out_cs};
-    return OutDst{a.out, a.out_cs, C * cj, 0};
+    if (a.out2 && C * cj >= a.out_ca) return OutDst{a.out2, a.out2_cs, C * cj - a.out_ca};
+    return OutDst{a.out, a.out_cs, C * cj};
 }
 
 // What happens to a finished output value (template parameter RELU of the kernels below).
@@ -143,6 +140,71 @@ __device__ __forceinline__ uint32_t positive_halves(uint32_t v) {
     return ((lo - 1u) < 0x7f80u ? 0x0000ffffu : 0u) | ((hi - 1u) < 0x7f80u ? 0xffff0000u : 0u);
 }
 
+// Partial sums and mask values of one store unit, in vector types that can be operands of the
+// assembly below.
+typedef float pin_t __attribute__((ext_vector_type(4)));
+typedef uint32_t mask_t __attribute__((ext_vector_type(2)));
+
+// Side loads: loads that the compiler does not see.  Whenever a register filled by an ordinary global load
+// is first used, the compiler drains the vector-memory queue far enough for that load - and, since it
+// cannot order the staging loads (which write LDS, or are assembly themselves) against it, in effect the
+// whole queue: s_waitcnt vmcnt(0) or nearly so, once per plane step, with three planes of staging loads in
+// flight.  Every kernel that reads partial sums or a mask paid a full memory latency per step for it.
+// Where registers allow, those values are therefore fetched by assembly at the START of the step BEFORE the
+// one that uses them, into a second set of registers.  Vector-memory operations complete in issue order and
+// a step issues its staging loads and stores after them, so the wait that ends every step (at most
+// (DIST - 1) * LOADS operations outstanding) already covers them: the registers pass through that wait as
+// operands (side_fence), nothing reads them earlier, and they hold their data at every block boundary, where
+// the compiler is free to copy them.  The step that uses them needs no wait at all.  Marches over ragged
+// patches, whose loads are predicated, keep the ordinary loads.
+__device__ __forceinline__ void side_load(pin_t &d, const float *p) {
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(d) : "v"(p) : "memory");
+}
+__device__ __forceinline__ void side_load(mask_t &d, const uint16_t *p) {
+    asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(d) : "v"(p) : "memory");
+}
+// The wait of a step's end (NV vector-memory operations may stay outstanding; LG: LDS operations must have
+// finished as well) with the side registers as operands.
+#define SP3D_SIDE8(a) "+v"(a[0][0]), "+v"(a[0][1]), "+v"(a[0][2]), "+v"(a[0][3]), "+v"(a[1][0]), "+v"(a[1][1]), \
+                      "+v"(a[1][2]), "+v"(a[1][3])
+template <int NV, bool LG, bool PINS, bool MASK>
+__device__ __forceinline__ void side_fence(pin_t (&p)[2][4], mask_t (&m)[2][4]) {
+    if (LG) {
+        if (PINS && MASK) asm volatile("s_waitcnt vmcnt(%16) lgkmcnt(0)" : SP3D_SIDE8(p), SP3D_SIDE8(m) : "n"(NV) : "memory");
+        else if (PINS) asm volatile("s_waitcnt vmcnt(%8) lgkmcnt(0)" : SP3D_SIDE8(p) : "n"(NV) : "memory");
+        else if (MASK) asm volatile("s_waitcnt vmcnt(%8) lgkmcnt(0)" : SP3D_SIDE8(m) : "n"(NV) : "memory");
+        else asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(NV) : "memory");
+    } else {
+        if (PINS && MASK) asm volatile("s_waitcnt vmcnt(%16)" : SP3D_SIDE8(p), SP3D_SIDE8(m) : "n"(NV) : "memory");
+        else if (PINS) asm volatile("s_waitcnt vmcnt(%8)" : SP3D_SIDE8(p) : "n"(NV) : "memory");
+        else if (MASK) asm volatile("s_waitcnt vmcnt(%8)" : SP3D_SIDE8(m) : "n"(NV) : "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NV) : "memory");
+    }
+}
+#undef SP3D_SIDE8
+// What a kernel variant fetches per store unit besides its operands, and whether it does so by side loads.
+// Measured: the mask gains from them (3-D 32 -> 32 at 512^3: 7.45 -> 7.08 ms; 2-D: 8 - 9 %) except in the 3-D
+// two-chunk kernel, whose registers are all taken (4.07 -> 4.71 ms with them); the partial sums do not gain
+// (their cost was the access pattern, see part_unit), so they stay ordinary loads.
+template <int MODE, int RELU, int KD, bool PAIR> struct Side {
+    static constexpr bool PINS = MODE == kMiddle || MODE == kLast;
+    static constexpr bool MASK = RELU == kMask && (MODE == kSingle || MODE == kLast);
+    static constexpr bool ASYNC = MASK && !PINS && (KD == 1 || !PAIR);
+};
+// Role of a step in the chain of side loads.
+enum SideStep { kSideNone = 0,     // no side loads (nothing to fetch, or a ragged patch)
+                kSideFetch = 1,    // fetch for the next step, nothing to use yet
+                kSideUse = 2 };    // use what the previous step fetched, fetch for the next
+
+// fp32 partial sums between the launches of a layer are kept in FRAGMENT order, not in the layout of the
+// output tensor: every launch of the layer has the same decomposition into workgroups and waves, so a wave
+// reads back exactly what the same wave of the previous launch wrote, and what a wave moves per store unit
+// (64 lanes x 4 channels) is one contiguous kilobyte - lane l at byte 16 l.  (In tensor order the 16 bytes of
+// neighbouring lanes lie a whole voxel record apart, 4 KB at 1024 channels, and a wave-wide access touches 64
+// cache lines; those accesses, not the arithmetic, bounded the launches of wide layers.)  A wave's region
+// holds [plane of the D chunk][row][unit][lane]; part_unit() is the float offset of a unit inside it.
+__device__ __forceinline__ size_t part_unit(int d, int h, int q) { return static_cast<size_t>((d * RH + h) * 4 + q) * 256; }
+
 // Per-wave state of the march that the side work of a step needs.
 template <bool HAS_BIAS>
 struct Ctx {
@@ -153,7 +215,7 @@ struct Ctx {
     char *lds_stage;            // LDS chunk plane this wave fills (ring slot 0)
     uint16_t *obase;            // output address of (plane 0, first row of the wave, this lane)
     const uint16_t *mbase;      // same position in the mask tensor
-    float *pbase;               // same position in the fp32 partial-sum buffer
+    float *pbase;               // this lane's slot in the wave's region of the fp32 partial-sum buffer
     size_t oplane, orow;        // output elements per padded plane / per padded row
     bool okrow[RH];             // row/column of this lane lies inside the tile interior
     float bv[HAS_BIAS ? 16 : 1];
@@ -173,17 +235,17 @@ __device__ __forceinline__ void stage(const Ctx<HAS_BIAS> &c, int dplane, int j,
 
 // Partial sums of 4 channels of row h of plane d written by the previous input chunk.
 template <bool FULL, bool HAS_BIAS>
-__device__ __forceinline__ float4 load_partial(const Ctx<HAS_BIAS> &c, int d, int h, int q) {
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (FULL || c.okrow[h]) v = *reinterpret_cast<const float4 *>(c.pbase + d * c.oplane + h * c.orow + 8 * q);
+__device__ __forceinline__ pin_t load_partial(const Ctx<HAS_BIAS> &c, int d, int h, int q) {
+    pin_t v = pin_t{0.f, 0.f, 0.f, 0.f};
+    if (FULL || c.okrow[h]) v = *reinterpret_cast<const pin_t *>(c.pbase + part_unit(d, h, q));
     return v;
 }
 
 // The 4 mask values that belong to one store unit (fetched at the start of the step, like the partial sums).
 template <bool FULL, bool HAS_BIAS>
-__device__ __forceinline__ uint2 load_mask(const Ctx<HAS_BIAS> &c, int d, int h, int q) {
-    uint2 v = make_uint2(0u, 0u);
-    if (FULL || c.okrow[h]) v = *reinterpret_cast<const uint2 *>(c.mbase + d * c.oplane + h * c.orow + 8 * q);
+__device__ __forceinline__ mask_t load_mask(const Ctx<HAS_BIAS> &c, int d, int h, int q) {
+    mask_t v = mask_t{0u, 0u};
+    if (FULL || c.okrow[h]) v = *reinterpret_cast<const mask_t *>(c.mbase + d * c.oplane + h * c.orow + 8 * q);
     return v;
 }
 
@@ -192,14 +254,14 @@ __device__ __forceinline__ uint2 load_mask(const Ctx<HAS_BIAS> &c, int d, int h,
 // apply ReLU, convert and store bf16 (8 bytes).
 template <int MODE, int RELU, bool FULL, bool HAS_BIAS>
 __device__ __forceinline__ void store_unit(const Ctx<HAS_BIAS> &c, int d, const f32x16 (&s)[RH],
-                                           const float4 (&pin)[RH][4], const uint2 (&mk)[RH][4], int h, int q) {
+                                           const pin_t (&pin)[RH][4], const mask_t (&mk)[RH][4], int h, int q) {
     float v0 = s[h][4 * q], v1 = s[h][4 * q + 1], v2 = s[h][4 * q + 2], v3 = s[h][4 * q + 3];
     if (MODE == kMiddle || MODE == kLast) {
         v0 += pin[h][q].x; v1 += pin[h][q].y; v2 += pin[h][q].z; v3 += pin[h][q].w;
     }
     const size_t at = d * c.oplane + h * c.orow + 8 * q;
     if (MODE == kFirst || MODE == kMiddle) {
-        if (FULL || c.okrow[h]) *reinterpret_cast<float4 *>(c.pbase + at) = make_float4(v0, v1, v2, v3);
+        if (FULL || c.okrow[h]) *reinterpret_cast<float4 *>(c.pbase + part_unit(d, h, q)) = make_float4(v0, v1, v2, v3);
         return;
     }
     if (RELU == kRelu) {
@@ -222,21 +284,36 @@ __device__ __forceinline__ void store_unit(const Ctx<HAS_BIAS> &c, int d, const 
 // consume them.  P = Dp mod 4: output plane Dp-kd lives in slot (P-kd) mod 4, plane Dp-3 in slot (P+1) mod 4.
 // FULL: the patch lies completely inside the tile interior, so stores need no mask (no branches in
 // the step, which lets the scheduler weave the side work between the MFMAs).
-template <int P, bool EPI, int MODE, int RELU, bool FULL, int KD, bool HAS_BIAS>
+// SIDE (see side_load): kSideNone - the step loads its own partial sums / mask values (pin, mk) the ordinary
+// way; otherwise it uses the ones the previous step fetched (kSideUse) and first of all fetches those of the
+// plane that the next step finishes, Dp - 2, into the other set (npin, nmk), which the caller passes through
+// the wait that ends the step.
+template <int P, bool EPI, int MODE, int RELU, bool FULL, int KD, int SIDE, bool HAS_BIAS>
 __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, int lane, const char *lbase,
-                                           const bf16x8 (&wf)[NFRAG], f32x16 (&acc)[4][RH]) {
+                                           const bf16x8 (&wf)[NFRAG], f32x16 (&acc)[4][RH],
+                                           pin_t (&pin)[RH][4], mask_t (&mk)[RH][4],
+                                           pin_t (&npin)[RH][4], mask_t (&nmk)[RH][4]) {
     constexpr int NR = RH + 2;
     constexpr int DONE = (P + 1) & 3;
+    using S = Side<MODE, RELU, KD, false>;
     bf16x8 b[2][NR];
-    float4 pin[RH][4];      // partial sums of the plane being finished (chunks after the first)
-    uint2 mk[RH][4];        // mask values of the plane being finished (RELU == kMask)
-    if (EPI && (MODE == kMiddle || MODE == kLast)) {
+    if (SIDE != kSideNone) {
+#pragma unroll
+        for (int h = 0; h < RH; ++h)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const size_t at = (Dp - 2) * c.oplane + h * c.orow + 8 * q;
+                if (S::PINS) side_load(npin[h][q], c.pbase + part_unit(Dp - 2, h, q));
+                if (S::MASK) side_load(nmk[h][q], c.mbase + at);
+            }
+    }
+    if (SIDE == kSideNone && EPI && S::PINS) {
 #pragma unroll
         for (int h = 0; h < RH; ++h)
 #pragma unroll
             for (int q = 0; q < 4; ++q) pin[h][q] = load_partial<FULL>(c, Dp - 3, h, q);
     }
-    if (EPI && RELU == kMask && (MODE == kSingle || MODE == kLast)) {
+    if (SIDE == kSideNone && EPI && S::MASK) {
 #pragma unroll
         for (int h = 0; h < RH; ++h)
 #pragma unroll
@@ -347,7 +424,8 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
                         od.co + 4 * hi;
     c.obase = od.base + opos;
     c.mbase = a.mask + opos;
-    c.pbase = a.part + od.part_off + opos;
+    // wave `wave` of workgroup `logical`: a region of dchunk planes x RH rows x 4 units x 1 KB
+    c.pbase = a.part + (static_cast<size_t>(logical) * kWaves + wave) * a.dchunk * (RH * 4 * 256) + lane * 4;
 #pragma unroll
     for (int h = 0; h < RH; ++h) c.okrow[h] = h0 + wave * RH + h < bx.bh && w0 + col < bx.bw;
     // the bias is folded into the accumulators: a slot starts from the bias instead of zero
@@ -388,49 +466,69 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
 
     auto march = [&](auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
-        // the first three steps have no finished plane to store (nplanes >= 3 always)
-        plane_step<0, false, MODE, RELU, FULL, KD>(c, 0, lane, lbase, wf, acc);
+        using S = Side<MODE, RELU, KD, false>;
+        // whole patches fetch their partial sums / mask values one step ahead (see side_load): steps with an even
+        // plane index use set A and fetch into set B, odd ones the other way round
+        constexpr bool ASYNC = FULL && S::ASYNC;
+        constexpr int FETCH = ASYNC ? kSideFetch : kSideNone, USE = ASYNC ? kSideUse : kSideNone;
+        pin_t pinA[RH][4], pinB[RH][4];
+        mask_t mkA[RH][4], mkB[RH][4];
+        // (a step with stores issues LOADS + 8 >= (DIST - 1) * LOADS operations after its side loads; the
+        // fetch-only step issues just its LOADS staging loads after them and waits accordingly)
+#define SP3D_STEP_END_SIDE(NV, NP, NM)                                                   \
+    do {                                                                                 \
+        side_fence<NV, false, ASYNC && S::PINS, ASYNC && S::MASK>(NP, NM);               \
+        __builtin_amdgcn_s_barrier();                                                    \
+    } while (0)
+        static_assert(LOADS + 8 >= (DIST - 1) * LOADS, "side loads must be older than what the step-end wait lets stay in flight");
+        // the first three steps have no finished plane to store (nplanes >= 3 always); the third one fetches
+        // what the first store needs
+        plane_step<0, false, MODE, RELU, FULL, KD, kSideNone>(c, 0, lane, lbase, wf, acc, pinA, mkA, pinB, mkB);
         SP3D_STEP_END();
-        plane_step<1, false, MODE, RELU, FULL, KD>(c, 1, lane, lbase + PLANE_BYTES, wf, acc);
+        plane_step<1, false, MODE, RELU, FULL, KD, kSideNone>(c, 1, lane, lbase + PLANE_BYTES, wf, acc, pinA, mkA,
+                                                              pinB, mkB);
         SP3D_STEP_END();
-        plane_step<2, false, MODE, RELU, FULL, KD>(c, 2, lane, lbase + 2 * PLANE_BYTES, wf, acc);
-        SP3D_STEP_END();
+        plane_step<2, false, MODE, RELU, FULL, KD, FETCH>(c, 2, lane, lbase + 2 * PLANE_BYTES, wf, acc, pinA, mkA,
+                                                          pinB, mkB);
+        SP3D_STEP_END_SIDE(ASYNC ? LOADS : (DIST - 1) * LOADS, pinB, mkB);
         // steps 3, 4, 5, 6, 7, ...: planes mod 4 = 3, 0, 1, 2, 3, ...
-#define SP3D_MAIN_STEP(OFF, PHASE)                                                                   \
+#define SP3D_MAIN_STEP(OFF, PHASE, CP, CM, NP, NM)                                                   \
     if (D + (OFF) < nplanes) {                                                                       \
-        plane_step<PHASE, true, MODE, RELU, FULL, KD>(c, D + (OFF), lane, lbase + (PHASE) * PLANE_BYTES, wf, acc); \
-        SP3D_STEP_END();                                                                             \
+        plane_step<PHASE, true, MODE, RELU, FULL, KD, USE>(c, D + (OFF), lane, lbase + (PHASE) * PLANE_BYTES, wf, \
+                                                           acc, CP, CM, NP, NM);                     \
+        SP3D_STEP_END_SIDE((DIST - 1) * LOADS, NP, NM);                                              \
     }
         for (int D = 3; D < nplanes; D += 4) {
-            SP3D_MAIN_STEP(0, 3)
-            SP3D_MAIN_STEP(1, 0)
-            SP3D_MAIN_STEP(2, 1)
-            SP3D_MAIN_STEP(3, 2)
+            SP3D_MAIN_STEP(0, 3, pinB, mkB, pinA, mkA)
+            SP3D_MAIN_STEP(1, 0, pinA, mkA, pinB, mkB)
+            SP3D_MAIN_STEP(2, 1, pinB, mkB, pinA, mkA)
+            SP3D_MAIN_STEP(3, 2, pinA, mkA, pinB, mkB)
         }
 #undef SP3D_MAIN_STEP
-        // the last output plane (dn-1) finished in the last step; it sits in slot (dn-1) mod 4
+#undef SP3D_STEP_END_SIDE
+        // the last output plane (dn-1) finished in the last step; it sits in slot (dn-1) mod 4, and with side
+        // loads the last step (plane index dn + 1, of the parity of dn - 1) fetched its values: into set B if
+        // that index is even
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        float4 pin[RH][4];
-        uint2 mk[RH][4];
-        if (MODE == kMiddle || MODE == kLast) {
+        if (!ASYNC && S::PINS) {
 #pragma unroll
             for (int h = 0; h < RH; ++h)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) pin[h][q] = load_partial<FULL>(c, dn - 1, h, q);
+                for (int q = 0; q < 4; ++q) pinA[h][q] = pinB[h][q] = load_partial<FULL>(c, dn - 1, h, q);
         }
-        if (RELU == kMask && (MODE == kSingle || MODE == kLast)) {
+        if (!ASYNC && S::MASK) {
 #pragma unroll
             for (int h = 0; h < RH; ++h)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) mk[h][q] = load_mask<FULL>(c, dn - 1, h, q);
+                for (int q = 0; q < 4; ++q) mkA[h][q] = mkB[h][q] = load_mask<FULL>(c, dn - 1, h, q);
         }
 #pragma unroll
         for (int s = 0; s < 4; ++s)
             if (s == ((dn - 1) & 3)) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    store_unit<MODE, RELU, FULL>(c, dn - 1, acc[s], pin, mk, 0, q);
-                    store_unit<MODE, RELU, FULL>(c, dn - 1, acc[s], pin, mk, 1, q);
+                    store_unit<MODE, RELU, FULL>(c, dn - 1, acc[s], (s & 1) ? pinA : pinB, (s & 1) ? mkA : mkB, 0, q);
+                    store_unit<MODE, RELU, FULL>(c, dn - 1, acc[s], (s & 1) ? pinA : pinB, (s & 1) ? mkA : mkB, 1, q);
                 }
             }
     };
@@ -504,16 +602,16 @@ __device__ __forceinline__ void stage(const Ctx<HAS_BIAS> &c, int dplane, int j)
 }
 
 template <bool FULL, bool HAS_BIAS>
-__device__ __forceinline__ float4 load_partial(const Ctx<HAS_BIAS> &c, int d, int h, int q) {
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (FULL || c.okrow[h]) v = *reinterpret_cast<const float4 *>(c.pbase + d * c.oplane + h * c.orow + 8 * q);
+__device__ __forceinline__ pin_t load_partial(const Ctx<HAS_BIAS> &c, int d, int h, int q) {
+    pin_t v = pin_t{0.f, 0.f, 0.f, 0.f};
+    if (FULL || c.okrow[h]) v = *reinterpret_cast<const pin_t *>(c.pbase + part_unit(d, h, q));
     return v;
 }
 
 template <bool FULL, bool HAS_BIAS>
-__device__ __forceinline__ uint2 load_mask(const Ctx<HAS_BIAS> &c, int d, int h, int q) {
-    uint2 v = make_uint2(0u, 0u);
-    if (FULL || c.okrow[h]) v = *reinterpret_cast<const uint2 *>(c.mbase + d * c.oplane + h * c.orow + 8 * q);
+__device__ __forceinline__ mask_t load_mask(const Ctx<HAS_BIAS> &c, int d, int h, int q) {
+    mask_t v = mask_t{0u, 0u};
+    if (FULL || c.okrow[h]) v = *reinterpret_cast<const mask_t *>(c.mbase + d * c.oplane + h * c.orow + 8 * q);
     return v;
 }
 
@@ -522,7 +620,7 @@ __device__ __forceinline__ uint2 load_mask(const Ctx<HAS_BIAS> &c, int d, int h,
 // convert / store bf16
 template <int MODE, int RELU, bool FULL, bool HAS_BIAS>
 __device__ __forceinline__ void finish_unit(const Ctx<HAS_BIAS> &c, int d, const f32x16 (&s)[RH], const char *red,
-                                            const float4 (&pin)[RH][4], const uint2 (&mk)[RH][4], int h, int q) {
+                                            const pin_t (&pin)[RH][4], const mask_t (&mk)[RH][4], int h, int q) {
     const float4 o = *reinterpret_cast<const float4 *>(red + (h * 4 + q) * 1024);
     float v0 = s[h][4 * q] + o.x, v1 = s[h][4 * q + 1] + o.y, v2 = s[h][4 * q + 2] + o.z, v3 = s[h][4 * q + 3] + o.w;
     if (MODE == kMiddle || MODE == kLast) {
@@ -530,7 +628,7 @@ __device__ __forceinline__ void finish_unit(const Ctx<HAS_BIAS> &c, int d, const
     }
     const size_t at = d * c.oplane + h * c.orow + 8 * q;
     if (MODE == kFirst || MODE == kMiddle) {
-        if (FULL || c.okrow[h]) *reinterpret_cast<float4 *>(c.pbase + at) = make_float4(v0, v1, v2, v3);
+        if (FULL || c.okrow[h]) *reinterpret_cast<float4 *>(c.pbase + part_unit(d, h, q)) = make_float4(v0, v1, v2, v3);
         return;
     }
     if (RELU == kRelu) {
@@ -555,25 +653,40 @@ __device__ __forceinline__ void give_unit(const f32x16 (&s)[RH], char *red, int 
 // ROLE 1 (chunk 1): GIVE = plane Dp - 3 (slot (P + 2) mod 5) goes to the hand-over buffer Dp & 1 and its
 // slot is cleared.  ROLE 0 (chunk 0): FIN = plane Dp - 4 (slot (P + 1) mod 5) is finished from the buffer
 // written in the previous step, (Dp - 1) & 1, and its slot returns to the bias.
-template <int P, int ROLE, bool GIVE, bool FIN, int MODE, int RELU, bool FULL, int KD, bool HAS_BIAS>
+// SIDE (chunk-0 wave; see side_load): kSideNone - the step loads its own partial sums / mask values (pin, mk)
+// the ordinary way; otherwise it uses the ones the previous step fetched (kSideUse) and first of all fetches
+// those of the plane that the next step finishes, Dp - 3, into the other set (npin, nmk), which the caller
+// passes through the wait that ends the step.
+template <int P, int ROLE, bool GIVE, bool FIN, int MODE, int RELU, bool FULL, int KD, int SIDE, bool HAS_BIAS>
 __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const char *lbase,
-                                           const bf16x8 (&wf)[NFRAG], f32x16 (&acc)[NSLOT][RH]) {
+                                           const bf16x8 (&wf)[NFRAG], f32x16 (&acc)[NSLOT][RH],
+                                           pin_t (&pin)[RH][4], mask_t (&mk)[RH][4],
+                                           pin_t (&npin)[RH][4], mask_t (&nmk)[RH][4]) {
     constexpr int NR = RH + 2;
-    constexpr int SIDE = ROLE == 1 ? (P + 2) % NSLOT : (P + 1) % NSLOT;     // slot of the side work
+    constexpr int SSLOT = ROLE == 1 ? (P + 2) % NSLOT : (P + 1) % NSLOT;     // slot of the side work
     constexpr int NEXT = (P + 1) % NSLOT;      // slot of output plane Dp + 1: must be clean when this step ends
     constexpr bool ACTIVE = ROLE == 1 ? GIVE : FIN;
+    using S = Side<MODE, RELU, KD, true>;
     bf16x8 b[2][NR];
     char *red_w = c.red + (Dp & 1) * RED_BYTES;
     const char *red_r = c.red + ((Dp - 1) & 1) * RED_BYTES;
-    float4 pin[RH][4];
-    uint2 mk[RH][4];
-    if (ROLE == 0 && FIN && (MODE == kMiddle || MODE == kLast)) {
+    if (ROLE == 0 && SIDE != kSideNone) {
+#pragma unroll
+        for (int h = 0; h < RH; ++h)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const size_t at = (Dp - 3) * c.oplane + h * c.orow + 8 * q;
+                if (S::PINS) side_load(npin[h][q], c.pbase + part_unit(Dp - 3, h, q));
+                if (S::MASK) side_load(nmk[h][q], c.mbase + at);
+            }
+    }
+    if (SIDE == kSideNone && ROLE == 0 && FIN && S::PINS) {
 #pragma unroll
         for (int h = 0; h < RH; ++h)
 #pragma unroll
             for (int q = 0; q < 4; ++q) pin[h][q] = load_partial<FULL>(c, Dp - 4, h, q);
     }
-    if (ROLE == 0 && FIN && RELU == kMask && (MODE == kSingle || MODE == kLast)) {
+    if (SIDE == kSideNone && ROLE == 0 && FIN && S::MASK) {
 #pragma unroll
         for (int h = 0; h < RH; ++h)
 #pragma unroll
@@ -598,11 +711,11 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const
         if (gi < 4) {
             if (ACTIVE) {
                 if (ROLE == 1) {
-                    give_unit(acc[SIDE], red_w, 0, gi);
-                    give_unit(acc[SIDE], red_w, 1, gi);
+                    give_unit(acc[SSLOT], red_w, 0, gi);
+                    give_unit(acc[SSLOT], red_w, 1, gi);
                 } else {
-                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SIDE], red_r, pin, mk, 0, gi);
-                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SIDE], red_r, pin, mk, 1, gi);
+                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], red_r, pin, mk, 0, gi);
+                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], red_r, pin, mk, 1, gi);
                 }
             }
         } else {
@@ -611,7 +724,7 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 acc[NEXT][gi - 4][i] = (ROLE == 0 && HAS_BIAS) ? c.bv[HAS_BIAS ? i : 0] : 0.f;
-                if (ROLE == 1 && GIVE) acc[SIDE][gi - 4][i] = 0.f;
+                if (ROLE == 1 && GIVE) acc[SSLOT][gi - 4][i] = 0.f;
             }
         }
 #pragma unroll
@@ -640,29 +753,42 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const
 // The two steps after the last input plane: only the side work is left.  Dp = nplanes: chunk 1 hands over
 // the last output plane (Dp - 3 = dn - 1), chunk 0 finishes plane Dp - 4; Dp = nplanes + 1: chunk 0 finishes
 // the last plane.  Same slot arithmetic as plane_step, so every accumulator index stays a constant.
-template <int P, int ROLE, bool GIVE, bool FIN, int MODE, int RELU, bool FULL, bool HAS_BIAS>
-__device__ __forceinline__ void drain_step(const Ctx<HAS_BIAS> &c, int Dp, f32x16 (&acc)[NSLOT][RH]) {
-    constexpr int SIDE = ROLE == 1 ? (P + 2) % NSLOT : (P + 1) % NSLOT;
+template <int P, int ROLE, bool GIVE, bool FIN, int MODE, int RELU, bool FULL, int KD, int SIDE, bool HAS_BIAS>
+__device__ __forceinline__ void drain_step(const Ctx<HAS_BIAS> &c, int Dp, f32x16 (&acc)[NSLOT][RH],
+                                           pin_t (&pin)[RH][4], mask_t (&mk)[RH][4],
+                                           pin_t (&npin)[RH][4], mask_t (&nmk)[RH][4]) {
+    constexpr int SSLOT = ROLE == 1 ? (P + 2) % NSLOT : (P + 1) % NSLOT;
+    using S = Side<MODE, RELU, KD, true>;
+    // side loads: the first drain step, and a step 3 that is one already (a march of three planes), fetch for
+    // the step after them like a plane step
+    if (ROLE == 0 && SIDE != kSideNone && Dp <= c.nplanes) {
+#pragma unroll
+        for (int h = 0; h < RH; ++h)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const size_t at = (Dp - 3) * c.oplane + h * c.orow + 8 * q;
+                if (S::PINS) side_load(npin[h][q], c.pbase + part_unit(Dp - 3, h, q));
+                if (S::MASK) side_load(nmk[h][q], c.mbase + at);
+            }
+    }
     if (ROLE == 1) {
         if (GIVE && Dp == c.nplanes) {
             char *red_w = c.red + (Dp & 1) * RED_BYTES;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                give_unit(acc[SIDE], red_w, 0, q);
-                give_unit(acc[SIDE], red_w, 1, q);
+                give_unit(acc[SSLOT], red_w, 0, q);
+                give_unit(acc[SSLOT], red_w, 1, q);
             }
         }
     } else if (FIN) {
         const char *red_r = c.red + ((Dp - 1) & 1) * RED_BYTES;
-        float4 pin[RH][4];
-        uint2 mk[RH][4];
-        if (MODE == kMiddle || MODE == kLast) {
+        if (SIDE == kSideNone && S::PINS) {
 #pragma unroll
             for (int h = 0; h < RH; ++h)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) pin[h][q] = load_partial<FULL>(c, Dp - 4, h, q);
         }
-        if (RELU == kMask && (MODE == kSingle || MODE == kLast)) {
+        if (SIDE == kSideNone && S::MASK) {
 #pragma unroll
             for (int h = 0; h < RH; ++h)
 #pragma unroll
@@ -670,15 +796,15 @@ __device__ __forceinline__ void drain_step(const Ctx<HAS_BIAS> &c, int Dp, f32x1
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SIDE], red_r, pin, mk, 0, q);
-            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SIDE], red_r, pin, mk, 1, q);
+            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], red_r, pin, mk, 0, q);
+            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], red_r, pin, mk, 1, q);
         }
     }
 }
 
 template <int ROLE, int MODE, bool HAS_BIAS, int RELU, int KD>
-__device__ __forceinline__ void run(const ConvArgs &a, char *lds, int tile, const TileBox &bx, int d0, int h0, int w0,
-                                    int dn, int cj, int rg) {
+__device__ __forceinline__ void run(const ConvArgs &a, char *lds, int logical, int tile, const TileBox &bx, int d0,
+                                    int h0, int w0, int dn, int cj, int rg) {
     const Geo &g = a.g;
     const int lane = threadIdx.x & 63;
     const int col = lane & 31, hi = lane >> 5;
@@ -718,7 +844,8 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int tile, cons
                         od.co + 4 * hi;
     c.obase = od.base + opos;
     c.mbase = a.mask + opos;
-    c.pbase = a.part + od.part_off + opos;
+    // the chunk-0 wave of row group rg of workgroup `logical`: dchunk planes x RH rows x 4 units x 1 KB
+    c.pbase = a.part + (static_cast<size_t>(logical) * NRG + rg) * a.dchunk * (RH * 4 * 256) + lane * 4;
 #pragma unroll
     for (int h = 0; h < RH; ++h) c.okrow[h] = h0 + rg * RH + h < bx.bh && w0 + col < bx.bw;
     if (HAS_BIAS) {
@@ -755,33 +882,64 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int tile, cons
 
     auto march = [&](auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
-        plane_step<0, ROLE, false, false, MODE, RELU, FULL, KD>(c, 0, lbase, wf, acc);
+        using S = Side<MODE, RELU, KD, true>;
+        // whole patches: the chunk-0 wave fetches its partial sums / mask values one step ahead (see side_load),
+        // alternating between two sets of registers
+        constexpr bool ASYNC = FULL && ROLE == 0 && S::ASYNC;
+        constexpr int FETCH = ASYNC ? kSideFetch : kSideNone, USE = ASYNC ? kSideUse : kSideNone;
+        pin_t pinA[RH][4], pinB[RH][4];
+        mask_t mkA[RH][4], mkB[RH][4];
+        // A step that finishes a plane issues LOADS + 8 operations after its side loads, which the wait at its
+        // end lets stay in flight; a fetch-only step issues just its staging loads after them and waits
+        // accordingly; a drain step issues no staging loads and waits for everything.
+        static_assert(LOADS + 8 >= (DIST - 1) * LOADS, "side loads must be older than what the step-end wait lets stay in flight");
+#define SP3D_STEP_END_SIDE(NV, NP, NM)                                              \
+    do {                                                                            \
+        side_fence<NV, true, ASYNC && S::PINS, ASYNC && S::MASK>(NP, NM);           \
+        __builtin_amdgcn_s_barrier();                                               \
+    } while (0)
+        plane_step<0, ROLE, false, false, MODE, RELU, FULL, KD, kSideNone>(c, 0, lbase, wf, acc, pinA, mkA, pinB, mkB);
         SP3D_STEP_END();
-        plane_step<1, ROLE, false, false, MODE, RELU, FULL, KD>(c, 1, lbase + PLANE_BYTES, wf, acc);
+        plane_step<1, ROLE, false, false, MODE, RELU, FULL, KD, kSideNone>(c, 1, lbase + PLANE_BYTES, wf, acc, pinA, mkA,
+                                                                          pinB, mkB);
         SP3D_STEP_END();
-        plane_step<2, ROLE, false, false, MODE, RELU, FULL, KD>(c, 2, lbase + 2 * PLANE_BYTES, wf, acc);
+        plane_step<2, ROLE, false, false, MODE, RELU, FULL, KD, kSideNone>(c, 2, lbase + 2 * PLANE_BYTES, wf, acc, pinA,
+                                                                          mkA, pinB, mkB);
         SP3D_STEP_END();
         // Steps 3, 4, ... with slot phase Dp mod 5 as a compile-time constant (the ring slot Dp mod 4 is a
         // run-time offset: a period of 20 steps would be needed to make both constants).  The march runs two
-        // steps past the last input plane; those only hand over / finish what is left.
-#define SP3D_STEP(DP, PHASE, GIVE_EN, FIN_EN)                                                              \
+        // steps past the last input plane; those only hand over / finish what is left.  Step 3 is the first
+        // to hand a plane over (and fetches the side values of step 4), step 4 the first to finish one.
+#define SP3D_STEP(DP, PHASE, GIVE_EN, FIN_EN, SIDE_EN, CP, CM, NP, NM)                                     \
     if ((DP) < nplanes) {                                                                                  \
-        plane_step<PHASE, ROLE, GIVE_EN, FIN_EN, MODE, RELU, FULL, KD>(c, (DP), lbase + ((DP) % NBUF) * PLANE_BYTES, \
-                                                                   wf, acc);                              \
-        SP3D_STEP_END();                                                                                   \
+        plane_step<PHASE, ROLE, GIVE_EN, FIN_EN, MODE, RELU, FULL, KD, SIDE_EN>(                           \
+            c, (DP), lbase + ((DP) % NBUF) * PLANE_BYTES, wf, acc, CP, CM, NP, NM);                        \
+        SP3D_STEP_END_SIDE(((SIDE_EN) == kSideFetch ? LOADS : (DIST - 1) * LOADS), NP, NM);                \
     } else if ((DP) < nplanes + 2) {                                                                       \
-        drain_step<PHASE, ROLE, GIVE_EN, FIN_EN, MODE, RELU, FULL>(c, (DP), acc);                          \
-        SP3D_STEP_END();                                                                                   \
+        drain_step<PHASE, ROLE, GIVE_EN, FIN_EN, MODE, RELU, FULL, KD, SIDE_EN>(c, (DP), acc, CP, CM, NP, NM); \
+        SP3D_STEP_END_SIDE(((SIDE_EN) == kSideNone ? (DIST - 1) * LOADS : 0), NP, NM);                     \
     }
-        SP3D_STEP(3, 3, true, false)
-        for (int D = 4; D < nplanes + 2; D += NSLOT) {
-            SP3D_STEP(D, 4, true, true)
-            SP3D_STEP(D + 1, 0, true, true)
-            SP3D_STEP(D + 2, 1, true, true)
-            SP3D_STEP(D + 3, 2, true, true)
-            SP3D_STEP(D + 4, 3, true, true)
+        SP3D_STEP(3, 3, true, false, FETCH, pinA, mkA, pinB, mkB)
+        SP3D_STEP(4, 4, true, true, USE, pinB, mkB, pinA, mkA)
+        for (int D = 5; D < nplanes + 2; D += NSLOT) {
+            SP3D_STEP(D, 0, true, true, USE, pinA, mkA, pinB, mkB)
+            SP3D_STEP(D + 1, 1, true, true, USE, pinB, mkB, pinA, mkA)
+            SP3D_STEP(D + 2, 2, true, true, USE, pinA, mkA, pinB, mkB)
+            SP3D_STEP(D + 3, 3, true, true, USE, pinB, mkB, pinA, mkA)
+            SP3D_STEP(D + 4, 4, true, true, USE, pinA, mkA, pinB, mkB)
+            // five steps per round: the sets have changed roles
+            if (ASYNC) {
+#pragma unroll
+                for (int h = 0; h < RH; ++h)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const pin_t tp = pinA[h][q]; pinA[h][q] = pinB[h][q]; pinB[h][q] = tp;
+                        const mask_t tm = mkA[h][q]; mkA[h][q] = mkB[h][q]; mkB[h][q] = tm;
+                    }
+            }
         }
 #undef SP3D_STEP
+#undef SP3D_STEP_END_SIDE
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // clamped staging loads of the last steps
     };
     if (h0 + PH <= bx.bh && w0 + PW <= bx.bw) march(std::true_type{});
@@ -808,8 +966,8 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_pair_kernel(ConvArgs a)
     if (dn <= 0 || h0 >= bx.bh || w0 >= bx.bw) return;     // patch of the largest box that this tile's box lacks
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // two copies of the march, one per role, so that each is straight-line code for the scheduler
-    if (wave < 2) run<0, MODE, HAS_BIAS, RELU, KD>(a, lds, tile, bx, d0, h0, w0, dn, cj, wave & 1);
-    else run<1, MODE, HAS_BIAS, RELU, KD>(a, lds, tile, bx, d0, h0, w0, dn, cj, wave & 1);
+    if (wave < 2) run<0, MODE, HAS_BIAS, RELU, KD>(a, lds, logical, tile, bx, d0, h0, w0, dn, cj, wave & 1);
+    else run<1, MODE, HAS_BIAS, RELU, KD>(a, lds, logical, tile, bx, d0, h0, w0, dn, cj, wave & 1);
 }
 
 }  // namespace wide
@@ -825,13 +983,37 @@ static size_t pack_bytes(int ki, int ko) {
     return static_cast<size_t>(ki / C) * (ko / C) * NFRAG * 64 * 16;
 }
 
+// How a layer is cut into workgroups (the same for every launch of the layer).
+struct PatchPlan { int nh, nw, dchunk, nd; long long nblocks; bool pairs; };
+static PatchPlan plan_patches(const Geo &g, int ki, int ko) {
+    PatchPlan p;
+    const int nco = ko / C;
+    // input channels in multiples of 64: two chunks per launch, summed on chip (4-row patches)
+    p.pairs = ki % (2 * C) == 0;
+    const int ph = p.pairs ? wide::PH : PH;
+    // patches cover the largest output box of the grid (the interior grown on both sides)
+    const int ed = g.td + 2 * grow_d(g), eh = g.th + 2 * g.grow, ew = g.tw + 2 * g.grow;
+    p.nh = (eh + ph - 1) / ph;
+    p.nw = (ew + PW - 1) / PW;
+    // D chunk: whole box depth unless that leaves the chip short of workgroups
+    const long long base = 1LL * g.ntiles * p.nh * p.nw * nco;
+    int dchunk = ed;
+    while (base * ((ed + dchunk - 1) / dchunk) < 1024 && dchunk > 16) dchunk = (dchunk + 1) / 2;
+    p.dchunk = dchunk;
+    p.nd = (ed + dchunk - 1) / dchunk;
+    p.nblocks = base * p.nd;
+    return p;
+}
+
 // workspace: packed weight fragments, then (layers that need more than one launch: more than one input
-// chunk, or more than one pair of chunks when Cin is a multiple of 64) fp32 partial sums laid out like the
-// output tensor
+// chunk, or more than one pair of chunks when Cin is a multiple of 64) the fp32 partial sums: per workgroup
+// and wave that stores results, dchunk planes x RH rows x 4 units x 1 KB (see part_unit)
 size_t conv_mfma_ws_bytes(const Geo &g, int ki, int ko) {
     size_t n = pack_bytes(ki, ko);
-    const int launches = ki % (2 * C) == 0 ? ki / (2 * C) : ki / C;
-    if (launches > 1) n += static_cast<size_t>(g.ntiles) * g.tile_vox * ko * sizeof(float);
+    const PatchPlan p = plan_patches(g, ki, ko);
+    const int launches = p.pairs ? ki / (2 * C) : ki / C;
+    if (launches > 1)
+        n += static_cast<size_t>(p.nblocks) * (p.pairs ? wide::NRG : kWaves) * p.dchunk * (RH * 4 * 256 * sizeof(float));
     return n;
 }
 
@@ -876,20 +1058,13 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
         if (in_b && c0 >= in_ca) { *base = in_b; *cs = ki - in_ca; *co = c0 - in_ca; }
         else { *base = in_a; *cs = in_b ? in_ca : ki; *co = c0; }
     };
-    // input channels in multiples of 64: two chunks per launch, summed on chip (4-row patches)
-    const bool pairs = ki % (2 * C) == 0;
-    const int ph = pairs ? wide::PH : PH;
-    // patches cover the largest output box of the grid (the interior grown on both sides)
-    const int ed = g.td + 2 * grow_d(g), eh = g.th + 2 * g.grow, ew = g.tw + 2 * g.grow;
-    a.nh = (eh + ph - 1) / ph;
-    a.nw = (ew + PW - 1) / PW;
-    // D chunk: whole box depth unless that leaves the chip short of workgroups
-    long long base = 1LL * g.ntiles * a.nh * a.nw * nco;
-    int dchunk = ed;
-    while (base * ((ed + dchunk - 1) / dchunk) < 1024 && dchunk > 16) dchunk = (dchunk + 1) / 2;
-    a.dchunk = dchunk;
-    a.nd = (ed + dchunk - 1) / dchunk;
-    const long long nb = base * a.nd;
+    const PatchPlan pl = plan_patches(g, ki, ko);
+    const bool pairs = pl.pairs;
+    a.nh = pl.nh;
+    a.nw = pl.nw;
+    a.dchunk = pl.dchunk;
+    a.nd = pl.nd;
+    const long long nb = pl.nblocks;
     if (nb > 0x7ffffff0LL) return SP_EGEOM;
     a.nblocks = static_cast<int>(nb);
     const unsigned grid = static_cast<unsigned>((nb + 7) / 8 * 8);

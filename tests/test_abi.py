@@ -200,10 +200,16 @@ def test_workspace_sizes_of_the_kernel_families():
     frag = 27 * 2 * 64 * 16                                    # packed weight fragments of one 32x32 pair
     assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 32, 32, sp3d.SP_BF16) == frag
     assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 32, 64, sp3d.SP_BF16) == 2 * frag      # one input chunk: no partials
-    padded64 = sp3d.sp_padded_elems(g, 64)
+    # fp32 partial sums between the launches of a layer: one value per output element of the patches that cover the
+    # tiles (here whole patches: the 128^3 interior voxels), 64 output channels
+    partial64 = 4 * 128 ** 3 * 64
     assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 64, 64, sp3d.SP_BF16) == 4 * frag              # one pair of chunks
-    assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 96, 64, sp3d.SP_BF16) == 6 * frag + 4 * padded64   # three launches
-    assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 128, 64, sp3d.SP_BF16) == 8 * frag + 4 * padded64  # two pairs
+    assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 96, 64, sp3d.SP_BF16) == 6 * frag + partial64   # three launches
+    assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 128, 64, sp3d.SP_BF16) == 8 * frag + partial64  # two pairs
+    # ragged tiles: patches of 8 x 32 (one chunk per launch) or 4 x 32 (pairs) voxels are stored whole
+    r = sp3d.Geom(1, (4, 10, 40), (1, 1, 1))
+    assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, r, 96, 32, sp3d.SP_BF16) == 3 * frag + 4 * 4 * 16 * 64 * 32
+    assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, r, 128, 32, sp3d.SP_BF16) == 4 * frag + 4 * 4 * 12 * 64 * 32
     assert sp3d.sp_workspace_bytes(sp3d.SP_OP_DGRAD, g, 32, 64, sp3d.SP_BF16) == 2 * frag           # the kernel's input is dz
     assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 1, 32, sp3d.SP_BF16) == 0               # first-layer kernel
     assert sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g, 8, 16, sp3d.SP_F32) == 0                # direct kernel
