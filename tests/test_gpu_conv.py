@@ -252,3 +252,52 @@ def test_two_tensor_variants_reject_what_they_cannot_do():
     with pytest.raises(sp3d.Sp3dError) as e:
         sp3d.conv3d_fwd2(a, 16, a, 16, w, None, y, g, 32, sp3d.SP_BF16, 0, None)
     assert e.value.code == sp3d.SP_EUNSUPPORTED
+
+
+@pytest.mark.parametrize("d", [1, 2, 3, 4, 5, 6, 7, 9])
+@pytest.mark.parametrize("cin,cout,flat", [(32, 32, 0), (64, 64, 0), (32, 32, 1), (64, 64, 1), (96, 32, 0), (128, 32, 1),
+                                           (32, 96, 1), (32, 128, 0)])
+def test_every_march_length_with_mask_and_partial_sums(d, cin, cout, flat):
+    """Whole patches (the marches that fetch mask values a step ahead into alternating register sets, and keep
+    partial sums in fragment order) for every length of the D march modulo the slot and set periods: the masked
+    data gradient equals the plain one followed by the mask, bit for bit, and the oracle within tolerance; layers
+    with several launches (96 and 128 kernel input channels, in the forward pass or - with the mask in the last
+    launch - in the data gradient) match the oracle too."""
+    n, dhw, grid = 1, (d, 8, 32), (1, 1, 1)
+    g = sp3d.Geom(n, dhw, grid, 1, 0, flat)
+    dt = DT["bf16"]
+    ws = sp3d.alloc_ws(max(sp3d.sp_workspace_bytes(op, g, cin, cout, dt) for op in (sp3d.SP_OP_FWD, sp3d.SP_OP_DGRAD)))
+    taps = (3, 3) if flat else (3, 3, 3)
+    x = draw("bf16", (n,) + dhw + (cin,), 31)
+    dz = draw("bf16", (n,) + dhw + (cout,), 32)
+    w = synth.weights(cin, cout, 33, "bf16", taps=taps)
+    xr = np.where(widen(x) > 0, x, np.zeros_like(x))
+
+    def padded(V, c):
+        P = sp3d.alloc_padded(g, c, dt)
+        sp3d.sp_partition(to_dev(V), P, g, c, dt)
+        sp3d.sp_halo_exchange(P, g, c, dt)
+        return P
+
+    def volume(P, c):
+        V = torch.empty((n,) + dhw + (c,), dtype=P.dtype, device="cuda")
+        sp3d.sp_unpartition(P, V, g, c, dt)
+        return V
+
+    if flat:
+        from oracle import flat as O2
+        ref_y = O2.conv_fwd(widen(x), widen(w), relu=True)
+        ref_dx = O2.conv_dgrad(widen(dz), widen(w))
+    else:
+        ref_y = conv3d.conv3d_fwd(x, widen(w), None, True)
+        ref_dx = conv3d.conv3d_dgrad(dz, widen(w))
+    Px, Pz, Pm = padded(x, cin), padded(dz, cout), padded(xr, cin)
+    Py = sp3d.alloc_padded(g, cout, dt)
+    sp3d.conv3d_fwd(Px, to_dev(w), None, Py, g, cin, cout, dt, sp3d.SP_FLAG_RELU, ws)
+    assert rel_err(f64(volume(Py, cout)), ref_y) <= TOL["bf16"]
+    Pd, Pf = sp3d.alloc_padded(g, cin, dt), sp3d.alloc_padded(g, cin, dt)
+    sp3d.conv3d_dgrad(Pz, to_dev(w), Pd, g, cin, cout, dt, ws)
+    sp3d.conv3d_dgrad_relu(Pz, to_dev(w), Pm, Pf, g, cin, cout, dt, ws)
+    plain, fused = volume(Pd, cin), volume(Pf, cin)
+    assert rel_err(f64(plain), ref_dx) <= TOL["bf16"]
+    assert torch.equal(fused, torch.where(to_dev(xr).float() > 0, plain, torch.zeros_like(plain)))
