@@ -324,7 +324,7 @@ def main():
     # ---- CPU baseline: the fp64 oracle, as it stands, on a bounded sample of the same workload ----
     if not args.no_cpu_baseline:
         from oracle import conv3d as oc
-        b = min(96, S)
+        b = min(112, S)          # about 11 s of oracle work on 16 host cores
         xs = np.ascontiguousarray(x_h[:, :b, :b, :b])
         dys = np.ascontiguousarray(dy_h[:, :b, :b, :b])
         w64 = synth.bf16_bits_to_f32(w_h).astype(np.float64)
