@@ -93,7 +93,9 @@ enum {                                                    /* sp_workspace_bytes 
 size_t sp_padded_elems(const sp_geom_t *g, int c);
 size_t sp_msg_elems(const sp_geom_t *g, int c);
 /* Bytes of scratch the convolution `op` needs for these sizes (may be 0); (size_t)-1 if the
- * combination is invalid or unsupported. */
+ * combination is invalid or unsupported.  The size depends on the whole geometry (`grow` and `flat`
+ * included): ask with the geometry that the call will get.  What a call leaves in the workspace is
+ * of no use to the caller. */
 size_t sp_workspace_bytes(int op, const sp_geom_t *g, int cin, int cout, sp_dtype_t dt);
 /* SP_OK or the error the geometry would raise. */
 int sp_check_geom(const sp_geom_t *g);
