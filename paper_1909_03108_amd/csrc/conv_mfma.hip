@@ -83,7 +83,24 @@ struct ConvArgs {
     int dchunk;             // output planes per workgroup
     int nd, nh, nw;         // patches per tile along D, H, W
     int nblocks;            // real workgroups (grid is rounded up to a multiple of 8)
+    int fold, fold_w;       // 2-D variant, tiles narrower than half a patch: `fold` consecutive slices lie side by
+                            // side in a patch, each in a strip of fold_w = box width + 2 columns (fold = 1: none)
 };
+
+// Slices side by side (2-D variant).  A tile of 8 x 8 voxels fills a quarter of the 32 columns that the MFMAs of a
+// patch compute.  Slices do not interact, so `fold` of them share a patch: strip s of the staged plane holds
+// columns 0 .. box width + 1 of slice s, and a plane step handles `fold` slices at once (output columns whose
+// 3-column window straddles two strips are computed and dropped).  Only per-lane offsets change: the source
+// offsets of the staging loads, the output / mask position of a lane, and the strides of a step; the kernels'
+// marches are untouched.  Staged "plane" G then means slices F (G - 1) + 1 + s of the chunk (in padded
+// coordinates), so that plane G still feeds output step G - 1; planes 0 and the last, which feed no output,
+// are clamped to their neighbours instead of reaching outside the tile.
+struct FoldCol { int s, c; };      // strip and column inside it
+__device__ __forceinline__ FoldCol fold_col(int col, int fold, int fold_w) {
+    if (fold == 1) return FoldCol{0, col};
+    const int s = col / fold_w;
+    return FoldCol{s, col - s * fold_w};
+}
 
 // Pre-swizzle the weights into MFMA A-fragment order.  wpack[chunk i][block j][tap][half][lane] = the 8
 // input channels k = 32i + 16*half + 8*(lane/32) + e of output channel m = 32j + lane%32.
@@ -211,6 +228,7 @@ struct Ctx {
     const uint16_t *tin0;       // first padded input plane of this workgroup's D chunk (at the chunk's channels)
     size_t plane_elems;         // input elements per padded plane of the tile
     int nplanes;                // input planes of the chunk (output planes + 2)
+    int plo, phi;               // staged planes are clamped to [plo, phi] (slices side by side: the outer two are not real)
     int goff[LOADS];            // per-lane source offsets of the staging loads (elements)
     char *lds_stage;            // LDS chunk plane this wave fills (ring slot 0)
     uint16_t *obase;            // output address of (plane 0, first row of the wave, this lane)
@@ -226,7 +244,7 @@ struct Ctx {
 // one needed are clamped (their ring slot is never read), so every step issues exactly LOADS loads.
 template <bool HAS_BIAS>
 __device__ __forceinline__ void stage(const Ctx<HAS_BIAS> &c, int dplane, int j, int lane) {
-    const uint16_t *p = c.tin0 + min(dplane, c.nplanes - 1) * c.plane_elems;
+    const uint16_t *p = c.tin0 + static_cast<ptrdiff_t>(min(max(dplane, c.plo), c.phi)) * static_cast<ptrdiff_t>(c.plane_elems);
     char *dst = c.lds_stage + (dplane % NBUF) * PLANE_BYTES + j * 1024;
     if (64 * j + lane < PLANE_VOX)
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p + c.goff[j]),
@@ -387,7 +405,7 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
     const int tile = t;
     const int d0 = pd_i * a.dchunk, h0 = ph_i * PH, w0 = pw_i * PW;      // coordinates inside the output box
     const TileBox bx = tile_box(g, tile);
-    const int dn = min(a.dchunk, bx.bd - d0);                           // output planes to produce
+    int dn = min(a.dchunk, bx.bd - d0);                                 // output planes (slices) to produce
     // the patches are laid out for the largest box of the grid; a tile at the volume border has a smaller one
     if (dn <= 0 || h0 >= bx.bh || w0 >= bx.bw) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -403,31 +421,40 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
     }
 
     Ctx<HAS_BIAS> c;
-    c.plane_elems = static_cast<size_t>(g.ph) * g.pw * a.in_cs;
-    c.tin0 = a.in + (static_cast<size_t>(tile) * g.tile_vox + bx.org) * a.in_cs + d0 * c.plane_elems + a.in_co;
+    const int F = KD == 1 ? a.fold : 1;         // slices side by side (see fold_col); dn is a multiple of F
+    const size_t plane_real = static_cast<size_t>(g.ph) * g.pw * a.in_cs;
+    c.plane_elems = plane_real * F;
+    c.tin0 = a.in + (static_cast<size_t>(tile) * g.tile_vox + bx.org) * a.in_cs + d0 * plane_real + a.in_co -
+             static_cast<ptrdiff_t>(F - 1) * static_cast<ptrdiff_t>(plane_real);
+    dn /= F;                                    // from here on: output steps
     c.nplanes = dn + 2;
+    c.plo = F > 1 ? 1 : 0;
+    c.phi = F > 1 ? c.nplanes - 2 : c.nplanes - 1;
     // Wave w fills chunk plane w (channels 8w..8w+7 of every voxel); load j covers patch-local voxels
     // 64j..64j+63.  Voxels beyond the box and its one-voxel surround (ragged patches) are clamped to a valid
     // address; they only feed outputs that are never stored.
 #pragma unroll
     for (int j = 0; j < LOADS; ++j) {
         const int v = 64 * j + lane;
-        const int row = min(h0 + v / LCOLS, bx.bh + 1), colv = min(w0 + v % LCOLS, bx.bw + 1);
-        c.goff[j] = (row * g.pw + colv) * a.in_cs + wave * 8;
+        const FoldCol fc = fold_col(v % LCOLS, F, a.fold_w);
+        const int row = min(h0 + v / LCOLS, bx.bh + 1), colv = min(w0 + fc.c, bx.bw + 1);
+        c.goff[j] = ((min(fc.s, F - 1) * g.ph + row) * g.pw + colv) * a.in_cs + wave * 8;
     }
     c.lds_stage = lds + wave * CH_STRIDE;
     const OutDst od = out_dest(a, cj);
+    const FoldCol oc = fold_col(col, F, a.fold_w);
     c.orow = static_cast<size_t>(g.pw) * od.cs;
-    c.oplane = static_cast<size_t>(g.ph) * c.orow;
+    c.oplane = static_cast<size_t>(g.ph) * c.orow * F;
     const size_t opos = (static_cast<size_t>(tile) * g.tile_vox + bx.org) * od.cs +
-                        ((static_cast<size_t>(d0 + 1) * g.ph + h0 + wave * RH + 1) * g.pw + w0 + col + 1) * od.cs +
+                        ((static_cast<size_t>(d0 + 1 + min(oc.s, F - 1)) * g.ph + h0 + wave * RH + 1) * g.pw + w0 +
+                         oc.c + 1) * od.cs +
                         od.co + 4 * hi;
     c.obase = od.base + opos;
     c.mbase = a.mask + opos;
     // wave `wave` of workgroup `logical`: a region of dchunk planes x RH rows x 4 units x 1 KB
     c.pbase = a.part + (static_cast<size_t>(logical) * kWaves + wave) * a.dchunk * (RH * 4 * 256) + lane * 4;
 #pragma unroll
-    for (int h = 0; h < RH; ++h) c.okrow[h] = h0 + wave * RH + h < bx.bh && w0 + col < bx.bw;
+    for (int h = 0; h < RH; ++h) c.okrow[h] = h0 + wave * RH + h < bx.bh && w0 + oc.c < bx.bw && oc.s < F;
     // the bias is folded into the accumulators: a slot starts from the bias instead of zero
     // (without a bias the slots start from the constant zero and no registers are spent on it)
     if (HAS_BIAS) {
@@ -579,6 +606,7 @@ struct Ctx {
     const uint16_t *tin0;       // first padded input plane of the D chunk, at this wave's input chunk
     size_t plane_elems;
     int nplanes;
+    int plo, phi;               // staged planes are clamped to [plo, phi]
     int goff[LOADS];            // source offsets of the staging loads (elements)
     bool tail_lane;             // lane has a voxel in the last (partial) load of a chunk plane
     char *lds_stage;            // first chunk plane this wave fills, ring slot 0
@@ -594,7 +622,7 @@ struct Ctx {
 // staging load j (0..7) of plane `dplane`: chunk plane j / 4 of this wave's two, voxels 64 (j % 4) ..
 template <bool HAS_BIAS>
 __device__ __forceinline__ void stage(const Ctx<HAS_BIAS> &c, int dplane, int j) {
-    const uint16_t *p = c.tin0 + min(dplane, c.nplanes - 1) * c.plane_elems;
+    const uint16_t *p = c.tin0 + static_cast<ptrdiff_t>(min(max(dplane, c.plo), c.phi)) * static_cast<ptrdiff_t>(c.plane_elems);
     const char *dst = c.lds_stage + (dplane % NBUF) * PLANE_BYTES + (j / CP_LOADS) * CH_STRIDE + (j % CP_LOADS) * 1024;
     // only the last load of a chunk plane is partial (204 = 3 x 64 + 12 voxels); j is a compile-time constant
     // at every call site, so the other loads carry no predicate
@@ -823,31 +851,39 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int logical, i
     Ctx<HAS_BIAS> c;
     const uint16_t *src = ROLE ? a.in2 : a.in;
     const int src_cs = ROLE ? a.in2_cs : a.in_cs, src_co = ROLE ? a.in2_co : a.in_co;
-    c.plane_elems = static_cast<size_t>(g.ph) * g.pw * src_cs;
-    c.tin0 = src + (static_cast<size_t>(tile) * g.tile_vox + bx.org) * src_cs + d0 * c.plane_elems + src_co;
+    const int F = KD == 1 ? a.fold : 1;         // slices side by side (see fold_col); dn counts output steps
+    const size_t plane_real = static_cast<size_t>(g.ph) * g.pw * src_cs;
+    c.plane_elems = plane_real * F;
+    c.tin0 = src + (static_cast<size_t>(tile) * g.tile_vox + bx.org) * src_cs + d0 * plane_real + src_co -
+             static_cast<ptrdiff_t>(F - 1) * static_cast<ptrdiff_t>(plane_real);
     c.nplanes = dn + 2;
+    c.plo = F > 1 ? 1 : 0;
+    c.phi = F > 1 ? c.nplanes - 2 : c.nplanes - 1;
     // this wave fills chunk planes 2 rg and 2 rg + 1 (channels 16 rg .. 16 rg + 15) of its input chunk
 #pragma unroll
     for (int j = 0; j < LOADS; ++j) {
         const int v = 64 * (j % CP_LOADS) + lane;
-        const int row = min(h0 + v / LCOLS, bx.bh + 1), colv = min(w0 + v % LCOLS, bx.bw + 1);
-        c.goff[j] = (row * g.pw + colv) * src_cs + (2 * rg + j / CP_LOADS) * 8;       // clamped: always addressable
+        const FoldCol fc = fold_col(v % LCOLS, F, a.fold_w);
+        const int row = min(h0 + v / LCOLS, bx.bh + 1), colv = min(w0 + fc.c, bx.bw + 1);
+        c.goff[j] = ((min(fc.s, F - 1) * g.ph + row) * g.pw + colv) * src_cs + (2 * rg + j / CP_LOADS) * 8;   // always addressable
     }
     c.tail_lane = 64 * (CP_LOADS - 1) + lane < PLANE_VOX;
     c.lds_stage = lds + ROLE * CHUNK_BYTES + 2 * rg * CH_STRIDE;
     c.red = lds + RING_BYTES + rg * (RH * 4 * 1024) + lane * 16;
     const OutDst od = out_dest(a, cj);
+    const FoldCol oc = fold_col(col, F, a.fold_w);
     c.orow = static_cast<size_t>(g.pw) * od.cs;
-    c.oplane = static_cast<size_t>(g.ph) * c.orow;
+    c.oplane = static_cast<size_t>(g.ph) * c.orow * F;
     const size_t opos = (static_cast<size_t>(tile) * g.tile_vox + bx.org) * od.cs +
-                        ((static_cast<size_t>(d0 + 1) * g.ph + h0 + rg * RH + 1) * g.pw + w0 + col + 1) * od.cs +
+                        ((static_cast<size_t>(d0 + 1 + min(oc.s, F - 1)) * g.ph + h0 + rg * RH + 1) * g.pw + w0 +
+                         oc.c + 1) * od.cs +
                         od.co + 4 * hi;
     c.obase = od.base + opos;
     c.mbase = a.mask + opos;
     // the chunk-0 wave of row group rg of workgroup `logical`: dchunk planes x RH rows x 4 units x 1 KB
     c.pbase = a.part + (static_cast<size_t>(logical) * NRG + rg) * a.dchunk * (RH * 4 * 256) + lane * 4;
 #pragma unroll
-    for (int h = 0; h < RH; ++h) c.okrow[h] = h0 + rg * RH + h < bx.bh && w0 + col < bx.bw;
+    for (int h = 0; h < RH; ++h) c.okrow[h] = h0 + rg * RH + h < bx.bh && w0 + oc.c < bx.bw && oc.s < F;
     if (HAS_BIAS) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) c.bv[HAS_BIAS ? i : 0] = a.bias[C * cj + 8 * (i >> 2) + 4 * hi + (i & 3)];
@@ -966,8 +1002,9 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_pair_kernel(ConvArgs a)
     if (dn <= 0 || h0 >= bx.bh || w0 >= bx.bw) return;     // patch of the largest box that this tile's box lacks
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // two copies of the march, one per role, so that each is straight-line code for the scheduler
-    if (wave < 2) run<0, MODE, HAS_BIAS, RELU, KD>(a, lds, logical, tile, bx, d0, h0, w0, dn, cj, wave & 1);
-    else run<1, MODE, HAS_BIAS, RELU, KD>(a, lds, logical, tile, bx, d0, h0, w0, dn, cj, wave & 1);
+    const int dsteps = KD == 1 ? dn / a.fold : dn;       // slices side by side: a step produces `fold` of them
+    if (wave < 2) run<0, MODE, HAS_BIAS, RELU, KD>(a, lds, logical, tile, bx, d0, h0, w0, dsteps, cj, wave & 1);
+    else run<1, MODE, HAS_BIAS, RELU, KD>(a, lds, logical, tile, bx, d0, h0, w0, dsteps, cj, wave & 1);
 }
 
 }  // namespace wide
@@ -984,7 +1021,7 @@ static size_t pack_bytes(int ki, int ko) {
 }
 
 // How a layer is cut into workgroups (the same for every launch of the layer).
-struct PatchPlan { int nh, nw, dchunk, nd; long long nblocks; bool pairs; };
+struct PatchPlan { int nh, nw, dchunk, nd; long long nblocks; bool pairs; int fold, fold_w; };
 static PatchPlan plan_patches(const Geo &g, int ki, int ko) {
     PatchPlan p;
     const int nco = ko / C;
@@ -999,6 +1036,17 @@ static PatchPlan plan_patches(const Geo &g, int ki, int ko) {
     const long long base = 1LL * g.ntiles * p.nh * p.nw * nco;
     int dchunk = ed;
     while (base * ((ed + dchunk - 1) / dchunk) < 1024 && dchunk > 16) dchunk = (dchunk + 1) / 2;
+    // 2-D variant, tiles narrower than half a patch: up to 4 slices side by side (see fold_col); the tile's
+    // slice count and the D chunk must be multiples of it
+    p.fold = 1;
+    p.fold_w = ew + 2;
+    if (g.flat && 2 * (ew + 2) <= LCOLS) {
+        int f = LCOLS / (ew + 2);
+        if (f > 4) f = 4;
+        while (f > 1 && g.td % f) --f;
+        p.fold = f;
+        dchunk = (dchunk + f - 1) / f * f;
+    }
     p.dchunk = dchunk;
     p.nd = (ed + dchunk - 1) / dchunk;
     p.nblocks = base * p.nd;
@@ -1064,6 +1112,8 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
     a.nw = pl.nw;
     a.dchunk = pl.dchunk;
     a.nd = pl.nd;
+    a.fold = pl.fold;
+    a.fold_w = pl.fold_w;
     const long long nb = pl.nblocks;
     if (nb > 0x7ffffff0LL) return SP_EGEOM;
     a.nblocks = static_cast<int>(nb);

@@ -59,6 +59,13 @@ SMALL = [
     (1, (7, 5, 33), (1, 1, 1), 96, 32, "bf16"),        # three single chunks (first / middle / last)
     (1, (4, 16, 64), (1, 2, 2), 32, 32, "bf16"),       # whole patches: direct-to-LDS weight gradient
     (1, (3, 16, 40), (1, 2, 1), 5, 32, "bf16"),        # the slab input on the matrix cores (zero-padded channels)
+    # tiles narrower than half a patch: several slices side by side in one patch
+    (1, (8, 8, 8), (1, 1, 1), 32, 32, "bf16"),         # 8 wide: 3 would fit, 2 divide the 8 slices
+    (1, (3, 8, 8), (1, 1, 1), 32, 32, "bf16"),         # 3 slices side by side, one step
+    (1, (12, 8, 8), (1, 2, 2), 64, 64, "bf16"),        # 4 x 4 tiles: 4 slices side by side, pairs of chunks
+    (1, (6, 16, 24), (1, 1, 2), 128, 64, "bf16"),      # 12 wide: 2 side by side; two launches with partial sums
+    (2, (4, 8, 10), (2, 1, 1), 96, 32, "bf16"),        # batch 2, grid over the stack, three launches
+    (1, (5, 8, 8), (1, 1, 1), 64, 32, "bf16"),         # 5 slices: no divisor below 4, nothing side by side
 ]
 
 
@@ -232,7 +239,8 @@ def test_upconv_fwd_dgrad_wgrad_match_oracle(n, dhw, grid, cin, cout, dtype):
 
 
 @pytest.mark.parametrize("dhw,grid,chans", [((3, 24, 80), (1, 2, 2), (32, 32, 32)),
-                                            ((2, 16, 64), (2, 2, 1), (64, 64, 32))])
+                                            ((2, 16, 64), (2, 2, 1), (64, 64, 32)),
+                                            ((4, 16, 16), (1, 2, 2), (32, 64, 32))])     # slices side by side, grown boxes
 def test_two_layers_after_one_exchange_of_wide_margins(dhw, grid, chans):
     """halo 2, first layer with grow 1 (no growth along the slice axis), second layer on its own voxels:
     bit for bit the result of two layers with one exchange each on the one-voxel layout"""
