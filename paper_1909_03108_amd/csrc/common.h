@@ -126,6 +126,12 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
                      int cin, int cout, bool relu, bool dgrad, void *ws, hipStream_t s,
                      const void *mask = nullptr, const ConvSplit *split = nullptr);
 
+// wide layers on few voxels: output-stationary implicit GEMM on the packed weights (conv_gemm.hip);
+// launch_conv_mfma hands such layers over after packing
+bool conv_gemm_preferred(const Geo &g, int ki, int ko);
+int launch_conv_gemm(const void *Pin, const void *wpack, const float *bias, void *Pout, const Geo &g, int ki, int ko,
+                     bool relu, hipStream_t s, const void *mask, const ConvSplit *split);
+
 // single-input-channel first layer (conv_c1.hip)
 bool conv_c1_supported(const Geo &g, int cin, int cout, sp_dtype_t dt);
 int launch_conv_c1_fwd(const void *Px, const void *w, const float *bias, void *Py, const Geo &g, int cout,

@@ -121,11 +121,11 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t *__res
     // forward: w[tap][cin = k][cout = m] (row length ko); dgrad: w[26-tap][cin = m][cout = k] (row length ki)
     if (flat) {
         // w[3][3][..][..]: its 9 taps are the kernel's taps 9..17 (kd = 1); the other fragments are never loaded
+        // and stay unwritten
         const int t9 = tap - 9;
-        uint16_t v = 0;
         if (t9 >= 0 && t9 < 9)
-            v = dgrad ? w[(static_cast<size_t>(8 - t9) * ko + m) * ki + k] : w[(static_cast<size_t>(t9) * ki + k) * ko + m];
-        wpack[idx] = v;
+            wpack[idx] = dgrad ? w[(static_cast<size_t>(8 - t9) * ko + m) * ki + k]
+                               : w[(static_cast<size_t>(t9) * ki + k) * ko + m];
         return;
     }
     wpack[idx] = dgrad ? w[(static_cast<size_t>(26 - tap) * ko + m) * ki + k]
@@ -1058,6 +1058,7 @@ static PatchPlan plan_patches(const Geo &g, int ki, int ko) {
 // and wave that stores results, dchunk planes x RH rows x 4 units x 1 KB (see part_unit)
 size_t conv_mfma_ws_bytes(const Geo &g, int ki, int ko) {
     size_t n = pack_bytes(ki, ko);
+    if (conv_gemm_preferred(g, ki, ko)) return n;      // one launch, sums stay in registers
     const PatchPlan p = plan_patches(g, ki, ko);
     const int launches = p.pairs ? ki / (2 * C) : ki / C;
     if (launches > 1)
@@ -1074,6 +1075,8 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
                        static_cast<const uint16_t *>(w), static_cast<uint16_t *>(ws), ki, ko, dgrad ? 1 : 0, g.flat);
     int rc = record_hip(hipGetLastError());
     if (rc != SP_OK) return rc;
+    // wide layers on few voxels: one launch that keeps the sums in registers over all input channels
+    if (conv_gemm_preferred(g, ki, ko)) return launch_conv_gemm(Pin, ws, bias, Pout, g, ki, ko, relu, s, mask, split);
     ConvArgs a;
     a.in = static_cast<const uint16_t *>(Pin);
     a.bias = bias;

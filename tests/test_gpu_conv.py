@@ -101,6 +101,9 @@ SMALL = [
     # few input channels: zero-padded copies, then the matrix-core kernels
     (1, (6, 10, 40), (1, 2, 1), 3, 32, "bf16"),
     (1, (4, 8, 16), (2, 1, 1), 40, 64, "bf16"),       # 40 -> 64 channels: a pair of chunks
+    # wide layers on few voxels (the bottom of a deep network): 8 and 9 launches with partial sums between them
+    (1, (4, 8, 8), (1, 2, 2), 512, 128, "bf16"),      # 4 x 4 x 4 tiles
+    (2, (5, 8, 6), (1, 2, 1), 576, 256, "bf16"),      # batch 2
 ]
 
 

@@ -66,6 +66,10 @@ SMALL = [
     (1, (6, 16, 24), (1, 1, 2), 128, 64, "bf16"),      # 12 wide: 2 side by side; two launches with partial sums
     (2, (4, 8, 10), (2, 1, 1), 96, 32, "bf16"),        # batch 2, grid over the stack, three launches
     (1, (5, 8, 8), (1, 1, 1), 64, 32, "bf16"),         # 5 slices: no divisor below 4, nothing side by side
+    # wide layers on few voxels: the output-stationary kernel
+    (1, (4, 8, 8), (1, 2, 2), 512, 128, "bf16"),       # forward, one whole voxel group
+    (1, (3, 6, 10), (1, 1, 2), 128, 512, "bf16"),      # data gradient (plain and masked), ragged voxel group
+    (1, (5, 16, 8), (1, 2, 1), 640, 256, "bf16"),      # three voxel groups, two groups of output blocks
 ]
 
 
@@ -112,8 +116,11 @@ def test_conv_fwd_dgrad_wgrad_match_oracle(n, dhw, grid, cin, cout, dtype):
     assert rel_err(f64(db), O.bias_grad(widen(dz))) <= tol
 
 
-def test_two_tensor_convolutions_equal_the_concatenated_ones():
-    n, dhw, grid, ca, cb, cout = 1, (3, 12, 40), (1, 2, 1), 32, 32, 64
+@pytest.mark.parametrize("dhw,grid,ca,cb,cout", [((3, 12, 40), (1, 2, 1), 32, 32, 64),
+                                                 ((3, 8, 10), (1, 1, 2), 256, 256, 128),   # output-stationary kernel,
+                                                 ((2, 4, 8), (1, 1, 1), 64, 64, 512)])     # forward / data gradient
+def test_two_tensor_convolutions_equal_the_concatenated_ones(dhw, grid, ca, cb, cout):
+    n = 1
     L = Layer(n, dhw, grid, ca + cb, cout, "bf16")
     g, dt = L.g, L.dt
     xa, xb = draw("bf16", (n,) + dhw + (ca,), 1), draw("bf16", (n,) + dhw + (cb,), 2)
@@ -240,7 +247,8 @@ def test_upconv_fwd_dgrad_wgrad_match_oracle(n, dhw, grid, cin, cout, dtype):
 
 @pytest.mark.parametrize("dhw,grid,chans", [((3, 24, 80), (1, 2, 2), (32, 32, 32)),
                                             ((2, 16, 64), (2, 2, 1), (64, 64, 32)),
-                                            ((4, 16, 16), (1, 2, 2), (32, 64, 32))])     # slices side by side, grown boxes
+                                            ((4, 16, 16), (1, 2, 2), (32, 64, 32)),      # slices side by side, grown boxes
+                                            ((2, 8, 16), (1, 2, 2), (512, 512, 128))])   # output-stationary kernel, grown boxes
 def test_two_layers_after_one_exchange_of_wide_margins(dhw, grid, chans):
     """halo 2, first layer with grow 1 (no growth along the slice axis), second layer on its own voxels:
     bit for bit the result of two layers with one exchange each on the one-voxel layout"""
@@ -255,7 +263,9 @@ def test_two_layers_after_one_exchange_of_wide_margins(dhw, grid, chans):
         g, dt = La.g, La.dt
         Px = La.padded(x, c0)
         P1, P2 = sp3d.alloc_padded(g, c1, dt), sp3d.alloc_padded(g, c2, dt)
-        sp3d.conv3d_fwd(Px, w1, None, P1, g.grown(halo - 1), c0, c1, dt, sp3d.SP_FLAG_RELU, La.ws[sp3d.SP_OP_FWD])
+        g1 = g.grown(halo - 1)              # the workspace size depends on the output box
+        ws1 = sp3d.alloc_ws(sp3d.sp_workspace_bytes(sp3d.SP_OP_FWD, g1, c0, c1, dt))
+        sp3d.conv3d_fwd(Px, w1, None, P1, g1, c0, c1, dt, sp3d.SP_FLAG_RELU, ws1)
         if halo == 1:
             sp3d.sp_halo_exchange(P1, g, c1, dt)
         sp3d.conv3d_fwd(P1, w2, None, P2, g, c1, c2, dt, sp3d.SP_FLAG_RELU, Lb.ws[sp3d.SP_OP_FWD])
@@ -270,17 +280,20 @@ def _rel_rms(got, ref):
 
 
 @pytest.mark.timeout(600)
-@pytest.mark.parametrize("convs", [2, 4])
-def test_flat_unet_against_the_composed_oracle(convs):
+@pytest.mark.parametrize("convs,channels,dhw", [(2, (32, 64, 128), (3, 32, 32)), (4, (32, 64, 128), (3, 32, 32)),
+                                                (2, (32, 512), (2, 16, 16))])      # wide bottom level on 8 x 8 voxels
+def test_flat_unet_against_the_composed_oracle(convs, channels, dhw):
     """The 2-D U-Net (slab input with 5 channels, the same architecture with 2-D operations) on a 2 x 2 tile
     grid against the storage-aware oracle chain: free-running forward to 3e-2 element-wise / 1e-2 rms (twice that
     with four convolutions per block),
     free-running backward as a wiring check (0.25 in relative rms: ReLU decisions within the forward error of
-    zero flip), a second step bit for bit, and the two-layers-per-exchange layout bit for bit."""
+    zero flip), a second step bit for bit, and the two-layers-per-exchange layout bit for bit.  The third
+    configuration has a 512-channel bottom level: the output-stationary kernel in the forward pass and, with the
+    ReLU mask and a grown box, in the backward pass."""
     from oracle import unet as OU
     from paper_1909_03108_amd import unet as PU
-    channels, in_ch, classes = (32, 64, 128), 5, 3
-    n, dhw, grid = 1, (3, 32, 32), (1, 2, 2)
+    in_ch, classes = 5, 3
+    n, grid = 1, (1, 2, 2)
     plan = PU.layer_plan(channels, in_ch, classes, convs, flat=True)
     x = synth.normal_volume((n,) + dhw + (in_ch,), 11, "bf16")
     w_h = {name: synth.weights(shape[2], shape[3], 100 + k, "bf16", taps=shape[:2])
