@@ -64,38 +64,53 @@ template <> __device__ __forceinline__ Bytes16 *at<Bytes16>(Bytes16 *p, long lon
     return reinterpret_cast<Bytes16 *>(reinterpret_cast<char *>(p) + off);
 }
 
+// Offsets (source, destination) of vector j of row chunk rc, and whether it exists.  With rc taken from the
+// block index alone the whole row / tile decode is wave-uniform and runs on the scalar unit.
+template <typename T, bool INVERSE>
+__device__ __forceinline__ bool partition_offsets(const PartArgs &a, unsigned rc, unsigned jl, long long *so,
+                                                  long long *dof) {
+    const Geo &g = a.g;
+    const long long D = 1LL * g.gd * g.td, H = 1LL * g.gh * g.th, W = 1LL * g.gw * g.tw;
+    const unsigned rcc = rc < a.nchunks ? rc : 0;
+    const unsigned row = fdiv(rcc, a.cpr);
+    const unsigned j = fmod_(rcc, row, a.cpr) * a.tpr + jl;
+    // row -> (tile, ld, lh)
+    const unsigned tile = fdiv(row, a.rows_per_tile);
+    const unsigned r = fmod_(row, tile, a.rows_per_tile);
+    const unsigned ld = fdiv(r, a.th), lh = fmod_(r, ld, a.th);
+    // tile -> (n, a, b, c)
+    const unsigned t1 = fdiv(tile, a.gw), tc = fmod_(tile, t1, a.gw);
+    const unsigned t2 = fdiv(t1, a.gh), tb = fmod_(t1, t2, a.gh);
+    const unsigned tn = fdiv(t2, a.gd), ta = fmod_(t2, tn, a.gd);
+    const long long vvox = ((tn * D + ta * g.td + ld) * H + tb * g.th + lh) * W + 1LL * tc * g.tw;
+    const long long pvox = tile * g.tile_vox + (1LL * (ld + g.halo) * g.ph + lh + g.halo) * g.pw + g.halo;
+    // offsets in vectors; rows of Bytes16 start at any even byte, so those are kept in bytes
+    constexpr long long JS = std::is_same<T, Bytes16>::value ? 16 : 1;
+    *so = (INVERSE ? pvox : vvox) * a.vpv_num + j * JS;
+    *dof = (INVERSE ? vvox : pvox) * a.vpv_num + j * JS;
+    return rc < a.nchunks && j < static_cast<unsigned>(a.rowvecs);
+}
+
 template <typename T, bool INVERSE, int VPT>
 __global__ __launch_bounds__(kThreads) void partition_kernel(const T *__restrict__ src,
                                                              T *__restrict__ dst, PartArgs a) {
-    const Geo &g = a.g;
-    const unsigned rpb = kThreads / a.tpr;                  // row chunks per block and pass
-    const long long D = 1LL * g.gd * g.td, H = 1LL * g.gh * g.th, W = 1LL * g.gw * g.tw;
     T v[VPT];
     long long so[VPT], do_[VPT];
     bool ok[VPT];
+    if (a.tpr == kThreads) {   // a block per row chunk (rows of at least 256 vectors): uniform decode
 #pragma unroll
-    for (int k = 0; k < VPT; ++k) {
-        const unsigned rc = (blockIdx.x * VPT + k) * rpb + threadIdx.x / a.tpr;   // row chunk index
-        const unsigned rcc = rc < a.nchunks ? rc : 0;
-        const unsigned row = fdiv(rcc, a.cpr);
-        const unsigned j = fmod_(rcc, row, a.cpr) * a.tpr + threadIdx.x % a.tpr;
-        ok[k] = rc < a.nchunks && j < static_cast<unsigned>(a.rowvecs);
-        // row -> (tile, ld, lh)
-        const unsigned tile = fdiv(row, a.rows_per_tile);
-        const unsigned r = fmod_(row, tile, a.rows_per_tile);
-        const unsigned ld = fdiv(r, a.th), lh = fmod_(r, ld, a.th);
-        // tile -> (n, a, b, c)
-        const unsigned t1 = fdiv(tile, a.gw), tc = fmod_(tile, t1, a.gw);
-        const unsigned t2 = fdiv(t1, a.gh), tb = fmod_(t1, t2, a.gh);
-        const unsigned tn = fdiv(t2, a.gd), ta = fmod_(t2, tn, a.gd);
-        const long long vvox = ((tn * D + ta * g.td + ld) * H + tb * g.th + lh) * W + 1LL * tc * g.tw;
-        const long long pvox = tile * g.tile_vox +
-                               (1LL * (ld + g.halo) * g.ph + lh + g.halo) * g.pw + g.halo;
-        // offsets in vectors; rows of Bytes16 start at any even byte, so those are kept in bytes
-        constexpr long long JS = std::is_same<T, Bytes16>::value ? 16 : 1;
-        so[k] = (INVERSE ? pvox : vvox) * a.vpv_num + j * JS;
-        do_[k] = (INVERSE ? vvox : pvox) * a.vpv_num + j * JS;
-        if (ok[k]) v[k] = ld_stream(at(src, so[k]));
+        for (int k = 0; k < VPT; ++k) {
+            ok[k] = partition_offsets<T, INVERSE>(a, blockIdx.x * VPT + k, threadIdx.x, &so[k], &do_[k]);
+            if (ok[k]) v[k] = ld_stream(at(src, so[k]));
+        }
+    } else {
+        const unsigned rpb = kThreads / a.tpr;                  // row chunks per block and pass
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            ok[k] = partition_offsets<T, INVERSE>(a, (blockIdx.x * VPT + k) * rpb + threadIdx.x / a.tpr,
+                                                  threadIdx.x % a.tpr, &so[k], &do_[k]);
+            if (ok[k]) v[k] = ld_stream(at(src, so[k]));
+        }
     }
 #pragma unroll
     for (int k = 0; k < VPT; ++k)

@@ -589,7 +589,9 @@ void plan(const Geo &g, int cin, int cout, WgradArgs *a) {
 // the contiguous run of workgroups [s*gpp/8, (s+1)*gpp/8) in order, and the eight run sums are combined by
 // a fixed three-level tree, so the grouping depends only on gpp and the result is reproducible.  (One
 // serial chain of gpp dependent loads per output was latency-bound: 72 us for 28 MB of partials.)
-constexpr int RSPLIT = 8;
+// With fewer than eight workgroups per pair (wide layers: a pair per workgroup) one lane adds them all:
+// seven idle lanes per output made the plain re-layout of a 1024 x 1024 layer's 38 MB cost 0.24 ms.
+template <int RSPLIT>
 __global__ __launch_bounds__(256) void reduce_wgrad_kernel(const float *__restrict__ part_w,
                                                            const float *__restrict__ part_b,
                                                            float *__restrict__ dw, float *__restrict__ db,
@@ -617,9 +619,11 @@ __global__ __launch_bounds__(256) void reduce_wgrad_kernel(const float *__restri
         for (int k = k0; k < k1; ++k) s += p[k * C];
     }
     // lanes 8j .. 8j+7 hold the run sums of one output (every lane of the wave takes part in the shuffles)
-    s += __shfl_xor(s, 1);
-    s += __shfl_xor(s, 2);
-    s += __shfl_xor(s, 4);
+    if (RSPLIT == 8) {
+        s += __shfl_xor(s, 1);
+        s += __shfl_xor(s, 2);
+        s += __shfl_xor(s, 4);
+    }
     if (sub == 0) {
         if (e < nw_) dw[e] = s;
         else if (db && e < nw_ + cout) db[e - nw_] = s;
@@ -677,9 +681,15 @@ int launch_wgrad_mfma(const void *Px, const void *Pdz, float *dw, float *db, con
         hipLaunchKernelGGL(plain[g.flat], dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
     int rc = record_hip(hipGetLastError());
     if (rc != SP_OK) return rc;
-    const long long n = (1LL * ntaps * cin * cout + cout) * RSPLIT;
-    hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, s, a.part_w,
-                       a.part_b, dw, db, cin, cout, a.gpp, ntaps);
+    const int rsplit = a.gpp >= 8 ? 8 : 1;
+    const long long n = (1LL * ntaps * cin * cout + cout) * rsplit;
+    const dim3 rgrid(static_cast<unsigned>((n + 255) / 256));
+    if (rsplit == 8)
+        hipLaunchKernelGGL(reduce_wgrad_kernel<8>, rgrid, dim3(256), 0, s, a.part_w, a.part_b, dw, db, cin, cout,
+                           a.gpp, ntaps);
+    else
+        hipLaunchKernelGGL(reduce_wgrad_kernel<1>, rgrid, dim3(256), 0, s, a.part_w, a.part_b, dw, db, cin, cout,
+                           a.gpp, ntaps);
     return record_hip(hipGetLastError());
 }
 
