@@ -286,3 +286,63 @@ def test_configuration_5_decoder_layer_256_sampled():
     sp3d.conv3d_dgrad_relu(Pz, to_dev(w2), Ps, Pa, g, 32, 32, dt, ws1)
     check(Pa, lambda b: np.where(widen(skip[:, b[0]:b[1], b[2]:b[3], b[4]:b[5]]) > 0,
                                  conv3d.conv3d_dgrad(dz, W2d, box=b), 0.0), "dgrad_relu")
+
+
+FULL_SIZE_STACKS = {
+    # name: (channels, input channels, convolutions per level, volume, grid of the timed run, 2-D variant)
+    "c5": ((32, 64, 128, 256), 1, 2, (256, 256, 256), (4, 4, 1), False),
+    "paper_3d_at_256": ((32, 64, 128, 256, 512, 1024), 1, 4, (256, 256, 256), (4, 4, 1), False),
+    "paper_2d": ((32, 64, 128, 256, 512, 1024), 5, 4, (16, 512, 512), (1, 2, 2), True),
+}
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("stack", sorted(FULL_SIZE_STACKS))
+def test_full_size_stack_tiled_equals_unpartitioned(stack):
+    """A whole U-Net stack at full size, in the launch configuration bench.py times, against the same stack on
+    ONE tile that holds the whole volume (grid 1x1x1: no neighbours, every margin is zero padding).
+      c5               configuration 5: 256^3, channels 32/64/128/256, two convolutions per level, grid 4x4x1
+                       (bench.py --workload c5);
+      paper_3d_at_256  the paper's own network shape (Sec. 3: six levels up to 1024 filters, four convolutions per
+                       block) on 256^3, grid 4x4x1 (tiles down to 2 x 2 x 8) - bench.py --workload paper512 runs
+                       it on 512^3, where one tile holding the whole volume does not fit the index range;
+      paper_2d         the 2-D variant on 16 slabs of 512 x 512 x 5, grid 1x2x2 (bench.py --workload paper2d).
+    A full fp64 pass of these stacks is out of reach of the CPU oracle, so the check is the property the method
+    claims at any size (abstract: the distribution is transparent): partitioned == unpartitioned.  Every output
+    voxel sums its taps and channels in the same order whatever tile it lies in, so logits, the image gradient
+    and with them every stored ReLU / pooling decision must agree bit for bit; the weight gradients add their
+    voxels in a tile-dependent order and are held to 1e-3 of their rms (fp32 sums of up to 1.7e7 terms).  The
+    per-operation parity of the stacks with the oracle is established at small sizes in test_gpu_unet.py /
+    test_gpu_flat.py and on sampled boxes of full-size layers above; this test ties the full-size tiled runs
+    to them."""
+    from paper_1909_03108_amd import unet as PU
+    channels, in_ch, convs, dhw, timed_grid, flat = FULL_SIZE_STACKS[stack]
+    n, classes = 1, 3
+    plan = PU.layer_plan(channels, in_ch, classes, convs, flat=flat)
+    if in_ch == 1:
+        x = synth.ct_like_volume((n,) + dhw + (in_ch,), synth.seed_for(5, synth.T_INPUT), "bf16")
+    else:
+        x = synth.normal_volume((n,) + dhw + (in_ch,), synth.seed_for(5, synth.T_INPUT), "bf16")
+    x = to_dev(x)
+    nt = 2 if flat else 3        # taps: (kh, kw) or (kd, kh, kw), then (cin, cout)
+    w_d = {name: to_dev(synth.weights(shape[nt], shape[nt + 1], synth.seed_for(5, synth.T_WEIGHT0 + k), "bf16",
+                                      taps=shape[:nt])) for k, (name, shape) in enumerate(plan)}
+    dl = to_dev(synth.normal_volume((n,) + dhw + (classes,), synth.seed_for(5, synth.T_UPSTREAM), "bf16"))
+    res = []
+    for grid in (timed_grid, (1, 1, 1)):
+        net = PU.UNet(n, dhw, grid, w_d, channels, in_ch, classes, convs=convs, flat=flat)
+        logits = net.forward(x)
+        grads, dx = net.backward(dl)
+        res.append((logits.clone(), {k: v.clone() for k, v in grads.items()}, dx.clone()))
+        del net, logits, grads, dx
+        torch.cuda.empty_cache()
+    (l1, g1, d1), (l2, g2, d2) = res
+    assert torch.isfinite(l1.float()).all() and float(l1.float().abs().max()) > 0
+    assert torch.equal(l1, l2), "logits differ between the tiled and the one-tile run"
+    assert torch.equal(d1, d2), "image gradient differs between the tiled and the one-tile run"
+    worst = 0.0
+    for k, _ in plan:
+        a, b = g1[k].double(), g2[k].double()
+        worst = max(worst, float((a - b).abs().max() / b.pow(2).mean().sqrt()))
+    print("%s: weight gradients, grid %s against 1x1x1: worst |diff| / rms = %.2e" % (stack, timed_grid, worst))
+    assert worst <= 1e-3
