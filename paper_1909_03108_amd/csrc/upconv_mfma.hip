@@ -397,8 +397,19 @@ __global__ __launch_bounds__(256) void upconv_wgrad_reduce_kernel(const float *_
         const int co = e % cout, ci = (e / cout) % cin, tap = e / (cout * cin);
         const int group = (ci / gci) * nco + co / C;
         const float *p = part_w + ((static_cast<size_t>(group) * wpg * 8 + tap) * gci + ci % gci) * C + co % C;
+        // sixteen loads in flight, added in workgroup order (a chain of dependent loads pays the memory latency
+        // once per partial)
+        const size_t kstride = static_cast<size_t>(8) * gci * C;
         float s = 0.f;
-        for (int k = 0; k < wpg; ++k) s += p[static_cast<size_t>(k) * 8 * gci * C];
+        int k = 0;
+        for (; k + 16 <= wpg; k += 16) {
+            float v[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v[i] = p[(k + i) * kstride];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s += v[i];
+        }
+        for (; k < wpg; ++k) s += p[k * kstride];
         du[e] = s;
     } else if (db && e < nw + cout) {
         const int co = e - nw;
