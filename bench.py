@@ -15,6 +15,7 @@ dense bf16 peak, `cpu_baseline` is the fp64 oracle timed on the host cores on a 
 tensors.
 """
 import argparse
+import itertools
 import json
 import os
 import sys
@@ -281,6 +282,19 @@ def main():
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                 "traffic": MEASURED_TRAFFIC_BYTES.get(S)}
     msg_bytes = sp3d.sp_msg_elems(g, c) * 2
+    # halo_unpack writes every margin region and reads only those whose neighbour tile exists
+    tile = (S // grid[0], S // grid[1], S // grid[2])
+    nb_vox = 0
+    for delta in itertools.product((-1, 0, 1), repeat=3):
+        if delta == (0, 0, 0):
+            continue
+        region = 1
+        tiles = 1
+        for ax in range(3):
+            region *= tile[ax] if delta[ax] == 0 else 1
+            tiles *= grid[ax] if delta[ax] == 0 else grid[ax] - 1
+        nb_vox += n * tiles * region
+    unpack_bytes = msg_bytes + nb_vox * c * 2
     other = [
         {"kernel": "wgrad_mfma_kernel (conv3d_wgrad)", "bound": "mfma",
          "achieved": round(flop_pass / (avg_ms["conv3d_wgrad"] * 1e-3) / 1e12, 1),
@@ -289,6 +303,13 @@ def main():
         {"kernel": "halo_pack", "bound": "hbm",
          "achieved": round(2 * msg_bytes / (avg_ms["halo_pack"] * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
          "unit": "GB/s", "frac": round(2 * msg_bytes / (avg_ms["halo_pack"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+        {"kernel": "halo_unpack", "bound": "hbm",
+         "achieved": round(unpack_bytes / (avg_ms["halo_unpack"] * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
+         "unit": "GB/s", "frac": round(unpack_bytes / (avg_ms["halo_unpack"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+        {"kernel": "sp_unpartition", "bound": "hbm",
+         "achieved": round(2 * vox * c * 2 / (avg_ms["sp_unpartition"] * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
+         "unit": "GB/s",
+         "frac": round(2 * vox * c * 2 / (avg_ms["sp_unpartition"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
         {"kernel": "sp_partition", "bound": "hbm",
          "achieved": round(2 * vox * c * 2 / (avg_ms["sp_partition"] * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
          "unit": "GB/s",
