@@ -63,6 +63,8 @@ struct WgradArgs {
     int dchunk, nd, nh, nw;
     int nitems;           // work items per pair
     int ngroups;          // real workgroups = pairs * gpp; grid is rounded up to a multiple of 8
+    int fold, fold_w;     // 2-D variant, tiles narrower than half a patch: `fold` consecutive slices lie side by
+                          // side in a staged plane, each in a strip of fold_w = tile width + 2 columns (1: none)
 };
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -188,6 +190,20 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
     const size_t xplane = static_cast<size_t>(g.ph) * g.pw * xs.cs, zplane = static_cast<size_t>(g.ph) * g.pw * a.dz_cs;
     const int xrow_elems = g.pw * xs.cs, zrow_elems = g.pw * a.dz_cs;
 
+    // Slices side by side (2-D variant, tiles at most 15 voxels wide: one patch column block, w0 = 0).  Slices do
+    // not interact, so F of them share a staged plane: strip s holds padded columns 0 .. tile width + 1 of a
+    // slice, and a plane step adds F slices to the sums.  dz column Z meets x columns Z, Z + 1, Z + 2; it is
+    // staged (non-zero) only where x column Z + 1 is an interior column of its strip, so all three lie in that
+    // strip and no product pairs voxels of different slices.
+    // Per thread: strip and padded column of its main x chunk, of its edge x chunk and of its dz chunk.
+    const int F = KD == 1 ? a.fold : 1;
+    int xs_m = 0, xc_m = sv, xs_e = 0, xc_e = ev, zs_m = 0, zc_m = sv + 1;
+    if (F > 1) {
+        xs_m = sv / a.fold_w; xc_m = sv - xs_m * a.fold_w;
+        xs_e = ev / a.fold_w; xc_e = ev - xs_e * a.fold_w;
+        zs_m = (sv + 1) / a.fold_w; zc_m = sv + 1 - zs_m * a.fold_w;
+    }
+
     for (int item = gsub; item < a.nitems; item += a.gpp) {
         int t = item;
         const int pw_i = t % a.nw; t /= a.nw;
@@ -200,30 +216,38 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
         const uint16_t *tz = a.dz + static_cast<size_t>(tile) * g.tile_vox * a.dz_cs + dz_co;
 
         // source offsets inside a plane and validity (x: the interior and one voxel around it; dz: tile interior)
-        const int xsrc0 = ((h0 + sr) * g.pw + w0 + sv) * xs.cs + c4 * 8;
-        const int xsrce = ((h0 + er) * g.pw + w0 + ev) * xs.cs + c4 * 8;
-        const int zsrc0 = ((h0 + sr + 1) * g.pw + w0 + sv + 1) * a.dz_cs + c4 * 8;
+        const int xsrc0 = ((h0 + sr) * g.pw + w0 + xc_m) * xs.cs + c4 * 8;
+        const int xsrce = ((h0 + er) * g.pw + w0 + xc_e) * xs.cs + c4 * 8;
+        const int zsrc0 = ((h0 + sr + 1) * g.pw + w0 + zc_m) * a.dz_cs + c4 * 8;
+        // columns: inside the tile's padded row (x) / interior (dz); folded: inside a strip that exists
+        const bool xcol = F > 1 ? xs_m < F : w0 + sv < g.tw + 2;
+        const bool ecol = F > 1 ? xs_e < F : w0 + ev < g.tw + 2;
+        const bool zcol = F > 1 ? zs_m < F && zc_m >= 1 && zc_m <= g.tw : w0 + sv < g.tw;
         bool xok[3], zok[2];
 #pragma unroll
-        for (int i = 0; i < 3; ++i)
-            xok[i] = sr + 4 * i < XR && h0 + sr + 4 * i < g.th + 2 && w0 + sv < g.tw + 2;
-        const bool eok = tid < 8 * XR && h0 + er < g.th + 2 && w0 + ev < g.tw + 2;
+        for (int i = 0; i < 3; ++i) xok[i] = sr + 4 * i < XR && h0 + sr + 4 * i < g.th + 2 && xcol;
+        const bool eok = tid < 8 * XR && h0 + er < g.th + 2 && ecol;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) zok[i] = h0 + sr + 4 * i < g.th && w0 + sv < g.tw;
+        for (int i = 0; i < 2; ++i) zok[i] = h0 + sr + 4 * i < g.th && zcol;
+        // folded: step S of the march stands for slices F * (S - 1) + s of the chunk on the x side (steps 0 and
+        // the last meet no dz and are clamped into the chunk) and F * S + s on the dz side
+        const int dsteps = F > 1 ? dn / F : dn;
 
         // staged chunks travel in registers from the global loads (issued before a plane's MFMAs)
         // to the LDS writes (after them)
         uint4 xs0, xs1, xs2, xs3, zs0, zs1;
 #define SP3D_LDG(ok, ptr, safe) ldg_clamped(ok, ptr, safe)
+#define SP3D_XSLICE(D, S_) (F > 1 ? d0 + 1 + min(max(((D) - 1) * F + (S_), 0), dn - 1) : d0 + (D))
 #define SP3D_FETCH(D)                                                                  \
     do {                                                                               \
-        const uint16_t *px = tx + (d0 + (D)) * xplane;                                 \
+        const uint16_t *px = tx + SP3D_XSLICE(D, xs_m) * xplane;                       \
+        const uint16_t *pe = tx + SP3D_XSLICE(D, xs_e) * xplane;                       \
         xs0 = SP3D_LDG(xok[0], px + xsrc0, tx);                                        \
         xs1 = SP3D_LDG(xok[1], px + xsrc0 + 4 * xrow_elems, tx);                       \
         xs2 = SP3D_LDG(xok[2], px + xsrc0 + 8 * xrow_elems, tx);                       \
-        xs3 = SP3D_LDG(eok, px + xsrce, tx);                                           \
-        const bool zreal = (D) < dn;                                                   \
-        const uint16_t *pz = tz + (d0 + (D) + 1) * zplane;                             \
+        xs3 = SP3D_LDG(eok, pe + xsrce, tx);                                           \
+        const bool zreal = (D) < dsteps;                                               \
+        const uint16_t *pz = tz + (F > 1 ? d0 + 1 + (D) * F + zs_m : d0 + (D) + 1) * zplane; \
         zs0 = SP3D_LDG(zreal && zok[0], pz + zsrc0, tz);                               \
         zs1 = SP3D_LDG(zreal && zok[1], pz + zsrc0 + 4 * zrow_elems, tz);              \
     } while (0)
@@ -236,7 +260,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
     } while (0)
 #define SP3D_COMMIT(D)                                                                 \
     do {                                                                               \
-        const bool zreal = (D) < dn;                                                   \
+        const bool zreal = (D) < dsteps;                                               \
         xs0 = keep_if(xok[0], xs0); xs1 = keep_if(xok[1], xs1);                        \
         xs2 = keep_if(xok[2], xs2); xs3 = keep_if(eok, xs3);                           \
         zs0 = keep_if(zreal && zok[0], zs0); zs1 = keep_if(zreal && zok[1], zs1);      \
@@ -265,7 +289,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
 
         // x is double buffered and the dz ring has 4 slots, so plane D+1 can be written while other
         // waves still read planes D, D-1, D-2: one barrier per plane.
-        const int nplanes = dn + 2;
+        const int nplanes = dsteps + 2;
         for (int D = 0; D < nplanes; D += 4) {
 #pragma unroll
             for (int ph = 0; ph < 4; ++ph) {
@@ -276,7 +300,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
                     const char *xl = xlane + (Dp & 1) * X_BYTES;
                     // 2-D variant: x planes 0 and dn + 1 are the D margins, which hold nothing defined (and
                     // meet no dz plane): they must not reach the matrix cores
-                    if (KD == 1 && (Dp < 1 || Dp > dn)) {
+                    if (KD == 1 && (Dp < 1 || Dp > dsteps)) {
                     } else if (ph == 0) plane_step<0, KD>(xl, zlane, acc);
                     else if (ph == 1) plane_step<1, KD>(xl, zlane, acc);
                     else if (ph == 2) plane_step<2, KD>(xl, zlane, acc);
@@ -289,6 +313,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
     }
 
 #undef SP3D_LDG
+#undef SP3D_XSLICE
 #undef SP3D_FETCH
 #undef SP3D_BSUM
 #undef SP3D_COMMIT
@@ -576,6 +601,18 @@ void plan(const Geo &g, int cin, int cout, WgradArgs *a) {
     const long long base = 1LL * g.ntiles * a->nh * a->nw;
     int dchunk = g.td;
     while (base * ((g.td + dchunk - 1) / dchunk) < gpp && dchunk > 16) dchunk = (dchunk + 1) / 2;
+    // 2-D variant, tiles narrower than half a patch: up to 4 slices side by side in a staged plane; the tile's
+    // slice count and the D chunk must be multiples of that number (only the register-staged kernel folds: such
+    // tiles are never whole patches)
+    a->fold = 1;
+    a->fold_w = g.tw + 2;
+    if (g.flat && 2 * (g.tw + 2) <= XC) {
+        int f = XC / (g.tw + 2);
+        if (f > 4) f = 4;
+        while (f > 1 && g.td % f) --f;
+        a->fold = f;
+        dchunk = (dchunk + f - 1) / f * f;
+    }
     a->dchunk = dchunk;
     a->nd = (g.td + dchunk - 1) / dchunk;
     const long long items = base * a->nd;
