@@ -38,9 +38,10 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int C = 32;                            // channels of a chunk / block
 constexpr int CB = 4;                            // output blocks per workgroup
-constexpr int VB = 2;                            // 32-voxel segments per wave
+constexpr int VBMAX = 2;                         // 32-voxel segments per wave: 2, or 1 for layers that would
+                                                 // otherwise leave half of the compute units without a workgroup
 constexpr int kWaves = 4, kThreads = 256;
-constexpr int WG_VOX = kWaves * VB * 32;         // 256 output voxels per workgroup
+constexpr int wg_vox(int vb) { return kWaves * vb * 32; }      // 256 (or 128) output voxels per workgroup
 constexpr int ROW = 3;                           // taps per K step (one row of the kernel)
 constexpr int STAGE_FRAGS = CB * ROW * 2;        // 24 weight fragments (1 KB each) per K step
 constexpr int STAGE_U4 = STAGE_FRAGS * 64;       // in 16-byte pieces: 6 per thread
@@ -64,7 +65,7 @@ struct GemmArgs {
     const uint16_t *mask;    // kMask: tensor laid out like `out`; results are zeroed where it is not positive
     Geo g;
     int nci, nco;            // input chunks, output blocks
-    int nvg;                 // voxel groups of WG_VOX
+    int nvg;                 // voxel groups of wg_vox(VB)
     int nblocks;             // nvg * nco / CB real workgroups (grid is rounded up to a multiple of 8)
     int nvox;                // ntiles * ed * eh * ew: voxels of the largest output box, every tile
     int ed, eh, ew;          // largest output box of the grid (interior grown on both sides)
@@ -85,7 +86,7 @@ __device__ __forceinline__ uint32_t positive_halves(uint32_t v) {
 
 // Per-thread state of the K loop.
 struct Ctx {
-    long long pv[VB];            // padded voxel index of this lane's output voxel in segment s
+    long long pv[VBMAX];         // padded voxel index of this lane's output voxel in segment s
     int hi;                      // lane / 32: which 8 channels of a 16-channel half this lane supplies
     int tid;
     int cg;                      // first output block of the workgroup / CB
@@ -113,6 +114,7 @@ __device__ __forceinline__ void advance(const GemmArgs &a, int &i, int &r) {
 
 // Issue the loads of K step (chunk i, row r): this thread's share of the 24 weight fragments (to registers, on
 // their way to LDS) and this lane's B fragments of the step.
+template <int VB>
 __device__ __forceinline__ void fetch(const GemmArgs &a, const Ctx &c, int i, int r, uint4 (&areg)[STAGE_LOADS],
                                       bf16x8 (&b)[VB][ROW][2]) {
     const int tap0 = TAP0 + ROW * r;
@@ -137,6 +139,7 @@ __device__ __forceinline__ void fetch(const GemmArgs &a, const Ctx &c, int i, in
 }
 
 // All MFMAs of one K step: weights from LDS stage `abuf`, voxels from registers.
+template <int VB>
 __device__ __forceinline__ void contract(const char *abuf, int lane, const bf16x8 (&b)[VB][ROW][2],
                                          f32x16 (&acc)[CB][VB]) {
 #pragma unroll
@@ -161,6 +164,7 @@ __device__ __forceinline__ void contract(const char *abuf, int lane, const bf16x
 // step j - 1 into `aw`, go to the other LDS stage, which every wave left at the barrier that ended step j - 1.
 // (i, r) = chunk and kernel row of step j + 2; past the last step it stays there: those loads are harmless,
 // and what they fill is never read.
+template <int VB>
 __device__ __forceinline__ void step(const GemmArgs &a, const Ctx &c, char *cur, char *other, int lane, int &i, int &r,
                                      const bf16x8 (&bc)[VB][ROW][2], bf16x8 (&bn)[VB][ROW][2],
                                      const uint4 (&aw)[STAGE_LOADS], uint4 (&an)[STAGE_LOADS], f32x16 (&acc)[CB][VB]) {
@@ -173,7 +177,7 @@ __device__ __forceinline__ void step(const GemmArgs &a, const Ctx &c, char *cur,
     advance(a, i, r);
 }
 
-template <int RELU, bool HAS_BIAS>
+template <int RELU, bool HAS_BIAS, int VB>
 __global__ __launch_bounds__(kThreads, 1) void conv_gemm_kernel(GemmArgs a) {
     extern __shared__ __align__(16) char lds[];
     // workgroups of one XCD (blockIdx % 8) get consecutive logical ids: they share output blocks, i.e. weights
@@ -335,16 +339,22 @@ int launch_conv_gemm(const void *Pin, const void *wpack, const float *bias, void
     a.dbox = make_fastdiv(static_cast<uint32_t>(b.ed * b.eh * b.ew));
     a.dplane = make_fastdiv(static_cast<uint32_t>(b.eh * b.ew));
     a.drow = make_fastdiv(static_cast<uint32_t>(b.ew));
-    a.nvg = (a.nvox + WG_VOX - 1) / WG_VOX;
+    // 256 voxels per workgroup; 128 where that leaves at most half of the 256 compute units with a workgroup (the
+    // kernel is bound by its voxel-fragment loads, which then spread over twice the vector caches)
+    const int nvg2 = (a.nvox + wg_vox(2) - 1) / wg_vox(2);
+    const int vb = nvg2 * (a.nco / CB) <= 128 ? 1 : 2;
+    a.nvg = (a.nvox + wg_vox(vb) - 1) / wg_vox(vb);
     a.nblocks = a.nvg * (a.nco / CB);
     const unsigned grid = static_cast<unsigned>((a.nblocks + 7) / 8 * 8);
     using Kern = void (*)(GemmArgs);
-    // [bias][epilogue]; a bias never comes with a mask
-    static const Kern kern[2][3] = {
-        {conv_gemm_kernel<kNone, false>, conv_gemm_kernel<kRelu, false>, conv_gemm_kernel<kMask, false>},
-        {conv_gemm_kernel<kNone, true>, conv_gemm_kernel<kRelu, true>, conv_gemm_kernel<kMask, false>}};
+    // [segments per wave - 1][bias][epilogue]; a bias never comes with a mask
+    static const Kern kern[2][2][3] = {
+        {{conv_gemm_kernel<kNone, false, 1>, conv_gemm_kernel<kRelu, false, 1>, conv_gemm_kernel<kMask, false, 1>},
+         {conv_gemm_kernel<kNone, true, 1>, conv_gemm_kernel<kRelu, true, 1>, conv_gemm_kernel<kMask, false, 1>}},
+        {{conv_gemm_kernel<kNone, false, 2>, conv_gemm_kernel<kRelu, false, 2>, conv_gemm_kernel<kMask, false, 2>},
+         {conv_gemm_kernel<kNone, true, 2>, conv_gemm_kernel<kRelu, true, 2>, conv_gemm_kernel<kMask, false, 2>}}};
     const int epi = mask ? kMask : (relu ? kRelu : kNone);
-    hipLaunchKernelGGL(kern[bias ? 1 : 0][epi], dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
+    hipLaunchKernelGGL(kern[vb - 1][bias ? 1 : 0][epi], dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
     return record_hip(hipGetLastError());
 }
 

@@ -70,6 +70,10 @@ SMALL = [
     (1, (4, 8, 8), (1, 2, 2), 512, 128, "bf16"),       # forward, one whole voxel group
     (1, (3, 6, 10), (1, 1, 2), 128, 512, "bf16"),      # data gradient (plain and masked), ragged voxel group
     (1, (5, 16, 8), (1, 2, 1), 640, 256, "bf16"),      # three voxel groups, two groups of output blocks
+    # (the cases above fill at most half of the chip and run with 128 voxels per workgroup; these two have more
+    # than 128 workgroups of 256 voxels in the forward and in the data-gradient direction)
+    (1, (9, 32, 32), (1, 2, 2), 512, 512, "bf16"),     # 36 voxel groups x 4 groups of output blocks, both directions
+    (1, (17, 32, 32), (1, 1, 2), 512, 256, "bf16"),    # forward: 68 x 2 workgroups of 256; data gradient: 128-voxel groups
 ]
 
 
