@@ -379,8 +379,8 @@ __global__ __launch_bounds__(kThreads) void concat_kernel(E *__restrict__ a, int
 }
 
 template <typename E>
-__global__ __launch_bounds__(kThreads) void add_kernel(const E *__restrict__ a, const E *__restrict__ b,
-                                                       E *__restrict__ o, size_t n) {
+// (no __restrict__: the output may be the same tensor as either input; every thread reads and writes its own index)
+__global__ __launch_bounds__(kThreads) void add_kernel(const E *a, const E *b, E *o, size_t n) {
     const size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
     if (i < n) stf<E>(o, i, ldf<E>(a, i) + ldf<E>(b, i));
 }
@@ -401,8 +401,7 @@ __global__ __launch_bounds__(kThreads) void concat_x8_kernel(uint4 *__restrict__
 }
 
 // element-wise sum, bf16, 8 elements per thread
-__global__ __launch_bounds__(kThreads) void add_bf16x8_kernel(const uint4 *__restrict__ a, const uint4 *__restrict__ b,
-                                                              uint4 *__restrict__ o, size_t nvec) {
+__global__ __launch_bounds__(kThreads) void add_bf16x8_kernel(const uint4 *a, const uint4 *b, uint4 *o, size_t nvec) {
     const size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
     if (i >= nvec) return;
     const uint4 x = a[i], y = b[i];

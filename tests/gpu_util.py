@@ -1,4 +1,7 @@
 """Helpers for the GPU parity tests: host<->device plumbing and the error metric."""
+import sys
+import time
+
 import numpy as np
 import torch
 
@@ -57,3 +60,12 @@ def guard_alloc(shape, dtype, fill):
 
 def guards_intact(buf, fill):
     return bool((buf[:4096] == fill).all() and (buf[-4096:] == fill).all())
+
+
+_T0 = time.time()
+
+
+def progress(msg):
+    """One line on the real stderr (not captured): long oracle passes report their steps."""
+    sys.__stderr__.write("[%7.1f s] %s\n" % (time.time() - _T0, msg))
+    sys.__stderr__.flush()

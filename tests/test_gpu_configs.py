@@ -12,7 +12,7 @@ import torch
 
 from oracle import conv3d
 from paper_1909_03108_amd import sp3d, synth
-from gpu_util import TOL, bits, f64, rel_err, to_dev, widen
+from gpu_util import TOL, bits, f64, progress, rel_err, to_dev, widen
 from test_gpu_conv import Layer
 
 pytestmark = pytest.mark.gpu
@@ -346,3 +346,145 @@ def test_full_size_stack_tiled_equals_unpartitioned(stack):
         worst = max(worst, float((a - b).abs().max() / b.pow(2).mean().sqrt()))
     print("%s: weight gradients, grid %s against 1x1x1: worst |diff| / rms = %.2e" % (stack, timed_grid, worst))
     assert worst <= 1e-3
+
+
+# ---- configuration 5, layer by layer, at its real size and tile shapes ------------------------------------------
+
+def _relu_bits(a):
+    return np.where(widen(a) > 0, a, np.zeros_like(a))
+
+
+def _strided_boxes(dhw, tile, rng, nrandom):
+    """Boxes for layers whose full fp64 pass is too long: sample_boxes plus whole 8 x 8 x W columns through the
+    first, a middle and the last tile, so that every patch position along W (whole rows of the 32-column patches
+    and the march's first and last planes) is compared."""
+    D, H, W = dhw
+    boxes = sample_boxes(dhw, tile, rng, nrandom=nrandom)
+    for d0, h0 in ((0, 0), (D // 2 - 4, H // 2 - 4), (D - 8, H - 8)):
+        boxes.append((d0, d0 + 8, h0, h0 + 8, 0, W))
+    return boxes
+
+
+# cin (or (ca, cb) for the decoder layers that read concat(skip, up)), cout, cube edge.  Grid 4x4x1 throughout:
+# tiles 64x64x256, 32x32x128, 16x16x64, 8x8x32 -- the shapes `bench.py --workload c5` times.
+C5_LAYERS = [
+    (1, 32, 256), (32, 32, 256),
+    (32, 64, 128), (64, 64, 128),
+    (64, 128, 64), (128, 128, 64),
+    (128, 256, 32), (256, 256, 32),
+    ((128, 128), 128, 64),
+    ((64, 64), 64, 128),
+    ((32, 32), 32, 256),
+]
+FULL_PASS_GFLOP = 500.0       # layers up to this size are compared on every output element
+
+
+@pytest.mark.timeout(1500)
+@pytest.mark.parametrize("cin,cout,edge", C5_LAYERS,
+                         ids=["%s_to_%d_at_%d" % (str(c).replace(" ", ""), o, e) for c, o, e in C5_LAYERS])
+def test_configuration_5_layers_real_size(cin, cout, edge):
+    """Every distinct 3x3x3 layer of the configuration-5 stack (4 levels, channels 32/64/128/256, two
+    convolutions per level, decoder layers on concat(skip, up)) at its real volume and on the 4x4x1 grid, against
+    the fp64 oracle: forward with bias and ReLU, data gradient, data gradient with the ReLU mask of the layer
+    input, weight and bias gradient.  Inputs are seeded stand-ins of the right shape and distribution (a ReLU
+    output -- half zeros -- where the network has one, the CT-like volume for the first layer) and never come from
+    the GPU.  Layers of at most 0.5 TFLOP per pass are compared on every output element; the larger ones on
+    sampled boxes (volume corners, tile faces, points where four tiles meet, whole columns along W).  Weight
+    gradients are compared in full where that takes the oracle under half a minute, else on 1024 - 4096 seeded
+    entries, each a full reduction over the volume."""
+    two = isinstance(cin, tuple)
+    ca, cb = cin if two else (cin, 0)
+    ct = ca + cb
+    n, dhw, grid = 1, (edge,) * 3, (4, 4, 1)
+    L = Layer(n, dhw, grid, ct, cout, "bf16")
+    g, dt, tol = L.g, L.dt, TOL["bf16"]
+    sd = lambda k: synth.seed_for(5, 70 + k) + 1000 * (ct + cout + edge)
+    if ct == 1:
+        x = synth.ct_like_volume((n,) + dhw + (1,), sd(0), "bf16")
+    else:
+        x = _relu_bits(synth.normal_volume((n,) + dhw + (ct,), sd(0), "bf16"))
+        if two:       # the up-convolution half of the concat is not a ReLU output
+            x[..., ca:] = synth.normal_volume((n,) + dhw + (cb,), sd(1), "bf16")
+    dz = synth.normal_volume((n,) + dhw + (cout,), sd(2), "bf16")
+    w = synth.weights(ct, cout, sd(3), "bf16")
+    bias = (0.05 * np.cos(np.arange(cout))).astype(np.float32)
+    Wd, bd = widen(w), bias.astype(np.float64)
+    w_dev, b_dev = to_dev(w), torch.from_numpy(bias).cuda()
+    gflop = 2 * 27 * ct * cout * edge ** 3 / 1e9
+    rng = np.random.default_rng(edge + ct)
+    boxes = None if gflop <= FULL_PASS_GFLOP else _strided_boxes(dhw, g.tile, rng, 8)
+
+    def compare(vol_dev, fn, what, chans=slice(None)):
+        if boxes is None:
+            e = rel_err(f64(vol_dev), fn(None)[..., chans])
+        else:
+            e = max(rel_err(f64(vol_dev[:, b[0]:b[1], b[2]:b[3], b[4]:b[5]]), fn(b)[..., chans]) for b in boxes)
+        progress("c5 layer %s -> %d at %d^3: %s rel err %.2e" % (cin, cout, edge, what, e))
+        assert e <= tol, (what, e)
+
+    def crop(a, b):
+        return a if b is None else a[:, b[0]:b[1], b[2]:b[3], b[4]:b[5]]
+
+    # inputs as the network holds them: partitioned, margins exchanged
+    if two:
+        Pa, Pb = L.padded(np.ascontiguousarray(x[..., :ca]), ca), L.padded(np.ascontiguousarray(x[..., ca:]), cb)
+    else:
+        Pa = L.padded(x, ct)
+    Pz = L.padded(dz, cout)
+
+    # forward, bias, ReLU
+    Py = sp3d.alloc_padded(g, cout, dt)
+    if two:
+        sp3d.conv3d_fwd2(Pa, ca, Pb, cb, w_dev, b_dev, Py, g, cout, dt, sp3d.SP_FLAG_RELU, L.ws[sp3d.SP_OP_FWD])
+    else:
+        sp3d.conv3d_fwd(Pa, w_dev, b_dev, Py, g, ct, cout, dt, sp3d.SP_FLAG_RELU, L.ws[sp3d.SP_OP_FWD])
+    compare(L.volume(Py, cout), lambda b: conv3d.conv3d_fwd(x, Wd, bd, relu=True, box=b), "fwd")
+    del Py
+
+    # data gradient (plain), then with the ReLU mask of the layer input applied in the store
+    ref_dx = {}
+
+    def dgrad_ref(b):
+        if b not in ref_dx:
+            ref_dx[b] = conv3d.conv3d_dgrad(dz, Wd, box=b)
+        return ref_dx[b]
+
+    if two:
+        Pda, Pdb = sp3d.alloc_padded(g, ca, dt), sp3d.alloc_padded(g, cb, dt)
+        sp3d.conv3d_dgrad2(Pz, w_dev, Pda, ca, Pdb, cb, g, cout, dt, L.ws[sp3d.SP_OP_DGRAD])
+        compare(L.volume(Pda, ca), dgrad_ref, "dgrad2 a", slice(0, ca))
+        compare(L.volume(Pdb, cb), dgrad_ref, "dgrad2 b", slice(ca, ct))
+        del Pda, Pdb
+    else:
+        Pdx = sp3d.alloc_padded(g, ct, dt)
+        sp3d.conv3d_dgrad(Pz, w_dev, Pdx, g, ct, cout, dt, L.ws[sp3d.SP_OP_DGRAD])
+        dx_plain = L.volume(Pdx, ct)
+        compare(dx_plain, dgrad_ref, "dgrad")
+        if ct % 32 == 0:      # (the image gradient of the first layer has no ReLU in front of it)
+            Pdm = sp3d.alloc_padded(g, ct, dt)
+            sp3d.conv3d_dgrad_relu(Pz, w_dev, Pa, Pdm, g, ct, cout, dt, L.ws[sp3d.SP_OP_DGRAD])
+            dx_mask = L.volume(Pdm, ct)
+            compare(dx_mask, lambda b: np.where(widen(crop(x, b)) > 0, dgrad_ref(b), 0.0), "dgrad_relu")
+            keep = to_dev(x).float() > 0
+            assert torch.equal(dx_mask, torch.where(keep, dx_plain, torch.zeros_like(dx_plain)))
+            del Pdm, dx_mask, keep
+        del Pdx, dx_plain
+    ref_dx.clear()
+
+    # weight and bias gradient
+    dw = torch.full((3, 3, 3, ct, cout), 123.0, dtype=torch.float32, device="cuda")
+    db = torch.full((cout,), 123.0, dtype=torch.float32, device="cuda")
+    if two:
+        sp3d.conv3d_wgrad2(Pa, ca, Pb, cb, Pz, dw, db, g, cout, dt, L.ws[sp3d.SP_OP_WGRAD])
+    else:
+        sp3d.conv3d_wgrad(Pa, Pz, dw, db, g, ct, cout, dt, L.ws[sp3d.SP_OP_WGRAD])
+    if gflop <= 120.0:
+        assert rel_err(f64(dw), conv3d.conv3d_wgrad(x, dz)) <= tol
+    else:
+        nsel = 4096 if edge <= 128 else 1024
+        sel = np.unique(np.concatenate([rng.integers(0, 27 * ct * cout, nsel),
+                                        np.arange(27) * ct * cout + (np.arange(27) * 37) % (ct * cout)]))
+        # floor of the error measure: rms of the sampled entries (all are sums of i.i.d. products)
+        assert rel_err(f64(dw).ravel()[sel], conv3d.conv3d_wgrad(x, dz, sel=sel)) <= tol
+    assert rel_err(f64(db), conv3d.bias_grad(dz)) <= tol
+    progress("c5 layer %s -> %d at %d^3: wgrad done" % (cin, cout, edge))

@@ -182,3 +182,131 @@ def test_odd_tile_extent_is_rejected():
     with pytest.raises(sp3d.Sp3dError) as e:
         sp3d.sp_maxpool2_fwd(x, x, g, 4, sp3d.SP_BF16)
     assert e.value.code == sp3d.SP_EGEOM
+
+
+# ---- the glue of the configuration-5 stack at its real shapes (grid 4x4x1, fine volumes 256^3 / 128^3 / 64^3) ------
+
+C5_LEVELS = [(256, 32), (128, 64), (64, 128)]       # fine cube edge, channels of the level that is pooled
+
+
+def _relu_bits(a):
+    return np.where(widen(a) > 0, a, np.zeros_like(a))
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("edge,c", C5_LEVELS)
+def test_configuration_5_pools_real_size(edge, c):
+    """The three poolings of the configuration-5 stack at their real shapes: forward, backward and the encoder's
+    backward join, every element against the oracle.  The pooled tensor is a ReLU output (half zeros: windows
+    with ties are common).  Pooling is window-local, so the oracle is evaluated slab by slab along D to bound
+    host memory; selects are compared bit for bit, the join's single rounded sum to half a bf16 ulp."""
+    n, dhw, grid, dtype = 1, (edge,) * 3, (4, 4, 1), "bf16"
+    gf = sp3d.Geom(n, dhw, grid)
+    gc = sp3d.coarse_geom(gf)
+    dt = DT[dtype]
+    x = _relu_bits(draw(dtype, (n,) + dhw + (c,), 31))
+    dy = draw(dtype, (n,) + (edge // 2,) * 3 + (c,), 32)
+    skip = draw(dtype, (n,) + dhw + (c,), 33)
+    Px, Pdy, Ps = padded(gf, x, c, dt), padded(gc, dy, c, dt), padded(gf, skip, c, dt)
+    Py, Pdx, Pj = sp3d.alloc_padded(gc, c, dt), sp3d.alloc_padded(gf, c, dt), sp3d.alloc_padded(gf, c, dt)
+    sp3d.sp_maxpool2_fwd(Px, Py, gf, c, dt)
+    sp3d.sp_maxpool2_bwd(Px, Pdy, Pdx, gf, c, dt)
+    sp3d.sp_maxpool2_bwd_join(Px, Pdy, Ps, Pj, gf, c, dt)
+    y, dx, dj = (volume(g_, P, c, dt) for g_, P in ((gc, Py), (gf, Pdx), (gf, Pj)))
+    step = 32
+    for d0 in range(0, edge, step):
+        xs, ds = widen(x[:, d0:d0 + step]), widen(dy[:, d0 // 2:(d0 + step) // 2])
+        assert np.array_equal(f64(y[:, d0 // 2:(d0 + step) // 2]), U.maxpool2_fwd(xs)), ("fwd", d0)
+        ref = U.maxpool2_bwd(xs, ds)
+        assert np.array_equal(f64(dx[:, d0:d0 + step]), ref), ("bwd", d0)
+        ref = np.where(xs > 0, ref + widen(skip[:, d0:d0 + step]), 0.0)
+        assert rel_err(f64(dj[:, d0:d0 + step]), ref) <= 2.0 ** -8, ("join", d0)
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("edge,cin,cout", [(64, 256, 128), (128, 128, 64), (256, 64, 32)])
+def test_configuration_5_upconvs_real_size(edge, cin, cout):
+    """The three transposed convolutions of the configuration-5 stack at their real shapes (edge = the fine
+    side).  The operation is local to a coarse voxel, so forward and data gradient are compared on whole coarse
+    D planes (all of H and W: every tile and every segment of a row) -- every plane for the smallest level, the
+    first / last planes of every tile and seeded others for the larger ones; the weight gradient, a reduction
+    over all voxels, in full for the smallest level and on a seeded 16 x 16 block of (ci, co) pairs for every tap
+    otherwise (the definition is independent per pair); the bias gradient in full."""
+    n, dhw, grid, dtype = 1, (edge,) * 3, (4, 4, 1), "bf16"
+    gf = sp3d.Geom(n, dhw, grid)
+    gc = sp3d.coarse_geom(gf)
+    dt, tol = DT[dtype], TOL[dtype]
+    ce = edge // 2
+    x = _relu_bits(draw(dtype, (n,) + (ce,) * 3 + (cin,), 41))
+    dy = draw(dtype, (n,) + dhw + (cout,), 42)
+    u = synth.weights(cin, cout, 43, dtype, taps=(2, 2, 2))
+    bias = (0.1 * np.sin(np.arange(cout))).astype(np.float32)
+    ud = widen(u)
+    Px, Pdy = padded(gc, x, cin, dt), padded(gf, dy, cout, dt)
+    Py, Pdx = sp3d.alloc_padded(gf, cout, dt), sp3d.alloc_padded(gc, cin, dt)
+    sp3d.sp_upconv2_fwd(Px, to_dev(u), torch.from_numpy(bias).cuda(), Py, gf, cin, cout, dt)
+    sp3d.sp_upconv2_dgrad(Pdy, to_dev(u), Pdx, gf, cin, cout, dt)
+    y, dx = volume(gf, Py, cout, dt), volume(gc, Pdx, cin, dt)
+    rng = np.random.default_rng(edge)
+    td = ce // 4
+    if ce <= 32:
+        planes = list(range(ce))
+    else:
+        planes = sorted(set([a * td for a in range(4)] + [a * td + td - 1 for a in range(4)] +
+                            [int(v) for v in rng.integers(0, ce, 6)]))
+    for d in planes:
+        ref = U.upconv2_fwd(widen(x[:, d:d + 1]), ud, bias)
+        assert rel_err(f64(y[:, 2 * d:2 * d + 2]), ref) <= tol, ("fwd", d)
+        ref = U.upconv2_dgrad(widen(dy[:, 2 * d:2 * d + 2]), ud)
+        assert rel_err(f64(dx[:, d:d + 1]), ref) <= tol, ("dgrad", d)
+    du = torch.full((2, 2, 2, cin, cout), 7.0, dtype=torch.float32, device="cuda")
+    db = torch.full((cout,), 7.0, dtype=torch.float32, device="cuda")
+    ws = sp3d.alloc_ws(sp3d.sp_workspace_bytes(sp3d.SP_OP_UPCONV_WGRAD, gf, cin, cout, dt))
+    sp3d.sp_upconv2_wgrad(Px, Pdy, du, db, gf, cin, cout, dt, ws)
+    if ce <= 32:
+        ref_du, ref_db = U.upconv2_wgrad(widen(x), widen(dy))
+        assert rel_err(f64(du), ref_du) <= tol
+    else:
+        ci = np.sort(rng.choice(cin, 16, replace=False))
+        co = np.sort(rng.choice(cout, 16, replace=False))
+        ref_du, _ = U.upconv2_wgrad(widen(x[..., ci]), widen(dy[..., co]))
+        assert rel_err(f64(du)[:, :, :, ci][..., co], ref_du) <= tol
+        ref_db = widen(dy).reshape(-1, cout).sum(axis=0)
+    assert rel_err(f64(db), ref_db) <= tol
+
+
+@pytest.mark.timeout(900)
+def test_configuration_5_head_real_size():
+    """The 1x1x1 classifier 32 -> 3 on 256^3, grid 4x4x1: forward with bias, data gradient, data gradient with
+    the ReLU mask of its input, weight and bias gradient -- every element, the oracle evaluated slab by slab
+    along D (the operation is voxel-local; the weight gradient is a sum over voxels, added slab by slab)."""
+    n, dhw, grid, dtype, cin, cout = 1, (256,) * 3, (4, 4, 1), "bf16", 32, 3
+    g = sp3d.Geom(n, dhw, grid)
+    dt, tol = DT[dtype], TOL[dtype]
+    x = _relu_bits(draw(dtype, (n,) + dhw + (cin,), 51))
+    dy = draw(dtype, (n,) + dhw + (cout,), 52)
+    p = synth.weights(cin, cout, 53, dtype, taps=(1, 1, 1))
+    pw = widen(p).reshape(cin, cout)
+    bias = np.array([0.3, -0.2, 0.1], dtype=np.float32)
+    Px, Pdy = padded(g, x, cin, dt), padded(g, dy, cout, dt)
+    Py, Pdx, Pdm = sp3d.alloc_padded(g, cout, dt), sp3d.alloc_padded(g, cin, dt), sp3d.alloc_padded(g, cin, dt)
+    sp3d.sp_pointwise_fwd(Px, to_dev(p), torch.from_numpy(bias).cuda(), Py, g, cin, cout, dt)
+    sp3d.sp_pointwise_dgrad(Pdy, to_dev(p), Pdx, g, cin, cout, dt)
+    sp3d.sp_pointwise_dgrad_relu(Pdy, to_dev(p), Px, Pdm, g, cin, cout, dt)
+    dp = torch.empty((cin, cout), dtype=torch.float32, device="cuda")
+    db = torch.empty((cout,), dtype=torch.float32, device="cuda")
+    ws = sp3d.alloc_ws(sp3d.sp_workspace_bytes(sp3d.SP_OP_POINTWISE_WGRAD, g, cin, cout, dt))
+    sp3d.sp_pointwise_wgrad(Px, Pdy, dp, db, g, cin, cout, dt, ws)
+    y, dx, dm = volume(g, Py, cout, dt), volume(g, Pdx, cin, dt), volume(g, Pdm, cin, dt)
+    ref_dp, ref_db = np.zeros((cin, cout)), np.zeros(cout)
+    step = 32
+    for d0 in range(0, 256, step):
+        xs, ds = widen(x[:, d0:d0 + step]), widen(dy[:, d0:d0 + step])
+        assert rel_err(f64(y[:, d0:d0 + step]), U.pointwise_fwd(xs, pw, bias)) <= tol, ("fwd", d0)
+        ref = U.pointwise_dgrad(ds, pw)
+        assert rel_err(f64(dx[:, d0:d0 + step]), ref) <= tol, ("dgrad", d0)
+        assert rel_err(f64(dm[:, d0:d0 + step]), np.where(xs > 0, ref, 0.0)) <= tol, ("dgrad_relu", d0)
+        a, b = U.pointwise_wgrad(xs, ds)
+        ref_dp += a
+        ref_db += b
+    assert rel_err(f64(dp), ref_dp) <= tol and rel_err(f64(db), ref_db) <= tol

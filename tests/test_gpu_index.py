@@ -5,7 +5,7 @@ import torch
 
 from oracle import tiling
 from paper_1909_03108_amd import sp3d
-from gpu_util import DT, bits, guard_alloc, guards_intact, to_dev
+from gpu_util import DT, bits, guard_alloc, guards_intact, progress, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -106,3 +106,68 @@ def test_relu_bwd_mask_bit_exact():
         sp3d.sp_relu_bwd(dy, y, dz, g, 3, dt)
         ref = torch.where(y > 0, dy, torch.zeros_like(dy))
         assert torch.equal(dz, ref)
+
+
+# the geometries of the workload list's large configurations: n, dhw, grid, c
+CONFIG_GEOMETRIES = [
+    (1, (256, 256, 256), (4, 4, 2), 1),      # configuration 3, the CT volume (2-byte records)
+    (1, (256, 256, 256), (4, 4, 2), 32),     # configuration 3, 32 channels, W split
+    (1, (512, 512, 512), (4, 4, 1), 32),     # configuration 4: 128 x 128 x 512 tiles, 8.6 GB
+]
+
+
+@pytest.mark.timeout(1200)
+@pytest.mark.parametrize("n,dhw,grid,c", CONFIG_GEOMETRIES, ids=["c3_c1", "c3_c32", "c4_c32"])
+def test_index_ops_bit_exact_at_configuration_geometries(n, dhw, grid, c):
+    """partition -> pack -> unpack -> unpartition and the one-pass exchange at the full extents of
+    configurations 3 and 4, every element of the padded array, the message array and the reassembled volume
+    against the slicing oracle, as raw bits."""
+    from paper_1909_03108_amd import synth
+    g = sp3d.Geom(n, dhw, grid, 1)
+    dt, tdt, h = DT["bf16"], torch.bfloat16, 1
+    V = synth.normal_volume((n,) + dhw + (c,), 1234, "bf16")
+    fill = 7.0
+    fill_bits = bits(torch.tensor([fill], dtype=tdt, device="cuda"))[0]
+    Vd = to_dev(V)
+
+    pbuf, P = guard_alloc(g.padded_shape + (c,), tdt, fill)
+    sp3d.sp_partition(Vd, P, g, c, dt)
+    ref_P = tiling.partition(V, grid, h)
+    got = bits(P)
+    inner = (slice(None),) * 4 + (slice(h, -h),) * 3
+    assert np.array_equal(got[inner], ref_P[inner]), "partition: interiors"
+    for ax in (4, 5, 6):            # the six margin slabs of every tile still hold the fill value
+        for sl in (slice(0, h), slice(-h, None)):
+            idx = [slice(None)] * 8
+            idx[ax] = sl
+            assert np.all(got[tuple(idx)] == fill_bits), "partition wrote a margin"
+    assert guards_intact(pbuf, fill)
+    del got
+
+    mbuf, M = guard_alloc((sp3d.sp_msg_elems(g, c),), tdt, fill)
+    sp3d.halo_pack(P, M, g, c, dt)
+    ref_M = tiling.halo_pack(ref_P, h)
+    del ref_P
+    assert np.array_equal(bits(M).reshape(ref_M.shape), ref_M), "pack"
+    progress("index ops %s c=%d: partition, pack ok" % (dhw, c))
+    assert guards_intact(mbuf, fill)
+    del ref_M
+
+    sp3d.halo_unpack(P, M, g, c, dt)
+    ref_full = tiling.padded_reference(V, grid, h)
+    assert np.array_equal(bits(P), ref_full), "unpack"
+    progress("index ops %s c=%d: unpack ok" % (dhw, c))
+    assert guards_intact(pbuf, fill)
+
+    vbuf, V2 = guard_alloc((n,) + dhw + (c,), tdt, fill)
+    sp3d.sp_unpartition(P, V2, g, c, dt)
+    assert np.array_equal(bits(V2), V), "unpartition"
+    assert guards_intact(vbuf, fill)
+    del vbuf, V2
+
+    # the one-pass exchange on a freshly partitioned tensor (reusing P's memory)
+    P.fill_(fill)
+    sp3d.sp_partition(Vd, P, g, c, dt)
+    sp3d.sp_halo_exchange(P, g, c, dt)
+    assert np.array_equal(bits(P), ref_full), "one-pass exchange"
+    assert guards_intact(pbuf, fill)

@@ -3,16 +3,35 @@ import numpy as np
 import pytest
 
 from oracle import unet as OU
-from paper_1909_03108_amd import unet as PU
 
 torch = pytest.importorskip("torch")
 F = torch.nn.functional
 
 
+def weight_shapes(channels, in_ch, classes, convs, nd=3):
+    """The weight tensors the oracle's stack reads (name, shape), written out here so that this pin owes nothing
+    to the product package: `convs` 3^nd convolutions per encoder level (the first takes the previous level's
+    channels), per decoder level a 2^nd transposed convolution to the skip's width and `convs` convolutions (the
+    first on concat(skip, up)), and a 1^nd head."""
+    plan, prev = [], in_ch
+    for i, c in enumerate(channels):
+        for k in range(convs):
+            plan.append(("enc%d_%s" % (i, "abcd"[k]), (3,) * nd + (c if k else prev, c)))
+        prev = c
+    for i in reversed(range(len(channels) - 1)):
+        c = channels[i]
+        plan.append(("up%d" % i, (2,) * nd + (prev, c)))
+        for k in range(convs):
+            plan.append(("dec%d_%s" % (i, "abcd"[k]), (3,) * nd + (c if k else 2 * c, c)))
+        prev = c
+    plan.append(("head", (1,) * nd + (prev, classes)))
+    return plan
+
+
 @pytest.mark.parametrize("convs", [2, 4, 1])
 def test_unet_oracle_matches_torch_autograd(rng, convs):
     channels, in_ch, classes = (2, 3, 4), 1, 2
-    plan = PU.layer_plan(channels, in_ch, classes, convs)
+    plan = weight_shapes(channels, in_ch, classes, convs)
     w = {name: rng.standard_normal(shape) * 0.4 for name, shape in plan}
     x = rng.standard_normal((1, 4, 8, 4, in_ch))
     dl = rng.standard_normal((1, 4, 8, 4, classes))
@@ -51,7 +70,7 @@ def test_unet_oracle_matches_torch_autograd(rng, convs):
 def test_flat_unet_oracle_matches_torch_autograd(rng, convs):
     """the 2-D variant: the library's 3-D routines with kernels / windows of extent 1 along D"""
     channels, in_ch, classes = (2, 3, 4), 5, 2
-    plan = PU.layer_plan(channels, in_ch, classes, convs, flat=True)
+    plan = weight_shapes(channels, in_ch, classes, convs, nd=2)
     w = {name: rng.standard_normal(shape) * 0.4 for name, shape in plan}
     x = rng.standard_normal((1, 3, 8, 4, in_ch))
     dl = rng.standard_normal((1, 3, 8, 4, classes))
