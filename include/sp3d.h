@@ -11,7 +11,8 @@
  * General rules for every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller, at least 16-byte aligned.
  *     The library allocates nothing, frees nothing and keeps no state between calls except
- *     the code of the last HIP error.
+ *     the code of the last HIP error (and the contents of the built-in scratch buffer of
+ *     conv3d_wgrad_static, which no call relies on).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call checks
  *     its arguments on the host, enqueues its kernels on `stream` and returns without
  *     synchronising.
@@ -170,6 +171,20 @@ int conv3d_dgrad_relu(const void *Pdz, const void *w, const void *Px, void *Pdx,
  * are reproducible run to run.  dw, db are float and are overwritten (not accumulated). */
 int conv3d_wgrad(const void *Px, const void *Pdz, float *dw, float *db, const sp_geom_t *g,
                  int cin, int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream);
+
+/* conv3d_wgrad for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the partial sums go to a buffer of
+ * SP_STATIC_SCRATCH_BYTES that lives inside the library, one copy per GPU, held until the process ends.
+ * Same arguments, same kernels and the same bits in dw / db as conv3d_wgrad.  The call allocates and frees
+ * nothing; its first call on a device looks up that device's copy of the buffer (make that call outside a
+ * graph capture).  SP_EWORKSPACE, with nothing enqueued, if sp_workspace_bytes(SP_OP_WGRAD, ...) for these
+ * sizes exceeds SP_STATIC_SCRATCH_BYTES (32 MiB: enough for every layer with up to 512 x 512 channels).
+ * Nothing in the buffer has to start at zero: every partial sum that the reduction reads is written by the
+ * same call.  All calls on one GPU share the buffer: calls that overlap in time on one GPU (two streams, two
+ * host threads) race; calls on one stream, one after the other, are safe. */
+enum { SP_STATIC_SCRATCH_BYTES = 32 << 20 };
+int conv3d_wgrad_static(const void *Px, const void *Pdz, float *dw, float *db, const sp_geom_t *g,
+                        int cin, int cout, sp_dtype_t dt, void *stream);
 
 /* The three passes on a channel-wise concatenation that is never materialised (the decoder of the
  * U-Net of Sec. 3 convolves concat(skip, up)): the layer's input channels [0, ca) live in tensor a

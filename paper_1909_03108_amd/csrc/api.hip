@@ -3,10 +3,36 @@
 #include "common.h"
 
 #include <atomic>
+#include <mutex>
 
 namespace sp3d {
 
 static std::atomic<int> g_last_hip_error{0};
+
+// Scratch memory of conv3d_wgrad_static: one copy per GPU, held from module load until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress; every use of the memory (kernel
+// arguments) goes through the per-device address that static_scratch() returns.
+static __device__ __align__(256) unsigned char scratch[SP_STATIC_SCRATCH_BYTES];
+
+static int static_scratch(void **out) {
+    enum { kMaxDevices = 64 };
+    static std::mutex mu;
+    static void *addr[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return record_hip(e);
+    if (dev < 0 || dev >= kMaxDevices) return SP_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[dev]) {            // first call on this device, with it current: look its copy up once
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return record_hip(e);
+        if (!p) return SP_ELAUNCH;
+        addr[dev] = p;
+    }
+    *out = addr[dev];
+    return SP_OK;
+}
 
 int record_hip(hipError_t e) {
     if (e == hipSuccess) return SP_OK;
@@ -296,6 +322,20 @@ int conv3d_wgrad(const void *Px, const void *Pdz, float *dw, float *db, const sp
     if (mfma)
         return launch_wgrad_mfma(shifted(Px, o, cin, dt), shifted(Pdz, o, cout, dt), dw, db, o, cin, cout, ws, s);
     return launch_wgrad_direct(Px, Pdz, dw, db, o, cin, cout, dt, ws, s);
+}
+
+int conv3d_wgrad_static(const void *Px, const void *Pdz, float *dw, float *db, const sp_geom_t *g, int cin,
+                        int cout, sp_dtype_t dt, void *stream) {
+    // every argument check of conv3d_wgrad that can fail does so before the scratch address is looked up
+    Geo o;
+    int rc = check_conv_args(Px, Pdz, dw, g, cin, cout, dt, &o);
+    if (rc != SP_OK) return rc;
+    const size_t need = sp_workspace_bytes(SP_OP_WGRAD, g, cin, cout, dt);
+    if (need == static_cast<size_t>(-1)) return SP_EUNSUPPORTED;
+    if (need > static_cast<size_t>(SP_STATIC_SCRATCH_BYTES)) return SP_EWORKSPACE;
+    void *ws = nullptr;
+    if ((rc = static_scratch(&ws)) != SP_OK) return rc;
+    return conv3d_wgrad(Px, Pdz, dw, db, g, cin, cout, dt, ws, SP_STATIC_SCRATCH_BYTES, stream);
 }
 
 // ---- the same three passes on a channel-wise concatenation that is never materialised ----------------

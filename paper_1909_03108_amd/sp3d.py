@@ -9,6 +9,7 @@ import os
 SP_F32, SP_BF16 = 0, 1
 SP_OK, SP_EINVAL, SP_EGEOM, SP_EUNSUPPORTED, SP_EWORKSPACE, SP_ELAUNCH = 0, -1, -2, -3, -4, -5
 SP_FLAG_RELU = 1
+SP_STATIC_SCRATCH_BYTES = 32 << 20
 SP_OP_FWD, SP_OP_DGRAD, SP_OP_WGRAD, SP_OP_UPCONV_WGRAD, SP_OP_POINTWISE_WGRAD, SP_OP_LOSS = 0, 1, 2, 3, 4, 5
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsp3d.so")
@@ -16,7 +17,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsp3d.so"
 EXPORTS = ["sp_padded_elems", "sp_msg_elems", "sp_workspace_bytes", "sp_check_geom", "sp_strerror",
            "sp_last_hip_error", "sp_partition", "sp_unpartition", "halo_pack", "halo_unpack",
            "sp_halo_exchange",
-           "conv3d_fwd", "conv3d_dgrad", "conv3d_dgrad_relu", "conv3d_wgrad", "conv3d_fwd2", "conv3d_dgrad2",
+           "conv3d_fwd", "conv3d_dgrad", "conv3d_dgrad_relu", "conv3d_wgrad", "conv3d_wgrad_static", "conv3d_fwd2", "conv3d_dgrad2",
            "conv3d_wgrad2", "sp_relu_bwd",
            "sp_maxpool2_fwd", "sp_maxpool2_bwd", "sp_maxpool2_bwd_join", "sp_upconv2_fwd", "sp_upconv2_dgrad", "sp_upconv2_wgrad",
            "sp_pointwise_fwd", "sp_pointwise_dgrad", "sp_pointwise_dgrad_relu", "sp_pointwise_wgrad", "sp_concat", "sp_split", "sp_add",
@@ -80,6 +81,7 @@ def lib():
         L.conv3d_dgrad.argtypes, L.conv3d_dgrad.restype = [P, P, P, G, I, I, I, P, Z, P], I
         L.conv3d_dgrad_relu.argtypes, L.conv3d_dgrad_relu.restype = [P, P, P, P, G, I, I, I, P, Z, P], I
         L.conv3d_wgrad.argtypes, L.conv3d_wgrad.restype = [P, P, P, P, G, I, I, I, P, Z, P], I
+        L.conv3d_wgrad_static.argtypes, L.conv3d_wgrad_static.restype = [P, P, P, P, G, I, I, I, P], I
         L.conv3d_fwd2.argtypes, L.conv3d_fwd2.restype = [P, I, P, I, P, P, P, G, I, I, U, P, Z, P], I
         L.conv3d_dgrad2.argtypes, L.conv3d_dgrad2.restype = [P, P, P, I, P, I, G, I, I, P, Z, P], I
         L.conv3d_wgrad2.argtypes, L.conv3d_wgrad2.restype = [P, I, P, I, P, P, P, G, I, I, P, Z, P], I
@@ -209,6 +211,11 @@ def conv3d_wgrad(Px, Pdz, dw, db, g, cin, cout, dt, ws=None, stream=None):
     wp, wb = _ws(ws)
     _check(lib().conv3d_wgrad(_ptr(Px), _ptr(Pdz), _ptr(dw), _ptr(db), ctypes.byref(g), cin, cout, dt,
                               wp, wb, _stream(stream)), "conv3d_wgrad")
+
+
+def conv3d_wgrad_static(Px, Pdz, dw, db, g, cin, cout, dt, stream=None):
+    _check(lib().conv3d_wgrad_static(_ptr(Px), _ptr(Pdz), _ptr(dw), _ptr(db), ctypes.byref(g), cin, cout, dt,
+                                     _stream(stream)), "conv3d_wgrad_static")
 
 
 def sp_relu_bwd(Pdy, Py, Pdz, g, c, dt, stream=None):
