@@ -8,6 +8,12 @@ One "step" is one pass of the whole path over one synthetic 512^3 x 32-channel b
     partition dy -> halo pack -> halo unpack -> conv3d_dgrad -> unpartition dx
     conv3d_wgrad (dw, db)
 
+The padded arrays are zeroed once when they are allocated, so the step's halo calls carry the SP_HALO_* flags:
+nothing is packed for directions in which a tile has no neighbour and the zero margins at the volume border are
+not rewritten.  Their bandwidth figures count the bytes such a call moves (regions with a neighbour, read once
+and written once); the same calls without the flags (every region packed, border margins zero-filled) are timed
+after the step and reported beside them with their own byte counts.
+
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.  `value` is 3 conv passes'
 FLOPs divided by the whole step time, i.e. it is charged for partitioning and halo exchange too;
 `roofline` rates the dominant kernel (algorithmic FLOPs of one launch / its HIP-event time) against the
@@ -56,6 +62,9 @@ def parse():
     ap.add_argument("--halo", type=int, default=1, choices=[1, 2],
                     help="U-Net workloads: margin width of the layout; 2 = two layers of a block share one exchange "
                          "(the first also computes the voxel shell the second reads)")
+    ap.add_argument("--gather", action="store_true",
+                    help="U-Net workloads: no halo exchange where the kernels can gather (SP_HALO_GATHER: the "
+                         "convolutions read their margin voxels from the neighbour tiles' interiors)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (torch copy_) so that profiler "
                          "byte counters can be scaled against a kernel of known traffic")
@@ -96,7 +105,8 @@ def bench_unet(args):
     w = {name: dev(synth.weights(shape[nd], shape[nd + 1], synth.seed_for(5, synth.T_WEIGHT0 + k), "bf16",
                                  taps=shape[:nd])) for k, (name, shape) in enumerate(plan)}
     dl = dev(synth.normal_volume((n,) + dhw + (classes,), synth.seed_for(5, synth.T_UPSTREAM), "bf16"))
-    net = unet.UNet(n, dhw, grid, w, channels, in_ch, classes, convs=convs, halo=args.halo, flat=flat)
+    net = unet.UNet(n, dhw, grid, w, channels, in_ch, classes, convs=convs, halo=args.halo, flat=flat,
+                    gather=args.gather)
 
     labels = None
     if args.loss:
@@ -143,7 +153,8 @@ def bench_unet(args):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": name + (", grid %dx%dx%d, halo %d, forward + backward (weight and data gradients, "
                                        "no image gradient)" % (grid + (args.halo,))) + (", upstream gradient from the Dice + CE loss"
-                                                              if args.loss else ""),
+                                                              if args.loss else "")
+                               + (", halos gathered by the convolutions (no exchange)" if args.gather else ""),
                    "tflop_per_step": round(flop / 1e12, 2),
                    "hbm_allocated_gb": round(torch.cuda.max_memory_allocated() / 1e9, 1)}}))
 
@@ -189,16 +200,17 @@ def main():
     db = torch.empty((c,), dtype=torch.float32, device="cuda")
     wsp = {op: sp3d.alloc_ws(sp3d.sp_workspace_bytes(op, g, c, c, dt)) for op in (0, 1, 2)}
     stream = torch.cuda.current_stream()
+    gb = g.with_opts(sp3d.SP_HALO_SKIP_SEND | sp3d.SP_HALO_KEEP_ZERO)    # halo calls of the step
 
     calls = [
         ("sp_partition", lambda: sp3d.sp_partition(x_vol, Px, g, c, dt, stream)),
-        ("halo_pack", lambda: sp3d.halo_pack(Px, M, g, c, dt, stream)),
-        ("halo_unpack", lambda: sp3d.halo_unpack(Px, M, g, c, dt, stream)),
+        ("halo_pack", lambda: sp3d.halo_pack(Px, M, gb, c, dt, stream)),
+        ("halo_unpack", lambda: sp3d.halo_unpack(Px, M, gb, c, dt, stream)),
         ("conv3d_fwd", lambda: sp3d.conv3d_fwd(Px, w, None, Py, g, c, c, dt, 0, wsp[0], stream)),
         ("sp_unpartition", lambda: sp3d.sp_unpartition(Py, y_vol, g, c, dt, stream)),
         ("sp_partition", lambda: sp3d.sp_partition(dy_vol, Pdy, g, c, dt, stream)),
-        ("halo_pack", lambda: sp3d.halo_pack(Pdy, M, g, c, dt, stream)),
-        ("halo_unpack", lambda: sp3d.halo_unpack(Pdy, M, g, c, dt, stream)),
+        ("halo_pack", lambda: sp3d.halo_pack(Pdy, M, gb, c, dt, stream)),
+        ("halo_unpack", lambda: sp3d.halo_unpack(Pdy, M, gb, c, dt, stream)),
         ("conv3d_dgrad", lambda: sp3d.conv3d_dgrad(Pdy, w, Pdx, g, c, c, dt, wsp[1], stream)),
         ("sp_unpartition", lambda: sp3d.sp_unpartition(Pdx, dx_vol, g, c, dt, stream)),
         ("conv3d_wgrad", lambda: sp3d.conv3d_wgrad(Px, Pdy, dw, db, g, c, c, dt, wsp[2], stream)),
@@ -235,30 +247,37 @@ def main():
 
     gemm_tflops = None
     if args.calib_gemm:
-        ga = torch.randn(8192, 8192, device="cuda").bfloat16()
-        gb = torch.randn(8192, 8192, device="cuda").bfloat16()
+        ma = torch.randn(8192, 8192, device="cuda").bfloat16()
+        mb = torch.randn(8192, 8192, device="cuda").bfloat16()
         for _ in range(3):
-            gc_ = ga @ gb
+            mc = ma @ mb
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(20):
-            gc_ = ga @ gb
+            mc = ma @ mb
         e1.record()
         torch.cuda.synchronize()
         gemm_tflops = 20 * 2.0 * 8192 ** 3 / (e0.elapsed_time(e1) * 1e-3) / 1e12
-        del ga, gb, gc_
+        del ma, mb, mc
 
-    # outside the timed step: the one-pass exchange (what a one-GPU caller would use instead of pack + unpack)
-    ex = []
-    for _ in range(10):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        sp3d.sp_halo_exchange(Px, g, c, dt, stream)
-        e1.record(stream)
-        ex.append((e0, e1))
-    torch.cuda.synchronize()
-    exchange_ms = sorted(a.elapsed_time(b) for a, b in ex)[len(ex) // 2]
+    # outside the timed step: the one-pass exchange (what a one-GPU caller would use instead of pack + unpack), and
+    # pack / unpack / exchange without the border flags (all 26 regions packed, border margins zero-filled)
+    def median_ms(f, reps=10):
+        ev = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            f()
+            e1.record(stream)
+            ev.append((e0, e1))
+        torch.cuda.synchronize()
+        return sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
+
+    exchange_ms = median_ms(lambda: sp3d.sp_halo_exchange(Px, gb, c, dt, stream))
+    full_ms = {"halo_pack": median_ms(lambda: sp3d.halo_pack(Px, M, g, c, dt, stream)),
+               "halo_unpack": median_ms(lambda: sp3d.halo_unpack(Px, M, g, c, dt, stream)),
+               "sp_halo_exchange": median_ms(lambda: sp3d.sp_halo_exchange(Px, g, c, dt, stream))}
 
     per = {}
     for name, e0, e1 in events:
@@ -280,7 +299,10 @@ def main():
     roofline = {"kernel": "conv_mfma_kernel (conv3d_fwd / conv3d_dgrad)", "bound": "mfma",
                 "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(S)}
+                "traffic": MEASURED_TRAFFIC_BYTES.get(S),
+                "traffic_source": ("not measured in this run: a constant taken from the rocprofv3 --pmc FETCH_SIZE / "
+                                   "WRITE_SIZE runs summarised in profiles/bench_512_hbm_traffic.md"
+                                   if MEASURED_TRAFFIC_BYTES.get(S) else None)}
     msg_bytes = sp3d.sp_msg_elems(g, c) * 2
     # halo_unpack writes every margin region and reads only those whose neighbour tile exists
     tile = (S // grid[0], S // grid[1], S // grid[2])
@@ -294,18 +316,27 @@ def main():
             region *= tile[ax] if delta[ax] == 0 else 1
             tiles *= grid[ax] if delta[ax] == 0 else grid[ax] - 1
         nb_vox += n * tiles * region
-    unpack_bytes = msg_bytes + nb_vox * c * 2
+    nb_bytes = nb_vox * c * 2              # message bytes that have a receiving tile
+    unpack_bytes = msg_bytes + nb_bytes    # without the flags: every margin written, those with a neighbour read
+
+    def hbm(kernel, nbytes, ms, note):
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        return {"kernel": kernel, "bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(gbs / PEAK_HBM_GBS, 4), "bytes": int(nbytes), "ms": round(ms, 4), "what": note}
+
     other = [
         {"kernel": "wgrad_mfma_kernel (conv3d_wgrad)", "bound": "mfma",
          "achieved": round(flop_pass / (avg_ms["conv3d_wgrad"] * 1e-3) / 1e12, 1),
          "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
          "frac": round(flop_pass / (avg_ms["conv3d_wgrad"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)},
-        {"kernel": "halo_pack", "bound": "hbm",
-         "achieved": round(2 * msg_bytes / (avg_ms["halo_pack"] * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
-         "unit": "GB/s", "frac": round(2 * msg_bytes / (avg_ms["halo_pack"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
-        {"kernel": "halo_unpack", "bound": "hbm",
-         "achieved": round(unpack_bytes / (avg_ms["halo_unpack"] * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
-         "unit": "GB/s", "frac": round(unpack_bytes / (avg_ms["halo_unpack"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+        hbm("halo_pack", 2 * nb_bytes, avg_ms["halo_pack"],
+            "in the step, SP_HALO_SKIP_SEND: the regions that have a receiver, read + written once"),
+        hbm("halo_unpack", 2 * nb_bytes, avg_ms["halo_unpack"],
+            "in the step, SP_HALO_KEEP_ZERO: the margins that have a neighbour, read + written once"),
+        hbm("halo_pack, all 26 regions", 2 * msg_bytes, full_ms["halo_pack"],
+            "after the step, no flags: every region read + written (a third of them have no receiver on this grid)"),
+        hbm("halo_unpack, border zero-filled", unpack_bytes, full_ms["halo_unpack"],
+            "after the step, no flags: every margin written, those with a neighbour read"),
         {"kernel": "sp_unpartition", "bound": "hbm",
          "achieved": round(2 * vox * c * 2 / (avg_ms["sp_unpartition"] * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
          "unit": "GB/s",
@@ -337,6 +368,7 @@ def main():
                                                                    + avg_ms["conv3d_wgrad"]) * 1e-3) / 1e12
                                                   / PEAK_BF16_TFLOPS, 4)},
         "halo_exchange_fused_ms": round(exchange_ms, 4),
+        "halo_exchange_fused_zero_fill_ms": round(full_ms["sp_halo_exchange"], 4),
         "library_gemm_tflops": None if gemm_tflops is None else round(gemm_tflops, 1),
         "roofline": roofline,
         "roofline_other": other,

@@ -64,6 +64,7 @@ typedef struct sp_geom {
     int32_t halo;         /* margin width of the layout, 1..SP_MAX_HALO          */
     int32_t grow;         /* conv3d_fwd*, conv3d_dgrad*: 0 <= grow < halo, see below; ignored elsewhere */
     int32_t flat;         /* 0: 3-D operations; 1: the 2-D variant (D = stack of slices), see above       */
+    int32_t opts;         /* SP_HALO_* flags, see below; 0 = none                                           */
 } sp_geom_t;
 
 enum { SP_MAX_HALO = 4 };
@@ -80,6 +81,25 @@ enum {
 };
 
 enum { SP_FLAG_RELU = 1 };                                /* conv3d_fwd: y = max(z, 0) */
+/* sp_geom_t.opts.  A tile at the border of the volume has no neighbour in some directions: nothing it packs
+ * for them is ever delivered, and the margins lying there are zero padding, not received data.
+ *   SP_HALO_SKIP_SEND  halo_pack does not write the message regions that have no receiver (they keep whatever
+ *                      they held).
+ *   SP_HALO_KEEP_ZERO  halo_unpack and sp_halo_exchange do not write the margin regions at the volume border:
+ *                      the caller guarantees that they hold zeros already.  A padded array that was zeroed once
+ *                      stays that way, since no entry point writes margins beyond the volume border (the
+ *                      convolutions with `grow` stop there too).
+ *   SP_HALO_GATHER     conv3d_fwd*, conv3d_dgrad*, conv3d_wgrad*: the exchange fused into the convolution (Fig. 1b
+ *                      and Sec. 2 with all tiles in one memory): wherever the call would read a margin voxel of
+ *                      its input tensor that has a neighbour tile, it reads the voxel that the exchange would have
+ *                      copied there - the neighbour's own voxel - so the input needs no halo_pack / halo_unpack /
+ *                      sp_halo_exchange at all, and its margins towards neighbours are neither read nor written.
+ *                      Margins at the volume border are read from the tensor and must hold zeros (as after
+ *                      SP_HALO_KEEP_ZERO).  Same bits as the exchange followed by the plain call.  bf16 with
+ *                      channel counts in multiples of 32, halo = 1, grow = 0, 3-D; the weight gradient also needs
+ *                      tile extents along H and W in multiples of 8 and 32.  SP_EUNSUPPORTED otherwise (exchange
+ *                      and call without the flag instead). */
+enum { SP_HALO_SKIP_SEND = 1, SP_HALO_KEEP_ZERO = 2, SP_HALO_GATHER = 4 };
 enum {                                                    /* sp_workspace_bytes `op`   */
     SP_OP_FWD = 0, SP_OP_DGRAD = 1, SP_OP_WGRAD = 2,      /* the 3x3x3 convolution     */
     SP_OP_UPCONV_WGRAD = 3,                               /* sp_upconv2_wgrad          */
@@ -98,6 +118,9 @@ size_t sp_msg_elems(const sp_geom_t *g, int c);
  * included): ask with the geometry that the call will get.  What a call leaves in the workspace is
  * of no use to the caller. */
 size_t sp_workspace_bytes(int op, const sp_geom_t *g, int cin, int cout, sp_dtype_t dt);
+/* 1 if conv3d_fwd* (op = SP_OP_FWD), conv3d_dgrad* (SP_OP_DGRAD) or conv3d_wgrad* (SP_OP_WGRAD) accepts
+ * SP_HALO_GATHER for these sizes (g->opts itself is not looked at), else 0. */
+int sp_gather_supported(int op, const sp_geom_t *g, int cin, int cout, sp_dtype_t dt);
 /* SP_OK or the error the geometry would raise. */
 int sp_check_geom(const sp_geom_t *g);
 const char *sp_strerror(int code);
@@ -114,13 +137,14 @@ int sp_unpartition(const void *P, void *vol, const sp_geom_t *g, int c, sp_dtype
 
 /* ---- halo exchange (Fig. 1b; Sec. 2: "exchange margins ... pad the patches") ---------------- */
 
-/* Sending side: copy the 26 boundary regions of every tile's interior into its message.
- * Reads P's interiors only.  Bit-exact. */
+/* Sending side: copy the 26 boundary regions of every tile's interior into its message (with
+ * SP_HALO_SKIP_SEND: those that have a receiving tile).  Reads P's interiors only.  Bit-exact. */
 int halo_pack(const void *P, void *msg, const sp_geom_t *g, int c, sp_dtype_t dt, void *stream);
 /* Receiving side: for every tile and direction `dir`, fill the margin region lying in direction
  * `dir` from region -dir of the message of the neighbour tile at +dir; zero-fill it when that
- * neighbour is outside the grid (zero 'same' padding at the volume border).  Writes margins
- * only; interiors are untouched.  P is updated in place.  Bit-exact. */
+ * neighbour is outside the grid (zero 'same' padding at the volume border; with SP_HALO_KEEP_ZERO
+ * such a region is left as it is).  Writes margins only; interiors are untouched.  P is updated in
+ * place.  Bit-exact. */
 int halo_unpack(void *P, const void *msg, const sp_geom_t *g, int c, sp_dtype_t dt, void *stream);
 /* halo_pack + delivery + halo_unpack in one pass for the case that all tiles live in one memory
  * (Sec. 2, Fig. 1b with the sending and the receiving device being the same): every margin region

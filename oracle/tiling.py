@@ -147,6 +147,24 @@ def halo_unpack(P, M, h=1):
     return out
 
 
+def delivered(grid, tile, h=1):
+    """Which entries of the message array anyone receives: [gd,gh,gw,R] booleans, True for the voxels of a
+    region whose direction leads to a tile of the grid.  (Fig. 1b: margins are exchanged between neighbouring
+    patches; a patch at the border of the image has no neighbour on that side.)"""
+    gd, gh, gw = grid
+    sizes = region_sizes(tile, h)
+    offs = np.concatenate(([0], np.cumsum(sizes)))
+    out = np.zeros((gd, gh, gw, offs[-1]), dtype=bool)
+    for k, delta in enumerate(DIRECTIONS):
+        for a in range(gd):
+            for b in range(gh):
+                for c in range(gw):
+                    na, nb, nc = a + delta[0], b + delta[1], c + delta[2]
+                    if 0 <= na < gd and 0 <= nb < gh and 0 <= nc < gw:
+                        out[a, b, c, offs[k]:offs[k + 1]] = True
+    return out
+
+
 def exchange(P, h=1):
     """pack followed by unpack."""
     return halo_unpack(P, halo_pack(P, h), h)

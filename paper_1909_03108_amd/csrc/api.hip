@@ -44,7 +44,7 @@ int make_geo(const sp_geom_t *g, Geo *out) {
     if (!g) return SP_EINVAL;
     if (g->n <= 0 || g->d <= 0 || g->h <= 0 || g->w <= 0 || g->gd <= 0 || g->gh <= 0 ||
         g->gw <= 0 || g->halo < 0 || g->grow < 0 || (g->grow > 0 && g->grow >= g->halo) ||
-        (g->flat != 0 && g->flat != 1))
+        (g->flat != 0 && g->flat != 1) || (g->opts & ~(SP_HALO_SKIP_SEND | SP_HALO_KEEP_ZERO | SP_HALO_GATHER)))
         return SP_EINVAL;
     if (g->d % g->gd || g->h % g->gh || g->w % g->gw) return SP_EGEOM;
     if (g->halo < 1 || g->halo > SP_MAX_HALO) return SP_EUNSUPPORTED;
@@ -122,6 +122,17 @@ size_t sp_msg_elems(const sp_geom_t *g, int c) {
 }
 
 int sp_check_geom(const sp_geom_t *g) { return make_geo(g, nullptr); }
+
+int sp_gather_supported(int op, const sp_geom_t *g, int cin, int cout, sp_dtype_t dt) {
+    Geo o;
+    if (make_geo(g, &o) != SP_OK || !chan_ok(cin) || !chan_ok(cout) || !dtype_ok(dt)) return 0;
+    switch (op) {
+    case SP_OP_FWD: return conv_mfma_gather_supported(o, cin, cout, dt) ? 1 : 0;
+    case SP_OP_DGRAD: return conv_mfma_gather_supported(o, cout, cin, dt) ? 1 : 0;     // channel roles swapped
+    case SP_OP_WGRAD: return wgrad_mfma_gather_supported(o, cin, cout, dt) ? 1 : 0;
+    default: return 0;
+    }
+}
 
 size_t sp_workspace_bytes(int op, const sp_geom_t *g, int cin, int cout, sp_dtype_t dt) {
     Geo o;
@@ -213,7 +224,7 @@ int halo_pack(const void *P, void *msg, const sp_geom_t *g, int c, sp_dtype_t dt
     if (overlap(P, static_cast<size_t>(o.ntiles) * o.tile_vox * c * es, msg,
                 static_cast<size_t>(o.ntiles) * o.msg_vox * c * es))
         return SP_EINVAL;
-    return launch_halo_pack(P, msg, o, c, dt, static_cast<hipStream_t>(stream));
+    return launch_halo_pack(P, msg, o, c, dt, g->opts, static_cast<hipStream_t>(stream));
 }
 
 int halo_unpack(void *P, const void *msg, const sp_geom_t *g, int c, sp_dtype_t dt, void *stream) {
@@ -224,14 +235,14 @@ int halo_unpack(void *P, const void *msg, const sp_geom_t *g, int c, sp_dtype_t 
     if (overlap(P, static_cast<size_t>(o.ntiles) * o.tile_vox * c * es, msg,
                 static_cast<size_t>(o.ntiles) * o.msg_vox * c * es))
         return SP_EINVAL;
-    return launch_halo_unpack(P, msg, o, c, dt, static_cast<hipStream_t>(stream));
+    return launch_halo_unpack(P, msg, o, c, dt, g->opts, static_cast<hipStream_t>(stream));
 }
 
 int sp_halo_exchange(void *P, const sp_geom_t *g, int c, sp_dtype_t dt, void *stream) {
     Geo o;
     int rc = check_copy_args(P, P, g, c, dt, &o);
     if (rc != SP_OK) return rc;
-    return launch_halo_exchange(P, o, c, dt, static_cast<hipStream_t>(stream));
+    return launch_halo_exchange(P, o, c, dt, g->opts, static_cast<hipStream_t>(stream));
 }
 
 static int check_conv_args(const void *a, const void *b, const void *c, const sp_geom_t *g, int cin,
@@ -257,10 +268,12 @@ int conv3d_fwd(const void *Px, const void *w, const float *bias, void *Py, const
     if (overlap(Px, pv * cin * es, Py, pv * cout * es)) return SP_EINVAL;
     const bool relu = flags & SP_FLAG_RELU;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool gather = g->opts & SP_HALO_GATHER;
+    if (gather && !conv_mfma_gather_supported(o, cin, cout, dt)) return SP_EUNSUPPORTED;
     if (conv_mfma_supported(o, cin, cout, dt)) {
         const size_t need = conv_mfma_ws_bytes(o, cin, cout);
         if (need && (!ws || ws_bytes < need || !aligned16(ws))) return SP_EWORKSPACE;
-        return launch_conv_mfma(Px, w, bias, Py, o, cin, cout, relu, false, ws, s);
+        return launch_conv_mfma(Px, w, bias, Py, o, cin, cout, relu, false, ws, s, nullptr, nullptr, gather);
     }
     if (o.grow == 0 && conv_c1_supported(o, cin, cout, dt))
         return launch_conv_c1_fwd(shifted(Px, o, 1, dt), w, bias, shifted(Py, o, cout, dt), o, cout, relu, s);
@@ -284,10 +297,12 @@ static int dgrad_impl(const void *Pdz, const void *w, const void *Pmask, void *P
     if (Pmask && (!aligned16(Pmask) || overlap(Pmask, pv * cin * es, Pdx, pv * cin * es))) return SP_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     // the kernel's "input channels" are cout and its "output channels" are cin
+    const bool gather = g->opts & SP_HALO_GATHER;
+    if (gather && !conv_mfma_gather_supported(o, cout, cin, dt)) return SP_EUNSUPPORTED;
     if (conv_mfma_supported(o, cout, cin, dt)) {
         const size_t need = conv_mfma_ws_bytes(o, cout, cin);
         if (need && (!ws || ws_bytes < need || !aligned16(ws))) return SP_EWORKSPACE;
-        return launch_conv_mfma(Pdz, w, nullptr, Pdx, o, cout, cin, false, true, ws, s, Pmask);
+        return launch_conv_mfma(Pdz, w, nullptr, Pdx, o, cout, cin, false, true, ws, s, Pmask, nullptr, gather);
     }
     return launch_conv_direct(Pdz, w, nullptr, Pdx, o, cout, cin, dt, false, true, s, 3, Pmask);
 }
@@ -310,6 +325,8 @@ int conv3d_wgrad(const void *Px, const void *Pdz, float *dw, float *db, const sp
     if (rc != SP_OK) return rc;
     if (db && (reinterpret_cast<uintptr_t>(db) & 3u)) return SP_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool gather = g->opts & SP_HALO_GATHER;
+    if (gather && !wgrad_mfma_gather_supported(o, cin, cout, dt)) return SP_EUNSUPPORTED;
     const bool c1 = conv_c1_supported(o, cin, cout, dt);
     const bool mfma = !c1 && wgrad_mfma_supported(o, cin, cout, dt);
     const bool pad = !c1 && !mfma && chan_pad_supported(o, cin, cout, dt);
@@ -320,7 +337,8 @@ int conv3d_wgrad(const void *Px, const void *Pdz, float *dw, float *db, const sp
     if (pad) return launch_wgrad_chan_pad(Px, Pdz, dw, db, o, cin, cout, dt, ws, s);
     if (c1) return launch_wgrad_c1(shifted(Px, o, 1, dt), shifted(Pdz, o, cout, dt), dw, db, o, cout, ws, s);
     if (mfma)
-        return launch_wgrad_mfma(shifted(Px, o, cin, dt), shifted(Pdz, o, cout, dt), dw, db, o, cin, cout, ws, s);
+        return launch_wgrad_mfma(shifted(Px, o, cin, dt), shifted(Pdz, o, cout, dt), dw, db, o, cin, cout, ws, s, nullptr, 0,
+                                 gather);
     return launch_wgrad_direct(Px, Pdz, dw, db, o, cin, cout, dt, ws, s);
 }
 
@@ -357,13 +375,15 @@ int conv3d_fwd2(const void *Pxa, int ca, const void *Pxb, int cb, const void *w,
     if ((rc = check_pair(Pxa, ca, Pxb, cb, dt)) != SP_OK) return rc;
     if (flags & ~static_cast<uint32_t>(SP_FLAG_RELU)) return SP_EINVAL;
     if (!conv_mfma_supported(o, ca + cb, cout, dt)) return SP_EUNSUPPORTED;
+    const bool gather = g->opts & SP_HALO_GATHER;
+    if (gather && !conv_mfma_gather_supported(o, ca + cb, cout, dt)) return SP_EUNSUPPORTED;
     const size_t pv = static_cast<size_t>(o.ntiles) * o.tile_vox;
     if (overlap(Pxa, pv * ca * 2, Py, pv * cout * 2) || overlap(Pxb, pv * cb * 2, Py, pv * cout * 2)) return SP_EINVAL;
     const size_t need = conv_mfma_ws_bytes(o, ca + cb, cout);
     if (need && (!ws || ws_bytes < need || !aligned16(ws))) return SP_EWORKSPACE;
     const ConvSplit sp{Pxb, ca, nullptr, 0};
     return launch_conv_mfma(Pxa, w, bias, Py, o, ca + cb, cout, flags & SP_FLAG_RELU, false, ws,
-                            static_cast<hipStream_t>(stream), nullptr, &sp);
+                            static_cast<hipStream_t>(stream), nullptr, &sp, gather);
 }
 
 int conv3d_dgrad2(const void *Pdz, const void *w, void *Pdxa, int ca, void *Pdxb, int cb, const sp_geom_t *g,
@@ -373,6 +393,8 @@ int conv3d_dgrad2(const void *Pdz, const void *w, void *Pdxa, int ca, void *Pdxb
     if (rc != SP_OK) return rc;
     if ((rc = check_pair(Pdxa, ca, Pdxb, cb, dt)) != SP_OK) return rc;
     if (!conv_mfma_supported(o, cout, ca + cb, dt)) return SP_EUNSUPPORTED;
+    const bool gather = g->opts & SP_HALO_GATHER;
+    if (gather && !conv_mfma_gather_supported(o, cout, ca + cb, dt)) return SP_EUNSUPPORTED;
     const size_t pv = static_cast<size_t>(o.ntiles) * o.tile_vox;
     if (overlap(Pdz, pv * cout * 2, Pdxa, pv * ca * 2) || overlap(Pdz, pv * cout * 2, Pdxb, pv * cb * 2) ||
         overlap(Pdxa, pv * ca * 2, Pdxb, pv * cb * 2))
@@ -381,7 +403,7 @@ int conv3d_dgrad2(const void *Pdz, const void *w, void *Pdxa, int ca, void *Pdxb
     if (need && (!ws || ws_bytes < need || !aligned16(ws))) return SP_EWORKSPACE;
     const ConvSplit sp{nullptr, 0, Pdxb, ca};
     return launch_conv_mfma(Pdz, w, nullptr, Pdxa, o, cout, ca + cb, false, true, ws,
-                            static_cast<hipStream_t>(stream), nullptr, &sp);
+                            static_cast<hipStream_t>(stream), nullptr, &sp, gather);
 }
 
 int conv3d_wgrad2(const void *Pxa, int ca, const void *Pxb, int cb, const void *Pdz, float *dw, float *db,
@@ -392,10 +414,12 @@ int conv3d_wgrad2(const void *Pxa, int ca, const void *Pxb, int cb, const void *
     if ((rc = check_pair(Pxa, ca, Pxb, cb, dt)) != SP_OK) return rc;
     if (db && (reinterpret_cast<uintptr_t>(db) & 3u)) return SP_EINVAL;
     if (!wgrad_mfma_supported(o, ca + cb, cout, dt)) return SP_EUNSUPPORTED;
+    const bool gather = g->opts & SP_HALO_GATHER;
+    if (gather && !wgrad_mfma_gather_supported(o, ca + cb, cout, dt)) return SP_EUNSUPPORTED;
     const size_t need = wgrad_mfma_ws_bytes(o, ca + cb, cout);
     if (!ws || ws_bytes < need || !aligned16(ws)) return SP_EWORKSPACE;
     return launch_wgrad_mfma(shifted(Pxa, o, ca, dt), shifted(Pdz, o, cout, dt), dw, db, o, ca + cb, cout, ws,
-                             static_cast<hipStream_t>(stream), shifted(Pxb, o, cb, dt), ca);
+                             static_cast<hipStream_t>(stream), shifted(Pxb, o, cb, dt), ca, gather);
 }
 
 int sp_relu_bwd(const void *Pdy, const void *Py, void *Pdz, const sp_geom_t *g, int c, sp_dtype_t dt,

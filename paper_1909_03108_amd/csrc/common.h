@@ -55,9 +55,10 @@ void make_regions(const Geo &g, RegionTable *t);
 // launchers implemented in the kernel sources -------------------------------------------------
 int launch_partition(const void *vol, void *P, const Geo &g, int c, sp_dtype_t dt, bool inverse,
                      hipStream_t s);
-int launch_halo_pack(const void *P, void *msg, const Geo &g, int c, sp_dtype_t dt, hipStream_t s);
-int launch_halo_unpack(void *P, const void *msg, const Geo &g, int c, sp_dtype_t dt, hipStream_t s);
-int launch_halo_exchange(void *P, const Geo &g, int c, sp_dtype_t dt, hipStream_t s);
+// border: the SP_HALO_* flags of the call's geometry
+int launch_halo_pack(const void *P, void *msg, const Geo &g, int c, sp_dtype_t dt, int border, hipStream_t s);
+int launch_halo_unpack(void *P, const void *msg, const Geo &g, int c, sp_dtype_t dt, int border, hipStream_t s);
+int launch_halo_exchange(void *P, const Geo &g, int c, sp_dtype_t dt, int border, hipStream_t s);
 int launch_relu_bwd(const void *dy, const void *y, void *dz, size_t elems, sp_dtype_t dt,
                     hipStream_t s);
 
@@ -122,9 +123,11 @@ struct ConvSplit {
     void *out2; int out_ca;
 };
 // mask (optional, data gradient): tensor laid out like Pout; results are zeroed where it is not positive
+// gather: margin voxels that have a neighbour tile are read from that tile's interior (SP_HALO_GATHER)
+bool conv_mfma_gather_supported(const Geo &g, int cin, int cout, sp_dtype_t dt);
 int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Pout, const Geo &g,
                      int cin, int cout, bool relu, bool dgrad, void *ws, hipStream_t s,
-                     const void *mask = nullptr, const ConvSplit *split = nullptr);
+                     const void *mask = nullptr, const ConvSplit *split = nullptr, bool gather = false);
 
 // wide layers on few voxels: output-stationary implicit GEMM on the packed weights (conv_gemm.hip);
 // launch_conv_mfma hands such layers over after packing
@@ -143,8 +146,11 @@ int launch_wgrad_c1(const void *Px, const void *Pdz, float *dw, float *db, const
 bool wgrad_mfma_supported(const Geo &g, int cin, int cout, sp_dtype_t dt);
 size_t wgrad_mfma_ws_bytes(const Geo &g, int cin, int cout);
 // Px2 (optional): the input channels [ca, cin) live in a second tensor of cin - ca channels per voxel
+// gather: margin voxels of x that have a neighbour tile are read from that tile's interior (SP_HALO_GATHER)
+bool wgrad_mfma_gather_supported(const Geo &g, int cin, int cout, sp_dtype_t dt);
 int launch_wgrad_mfma(const void *Px, const void *Pdz, float *dw, float *db, const Geo &g,
-                      int cin, int cout, void *ws, hipStream_t s, const void *Px2 = nullptr, int ca = 0);
+                      int cin, int cout, void *ws, hipStream_t s, const void *Px2 = nullptr, int ca = 0,
+                      bool gather = false);
 
 // few input channels (not a multiple of 32) on the matrix cores through zero-padded copies (chan_pad.hip)
 bool chan_pad_supported(const Geo &g, int cin, int cout, sp_dtype_t dt);
@@ -164,6 +170,7 @@ struct FastDiv {
 };
 inline FastDiv make_fastdiv(uint32_t d) {
     FastDiv f{d, 0, 0, 0};
+    if (d == 0) return f;                                      // (no divisor: callers never divide by it)
     uint32_t L = 31;
     while (!((d >> L) & 1)) --L;                               // floor(log2 d), d >= 1
     if ((d & (d - 1)) == 0) { f.shift = L; return f; }         // power of two: plain shift

@@ -85,7 +85,37 @@ struct ConvArgs {
     int nblocks;            // real workgroups (grid is rounded up to a multiple of 8)
     int fold, fold_w;       // 2-D variant, tiles narrower than half a patch: `fold` consecutive slices lie side by
                             // side in a patch, each in a strip of fold_w = box width + 2 columns (fold = 1: none)
+    int gather;             // 1: margin voxels that have a neighbour tile are staged from that tile's interior
 };
+
+// Gathered halos (SP_HALO_GATHER).  The voxel that the exchange would copy into a tile's margin lies, in the
+// neighbour tile, exactly one tile extent further along the axis: margin row 0 of tile (a, b, c) is interior row
+// th of tile (a, b - 1, c).  A staging load that falls into a margin therefore only needs a constant added to its
+// source offset - tile stride of the neighbour minus the tile extent along the axis - and the exchange is not
+// needed at all.  Along H and W the constant is per lane and fixed for the whole march (it goes into goff);
+// along D it applies to the first and the last staged plane of a march that starts / ends at the tile's own
+// first / last plane (dlo, dhi: wave-uniform).  The offsets of several axes add up (edges, corners).  Margins
+// at the volume border are still read from the tensor itself, where they hold the zero padding.
+struct GatherShift {
+    int hm, hp, wm, wp;         // element offsets for margin row 0 / th + 1 and margin column 0 / tw + 1 (0: no neighbour)
+    ptrdiff_t dm, dp;           // element offsets for margin plane 0 / td + 1
+};
+__device__ __forceinline__ GatherShift gather_shift(const Geo &g, int tile, int cs) {
+    GatherShift s;
+    const int tc = tile % g.gw, t1 = tile / g.gw;
+    const int tb = t1 % g.gh, ta = (t1 / g.gh) % g.gd;
+    const ptrdiff_t tv = static_cast<ptrdiff_t>(g.tile_vox);
+    const ptrdiff_t w = (tv - g.tw) * cs;                                              // to tile c + 1
+    const ptrdiff_t h = (tv * g.gw - static_cast<ptrdiff_t>(g.th) * g.pw) * cs;         // to tile b + 1
+    const ptrdiff_t d = (tv * g.gw * g.gh - static_cast<ptrdiff_t>(g.td) * g.ph * g.pw) * cs;   // to tile a + 1
+    s.wm = tc > 0 ? static_cast<int>(-w) : 0;
+    s.wp = tc < g.gw - 1 ? static_cast<int>(w) : 0;
+    s.hm = tb > 0 ? static_cast<int>(-h) : 0;
+    s.hp = tb < g.gh - 1 ? static_cast<int>(h) : 0;
+    s.dm = ta > 0 ? -d : 0;
+    s.dp = ta < g.gd - 1 ? d : 0;
+    return s;
+}
 
 // Slices side by side (2-D variant).  A tile of 8 x 8 voxels fills a quarter of the 32 columns that the MFMAs of a
 // patch compute.  Slices do not interact, so `fold` of them share a patch: strip s of the staged plane holds
@@ -229,6 +259,7 @@ struct Ctx {
     size_t plane_elems;         // input elements per padded plane of the tile
     int nplanes;                // input planes of the chunk (output planes + 2)
     int plo, phi;               // staged planes are clamped to [plo, phi] (slices side by side: the outer two are not real)
+    ptrdiff_t dlo, dhi;         // gathered halos: what to add for staged plane 0 / the last one (else 0)
     int goff[LOADS];            // per-lane source offsets of the staging loads (elements)
     char *lds_stage;            // LDS chunk plane this wave fills (ring slot 0)
     uint16_t *obase;            // output address of (plane 0, first row of the wave, this lane)
@@ -244,7 +275,9 @@ struct Ctx {
 // one needed are clamped (their ring slot is never read), so every step issues exactly LOADS loads.
 template <bool HAS_BIAS>
 __device__ __forceinline__ void stage(const Ctx<HAS_BIAS> &c, int dplane, int j, int lane) {
-    const uint16_t *p = c.tin0 + static_cast<ptrdiff_t>(min(max(dplane, c.plo), c.phi)) * static_cast<ptrdiff_t>(c.plane_elems);
+    const int dpl = min(max(dplane, c.plo), c.phi);
+    const uint16_t *p = c.tin0 + static_cast<ptrdiff_t>(dpl) * static_cast<ptrdiff_t>(c.plane_elems) +
+                        (dpl == 0 ? c.dlo : 0) + (dpl == c.nplanes - 1 ? c.dhi : 0);
     char *dst = c.lds_stage + (dplane % NBUF) * PLANE_BYTES + j * 1024;
     if (64 * j + lane < PLANE_VOX)
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p + c.goff[j]),
@@ -440,6 +473,19 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
         const int row = min(h0 + v / LCOLS, bx.bh + 1), colv = min(w0 + fc.c, bx.bw + 1);
         c.goff[j] = ((min(fc.s, F - 1) * g.ph + row) * g.pw + colv) * a.in_cs + wave * 8;
     }
+    c.dlo = c.dhi = 0;
+    if (a.gather) {          // (host: one-voxel margins, no grown box, 3-D)
+        const GatherShift gs = gather_shift(g, tile, a.in_cs);
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) {
+            const int v = 64 * j + lane;
+            const int row = min(h0 + v / LCOLS, bx.bh + 1), colv = min(w0 + v % LCOLS, bx.bw + 1);
+            c.goff[j] += (row == 0 ? gs.hm : 0) + (row == g.th + 1 ? gs.hp : 0) + (colv == 0 ? gs.wm : 0) +
+                         (colv == g.tw + 1 ? gs.wp : 0);
+        }
+        if (d0 == 0) c.dlo = gs.dm;
+        if (d0 + dn == g.td) c.dhi = gs.dp;
+    }
     c.lds_stage = lds + wave * CH_STRIDE;
     const OutDst od = out_dest(a, cj);
     const FoldCol oc = fold_col(col, F, a.fold_w);
@@ -607,6 +653,7 @@ struct Ctx {
     size_t plane_elems;
     int nplanes;
     int plo, phi;               // staged planes are clamped to [plo, phi]
+    ptrdiff_t dlo, dhi;         // gathered halos: what to add for staged plane 0 / the last one (else 0)
     int goff[LOADS];            // source offsets of the staging loads (elements)
     bool tail_lane;             // lane has a voxel in the last (partial) load of a chunk plane
     char *lds_stage;            // first chunk plane this wave fills, ring slot 0
@@ -622,7 +669,9 @@ struct Ctx {
 // staging load j (0..7) of plane `dplane`: chunk plane j / 4 of this wave's two, voxels 64 (j % 4) ..
 template <bool HAS_BIAS>
 __device__ __forceinline__ void stage(const Ctx<HAS_BIAS> &c, int dplane, int j) {
-    const uint16_t *p = c.tin0 + static_cast<ptrdiff_t>(min(max(dplane, c.plo), c.phi)) * static_cast<ptrdiff_t>(c.plane_elems);
+    const int dpl = min(max(dplane, c.plo), c.phi);
+    const uint16_t *p = c.tin0 + static_cast<ptrdiff_t>(dpl) * static_cast<ptrdiff_t>(c.plane_elems) +
+                        (dpl == 0 ? c.dlo : 0) + (dpl == c.nplanes - 1 ? c.dhi : 0);
     const char *dst = c.lds_stage + (dplane % NBUF) * PLANE_BYTES + (j / CP_LOADS) * CH_STRIDE + (j % CP_LOADS) * 1024;
     // only the last load of a chunk plane is partial (204 = 3 x 64 + 12 voxels); j is a compile-time constant
     // at every call site, so the other loads carry no predicate
@@ -867,6 +916,19 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int logical, i
         const int row = min(h0 + v / LCOLS, bx.bh + 1), colv = min(w0 + fc.c, bx.bw + 1);
         c.goff[j] = ((min(fc.s, F - 1) * g.ph + row) * g.pw + colv) * src_cs + (2 * rg + j / CP_LOADS) * 8;   // always addressable
     }
+    c.dlo = c.dhi = 0;
+    if (a.gather) {          // see GatherShift
+        const GatherShift gs = gather_shift(g, tile, src_cs);
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) {
+            const int v = 64 * (j % CP_LOADS) + lane;
+            const int row = min(h0 + v / LCOLS, bx.bh + 1), colv = min(w0 + v % LCOLS, bx.bw + 1);
+            c.goff[j] += (row == 0 ? gs.hm : 0) + (row == g.th + 1 ? gs.hp : 0) + (colv == 0 ? gs.wm : 0) +
+                         (colv == g.tw + 1 ? gs.wp : 0);
+        }
+        if (d0 == 0) c.dlo = gs.dm;
+        if (d0 + dn == g.td) c.dhi = gs.dp;
+    }
     c.tail_lane = 64 * (CP_LOADS - 1) + lane < PLANE_VOX;
     c.lds_stage = lds + ROLE * CHUNK_BYTES + 2 * rg * CH_STRIDE;
     c.red = lds + RING_BYTES + rg * (RH * 4 * 1024) + lane * 16;
@@ -1066,9 +1128,18 @@ size_t conv_mfma_ws_bytes(const Geo &g, int ki, int ko) {
     return n;
 }
 
+bool conv_mfma_gather_supported(const Geo &g, int ki, int ko, sp_dtype_t dt) {
+    // the marching kernels on a one-voxel margin, interiors only; per-lane offsets to the H / W neighbours (and
+    // their sum at an edge) must fit the 32-bit staging offsets
+    if (!conv_mfma_supported(g, ki, ko, dt) || g.halo != 1 || g.grow != 0 || g.flat || conv_gemm_preferred(g, ki, ko))
+        return false;
+    return static_cast<long long>(g.tile_vox) * (g.gw + 1) * (ki > ko ? ki : ko) < 0x7fffffffLL;
+}
+
 int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Pout, const Geo &g,
                      int ki, int ko, bool relu, bool dgrad, void *ws, hipStream_t s, const void *mask,
-                     const ConvSplit *split) {
+                     const ConvSplit *split, bool gather) {
+    if (gather && !conv_mfma_gather_supported(g, ki, ko, SP_BF16)) return SP_EUNSUPPORTED;
     const int nci = ki / C, nco = ko / C;
     const int pack_elems = nci * nco * NFRAG * 64 * 8;
     hipLaunchKernelGGL(pack_weights_kernel, dim3((pack_elems + 255) / 256), dim3(256), 0, s,
@@ -1117,6 +1188,7 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
     a.nd = pl.nd;
     a.fold = pl.fold;
     a.fold_w = pl.fold_w;
+    a.gather = gather ? 1 : 0;
     const long long nb = pl.nblocks;
     if (nb > 0x7ffffff0LL) return SP_EGEOM;
     a.nblocks = static_cast<int>(nb);

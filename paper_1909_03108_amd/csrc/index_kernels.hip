@@ -3,6 +3,8 @@
 // are as wide as the voxel record (C * element size) allows, up to 16 bytes per lane.
 #include "common.h"
 
+#include <algorithm>
+
 namespace sp3d {
 
 namespace {
@@ -145,16 +147,21 @@ int partition_dispatch(const void *vol, void *P, const PartArgs &a, bool inverse
 }
 
 // ---------------------------------------------------------------------------------------------
-// halo pack / unpack.  One block serves a chunk of one region of one tile.
+// halo pack / unpack.  One block serves a chunk of one region of one tile; a block whose region the call leaves
+// alone (SP_HALO_*: the tile has no neighbour in that direction) returns at once.
 constexpr int kHaloChunk = kThreads * kVpt;   // vectors per block
 
 struct HaloArgs {
     Geo g;
     RegionTable t;
-    int blk_prefix[27];   // first block (within a tile) of each region; [26] = blocks per tile
+    int order[26];        // regions in the order their blocks follow each other inside a tile: largest first, so
+                          // that the search below ends after a step or two for nearly every block (the message
+                          // layout is not affected: it is given by the regions' offsets)
+    int blk_prefix[27];   // first block (within a tile) of the region at each position; [26] = blocks per tile
     FastDiv ehw[26], ew[26];   // per region: ext[1]*ext[2] and ext[2]
     FastDiv vpv;          // vectors per voxel
     FastDiv bpt, gw, gh, gd;
+    int skip;             // 1: regions whose direction leads outside the grid are left alone (SP_HALO_*)
 };
 
 // MODE: kPack = tile interiors -> messages; kUnpack = neighbours' messages -> margins (zeros where the
@@ -168,15 +175,16 @@ __global__ __launch_bounds__(kThreads) void halo_kernel(const T *src, T *dst, Ha
     constexpr bool UNPACK = MODE != kPack;
     const Geo &g = a.g;
     const unsigned tile = fdiv(blockIdx.x, a.bpt), rem = fmod_(blockIdx.x, tile, a.bpt);
-    int ri = 0;
-    while (ri < 25 && static_cast<unsigned>(a.blk_prefix[ri + 1]) <= rem) ++ri;   // uniform
+    int pi = 0;
+    while (pi < 25 && static_cast<unsigned>(a.blk_prefix[pi + 1]) <= rem) ++pi;   // uniform
+    const int ri = a.order[pi];
     const Region &r = a.t.r[ri];
-    const unsigned chunk = rem - a.blk_prefix[ri];
+    unsigned chunk = rem - a.blk_prefix[pi];
     const unsigned nvec = static_cast<unsigned>(r.ext[0]) * r.ext[1] * r.ext[2] * a.vpv.d;
     if (chunk * kHaloChunk >= nvec) return;   // uniform; cannot happen with the block counts of halo_dispatch
 
     long long nb_msg = -1;   // UNPACK: voxel offset of the neighbour's message region, -1 = none
-    if (UNPACK) {
+    if (UNPACK || a.skip) {
         const unsigned t1 = fdiv(tile, a.gw), tc = fmod_(tile, t1, a.gw);
         const unsigned t2 = fdiv(t1, a.gh), tb = fmod_(t1, t2, a.gh);
         const unsigned tn = fdiv(t2, a.gd), ta = fmod_(t2, tn, a.gd);
@@ -185,7 +193,16 @@ __global__ __launch_bounds__(kThreads) void halo_kernel(const T *src, T *dst, Ha
         if (na >= 0 && na < g.gd && nb >= 0 && nb < g.gh && nc >= 0 && nc < g.gw) {
             const long long ntile = ((1LL * tn * g.gd + na) * g.gh + nb) * g.gw + nc;
             nb_msg = MODE == kExchange ? ntile : ntile * g.msg_vox + a.t.r[r.opposite].off;
+        } else if (a.skip) {
+            return;          // uniform: nobody receives this region / its margin holds zeros already
         }
+    }
+    // Consecutive blocks run on consecutive XCDs.  In a region of many chunks every XCD gets a contiguous
+    // eighth of the chunks instead of every eighth chunk (as in xcd_contiguous_block(), but per tile and region:
+    // over the whole grid the XCDs would get unequal shares of the zero-fill work).  A bijection of the chunks.
+    {
+        const unsigned nch = a.blk_prefix[pi + 1] - a.blk_prefix[pi];
+        if (nch >= 64 && (nch & 7u) == 0) chunk = (chunk & 7u) * (nch >> 3) + (chunk >> 3);
     }
     const int *org = UNPACK ? r.recv : r.send;
     const int *nsend = a.t.r[r.opposite].send;     // kExchange: the box the neighbour would have packed
@@ -193,21 +210,41 @@ __global__ __launch_bounds__(kThreads) void halo_kernel(const T *src, T *dst, Ha
     T v[kVpt];
     long long mo[kVpt], po[kVpt];   // vector offsets in the message and in the padded tensor
     bool ok[kVpt];
-#pragma unroll
-    for (int k = 0; k < kVpt; ++k) {
-        const unsigned j = chunk * kHaloChunk + k * kThreads + threadIdx.x;
-        ok[k] = j < nvec;
-        const unsigned jj = ok[k] ? j : 0;
-        const unsigned vox = fdiv(jj, a.vpv), cv = fmod_(jj, vox, a.vpv);
+    // vector j of the region -> its offsets in the padded tensor and in the message (or, kExchange, in the
+    // neighbour's interior)
+    auto locate = [&](unsigned j, long long *pout, long long *mout) {
+        const unsigned vox = fdiv(j, a.vpv), cv = fmod_(j, vox, a.vpv);
         const unsigned ld = fdiv(vox, a.ehw[ri]), q = fmod_(vox, ld, a.ehw[ri]);
         const unsigned lh = fdiv(q, a.ew[ri]), lw = fmod_(q, lh, a.ew[ri]);
         const long long pvox = tile * g.tile_vox + (1LL * (org[0] + ld) * g.ph + org[1] + lh) * g.pw + org[2] + lw;
-        po[k] = pvox * a.vpv.d + cv;
+        *pout = pvox * a.vpv.d + cv;
         if (MODE == kExchange)
-            mo[k] = (nb_msg * g.tile_vox + (1LL * (nsend[0] + ld) * g.ph + nsend[1] + lh) * g.pw + nsend[2] + lw) *
+            *mout = (nb_msg * g.tile_vox + (1LL * (nsend[0] + ld) * g.ph + nsend[1] + lh) * g.pw + nsend[2] + lw) *
                         a.vpv.d + cv;
         else
-            mo[k] = (msg0 + vox) * a.vpv.d + cv;
+            *mout = (msg0 + vox) * a.vpv.d + cv;
+    };
+    if ((static_cast<unsigned>(r.ext[2]) * a.vpv.d) % kHaloChunk == 0) {
+        // rows that are whole multiples of a block's vectors (the D and H faces of large tiles): the block lies
+        // inside one row, so its first vector is located once, on the scalar unit, and a lane only adds its index
+        long long p0, m0;
+        locate(chunk * kHaloChunk, &p0, &m0);
+#pragma unroll
+        for (int k = 0; k < kVpt; ++k) {
+            ok[k] = true;
+            po[k] = p0 + k * kThreads + threadIdx.x;
+            mo[k] = m0 + k * kThreads + threadIdx.x;
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < kVpt; ++k) {
+            const unsigned j = chunk * kHaloChunk + k * kThreads + threadIdx.x;
+            ok[k] = j < nvec;
+            locate(ok[k] ? j : 0, &po[k], &mo[k]);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < kVpt; ++k) {
         v[k] = zero_vec<T>();
         if (ok[k] && (!UNPACK || nb_msg >= 0)) v[k] = ld_stream(src + (UNPACK ? mo[k] : po[k]));
     }
@@ -219,18 +256,29 @@ __global__ __launch_bounds__(kThreads) void halo_kernel(const T *src, T *dst, Ha
 template <int VB>
 int halo_dispatch(const void *src, void *dst, HaloArgs &a, int mode, hipStream_t s) {
     using T = typename VecT<VB>::type;
-    int acc = 0;
+    int nblk[26];
     for (int i = 0; i < 26; ++i) {
-        a.blk_prefix[i] = acc;
         const long long nvec = 1LL * a.t.r[i].ext[0] * a.t.r[i].ext[1] * a.t.r[i].ext[2] * a.vpv.d;
         if (nvec > 0xffffff00LL) return SP_EGEOM;
         a.ehw[i] = make_fastdiv(static_cast<uint32_t>(a.t.r[i].ext[1]) * a.t.r[i].ext[2]);
         a.ew[i] = make_fastdiv(a.t.r[i].ext[2]);
         // 2-D variant: slices do not interact, the regions above and below a tile are not moved
-        if (a.g.flat && a.t.r[i].delta[0] != 0) continue;
-        acc += static_cast<int>((nvec + kHaloChunk - 1) / kHaloChunk);
+        nblk[i] = (a.g.flat && a.t.r[i].delta[0] != 0) ? 0 : static_cast<int>((nvec + kHaloChunk - 1) / kHaloChunk);
+        // a direction along an axis that the grid does not split leads outside the grid for every tile: with
+        // SP_HALO_* such a region gets no blocks at all (instead of blocks that find that out and return)
+        const int gdim[3] = {a.g.gd, a.g.gh, a.g.gw};
+        for (int k = 0; k < 3; ++k)
+            if (a.skip && a.t.r[i].delta[k] != 0 && gdim[k] == 1) nblk[i] = 0;
+        a.order[i] = i;
+    }
+    std::stable_sort(a.order, a.order + 26, [&](int x, int y) { return nblk[x] > nblk[y]; });
+    int acc = 0;
+    for (int p = 0; p < 26; ++p) {
+        a.blk_prefix[p] = acc;
+        acc += nblk[a.order[p]];
     }
     a.blk_prefix[26] = acc;
+    if (acc == 0) return SP_OK;       // one tile and nothing to do beyond the volume border: no launch
     a.bpt = make_fastdiv(acc);
     a.gw = make_fastdiv(a.g.gw);
     a.gh = make_fastdiv(a.g.gh);
@@ -254,24 +302,22 @@ int halo_dispatch(const void *src, void *dst, HaloArgs &a, int mode, hipStream_t
 // ReLU backward mask: dz = dy where y > 0 else 0.
 template <typename E> __device__ __forceinline__ bool positive(E v);
 template <> __device__ __forceinline__ bool positive<float>(float v) { return v > 0.f; }
-// bf16 bits: positive and non-zero (NaN counts as not positive only if its sign bit is set)
+// bf16 bits: positive, non-zero and not NaN (a NaN of either sign is not positive)
 template <> __device__ __forceinline__ bool positive<uint16_t>(uint16_t v) {
     return (v & 0x8000u) == 0 && (v & 0x7fffu) != 0 && (v & 0x7fffu) <= 0x7f80u;
 }
 
+// (dz may be the same tensor as dy, so no __restrict__ on those two: every thread reads and writes its own index)
 template <typename E>
-__global__ __launch_bounds__(kThreads) void relu_bwd_kernel(const E *__restrict__ dy,
-                                                            const E *__restrict__ y,
-                                                            E *__restrict__ dz, size_t n) {
+__global__ __launch_bounds__(kThreads) void relu_bwd_kernel(const E *dy, const E *__restrict__ y, E *dz, size_t n) {
     const size_t stride = static_cast<size_t>(gridDim.x) * kThreads;
     for (size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x; i < n; i += stride)
         dz[i] = positive<E>(y[i]) ? dy[i] : E(0);
 }
 
 // 16-byte variant for bf16 (8 elements per thread): mask built from the sign/zero test of each half word
-__global__ __launch_bounds__(kThreads) void relu_bwd_bf16x8_kernel(const u32x4 *__restrict__ dy,
-                                                                   const u32x4 *__restrict__ y,
-                                                                   u32x4 *__restrict__ dz, size_t nvec) {
+__global__ __launch_bounds__(kThreads) void relu_bwd_bf16x8_kernel(const u32x4 *dy, const u32x4 *__restrict__ y,
+                                                                   u32x4 *dz, size_t nvec) {
     const size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
     if (i >= nvec) return;
     const u32x4 g = dy[i], v = y[i];
@@ -322,12 +368,13 @@ int launch_partition(const void *vol, void *P, const Geo &g, int c, sp_dtype_t d
     }
 }
 
-static int halo_launch(const void *src, void *dst, const Geo &g, int c, sp_dtype_t dt, int mode,
+static int halo_launch(const void *src, void *dst, const Geo &g, int c, sp_dtype_t dt, int mode, int border,
                        hipStream_t s) {
     const size_t rec = static_cast<size_t>(c) * elem_size(dt);
     const int vb = vec_bytes(rec);
     HaloArgs a;
     a.g = g;
+    a.skip = (border & (mode == kPack ? SP_HALO_SKIP_SEND : SP_HALO_KEEP_ZERO)) ? 1 : 0;
     make_regions(g, &a.t);
     a.vpv = make_fastdiv(static_cast<uint32_t>(rec / vb));
     switch (vb) {
@@ -338,16 +385,16 @@ static int halo_launch(const void *src, void *dst, const Geo &g, int c, sp_dtype
     }
 }
 
-int launch_halo_pack(const void *P, void *msg, const Geo &g, int c, sp_dtype_t dt, hipStream_t s) {
-    return halo_launch(P, msg, g, c, dt, kPack, s);
+int launch_halo_pack(const void *P, void *msg, const Geo &g, int c, sp_dtype_t dt, int border, hipStream_t s) {
+    return halo_launch(P, msg, g, c, dt, kPack, border, s);
 }
 
-int launch_halo_unpack(void *P, const void *msg, const Geo &g, int c, sp_dtype_t dt, hipStream_t s) {
-    return halo_launch(msg, P, g, c, dt, kUnpack, s);
+int launch_halo_unpack(void *P, const void *msg, const Geo &g, int c, sp_dtype_t dt, int border, hipStream_t s) {
+    return halo_launch(msg, P, g, c, dt, kUnpack, border, s);
 }
 
-int launch_halo_exchange(void *P, const Geo &g, int c, sp_dtype_t dt, hipStream_t s) {
-    return halo_launch(P, P, g, c, dt, kExchange, s);
+int launch_halo_exchange(void *P, const Geo &g, int c, sp_dtype_t dt, int border, hipStream_t s) {
+    return halo_launch(P, P, g, c, dt, kExchange, border, s);
 }
 
 int launch_relu_bwd(const void *dy, const void *y, void *dz, size_t elems, sp_dtype_t dt,

@@ -65,6 +65,8 @@ struct WgradArgs {
     int ngroups;          // real workgroups = pairs * gpp; grid is rounded up to a multiple of 8
     int fold, fold_w;     // 2-D variant, tiles narrower than half a patch: `fold` consecutive slices lie side by
                           // side in a staged plane, each in a strip of fold_w = tile width + 2 columns (1: none)
+    int gather;           // 1 (direct-to-LDS kernel, 3-D): x margin voxels that have a neighbour tile are staged
+                          // from that tile's interior, one tile extent further along the axis (SP_HALO_GATHER)
 };
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -517,13 +519,43 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_dma_kernel(WgradArgs a) {
         const uint16_t *tz = a.dz + (static_cast<size_t>(tile) * g.tile_vox + static_cast<size_t>(d0 + 1) * g.ph * g.pw +
                                      h0 * g.pw + w0) * a.dz_cs + dz_co;
 
+        // Gathered halos: a margin voxel of x that the exchange would have filled is, in the neighbour tile, the
+        // interior voxel one tile extent further along the axis.  Along H and W that is a per-lane constant for
+        // this item's patch (gxa), along D a uniform one for the item's first / last x plane (dlo, dhi).  Margins
+        // at the volume border are read from the tensor itself (zero padding).
+        int gxa[DMA_X];
+        ptrdiff_t dlo = 0, dhi = 0;
+#pragma unroll
+        for (int j = 0; j < DMA_X; ++j) gxa[j] = gx[j];
+        if (a.gather) {
+            const int tc = tile % g.gw, t1 = tile / g.gw;
+            const int tb = t1 % g.gh, ta = (t1 / g.gh) % g.gd;
+            const ptrdiff_t tv = static_cast<ptrdiff_t>(g.tile_vox);
+            const ptrdiff_t sw = (tv - g.tw) * xs.cs;
+            const ptrdiff_t sh = (tv * g.gw - static_cast<ptrdiff_t>(g.th) * g.pw) * xs.cs;
+            const ptrdiff_t sd = (tv * g.gw * g.gh - static_cast<ptrdiff_t>(g.td) * g.ph * g.pw) * xs.cs;
+#pragma unroll
+            for (int j = 0; j < DMA_X; ++j) {
+                const int u = j < 2 ? 2 * wave + j : (wave < 6 ? 16 + wave : 2 * wave + 1);
+                const int v = min((u % XG) * 32 + (lane >> 1), XVOX - 1);
+                const int row = h0 + v / XC, col = w0 + v % XC;
+                gxa[j] += (row == 0 && tb > 0 ? static_cast<int>(-sh) : 0) +
+                          (row == g.th + 1 && tb < g.gh - 1 ? static_cast<int>(sh) : 0) +
+                          (col == 0 && tc > 0 ? static_cast<int>(-sw) : 0) +
+                          (col == g.tw + 1 && tc < g.gw - 1 ? static_cast<int>(sw) : 0);
+            }
+            if (d0 == 0 && ta > 0) dlo = -sd;
+            if (d0 + dn == g.td && ta < g.gd - 1) dhi = sd;
+        }
+
         // Stage planes D of x and dz into ring slots sx, sz.  Planes past the last one are clamped to it:
         // their slots are either never read or masked, and every call issues exactly DMA_PER_WAVE loads.
 #define SP3D_STAGE(D, sx, sz)                                                                      \
     do {                                                                                           \
-        const uint16_t *px = tx + min((D), dn + 1) * xplane;                                       \
+        const int dx_ = min((D), dn + 1);                                                          \
+        const uint16_t *px = tx + dx_ * xplane + (dx_ == 0 ? dlo : 0) + (dx_ == dn + 1 ? dhi : 0); \
         const uint16_t *pz = tz + min((D), dn - 1) * zplane;                                       \
-        _Pragma("unroll") for (int j = 0; j < DMA_X; ++j) dma16(px + gx[j], lds + lx[j] + (sx) * XD_BYTES); \
+        _Pragma("unroll") for (int j = 0; j < DMA_X; ++j) dma16(px + gxa[j], lds + lx[j] + (sx) * XD_BYTES); \
         _Pragma("unroll") for (int j = 0; j < DMA_Z; ++j) dma16(pz + gz[j], lds + lz[j] + (sz) * Z_PLANE);  \
     } while (0)
 
@@ -681,10 +713,19 @@ size_t wgrad_mfma_ws_bytes(const Geo &g, int cin, int cout) {
     return static_cast<size_t>(a.ngroups) * (taps_of(g) * C * C + C) * sizeof(float);
 }
 
+bool wgrad_mfma_gather_supported(const Geo &g, int cin, int cout, sp_dtype_t dt) {
+    // the direct-to-LDS kernel (whole patches), one-voxel margins, 3-D; per-lane offsets to the H / W neighbours
+    // (and their sum at an edge) must fit the 32-bit staging offsets
+    return wgrad_mfma_supported(g, cin, cout, dt) && g.halo == 1 && !g.flat && g.th % PH == 0 && g.tw % PW == 0 &&
+           static_cast<long long>(g.tile_vox) * (g.gw + 1) * cin < 0x7fffffffLL;
+}
+
 int launch_wgrad_mfma(const void *Px, const void *Pdz, float *dw, float *db, const Geo &g, int cin, int cout,
-                      void *ws, hipStream_t s, const void *Px2, int ca) {
+                      void *ws, hipStream_t s, const void *Px2, int ca, bool gather) {
+    if (gather && !wgrad_mfma_gather_supported(g, cin, cout, SP_BF16)) return SP_EUNSUPPORTED;
     WgradArgs a;
     plan(g, cin, cout, &a);
+    a.gather = gather ? 1 : 0;
     a.x = static_cast<const uint16_t *>(Px);
     a.x2 = static_cast<const uint16_t *>(Px2);
     if (Px2) { a.x_cs = ca; a.x_ca = ca; a.x2_cs = cin - ca; }

@@ -9,12 +9,13 @@ import os
 SP_F32, SP_BF16 = 0, 1
 SP_OK, SP_EINVAL, SP_EGEOM, SP_EUNSUPPORTED, SP_EWORKSPACE, SP_ELAUNCH = 0, -1, -2, -3, -4, -5
 SP_FLAG_RELU = 1
+SP_HALO_SKIP_SEND, SP_HALO_KEEP_ZERO, SP_HALO_GATHER = 1, 2, 4
 SP_STATIC_SCRATCH_BYTES = 32 << 20
 SP_OP_FWD, SP_OP_DGRAD, SP_OP_WGRAD, SP_OP_UPCONV_WGRAD, SP_OP_POINTWISE_WGRAD, SP_OP_LOSS = 0, 1, 2, 3, 4, 5
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsp3d.so")
 
-EXPORTS = ["sp_padded_elems", "sp_msg_elems", "sp_workspace_bytes", "sp_check_geom", "sp_strerror",
+EXPORTS = ["sp_padded_elems", "sp_msg_elems", "sp_workspace_bytes", "sp_check_geom", "sp_gather_supported", "sp_strerror",
            "sp_last_hip_error", "sp_partition", "sp_unpartition", "halo_pack", "halo_unpack",
            "sp_halo_exchange",
            "conv3d_fwd", "conv3d_dgrad", "conv3d_dgrad_relu", "conv3d_wgrad", "conv3d_wgrad_static", "conv3d_fwd2", "conv3d_dgrad2",
@@ -28,14 +29,20 @@ class Geom(ctypes.Structure):
     """sp_geom_t: volume extents, tile grid (D,H,W order), margin width of the layout, and by how much the
     convolutions grow their output box beyond the interior (0 unless several layers share one exchange).
     flat = 1 selects the 2-D variant: D is a stack of independent slices (3x3 kernels, 1x2x2 windows)."""
-    _fields_ = [(k, ctypes.c_int32) for k in ("n", "d", "h", "w", "gd", "gh", "gw", "halo", "grow", "flat")]
+    _fields_ = [(k, ctypes.c_int32) for k in ("n", "d", "h", "w", "gd", "gh", "gw", "halo", "grow", "flat", "opts")]
 
-    def __init__(self, n, dhw, grid, halo=1, grow=0, flat=0):
-        super().__init__(n, dhw[0], dhw[1], dhw[2], grid[0], grid[1], grid[2], halo, grow, int(flat))
+    def __init__(self, n, dhw, grid, halo=1, grow=0, flat=0, opts=0):
+        super().__init__(n, dhw[0], dhw[1], dhw[2], grid[0], grid[1], grid[2], halo, grow, int(flat), opts)
 
     def grown(self, grow):
         """The same geometry with another `grow`."""
-        return Geom(self.n, (self.d, self.h, self.w), (self.gd, self.gh, self.gw), self.halo, grow, self.flat)
+        return Geom(self.n, (self.d, self.h, self.w), (self.gd, self.gh, self.gw), self.halo, grow, self.flat,
+                    self.opts)
+
+    def with_opts(self, opts):
+        """The same geometry with other SP_HALO_* flags."""
+        return Geom(self.n, (self.d, self.h, self.w), (self.gd, self.gh, self.gw), self.halo, self.grow, self.flat,
+                    opts)
 
     @property
     def tile(self):
@@ -71,6 +78,7 @@ def lib():
         L.sp_msg_elems.argtypes, L.sp_msg_elems.restype = [G, I], Z
         L.sp_workspace_bytes.argtypes, L.sp_workspace_bytes.restype = [I, G, I, I, I], Z
         L.sp_check_geom.argtypes, L.sp_check_geom.restype = [G], I
+        L.sp_gather_supported.argtypes, L.sp_gather_supported.restype = [I, G, I, I, I], I
         L.sp_strerror.argtypes, L.sp_strerror.restype = [I], ctypes.c_char_p
         L.sp_last_hip_error.argtypes, L.sp_last_hip_error.restype = [], I
         for name in ("sp_partition", "sp_unpartition", "halo_pack", "halo_unpack"):
@@ -137,6 +145,10 @@ def sp_padded_elems(g, c):
 
 def sp_msg_elems(g, c):
     return lib().sp_msg_elems(ctypes.byref(g), c)
+
+
+def sp_gather_supported(op, g, cin, cout, dt):
+    return bool(lib().sp_gather_supported(op, ctypes.byref(g), cin, cout, dt))
 
 
 def sp_workspace_bytes(op, g, cin, cout, dt):

@@ -50,7 +50,7 @@ def layer_plan(channels=(32, 64, 128, 256), in_ch=1, classes=3, convs=2, flat=Fa
 
 class UNet:
     def __init__(self, n, dhw, grid, weights, channels=(32, 64, 128, 256), in_ch=1, classes=3,
-                 dt=sp3d.SP_BF16, convs=2, halo=1, flat=False):
+                 dt=sp3d.SP_BF16, convs=2, halo=1, flat=False, gather=False):
         self.channels, self.in_ch, self.classes, self.dt = tuple(channels), in_ch, classes, dt
         self.convs = convs
         # Runs of more than two layers would need ReLU masks further around the tiles in the backward pass than
@@ -58,6 +58,9 @@ class UNet:
         # leaves it run length - j voxels out).
         assert 1 <= halo <= 2
         self.halo = halo
+        # gather: layers whose kernels can do it read their margins from the neighbour tiles' interiors
+        # (SP_HALO_GATHER) instead of having them exchanged first; the others exchange as before
+        self.gather = bool(gather) and halo == 1
         self.free = {}                        # (padded shape, channels) -> released gradient buffers
         self.L = len(channels)
         self.flat = bool(flat)
@@ -117,15 +120,26 @@ class UNet:
                 plan[k0 + j] = (j == 0, s - 1 - j, j, s)
         return plan
 
+    def _gathers(self, op, g, cin, cout):
+        return self.gather and sp3d.sp_gather_supported(op, g, cin, cout, self.dt)
+
+    def _x_gathered(self, g, cin, cout):
+        """a layer's saved input stays without halos only if both kernels that read them can gather"""
+        return self._gathers(sp3d.SP_OP_FWD, g, cin, cout) and self._gathers(sp3d.SP_OP_WGRAD, g, cin, cout)
+
     def _exchange(self, P, g, c):
-        """All tiles share this GPU's memory, so margins are filled straight from the neighbours' interiors."""
-        sp3d.sp_halo_exchange(P, g, c, self.dt)
+        """All tiles share this GPU's memory, so margins are filled straight from the neighbours' interiors.
+        Margins at the volume border are left alone: every padded tensor of the driver is zeroed when it is
+        allocated and nothing writes beyond the border afterwards, so they hold their zero padding already."""
+        sp3d.sp_halo_exchange(P, g.with_opts(sp3d.SP_HALO_KEEP_ZERO), c, self.dt)
 
     def _conv(self, Px, name, g, cin, cout, grow=0):
         """Px must hold its halos.  Returns relu(conv(Px)) as padded tiles (written: the interiors and `grow`
         voxels around them)."""
         Py = self._buf(name + ".y", g, cout)
         gg = g.grown(grow) if grow else g
+        if self._x_gathered(g, cin, cout):
+            gg = g.with_opts(sp3d.SP_HALO_GATHER)
         sp3d.conv3d_fwd(Px, self.w[name], None, Py, gg, cin, cout, self.dt, sp3d.SP_FLAG_RELU,
                         self._ws(sp3d.SP_OP_FWD, gg, cin, cout))
         return Py
@@ -139,16 +153,19 @@ class UNet:
             exch, grow = plan[k][0], plan[k][1]
             if k == 0 and P2 is not None:
                 ca = cin // 2
-                self._exchange(P, g, ca)
-                self._exchange(P2, g, ca)
+                gg = g.grown(grow) if grow else g
+                if self._x_gathered(g, cin, c):
+                    gg = g.with_opts(sp3d.SP_HALO_GATHER)
+                else:
+                    self._exchange(P, g, ca)
+                    self._exchange(P2, g, ca)
                 A[name + ".x"] = (P, P2)
                 Py = self._buf(name + ".y", g, c)
-                gg = g.grown(grow) if grow else g
                 sp3d.conv3d_fwd2(P, ca, P2, ca, self.w[name], None, Py, gg, c, self.dt, sp3d.SP_FLAG_RELU,
                                  self._ws(sp3d.SP_OP_FWD, gg, cin, c))
                 P = Py
                 continue
-            if exch:
+            if exch and not self._x_gathered(g, cin if k == 0 else c, c):
                 self._exchange(P, g, cin if k == 0 else c)
             A[name + ".x"] = P
             P = self._conv(P, name, g, cin if k == 0 else c, c, grow)
@@ -233,24 +250,31 @@ class UNet:
         dw = torch.empty(tuple(self.w[name].shape), dtype=torch.float32, device="cuda")
         if isinstance(Px, tuple):                 # x = concat(Px[0], Px[1]): gradients go to two tensors
             ca = cin // 2
-            sp3d.conv3d_wgrad2(Px[0], ca, Px[1], ca, Pdy, dw, None, g, cout, dt,
+            gx = g.with_opts(sp3d.SP_HALO_GATHER) if self._x_gathered(g, cin, cout) else g
+            sp3d.conv3d_wgrad2(Px[0], ca, Px[1], ca, Pdy, dw, None, gx, cout, dt,
                                self._ws(sp3d.SP_OP_WGRAD, g, cin, cout))
             grads[name] = dw
-            if exchange:
+            gz = g
+            if self._gathers(sp3d.SP_OP_DGRAD, g, cin, cout):
+                gz = g.with_opts(sp3d.SP_HALO_GATHER)
+            elif exchange:
                 self._exchange(Pdy, g, cout)
             Pa, Pb = self._tmp(g, ca), self._tmp(g, ca)
-            sp3d.conv3d_dgrad2(Pdy, self.w[name], Pa, ca, Pb, ca, g, cout, dt,
+            sp3d.conv3d_dgrad2(Pdy, self.w[name], Pa, ca, Pb, ca, gz, cout, dt,
                                self._ws(sp3d.SP_OP_DGRAD, g, cin, cout))          # first layer of its run: no grow
             self._release(Pdy, g, cout)
             return (Pa, Pb)
-        sp3d.conv3d_wgrad(Px, Pdy, dw, None, g, cin, cout, dt, self._ws(sp3d.SP_OP_WGRAD, g, cin, cout))
+        gx = g.with_opts(sp3d.SP_HALO_GATHER) if self._x_gathered(g, cin, cout) else g
+        sp3d.conv3d_wgrad(Px, Pdy, dw, None, gx, cin, cout, dt, self._ws(sp3d.SP_OP_WGRAD, g, cin, cout))
         grads[name] = dw
         Pdx = None
         if need_dx:
-            if exchange:
+            gg = g.grown(grow) if grow else g
+            if self._gathers(sp3d.SP_OP_DGRAD, g, cin, cout):
+                gg = g.with_opts(sp3d.SP_HALO_GATHER)
+            elif exchange:
                 self._exchange(Pdy, g, cout)
             Pdx = self._tmp(g, cin)
-            gg = g.grown(grow) if grow else g
             if mask_next:
                 sp3d.conv3d_dgrad_relu(Pdy, self.w[name], Px, Pdx, gg, cin, cout, dt,
                                        self._ws(sp3d.SP_OP_DGRAD, gg, cin, cout))

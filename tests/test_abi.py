@@ -239,3 +239,32 @@ def test_geometry_limits():
     assert sp3d.sp_check_geom(sp3d.Geom(1, (2048, 2048, 2048), (1, 1, 1))) == sp3d.SP_EGEOM
     assert sp3d.sp_check_geom(sp3d.Geom(1, (2048, 2048, 2048), (2, 2, 2))) == sp3d.SP_OK
     assert sp3d.sp_check_geom(sp3d.Geom(1, (7, 8, 8), (7, 1, 1))) == sp3d.SP_OK
+
+
+@pytest.mark.timeout(30)
+def test_halo_options_and_the_one_tile_grid():
+    """sp_geom_t.opts: unknown bits are an argument error; on a grid of one tile every direction leads beyond the
+    volume border, so with SP_HALO_SKIP_SEND / SP_HALO_KEEP_ZERO the halo calls have nothing to do and return
+    without a launch (checked here without a GPU: a launch would fail); SP_HALO_GATHER is refused where no kernel
+    gathers, and sp_gather_supported says so beforehand."""
+    L = sp3d.lib()
+    one = sp3d.Geom(1, (5, 7, 9), (1, 1, 1), opts=sp3d.SP_HALO_SKIP_SEND | sp3d.SP_HALO_KEEP_ZERO)
+    for c, dt in ((4, sp3d.SP_BF16), (3, sp3d.SP_F32), (32, sp3d.SP_BF16)):
+        assert L.halo_pack(FAKE, FAKE * 16, ctypes.byref(one), c, dt, None) == sp3d.SP_OK
+        assert L.halo_unpack(FAKE, FAKE * 16, ctypes.byref(one), c, dt, None) == sp3d.SP_OK
+        assert L.sp_halo_exchange(FAKE, ctypes.byref(one), c, dt, None) == sp3d.SP_OK
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (8, 8, 8), (2, 2, 2), opts=8)) == sp3d.SP_EINVAL
+    assert sp3d.sp_check_geom(sp3d.Geom(1, (8, 8, 8), (2, 2, 2), opts=7)) == sp3d.SP_OK
+    bf = sp3d.SP_BF16
+    g = sp3d.Geom(1, (8, 16, 64), (2, 2, 1))
+    assert all(sp3d.sp_gather_supported(op, g, 32, 64, bf) for op in (0, 1, 2))
+    assert sp3d.sp_gather_supported(sp3d.SP_OP_FWD, sp3d.Geom(1, (12, 20, 72), (2, 2, 1)), 32, 32, bf)       # ragged patches
+    assert not sp3d.sp_gather_supported(sp3d.SP_OP_WGRAD, sp3d.Geom(1, (12, 20, 72), (2, 2, 1)), 32, 32, bf)
+    assert not sp3d.sp_gather_supported(sp3d.SP_OP_FWD, g, 1, 32, bf)                 # first layer
+    assert not sp3d.sp_gather_supported(sp3d.SP_OP_FWD, g, 32, 32, sp3d.SP_F32)
+    assert not sp3d.sp_gather_supported(sp3d.SP_OP_FWD, sp3d.Geom(1, (8, 16, 64), (2, 2, 1), halo=2), 32, 32, bf)
+    assert not sp3d.sp_gather_supported(sp3d.SP_OP_FWD, sp3d.Geom(1, (8, 16, 64), (2, 2, 1), flat=1), 32, 32, bf)
+    gg = g.with_opts(sp3d.SP_HALO_GATHER)
+    assert L.conv3d_fwd(FAKE, FAKE * 2, None, FAKE * 16, ctypes.byref(gg), 1, 32, bf, 0, FAKE * 32, 1 << 20, None) == sp3d.SP_EUNSUPPORTED
+    assert L.conv3d_wgrad(FAKE, FAKE * 2, FAKE * 4, None, ctypes.byref(sp3d.Geom(1, (12, 20, 72), (2, 2, 1), opts=4)),
+                          32, 32, bf, FAKE * 32, 1 << 30, None) == sp3d.SP_EUNSUPPORTED

@@ -93,6 +93,57 @@ def test_partition_pack_unpack_unpartition_bit_exact(n, dhw, grid, c, dtype, h):
     assert guards_intact(vbuf, fill)
 
 
+@pytest.mark.parametrize("n,dhw,grid,c,dtype,h", [k + (1,) for k in CASES[:9]] + WIDE[:4])
+def test_border_flags_skip_what_has_no_receiver_and_keep_zero_margins(n, dhw, grid, c, dtype, h):
+    """SP_HALO_SKIP_SEND: halo_pack writes exactly the message entries some tile receives (the oracle's
+    tiling.delivered) and leaves the others untouched.  SP_HALO_KEEP_ZERO: halo_unpack / sp_halo_exchange write
+    exactly the margins that have a neighbour; the margins at the volume border - the positions where the
+    zero-padded reference holds padding - are left as they are, so a zeroed array ends up as the full reference."""
+    g0 = sp3d.Geom(n, dhw, grid, h)
+    g = g0.with_opts(sp3d.SP_HALO_SKIP_SEND | sp3d.SP_HALO_KEEP_ZERO)
+    dt = DT[dtype]
+    tdt = sp3d.torch_dtype(dt)
+    V = make_volume(n, dhw, c, dtype, 12)
+    fill = 7.0
+    fill_bits = bits(torch.tensor([fill], dtype=tdt, device="cuda"))[0]
+    ref_P = tiling.partition(V, grid, h)
+    ref_M = tiling.halo_pack(ref_P, h)
+    ref_full = tiling.padded_reference(V, grid, h)
+    tile = tiling.tile_extents(dhw, grid)
+    deliv = np.broadcast_to(tiling.delivered(grid, tile, h)[None, ..., None], ref_M.shape)
+    # positions of the padded array that lie outside the volume: where the reference of an all-ones volume is zero
+    outside = tiling.padded_reference(np.ones(V.shape, dtype=np.uint8), grid, h) == 0
+
+    pbuf, P = guard_alloc(g.padded_shape + (c,), tdt, fill)
+    sp3d.sp_partition(to_dev(V), P, g, c, dt)
+    mbuf, M = guard_alloc((sp3d.sp_msg_elems(g, c),), tdt, fill)
+    sp3d.halo_pack(P, M, g, c, dt)
+    got_M = bits(M).reshape(ref_M.shape)
+    assert np.array_equal(got_M[deliv], ref_M[deliv])
+    assert np.all(got_M[~deliv] == fill_bits)
+    assert guards_intact(mbuf, fill)
+    for one_pass in (False, True):
+        if one_pass:
+            P.fill_(fill)
+            sp3d.sp_partition(to_dev(V), P, g, c, dt)
+            sp3d.sp_halo_exchange(P, g, c, dt)
+        else:
+            sp3d.halo_unpack(P, M, g, c, dt)
+        got = bits(P)
+        assert np.array_equal(got[~outside], ref_full[~outside])
+        assert np.all(got[outside] == fill_bits)
+        assert guards_intact(pbuf, fill)
+    # on a zeroed array the flagged calls give the complete padded tiles
+    Q = sp3d.alloc_padded(g, c, dt)
+    sp3d.sp_partition(to_dev(V), Q, g, c, dt)
+    sp3d.sp_halo_exchange(Q, g, c, dt)
+    assert np.array_equal(bits(Q), ref_full)
+    # and an unknown flag is an argument error
+    with pytest.raises(sp3d.Sp3dError) as e:
+        sp3d.sp_halo_exchange(Q, g0.with_opts(8), c, dt)
+    assert e.value.code == sp3d.SP_EINVAL
+
+
 def test_relu_bwd_mask_bit_exact():
     g = sp3d.Geom(1, (6, 4, 10), (3, 2, 5))
     for dtype in ("bf16", "f32"):

@@ -277,3 +277,40 @@ def test_unet_two_layers_per_exchange_bit_identical(convs):
         assert torch.equal(g1[k], g2[k]), k
     print("exchanges per two steps: one per layer %d, two layers per exchange %d" % tuple(count))
     assert count[1] < count[0]
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("convs,grid", [(2, (2, 2, 1)), (4, (2, 2, 2))])
+def test_unet_gathered_halos_bit_identical(convs, grid):
+    """The exchange fused into the convolutions (SP_HALO_GATHER: margins read from the neighbour tiles' interiors):
+    logits, image gradient and every weight gradient of a whole forward + backward are bit for bit those of the
+    exchange-then-convolve path, whose parity with the oracle the tests above establish; the layers whose kernels
+    gather run without any exchange."""
+    channels, in_ch, classes = (32, 64, 128), 1, 3
+    n, dhw = 1, (16, 32, 128)              # tiles 8 x 16 x 64|128 ... 2 x 4 x 16|32: whole patches at the top level only
+    plan = PU.layer_plan(channels, in_ch, classes, convs)
+    x = to_dev(synth.ct_like_volume((n,) + dhw + (in_ch,), synth.seed_for(9, synth.T_INPUT), "bf16"))
+    w_d = {name: to_dev(synth.weights(shape[3], shape[4], synth.seed_for(9, synth.T_WEIGHT0 + k), "bf16",
+                                      taps=shape[:3])) for k, (name, shape) in enumerate(plan)}
+    dl = to_dev(synth.normal_volume((n,) + dhw + (classes,), synth.seed_for(9, synth.T_UPSTREAM), "bf16"))
+    res, count = [], []
+    for gather in (False, True):
+        net = PU.UNet(n, dhw, grid, w_d, channels, in_ch, classes, convs=convs, gather=gather)
+        calls = [0]
+        inner = net._exchange
+
+        def counted(P, g, c, inner=inner, calls=calls):
+            calls[0] += 1
+            inner(P, g, c)
+        net._exchange = counted
+        for _ in range(2):                       # the second step runs on recycled buffers
+            logits = net.forward(x)
+            grads, dx = net.backward(dl)
+        res.append((logits, grads, dx))
+        count.append(calls[0])
+    (l1, g1, d1), (l2, g2, d2) = res
+    assert torch.equal(l1, l2) and torch.equal(d1, d2)
+    for k, _ in plan:
+        assert torch.equal(g1[k], g2[k]), k
+    print("exchanges per two steps: %d, with gathered halos %d" % tuple(count))
+    assert count[1] < count[0]

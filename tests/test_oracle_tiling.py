@@ -177,3 +177,21 @@ def test_wider_margins_reproduce_wider_windows(rng, dhw, grid, h):
     assert np.array_equal(tiling.exchange(P, h), tiling.padded_reference(V, grid, h))
     tile = tiling.tile_extents(dhw, grid)
     assert sum(tiling.region_sizes(tile, h)) == tiling.margin_voxels(tile, h) == tiling.halo_pack(P, h).shape[4]
+
+
+@pytest.mark.parametrize("dhw,grid,h", [((4, 6, 8), (2, 3, 2), 1), ((6, 4, 4), (3, 1, 2), 2), ((3, 3, 3), (1, 1, 1), 1)])
+def test_delivered_mask_is_exactly_what_unpack_reads(dhw, grid, h):
+    """tiling.delivered() against the receiving side itself: garbage in the entries it calls undelivered does not
+    change any padded tile, and every entry it calls delivered does reach some margin (a unique tag planted in the
+    message shows up after unpack)."""
+    rng = np.random.default_rng(5)
+    V = rng.integers(1, 1000, size=(1,) + dhw + (2,)).astype(np.int64)
+    P = tiling.partition(V, grid, h)
+    M = tiling.halo_pack(P, h)
+    tile = tiling.tile_extents(dhw, grid)
+    mask = tiling.delivered(grid, tile, h)[None, ..., None] & np.ones_like(M, dtype=bool)
+    ref = tiling.halo_unpack(P, M, h)
+    assert np.array_equal(tiling.halo_unpack(P, np.where(mask, M, -7), h), ref)
+    tags = np.arange(M.size, dtype=np.int64).reshape(M.shape) + 10 ** 6       # unique, and none occurs in V
+    got = tiling.halo_unpack(P, tags, h)
+    assert set(got[got >= 10 ** 6].tolist()) == set(tags[mask].tolist())
