@@ -62,9 +62,15 @@ def parse():
     ap.add_argument("--halo", type=int, default=1, choices=[1, 2],
                     help="U-Net workloads: margin width of the layout; 2 = two layers of a block share one exchange "
                          "(the first also computes the voxel shell the second reads)")
+    ap.add_argument("--coarse-grid", default=None,
+                    help="U-Net workloads: tile grid gd,gh,gw of the coarse levels (tiles merged below "
+                         "--coarse-from); default: the same grid at every level")
+    ap.add_argument("--coarse-from", type=int, default=3,
+                    help="U-Net workloads: first level (0 = full resolution) that uses --coarse-grid")
     ap.add_argument("--gather", action="store_true",
-                    help="U-Net workloads: no halo exchange where the kernels can gather (SP_HALO_GATHER: the "
-                         "convolutions read their margin voxels from the neighbour tiles' interiors)")
+                    help="no halo exchange where the kernels can gather (SP_HALO_GATHER: the convolutions read "
+                         "their margin voxels from the neighbour tiles' interiors); in the headline workload the "
+                         "step then has no halo_pack / halo_unpack launches")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (torch copy_) so that profiler "
                          "byte counters can be scaled against a kernel of known traffic")
@@ -105,8 +111,12 @@ def bench_unet(args):
     w = {name: dev(synth.weights(shape[nd], shape[nd + 1], synth.seed_for(5, synth.T_WEIGHT0 + k), "bf16",
                                  taps=shape[:nd])) for k, (name, shape) in enumerate(plan)}
     dl = dev(synth.normal_volume((n,) + dhw + (classes,), synth.seed_for(5, synth.T_UPSTREAM), "bf16"))
+    grids = None
+    if args.coarse_grid:
+        cg = tuple(int(v) for v in args.coarse_grid.split(","))
+        grids = [grid if i < args.coarse_from else cg for i in range(len(channels))]
     net = unet.UNet(n, dhw, grid, w, channels, in_ch, classes, convs=convs, halo=args.halo, flat=flat,
-                    gather=args.gather)
+                    gather=args.gather, grids=grids)
 
     labels = None
     if args.loss:
@@ -154,7 +164,8 @@ def bench_unet(args):
         "config": {"workload": name + (", grid %dx%dx%d, halo %d, forward + backward (weight and data gradients, "
                                        "no image gradient)" % (grid + (args.halo,))) + (", upstream gradient from the Dice + CE loss"
                                                               if args.loss else "")
-                               + (", halos gathered by the convolutions (no exchange)" if args.gather else ""),
+                               + (", halos gathered by the convolutions (no exchange)" if args.gather else "")
+                               + (", grid %s from level %d on" % (args.coarse_grid, args.coarse_from) if grids else ""),
                    "tflop_per_step": round(flop / 1e12, 2),
                    "hbm_allocated_gb": round(torch.cuda.max_memory_allocated() / 1e9, 1)}}))
 
@@ -202,19 +213,22 @@ def main():
     stream = torch.cuda.current_stream()
     gb = g.with_opts(sp3d.SP_HALO_SKIP_SEND | sp3d.SP_HALO_KEEP_ZERO)    # halo calls of the step
 
+    gc = g.with_opts(sp3d.SP_HALO_GATHER) if args.gather else g    # convolutions of the step
     calls = [
         ("sp_partition", lambda: sp3d.sp_partition(x_vol, Px, g, c, dt, stream)),
         ("halo_pack", lambda: sp3d.halo_pack(Px, M, gb, c, dt, stream)),
         ("halo_unpack", lambda: sp3d.halo_unpack(Px, M, gb, c, dt, stream)),
-        ("conv3d_fwd", lambda: sp3d.conv3d_fwd(Px, w, None, Py, g, c, c, dt, 0, wsp[0], stream)),
+        ("conv3d_fwd", lambda: sp3d.conv3d_fwd(Px, w, None, Py, gc, c, c, dt, 0, wsp[0], stream)),
         ("sp_unpartition", lambda: sp3d.sp_unpartition(Py, y_vol, g, c, dt, stream)),
         ("sp_partition", lambda: sp3d.sp_partition(dy_vol, Pdy, g, c, dt, stream)),
         ("halo_pack", lambda: sp3d.halo_pack(Pdy, M, gb, c, dt, stream)),
         ("halo_unpack", lambda: sp3d.halo_unpack(Pdy, M, gb, c, dt, stream)),
-        ("conv3d_dgrad", lambda: sp3d.conv3d_dgrad(Pdy, w, Pdx, g, c, c, dt, wsp[1], stream)),
+        ("conv3d_dgrad", lambda: sp3d.conv3d_dgrad(Pdy, w, Pdx, gc, c, c, dt, wsp[1], stream)),
         ("sp_unpartition", lambda: sp3d.sp_unpartition(Pdx, dx_vol, g, c, dt, stream)),
-        ("conv3d_wgrad", lambda: sp3d.conv3d_wgrad(Px, Pdy, dw, db, g, c, c, dt, wsp[2], stream)),
+        ("conv3d_wgrad", lambda: sp3d.conv3d_wgrad(Px, Pdy, dw, db, gc, c, c, dt, wsp[2], stream)),
     ]
+    if args.gather:        # the convolutions read their neighbours' voxels themselves: no pack, no unpack
+        calls = [kv for kv in calls if not kv[0].startswith("halo_")]
 
     def step(events=None):
         for name, f in calls:
@@ -288,6 +302,10 @@ def main():
     vox = n * S * S * S
     flop_pass = 2.0 * 27 * c * c * vox
     value = 3 * flop_pass / (ms_per_step * 1e-3) / 1e12
+    if args.gather:        # not part of the step: timed once each for the report
+        avg_ms["halo_pack"] = median_ms(lambda: sp3d.halo_pack(Px, M, gb, c, dt, stream))
+        avg_ms["halo_unpack"] = median_ms(lambda: sp3d.halo_unpack(Px, M, gb, c, dt, stream))
+        count["halo_pack"] = count["halo_unpack"] = 0
     halo_ms = (avg_ms["halo_pack"] * count["halo_pack"] + avg_ms["halo_unpack"] * count["halo_unpack"])
     part_ms = (avg_ms["sp_partition"] * count["sp_partition"]
                + avg_ms["sp_unpartition"] * count["sp_unpartition"])
@@ -353,8 +371,10 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%s: %d^3 volume, Cin=Cout=32, grid %dx%dx%d, halo 1, "
-                               "fwd+dgrad+wgrad with partition/halo/unpartition"
-                               % (cfg["name"] if S == 512 else "c4 recipe at reduced size", S, *grid),
+                               "fwd+dgrad+wgrad with partition/halo/unpartition%s"
+                               % (cfg["name"] if S == 512 else "c4 recipe at reduced size", S, *grid,
+                                  " (--gather: no pack / unpack in the step, the convolutions read their "
+                                  "neighbours' voxels themselves)" if args.gather else ""),
                    "input_gen_s": round(t_gen, 1)},
         "halo_overhead_pct": round(100.0 * halo_ms / kernel_ms, 2),
         "partition_halo_overhead_pct": round(100.0 * (halo_ms + part_ms) / kernel_ms, 2),

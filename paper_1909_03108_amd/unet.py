@@ -50,7 +50,7 @@ def layer_plan(channels=(32, 64, 128, 256), in_ch=1, classes=3, convs=2, flat=Fa
 
 class UNet:
     def __init__(self, n, dhw, grid, weights, channels=(32, 64, 128, 256), in_ch=1, classes=3,
-                 dt=sp3d.SP_BF16, convs=2, halo=1, flat=False, gather=False):
+                 dt=sp3d.SP_BF16, convs=2, halo=1, flat=False, gather=False, grids=None):
         self.channels, self.in_ch, self.classes, self.dt = tuple(channels), in_ch, classes, dt
         self.convs = convs
         # Runs of more than two layers would need ReLU masks further around the tiles in the backward pass than
@@ -64,8 +64,16 @@ class UNet:
         self.free = {}                        # (padded shape, channels) -> released gradient buffers
         self.L = len(channels)
         self.flat = bool(flat)
-        self.g = [sp3d.Geom(n, (dhw[0] if flat else dhw[0] >> i, dhw[1] >> i, dhw[2] >> i), grid, halo, 0, flat)
+        # grids: one tile grid per level (default: `grid` everywhere).  The paper allows one or more patches per
+        # device (Fig. 1a), and a deep network's coarse levels are small: merging their tiles into fewer, larger
+        # ones gives the convolutions longer marches and fuller patches.  Where two neighbouring levels differ, the
+        # tensor that crosses (pooled activation, up-convolution input, their gradients) is reassembled and cut
+        # again (sp_unpartition + sp_partition on a tensor an eighth of the finer level's size).
+        self.grids = [tuple(grid)] * self.L if grids is None else [tuple(q) for q in grids]
+        assert len(self.grids) == self.L
+        self.g = [sp3d.Geom(n, (dhw[0] if flat else dhw[0] >> i, dhw[1] >> i, dhw[2] >> i), self.grids[i], halo, 0, flat)
                   for i in range(self.L)]
+        self.vols = {}                        # (shape) -> volume used to carry a tensor from one grid to another
         for g in self.g:
             assert sp3d.sp_check_geom(g) == sp3d.SP_OK
         self.w = weights                      # name -> device tensor
@@ -193,6 +201,20 @@ class UNet:
     # gradient buffers are short-lived: they come from a free list keyed by shape and go back to it as
     # soon as their consumer has run, so the backward pass needs a few of the largest tensors, not one per
     # layer
+    def _regrid(self, P, g_from, g_to, c, out):
+        """The tensor P (tiles of g_from) as tiles of g_to (same volume, another grid), written into `out`."""
+        assert (g_from.n, g_from.d, g_from.h, g_from.w) == (g_to.n, g_to.d, g_to.h, g_to.w)
+        shape = (g_from.n, g_from.d, g_from.h, g_from.w, c)
+        V = self.vols.get(shape)
+        if V is None:
+            V = self.vols[shape] = torch.empty(shape, dtype=P.dtype, device="cuda")
+        sp3d.sp_unpartition(P, V, g_from, c, self.dt)
+        sp3d.sp_partition(V, out, g_to, c, self.dt)
+        return out
+
+    def _same_grid(self, i, j):
+        return self.grids[i] == self.grids[j]
+
     def _tmp(self, g, c):
         key = (g.padded_shape, c)
         lst = self.free.setdefault(key, [])
@@ -213,12 +235,21 @@ class UNet:
             g, c = self.g[i], ch[i]
             if i > 0:
                 Pp = self._buf("pool%d" % i, g, prev)
-                sp3d.sp_maxpool2_fwd(P, Pp, self.g[i - 1], prev, dt)
+                if self._same_grid(i - 1, i):
+                    sp3d.sp_maxpool2_fwd(P, Pp, self.g[i - 1], prev, dt)
+                else:                                # pooled on the finer level's grid, then cut for this level's
+                    gq = sp3d.coarse_geom(self.g[i - 1])
+                    Pq = self._buf("pool%d.q" % i, gq, prev)
+                    sp3d.sp_maxpool2_fwd(P, Pq, self.g[i - 1], prev, dt)
+                    self._regrid(Pq, gq, g, prev, Pp)
                 P = Pp
             P = self._block_fwd("enc%d" % i, P, g, prev, c, A)   # level output: pool input / skip / ReLU mask
             prev = c
         for i in range(self.L - 2, -1, -1):
             g, c = self.g[i], ch[i]
+            if not self._same_grid(i, i + 1):        # the coarse tensor on the finer level's grid
+                gq = sp3d.coarse_geom(g)
+                P = self._regrid(P, self.g[i + 1], gq, prev, self._buf("up%d.q" % i, gq, prev))
             A["up%d.x" % i] = P
             Pu = self._buf("up%d.y" % i, g, c)
             sp3d.sp_upconv2_fwd(P, self.w["up%d" % i], None, Pu, g, prev, c, dt)
@@ -335,8 +366,15 @@ class UNet:
             sp3d.sp_upconv2_wgrad(A["up%d.x" % i], Pu, du, None, g, up_in, c, dt,
                                   self._ws(sp3d.SP_OP_UPCONV_WGRAD, g, up_in, c))
             grads["up%d" % i] = du
-            Pg = self._tmp(self.g[i + 1], up_in)
-            sp3d.sp_upconv2_dgrad(Pu, self.w["up%d" % i], Pg, g, up_in, c, dt)
+            if self._same_grid(i, i + 1):
+                Pg = self._tmp(self.g[i + 1], up_in)
+                sp3d.sp_upconv2_dgrad(Pu, self.w["up%d" % i], Pg, g, up_in, c, dt)
+            else:
+                gq = sp3d.coarse_geom(g)
+                Pq = self._tmp(gq, up_in)
+                sp3d.sp_upconv2_dgrad(Pu, self.w["up%d" % i], Pq, g, up_in, c, dt)
+                Pg = self._regrid(Pq, gq, self.g[i + 1], up_in, self._tmp(self.g[i + 1], up_in))
+                self._release(Pq, gq, up_in)
             self._release(Pu, g, c)
         joined = False            # Pg already is d/dz of the level's last layer (pool backward + skip + ReLU mask)
         for i in range(self.L - 1, -1, -1):
@@ -347,6 +385,11 @@ class UNet:
                 # the level above: gradient through its pooling, plus the one that came through its skip
                 # connection, masked by the ReLU of its output (which is the pooling input), in one sweep
                 Ps = skip_grad.pop(i - 1)
+                if not self._same_grid(i - 1, i):     # the pooled tensor's gradient on the finer level's grid
+                    gq = sp3d.coarse_geom(self.g[i - 1])
+                    Pq = self._regrid(Pg, g, gq, cin, self._tmp(gq, cin))
+                    self._release(Pg, g, cin)
+                    Pg, g = Pq, gq
                 sp3d.sp_maxpool2_bwd_join(A["enc%d.y" % (i - 1)], Pg, Ps, Ps, self.g[i - 1], cin, dt)
                 self._release(Pg, g, cin)
                 Pg, joined = Ps, True
