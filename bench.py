@@ -293,6 +293,13 @@ def main():
                "halo_unpack": median_ms(lambda: sp3d.halo_unpack(Px, M, g, c, dt, stream)),
                "sp_halo_exchange": median_ms(lambda: sp3d.sp_halo_exchange(Px, g, c, dt, stream))}
 
+    # The same forward launch on an all-zero input: its arithmetic, memory traffic and instruction stream are
+    # unchanged, only the operands' bits stop toggling.  If it runs faster, the rate of the real launch is set by
+    # the chip's power management (clock under load), not by the kernel's schedule.
+    Pzero = torch.zeros_like(Py)
+    fwd_zero_ms = median_ms(lambda: sp3d.conv3d_fwd(Pzero, w, None, Py, g, c, c, dt, 0, wsp[0], stream), reps=5)
+    del Pzero
+
     per = {}
     for name, e0, e1 in events:
         per.setdefault(name, []).append(e0.elapsed_time(e1))
@@ -390,6 +397,11 @@ def main():
         "halo_exchange_fused_ms": round(exchange_ms, 4),
         "halo_exchange_fused_zero_fill_ms": round(full_ms["sp_halo_exchange"], 4),
         "library_gemm_tflops": None if gemm_tflops is None else round(gemm_tflops, 1),
+        "power_probe": {"conv3d_fwd_ms": round(avg_ms["conv3d_fwd"], 4), "conv3d_fwd_zero_input_ms": round(fwd_zero_ms, 4),
+                        "what": "the same launch on an all-zero input tensor (same work, operand bits do not toggle), "
+                                "timed after the step: a faster run means the real one is held by the chip's power "
+                                "management; library_gemm_tflops is the vendor GEMM (torch.matmul 8192^3 bf16, N(0,1) "
+                                "data) on this box for comparison"},
         "roofline": roofline,
         "roofline_other": other,
     }
