@@ -71,6 +71,9 @@ def parse():
                     help="no halo exchange where the kernels can gather (SP_HALO_GATHER: the convolutions read "
                          "their margin voxels from the neighbour tiles' interiors); in the headline workload the "
                          "step then has no halo_pack / halo_unpack launches")
+    ap.add_argument("--bits", action="store_true",
+                    help="U-Net workloads: ReLU masks between the layers of a block as one bit per value "
+                         "(conv3d_fwd_bits / conv3d_dgrad_bits) instead of re-reading the activation")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (torch copy_) so that profiler "
                          "byte counters can be scaled against a kernel of known traffic")
@@ -116,7 +119,7 @@ def bench_unet(args):
         cg = tuple(int(v) for v in args.coarse_grid.split(","))
         grids = [grid if i < args.coarse_from else cg for i in range(len(channels))]
     net = unet.UNet(n, dhw, grid, w, channels, in_ch, classes, convs=convs, halo=args.halo, flat=flat,
-                    gather=args.gather, grids=grids)
+                    gather=args.gather, grids=grids, bits=args.bits)
 
     labels = None
     if args.loss:
@@ -165,6 +168,7 @@ def bench_unet(args):
                                        "no image gradient)" % (grid + (args.halo,))) + (", upstream gradient from the Dice + CE loss"
                                                               if args.loss else "")
                                + (", halos gathered by the convolutions (no exchange)" if args.gather else "")
+                               + (", one-bit ReLU masks inside the blocks" if args.bits else "")
                                + (", grid %s from level %d on" % (args.coarse_grid, args.coarse_from) if grids else ""),
                    "tflop_per_step": round(flop / 1e12, 2),
                    "hbm_allocated_gb": round(torch.cuda.max_memory_allocated() / 1e9, 1)}}))

@@ -188,6 +188,38 @@ int conv3d_dgrad(const void *Pdz, const void *w, void *Pdx, const sp_geom_t *g, 
 int conv3d_dgrad_relu(const void *Pdz, const void *w, const void *Px, void *Pdx, const sp_geom_t *g,
                       int cin, int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream);
 
+/* ---- the ReLU mask as one bit per value ---------------------------------------------------
+ * The backward pass of a conv + ReLU stack (Sec. 3) needs of a layer's input only whether each value was
+ * positive.  Read as a tensor that is a second full pass over the activation; as bits it is 1/16 of it.
+ * Layout of `bits` for a padded-tile array of C channels (C a multiple of 32; bf16): per padded voxel p
+ * (index as in P, channels dropped) and block b of 32 channels two uint16_t words, at word index
+ * (p * C/32 + b) * 2 + hi; word `hi` holds channel 32 b + 8 q + 4 hi + i in bit 4 q + i (q, i = 0..3).
+ * (The order in which the matrix cores hand results to lanes, so that neither side shuffles.)
+ * A bit is 1 where the value is positive - not zero, not negative, not NaN.  Only the words of interior
+ * voxels mean anything: conv3d_fwd_bits leaves the others unwritten and no call reads them. */
+
+/* Bytes of the bit array for C channels; 0 if the geometry or C is invalid. */
+size_t sp_relu_bits_bytes(const sp_geom_t *g, int c);
+/* 1 if conv3d_fwd_bits (op = SP_OP_FWD) / conv3d_dgrad_bits (SP_OP_DGRAD) runs for these sizes, else 0.
+ * They serve the 3-D bf16 layers with channel counts in multiples of 32, and (forward) the first layer with
+ * its single input channel; use the tensor forms elsewhere. */
+int sp_relu_bits_supported(int op, const sp_geom_t *g, int cin, int cout, sp_dtype_t dt);
+/* bits <- (Py > 0) for every padded voxel (margins included: whatever they hold). */
+int sp_relu_bits(const void *Py, void *bits, const sp_geom_t *g, int c, sp_dtype_t dt, void *stream);
+/* conv3d_fwd with SP_FLAG_RELU (which `flags` must hold) that also writes the bits of its result Py:
+ * Py as from conv3d_fwd, bits as from sp_relu_bits(Py) at the interior voxels.  SP_EUNSUPPORTED where
+ * sp_relu_bits_supported says 0. */
+int conv3d_fwd_bits(const void *Px, const void *w, const float *bias, void *Py, void *bits, const sp_geom_t *g,
+                    int cin, int cout, sp_dtype_t dt, uint32_t flags, void *ws, size_t ws_bytes, void *stream);
+/* The same for the two-tensor forward pass conv3d_fwd2 (declared below; Cin = ca + cb). */
+int conv3d_fwd2_bits(const void *Pxa, int ca, const void *Pxb, int cb, const void *w, const float *bias,
+                     void *Py, void *bits, const sp_geom_t *g, int cout, sp_dtype_t dt, uint32_t flags,
+                     void *ws, size_t ws_bytes, void *stream);
+/* conv3d_dgrad_relu with the mask given as bits (of the layer's forward input, Cin channels) instead of
+ * the tensor Px: the same bits in Pdx as conv3d_dgrad_relu with the Px that the bits were taken from. */
+int conv3d_dgrad_bits(const void *Pdz, const void *w, const void *bits, void *Pdx, const sp_geom_t *g,
+                      int cin, int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream);
+
 /* Weight gradient.  dw[kd][kh][kw][ci][co] = sum over tiles and interior voxels v of
  * Px[v + (kd,kh,kw)][ci] * Pdz[v + (1,1,1)][co];  db[co] = sum of Pdz interiors (db may be NULL).
  * Px must hold its halos (as left by the forward pass); only the interiors of Pdz are read.

@@ -256,9 +256,15 @@ static int check_conv_args(const void *a, const void *b, const void *c, const sp
     return SP_OK;
 }
 
-int conv3d_fwd(const void *Px, const void *w, const float *bias, void *Py, const sp_geom_t *g,
-               int cin, int cout, sp_dtype_t dt, uint32_t flags, void *ws, size_t ws_bytes,
-               void *stream) {
+// forward kernels that can write the one-bit ReLU mask: the 3-D marching kernels and the one-input-channel layer
+static bool fwd_bits_supported(const Geo &o, int cin, int cout, sp_dtype_t dt) {
+    return conv_mfma_bits_supported(o, cin, cout, dt) ||
+           (!conv_mfma_supported(o, cin, cout, dt) && o.grow == 0 && conv_c1_supported(o, cin, cout, dt));
+}
+
+static int fwd_impl(const void *Px, const void *w, const float *bias, void *Py, void *bits, const sp_geom_t *g,
+                    int cin, int cout, sp_dtype_t dt, uint32_t flags, void *ws, size_t ws_bytes,
+                    void *stream) {
     Geo o;
     int rc = check_conv_args(Px, w, Py, g, cin, cout, dt, &o);
     if (rc != SP_OK) return rc;
@@ -270,13 +276,21 @@ int conv3d_fwd(const void *Px, const void *w, const float *bias, void *Py, const
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool gather = g->opts & SP_HALO_GATHER;
     if (gather && !conv_mfma_gather_supported(o, cin, cout, dt)) return SP_EUNSUPPORTED;
+    if (bits) {
+        if (!relu) return SP_EINVAL;
+        if (!fwd_bits_supported(o, cin, cout, dt)) return SP_EUNSUPPORTED;
+        if ((reinterpret_cast<uintptr_t>(bits) & 3) || overlap(bits, pv * (cout / 32) * 4, Py, pv * cout * es) ||
+            overlap(bits, pv * (cout / 32) * 4, Px, pv * cin * es))
+            return SP_EINVAL;
+    }
     if (conv_mfma_supported(o, cin, cout, dt)) {
         const size_t need = conv_mfma_ws_bytes(o, cin, cout);
         if (need && (!ws || ws_bytes < need || !aligned16(ws))) return SP_EWORKSPACE;
-        return launch_conv_mfma(Px, w, bias, Py, o, cin, cout, relu, false, ws, s, nullptr, nullptr, gather);
+        return launch_conv_mfma(Px, w, bias, Py, o, cin, cout, relu, false, ws, s, nullptr, nullptr, gather, bits);
     }
     if (o.grow == 0 && conv_c1_supported(o, cin, cout, dt))
-        return launch_conv_c1_fwd(shifted(Px, o, 1, dt), w, bias, shifted(Py, o, cout, dt), o, cout, relu, s);
+        return launch_conv_c1_fwd(shifted(Px, o, 1, dt), w, bias, shifted(Py, o, cout, dt), o, cout, relu, s,
+                                  bits ? static_cast<char *>(bits) + interior_shift(o) * (cout / 32) * 4 : nullptr);
     // few input channels: zero-padded copies in the workspace, then the matrix-core kernel
     if (!conv_c1_supported(o, cin, cout, dt) && chan_pad_supported(o, cin, cout, dt)) {
         const size_t need = chan_pad_fwd_ws_bytes(o, cin, cout);
@@ -286,8 +300,21 @@ int conv3d_fwd(const void *Px, const void *w, const float *bias, void *Py, const
     return launch_conv_direct(Px, w, bias, Py, o, cin, cout, dt, relu, false, s);
 }
 
+int conv3d_fwd(const void *Px, const void *w, const float *bias, void *Py, const sp_geom_t *g,
+               int cin, int cout, sp_dtype_t dt, uint32_t flags, void *ws, size_t ws_bytes,
+               void *stream) {
+    return fwd_impl(Px, w, bias, Py, nullptr, g, cin, cout, dt, flags, ws, ws_bytes, stream);
+}
+
+int conv3d_fwd_bits(const void *Px, const void *w, const float *bias, void *Py, void *bits, const sp_geom_t *g,
+                    int cin, int cout, sp_dtype_t dt, uint32_t flags, void *ws, size_t ws_bytes, void *stream) {
+    if (!bits) return SP_EINVAL;
+    return fwd_impl(Px, w, bias, Py, bits, g, cin, cout, dt, flags, ws, ws_bytes, stream);
+}
+
 static int dgrad_impl(const void *Pdz, const void *w, const void *Pmask, void *Pdx, const sp_geom_t *g, int cin,
-                      int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream) {
+                      int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream,
+                      const void *bits = nullptr) {
     Geo o;
     int rc = check_conv_args(Pdz, w, Pdx, g, cin, cout, dt, &o);
     if (rc != SP_OK) return rc;
@@ -299,10 +326,16 @@ static int dgrad_impl(const void *Pdz, const void *w, const void *Pmask, void *P
     // the kernel's "input channels" are cout and its "output channels" are cin
     const bool gather = g->opts & SP_HALO_GATHER;
     if (gather && !conv_mfma_gather_supported(o, cout, cin, dt)) return SP_EUNSUPPORTED;
+    if (bits) {
+        if (!conv_mfma_bits_supported(o, cout, cin, dt)) return SP_EUNSUPPORTED;
+        if ((reinterpret_cast<uintptr_t>(bits) & 3) || overlap(bits, pv * (cin / 32) * 4, Pdx, pv * cin * es))
+            return SP_EINVAL;
+    }
     if (conv_mfma_supported(o, cout, cin, dt)) {
         const size_t need = conv_mfma_ws_bytes(o, cout, cin);
         if (need && (!ws || ws_bytes < need || !aligned16(ws))) return SP_EWORKSPACE;
-        return launch_conv_mfma(Pdz, w, nullptr, Pdx, o, cout, cin, false, true, ws, s, Pmask, nullptr, gather);
+        return launch_conv_mfma(Pdz, w, nullptr, Pdx, o, cout, cin, false, true, ws, s, Pmask, nullptr, gather,
+                                const_cast<void *>(bits));
     }
     return launch_conv_direct(Pdz, w, nullptr, Pdx, o, cout, cin, dt, false, true, s, 3, Pmask);
 }
@@ -316,6 +349,41 @@ int conv3d_dgrad_relu(const void *Pdz, const void *w, const void *Px, void *Pdx,
                       int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream) {
     if (!Px) return SP_EINVAL;
     return dgrad_impl(Pdz, w, Px, Pdx, g, cin, cout, dt, ws, ws_bytes, stream);
+}
+
+int conv3d_dgrad_bits(const void *Pdz, const void *w, const void *bits, void *Pdx, const sp_geom_t *g, int cin,
+                      int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream) {
+    if (!bits) return SP_EINVAL;
+    return dgrad_impl(Pdz, w, nullptr, Pdx, g, cin, cout, dt, ws, ws_bytes, stream, bits);
+}
+
+size_t sp_relu_bits_bytes(const sp_geom_t *g, int c) {
+    Geo o;
+    if (make_geo(g, &o) != SP_OK || c <= 0 || c % 32) return 0;
+    return static_cast<size_t>(o.ntiles) * o.tile_vox * (c / 32) * 4;
+}
+
+int sp_relu_bits_supported(int op, const sp_geom_t *g, int cin, int cout, sp_dtype_t dt) {
+    Geo o;
+    if (make_geo(g, &o) != SP_OK || !chan_ok(cin) || !chan_ok(cout) || !dtype_ok(dt)) return 0;
+    switch (op) {
+    case SP_OP_FWD: return fwd_bits_supported(o, cin, cout, dt) ? 1 : 0;
+    case SP_OP_DGRAD: return conv_mfma_bits_supported(o, cout, cin, dt) ? 1 : 0;     // channel roles swapped
+    default: return 0;
+    }
+}
+
+int sp_relu_bits(const void *Py, void *bits, const sp_geom_t *g, int c, sp_dtype_t dt, void *stream) {
+    if (!Py || !bits) return SP_EINVAL;
+    Geo o;
+    int rc = make_geo(g, &o);
+    if (rc != SP_OK) return rc;
+    if (c <= 0) return SP_EINVAL;
+    if (dt != SP_BF16 || c % 32) return SP_EUNSUPPORTED;
+    const size_t pv = static_cast<size_t>(o.ntiles) * o.tile_vox;
+    if (!aligned16(Py) || (reinterpret_cast<uintptr_t>(bits) & 3) || overlap(Py, pv * c * 2, bits, pv * (c / 32) * 4))
+        return SP_EINVAL;
+    return launch_relu_bits(Py, bits, pv * (c / 32), static_cast<hipStream_t>(stream));
 }
 
 int conv3d_wgrad(const void *Px, const void *Pdz, float *dw, float *db, const sp_geom_t *g, int cin,
@@ -366,9 +434,9 @@ static int check_pair(const void *a, int ca, const void *b, int cb, sp_dtype_t d
     return SP_OK;
 }
 
-int conv3d_fwd2(const void *Pxa, int ca, const void *Pxb, int cb, const void *w, const float *bias, void *Py,
-                const sp_geom_t *g, int cout, sp_dtype_t dt, uint32_t flags, void *ws, size_t ws_bytes,
-                void *stream) {
+static int fwd2_impl(const void *Pxa, int ca, const void *Pxb, int cb, const void *w, const float *bias, void *Py,
+                     void *bits, const sp_geom_t *g, int cout, sp_dtype_t dt, uint32_t flags, void *ws,
+                     size_t ws_bytes, void *stream) {
     Geo o;
     int rc = check_conv_args(Pxa, w, Py, g, ca + cb, cout, dt, &o);
     if (rc != SP_OK) return rc;
@@ -381,9 +449,30 @@ int conv3d_fwd2(const void *Pxa, int ca, const void *Pxb, int cb, const void *w,
     if (overlap(Pxa, pv * ca * 2, Py, pv * cout * 2) || overlap(Pxb, pv * cb * 2, Py, pv * cout * 2)) return SP_EINVAL;
     const size_t need = conv_mfma_ws_bytes(o, ca + cb, cout);
     if (need && (!ws || ws_bytes < need || !aligned16(ws))) return SP_EWORKSPACE;
+    if (bits) {
+        if (!(flags & SP_FLAG_RELU)) return SP_EINVAL;
+        if (!conv_mfma_bits_supported(o, ca + cb, cout, dt)) return SP_EUNSUPPORTED;
+        const size_t nb = pv * (cout / 32) * 4;
+        if ((reinterpret_cast<uintptr_t>(bits) & 3) || overlap(bits, nb, Py, pv * cout * 2) ||
+            overlap(bits, nb, Pxa, pv * ca * 2) || overlap(bits, nb, Pxb, pv * cb * 2))
+            return SP_EINVAL;
+    }
     const ConvSplit sp{Pxb, ca, nullptr, 0};
     return launch_conv_mfma(Pxa, w, bias, Py, o, ca + cb, cout, flags & SP_FLAG_RELU, false, ws,
-                            static_cast<hipStream_t>(stream), nullptr, &sp, gather);
+                            static_cast<hipStream_t>(stream), nullptr, &sp, gather, bits);
+}
+
+int conv3d_fwd2(const void *Pxa, int ca, const void *Pxb, int cb, const void *w, const float *bias, void *Py,
+                const sp_geom_t *g, int cout, sp_dtype_t dt, uint32_t flags, void *ws, size_t ws_bytes,
+                void *stream) {
+    return fwd2_impl(Pxa, ca, Pxb, cb, w, bias, Py, nullptr, g, cout, dt, flags, ws, ws_bytes, stream);
+}
+
+int conv3d_fwd2_bits(const void *Pxa, int ca, const void *Pxb, int cb, const void *w, const float *bias, void *Py,
+                     void *bits, const sp_geom_t *g, int cout, sp_dtype_t dt, uint32_t flags, void *ws,
+                     size_t ws_bytes, void *stream) {
+    if (!bits) return SP_EINVAL;
+    return fwd2_impl(Pxa, ca, Pxb, cb, w, bias, Py, bits, g, cout, dt, flags, ws, ws_bytes, stream);
 }
 
 int conv3d_dgrad2(const void *Pdz, const void *w, void *Pdxa, int ca, void *Pdxb, int cb, const sp_geom_t *g,

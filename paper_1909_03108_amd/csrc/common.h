@@ -61,6 +61,8 @@ int launch_halo_unpack(void *P, const void *msg, const Geo &g, int c, sp_dtype_t
 int launch_halo_exchange(void *P, const Geo &g, int c, sp_dtype_t dt, int border, hipStream_t s);
 int launch_relu_bwd(const void *dy, const void *y, void *dz, size_t elems, sp_dtype_t dt,
                     hipStream_t s);
+// one-bit ReLU mask of a bf16 tensor: `blocks` records of 32 channels -> one 32-bit word each
+int launch_relu_bits(const void *y, void *bits, size_t blocks, hipStream_t s);
 
 // ks = kernel extent per axis (3, or 1 for the 1x1x1 convolution); mask (optional): tensor laid out like Pout,
 // results are zeroed where it is not positive
@@ -124,10 +126,14 @@ struct ConvSplit {
 };
 // mask (optional, data gradient): tensor laid out like Pout; results are zeroed where it is not positive
 // gather: margin voxels that have a neighbour tile are read from that tile's interior (SP_HALO_GATHER)
+// bits (optional): the one-bit ReLU mask (layout: sp3d.h, sp_relu_bits) - read by a data gradient instead of a
+// mask tensor (zero where the bit is clear), written by a forward pass with ReLU (bit = result positive)
 bool conv_mfma_gather_supported(const Geo &g, int cin, int cout, sp_dtype_t dt);
+bool conv_mfma_bits_supported(const Geo &g, int cin, int cout, sp_dtype_t dt);
 int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Pout, const Geo &g,
                      int cin, int cout, bool relu, bool dgrad, void *ws, hipStream_t s,
-                     const void *mask = nullptr, const ConvSplit *split = nullptr, bool gather = false);
+                     const void *mask = nullptr, const ConvSplit *split = nullptr, bool gather = false,
+                     void *bits = nullptr);
 
 // wide layers on few voxels: output-stationary implicit GEMM on the packed weights (conv_gemm.hip);
 // launch_conv_mfma hands such layers over after packing
@@ -137,8 +143,9 @@ int launch_conv_gemm(const void *Pin, const void *wpack, const float *bias, void
 
 // single-input-channel first layer (conv_c1.hip)
 bool conv_c1_supported(const Geo &g, int cin, int cout, sp_dtype_t dt);
+// bits (optional, with relu): also writes the one-bit ReLU mask of the result (pointer shifted like Py)
 int launch_conv_c1_fwd(const void *Px, const void *w, const float *bias, void *Py, const Geo &g, int cout,
-                       bool relu, hipStream_t s);
+                       bool relu, hipStream_t s, void *bits = nullptr);
 size_t wgrad_c1_ws_bytes(const Geo &g, int cout);
 int launch_wgrad_c1(const void *Px, const void *Pdz, float *dw, float *db, const Geo &g, int cout, void *ws,
                     hipStream_t s);

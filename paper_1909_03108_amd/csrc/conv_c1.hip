@@ -30,6 +30,7 @@ struct C1Args {
     const uint16_t *w;     // [27][1][cout]
     const float *bias;
     uint16_t *y;           // forward: padded tiles, cout channels
+    uint16_t *bits;        // forward, optional: one-bit ReLU mask of y (layout: sp3d.h, sp_relu_bits)
     const uint16_t *dz;    // weight gradient: padded tiles, cout channels
     float *part;           // weight gradient: [ngroups][cout/32][32 taps][32]
     Geo g;
@@ -87,7 +88,10 @@ __host__ __device__ constexpr int fwd_tap_off(int t) {
 // the input voxels of the next one are already on their way into registers (wave w fetches rows w, w + 4, ...;
 // lanes 0..33 one voxel each), and they are written to the other half of a double-buffered LDS array afterwards,
 // so neither the memory latency nor more than one barrier per brick lies on the critical path.
-template <bool RELU, bool HAS_BIAS>
+// BITS: the kernel also writes the one-bit form of its result's ReLU mask.  The matrix cores hand lane (voxel,
+// half) the channels 8 q + 4 half + i of its voxel, which is the order of the bits in the mask's 16-bit words:
+// each lane collects its word from the packed results and stores it (a wave: 128 consecutive bytes per block).
+template <bool RELU, bool HAS_BIAS, bool BITS>
 __global__ __launch_bounds__(kThreads) void conv_c1_fwd_kernel(C1Args a, int nhg) {
     __shared__ __attribute__((aligned(16))) uint16_t lx[2][FXVOX + 8];
     __shared__ __attribute__((aligned(16))) char ly[kThreads / 64][2][YBUF];
@@ -184,11 +188,23 @@ __global__ __launch_bounds__(kThreads) void conv_c1_fwd_kernel(C1Args a, int nhg
                         acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[1].v, xf[k][1].v, acc[k], 0, 0, 0);
 #pragma unroll
                     for (int k = 0; k < 2; ++k) {
+                        uint32_t word = 0;
 #pragma unroll
                         for (int q = 0; q < 4; ++q) {
                             uint32_t p0 = pack2(acc[k][4 * q], acc[k][4 * q + 1]), p1 = pack2(acc[k][4 * q + 2], acc[k][4 * q + 3]);
                             if (RELU) { p0 = relu2(p0); p1 = relu2(p1); }
                             *reinterpret_cast<uint2 *>(wr_at + k * YBUF + 16 * q) = make_uint2(p0, p1);
+                            if (BITS)       // positive: not zero, not negative, not NaN
+                                word |= (((p0 & 0xffffu) - 1u < 0x7f80u ? 1u : 0u) | ((p0 >> 16) - 1u < 0x7f80u ? 2u : 0u) |
+                                         ((p1 & 0xffffu) - 1u < 0x7f80u ? 4u : 0u) | ((p1 >> 16) - 1u < 0x7f80u ? 8u : 0u))
+                                        << (4 * q);
+                        }
+                        if (BITS) {
+                            const int oh = h0 + r0 + r + k;
+                            const size_t vox = static_cast<size_t>(tile) * g.tile_vox +
+                                               (static_cast<size_t>(od + 1) * g.ph + oh + 1) * g.pw + w0 + 1 + col;
+                            if (oh < g.th && w0 + col < g.tw)
+                                a.bits[(vox * ncb + cb) * 2 + hi] = static_cast<uint16_t>(word);
                         }
                     }
                     // the LDS unit serves a wave's accesses in order, so the reads below see the writes above
@@ -372,24 +388,29 @@ bool conv_c1_supported(const Geo &g, int cin, int cout, sp_dtype_t dt) {
 }
 
 int launch_conv_c1_fwd(const void *Px, const void *w, const float *bias, void *Py, const Geo &g, int cout,
-                       bool relu, hipStream_t s) {
+                       bool relu, hipStream_t s, void *bits) {
+    if (bits && !relu) return SP_EINVAL;
     C1Args a{};
     a.x = static_cast<const uint16_t *>(Px);
     a.w = static_cast<const uint16_t *>(w);
     a.bias = bias;
     a.y = static_cast<uint16_t *>(Py);
+    a.bits = static_cast<uint16_t *>(bits);
     a.g = g;
     a.cout = cout;
     a.relu = relu ? 1 : 0;
     plan(g, &a);
     const int nhg = (g.th + FH - 1) / FH;
     const dim3 grid(static_cast<unsigned>(1LL * g.ntiles * g.td * nhg)), block(kThreads);
-    if (relu) {
-        if (bias) hipLaunchKernelGGL((conv_c1_fwd_kernel<true, true>), grid, block, 0, s, a, nhg);
-        else hipLaunchKernelGGL((conv_c1_fwd_kernel<true, false>), grid, block, 0, s, a, nhg);
+    if (bits) {
+        if (bias) hipLaunchKernelGGL((conv_c1_fwd_kernel<true, true, true>), grid, block, 0, s, a, nhg);
+        else hipLaunchKernelGGL((conv_c1_fwd_kernel<true, false, true>), grid, block, 0, s, a, nhg);
+    } else if (relu) {
+        if (bias) hipLaunchKernelGGL((conv_c1_fwd_kernel<true, true, false>), grid, block, 0, s, a, nhg);
+        else hipLaunchKernelGGL((conv_c1_fwd_kernel<true, false, false>), grid, block, 0, s, a, nhg);
     } else {
-        if (bias) hipLaunchKernelGGL((conv_c1_fwd_kernel<false, true>), grid, block, 0, s, a, nhg);
-        else hipLaunchKernelGGL((conv_c1_fwd_kernel<false, false>), grid, block, 0, s, a, nhg);
+        if (bias) hipLaunchKernelGGL((conv_c1_fwd_kernel<false, true, false>), grid, block, 0, s, a, nhg);
+        else hipLaunchKernelGGL((conv_c1_fwd_kernel<false, false, false>), grid, block, 0, s, a, nhg);
     }
     return record_hip(hipGetLastError());
 }

@@ -75,7 +75,8 @@ struct ConvArgs {
     uint16_t *out;          // output tensor (out_cs channels per voxel)
     uint16_t *out2;         // optional second output tensor (out2_cs channels per voxel): output channels
     int out_ca, out2_cs;    //   [out_ca, ko) go there, [0, out_ca) to `out`
-    const uint16_t *mask;   // RELU == 2: tensor laid out like `out`; results are zeroed where it is not positive
+    const uint16_t *mask;   // kMask: tensor laid out like `out`; results are zeroed where it is not positive
+    uint16_t *bits;         // kMaskBits (read) / kReluBits (written): one bit per output value, see relu_bit
     float *part;            // fp32 partial sums in fragment order (see part_unit)
     Geo g;
     int in_cs, in_co, out_cs;
@@ -178,8 +179,19 @@ __device__ __forceinline__ OutDst out_dest(const ConvArgs &a, int cj) {
 
 // What happens to a finished output value (template parameter RELU of the kernels below).
 enum Epilogue { kNone = 0, kRelu = 1,   // max(z, 0): forward with SP_FLAG_RELU
-                kMask = 2 };            // z where the mask tensor is positive, else 0: the data gradient followed
+                kMask = 2,              // z where the mask tensor is positive, else 0: the data gradient followed
                                         // by the backward of the ReLU that produced the layer's input
+                kMaskBits = 3,          // kMask with the one-bit form of the mask
+                kReluBits = 4 };        // kRelu that also writes the one-bit mask of its result
+constexpr bool is_relu(int e) { return e == kRelu || e == kReluBits; }
+
+// One-bit ReLU mask.  The masked data gradient needs of the activation only "was it positive"; as a tensor that
+// costs a second full read (64 bytes per voxel and 32 channels), as bits 4 bytes.  The bits are kept in the order
+// in which the matrix cores hand results to the lanes, so that neither side has to shuffle: per padded voxel and
+// block of 32 channels two 16-bit words, word `hi` holding channel 8 q + 4 hi + i in bit 4 q + i (q = 0..3,
+// i = 0..3) - exactly the 16 values that lane 32 hi + voxel holds for a row.  Word index:
+// (padded voxel index * blocks + block) * 2 + hi.  Only interior voxels are ever written or read.
+// A bit is set where the bf16 value is positive: not zero, not negative, not NaN (positive_halves).
 
 // two bf16 in a word -> 0xffff in each half whose value is positive (not zero, not negative, not NaN)
 __device__ __forceinline__ uint32_t positive_halves(uint32_t v) {
@@ -210,33 +222,43 @@ __device__ __forceinline__ void side_load(pin_t &d, const float *p) {
 __device__ __forceinline__ void side_load(mask_t &d, const uint16_t *p) {
     asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(d) : "v"(p) : "memory");
 }
+// (a macro: a reference cannot bind to the vector element that receives the word)
+#define SP3D_SIDE_LOAD_BITS(d, p) asm volatile("global_load_ushort %0, %1, off" : "=v"(d) : "v"(p) : "memory")
 // The wait of a step's end (NV vector-memory operations may stay outstanding; LG: LDS operations must have
 // finished as well) with the side registers as operands.
 #define SP3D_SIDE8(a) "+v"(a[0][0]), "+v"(a[0][1]), "+v"(a[0][2]), "+v"(a[0][3]), "+v"(a[1][0]), "+v"(a[1][1]), \
                       "+v"(a[1][2]), "+v"(a[1][3])
-template <int NV, bool LG, bool PINS, bool MASK>
+#define SP3D_SIDE2(a) "+v"(a[0][0].x), "+v"(a[1][0].x)      // the bit form: one word per row, kept in [row][0].x
+template <int NV, bool LG, bool PINS, bool MASK, bool BITS>
 __device__ __forceinline__ void side_fence(pin_t (&p)[2][4], mask_t (&m)[2][4]) {
+    static_assert(!BITS || MASK, "the bit form is a form of the mask");
     if (LG) {
-        if (PINS && MASK) asm volatile("s_waitcnt vmcnt(%16) lgkmcnt(0)" : SP3D_SIDE8(p), SP3D_SIDE8(m) : "n"(NV) : "memory");
+        if (PINS && BITS) asm volatile("s_waitcnt vmcnt(%10) lgkmcnt(0)" : SP3D_SIDE8(p), SP3D_SIDE2(m) : "n"(NV) : "memory");
+        else if (PINS && MASK) asm volatile("s_waitcnt vmcnt(%16) lgkmcnt(0)" : SP3D_SIDE8(p), SP3D_SIDE8(m) : "n"(NV) : "memory");
         else if (PINS) asm volatile("s_waitcnt vmcnt(%8) lgkmcnt(0)" : SP3D_SIDE8(p) : "n"(NV) : "memory");
+        else if (BITS) asm volatile("s_waitcnt vmcnt(%2) lgkmcnt(0)" : SP3D_SIDE2(m) : "n"(NV) : "memory");
         else if (MASK) asm volatile("s_waitcnt vmcnt(%8) lgkmcnt(0)" : SP3D_SIDE8(m) : "n"(NV) : "memory");
         else asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(NV) : "memory");
     } else {
-        if (PINS && MASK) asm volatile("s_waitcnt vmcnt(%16)" : SP3D_SIDE8(p), SP3D_SIDE8(m) : "n"(NV) : "memory");
+        if (PINS && BITS) asm volatile("s_waitcnt vmcnt(%10)" : SP3D_SIDE8(p), SP3D_SIDE2(m) : "n"(NV) : "memory");
+        else if (PINS && MASK) asm volatile("s_waitcnt vmcnt(%16)" : SP3D_SIDE8(p), SP3D_SIDE8(m) : "n"(NV) : "memory");
         else if (PINS) asm volatile("s_waitcnt vmcnt(%8)" : SP3D_SIDE8(p) : "n"(NV) : "memory");
+        else if (BITS) asm volatile("s_waitcnt vmcnt(%2)" : SP3D_SIDE2(m) : "n"(NV) : "memory");
         else if (MASK) asm volatile("s_waitcnt vmcnt(%8)" : SP3D_SIDE8(m) : "n"(NV) : "memory");
         else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NV) : "memory");
     }
 }
 #undef SP3D_SIDE8
+#undef SP3D_SIDE2
 // What a kernel variant fetches per store unit besides its operands, and whether it does so by side loads.
 // Measured: the mask gains from them (3-D 32 -> 32 at 512^3: 7.45 -> 7.08 ms; 2-D: 8 - 9 %) except in the 3-D
 // two-chunk kernel, whose registers are all taken (4.07 -> 4.71 ms with them); the partial sums do not gain
 // (their cost was the access pattern, see part_unit), so they stay ordinary loads.
 template <int MODE, int RELU, int KD, bool PAIR> struct Side {
     static constexpr bool PINS = MODE == kMiddle || MODE == kLast;
-    static constexpr bool MASK = RELU == kMask && (MODE == kSingle || MODE == kLast);
-    static constexpr bool ASYNC = MASK && !PINS && (KD == 1 || !PAIR);
+    static constexpr bool MASK = (RELU == kMask || RELU == kMaskBits) && (MODE == kSingle || MODE == kLast);
+    static constexpr bool BITS = MASK && RELU == kMaskBits;      // one 16-bit word per row instead of 4 x 8 bytes
+    static constexpr bool ASYNC = MASK && !PINS && (KD == 1 || !PAIR || BITS);
 };
 // Role of a step in the chain of side loads.
 enum SideStep { kSideNone = 0,     // no side loads (nothing to fetch, or a ragged patch)
@@ -252,6 +274,23 @@ enum SideStep { kSideNone = 0,     // no side loads (nothing to fetch, or a ragg
 // holds [plane of the D chunk][row][unit][lane]; part_unit() is the float offset of a unit inside it.
 __device__ __forceinline__ size_t part_unit(int d, int h, int q) { return static_cast<size_t>((d * RH + h) * 4 + q) * 256; }
 
+// Offset, in 16-bit words of the one-bit mask, of row h of output plane d from a lane's base: one word per voxel,
+// channel block and half, against 16 elements in the tensor.
+template <class CtxT>
+__device__ __forceinline__ size_t bits_off(const CtxT &c, int d, int h) { return (d * c.oplane + h * c.orow) >> 4; }
+
+// The four bits of a finished store unit (two packed bf16 pairs): bit i set where value i is positive.
+__device__ __forceinline__ uint32_t positive_nibble(uint2 pk) {
+    return ((pk.x & 0xffffu) - 1u < 0x7f80u ? 1u : 0u) | ((pk.x >> 16) - 1u < 0x7f80u ? 2u : 0u) |
+           ((pk.y & 0xffffu) - 1u < 0x7f80u ? 4u : 0u) | ((pk.y >> 16) - 1u < 0x7f80u ? 8u : 0u);
+}
+// ... and the reverse: 0xffff in each half of the two words whose bit is set
+__device__ __forceinline__ uint2 nibble_halves(uint32_t word, int q) {
+    const uint32_t n = word >> (4 * q);
+    return make_uint2(((n & 1u) ? 0x0000ffffu : 0u) | ((n & 2u) ? 0xffff0000u : 0u),
+                      ((n & 4u) ? 0x0000ffffu : 0u) | ((n & 8u) ? 0xffff0000u : 0u));
+}
+
 // Per-wave state of the march that the side work of a step needs.
 template <bool HAS_BIAS>
 struct Ctx {
@@ -264,6 +303,7 @@ struct Ctx {
     char *lds_stage;            // LDS chunk plane this wave fills (ring slot 0)
     uint16_t *obase;            // output address of (plane 0, first row of the wave, this lane)
     const uint16_t *mbase;      // same position in the mask tensor
+    uint16_t *bbase;            // this lane's word of that voxel in the one-bit mask (see relu_bit)
     float *pbase;               // this lane's slot in the wave's region of the fp32 partial-sum buffer
     size_t oplane, orow;        // output elements per padded plane / per padded row
     bool okrow[RH];             // row/column of this lane lies inside the tile interior
@@ -293,9 +333,13 @@ __device__ __forceinline__ pin_t load_partial(const Ctx<HAS_BIAS> &c, int d, int
 }
 
 // The 4 mask values that belong to one store unit (fetched at the start of the step, like the partial sums).
-template <bool FULL, bool HAS_BIAS>
+template <bool FULL, bool BITS, bool HAS_BIAS>
 __device__ __forceinline__ mask_t load_mask(const Ctx<HAS_BIAS> &c, int d, int h, int q) {
     mask_t v = mask_t{0u, 0u};
+    if (BITS) {         // the row's word, kept in unit 0
+        if (q == 0 && (FULL || c.okrow[h])) v.x = c.bbase[bits_off(c, d, h)];
+        return v;
+    }
     if (FULL || c.okrow[h]) v = *reinterpret_cast<const mask_t *>(c.mbase + d * c.oplane + h * c.orow + 8 * q);
     return v;
 }
@@ -305,7 +349,7 @@ __device__ __forceinline__ mask_t load_mask(const Ctx<HAS_BIAS> &c, int d, int h
 // apply ReLU, convert and store bf16 (8 bytes).
 template <int MODE, int RELU, bool FULL, bool HAS_BIAS>
 __device__ __forceinline__ void store_unit(const Ctx<HAS_BIAS> &c, int d, const f32x16 (&s)[RH],
-                                           const pin_t (&pin)[RH][4], const mask_t (&mk)[RH][4], int h, int q) {
+                                           const pin_t (&pin)[RH][4], mask_t (&mk)[RH][4], int h, int q) {
     float v0 = s[h][4 * q], v1 = s[h][4 * q + 1], v2 = s[h][4 * q + 2], v3 = s[h][4 * q + 3];
     if (MODE == kMiddle || MODE == kLast) {
         v0 += pin[h][q].x; v1 += pin[h][q].y; v2 += pin[h][q].z; v3 += pin[h][q].w;
@@ -315,7 +359,7 @@ __device__ __forceinline__ void store_unit(const Ctx<HAS_BIAS> &c, int d, const 
         if (FULL || c.okrow[h]) *reinterpret_cast<float4 *>(c.pbase + part_unit(d, h, q)) = make_float4(v0, v1, v2, v3);
         return;
     }
-    if (RELU == kRelu) {
+    if (is_relu(RELU)) {
         v0 = v0 < 0.f ? 0.f : v0; v1 = v1 < 0.f ? 0.f : v1;
         v2 = v2 < 0.f ? 0.f : v2; v3 = v3 < 0.f ? 0.f : v3;
     }
@@ -324,7 +368,18 @@ __device__ __forceinline__ void store_unit(const Ctx<HAS_BIAS> &c, int d, const 
         pk.x &= positive_halves(mk[h][q].x);
         pk.y &= positive_halves(mk[h][q].y);
     }
+    if (RELU == kMaskBits) {
+        const uint2 m = nibble_halves(mk[h][0].x, q);
+        pk.x &= m.x;
+        pk.y &= m.y;
+    }
     if (FULL || c.okrow[h]) *reinterpret_cast<uint2 *>(c.obase + at) = pk;
+    if (RELU == kReluBits) {
+        // the row's word collects in the (otherwise unused) mask register of unit 0 and leaves with the last unit
+        const uint32_t n = positive_nibble(pk) << (4 * q);
+        mk[h][0].x = q == 0 ? n : (mk[h][0].x | n);
+        if (q == 3 && (FULL || c.okrow[h])) c.bbase[bits_off(c, d, h)] = static_cast<uint16_t>(mk[h][0].x);
+    }
 }
 
 // All MFMAs of one staged input plane Dp, with the step's side work spread over the six MFMA groups:
@@ -355,7 +410,8 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, int l
             for (int q = 0; q < 4; ++q) {
                 const size_t at = (Dp - 2) * c.oplane + h * c.orow + 8 * q;
                 if (S::PINS) side_load(npin[h][q], c.pbase + part_unit(Dp - 2, h, q));
-                if (S::MASK) side_load(nmk[h][q], c.mbase + at);
+                if (S::MASK && !S::BITS) side_load(nmk[h][q], c.mbase + at);
+                if (S::BITS && q == 0) SP3D_SIDE_LOAD_BITS(nmk[h][0].x, c.bbase + bits_off(c, Dp - 2, h));
             }
     }
     if (SIDE == kSideNone && EPI && S::PINS) {
@@ -368,7 +424,7 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, int l
 #pragma unroll
         for (int h = 0; h < RH; ++h)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) mk[h][q] = load_mask<FULL>(c, Dp - 3, h, q);
+            for (int q = 0; q < 4; ++q) mk[h][q] = load_mask<FULL, S::BITS>(c, Dp - 3, h, q);
     }
 #pragma unroll
     for (int r = 0; r < NR; ++r)
@@ -491,12 +547,13 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
     const FoldCol oc = fold_col(col, F, a.fold_w);
     c.orow = static_cast<size_t>(g.pw) * od.cs;
     c.oplane = static_cast<size_t>(g.ph) * c.orow * F;
-    const size_t opos = (static_cast<size_t>(tile) * g.tile_vox + bx.org) * od.cs +
-                        ((static_cast<size_t>(d0 + 1 + min(oc.s, F - 1)) * g.ph + h0 + wave * RH + 1) * g.pw + w0 +
-                         oc.c + 1) * od.cs +
-                        od.co + 4 * hi;
+    const size_t ovox = static_cast<size_t>(tile) * g.tile_vox + bx.org +
+                        (static_cast<size_t>(d0 + 1 + min(oc.s, F - 1)) * g.ph + h0 + wave * RH + 1) * g.pw + w0 +
+                        oc.c + 1;
+    const size_t opos = ovox * od.cs + od.co + 4 * hi;
     c.obase = od.base + opos;
     c.mbase = a.mask + opos;
+    c.bbase = a.bits + (ovox * a.nco + cj) * 2 + hi;
     // wave `wave` of workgroup `logical`: a region of dchunk planes x RH rows x 4 units x 1 KB
     c.pbase = a.part + (static_cast<size_t>(logical) * kWaves + wave) * a.dchunk * (RH * 4 * 256) + lane * 4;
 #pragma unroll
@@ -550,7 +607,7 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
         // fetch-only step issues just its LOADS staging loads after them and waits accordingly)
 #define SP3D_STEP_END_SIDE(NV, NP, NM)                                                   \
     do {                                                                                 \
-        side_fence<NV, false, ASYNC && S::PINS, ASYNC && S::MASK>(NP, NM);               \
+        side_fence<NV, false, ASYNC && S::PINS, ASYNC && S::MASK, ASYNC && S::BITS>(NP, NM); \
         __builtin_amdgcn_s_barrier();                                                    \
     } while (0)
         static_assert(LOADS + 8 >= (DIST - 1) * LOADS, "side loads must be older than what the step-end wait lets stay in flight");
@@ -593,7 +650,7 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
 #pragma unroll
             for (int h = 0; h < RH; ++h)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) mkA[h][q] = mkB[h][q] = load_mask<FULL>(c, dn - 1, h, q);
+                for (int q = 0; q < 4; ++q) mkA[h][q] = mkB[h][q] = load_mask<FULL, S::BITS>(c, dn - 1, h, q);
         }
 #pragma unroll
         for (int s = 0; s < 4; ++s)
@@ -660,6 +717,7 @@ struct Ctx {
     char *red;                  // hand-over buffer of this wave's row group (buffer 0), lane part included
     uint16_t *obase;
     const uint16_t *mbase;
+    uint16_t *bbase;
     float *pbase;
     size_t oplane, orow;
     bool okrow[RH];
@@ -685,9 +743,13 @@ __device__ __forceinline__ pin_t load_partial(const Ctx<HAS_BIAS> &c, int d, int
     return v;
 }
 
-template <bool FULL, bool HAS_BIAS>
+template <bool FULL, bool BITS, bool HAS_BIAS>
 __device__ __forceinline__ mask_t load_mask(const Ctx<HAS_BIAS> &c, int d, int h, int q) {
     mask_t v = mask_t{0u, 0u};
+    if (BITS) {         // the row's word, kept in unit 0
+        if (q == 0 && (FULL || c.okrow[h])) v.x = c.bbase[bits_off(c, d, h)];
+        return v;
+    }
     if (FULL || c.okrow[h]) v = *reinterpret_cast<const mask_t *>(c.mbase + d * c.oplane + h * c.orow + 8 * q);
     return v;
 }
@@ -697,7 +759,7 @@ __device__ __forceinline__ mask_t load_mask(const Ctx<HAS_BIAS> &c, int d, int h
 // convert / store bf16
 template <int MODE, int RELU, bool FULL, bool HAS_BIAS>
 __device__ __forceinline__ void finish_unit(const Ctx<HAS_BIAS> &c, int d, const f32x16 (&s)[RH], const char *red,
-                                            const pin_t (&pin)[RH][4], const mask_t (&mk)[RH][4], int h, int q) {
+                                            const pin_t (&pin)[RH][4], mask_t (&mk)[RH][4], int h, int q) {
     const float4 o = *reinterpret_cast<const float4 *>(red + (h * 4 + q) * 1024);
     float v0 = s[h][4 * q] + o.x, v1 = s[h][4 * q + 1] + o.y, v2 = s[h][4 * q + 2] + o.z, v3 = s[h][4 * q + 3] + o.w;
     if (MODE == kMiddle || MODE == kLast) {
@@ -708,7 +770,7 @@ __device__ __forceinline__ void finish_unit(const Ctx<HAS_BIAS> &c, int d, const
         if (FULL || c.okrow[h]) *reinterpret_cast<float4 *>(c.pbase + part_unit(d, h, q)) = make_float4(v0, v1, v2, v3);
         return;
     }
-    if (RELU == kRelu) {
+    if (is_relu(RELU)) {
         v0 = v0 < 0.f ? 0.f : v0; v1 = v1 < 0.f ? 0.f : v1;
         v2 = v2 < 0.f ? 0.f : v2; v3 = v3 < 0.f ? 0.f : v3;
     }
@@ -717,7 +779,18 @@ __device__ __forceinline__ void finish_unit(const Ctx<HAS_BIAS> &c, int d, const
         pk.x &= positive_halves(mk[h][q].x);
         pk.y &= positive_halves(mk[h][q].y);
     }
+    if (RELU == kMaskBits) {
+        const uint2 m = nibble_halves(mk[h][0].x, q);
+        pk.x &= m.x;
+        pk.y &= m.y;
+    }
     if (FULL || c.okrow[h]) *reinterpret_cast<uint2 *>(c.obase + at) = pk;
+    if (RELU == kReluBits) {
+        // the row's word collects in the (otherwise unused) mask register of unit 0 and leaves with the last unit
+        const uint32_t n = positive_nibble(pk) << (4 * q);
+        mk[h][0].x = q == 0 ? n : (mk[h][0].x | n);
+        if (q == 3 && (FULL || c.okrow[h])) c.bbase[bits_off(c, d, h)] = static_cast<uint16_t>(mk[h][0].x);
+    }
 }
 
 // chunk-1 wave: hand 4 channels of row h of a complete plane over to the chunk-0 wave
@@ -754,7 +827,8 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const
             for (int q = 0; q < 4; ++q) {
                 const size_t at = (Dp - 3) * c.oplane + h * c.orow + 8 * q;
                 if (S::PINS) side_load(npin[h][q], c.pbase + part_unit(Dp - 3, h, q));
-                if (S::MASK) side_load(nmk[h][q], c.mbase + at);
+                if (S::MASK && !S::BITS) side_load(nmk[h][q], c.mbase + at);
+                if (S::BITS && q == 0) SP3D_SIDE_LOAD_BITS(nmk[h][0].x, c.bbase + bits_off(c, Dp - 3, h));
             }
     }
     if (SIDE == kSideNone && ROLE == 0 && FIN && S::PINS) {
@@ -767,7 +841,7 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const
 #pragma unroll
         for (int h = 0; h < RH; ++h)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) mk[h][q] = load_mask<FULL>(c, Dp - 4, h, q);
+            for (int q = 0; q < 4; ++q) mk[h][q] = load_mask<FULL, S::BITS>(c, Dp - 4, h, q);
     }
 #pragma unroll
     for (int r = 0; r < NR; ++r) b[0][r] = *reinterpret_cast<const bf16x8 *>(lbase + (r * LCOLS) * 16);
@@ -845,7 +919,8 @@ __device__ __forceinline__ void drain_step(const Ctx<HAS_BIAS> &c, int Dp, f32x1
             for (int q = 0; q < 4; ++q) {
                 const size_t at = (Dp - 3) * c.oplane + h * c.orow + 8 * q;
                 if (S::PINS) side_load(npin[h][q], c.pbase + part_unit(Dp - 3, h, q));
-                if (S::MASK) side_load(nmk[h][q], c.mbase + at);
+                if (S::MASK && !S::BITS) side_load(nmk[h][q], c.mbase + at);
+                if (S::BITS && q == 0) SP3D_SIDE_LOAD_BITS(nmk[h][0].x, c.bbase + bits_off(c, Dp - 3, h));
             }
     }
     if (ROLE == 1) {
@@ -869,7 +944,7 @@ __device__ __forceinline__ void drain_step(const Ctx<HAS_BIAS> &c, int Dp, f32x1
 #pragma unroll
             for (int h = 0; h < RH; ++h)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) mk[h][q] = load_mask<FULL>(c, Dp - 4, h, q);
+                for (int q = 0; q < 4; ++q) mk[h][q] = load_mask<FULL, S::BITS>(c, Dp - 4, h, q);
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -936,12 +1011,13 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int logical, i
     const FoldCol oc = fold_col(col, F, a.fold_w);
     c.orow = static_cast<size_t>(g.pw) * od.cs;
     c.oplane = static_cast<size_t>(g.ph) * c.orow * F;
-    const size_t opos = (static_cast<size_t>(tile) * g.tile_vox + bx.org) * od.cs +
-                        ((static_cast<size_t>(d0 + 1 + min(oc.s, F - 1)) * g.ph + h0 + rg * RH + 1) * g.pw + w0 +
-                         oc.c + 1) * od.cs +
-                        od.co + 4 * hi;
+    const size_t ovox = static_cast<size_t>(tile) * g.tile_vox + bx.org +
+                        (static_cast<size_t>(d0 + 1 + min(oc.s, F - 1)) * g.ph + h0 + rg * RH + 1) * g.pw + w0 +
+                        oc.c + 1;
+    const size_t opos = ovox * od.cs + od.co + 4 * hi;
     c.obase = od.base + opos;
     c.mbase = a.mask + opos;
+    c.bbase = a.bits + (ovox * a.nco + cj) * 2 + hi;
     // the chunk-0 wave of row group rg of workgroup `logical`: dchunk planes x RH rows x 4 units x 1 KB
     c.pbase = a.part + (static_cast<size_t>(logical) * NRG + rg) * a.dchunk * (RH * 4 * 256) + lane * 4;
 #pragma unroll
@@ -993,7 +1069,7 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int logical, i
         static_assert(LOADS + 8 >= (DIST - 1) * LOADS, "side loads must be older than what the step-end wait lets stay in flight");
 #define SP3D_STEP_END_SIDE(NV, NP, NM)                                              \
     do {                                                                            \
-        side_fence<NV, true, ASYNC && S::PINS, ASYNC && S::MASK>(NP, NM);           \
+        side_fence<NV, true, ASYNC && S::PINS, ASYNC && S::MASK, ASYNC && S::BITS>(NP, NM); \
         __builtin_amdgcn_s_barrier();                                               \
     } while (0)
         plane_step<0, ROLE, false, false, MODE, RELU, FULL, KD, kSideNone>(c, 0, lbase, wf, acc, pinA, mkA, pinB, mkB);
@@ -1136,10 +1212,18 @@ bool conv_mfma_gather_supported(const Geo &g, int ki, int ko, sp_dtype_t dt) {
     return static_cast<long long>(g.tile_vox) * (g.gw + 1) * (ki > ko ? ki : ko) < 0x7fffffffLL;
 }
 
+bool conv_mfma_bits_supported(const Geo &g, int ki, int ko, sp_dtype_t dt) {
+    // the 3-D marching kernels (the wide-layer GEMM form and the 2-D variant keep the mask tensor)
+    return conv_mfma_supported(g, ki, ko, dt) && !g.flat && !conv_gemm_preferred(g, ki, ko);
+}
+
 int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Pout, const Geo &g,
                      int ki, int ko, bool relu, bool dgrad, void *ws, hipStream_t s, const void *mask,
-                     const ConvSplit *split, bool gather) {
+                     const ConvSplit *split, bool gather, void *bits) {
     if (gather && !conv_mfma_gather_supported(g, ki, ko, SP_BF16)) return SP_EUNSUPPORTED;
+    // one-bit mask: read by the data gradient in place of a mask tensor, written by a forward pass with ReLU
+    if (bits && (!conv_mfma_bits_supported(g, ki, ko, SP_BF16) || (split && split->out2) || mask || (!dgrad && !relu)))
+        return SP_EUNSUPPORTED;
     const int nci = ki / C, nco = ko / C;
     const int pack_elems = nci * nco * NFRAG * 64 * 8;
     hipLaunchKernelGGL(pack_weights_kernel, dim3((pack_elems + 255) / 256), dim3(256), 0, s,
@@ -1170,6 +1254,7 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
     // channels per voxel of the first output tensor (the whole output if there is no second one)
     const int out_cs_a = a.out2 ? a.out_ca : ko;
     a.mask = static_cast<const uint16_t *>(mask);
+    a.bits = static_cast<uint16_t *>(bits);
     a.part = reinterpret_cast<float *>(static_cast<char *>(ws) + pack_bytes(ki, ko));
     a.g = g;
     a.out_cs = out_cs_a;
@@ -1195,29 +1280,39 @@ int launch_conv_mfma(const void *Pin, const void *w, const float *bias, void *Po
     const unsigned grid = static_cast<unsigned>((nb + 7) / 8 * 8);
     using Kern = void (*)(ConvArgs);
     // [mode][bias][epilogue]; combinations that cannot occur (bias after the first launch, ReLU or mask before
-    // the last, bias together with a mask) reuse the plain variant
-#define SP3D_TABLE(K, KD)                                                                                  \
-    {{{K<kSingle, false, kNone, KD>, K<kSingle, false, kRelu, KD>, K<kSingle, false, kMask, KD>},            \
-      {K<kSingle, true, kNone, KD>, K<kSingle, true, kRelu, KD>, K<kSingle, false, kMask, KD>}},             \
-     {{K<kFirst, false, kNone, KD>, K<kFirst, false, kNone, KD>, K<kFirst, false, kNone, KD>},               \
-      {K<kFirst, true, kNone, KD>, K<kFirst, true, kNone, KD>, K<kFirst, true, kNone, KD>}},                 \
-     {{K<kMiddle, false, kNone, KD>, K<kMiddle, false, kNone, KD>, K<kMiddle, false, kNone, KD>},            \
-      {K<kMiddle, false, kNone, KD>, K<kMiddle, false, kNone, KD>, K<kMiddle, false, kNone, KD>}},           \
-     {{K<kLast, false, kNone, KD>, K<kLast, false, kRelu, KD>, K<kLast, false, kMask, KD>},                  \
-      {K<kLast, false, kNone, KD>, K<kLast, false, kRelu, KD>, K<kLast, false, kMask, KD>}}}
-    // [2-D variant][mode][bias][epilogue]
-    static const Kern kern[2][4][2][3] = {SP3D_TABLE(conv_mfma_kernel, 3), SP3D_TABLE(conv_mfma_kernel, 1)};
-    static const Kern kern2[2][4][2][3] = {SP3D_TABLE(wide::conv_mfma_pair_kernel, 3),
-                                           SP3D_TABLE(wide::conv_mfma_pair_kernel, 1)};
+    // the last, bias together with a mask) reuse the plain variant.  MB, RB: the two bit forms.
+#define SP3D_TABLE(K, KD, MB, RB)                                                                          \
+    {{{K<kSingle, false, kNone, KD>, K<kSingle, false, kRelu, KD>, K<kSingle, false, kMask, KD>,             \
+       K<kSingle, false, MB, KD>, K<kSingle, false, RB, KD>},                                                \
+      {K<kSingle, true, kNone, KD>, K<kSingle, true, kRelu, KD>, K<kSingle, false, kMask, KD>,               \
+       K<kSingle, false, MB, KD>, K<kSingle, true, RB, KD>}},                                                \
+     {{K<kFirst, false, kNone, KD>, K<kFirst, false, kNone, KD>, K<kFirst, false, kNone, KD>,                \
+       K<kFirst, false, kNone, KD>, K<kFirst, false, kNone, KD>},                                            \
+      {K<kFirst, true, kNone, KD>, K<kFirst, true, kNone, KD>, K<kFirst, true, kNone, KD>,                   \
+       K<kFirst, true, kNone, KD>, K<kFirst, true, kNone, KD>}},                                             \
+     {{K<kMiddle, false, kNone, KD>, K<kMiddle, false, kNone, KD>, K<kMiddle, false, kNone, KD>,             \
+       K<kMiddle, false, kNone, KD>, K<kMiddle, false, kNone, KD>},                                          \
+      {K<kMiddle, false, kNone, KD>, K<kMiddle, false, kNone, KD>, K<kMiddle, false, kNone, KD>,             \
+       K<kMiddle, false, kNone, KD>, K<kMiddle, false, kNone, KD>}},                                         \
+     {{K<kLast, false, kNone, KD>, K<kLast, false, kRelu, KD>, K<kLast, false, kMask, KD>,                   \
+       K<kLast, false, MB, KD>, K<kLast, false, RB, KD>},                                                    \
+      {K<kLast, false, kNone, KD>, K<kLast, false, kRelu, KD>, K<kLast, false, kMask, KD>,                   \
+       K<kLast, false, MB, KD>, K<kLast, false, RB, KD>}}}
+    // [2-D variant][mode][bias][epilogue]; the bit forms exist for the 3-D kernels only (the host refuses them
+    // for 2-D geometries; their table entries repeat the plain kernel)
+    static const Kern kern[2][4][2][5] = {SP3D_TABLE(conv_mfma_kernel, 3, kMaskBits, kReluBits),
+                                          SP3D_TABLE(conv_mfma_kernel, 1, kNone, kNone)};
+    static const Kern kern2[2][4][2][5] = {SP3D_TABLE(wide::conv_mfma_pair_kernel, 3, kMaskBits, kReluBits),
+                                           SP3D_TABLE(wide::conv_mfma_pair_kernel, 1, kNone, kNone)};
 #undef SP3D_TABLE
-    const int epi = mask ? kMask : (relu ? kRelu : kNone);
+    const int epi = bits ? (dgrad ? kMaskBits : kReluBits) : (mask ? kMask : (relu ? kRelu : kNone));
     // more than 64 KB of dynamic LDS has to be requested explicitly
     static const hipError_t attr = [] {
-        for (int i = 0; i < 48; ++i) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern[i / 24][(i / 6) & 3][(i / 3) & 1][i % 3]),
+        for (int i = 0; i < 80; ++i) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern[i / 40][(i / 10) & 3][(i / 5) & 1][i % 5]),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
             if (e != hipSuccess) return e;
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern2[i / 24][(i / 6) & 3][(i / 3) & 1][i % 3]),
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern2[i / 40][(i / 10) & 3][(i / 5) & 1][i % 5]),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, wide::LDS_BYTES);
             if (e != hipSuccess) return e;
         }

@@ -397,6 +397,40 @@ int launch_halo_exchange(void *P, const Geo &g, int c, sp_dtype_t dt, int border
     return halo_launch(P, P, g, c, dt, kExchange, border, s);
 }
 
+// One-bit ReLU mask of a bf16 tensor.  Four lanes share a record of 32 channels (16 bytes each, so a wave reads
+// a contiguous kilobyte); lane q holds channels 8 q .. 8 q + 7, of which the first four go to bits 4 q .. 4 q + 3
+// of the record's low 16-bit word and the last four to the same bits of the high one (the order in which the
+// matrix-core kernels produce and consume the bits).  The four contributions are OR-ed across the lanes.
+__global__ __launch_bounds__(kThreads) void relu_bits_kernel(const u32x4 *__restrict__ y, uint32_t *__restrict__ bits,
+                                                             size_t blocks) {
+    const size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
+    const size_t rec = i >> 2;
+    const int q = static_cast<int>(i & 3);
+    uint32_t word = 0;
+    if (rec < blocks) {
+        const u32x4 v = y[i];
+        uint32_t n = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            n |= positive<uint16_t>(static_cast<uint16_t>(v[k] & 0xffffu)) ? 1u << (2 * k) : 0u;
+            n |= positive<uint16_t>(static_cast<uint16_t>(v[k] >> 16)) ? 2u << (2 * k) : 0u;
+        }
+        word = ((n & 0xfu) << (4 * q)) | ((n >> 4) << (16 + 4 * q));
+    }
+    word |= __shfl_xor(word, 1);
+    word |= __shfl_xor(word, 2);
+    if (q == 0 && rec < blocks) bits[rec] = word;
+}
+
+int launch_relu_bits(const void *y, void *bits, size_t blocks, hipStream_t s) {
+    if (blocks == 0) return SP_OK;
+    const size_t nblk = (blocks * 4 + kThreads - 1) / kThreads;
+    if (nblk > 0x7fffffffULL) return SP_EGEOM;
+    hipLaunchKernelGGL(relu_bits_kernel, dim3(static_cast<unsigned>(nblk)), dim3(kThreads), 0, s,
+                       static_cast<const u32x4 *>(y), static_cast<uint32_t *>(bits), blocks);
+    return record_hip(hipGetLastError());
+}
+
 int launch_relu_bwd(const void *dy, const void *y, void *dz, size_t elems, sp_dtype_t dt,
                     hipStream_t s) {
     if (elems == 0) return SP_OK;

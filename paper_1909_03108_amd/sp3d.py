@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsp3d.so"
 EXPORTS = ["sp_padded_elems", "sp_msg_elems", "sp_workspace_bytes", "sp_check_geom", "sp_gather_supported", "sp_strerror",
            "sp_last_hip_error", "sp_partition", "sp_unpartition", "halo_pack", "halo_unpack",
            "sp_halo_exchange",
-           "conv3d_fwd", "conv3d_dgrad", "conv3d_dgrad_relu", "conv3d_wgrad", "conv3d_wgrad_static", "conv3d_fwd2", "conv3d_dgrad2",
+           "conv3d_fwd", "conv3d_dgrad", "conv3d_dgrad_relu", "sp_relu_bits_bytes", "sp_relu_bits_supported", "sp_relu_bits",
+           "conv3d_fwd_bits", "conv3d_fwd2_bits", "conv3d_dgrad_bits", "conv3d_wgrad", "conv3d_wgrad_static", "conv3d_fwd2", "conv3d_dgrad2",
            "conv3d_wgrad2", "sp_relu_bwd",
            "sp_maxpool2_fwd", "sp_maxpool2_bwd", "sp_maxpool2_bwd_join", "sp_upconv2_fwd", "sp_upconv2_dgrad", "sp_upconv2_wgrad",
            "sp_pointwise_fwd", "sp_pointwise_dgrad", "sp_pointwise_dgrad_relu", "sp_pointwise_wgrad", "sp_concat", "sp_split", "sp_add",
@@ -88,6 +89,12 @@ def lib():
         L.conv3d_fwd.argtypes, L.conv3d_fwd.restype = [P, P, P, P, G, I, I, I, U, P, Z, P], I
         L.conv3d_dgrad.argtypes, L.conv3d_dgrad.restype = [P, P, P, G, I, I, I, P, Z, P], I
         L.conv3d_dgrad_relu.argtypes, L.conv3d_dgrad_relu.restype = [P, P, P, P, G, I, I, I, P, Z, P], I
+        L.sp_relu_bits_bytes.argtypes, L.sp_relu_bits_bytes.restype = [G, I], Z
+        L.sp_relu_bits_supported.argtypes, L.sp_relu_bits_supported.restype = [I, G, I, I, I], I
+        L.sp_relu_bits.argtypes, L.sp_relu_bits.restype = [P, P, G, I, I, P], I
+        L.conv3d_fwd_bits.argtypes, L.conv3d_fwd_bits.restype = [P, P, P, P, P, G, I, I, I, U, P, Z, P], I
+        L.conv3d_fwd2_bits.argtypes, L.conv3d_fwd2_bits.restype = [P, I, P, I, P, P, P, P, G, I, I, U, P, Z, P], I
+        L.conv3d_dgrad_bits.argtypes, L.conv3d_dgrad_bits.restype = [P, P, P, P, G, I, I, I, P, Z, P], I
         L.conv3d_wgrad.argtypes, L.conv3d_wgrad.restype = [P, P, P, P, G, I, I, I, P, Z, P], I
         L.conv3d_wgrad_static.argtypes, L.conv3d_wgrad_static.restype = [P, P, P, P, G, I, I, I, P], I
         L.conv3d_fwd2.argtypes, L.conv3d_fwd2.restype = [P, I, P, I, P, P, P, G, I, I, U, P, Z, P], I
@@ -199,6 +206,36 @@ def conv3d_dgrad_relu(Pdz, w, Px, Pdx, g, cin, cout, dt, ws=None, stream=None):
     wp, wb = _ws(ws)
     _check(lib().conv3d_dgrad_relu(_ptr(Pdz), _ptr(w), _ptr(Px), _ptr(Pdx), ctypes.byref(g), cin, cout, dt, wp, wb,
                                    _stream(stream)), "conv3d_dgrad_relu")
+
+
+def sp_relu_bits_bytes(g, c):
+    return lib().sp_relu_bits_bytes(ctypes.byref(g), c)
+
+
+def sp_relu_bits_supported(op, g, cin, cout, dt):
+    return bool(lib().sp_relu_bits_supported(op, ctypes.byref(g), cin, cout, dt))
+
+
+def sp_relu_bits(Py, bits, g, c, dt, stream=None):
+    _check(lib().sp_relu_bits(_ptr(Py), _ptr(bits), ctypes.byref(g), c, dt, _stream(stream)), "sp_relu_bits")
+
+
+def conv3d_fwd_bits(Px, w, bias, Py, bits, g, cin, cout, dt, flags=0, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib().conv3d_fwd_bits(_ptr(Px), _ptr(w), _ptr(bias), _ptr(Py), _ptr(bits), ctypes.byref(g), cin, cout, dt,
+                                 flags, wp, wb, _stream(stream)), "conv3d_fwd_bits")
+
+
+def conv3d_fwd2_bits(Pxa, ca, Pxb, cb, w, bias, Py, bits, g, cout, dt, flags=0, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib().conv3d_fwd2_bits(_ptr(Pxa), ca, _ptr(Pxb), cb, _ptr(w), _ptr(bias), _ptr(Py), _ptr(bits),
+                                  ctypes.byref(g), cout, dt, flags, wp, wb, _stream(stream)), "conv3d_fwd2_bits")
+
+
+def conv3d_dgrad_bits(Pdz, w, bits, Pdx, g, cin, cout, dt, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib().conv3d_dgrad_bits(_ptr(Pdz), _ptr(w), _ptr(bits), _ptr(Pdx), ctypes.byref(g), cin, cout, dt, wp, wb,
+                                   _stream(stream)), "conv3d_dgrad_bits")
 
 
 def conv3d_fwd2(Pxa, ca, Pxb, cb, w, bias, Py, g, cout, dt, flags=0, ws=None, stream=None):

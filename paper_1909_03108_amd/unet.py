@@ -50,7 +50,7 @@ def layer_plan(channels=(32, 64, 128, 256), in_ch=1, classes=3, convs=2, flat=Fa
 
 class UNet:
     def __init__(self, n, dhw, grid, weights, channels=(32, 64, 128, 256), in_ch=1, classes=3,
-                 dt=sp3d.SP_BF16, convs=2, halo=1, flat=False, gather=False, grids=None):
+                 dt=sp3d.SP_BF16, convs=2, halo=1, flat=False, gather=False, grids=None, bits=False):
         self.channels, self.in_ch, self.classes, self.dt = tuple(channels), in_ch, classes, dt
         self.convs = convs
         # Runs of more than two layers would need ReLU masks further around the tiles in the backward pass than
@@ -61,6 +61,9 @@ class UNet:
         # gather: layers whose kernels can do it read their margins from the neighbour tiles' interiors
         # (SP_HALO_GATHER) instead of having them exchanged first; the others exchange as before
         self.gather = bool(gather) and halo == 1
+        # bits: a layer whose output is the next layer's input also writes the one-bit form of its ReLU mask,
+        # and that layer's data gradient reads the bits instead of the activation (where both kernels can)
+        self.bits = bool(bits) and halo == 1
         self.free = {}                        # (padded shape, channels) -> released gradient buffers
         self.L = len(channels)
         self.flat = bool(flat)
@@ -141,15 +144,32 @@ class UNet:
         allocated and nothing writes beyond the border afterwards, so they hold their zero padding already."""
         sp3d.sp_halo_exchange(P, g.with_opts(sp3d.SP_HALO_KEEP_ZERO), c, self.dt)
 
-    def _conv(self, Px, name, g, cin, cout, grow=0):
+    def _mask_bits(self, name, g, cin, cout, last):
+        """Buffer for the one-bit ReLU mask of layer `name`'s output, or None if the mask stays a tensor: the
+        layer must feed another layer of its block, and both its forward kernel and that layer's data gradient
+        (cout -> cout channels) must take the bit form."""
+        if (not self.bits or last or not sp3d.sp_relu_bits_supported(sp3d.SP_OP_FWD, g, cin, cout, self.dt)
+                or not sp3d.sp_relu_bits_supported(sp3d.SP_OP_DGRAD, g, cout, cout, self.dt)):
+            return None
+        key = (name + ".bits", g.padded_shape, cout)
+        t = self.pool.get(key)
+        if t is None:
+            t = self.pool[key] = torch.empty(sp3d.sp_relu_bits_bytes(g, cout) // 2, dtype=torch.int16, device="cuda")
+        return t
+
+    def _conv(self, Px, name, g, cin, cout, grow=0, bits=None):
         """Px must hold its halos.  Returns relu(conv(Px)) as padded tiles (written: the interiors and `grow`
-        voxels around them)."""
+        voxels around them); with `bits` the one-bit mask of the result goes there as well."""
         Py = self._buf(name + ".y", g, cout)
         gg = g.grown(grow) if grow else g
         if self._x_gathered(g, cin, cout):
             gg = g.with_opts(sp3d.SP_HALO_GATHER)
-        sp3d.conv3d_fwd(Px, self.w[name], None, Py, gg, cin, cout, self.dt, sp3d.SP_FLAG_RELU,
-                        self._ws(sp3d.SP_OP_FWD, gg, cin, cout))
+        if bits is not None:
+            sp3d.conv3d_fwd_bits(Px, self.w[name], None, Py, bits, gg, cin, cout, self.dt, sp3d.SP_FLAG_RELU,
+                                 self._ws(sp3d.SP_OP_FWD, gg, cin, cout))
+        else:
+            sp3d.conv3d_fwd(Px, self.w[name], None, Py, gg, cin, cout, self.dt, sp3d.SP_FLAG_RELU,
+                            self._ws(sp3d.SP_OP_FWD, gg, cin, cout))
         return Py
 
     def _block_fwd(self, block, P, g, cin, c, A, P2=None):
@@ -159,6 +179,9 @@ class UNet:
         for k in range(self.convs):
             name = "%s_%s" % (block, LETTERS[k])
             exch, grow = plan[k][0], plan[k][1]
+            mb = self._mask_bits(name, g, cin if k == 0 else c, c, k == self.convs - 1)
+            if mb is not None:
+                A["%s_%s.xbits" % (block, LETTERS[k + 1])] = mb
             if k == 0 and P2 is not None:
                 ca = cin // 2
                 gg = g.grown(grow) if grow else g
@@ -169,14 +192,18 @@ class UNet:
                     self._exchange(P2, g, ca)
                 A[name + ".x"] = (P, P2)
                 Py = self._buf(name + ".y", g, c)
-                sp3d.conv3d_fwd2(P, ca, P2, ca, self.w[name], None, Py, gg, c, self.dt, sp3d.SP_FLAG_RELU,
-                                 self._ws(sp3d.SP_OP_FWD, gg, cin, c))
+                if mb is not None:
+                    sp3d.conv3d_fwd2_bits(P, ca, P2, ca, self.w[name], None, Py, mb, gg, c, self.dt, sp3d.SP_FLAG_RELU,
+                                          self._ws(sp3d.SP_OP_FWD, gg, cin, c))
+                else:
+                    sp3d.conv3d_fwd2(P, ca, P2, ca, self.w[name], None, Py, gg, c, self.dt, sp3d.SP_FLAG_RELU,
+                                     self._ws(sp3d.SP_OP_FWD, gg, cin, c))
                 P = Py
                 continue
             if exch and not self._x_gathered(g, cin if k == 0 else c, c):
                 self._exchange(P, g, cin if k == 0 else c)
             A[name + ".x"] = P
-            P = self._conv(P, name, g, cin if k == 0 else c, c, grow)
+            P = self._conv(P, name, g, cin if k == 0 else c, c, grow, mb)
         A[block + ".y"] = P
         return P
 
@@ -306,7 +333,11 @@ class UNet:
             elif exchange:
                 self._exchange(Pdy, g, cout)
             Pdx = self._tmp(g, cin)
-            if mask_next:
+            xbits = self.A.get(name + ".xbits") if mask_next else None
+            if xbits is not None:
+                sp3d.conv3d_dgrad_bits(Pdy, self.w[name], xbits, Pdx, gg, cin, cout, dt,
+                                       self._ws(sp3d.SP_OP_DGRAD, gg, cin, cout))
+            elif mask_next:
                 sp3d.conv3d_dgrad_relu(Pdy, self.w[name], Px, Pdx, gg, cin, cout, dt,
                                        self._ws(sp3d.SP_OP_DGRAD, gg, cin, cout))
             else:

@@ -268,3 +268,38 @@ def test_halo_options_and_the_one_tile_grid():
     assert L.conv3d_fwd(FAKE, FAKE * 2, None, FAKE * 16, ctypes.byref(gg), 1, 32, bf, 0, FAKE * 32, 1 << 20, None) == sp3d.SP_EUNSUPPORTED
     assert L.conv3d_wgrad(FAKE, FAKE * 2, FAKE * 4, None, ctypes.byref(sp3d.Geom(1, (12, 20, 72), (2, 2, 1), opts=4)),
                           32, 32, bf, FAKE * 32, 1 << 30, None) == sp3d.SP_EUNSUPPORTED
+
+
+@pytest.mark.timeout(30)
+def test_one_bit_relu_mask_arguments():
+    """The bit form of the ReLU mask: size helper, the query, and every argument error of the calls that write or
+    read it (all raised before any launch)."""
+    L = sp3d.lib()
+    bf = sp3d.SP_BF16
+    g = sp3d.Geom(1, (8, 16, 64), (2, 2, 1))
+    gp = ctypes.byref(g)
+    assert sp3d.sp_relu_bits_bytes(g, 64) == sp3d.sp_padded_elems(g, 64) // 8
+    assert sp3d.sp_relu_bits_bytes(g, 48) == 0 and sp3d.sp_relu_bits_bytes(g, 0) == 0
+    assert sp3d.sp_relu_bits_supported(sp3d.SP_OP_FWD, g, 32, 64, bf)
+    assert sp3d.sp_relu_bits_supported(sp3d.SP_OP_DGRAD, g, 32, 64, bf)
+    assert sp3d.sp_relu_bits_supported(sp3d.SP_OP_FWD, g, 1, 32, bf)                   # the first layer's kernel
+    assert not sp3d.sp_relu_bits_supported(sp3d.SP_OP_DGRAD, g, 1, 32, bf)
+    assert not sp3d.sp_relu_bits_supported(sp3d.SP_OP_FWD, g, 32, 32, sp3d.SP_F32)
+    assert not sp3d.sp_relu_bits_supported(sp3d.SP_OP_FWD, sp3d.Geom(1, (8, 16, 64), (2, 2, 1), flat=1), 32, 32, bf)
+    A, B, C, D = FAKE * 64, FAKE * 128, FAKE * 192, FAKE * 256         # 4 MiB apart: tensors here take 1 MiB
+    relu = sp3d.SP_FLAG_RELU
+    # no bits pointer, no ReLU, misaligned bits, bits over the output
+    assert L.conv3d_fwd_bits(A, FAKE, None, B, None, gp, 32, 32, bf, relu, C, 1 << 30, None) == sp3d.SP_EINVAL
+    assert L.conv3d_fwd_bits(A, FAKE, None, B, D, gp, 32, 32, bf, 0, C, 1 << 30, None) == sp3d.SP_EINVAL
+    assert L.conv3d_fwd_bits(A, FAKE, None, B, D + 2, gp, 32, 32, bf, relu, C, 1 << 30, None) == sp3d.SP_EINVAL
+    assert L.conv3d_fwd_bits(A, FAKE, None, B, B, gp, 32, 32, bf, relu, C, 1 << 30, None) == sp3d.SP_EINVAL
+    assert L.conv3d_fwd_bits(A, FAKE, None, B, D, gp, 16, 32, bf, relu, C, 1 << 30, None) == sp3d.SP_EUNSUPPORTED
+    assert L.conv3d_fwd2_bits(A, 32, FAKE * 32, 32, FAKE, None, B, None, gp, 32, bf, relu, C, 1 << 30, None) == sp3d.SP_EINVAL
+    assert L.conv3d_fwd2_bits(A, 32, FAKE * 32, 32, FAKE, None, B, D, gp, 32, bf, 0, C, 1 << 30, None) == sp3d.SP_EINVAL
+    assert L.conv3d_dgrad_bits(A, FAKE, None, B, gp, 32, 32, bf, C, 1 << 30, None) == sp3d.SP_EINVAL
+    assert L.conv3d_dgrad_bits(A, FAKE, B, B, gp, 32, 32, bf, C, 1 << 30, None) == sp3d.SP_EINVAL          # bits over dx
+    assert L.conv3d_dgrad_bits(A, FAKE, D, B, gp, 16, 32, bf, C, 1 << 30, None) == sp3d.SP_EUNSUPPORTED
+    assert L.sp_relu_bits(A, None, gp, 32, bf, None) == sp3d.SP_EINVAL
+    assert L.sp_relu_bits(A, A, gp, 32, bf, None) == sp3d.SP_EINVAL
+    assert L.sp_relu_bits(A, D, gp, 48, bf, None) == sp3d.SP_EUNSUPPORTED
+    assert L.sp_relu_bits(A, D, gp, 32, sp3d.SP_F32, None) == sp3d.SP_EUNSUPPORTED

@@ -1,0 +1,187 @@
+"""GPU parity of the one-bit ReLU mask: the backward pass of a conv + ReLU stack (Sec. 3) with the "was the
+activation positive" information carried as one bit per value instead of read back from the activation tensor.
+The bits are decoded here from the layout that the header documents and compared with the sign test on the
+oracle's side; the convolutions that write or read them must give, bit for bit, what the tensor forms give."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import conv3d
+from paper_1909_03108_amd import sp3d, synth
+from gpu_util import TOL, bits as raw, f64, rel_err, to_dev, widen
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # n, dhw, grid, cin, cout
+    (1, (8, 16, 64), (1, 2, 1), 32, 32),          # whole patches, one input chunk
+    (1, (12, 20, 72), (2, 2, 1), 32, 32),         # ragged patches
+    (2, (8, 16, 32), (2, 1, 1), 64, 64),          # batch 2; a pair of input chunks summed on chip
+    (1, (6, 16, 64), (1, 2, 2), 128, 64),         # two pairs per layer: partial sums between launches
+    (1, (8, 8, 64), (2, 1, 2), 96, 32),           # three single chunks (first / middle / last)
+    (1, (80, 16, 64), (2, 2, 1), 32, 64),         # marches cut into D chunks; two output blocks
+    (1, (10, 12, 40), (1, 1, 1), 64, 96),         # ragged patches, pairs, three output blocks
+]
+
+
+def decode(words, c):
+    """uint16 words [..voxels.., c/32, 2] -> bool [..voxels.., c] by the documented layout: word `hi` of block b
+    holds channel 32 b + 8 q + 4 hi + i in bit 4 q + i."""
+    out = np.zeros(words.shape[:-2] + (c,), dtype=bool)
+    for b in range(c // 32):
+        for hi in range(2):
+            for q in range(4):
+                for i in range(4):
+                    out[..., 32 * b + 8 * q + 4 * hi + i] = (words[..., b, hi] >> (4 * q + i)) & 1
+    return out
+
+
+def bits_array(g, c, fill):
+    nbytes = sp3d.sp_relu_bits_bytes(g, c)
+    assert nbytes == sp3d.sp_padded_elems(g, c) // 32 * 4
+    return torch.full((nbytes // 2,), fill, dtype=torch.int16, device="cuda")
+
+
+def words_of(t, g, c):
+    return t.cpu().numpy().view(np.uint16).reshape(tuple(g.padded_shape) + (c // 32, 2))
+
+
+INTERIOR = (slice(None),) * 4 + (slice(1, -1),) * 3
+
+
+def special_values(shape, seed):
+    """bf16 bit patterns with every kind of value the sign test must tell apart"""
+    x = synth.normal_volume(shape, seed, "bf16").copy()
+    flat = x.reshape(-1)
+    rng = np.random.default_rng(seed)
+    for pattern in (0x0000, 0x8000, 0x7f80, 0xff80, 0x7fc0, 0xffc0, 0x0001, 0x8001, 0x7f81):
+        flat[rng.integers(0, flat.size, size=flat.size // 50)] = pattern
+    return x
+
+
+def test_bits_of_a_tensor_follow_the_documented_layout():
+    n, dhw, grid, c = 1, (6, 10, 12), (1, 2, 2), 96
+    g = sp3d.Geom(n, dhw, grid)
+    dt = sp3d.SP_BF16
+    x = special_values((n,) + dhw + (c,), 5)
+    P = sp3d.alloc_padded(g, c, dt)
+    sp3d.sp_partition(to_dev(x), P, g, c, dt)
+    sp3d.sp_halo_exchange(P, g, c, dt)
+    B = bits_array(g, c, -1)
+    sp3d.sp_relu_bits(P, B, g, c, dt)
+    torch.cuda.synchronize()
+    want = widen(raw(P)) > 0            # NaN > 0 is False; +inf > 0 is True; -0 > 0 is False
+    got = decode(words_of(B, g, c), c)
+    assert np.array_equal(got, want)
+    assert 0.3 < want[INTERIOR].mean() < 0.6        # (the margins at the volume border hold zeros)
+
+
+@pytest.mark.parametrize("n,dhw,grid,cin,cout", CASES)
+def test_convolutions_write_and_read_the_bits(n, dhw, grid, cin, cout):
+    g = sp3d.Geom(n, dhw, grid)
+    dt, tol = sp3d.SP_BF16, TOL["bf16"]
+    assert sp3d.sp_relu_bits_supported(sp3d.SP_OP_FWD, g, cin, cout, dt)
+    assert sp3d.sp_relu_bits_supported(sp3d.SP_OP_DGRAD, g, cin, cout, dt)
+    x = synth.normal_volume((n,) + dhw + (cin,), 41, "bf16")
+    dz = synth.normal_volume((n,) + dhw + (cout,), 42, "bf16")
+    w = synth.weights(cin, cout, 43, "bf16")
+    bias = np.linspace(-0.5, 0.5, cout).astype(np.float32)
+    w_d = to_dev(w)
+    ws = {op: sp3d.alloc_ws(sp3d.sp_workspace_bytes(op, g, cin, cout, dt)) for op in (0, 1)}
+    X, Z = sp3d.alloc_padded(g, cin, dt), sp3d.alloc_padded(g, cout, dt)
+    sp3d.sp_partition(to_dev(x), X, g, cin, dt)
+    sp3d.sp_partition(to_dev(dz), Z, g, cout, dt)
+    sp3d.sp_halo_exchange(X, g, cin, dt)
+    sp3d.sp_halo_exchange(Z, g, cout, dt)
+
+    # producer: the forward pass with ReLU, with and without a bias
+    for b_d in (torch.from_numpy(bias).cuda(), None):
+        Y0, Y1 = sp3d.alloc_padded(g, cout, dt), sp3d.alloc_padded(g, cout, dt)
+        B = bits_array(g, cout, 0x5a5a)
+        sp3d.conv3d_fwd(X, w_d, b_d, Y0, g, cin, cout, dt, sp3d.SP_FLAG_RELU, ws[0])
+        sp3d.conv3d_fwd_bits(X, w_d, b_d, Y1, B, g, cin, cout, dt, sp3d.SP_FLAG_RELU, ws[0])
+        torch.cuda.synchronize()
+        assert torch.equal(Y0, Y1)
+        words = words_of(B, g, cout)
+        assert np.array_equal(decode(words[INTERIOR], cout), (widen(raw(Y1)) > 0)[INTERIOR])
+        # margin words are not written
+        keep = np.ones(words.shape, dtype=bool)
+        keep[INTERIOR] = False
+        assert (words[keep] == 0x5a5a).all()
+        # and agree with the standalone producer at the interiors
+        B2 = bits_array(g, cout, 0)
+        sp3d.sp_relu_bits(Y1, B2, g, cout, dt)
+        assert np.array_equal(words_of(B2, g, cout)[INTERIOR], words[INTERIOR])
+    V = torch.empty((n,) + dhw + (cout,), dtype=torch.bfloat16, device="cuda")
+    sp3d.sp_unpartition(Y1, V, g, cout, dt)
+    ref = conv3d.conv3d_fwd(x, widen(w), None, relu=True)
+    assert rel_err(f64(V), ref) <= tol
+
+    # consumer: the data gradient masked by the bits of the layer input (with every special value in it)
+    xm = special_values((n,) + dhw + (cin,), 44)
+    M = sp3d.alloc_padded(g, cin, dt)
+    sp3d.sp_partition(to_dev(xm), M, g, cin, dt)
+    BM = bits_array(g, cin, 0)
+    sp3d.sp_relu_bits(M, BM, g, cin, dt)
+    D0, D1 = sp3d.alloc_padded(g, cin, dt), sp3d.alloc_padded(g, cin, dt)
+    sp3d.conv3d_dgrad_relu(Z, w_d, M, D0, g, cin, cout, dt, ws[1])
+    sp3d.conv3d_dgrad_bits(Z, w_d, BM, D1, g, cin, cout, dt, ws[1])
+    torch.cuda.synchronize()
+    assert torch.equal(D0[INTERIOR], D1[INTERIOR])
+    Vd = torch.empty((n,) + dhw + (cin,), dtype=torch.bfloat16, device="cuda")
+    sp3d.sp_unpartition(D1, Vd, g, cin, dt)
+    refd = np.where(widen(xm) > 0, conv3d.conv3d_dgrad(dz, widen(w)), 0.0)
+    assert rel_err(f64(Vd), refd) <= tol
+
+
+@pytest.mark.parametrize("dhw,grid,cout,halo", [((8, 32, 64), (1, 2, 1), 32, 1), ((6, 40, 72), (2, 1, 2), 64, 1),
+                                                ((8, 32, 64), (2, 1, 1), 32, 2)])
+def test_first_layer_writes_the_bits(dhw, grid, cout, halo):
+    """the layer with one input channel (the CT volume) has a kernel of its own"""
+    n, cin, dt = 1, 1, sp3d.SP_BF16
+    g = sp3d.Geom(n, dhw, grid, halo)
+    assert sp3d.sp_relu_bits_supported(sp3d.SP_OP_FWD, g, cin, cout, dt)
+    x = synth.ct_like_volume((n,) + dhw + (cin,), 51, "bf16")
+    w_d = to_dev(synth.weights(cin, cout, 52, "bf16"))
+    bias = torch.from_numpy(np.linspace(-0.2, 0.2, cout).astype(np.float32)).cuda()
+    X = sp3d.alloc_padded(g, cin, dt)
+    sp3d.sp_partition(to_dev(x), X, g, cin, dt)
+    sp3d.sp_halo_exchange(X, g, cin, dt)
+    ws = sp3d.alloc_ws(max(16, sp3d.sp_workspace_bytes(0, g, cin, cout, dt)))
+    Y0, Y1 = sp3d.alloc_padded(g, cout, dt), sp3d.alloc_padded(g, cout, dt)
+    B = bits_array(g, cout, 0x5a5a)
+    sp3d.conv3d_fwd(X, w_d, bias, Y0, g, cin, cout, dt, sp3d.SP_FLAG_RELU, ws)
+    sp3d.conv3d_fwd_bits(X, w_d, bias, Y1, B, g, cin, cout, dt, sp3d.SP_FLAG_RELU, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(Y0, Y1)
+    inner = (slice(None),) * 4 + (slice(halo, -halo),) * 3
+    words = words_of(B, g, cout)
+    pos = (widen(raw(Y1)) > 0)[inner]
+    assert np.array_equal(decode(words[inner], cout), pos)
+    assert 0.2 < pos.mean() < 0.8
+    keep = np.ones(words.shape, dtype=bool)
+    keep[inner] = False
+    assert (words[keep] == 0x5a5a).all()
+
+
+def test_bits_refusals():
+    dt = sp3d.SP_BF16
+    g = sp3d.Geom(1, (8, 16, 32), (1, 1, 1))
+    flat = sp3d.Geom(1, (8, 16, 32), (1, 1, 1), flat=1)
+    assert not sp3d.sp_relu_bits_supported(sp3d.SP_OP_FWD, flat, 32, 32, dt)          # 2-D variant
+    assert not sp3d.sp_relu_bits_supported(sp3d.SP_OP_FWD, g, 16, 32, dt)             # not the matrix-core path
+    assert not sp3d.sp_relu_bits_supported(sp3d.SP_OP_WGRAD, g, 32, 32, dt)
+    assert sp3d.sp_relu_bits_bytes(g, 48) == 0
+    X, Y = sp3d.alloc_padded(g, 32, dt), sp3d.alloc_padded(g, 32, dt)
+    B = bits_array(g, 32, 0)
+    w_d = to_dev(synth.weights(32, 32, 1, "bf16"))
+    ws = sp3d.alloc_ws(sp3d.sp_workspace_bytes(0, g, 32, 32, dt))
+    with pytest.raises(sp3d.Sp3dError) as e:          # bits without ReLU
+        sp3d.conv3d_fwd_bits(X, w_d, None, Y, B, g, 32, 32, dt, 0, ws)
+    assert e.value.code == sp3d.SP_EINVAL
+    with pytest.raises(sp3d.Sp3dError) as e:
+        sp3d.conv3d_fwd_bits(X, w_d, None, Y, B, flat, 32, 32, dt, sp3d.SP_FLAG_RELU, ws)
+    assert e.value.code == sp3d.SP_EUNSUPPORTED
+    with pytest.raises(sp3d.Sp3dError) as e:
+        sp3d.sp_relu_bits(X, B, g, 32, sp3d.SP_F32)
+    assert e.value.code == sp3d.SP_EUNSUPPORTED

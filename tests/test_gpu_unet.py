@@ -346,6 +346,34 @@ def test_unet_gathered_halos_bit_identical(convs, grid):
     assert count[1] < count[0]
 
 
+@pytest.mark.parametrize("convs,gather", [(2, False), (4, False), (4, True)])
+def test_unet_one_bit_relu_masks_bit_identical(convs, gather):
+    """ReLU masks inside the blocks carried as one bit per value (written by the forward convolution, read by the
+    next layer's data gradient) instead of re-read from the activation: every result of a forward + backward is
+    bit for bit that of the tensor-mask path; every layer with a successor in its block uses the bits."""
+    channels, in_ch, classes = (32, 64, 128), 1, 3
+    n, dhw, grid = 1, (16, 32, 128), (2, 2, 1)
+    plan = PU.layer_plan(channels, in_ch, classes, convs)
+    x = to_dev(synth.ct_like_volume((n,) + dhw + (in_ch,), synth.seed_for(9, synth.T_INPUT), "bf16"))
+    w_d = {name: to_dev(synth.weights(shape[3], shape[4], synth.seed_for(9, synth.T_WEIGHT0 + k), "bf16",
+                                      taps=shape[:3])) for k, (name, shape) in enumerate(plan)}
+    dl = to_dev(synth.normal_volume((n,) + dhw + (classes,), synth.seed_for(9, synth.T_UPSTREAM), "bf16"))
+    res, used = [], 0
+    for bits in (False, True):
+        net = PU.UNet(n, dhw, grid, w_d, channels, in_ch, classes, convs=convs, gather=gather, bits=bits)
+        for _ in range(2):                       # the second step runs on recycled buffers
+            logits = net.forward(x)
+            used = sum(1 for k in net.A if k.endswith(".xbits"))
+            grads, dx = net.backward(dl)
+        res.append((logits, grads, dx))
+    (l1, g1, d1), (l2, g2, d2) = res
+    assert torch.equal(l1, l2) and torch.equal(d1, d2)
+    for k, _ in plan:
+        assert torch.equal(g1[k], g2[k]), k
+    # every layer with a successor in its block hands bits on (the one-input-channel first layer included)
+    assert used == (2 * len(channels) - 1) * (convs - 1)
+
+
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("grids", [[(2, 2, 1), (2, 2, 1), (1, 1, 1)], [(2, 2, 2), (1, 2, 1), (1, 1, 1)],
                                    [(2, 4, 1), (1, 1, 1), (1, 1, 1)]])
