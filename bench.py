@@ -304,6 +304,19 @@ def main():
     fwd_zero_ms = median_ms(lambda: sp3d.conv3d_fwd(Pzero, w, None, Py, g, c, c, dt, 0, wsp[0], stream), reps=5)
     del Pzero
 
+    # The data gradient with the ReLU mask of the layer input (every inner layer of a conv + ReLU stack): mask read
+    # from the activation tensor, and mask given as one bit per value (written by conv3d_fwd_bits of the layer before)
+    Bx = torch.empty(sp3d.sp_relu_bits_bytes(g, c) // 2, dtype=torch.int16, device="cuda")
+    sp3d.sp_relu_bits(Px, Bx, g, c, dt, stream)
+    masked_ms = {
+        "conv3d_dgrad": median_ms(lambda: sp3d.conv3d_dgrad(Pdy, w, Pdx, g, c, c, dt, wsp[1], stream), reps=5),
+        "conv3d_dgrad_relu": median_ms(lambda: sp3d.conv3d_dgrad_relu(Pdy, w, Px, Pdx, g, c, c, dt, wsp[1], stream), reps=5),
+        "conv3d_dgrad_bits": median_ms(lambda: sp3d.conv3d_dgrad_bits(Pdy, w, Bx, Pdx, g, c, c, dt, wsp[1], stream), reps=5),
+        "conv3d_fwd_relu": median_ms(lambda: sp3d.conv3d_fwd(Px, w, None, Py, g, c, c, dt, sp3d.SP_FLAG_RELU, wsp[0], stream), reps=5),
+        "conv3d_fwd_bits": median_ms(lambda: sp3d.conv3d_fwd_bits(Px, w, None, Py, Bx, g, c, c, dt, sp3d.SP_FLAG_RELU, wsp[0], stream), reps=5),
+    }
+    del Bx
+
     per = {}
     for name, e0, e1 in events:
         per.setdefault(name, []).append(e0.elapsed_time(e1))
@@ -406,6 +419,9 @@ def main():
                                 "timed after the step: a faster run means the real one is held by the chip's power "
                                 "management; library_gemm_tflops is the vendor GEMM (torch.matmul 8192^3 bf16, N(0,1) "
                                 "data) on this box for comparison"},
+        "relu_mask_ms": dict({k: round(v, 4) for k, v in masked_ms.items()},
+                             what="after the step: the data gradient plain, masked by the activation tensor, and masked "
+                                  "by the one-bit form; the forward pass with ReLU without / with writing the bits"),
         "roofline": roofline,
         "roofline_other": other,
     }
