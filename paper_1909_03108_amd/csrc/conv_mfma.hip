@@ -279,16 +279,26 @@ __device__ __forceinline__ size_t part_unit(int d, int h, int q) { return static
 template <class CtxT>
 __device__ __forceinline__ size_t bits_off(const CtxT &c, int d, int h) { return (d * c.oplane + h * c.orow) >> 4; }
 
-// The four bits of a finished store unit (two packed bf16 pairs): bit i set where value i is positive.
-__device__ __forceinline__ uint32_t positive_nibble(uint2 pk) {
-    return ((pk.x & 0xffffu) - 1u < 0x7f80u ? 1u : 0u) | ((pk.x >> 16) - 1u < 0x7f80u ? 2u : 0u) |
-           ((pk.y & 0xffffu) - 1u < 0x7f80u ? 4u : 0u) | ((pk.y >> 16) - 1u < 0x7f80u ? 8u : 0u);
+// The four bits of a finished store unit, taken from the fp32 values before they are rounded: a value is stored
+// as a positive bf16 exactly if it exceeds 2^-134, the midpoint between zero and the smallest bf16 denormal (a tie
+// rounds to the even neighbour, zero; fp32 denormals are kept in these kernels' floating-point mode).  NaN compares
+// false and +inf true, as the sign test on the stored value has it.  One compare and one select per value, against
+// four integer operations on the packed halves.
+__device__ __forceinline__ uint32_t positive_nibble(float v0, float v1, float v2, float v3) {
+    constexpr float T = 0x1p-134f;
+    return (v0 > T ? 1u : 0u) | (v1 > T ? 2u : 0u) | (v2 > T ? 4u : 0u) | (v3 > T ? 8u : 0u);
 }
 // ... and the reverse: 0xffff in each half of the two words whose bit is set
 __device__ __forceinline__ uint2 nibble_halves(uint32_t word, int q) {
     const uint32_t n = word >> (4 * q);
     return make_uint2(((n & 1u) ? 0x0000ffffu : 0u) | ((n & 2u) ? 0xffff0000u : 0u),
                       ((n & 4u) ? 0x0000ffffu : 0u) | ((n & 8u) ? 0xffff0000u : 0u));
+}
+
+// kReluBits: write the mask word of row h of plane d that the four store units of the row collected.
+template <bool FULL, class CtxT>
+__device__ __forceinline__ void store_bits(const CtxT &c, int d, const mask_t (&mk)[RH][4], int h) {
+    if (FULL || c.okrow[h]) c.bbase[bits_off(c, d, h)] = static_cast<uint16_t>(mk[h][0].x);
 }
 
 // Per-wave state of the march that the side work of a step needs.
@@ -376,9 +386,9 @@ __device__ __forceinline__ void store_unit(const Ctx<HAS_BIAS> &c, int d, const 
     if (FULL || c.okrow[h]) *reinterpret_cast<uint2 *>(c.obase + at) = pk;
     if (RELU == kReluBits) {
         // the row's word collects in the (otherwise unused) mask register of unit 0 and leaves with the last unit
-        const uint32_t n = positive_nibble(pk) << (4 * q);
+        const uint32_t n = positive_nibble(v0, v1, v2, v3) << (4 * q);
         mk[h][0].x = q == 0 ? n : (mk[h][0].x | n);
-        if (q == 3 && (FULL || c.okrow[h])) c.bbase[bits_off(c, d, h)] = static_cast<uint16_t>(mk[h][0].x);
+        if (q == 3) store_bits<FULL>(c, d, mk, h);
     }
 }
 
@@ -787,9 +797,9 @@ __device__ __forceinline__ void finish_unit(const Ctx<HAS_BIAS> &c, int d, const
     if (FULL || c.okrow[h]) *reinterpret_cast<uint2 *>(c.obase + at) = pk;
     if (RELU == kReluBits) {
         // the row's word collects in the (otherwise unused) mask register of unit 0 and leaves with the last unit
-        const uint32_t n = positive_nibble(pk) << (4 * q);
+        const uint32_t n = positive_nibble(v0, v1, v2, v3) << (4 * q);
         mk[h][0].x = q == 0 ? n : (mk[h][0].x | n);
-        if (q == 3 && (FULL || c.okrow[h])) c.bbase[bits_off(c, d, h)] = static_cast<uint16_t>(mk[h][0].x);
+        if (q == 3) store_bits<FULL>(c, d, mk, h);
     }
 }
 

@@ -164,6 +164,29 @@ def test_first_layer_writes_the_bits(dhw, grid, cout, halo):
     assert (words[keep] == 0x5a5a).all()
 
 
+@pytest.mark.parametrize("cin,cout,shift", [(32, 32, 133), (64, 32, 131), (32, 32, 128)])
+def test_bits_at_the_smallest_values(cin, cout, shift):
+    """Outputs around the smallest bf16 denormal (2^-133): the bit must follow the value as stored - a sum that
+    rounds to zero is not positive - whatever the matrix cores and the conversion do with denormals."""
+    n, dhw, grid, dt = 1, (8, 16, 64), (1, 2, 1), sp3d.SP_BF16
+    g = sp3d.Geom(n, dhw, grid)
+    x = synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(synth.normal_volume((n,) + dhw + (cin,), 61, "bf16")) * 2.0 ** -60)
+    w = synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(synth.weights(cin, cout, 62, "bf16")) * 2.0 ** (60 - shift))
+    X = sp3d.alloc_padded(g, cin, dt)
+    sp3d.sp_partition(to_dev(x), X, g, cin, dt)
+    sp3d.sp_halo_exchange(X, g, cin, dt)
+    ws = sp3d.alloc_ws(sp3d.sp_workspace_bytes(0, g, cin, cout, dt))
+    Y0, Y1 = sp3d.alloc_padded(g, cout, dt), sp3d.alloc_padded(g, cout, dt)
+    B = bits_array(g, cout, 0)
+    sp3d.conv3d_fwd(X, to_dev(w), None, Y0, g, cin, cout, dt, sp3d.SP_FLAG_RELU, ws)
+    sp3d.conv3d_fwd_bits(X, to_dev(w), None, Y1, B, g, cin, cout, dt, sp3d.SP_FLAG_RELU, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(Y0, Y1)
+    y = raw(Y1)[INTERIOR]
+    assert np.array_equal(decode(words_of(B, g, cout)[INTERIOR], cout), (y != 0) & (y < 0x7f81))
+    print("stored values: %d zero, %d denormal, %d normal" % ((y == 0).sum(), ((y > 0) & (y < 0x80)).sum(), (y >= 0x80).sum()))
+
+
 def test_bits_refusals():
     dt = sp3d.SP_BF16
     g = sp3d.Geom(1, (8, 16, 32), (1, 1, 1))
