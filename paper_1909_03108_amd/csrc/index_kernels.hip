@@ -151,18 +151,36 @@ int partition_dispatch(const void *vol, void *P, const PartArgs &a, bool inverse
 // alone (SP_HALO_*: the tile has no neighbour in that direction) returns at once.
 constexpr int kHaloChunk = kThreads * kVpt;   // vectors per block
 
+// Everything a block needs to know about its region, in one 112-byte record: after the search for the block's
+// region the scalar unit fetches it with a single load (the region table, its opposite entry, the per-region
+// dividers and the order table were four dependent loads before; a wave spends more of its life on this preamble
+// than on its two memory round trips).  Records are in the order the regions' blocks follow each other inside a
+// tile: largest first, so that the search ends after a step or two for nearly every block (the message layout
+// is not affected: it is given by the regions' offsets).
+struct HaloRec {
+    int ext[3];           // extents (d,h,w) of the region
+    int org[3];           // pack: origin of the sent box; unpack / exchange: origin of the margin box (padded coordinates)
+    int delta[3];         // direction
+    int nsend[3];         // exchange: origin of the box the neighbour would have packed (the opposite region's)
+    long long off;        // voxel offset of the region inside a tile's message
+    long long off_opp;    // ... of the opposite region (what unpack reads from the neighbour's message)
+    FastDiv ehw, ew;      // ext[1]*ext[2] and ext[2]
+    unsigned nvec;        // vectors of the region
+    unsigned nch;         // its blocks
+    int whole_rows;       // 1: a row is a whole multiple of a block's vectors
+    int pad;
+};
+static_assert(sizeof(HaloRec) == 112, "one record = two scalar loads");
+
 struct HaloArgs {
     Geo g;
-    RegionTable t;
-    int order[26];        // regions in the order their blocks follow each other inside a tile: largest first, so
-                          // that the search below ends after a step or two for nearly every block (the message
-                          // layout is not affected: it is given by the regions' offsets)
+    HaloRec rec[26];
     int blk_prefix[27];   // first block (within a tile) of the region at each position; [26] = blocks per tile
-    FastDiv ehw[26], ew[26];   // per region: ext[1]*ext[2] and ext[2]
     FastDiv vpv;          // vectors per voxel
     FastDiv bpt, gw, gh, gd;
     int skip;             // 1: regions whose direction leads outside the grid are left alone (SP_HALO_*)
 };
+static_assert(sizeof(HaloArgs) + 16 <= 4096, "kernel arguments");
 
 // MODE: kPack = tile interiors -> messages; kUnpack = neighbours' messages -> margins (zeros where the
 // neighbour is outside the grid); kExchange = both at once when all tiles share one memory: every margin
@@ -177,10 +195,9 @@ __global__ __launch_bounds__(kThreads) void halo_kernel(const T *src, T *dst, Ha
     const unsigned tile = fdiv(blockIdx.x, a.bpt), rem = fmod_(blockIdx.x, tile, a.bpt);
     int pi = 0;
     while (pi < 25 && static_cast<unsigned>(a.blk_prefix[pi + 1]) <= rem) ++pi;   // uniform
-    const int ri = a.order[pi];
-    const Region &r = a.t.r[ri];
+    const HaloRec &r = a.rec[pi];
     unsigned chunk = rem - a.blk_prefix[pi];
-    const unsigned nvec = static_cast<unsigned>(r.ext[0]) * r.ext[1] * r.ext[2] * a.vpv.d;
+    const unsigned nvec = r.nvec;
     if (chunk * kHaloChunk >= nvec) return;   // uniform; cannot happen with the block counts of halo_dispatch
 
     long long nb_msg = -1;   // UNPACK: voxel offset of the neighbour's message region, -1 = none
@@ -192,7 +209,7 @@ __global__ __launch_bounds__(kThreads) void halo_kernel(const T *src, T *dst, Ha
         const int nc = static_cast<int>(tc) + r.delta[2];
         if (na >= 0 && na < g.gd && nb >= 0 && nb < g.gh && nc >= 0 && nc < g.gw) {
             const long long ntile = ((1LL * tn * g.gd + na) * g.gh + nb) * g.gw + nc;
-            nb_msg = MODE == kExchange ? ntile : ntile * g.msg_vox + a.t.r[r.opposite].off;
+            nb_msg = MODE == kExchange ? ntile : ntile * g.msg_vox + r.off_opp;
         } else if (a.skip) {
             return;          // uniform: nobody receives this region / its margin holds zeros already
         }
@@ -201,11 +218,9 @@ __global__ __launch_bounds__(kThreads) void halo_kernel(const T *src, T *dst, Ha
     // eighth of the chunks instead of every eighth chunk (as in xcd_contiguous_block(), but per tile and region:
     // over the whole grid the XCDs would get unequal shares of the zero-fill work).  A bijection of the chunks.
     {
-        const unsigned nch = a.blk_prefix[pi + 1] - a.blk_prefix[pi];
+        const unsigned nch = r.nch;
         if (nch >= 64 && (nch & 7u) == 0) chunk = (chunk & 7u) * (nch >> 3) + (chunk >> 3);
     }
-    const int *org = UNPACK ? r.recv : r.send;
-    const int *nsend = a.t.r[r.opposite].send;     // kExchange: the box the neighbour would have packed
     const long long msg0 = UNPACK ? nb_msg : tile * g.msg_vox + r.off;   // message region of this block
     T v[kVpt];
     long long mo[kVpt], po[kVpt];   // vector offsets in the message and in the padded tensor
@@ -214,17 +229,17 @@ __global__ __launch_bounds__(kThreads) void halo_kernel(const T *src, T *dst, Ha
     // neighbour's interior)
     auto locate = [&](unsigned j, long long *pout, long long *mout) {
         const unsigned vox = fdiv(j, a.vpv), cv = fmod_(j, vox, a.vpv);
-        const unsigned ld = fdiv(vox, a.ehw[ri]), q = fmod_(vox, ld, a.ehw[ri]);
-        const unsigned lh = fdiv(q, a.ew[ri]), lw = fmod_(q, lh, a.ew[ri]);
-        const long long pvox = tile * g.tile_vox + (1LL * (org[0] + ld) * g.ph + org[1] + lh) * g.pw + org[2] + lw;
+        const unsigned ld = fdiv(vox, r.ehw), q = fmod_(vox, ld, r.ehw);
+        const unsigned lh = fdiv(q, r.ew), lw = fmod_(q, lh, r.ew);
+        const long long pvox = tile * g.tile_vox + (1LL * (r.org[0] + ld) * g.ph + r.org[1] + lh) * g.pw + r.org[2] + lw;
         *pout = pvox * a.vpv.d + cv;
         if (MODE == kExchange)
-            *mout = (nb_msg * g.tile_vox + (1LL * (nsend[0] + ld) * g.ph + nsend[1] + lh) * g.pw + nsend[2] + lw) *
+            *mout = (nb_msg * g.tile_vox + (1LL * (r.nsend[0] + ld) * g.ph + r.nsend[1] + lh) * g.pw + r.nsend[2] + lw) *
                         a.vpv.d + cv;
         else
             *mout = (msg0 + vox) * a.vpv.d + cv;
     };
-    if ((static_cast<unsigned>(r.ext[2]) * a.vpv.d) % kHaloChunk == 0) {
+    if (r.whole_rows) {
         // rows that are whole multiples of a block's vectors (the D and H faces of large tiles): the block lies
         // inside one row, so its first vector is located once, on the scalar unit, and a lane only adds its index
         long long p0, m0;
@@ -254,28 +269,44 @@ __global__ __launch_bounds__(kThreads) void halo_kernel(const T *src, T *dst, Ha
 }
 
 template <int VB>
-int halo_dispatch(const void *src, void *dst, HaloArgs &a, int mode, hipStream_t s) {
+int halo_dispatch(const void *src, void *dst, HaloArgs &a, const RegionTable &t, int mode, hipStream_t s) {
     using T = typename VecT<VB>::type;
-    int nblk[26];
+    int nblk[26], order[26];
+    long long nvecs[26];
     for (int i = 0; i < 26; ++i) {
-        const long long nvec = 1LL * a.t.r[i].ext[0] * a.t.r[i].ext[1] * a.t.r[i].ext[2] * a.vpv.d;
+        const long long nvec = 1LL * t.r[i].ext[0] * t.r[i].ext[1] * t.r[i].ext[2] * a.vpv.d;
         if (nvec > 0xffffff00LL) return SP_EGEOM;
-        a.ehw[i] = make_fastdiv(static_cast<uint32_t>(a.t.r[i].ext[1]) * a.t.r[i].ext[2]);
-        a.ew[i] = make_fastdiv(a.t.r[i].ext[2]);
+        nvecs[i] = nvec;
         // 2-D variant: slices do not interact, the regions above and below a tile are not moved
-        nblk[i] = (a.g.flat && a.t.r[i].delta[0] != 0) ? 0 : static_cast<int>((nvec + kHaloChunk - 1) / kHaloChunk);
+        nblk[i] = (a.g.flat && t.r[i].delta[0] != 0) ? 0 : static_cast<int>((nvec + kHaloChunk - 1) / kHaloChunk);
         // a direction along an axis that the grid does not split leads outside the grid for every tile: with
         // SP_HALO_* such a region gets no blocks at all (instead of blocks that find that out and return)
         const int gdim[3] = {a.g.gd, a.g.gh, a.g.gw};
         for (int k = 0; k < 3; ++k)
-            if (a.skip && a.t.r[i].delta[k] != 0 && gdim[k] == 1) nblk[i] = 0;
-        a.order[i] = i;
+            if (a.skip && t.r[i].delta[k] != 0 && gdim[k] == 1) nblk[i] = 0;
+        order[i] = i;
     }
-    std::stable_sort(a.order, a.order + 26, [&](int x, int y) { return nblk[x] > nblk[y]; });
+    std::stable_sort(order, order + 26, [&](int x, int y) { return nblk[x] > nblk[y]; });
     int acc = 0;
     for (int p = 0; p < 26; ++p) {
+        const Region &r = t.r[order[p]], &o = t.r[r.opposite];
+        HaloRec &h = a.rec[p];
+        for (int k = 0; k < 3; ++k) {
+            h.ext[k] = r.ext[k];
+            h.org[k] = mode == kPack ? r.send[k] : r.recv[k];
+            h.delta[k] = r.delta[k];
+            h.nsend[k] = o.send[k];
+        }
+        h.off = r.off;
+        h.off_opp = o.off;
+        h.ehw = make_fastdiv(static_cast<uint32_t>(r.ext[1]) * r.ext[2]);
+        h.ew = make_fastdiv(r.ext[2]);
+        h.nvec = static_cast<unsigned>(nvecs[order[p]]);
+        h.nch = static_cast<unsigned>(nblk[order[p]]);
+        h.whole_rows = (static_cast<unsigned>(r.ext[2]) * a.vpv.d) % kHaloChunk == 0 ? 1 : 0;
+        h.pad = 0;
         a.blk_prefix[p] = acc;
-        acc += nblk[a.order[p]];
+        acc += nblk[order[p]];
     }
     a.blk_prefix[26] = acc;
     if (acc == 0) return SP_OK;       // one tile and nothing to do beyond the volume border: no launch
@@ -375,13 +406,14 @@ static int halo_launch(const void *src, void *dst, const Geo &g, int c, sp_dtype
     HaloArgs a;
     a.g = g;
     a.skip = (border & (mode == kPack ? SP_HALO_SKIP_SEND : SP_HALO_KEEP_ZERO)) ? 1 : 0;
-    make_regions(g, &a.t);
+    RegionTable t;
+    make_regions(g, &t);
     a.vpv = make_fastdiv(static_cast<uint32_t>(rec / vb));
     switch (vb) {
-    case 16: return halo_dispatch<16>(src, dst, a, mode, s);
-    case 8: return halo_dispatch<8>(src, dst, a, mode, s);
-    case 4: return halo_dispatch<4>(src, dst, a, mode, s);
-    default: return halo_dispatch<2>(src, dst, a, mode, s);
+    case 16: return halo_dispatch<16>(src, dst, a, t, mode, s);
+    case 8: return halo_dispatch<8>(src, dst, a, t, mode, s);
+    case 4: return halo_dispatch<4>(src, dst, a, t, mode, s);
+    default: return halo_dispatch<2>(src, dst, a, t, mode, s);
     }
 }
 
