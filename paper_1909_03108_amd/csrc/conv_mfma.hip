@@ -703,8 +703,23 @@ constexpr int CHUNK_BYTES = 4 * CH_STRIDE;           // 13184: one input chunk's
 constexpr int PLANE_BYTES = 2 * CHUNK_BYTES;         // both chunks of the pair
 constexpr int RING_BYTES = NBUF * PLANE_BYTES;       // 105472
 constexpr int RED_BYTES = NRG * RH * 4 * 64 * 16;    // 16384: one plane's hand-over (float4 per lane and unit)
-constexpr int LDS_BYTES = RING_BYTES + 2 * RED_BYTES;   // 138240
+// Weight fragments in LDS (3-D kernel).  A wave needs 54 fragments = 216 registers beside 160 accumulators, and
+// the register allocation of these kernels was over its 512 by 30 - 80 registers: the compiler spilled weight
+// fragments to scratch and reloaded them at their use, 1 - 7 times per plane step, and since it cannot tell its own
+// scratch load from the staging loads in flight it followed every reload with a wait for ALL outstanding memory
+// operations - the prefetch of three planes drained several times per step.  The twelve fragments of the taps with
+// kh = 2 and kd = 1, 2 (the ones a group of MFMAs uses last) therefore live in LDS, once per input chunk of the
+// pair (both waves of a chunk use the same ones), and are read at the start of the group that uses them: a read
+// the LDS counter tracks, no memory wait.
+constexpr int WL_FRAGS = 12;
+constexpr int WL_BYTES = 2 * WL_FRAGS * 1024;          // 24576: both input chunks of the pair
+constexpr int WL_BASE = RING_BYTES + 2 * RED_BYTES;
+constexpr int LDS_BYTES = WL_BASE + WL_BYTES;          // 162816
 static_assert(LDS_BYTES <= 160 * 1024, "LDS of one CU");
+__host__ __device__ constexpr bool wl_in_lds(int KD, int f) {      // fragment f = (tap, half)
+    return KD == 3 && ((f / 2) / 3) % 3 == 2 && (f / 2) / 9 >= 1;
+}
+__host__ __device__ constexpr int wl_index(int kd, int kw, int half) { return ((kd - 1) * 3 + kw) * 2 + half; }
 
 // direct-to-LDS load as in wgrad_mfma.hip: written as assembly so that the compiler neither tracks it nor
 // drains it before unrelated LDS accesses; the kernel counts the loads itself (s_waitcnt vmcnt)
@@ -725,6 +740,7 @@ struct Ctx {
     bool tail_lane;             // lane has a voxel in the last (partial) load of a chunk plane
     char *lds_stage;            // first chunk plane this wave fills, ring slot 0
     char *red;                  // hand-over buffer of this wave's row group (buffer 0), lane part included
+    const char *wl;             // this chunk's LDS-resident weight fragments, lane part included
     uint16_t *obase;
     const uint16_t *mbase;
     uint16_t *bbase;
@@ -865,6 +881,13 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const
                 b[(gi + 1) & 1][r] = *reinterpret_cast<const bf16x8 *>(
                     lbase + half2 * 2 * CH_STRIDE + (r * LCOLS + kw2) * 16);
         }
+        // the two weight fragments of this group that live in LDS (see WL_FRAGS); the MFMAs that use them are
+        // the last of the group
+        bf16x8 wl2[2];
+        if (KD == 3) {
+            wl2[0] = *reinterpret_cast<const bf16x8 *>(c.wl + wl_index(1, kw, half) * 1024);
+            wl2[1] = *reinterpret_cast<const bf16x8 *>(c.wl + wl_index(2, kw, half) * 1024);
+        }
         __builtin_amdgcn_sched_barrier(0);
         // eight staging loads over six groups
         stage(c, Dp + DIST, gi);
@@ -898,8 +921,9 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const
                 for (int kd = 0; kd < 3; ++kd) {
                     if (KD == 1 && kd != 1) continue;
                     const int slot = (P - kd + NSLOT) % NSLOT;
+                    const int f = ((kd * 3 + kh) * 3 + kw) * 2 + half;
                     acc[slot][h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        wf[((kd * 3 + kh) * 3 + kw) * 2 + half], b[gi & 1][r], acc[slot][h], 0, 0, 0);
+                        wl_in_lds(KD, f) ? wl2[kd - 1] : wf[f], b[gi & 1][r], acc[slot][h], 0, 0, 0);
                 }
             }
 #pragma unroll
@@ -978,7 +1002,13 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int logical, i
         for (int f = 0; f < NFRAG; ++f) {
             if (KD == 1 && f / 18 != 1) continue;
             const uint4 q = wp[(cj * NFRAG + f) * 64 + lane];
-            wf[f] = *reinterpret_cast<const bf16x8 *>(&q);
+            if (wl_in_lds(KD, f)) {      // both waves of a chunk write the same bytes
+                const int tap = f / 2;
+                *reinterpret_cast<uint4 *>(lds + WL_BASE + (ROLE * WL_FRAGS + wl_index(tap / 9, tap % 3, f & 1)) * 1024 +
+                                           lane * 16) = q;
+            } else {
+                wf[f] = *reinterpret_cast<const bf16x8 *>(&q);
+            }
         }
     }
 
@@ -1017,6 +1047,7 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int logical, i
     c.tail_lane = 64 * (CP_LOADS - 1) + lane < PLANE_VOX;
     c.lds_stage = lds + ROLE * CHUNK_BYTES + 2 * rg * CH_STRIDE;
     c.red = lds + RING_BYTES + rg * (RH * 4 * 1024) + lane * 16;
+    c.wl = lds + WL_BASE + ROLE * WL_FRAGS * 1024 + lane * 16;
     const OutDst od = out_dest(a, cj);
     const FoldCol oc = fold_col(col, F, a.fold_w);
     c.orow = static_cast<size_t>(g.pw) * od.cs;
@@ -1052,7 +1083,7 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int logical, i
     for (int i = 0; i < DIST; ++i)
 #pragma unroll
         for (int j = 0; j < LOADS; ++j) stage(c, i, j);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");      // staged planes and the parked weight fragments
     __builtin_amdgcn_s_barrier();
 
     // End of a step: plane Dp + 1 has landed when at most the loads of planes Dp + 2, Dp + 3 are in flight
