@@ -35,6 +35,9 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+// (a plain vector type: arrays of the runtime's uint4 class stayed in scratch memory - 12 stores and 12 loads per
+// K step, each with a wait that drained the voxel-fragment loads in flight)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int C = 32;                            // channels of a chunk / block
 constexpr int CB = 4;                            // output blocks per workgroup
@@ -115,7 +118,7 @@ __device__ __forceinline__ void advance(const GemmArgs &a, int &i, int &r) {
 // Issue the loads of K step (chunk i, row r): this thread's share of the 24 weight fragments (to registers, on
 // their way to LDS) and this lane's B fragments of the step.
 template <int VB>
-__device__ __forceinline__ void fetch(const GemmArgs &a, const Ctx &c, int i, int r, uint4 (&areg)[STAGE_LOADS],
+__device__ __forceinline__ void fetch(const GemmArgs &a, const Ctx &c, int i, int r, u32x4 (&areg)[STAGE_LOADS],
                                       bf16x8 (&b)[VB][ROW][2]) {
     const int tap0 = TAP0 + ROW * r;
 #pragma unroll
@@ -123,7 +126,7 @@ __device__ __forceinline__ void fetch(const GemmArgs &a, const Ctx &c, int i, in
         const int e = j * kThreads + c.tid;                     // piece of the stage
         const int cb = e / (ROW * 2 * 64), x = e - cb * (ROW * 2 * 64);
         const size_t frag0 = (static_cast<size_t>(i * a.nco + c.cg * CB + cb) * NTAP_PACK + tap0) * 2;
-        areg[j] = a.wpack[frag0 * 64 + x];
+        areg[j] = reinterpret_cast<const u32x4 *>(a.wpack)[frag0 * 64 + x];
     }
     const InSrc src = in_src(a, i);
     const long long ro = row_offset(c, r);
@@ -167,10 +170,10 @@ __device__ __forceinline__ void contract(const char *abuf, int lane, const bf16x
 template <int VB>
 __device__ __forceinline__ void step(const GemmArgs &a, const Ctx &c, char *cur, char *other, int lane, int &i, int &r,
                                      const bf16x8 (&bc)[VB][ROW][2], bf16x8 (&bn)[VB][ROW][2],
-                                     const uint4 (&aw)[STAGE_LOADS], uint4 (&an)[STAGE_LOADS], f32x16 (&acc)[CB][VB]) {
+                                     const u32x4 (&aw)[STAGE_LOADS], u32x4 (&an)[STAGE_LOADS], f32x16 (&acc)[CB][VB]) {
     fetch(a, c, i, r, an, bn);
     contract(cur, lane, bc, acc);
-    uint4 *dst = reinterpret_cast<uint4 *>(other);
+    u32x4 *dst = reinterpret_cast<u32x4 *>(other);
 #pragma unroll
     for (int j = 0; j < STAGE_LOADS; ++j) dst[j * kThreads + c.tid] = aw[j];
     __syncthreads();
@@ -228,13 +231,13 @@ __global__ __launch_bounds__(kThreads, 1) void conv_gemm_kernel(GemmArgs a) {
     // voxel fragments rotate through three register sets and the weight pieces through two; six steps per
     // iteration keep every set a compile-time name (the step count is a multiple of 6: nci is even).
     bf16x8 b0[VB][ROW][2], b1[VB][ROW][2], b2[VB][ROW][2];
-    uint4 a0[STAGE_LOADS], a1[STAGE_LOADS];
+    u32x4 a0[STAGE_LOADS], a1[STAGE_LOADS];
     char *const s0 = lds, *const s1 = lds + STAGE_BYTES;
     int i = 0, r = 0;
     fetch(a, c, i, r, a0, b0);
     advance(a, i, r);
     {
-        uint4 *dst = reinterpret_cast<uint4 *>(s0);
+        u32x4 *dst = reinterpret_cast<u32x4 *>(s0);
 #pragma unroll
         for (int j = 0; j < STAGE_LOADS; ++j) dst[j * kThreads + tid] = a0[j];
     }
