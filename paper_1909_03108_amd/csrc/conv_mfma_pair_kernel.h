@@ -1,0 +1,491 @@
+// The two-chunk form of the plane-marching convolution kernel (see conv_mfma.hip for the single-chunk form and
+// the common design).  Included by conv_mfma_pair.hip (3-D kernels) and conv_mfma_pair2d.hip (2-D variant), which
+// instantiate one half of the kernel table each, so that the two halves compile side by side.
+// Two input chunks per launch (layers with Cin a multiple of 64).  With one chunk per launch every extra
+// chunk costs a round trip of the fp32 partial sums through HBM (8 bytes per output value), which makes
+// wide layers bandwidth-bound.  Here a workgroup contracts 64 input channels at once and adds the two
+// halves on chip: the patch is 4 rows x 32 columns, waves 0, 1 take input chunk 0 and waves 2, 3 chunk 1
+// of the pair, each for one row group of 2 rows, with the same register-resident weights, D march and
+// fragment reuse as above.  When an output plane is complete, the chunk-1 wave writes its 2 x 16
+// accumulators to a small LDS buffer (during the next step, between its MFMAs); one step later, after the
+// step barrier, the chunk-0 wave of the same rows adds them to its own, converts and stores.  A plane
+// therefore lives in an accumulator slot for five steps (three contributing, one being handed over, one
+// being stored), hence five slots.  Layers with more than one pair still go through fp32 partial sums, but
+// half as often.
+#pragma once
+#include "conv_mfma_common.h"
+
+namespace sp3d {
+
+namespace convk {
+namespace wide {      // (inside the namespace of its constants: LOADS, PLANE_BYTES, ... mean the two-chunk kernel's)
+
+// direct-to-LDS load as in wgrad_mfma.hip: written as assembly so that the compiler neither tracks it nor
+// drains it before unrelated LDS accesses; the kernel counts the loads itself (s_waitcnt vmcnt)
+__device__ __forceinline__ void dma16(const uint16_t *src, const char *dst) {
+    const uint32_t l = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+        (const __attribute__((address_space(3))) char *)dst));
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(l) : "memory");
+}
+
+template <bool HAS_BIAS>
+struct Ctx {
+    const uint16_t *tin0;       // first padded input plane of the D chunk, at this wave's input chunk
+    size_t plane_elems;
+    int nplanes;
+    int plo, phi;               // staged planes are clamped to [plo, phi]
+    ptrdiff_t dlo, dhi;         // gathered halos: what to add for staged plane 0 / the last one (else 0)
+    int goff[LOADS];            // source offsets of the staging loads (elements)
+    bool tail_lane;             // lane has a voxel in the last (partial) load of a chunk plane
+    char *lds_stage;            // first chunk plane this wave fills, ring slot 0
+    char *red;                  // hand-over buffer of this wave's row group (buffer 0), lane part included
+    const char *wl;             // this chunk's LDS-resident weight fragments, lane part included
+    uint16_t *obase;
+    const uint16_t *mbase;
+    uint16_t *bbase;
+    float *pbase;
+    size_t oplane, orow;
+    bool okrow[RH];
+    float bv[HAS_BIAS ? 16 : 1];
+};
+
+// staging load j (0..7) of plane `dplane`: chunk plane j / 4 of this wave's two, voxels 64 (j % 4) ..
+template <bool HAS_BIAS>
+__device__ __forceinline__ void stage(const Ctx<HAS_BIAS> &c, int dplane, int j) {
+    const int dpl = min(max(dplane, c.plo), c.phi);
+    const uint16_t *p = c.tin0 + static_cast<ptrdiff_t>(dpl) * static_cast<ptrdiff_t>(c.plane_elems) +
+                        (dpl == 0 ? c.dlo : 0) + (dpl == c.nplanes - 1 ? c.dhi : 0);
+    const char *dst = c.lds_stage + (dplane % NBUF) * PLANE_BYTES + (j / CP_LOADS) * CH_STRIDE + (j % CP_LOADS) * 1024;
+    // only the last load of a chunk plane is partial (204 = 3 x 64 + 12 voxels); j is a compile-time constant
+    // at every call site, so the other loads carry no predicate
+    if (j % CP_LOADS != CP_LOADS - 1 || c.tail_lane) dma16(p + c.goff[j], dst);
+}
+
+template <bool FULL, bool HAS_BIAS>
+__device__ __forceinline__ pin_t load_partial(const Ctx<HAS_BIAS> &c, int d, int h, int q) {
+    pin_t v = pin_t{0.f, 0.f, 0.f, 0.f};
+    if (FULL || c.okrow[h]) v = *reinterpret_cast<const pin_t *>(c.pbase + part_unit(d, h, q));
+    return v;
+}
+
+template <bool FULL, bool BITS, bool HAS_BIAS>
+__device__ __forceinline__ mask_t load_mask(const Ctx<HAS_BIAS> &c, int d, int h, int q) {
+    mask_t v = mask_t{0u, 0u};
+    if (BITS) {         // the row's word, kept in unit 0
+        if (q == 0 && (FULL || c.okrow[h])) v.x = c.bbase[bits_off(c, d, h)];
+        return v;
+    }
+    if (FULL || c.okrow[h]) v = *reinterpret_cast<const mask_t *>(c.mbase + d * c.oplane + h * c.orow + 8 * q);
+    return v;
+}
+
+// chunk-0 wave: finish 4 channels of row h of plane d: own sum + the partner's (from LDS) + earlier pairs'
+// partial sums (pin, fetched at the start of the step), then store the new partial (fp32) or ReLU /
+// convert / store bf16
+template <int MODE, int RELU, bool FULL, bool HAS_BIAS>
+__device__ __forceinline__ void finish_unit(const Ctx<HAS_BIAS> &c, int d, const f32x16 (&s)[RH], const char *red,
+                                            const pin_t (&pin)[RH][4], mask_t (&mk)[RH][4], int h, int q) {
+    const float4 o = *reinterpret_cast<const float4 *>(red + (h * 4 + q) * 1024);
+    float v0 = s[h][4 * q] + o.x, v1 = s[h][4 * q + 1] + o.y, v2 = s[h][4 * q + 2] + o.z, v3 = s[h][4 * q + 3] + o.w;
+    if (MODE == kMiddle || MODE == kLast) {
+        v0 += pin[h][q].x; v1 += pin[h][q].y; v2 += pin[h][q].z; v3 += pin[h][q].w;
+    }
+    const size_t at = d * c.oplane + h * c.orow + 8 * q;
+    if (MODE == kFirst || MODE == kMiddle) {
+        if (FULL || c.okrow[h]) *reinterpret_cast<float4 *>(c.pbase + part_unit(d, h, q)) = make_float4(v0, v1, v2, v3);
+        return;
+    }
+    if (is_relu(RELU)) {
+        v0 = v0 < 0.f ? 0.f : v0; v1 = v1 < 0.f ? 0.f : v1;
+        v2 = v2 < 0.f ? 0.f : v2; v3 = v3 < 0.f ? 0.f : v3;
+    }
+    uint2 pk = make_uint2(pack2(v0, v1), pack2(v2, v3));
+    if (RELU == kMask) {
+        pk.x &= positive_halves(mk[h][q].x);
+        pk.y &= positive_halves(mk[h][q].y);
+    }
+    if (RELU == kMaskBits) {
+        const uint2 m = nibble_halves(mk[h][0].x, q);
+        pk.x &= m.x;
+        pk.y &= m.y;
+    }
+    if (FULL || c.okrow[h]) *reinterpret_cast<uint2 *>(c.obase + at) = pk;
+    if (RELU == kReluBits) {
+        // the row's word collects in the (otherwise unused) mask register of unit 0 and leaves with the last unit
+        const uint32_t n = positive_nibble(v0, v1, v2, v3) << (4 * q);
+        mk[h][0].x = q == 0 ? n : (mk[h][0].x | n);
+        if (q == 3) store_bits<FULL>(c, d, mk, h);
+    }
+}
+
+// chunk-1 wave: hand 4 channels of row h of a complete plane over to the chunk-0 wave
+__device__ __forceinline__ void give_unit(const f32x16 (&s)[RH], char *red, int h, int q) {
+    *reinterpret_cast<float4 *>(red + (h * 4 + q) * 1024) =
+        make_float4(s[h][4 * q], s[h][4 * q + 1], s[h][4 * q + 2], s[h][4 * q + 3]);
+}
+
+// One staged input plane Dp.  P = Dp mod 5: output plane Dp - kd accumulates in slot (P - kd) mod 5.
+// ROLE 1 (chunk 1): GIVE = plane Dp - 3 (slot (P + 2) mod 5) goes to the hand-over buffer Dp & 1 and its
+// slot is cleared.  ROLE 0 (chunk 0): FIN = plane Dp - 4 (slot (P + 1) mod 5) is finished from the buffer
+// written in the previous step, (Dp - 1) & 1, and its slot returns to the bias.
+// SIDE (chunk-0 wave; see side_load): kSideNone - the step loads its own partial sums / mask values (pin, mk)
+// the ordinary way; otherwise it uses the ones the previous step fetched (kSideUse) and first of all fetches
+// those of the plane that the next step finishes, Dp - 3, into the other set (npin, nmk), which the caller
+// passes through the wait that ends the step.
+template <int P, int ROLE, bool GIVE, bool FIN, int MODE, int RELU, bool FULL, int KD, int SIDE, bool HAS_BIAS>
+__device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const char *lbase,
+                                           const bf16x8 (&wf)[NFRAG], f32x16 (&acc)[NSLOT][RH],
+                                           pin_t (&pin)[RH][4], mask_t (&mk)[RH][4],
+                                           pin_t (&npin)[RH][4], mask_t (&nmk)[RH][4]) {
+    constexpr int NR = RH + 2;
+    constexpr int SSLOT = ROLE == 1 ? (P + 2) % NSLOT : (P + 1) % NSLOT;     // slot of the side work
+    constexpr int NEXT = (P + 1) % NSLOT;      // slot of output plane Dp + 1: must be clean when this step ends
+    constexpr bool ACTIVE = ROLE == 1 ? GIVE : FIN;
+    using S = Side<MODE, RELU, KD, true>;
+    bf16x8 b[2][NR];
+    char *red_w = c.red + (Dp & 1) * RED_BYTES;
+    const char *red_r = c.red + ((Dp - 1) & 1) * RED_BYTES;
+    if (ROLE == 0 && SIDE != kSideNone) {
+#pragma unroll
+        for (int h = 0; h < RH; ++h)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const size_t at = (Dp - 3) * c.oplane + h * c.orow + 8 * q;
+                if (S::PINS) side_load(npin[h][q], c.pbase + part_unit(Dp - 3, h, q));
+                if (S::MASK && !S::BITS) side_load(nmk[h][q], c.mbase + at);
+                if (S::BITS && q == 0) SP3D_SIDE_LOAD_BITS(nmk[h][0].x, c.bbase + bits_off(c, Dp - 3, h));
+            }
+    }
+    if (SIDE == kSideNone && ROLE == 0 && FIN && S::PINS) {
+#pragma unroll
+        for (int h = 0; h < RH; ++h)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) pin[h][q] = load_partial<FULL>(c, Dp - 4, h, q);
+    }
+    if (SIDE == kSideNone && ROLE == 0 && FIN && S::MASK) {
+#pragma unroll
+        for (int h = 0; h < RH; ++h)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) mk[h][q] = load_mask<FULL, S::BITS>(c, Dp - 4, h, q);
+    }
+#pragma unroll
+    for (int r = 0; r < NR; ++r) b[0][r] = *reinterpret_cast<const bf16x8 *>(lbase + (r * LCOLS) * 16);
+#pragma unroll
+    for (int gi = 0; gi < NG; ++gi) {
+        const int kw = gi >> 1, half = gi & 1;
+        if (gi + 1 < NG) {
+            const int kw2 = (gi + 1) >> 1, half2 = (gi + 1) & 1;
+#pragma unroll
+            for (int r = 0; r < NR; ++r)
+                b[(gi + 1) & 1][r] = *reinterpret_cast<const bf16x8 *>(
+                    lbase + half2 * 2 * CH_STRIDE + (r * LCOLS + kw2) * 16);
+        }
+        // the two weight fragments of this group that live in LDS (see WL_FRAGS); the MFMAs that use them are
+        // the last of the group
+        bf16x8 wl2[2];
+        if (KD == 3) {
+            wl2[0] = *reinterpret_cast<const bf16x8 *>(c.wl + wl_index(1, kw, half) * 1024);
+            wl2[1] = *reinterpret_cast<const bf16x8 *>(c.wl + wl_index(2, kw, half) * 1024);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // eight staging loads over six groups
+        stage(c, Dp + DIST, gi);
+        if (gi < 2) stage(c, Dp + DIST, NG + gi);
+        if (gi < 4) {
+            if (ACTIVE) {
+                if (ROLE == 1) {
+                    give_unit(acc[SSLOT], red_w, 0, gi);
+                    give_unit(acc[SSLOT], red_w, 1, gi);
+                } else {
+                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], red_r, pin, mk, 0, gi);
+                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], red_r, pin, mk, 1, gi);
+                }
+            }
+        } else {
+            // the slot of the next output plane starts from the bias (chunk 0) or zero (chunk 1); in the first
+            // steps it holds sums for planes that do not exist.  A handed-over slot is cleared as well.
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                acc[NEXT][gi - 4][i] = (ROLE == 0 && HAS_BIAS) ? c.bv[HAS_BIAS ? i : 0] : 0.f;
+                if (ROLE == 1 && GIVE) acc[SSLOT][gi - 4][i] = 0.f;
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh) {
+                const int h = r - kh;
+                if (h < 0 || h >= RH) continue;
+#pragma unroll
+                for (int kd = 0; kd < 3; ++kd) {
+                    if (KD == 1 && kd != 1) continue;
+                    const int slot = (P - kd + NSLOT) % NSLOT;
+                    const int f = ((kd * 3 + kh) * 3 + kw) * 2 + half;
+                    acc[slot][h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        wl_in_lds(KD, f) ? wl2[kd - 1] : wf[f], b[gi & 1][r], acc[slot][h], 0, 0, 0);
+                }
+            }
+#pragma unroll
+        for (int i = 0; i < KD * (RH + 1) * 2; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x006, 3, 0);   // up to three VALU / SALU
+            if (i % 6 == 2) __builtin_amdgcn_sched_group_barrier(0x060, 1, 0);   // a vector memory op
+        }
+    }
+}
+
+// The two steps after the last input plane: only the side work is left.  Dp = nplanes: chunk 1 hands over
+// the last output plane (Dp - 3 = dn - 1), chunk 0 finishes plane Dp - 4; Dp = nplanes + 1: chunk 0 finishes
+// the last plane.  Same slot arithmetic as plane_step, so every accumulator index stays a constant.
+template <int P, int ROLE, bool GIVE, bool FIN, int MODE, int RELU, bool FULL, int KD, int SIDE, bool HAS_BIAS>
+__device__ __forceinline__ void drain_step(const Ctx<HAS_BIAS> &c, int Dp, f32x16 (&acc)[NSLOT][RH],
+                                           pin_t (&pin)[RH][4], mask_t (&mk)[RH][4],
+                                           pin_t (&npin)[RH][4], mask_t (&nmk)[RH][4]) {
+    constexpr int SSLOT = ROLE == 1 ? (P + 2) % NSLOT : (P + 1) % NSLOT;
+    using S = Side<MODE, RELU, KD, true>;
+    // side loads: the first drain step, and a step 3 that is one already (a march of three planes), fetch for
+    // the step after them like a plane step
+    if (ROLE == 0 && SIDE != kSideNone && Dp <= c.nplanes) {
+#pragma unroll
+        for (int h = 0; h < RH; ++h)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const size_t at = (Dp - 3) * c.oplane + h * c.orow + 8 * q;
+                if (S::PINS) side_load(npin[h][q], c.pbase + part_unit(Dp - 3, h, q));
+                if (S::MASK && !S::BITS) side_load(nmk[h][q], c.mbase + at);
+                if (S::BITS && q == 0) SP3D_SIDE_LOAD_BITS(nmk[h][0].x, c.bbase + bits_off(c, Dp - 3, h));
+            }
+    }
+    if (ROLE == 1) {
+        if (GIVE && Dp == c.nplanes) {
+            char *red_w = c.red + (Dp & 1) * RED_BYTES;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                give_unit(acc[SSLOT], red_w, 0, q);
+                give_unit(acc[SSLOT], red_w, 1, q);
+            }
+        }
+    } else if (FIN) {
+        const char *red_r = c.red + ((Dp - 1) & 1) * RED_BYTES;
+        if (SIDE == kSideNone && S::PINS) {
+#pragma unroll
+            for (int h = 0; h < RH; ++h)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) pin[h][q] = load_partial<FULL>(c, Dp - 4, h, q);
+        }
+        if (SIDE == kSideNone && S::MASK) {
+#pragma unroll
+            for (int h = 0; h < RH; ++h)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) mk[h][q] = load_mask<FULL, S::BITS>(c, Dp - 4, h, q);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], red_r, pin, mk, 0, q);
+            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], red_r, pin, mk, 1, q);
+        }
+    }
+}
+
+template <int ROLE, int MODE, bool HAS_BIAS, int RELU, int KD>
+__device__ __forceinline__ void run(const ConvArgs &a, char *lds, int logical, int tile, const TileBox &bx, int d0,
+                                    int h0, int w0, int dn, int cj, int rg) {
+    const Geo &g = a.g;
+    const int lane = threadIdx.x & 63;
+    const int col = lane & 31, hi = lane >> 5;
+
+    bf16x8 wf[NFRAG];
+    {
+        const uint4 *wp = a.wpack + static_cast<size_t>(ROLE) * a.nco * NFRAG * 64;     // chunk ROLE of the pair
+#pragma unroll
+        for (int f = 0; f < NFRAG; ++f) {
+            if (KD == 1 && f / 18 != 1) continue;
+            const uint4 q = wp[(cj * NFRAG + f) * 64 + lane];
+            if (wl_in_lds(KD, f)) {      // both waves of a chunk write the same bytes
+                const int tap = f / 2;
+                *reinterpret_cast<uint4 *>(lds + WL_BASE + (ROLE * WL_FRAGS + wl_index(tap / 9, tap % 3, f & 1)) * 1024 +
+                                           lane * 16) = q;
+            } else {
+                wf[f] = *reinterpret_cast<const bf16x8 *>(&q);
+            }
+        }
+    }
+
+    Ctx<HAS_BIAS> c;
+    const uint16_t *src = ROLE ? a.in2 : a.in;
+    const int src_cs = ROLE ? a.in2_cs : a.in_cs, src_co = ROLE ? a.in2_co : a.in_co;
+    const int F = KD == 1 ? a.fold : 1;         // slices side by side (see fold_col); dn counts output steps
+    const size_t plane_real = static_cast<size_t>(g.ph) * g.pw * src_cs;
+    c.plane_elems = plane_real * F;
+    c.tin0 = src + (static_cast<size_t>(tile) * g.tile_vox + bx.org) * src_cs + d0 * plane_real + src_co -
+             static_cast<ptrdiff_t>(F - 1) * static_cast<ptrdiff_t>(plane_real);
+    c.nplanes = dn + 2;
+    c.plo = F > 1 ? 1 : 0;
+    c.phi = F > 1 ? c.nplanes - 2 : c.nplanes - 1;
+    // this wave fills chunk planes 2 rg and 2 rg + 1 (channels 16 rg .. 16 rg + 15) of its input chunk
+#pragma unroll
+    for (int j = 0; j < LOADS; ++j) {
+        const int v = 64 * (j % CP_LOADS) + lane;
+        const FoldCol fc = fold_col(v % LCOLS, F, a.fold_w);
+        const int row = min(h0 + v / LCOLS, bx.bh + 1), colv = min(w0 + fc.c, bx.bw + 1);
+        c.goff[j] = ((min(fc.s, F - 1) * g.ph + row) * g.pw + colv) * src_cs + (2 * rg + j / CP_LOADS) * 8;   // always addressable
+    }
+    c.dlo = c.dhi = 0;
+    if (a.gather) {          // see GatherShift
+        const GatherShift gs = gather_shift(g, tile, src_cs);
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) {
+            const int v = 64 * (j % CP_LOADS) + lane;
+            const int row = min(h0 + v / LCOLS, bx.bh + 1), colv = min(w0 + v % LCOLS, bx.bw + 1);
+            c.goff[j] += (row == 0 ? gs.hm : 0) + (row == g.th + 1 ? gs.hp : 0) + (colv == 0 ? gs.wm : 0) +
+                         (colv == g.tw + 1 ? gs.wp : 0);
+        }
+        if (d0 == 0) c.dlo = gs.dm;
+        if (d0 + dn == g.td) c.dhi = gs.dp;
+    }
+    c.tail_lane = 64 * (CP_LOADS - 1) + lane < PLANE_VOX;
+    c.lds_stage = lds + ROLE * CHUNK_BYTES + 2 * rg * CH_STRIDE;
+    c.red = lds + RING_BYTES + rg * (RH * 4 * 1024) + lane * 16;
+    c.wl = lds + WL_BASE + ROLE * WL_FRAGS * 1024 + lane * 16;
+    const OutDst od = out_dest(a, cj);
+    const FoldCol oc = fold_col(col, F, a.fold_w);
+    c.orow = static_cast<size_t>(g.pw) * od.cs;
+    c.oplane = static_cast<size_t>(g.ph) * c.orow * F;
+    const size_t ovox = static_cast<size_t>(tile) * g.tile_vox + bx.org +
+                        (static_cast<size_t>(d0 + 1 + min(oc.s, F - 1)) * g.ph + h0 + rg * RH + 1) * g.pw + w0 +
+                        oc.c + 1;
+    const size_t opos = ovox * od.cs + od.co + 4 * hi;
+    c.obase = od.base + opos;
+    c.mbase = a.mask + opos;
+    c.bbase = a.bits + (ovox * a.nco + cj) * 2 + hi;
+    // the chunk-0 wave of row group rg of workgroup `logical`: dchunk planes x RH rows x 4 units x 1 KB
+    c.pbase = a.part + (static_cast<size_t>(logical) * NRG + rg) * a.dchunk * (RH * 4 * 256) + lane * 4;
+#pragma unroll
+    for (int h = 0; h < RH; ++h) c.okrow[h] = h0 + rg * RH + h < bx.bh && w0 + oc.c < bx.bw && oc.s < F;
+    if (HAS_BIAS) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) c.bv[HAS_BIAS ? i : 0] = a.bias[C * cj + 8 * (i >> 2) + 4 * hi + (i & 3)];
+    }
+    // the bias is folded into the chunk-0 accumulators; chunk-1 accumulators start from zero
+    f32x16 acc[NSLOT][RH];
+#pragma unroll
+    for (int s = 0; s < NSLOT; ++s)
+#pragma unroll
+        for (int h = 0; h < RH; ++h)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[s][h][i] = (ROLE == 0 && HAS_BIAS) ? c.bv[HAS_BIAS ? i : 0] : 0.f;
+
+    const char *lbase = lds + ROLE * CHUNK_BYTES + hi * CH_STRIDE + (rg * RH * LCOLS + col) * 16;
+    const int nplanes = c.nplanes;
+
+#pragma unroll
+    for (int i = 0; i < DIST; ++i)
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) stage(c, i, j);
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");      // staged planes and the parked weight fragments
+    __builtin_amdgcn_s_barrier();
+
+    // End of a step: plane Dp + 1 has landed when at most the loads of planes Dp + 2, Dp + 3 are in flight
+    // (loads complete in order; stores share the counter and only make the wait stricter), and this wave's
+    // hand-over writes have reached LDS.
+#define SP3D_STEP_END()                                                                        \
+    do {                                                                                       \
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((DIST - 1) * LOADS) : "memory");   \
+        __builtin_amdgcn_s_barrier();                                                          \
+    } while (0)
+
+    auto march = [&](auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        using S = Side<MODE, RELU, KD, true>;
+        // whole patches: the chunk-0 wave fetches its partial sums / mask values one step ahead (see side_load),
+        // alternating between two sets of registers
+        constexpr bool ASYNC = FULL && ROLE == 0 && S::ASYNC;
+        constexpr int FETCH = ASYNC ? kSideFetch : kSideNone, USE = ASYNC ? kSideUse : kSideNone;
+        pin_t pinA[RH][4], pinB[RH][4];
+        mask_t mkA[RH][4], mkB[RH][4];
+        // A step that finishes a plane issues LOADS + 8 operations after its side loads, which the wait at its
+        // end lets stay in flight; a fetch-only step issues just its staging loads after them and waits
+        // accordingly; a drain step issues no staging loads and waits for everything.
+        static_assert(LOADS + 8 >= (DIST - 1) * LOADS, "side loads must be older than what the step-end wait lets stay in flight");
+#define SP3D_STEP_END_SIDE(NV, NP, NM)                                              \
+    do {                                                                            \
+        side_fence<NV, true, ASYNC && S::PINS, ASYNC && S::MASK, ASYNC && S::BITS>(NP, NM); \
+        __builtin_amdgcn_s_barrier();                                               \
+    } while (0)
+        plane_step<0, ROLE, false, false, MODE, RELU, FULL, KD, kSideNone>(c, 0, lbase, wf, acc, pinA, mkA, pinB, mkB);
+        SP3D_STEP_END();
+        plane_step<1, ROLE, false, false, MODE, RELU, FULL, KD, kSideNone>(c, 1, lbase + PLANE_BYTES, wf, acc, pinA, mkA,
+                                                                          pinB, mkB);
+        SP3D_STEP_END();
+        plane_step<2, ROLE, false, false, MODE, RELU, FULL, KD, kSideNone>(c, 2, lbase + 2 * PLANE_BYTES, wf, acc, pinA,
+                                                                          mkA, pinB, mkB);
+        SP3D_STEP_END();
+        // Steps 3, 4, ... with slot phase Dp mod 5 as a compile-time constant (the ring slot Dp mod 4 is a
+        // run-time offset: a period of 20 steps would be needed to make both constants).  The march runs two
+        // steps past the last input plane; those only hand over / finish what is left.  Step 3 is the first
+        // to hand a plane over (and fetches the side values of step 4), step 4 the first to finish one.
+#define SP3D_STEP(DP, PHASE, GIVE_EN, FIN_EN, SIDE_EN, CP, CM, NP, NM)                                     \
+    if ((DP) < nplanes) {                                                                                  \
+        plane_step<PHASE, ROLE, GIVE_EN, FIN_EN, MODE, RELU, FULL, KD, SIDE_EN>(                           \
+            c, (DP), lbase + ((DP) % NBUF) * PLANE_BYTES, wf, acc, CP, CM, NP, NM);                        \
+        SP3D_STEP_END_SIDE(((SIDE_EN) == kSideFetch ? LOADS : (DIST - 1) * LOADS), NP, NM);                \
+    } else if ((DP) < nplanes + 2) {                                                                       \
+        drain_step<PHASE, ROLE, GIVE_EN, FIN_EN, MODE, RELU, FULL, KD, SIDE_EN>(c, (DP), acc, CP, CM, NP, NM); \
+        SP3D_STEP_END_SIDE(((SIDE_EN) == kSideNone ? (DIST - 1) * LOADS : 0), NP, NM);                     \
+    }
+        SP3D_STEP(3, 3, true, false, FETCH, pinA, mkA, pinB, mkB)
+        SP3D_STEP(4, 4, true, true, USE, pinB, mkB, pinA, mkA)
+        for (int D = 5; D < nplanes + 2; D += NSLOT) {
+            SP3D_STEP(D, 0, true, true, USE, pinA, mkA, pinB, mkB)
+            SP3D_STEP(D + 1, 1, true, true, USE, pinB, mkB, pinA, mkA)
+            SP3D_STEP(D + 2, 2, true, true, USE, pinA, mkA, pinB, mkB)
+            SP3D_STEP(D + 3, 3, true, true, USE, pinB, mkB, pinA, mkA)
+            SP3D_STEP(D + 4, 4, true, true, USE, pinA, mkA, pinB, mkB)
+            // five steps per round: the sets have changed roles
+            if (ASYNC) {
+#pragma unroll
+                for (int h = 0; h < RH; ++h)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const pin_t tp = pinA[h][q]; pinA[h][q] = pinB[h][q]; pinB[h][q] = tp;
+                        const mask_t tm = mkA[h][q]; mkA[h][q] = mkB[h][q]; mkB[h][q] = tm;
+                    }
+            }
+        }
+#undef SP3D_STEP
+#undef SP3D_STEP_END_SIDE
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // clamped staging loads of the last steps
+    };
+    if (h0 + PH <= bx.bh && w0 + PW <= bx.bw) march(std::true_type{});
+    else march(std::false_type{});
+#undef SP3D_STEP_END
+}
+
+template <int MODE, bool HAS_BIAS, int RELU, int KD>
+__global__ __launch_bounds__(kThreads, 1) void conv_mfma_pair_kernel(ConvArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const Geo &g = a.g;
+    const int per_xcd = gridDim.x >> 3;
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= a.nblocks) return;
+    int t = logical;
+    const int cj = t % a.nco; t /= a.nco;
+    const int pw_i = t % a.nw; t /= a.nw;
+    const int ph_i = t % a.nh; t /= a.nh;
+    const int pd_i = t % a.nd; t /= a.nd;
+    const int tile = t;
+    const int d0 = pd_i * a.dchunk, h0 = ph_i * PH, w0 = pw_i * PW;
+    const TileBox bx = tile_box(g, tile);
+    const int dn = min(a.dchunk, bx.bd - d0);
+    if (dn <= 0 || h0 >= bx.bh || w0 >= bx.bw) return;     // patch of the largest box that this tile's box lacks
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // two copies of the march, one per role, so that each is straight-line code for the scheduler
+    const int dsteps = KD == 1 ? dn / a.fold : dn;       // slices side by side: a step produces `fold` of them
+    if (wave < 2) run<0, MODE, HAS_BIAS, RELU, KD>(a, lds, logical, tile, bx, d0, h0, w0, dsteps, cj, wave & 1);
+    else run<1, MODE, HAS_BIAS, RELU, KD>(a, lds, logical, tile, bx, d0, h0, w0, dsteps, cj, wave & 1);
+}
+
+}  // namespace wide
+}  // namespace convk
+
+}  // namespace sp3d
