@@ -198,14 +198,15 @@ __device__ __forceinline__ void side_fence(pin_t (&p)[2][4], mask_t (&m)[2][4]) 
 #undef SP3D_SIDE8
 #undef SP3D_SIDE2
 // What a kernel variant fetches per store unit besides its operands, and whether it does so by side loads.
-// Measured: the mask gains from them (3-D 32 -> 32 at 512^3: 7.45 -> 7.08 ms; 2-D: 8 - 9 %) except in the 3-D
-// two-chunk kernel, whose registers are all taken (4.07 -> 4.71 ms with them); the partial sums do not gain
-// (their cost was the access pattern, see part_unit), so they stay ordinary loads.
+// Measured: the mask gains from them (3-D 32 -> 32 at 512^3: 7.45 -> 7.08 ms; 2-D: 8 - 9 %; the 3-D two-chunk
+// kernel 3 %, now that part of its weight fragments live in LDS - while its registers were all taken the second
+// register set cost 4.07 -> 4.71 ms); the partial sums do not gain (their cost was the access pattern, see
+// part_unit), so they stay ordinary loads.
 template <int MODE, int RELU, int KD, bool PAIR> struct Side {
     static constexpr bool PINS = MODE == kMiddle || MODE == kLast;
     static constexpr bool MASK = (RELU == kMask || RELU == kMaskBits) && (MODE == kSingle || MODE == kLast);
     static constexpr bool BITS = MASK && RELU == kMaskBits;      // one 16-bit word per row instead of 4 x 8 bytes
-    static constexpr bool ASYNC = MASK && !PINS && (KD == 1 || !PAIR || BITS);
+    static constexpr bool ASYNC = MASK && !PINS;
 };
 // Role of a step in the chain of side loads.
 enum SideStep { kSideNone = 0,     // no side loads (nothing to fetch, or a ragged patch)
