@@ -1,6 +1,6 @@
-// bf16 3x3 convolution of the 2-D variant (geometry flag `flat`) for wide layers on few voxels - the bottom
-// levels of the 2-D U-Net (Sec. 3: 512 and 1024 filters on tiles of 16 x 16 voxels and less) - as an
-// output-stationary implicit GEMM on the gfx950 matrix cores.  Serves conv3d_fwd and, on weights packed with
+// bf16 3x3 (2-D variant, geometry flag `flat`) and 3x3x3 convolution for wide layers on few voxels - the bottom
+// levels of the 2-D U-Net (Sec. 3: 512 and 1024 filters on tiles of 16 x 16 voxels and less) and the 16^3 level of
+// the 3-D one - as an output-stationary implicit GEMM on the gfx950 matrix cores.  Serves conv3d_fwd and, on weights packed with
 // mirrored taps and swapped channel roles, conv3d_dgrad, like the plane-marching kernels of conv_mfma.hip.
 //
 // Why a second kernel family.  The marching kernels keep the weights of ONE pair of input chunks in
@@ -10,8 +10,8 @@
 // channels, keeps their sums in registers (8 accumulators of 32 x 32 per wave) over ALL taps and input
 // channels, and streams the weights: one launch per layer, no partial sums, and voxels are numbered across
 // rows, slices and tiles, so every MFMA column is a real voxel whatever the tile shape.  (With the 3x3x3 kernel
-// the marching kernels do three times the MFMAs per staged byte and stay ahead: measured, 32^3 voxels at 512
-// channels 0.72 ms against 0.97 ms here; so this family serves the 2-D variant only.)
+// the marching kernels do three times the MFMAs per staged byte; they are level with this family at 32^3 voxels
+// and ahead beyond, so in 3-D it serves the smallest level only: see conv_gemm_preferred.)
 //
 // Operands (v_mfma_f32_32x32x16_bf16, A = weights [32 output channels][16 input channels], B = voxels
 // [16 input channels][32 voxels]).  B: lane l supplies voxel l % 32, channels 8 (l / 32) .. + 7 of the
@@ -51,8 +51,10 @@ constexpr int STAGE_U4 = STAGE_FRAGS * 64;       // in 16-byte pieces: 6 per thr
 constexpr int STAGE_LOADS = STAGE_U4 / kThreads;
 constexpr int STAGE_BYTES = STAGE_FRAGS * 1024;
 constexpr int LDS_BYTES = 2 * STAGE_BYTES;       // 49152
-constexpr int NROWS = 3;                         // kernel rows
-constexpr int NTAP_PACK = 27, TAP0 = 9;          // packed weights: 27 tap slots per (chunk, block), the 3x3 kernel in 9 .. 17
+constexpr int NTAP_PACK = 27;                    // packed weights: 27 tap slots per (chunk, block); the 3x3 kernel of the
+                                                 // 2-D variant sits in 9 .. 17 (the taps with kd = 1)
+// kernel rows (kd, kh) of a K loop: 3 in the 2-D variant (KD = 1), 9 in 3-D (KD = 3)
+constexpr int nrows(int KD) { return 3 * KD; }
 
 enum Epilogue { kNone = 0, kRelu = 1, kMask = 2 };
 
@@ -104,23 +106,29 @@ __device__ __forceinline__ InSrc in_src(const GemmArgs &a, int i) {
     return InSrc{a.in, a.in_cs, c0};
 }
 
-// Voxel offset of kernel row kh at kw = 0, relative to the output voxel.
-__device__ __forceinline__ long long row_offset(const Ctx &c, int kh) { return (kh - 1) * c.row - 1; }
+// Voxel offset of kernel row r (= kh in the 2-D variant, 3 kd + kh in 3-D) at kw = 0, relative to the output voxel.
+template <int KD>
+__device__ __forceinline__ long long row_offset(const Ctx &c, int r) {
+    if (KD == 1) return (r - 1) * c.row - 1;
+    const int kd = r / 3, kh = r - 3 * kd;
+    return (kd - 1) * c.plane + (kh - 1) * c.row - 1;
+}
 
 // next K step, clamped to the last one.  Kernel rows outermost, chunks inside: a voxel's record of two
 // neighbouring chunks is one 128-byte line, so the second chunk finds in the vector cache what the first fetched
+template <int KD>
 __device__ __forceinline__ void advance(const GemmArgs &a, int &i, int &r) {
     int ni = i + 1, nr = r;
     if (ni == a.nci) { ni = 0; ++nr; }
-    if (nr < NROWS) { i = ni; r = nr; }
+    if (nr < nrows(KD)) { i = ni; r = nr; }
 }
 
 // Issue the loads of K step (chunk i, row r): this thread's share of the 24 weight fragments (to registers, on
 // their way to LDS) and this lane's B fragments of the step.
-template <int VB>
+template <int VB, int KD>
 __device__ __forceinline__ void fetch(const GemmArgs &a, const Ctx &c, int i, int r, u32x4 (&areg)[STAGE_LOADS],
                                       bf16x8 (&b)[VB][ROW][2]) {
-    const int tap0 = TAP0 + ROW * r;
+    const int tap0 = (KD == 1 ? 9 : 0) + ROW * r;
 #pragma unroll
     for (int j = 0; j < STAGE_LOADS; ++j) {
         const int e = j * kThreads + c.tid;                     // piece of the stage
@@ -129,7 +137,7 @@ __device__ __forceinline__ void fetch(const GemmArgs &a, const Ctx &c, int i, in
         areg[j] = reinterpret_cast<const u32x4 *>(a.wpack)[frag0 * 64 + x];
     }
     const InSrc src = in_src(a, i);
-    const long long ro = row_offset(c, r);
+    const long long ro = row_offset<KD>(c, r);
 #pragma unroll
     for (int s = 0; s < VB; ++s) {
         const uint16_t *p = src.base + (c.pv[s] + ro) * src.cs + src.co + 8 * c.hi;
@@ -167,20 +175,20 @@ __device__ __forceinline__ void contract(const char *abuf, int lane, const bf16x
 // step j - 1 into `aw`, go to the other LDS stage, which every wave left at the barrier that ended step j - 1.
 // (i, r) = chunk and kernel row of step j + 2; past the last step it stays there: those loads are harmless,
 // and what they fill is never read.
-template <int VB>
+template <int VB, int KD>
 __device__ __forceinline__ void step(const GemmArgs &a, const Ctx &c, char *cur, char *other, int lane, int &i, int &r,
                                      const bf16x8 (&bc)[VB][ROW][2], bf16x8 (&bn)[VB][ROW][2],
                                      const u32x4 (&aw)[STAGE_LOADS], u32x4 (&an)[STAGE_LOADS], f32x16 (&acc)[CB][VB]) {
-    fetch(a, c, i, r, an, bn);
+    fetch<VB, KD>(a, c, i, r, an, bn);
     contract(cur, lane, bc, acc);
     u32x4 *dst = reinterpret_cast<u32x4 *>(other);
 #pragma unroll
     for (int j = 0; j < STAGE_LOADS; ++j) dst[j * kThreads + c.tid] = aw[j];
     __syncthreads();
-    advance(a, i, r);
+    advance<KD>(a, i, r);
 }
 
-template <int RELU, bool HAS_BIAS, int VB>
+template <int RELU, bool HAS_BIAS, int VB, int KD>
 __global__ __launch_bounds__(kThreads, 1) void conv_gemm_kernel(GemmArgs a) {
     extern __shared__ __align__(16) char lds[];
     // workgroups of one XCD (blockIdx % 8) get consecutive logical ids: they share output blocks, i.e. weights
@@ -234,24 +242,24 @@ __global__ __launch_bounds__(kThreads, 1) void conv_gemm_kernel(GemmArgs a) {
     u32x4 a0[STAGE_LOADS], a1[STAGE_LOADS];
     char *const s0 = lds, *const s1 = lds + STAGE_BYTES;
     int i = 0, r = 0;
-    fetch(a, c, i, r, a0, b0);
-    advance(a, i, r);
+    fetch<VB, KD>(a, c, i, r, a0, b0);
+    advance<KD>(a, i, r);
     {
         u32x4 *dst = reinterpret_cast<u32x4 *>(s0);
 #pragma unroll
         for (int j = 0; j < STAGE_LOADS; ++j) dst[j * kThreads + tid] = a0[j];
     }
-    fetch(a, c, i, r, a1, b1);
-    advance(a, i, r);
+    fetch<VB, KD>(a, c, i, r, a1, b1);
+    advance<KD>(a, i, r);
     __syncthreads();
-    const int nk = a.nci * NROWS;
+    const int nk = a.nci * nrows(KD);
     for (int k = 0; k < nk; k += 6) {
-        step(a, c, s0, s1, lane, i, r, b0, b2, a1, a0, acc);
-        step(a, c, s1, s0, lane, i, r, b1, b0, a0, a1, acc);
-        step(a, c, s0, s1, lane, i, r, b2, b1, a1, a0, acc);
-        step(a, c, s1, s0, lane, i, r, b0, b2, a0, a1, acc);
-        step(a, c, s0, s1, lane, i, r, b1, b0, a1, a0, acc);
-        step(a, c, s1, s0, lane, i, r, b2, b1, a0, a1, acc);
+        step<VB, KD>(a, c, s0, s1, lane, i, r, b0, b2, a1, a0, acc);
+        step<VB, KD>(a, c, s1, s0, lane, i, r, b1, b0, a0, a1, acc);
+        step<VB, KD>(a, c, s0, s1, lane, i, r, b2, b1, a1, a0, acc);
+        step<VB, KD>(a, c, s1, s0, lane, i, r, b0, b2, a0, a1, acc);
+        step<VB, KD>(a, c, s0, s1, lane, i, r, b1, b0, a1, a0, acc);
+        step<VB, KD>(a, c, s1, s0, lane, i, r, b2, b1, a0, a1, acc);
     }
 
     // epilogue: ReLU / mask, convert, 8-byte stores (4 channels of a voxel)
@@ -291,15 +299,20 @@ Box max_box(const Geo &g) { return Box{g.td + 2 * grow_d(g), g.th + 2 * g.grow, 
 
 }  // namespace
 
-// Layers this family takes over from the plane-marching kernels (measured on 16 slices; old -> new): 512 channels
-// on 32 x 32 voxels 0.37 -> 0.21 ms, 1024 on 32 x 32 1.30 -> 0.70 ms, 1024 on 16 x 16 0.48 -> 0.37 ms; at 256
-// channels the marching kernels are as fast.  The criterion looks at the tile interiors only, so a layer is
-// served by the same family whatever its output box growth.
+// Layers this family takes over from the plane-marching kernels.  2-D variant (measured on 16 slices; marching ->
+// here, before this kernel's weight pieces left scratch memory): 512 channels on 32 x 32 voxels 0.37 -> 0.21 ms, 1024
+// on 32 x 32 1.30 -> 0.70 ms, 1024 on 16 x 16 0.48 -> 0.37 ms; at 256 channels the marching kernels are as fast.  3-D:
+// the bottom level of a deep network only - 1024 channels on 16^3 voxels 0.80 -> 0.40 ms on a 2 x 2 x 1 grid and 1.01 ->
+// 0.39 ms on 4 x 4 x 1 (tiles of 4 x 4 x 16 voxels leave most of a marching patch empty; here every MFMA column is a real
+// voxel), 512 -> 1024 0.37 -> 0.19 ms; on 32^3 voxels (512 channels) the two families are level (0.55 - 0.64 ms either way)
+// and on 64^3 the marching kernels win, because a staged plane feeds 27 taps there and 9 here.  The criterion looks
+// at the tile interiors only, so a layer is served by the same family whatever its output box growth.
 bool conv_gemm_preferred(const Geo &g, int ki, int ko) {
     const long long nint = 1LL * g.ntiles * g.int_vox;
     const Box b = max_box(g);
     const long long nbox = 1LL * g.ntiles * b.ed * b.eh * b.ew;
-    return g.flat && ki >= 512 && ki % (2 * C) == 0 && ko % (C * CB) == 0 && nint <= (1 << 16) && nbox < (1LL << 30);
+    if (ki < 512 || ki % (2 * C) != 0 || ko % (C * CB) != 0 || nbox >= (1LL << 30)) return false;
+    return nint <= (g.flat ? (1 << 16) : (1 << 13));
 }
 
 // wpack: the layer's weights in the fragment order of conv_mfma.hip (already packed, in the workspace).
@@ -350,14 +363,16 @@ int launch_conv_gemm(const void *Pin, const void *wpack, const float *bias, void
     a.nblocks = a.nvg * (a.nco / CB);
     const unsigned grid = static_cast<unsigned>((a.nblocks + 7) / 8 * 8);
     using Kern = void (*)(GemmArgs);
-    // [segments per wave - 1][bias][epilogue]; a bias never comes with a mask
-    static const Kern kern[2][2][3] = {
-        {{conv_gemm_kernel<kNone, false, 1>, conv_gemm_kernel<kRelu, false, 1>, conv_gemm_kernel<kMask, false, 1>},
-         {conv_gemm_kernel<kNone, true, 1>, conv_gemm_kernel<kRelu, true, 1>, conv_gemm_kernel<kMask, false, 1>}},
-        {{conv_gemm_kernel<kNone, false, 2>, conv_gemm_kernel<kRelu, false, 2>, conv_gemm_kernel<kMask, false, 2>},
-         {conv_gemm_kernel<kNone, true, 2>, conv_gemm_kernel<kRelu, true, 2>, conv_gemm_kernel<kMask, false, 2>}}};
+    // [3-D][segments per wave - 1][bias][epilogue]; a bias never comes with a mask
+#define SP3D_GEMM_TABLE(KD)                                                                                             \
+    {{{conv_gemm_kernel<kNone, false, 1, KD>, conv_gemm_kernel<kRelu, false, 1, KD>, conv_gemm_kernel<kMask, false, 1, KD>},  \
+      {conv_gemm_kernel<kNone, true, 1, KD>, conv_gemm_kernel<kRelu, true, 1, KD>, conv_gemm_kernel<kMask, false, 1, KD>}},   \
+     {{conv_gemm_kernel<kNone, false, 2, KD>, conv_gemm_kernel<kRelu, false, 2, KD>, conv_gemm_kernel<kMask, false, 2, KD>},  \
+      {conv_gemm_kernel<kNone, true, 2, KD>, conv_gemm_kernel<kRelu, true, 2, KD>, conv_gemm_kernel<kMask, false, 2, KD>}}}
+    static const Kern kern[2][2][2][3] = {SP3D_GEMM_TABLE(1), SP3D_GEMM_TABLE(3)};
+#undef SP3D_GEMM_TABLE
     const int epi = mask ? kMask : (relu ? kRelu : kNone);
-    hipLaunchKernelGGL(kern[vb - 1][bias ? 1 : 0][epi], dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
+    hipLaunchKernelGGL(kern[g.flat ? 0 : 1][vb - 1][bias ? 1 : 0][epi], dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
     return record_hip(hipGetLastError());
 }
 
