@@ -439,7 +439,51 @@ def test_configuration_5_layers_real_size(cin, cout, edge):
     else:
         sp3d.conv3d_fwd(Pa, w_dev, b_dev, Py, g, ct, cout, dt, sp3d.SP_FLAG_RELU, L.ws[sp3d.SP_OP_FWD])
     compare(L.volume(Py, cout), lambda b: conv3d.conv3d_fwd(x, Wd, bd, relu=True, box=b), "fwd")
-    del Py
+    # The options of the same call, at the same size, must reproduce that result bit for bit: the one-bit ReLU mask
+    # written beside it, and margins gathered from the neighbour tiles (the input's margins towards neighbours are
+    # overwritten with NaN for that run: nothing may read them).
+    gg = g.with_opts(sp3d.SP_HALO_GATHER)
+    gathers = all(sp3d.sp_gather_supported(op, g, ct, cout, dt) for op in (sp3d.SP_OP_FWD, sp3d.SP_OP_DGRAD))
+    Py2 = sp3d.alloc_padded(g, cout, dt)
+    ybits = None
+    if sp3d.sp_relu_bits_supported(sp3d.SP_OP_FWD, g, ct, cout, dt):
+        ybits = torch.zeros(sp3d.sp_relu_bits_bytes(g, cout) // 2, dtype=torch.int16, device="cuda")
+        if two:
+            sp3d.conv3d_fwd2_bits(Pa, ca, Pb, cb, w_dev, b_dev, Py2, ybits, g, cout, dt, sp3d.SP_FLAG_RELU, L.ws[sp3d.SP_OP_FWD])
+        else:
+            sp3d.conv3d_fwd_bits(Pa, w_dev, b_dev, Py2, ybits, g, ct, cout, dt, sp3d.SP_FLAG_RELU, L.ws[sp3d.SP_OP_FWD])
+        assert torch.equal(Py, Py2), "forward with the mask bits written"
+        ref_bits = torch.zeros_like(ybits)
+        sp3d.sp_relu_bits(Py, ref_bits, g, cout, dt)
+        inner = (slice(None),) * 4 + (slice(1, -1),) * 3
+        shape = tuple(g.padded_shape) + (cout // 32, 2)
+        assert torch.equal(ybits.view(shape)[inner], ref_bits.view(shape)[inner]), "mask bits of the forward pass"
+        progress("c5 layer %s -> %d at %d^3: forward with mask bits bit-identical" % (cin, cout, edge))
+    if gathers:
+        def poisoned(P):
+            Q = P.clone()
+            for ax, gdim in ((1, g.gd), (2, g.gh), (3, g.gw)):       # margins towards a neighbour tile, per axis
+                for t in range(gdim):
+                    idx = [slice(None)] * Q.dim()
+                    idx[ax] = t
+                    if t > 0:
+                        idx[ax + 3] = 0
+                        Q[tuple(idx)] = float("nan")
+                    if t < gdim - 1:
+                        idx[ax + 3] = -1
+                        Q[tuple(idx)] = float("nan")
+            return Q
+        Qa = poisoned(Pa)
+        if two:
+            Qb = poisoned(Pb)
+            sp3d.conv3d_fwd2(Qa, ca, Qb, cb, w_dev, b_dev, Py2, gg, cout, dt, sp3d.SP_FLAG_RELU, L.ws[sp3d.SP_OP_FWD])
+            del Qb
+        else:
+            sp3d.conv3d_fwd(Qa, w_dev, b_dev, Py2, gg, ct, cout, dt, sp3d.SP_FLAG_RELU, L.ws[sp3d.SP_OP_FWD])
+        assert torch.equal(Py, Py2), "forward with gathered halos"
+        del Qa
+        progress("c5 layer %s -> %d at %d^3: forward with gathered halos bit-identical" % (cin, cout, edge))
+    del Py, Py2, ybits
 
     # data gradient (plain), then with the ReLU mask of the layer input applied in the store
     ref_dx = {}
@@ -467,6 +511,14 @@ def test_configuration_5_layers_real_size(cin, cout, edge):
             compare(dx_mask, lambda b: np.where(widen(crop(x, b)) > 0, dgrad_ref(b), 0.0), "dgrad_relu")
             keep = to_dev(x).float() > 0
             assert torch.equal(dx_mask, torch.where(keep, dx_plain, torch.zeros_like(dx_plain)))
+            if sp3d.sp_relu_bits_supported(sp3d.SP_OP_DGRAD, g, ct, cout, dt):      # the mask as bits
+                xbits = torch.zeros(sp3d.sp_relu_bits_bytes(g, ct) // 2, dtype=torch.int16, device="cuda")
+                sp3d.sp_relu_bits(Pa, xbits, g, ct, dt)
+                Pdb2 = sp3d.alloc_padded(g, ct, dt)
+                sp3d.conv3d_dgrad_bits(Pz, w_dev, xbits, Pdb2, g, ct, cout, dt, L.ws[sp3d.SP_OP_DGRAD])
+                assert torch.equal(L.volume(Pdb2, ct), dx_mask), "data gradient masked by bits"
+                del xbits, Pdb2
+                progress("c5 layer %s -> %d at %d^3: data gradient masked by bits bit-identical" % (cin, cout, edge))
             del Pdm, dx_mask, keep
         del Pdx, dx_plain
     ref_dx.clear()
