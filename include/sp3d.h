@@ -158,8 +158,8 @@ int sp_halo_exchange(void *P, const sp_geom_t *g, int c, sp_dtype_t dt, void *st
  * for every interior voxel v of every tile (v in padded coordinates minus halo, so tap (1,1,1)
  * is the voxel itself): the 'valid' cross-correlation of each padded tile, which equals the
  * zero-padded 'same' convolution of the whole volume once halo_unpack has run on Px.
- * Writes y = z (or max(z,0) with SP_FLAG_RELU) into the interiors of Py; Py's margins are left
- * as they are.  bias may be NULL.  Px [..][Cin], Py [..][Cout] must not overlap.
+ * Writes y = z (or max(z,0) with SP_FLAG_RELU; of a NaN sum the result is NaN or, if its sign bit is set,
+ * possibly zero) into the interiors of Py; Py's margins are left as they are.  bias may be NULL.  Px [..][Cin], Py [..][Cout] must not overlap.
  * With g->grow = e > 0 the output box of a tile is its interior plus e voxels on every side on which
  * the tile has a neighbour in the grid (the voxels the next e layers of a block read, computed here
  * instead of exchanged); Px must be valid e + 1 voxels around the interior.  The rest of Py's
@@ -195,7 +195,8 @@ int conv3d_dgrad_relu(const void *Pdz, const void *w, const void *Px, void *Pdx,
  * (index as in P, channels dropped) and block b of 32 channels two uint16_t words, at word index
  * (p * C/32 + b) * 2 + hi; word `hi` holds channel 32 b + 8 q + 4 hi + i in bit 4 q + i (q, i = 0..3).
  * (The order in which the matrix cores hand results to lanes, so that neither side shuffles.)
- * A bit is 1 where the value is positive - not zero, not negative, not NaN.  Only the words of interior
+ * A bit is 1 where the value is positive - not zero, not negative, not NaN (conv3d_fwd_bits: a NaN result,
+ * which its ReLU keeps only with a clear sign bit, gets a 1).  Only the words of interior
  * voxels mean anything: conv3d_fwd_bits leaves the others unwritten and no call reads them. */
 
 /* Bytes of the bit array for C channels; 0 if the geometry or C is invalid. */

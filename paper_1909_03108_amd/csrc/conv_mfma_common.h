@@ -227,26 +227,48 @@ __device__ __forceinline__ size_t part_unit(int d, int h, int q) { return static
 template <class CtxT>
 __device__ __forceinline__ size_t bits_off(const CtxT &c, int d, int h) { return (d * c.oplane + h * c.orow) >> 4; }
 
-// The four bits of a finished store unit, taken from the fp32 values before they are rounded: a value is stored
-// as a positive bf16 exactly if it exceeds 2^-134, the midpoint between zero and the smallest bf16 denormal (a tie
-// rounds to the even neighbour, zero; fp32 denormals are kept in these kernels' floating-point mode).  NaN compares
-// false and +inf true, as the sign test on the stored value has it.  One compare and one select per value, against
-// four integer operations on the packed halves.
-__device__ __forceinline__ uint32_t positive_nibble(float v0, float v1, float v2, float v3) {
-    constexpr float T = 0x1p-134f;
-    return (v0 > T ? 1u : 0u) | (v1 > T ? 2u : 0u) | (v2 > T ? 4u : 0u) | (v3 > T ? 8u : 0u);
+// ReLU on the bit pattern of an fp32 value: whatever has the sign bit set (negative values, -0, NaNs with the sign
+// set) becomes +0, everything else stays as it is - one integer maximum, where the floating-point compare and select
+// (which keeps every NaN) cost two instructions and the two idle cycles the select waits for the compare's result.
+__device__ __forceinline__ float relu_f32(float v) { return __int_as_float(max(__float_as_int(v), 0)); }
+
+// The mask bit of a ReLU result v (sign clear), shifted into `word` from the right.  Taken from the fp32 value before
+// it is rounded: a value is stored as a positive bf16 exactly if it exceeds 2^-134 (pattern 0x00008000), the midpoint
+// between zero and the smallest bf16 denormal (a tie rounds to the even neighbour, zero; fp32 denormals are kept in
+// these kernels' floating-point mode), and for patterns with a clear sign the integer order is the floating-point
+// order: 0x8000 - pattern is negative exactly then (+inf included; a NaN, which ReLU leaves only with a clear sign,
+// counts as positive here, while the stand-alone bit kernel gives it a zero bit).  One subtraction and one funnel
+// shift per value and no compare: the compare-and-select form cost two instructions, two idle cycles and the OR.
+__device__ __forceinline__ uint32_t shift_in_positive(uint32_t word, float v) {
+    return __builtin_amdgcn_alignbit(word, static_cast<uint32_t>(0x8000 - __float_as_int(v)), 31);
 }
-// ... and the reverse: 0xffff in each half of the two words whose bit is set
-__device__ __forceinline__ uint2 nibble_halves(uint32_t word, int q) {
-    const uint32_t n = word >> (4 * q);
-    return make_uint2(((n & 1u) ? 0x0000ffffu : 0u) | ((n & 2u) ? 0xffff0000u : 0u),
-                      ((n & 4u) ? 0x0000ffffu : 0u) | ((n & 8u) ? 0xffff0000u : 0u));
+// After the row's 16 values went in, in the order k = 4 q + i, bit 15 - k holds value k: reverse.
+__device__ __forceinline__ uint16_t row_word(uint32_t shifted) {
+    return static_cast<uint16_t>(__builtin_bitreverse32(shifted) >> 16);
+}
+// ... and the reverse, for the reader.  spread_word, once per row: the row's word in the low half and the word
+// shifted right by one in the high half, so that bits k and k + 1 (k even) sit at position k of the two halves.
+// nibble_halves, per store unit q: 0xffff in each half of the unit's two packed words whose bit is set - a packed
+// shift that brings position 4 q (4 q + 2 for the second word) of both halves to their sign bits and a packed
+// arithmetic shift that fills the halves with it.
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t spread_word(uint32_t word) { return ((word >> 1) << 16) | (word & 0xffffu); }
+__device__ __forceinline__ uint32_t fill_from_bit(uint32_t spread, int k) {
+    union { uint32_t u; u16x2 v; s16x2 s; } r;
+    r.u = spread;
+    r.v = r.v << static_cast<unsigned short>(15 - k);
+    r.s = r.s >> static_cast<short>(15);
+    return r.u;
+}
+__device__ __forceinline__ uint2 nibble_halves(uint32_t spread, int q) {
+    return make_uint2(fill_from_bit(spread, 4 * q), fill_from_bit(spread, 4 * q + 2));
 }
 
 // kReluBits: write the mask word of row h of plane d that the four store units of the row collected.
 template <bool FULL, class CtxT>
 __device__ __forceinline__ void store_bits(const CtxT &c, int d, const mask_t (&mk)[RH][4], int h) {
-    if (FULL || c.okrow[h]) c.bbase[bits_off(c, d, h)] = static_cast<uint16_t>(mk[h][0].x);
+    if (FULL || c.okrow[h]) c.bbase[bits_off(c, d, h)] = row_word(mk[h][0].x);
 }
 
 // ---- the two-chunk kernel (conv_mfma_pair.hip) ------------------------------------------------

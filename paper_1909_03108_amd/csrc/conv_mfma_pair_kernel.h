@@ -96,8 +96,7 @@ __device__ __forceinline__ void finish_unit(const Ctx<HAS_BIAS> &c, int d, const
         return;
     }
     if (is_relu(RELU)) {
-        v0 = v0 < 0.f ? 0.f : v0; v1 = v1 < 0.f ? 0.f : v1;
-        v2 = v2 < 0.f ? 0.f : v2; v3 = v3 < 0.f ? 0.f : v3;
+        v0 = relu_f32(v0); v1 = relu_f32(v1); v2 = relu_f32(v2); v3 = relu_f32(v3);
     }
     uint2 pk = make_uint2(pack2(v0, v1), pack2(v2, v3));
     if (RELU == kMask) {
@@ -105,6 +104,7 @@ __device__ __forceinline__ void finish_unit(const Ctx<HAS_BIAS> &c, int d, const
         pk.y &= positive_halves(mk[h][q].y);
     }
     if (RELU == kMaskBits) {
+        if (q == 0) mk[h][0].x = spread_word(mk[h][0].x);
         const uint2 m = nibble_halves(mk[h][0].x, q);
         pk.x &= m.x;
         pk.y &= m.y;
@@ -112,8 +112,10 @@ __device__ __forceinline__ void finish_unit(const Ctx<HAS_BIAS> &c, int d, const
     if (FULL || c.okrow[h]) *reinterpret_cast<uint2 *>(c.obase + at) = pk;
     if (RELU == kReluBits) {
         // the row's word collects in the (otherwise unused) mask register of unit 0 and leaves with the last unit
-        const uint32_t n = positive_nibble(v0, v1, v2, v3) << (4 * q);
-        mk[h][0].x = q == 0 ? n : (mk[h][0].x | n);
+        uint32_t n = mk[h][0].x;
+        n = shift_in_positive(n, v0); n = shift_in_positive(n, v1);
+        n = shift_in_positive(n, v2); n = shift_in_positive(n, v3);
+        mk[h][0].x = n;
         if (q == 3) store_bits<FULL>(c, d, mk, h);
     }
 }
