@@ -280,6 +280,7 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
         if (KD == 1 && f / 18 != 1) continue;        // 2-D variant: only the taps with kd = 1 exist
         const uint4 q = a.wpack[(cj * NFRAG + f) * 64 + lane];
         wf[f] = *reinterpret_cast<const bf16x8 *>(&q);
+        if (KD == 3 && SP3D_PARKED(f)) park(wf[f]);
     }
 
     Ctx<HAS_BIAS> c;

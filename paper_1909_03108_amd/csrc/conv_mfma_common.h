@@ -117,6 +117,16 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
     return r.u;
 }
 
+// The 54 weight fragments of a lane (216 registers) do not fit beside everything else in the 256 ordinary vector
+// registers, and what the compiler evicts to the accumulation half of the register file it copies back before
+// every use (two thirds of all copies between the halves in the plane step, a quarter of its instructions).  The
+// matrix instructions read their A operand from either half: a fragment that passes through here is defined in
+// the accumulation half and is used from there, with no copy.
+#ifndef SP3D_PARKED
+#define SP3D_PARKED(f) ((f) % 3 == 0)
+#endif
+__device__ __forceinline__ void park(bf16x8 &w) { asm volatile("" : "+a"(w)); }
+
 // Where output block cj goes: tensor, its channels per voxel, channel offset.
 struct OutDst { uint16_t *base; int cs, co; };
 __device__ __forceinline__ OutDst out_dest(const ConvArgs &a, int cj) {

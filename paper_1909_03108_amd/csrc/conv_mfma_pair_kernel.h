@@ -309,6 +309,7 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int logical, i
                                            lane * 16) = q;
             } else {
                 wf[f] = *reinterpret_cast<const bf16x8 *>(&q);
+                if (KD == 3 && SP3D_PARKED(f)) park(wf[f]);
             }
         }
     }
