@@ -167,14 +167,20 @@ __device__ __forceinline__ void store_unit(const Ctx<HAS_BIAS> &c, int d, const 
 // way; otherwise it uses the ones the previous step fetched (kSideUse) and first of all fetches those of the
 // plane that the next step finishes, Dp - 2, into the other set (npin, nmk), which the caller passes through
 // the wait that ends the step.
-template <int P, bool EPI, int MODE, int RELU, bool FULL, int KD, int SIDE, bool HAS_BIAS>
-__device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, int lane, const char *lbase,
+template <int P, bool EPI, int MODE, int RELU, bool FULL, int KD, int SIDE, int NV, bool HAS_BIAS>
+__device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, int lane, const uint32_t (&lring)[2],
                                            const bf16x8 (&wf)[NFRAG], f32x16 (&acc)[4][RH],
                                            pin_t (&pin)[RH][4], mask_t (&mk)[RH][4],
-                                           pin_t (&npin)[RH][4], mask_t (&nmk)[RH][4]) {
+                                           pin_t (&npin)[RH][4], mask_t (&nmk)[RH][4], bf16x8 (&b0)[RH + 2]) {
     constexpr int NR = RH + 2;
     constexpr int DONE = (P + 1) & 3;
     using S = Side<MODE, RELU, KD, false>;
+    // ring slots of plane Dp and of plane Dp + 1, as a base register (slots 0, 1 / 2, 3) and an immediate that
+    // fits the instruction's 16-bit offset field
+    constexpr int PN = (P + 1) & 3;
+    const uint32_t lbase = lring[P >> 1], lnext = lring[PN >> 1];
+    constexpr int OFF = (P & 1) * PLANE_BYTES, OFFN = (PN & 1) * PLANE_BYTES;
+    static_assert(PLANE_BYTES + 2 * CH_STRIDE + ((RH + 1) * LCOLS + 2) * 16 + CH_STRIDE < 65536, "offset field");
     bf16x8 b[2][NR];
     if (SIDE != kSideNone) {
 #pragma unroll
@@ -200,8 +206,7 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, int l
             for (int q = 0; q < 4; ++q) mk[h][q] = load_mask<FULL, S::BITS>(c, Dp - 3, h, q);
     }
 #pragma unroll
-    for (int r = 0; r < NR; ++r)
-        b[0][r] = *reinterpret_cast<const bf16x8 *>(lbase + (r * LCOLS) * 16);
+    for (int r = 0; r < NR; ++r) b[0][r] = b0[r];       // group 0's fragments: read, and waited for, by the previous step
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi) {
         const int kw = gi >> 1, half = gi & 1;
@@ -209,15 +214,37 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, int l
             const int kw2 = (gi + 1) >> 1, half2 = (gi + 1) & 1;
 #pragma unroll
             for (int r = 0; r < NR; ++r)
-                b[(gi + 1) & 1][r] = *reinterpret_cast<const bf16x8 *>(
-                    lbase + half2 * 2 * CH_STRIDE + (r * LCOLS + kw2) * 16);
+                frag_read(b[(gi + 1) & 1][r], lbase, OFF + half2 * 2 * CH_STRIDE + (r * LCOLS + kw2) * 16);
+        } else {
+            // The step's one synchronisation sits here, before its last group, not at its end: plane Dp + 1
+            // must be complete (every wave's staging loads of it, issued two steps ago: loads complete in issue
+            // order and the only ones issued after them are those of plane Dp + 2 and the NG - 1 of this step,
+            // so "at most NV outstanding" implies it; stores share the counter and only make the wait more
+            // conservative), and every wave must have finished reading plane Dp, this step's own (its last
+            // fragment reads were issued a group ago; lgkmcnt(0) makes that formal), whose ring slot the next
+            // step's staging loads overwrite.  Behind the barrier the first group of the NEXT step is read
+            // already, while this step's last 18 MFMAs run: the step boundary itself has no wait, no barrier and
+            // no exposed LDS latency.  (With the synchronisation at the end of the step the matrix cores idled
+            // there for the barrier, the reads of two groups and their latency.)
+            side_fence<NV, true, SIDE != kSideNone && S::PINS, SIDE != kSideNone && S::MASK,
+                       SIDE != kSideNone && S::BITS>(npin, nmk);
+            __builtin_amdgcn_s_barrier();
+#pragma unroll
+            for (int r = 0; r < NR; ++r) frag_read(b[0][r], lnext, OFFN + (r * LCOLS) * 16);
         }
+        // this group's fragments were read a group ago; the NR reads issued just now may stay in flight
+        frag_wait<NR>(b[gi & 1]);
         // keep the reads of the next group ahead of this group's MFMAs (the scheduler would
         // otherwise sink every read to just before its first use and expose the LDS latency)
         __builtin_amdgcn_sched_barrier(0);
         stage(c, Dp + DIST, gi, lane);
         if (gi < 4) {
             if (EPI) {
+                // (the copies of the finished plane's sums out of the accumulation registers have no operand that
+                // is computed in the step, so the compiler emits all 32 at the top of the step, in front of its
+                // first MFMA; passing the plane through an empty statement here makes each group's eight depend
+                // on a point inside the group, where they are woven between the MFMAs like the rest)
+                asm volatile("" : "+a"(acc[DONE][0]), "+a"(acc[DONE][1]));
                 store_unit<MODE, RELU, FULL>(c, Dp - 3, acc[DONE], pin, mk, 0, gi);
                 store_unit<MODE, RELU, FULL>(c, Dp - 3, acc[DONE], pin, mk, 1, gi);
             }
@@ -247,6 +274,11 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, int l
             if (i % 6 == 2) __builtin_amdgcn_sched_group_barrier(0x060, 1, 0);   // a vector memory op
         }
     }
+    // the next step's first fragments, read 18 MFMAs ago: complete before they leave the step (beyond it the
+    // compiler may copy the registers at a block boundary, which it must not do while data is on its way)
+    frag_wait<0>(b[0]);
+#pragma unroll
+    for (int r = 0; r < NR; ++r) b0[r] = b[0][r];
 }
 
 template <int MODE, bool HAS_BIAS, int RELU, int KD>
@@ -357,16 +389,13 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
-    // End of a step: plane Dp+1 must be complete before anyone reads it in the next step.  Loads
-    // complete in issue order and the only loads issued after plane Dp+1's are those of planes Dp+2 and
-    // Dp+3, so "at most 2*LOADS vector memory operations outstanding" implies it is done (stores share
-    // the counter and only make the wait more conservative).  A bare s_barrier: __syncthreads() would
-    // make the compiler drain every staging load.
-#define SP3D_STEP_END()                                                              \
-    do {                                                                             \
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DIST - 1) * LOADS) : "memory");    \
-        __builtin_amdgcn_s_barrier();                                                \
-    } while (0)
+    // (the synchronisation of a step sits inside it, before its last MFMA group: see plane_step)
+    constexpr int NV_STEP = (DIST - 1) * LOADS - 1;     // plane Dp + 2's loads and the step's first NG - 1
+    static_assert(NG == LOADS, "one staging load per MFMA group");
+    const uint32_t lring[2] = {lds_addr(lbase), lds_addr(lbase + 2 * PLANE_BYTES)};
+    bf16x8 b0[RH + 2];
+#pragma unroll
+    for (int r = 0; r < RH + 2; ++r) b0[r] = *reinterpret_cast<const bf16x8 *>(lbase + (r * LCOLS) * 16);
 
     auto march = [&](auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
@@ -377,31 +406,20 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
         constexpr int FETCH = ASYNC ? kSideFetch : kSideNone, USE = ASYNC ? kSideUse : kSideNone;
         pin_t pinA[RH][4], pinB[RH][4];
         mask_t mkA[RH][4], mkB[RH][4];
-        // (a step with stores issues LOADS + 8 >= (DIST - 1) * LOADS operations after its side loads; the
-        // fetch-only step issues just its LOADS staging loads after them and waits accordingly)
-#define SP3D_STEP_END_SIDE(NV, NP, NM)                                                   \
-    do {                                                                                 \
-        side_fence<NV, false, ASYNC && S::PINS, ASYNC && S::MASK, ASYNC && S::BITS>(NP, NM); \
-        __builtin_amdgcn_s_barrier();                                                    \
-    } while (0)
-        static_assert(LOADS + 8 >= (DIST - 1) * LOADS, "side loads must be older than what the step-end wait lets stay in flight");
+        // (by its synchronisation point a step with stores has issued LOADS - 1 + 8 >= NV_STEP operations after its
+        // side loads, so the wait covers them; the fetch-only step has issued just LOADS - 1 staging loads after
+        // them and waits accordingly)
+        static_assert(LOADS - 1 + 8 >= NV_STEP, "side loads must be older than what the step's wait lets stay in flight");
         // the first three steps have no finished plane to store (nplanes >= 3 always); the third one fetches
         // what the first store needs
-        plane_step<0, false, MODE, RELU, FULL, KD, kSideNone>(c, 0, lane, lbase, wf, acc, pinA, mkA, pinB, mkB);
-        SP3D_STEP_END();
-        plane_step<1, false, MODE, RELU, FULL, KD, kSideNone>(c, 1, lane, lbase + PLANE_BYTES, wf, acc, pinA, mkA,
-                                                              pinB, mkB);
-        SP3D_STEP_END();
-        plane_step<2, false, MODE, RELU, FULL, KD, FETCH>(c, 2, lane, lbase + 2 * PLANE_BYTES, wf, acc, pinA, mkA,
-                                                          pinB, mkB);
-        SP3D_STEP_END_SIDE(ASYNC ? LOADS : (DIST - 1) * LOADS, pinB, mkB);
+        plane_step<0, false, MODE, RELU, FULL, KD, kSideNone, NV_STEP>(c, 0, lane, lring, wf, acc, pinA, mkA, pinB, mkB, b0);
+        plane_step<1, false, MODE, RELU, FULL, KD, kSideNone, NV_STEP>(c, 1, lane, lring, wf, acc, pinA, mkA, pinB, mkB, b0);
+        plane_step<2, false, MODE, RELU, FULL, KD, FETCH, (ASYNC ? LOADS - 1 : NV_STEP)>(c, 2, lane, lring, wf, acc, pinA,
+                                                                                        mkA, pinB, mkB, b0);
         // steps 3, 4, 5, 6, 7, ...: planes mod 4 = 3, 0, 1, 2, 3, ...
-#define SP3D_MAIN_STEP(OFF, PHASE, CP, CM, NP, NM)                                                   \
-    if (D + (OFF) < nplanes) {                                                                       \
-        plane_step<PHASE, true, MODE, RELU, FULL, KD, USE>(c, D + (OFF), lane, lbase + (PHASE) * PLANE_BYTES, wf, \
-                                                           acc, CP, CM, NP, NM);                     \
-        SP3D_STEP_END_SIDE((DIST - 1) * LOADS, NP, NM);                                              \
-    }
+#define SP3D_MAIN_STEP(OFF, PHASE, CP, CM, NP, NM)                                                            \
+    if (D + (OFF) < nplanes)                                                                                  \
+        plane_step<PHASE, true, MODE, RELU, FULL, KD, USE, NV_STEP>(c, D + (OFF), lane, lring, wf, acc, CP, CM, NP, NM, b0);
         for (int D = 3; D < nplanes; D += 4) {
             SP3D_MAIN_STEP(0, 3, pinB, mkB, pinA, mkA)
             SP3D_MAIN_STEP(1, 0, pinA, mkA, pinB, mkB)
@@ -409,7 +427,6 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
             SP3D_MAIN_STEP(3, 2, pinA, mkA, pinB, mkB)
         }
 #undef SP3D_MAIN_STEP
-#undef SP3D_STEP_END_SIDE
         // the last output plane (dn-1) finished in the last step; it sits in slot (dn-1) mod 4, and with side
         // loads the last step (plane index dn + 1, of the parity of dn - 1) fetched its values: into set B if
         // that index is even
@@ -438,7 +455,6 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
     };
     if (h0 + PH <= bx.bh && w0 + PW <= bx.bw) march(std::true_type{});
     else march(std::false_type{});
-#undef SP3D_STEP_END
 }
 
 }  // namespace

@@ -127,6 +127,24 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
 #endif
 __device__ __forceinline__ void park(bf16x8 &w) { asm volatile("" : "+a"(w)); }
 
+// LDS fragment reads by hand.  The compiler counts a direct-to-LDS load as an access of both memories, and
+// while one is in flight - here: always - it turns every wait for an LDS read into "all LDS reads done"
+// (s_waitcnt lgkmcnt(0)).  In the plane step that wait stands behind the reads of the NEXT group, issued a moment
+// earlier, so each of the six groups began by sitting out a full LDS latency with idle matrix cores.  LDS reads
+// return in issue order: "at most NR outstanding" is all a group needs, and that is what frag_wait states; the
+// registers pass through it as operands, so nothing uses them earlier.
+__device__ __forceinline__ void frag_read(bf16x8 &d, uint32_t base, int off) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(d) : "v"(base), "i"(off) : "memory");
+}
+// LDS address (the 32-bit offset that the instructions take) of a pointer into the dynamic LDS block
+__device__ __forceinline__ uint32_t lds_addr(const char *p) {
+    return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((const __attribute__((address_space(3))) char *)p));
+}
+template <int N>
+__device__ __forceinline__ void frag_wait(bf16x8 (&f)[4]) {
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]) : "n"(N) : "memory");
+}
+
 // Where output block cj goes: tensor, its channels per voxel, channel offset.
 struct OutDst { uint16_t *base; int cs, co; };
 __device__ __forceinline__ OutDst out_dest(const ConvArgs &a, int cj) {

@@ -134,12 +134,17 @@ __device__ __forceinline__ void give_unit(const f32x16 (&s)[RH], char *red, int 
 // the ordinary way; otherwise it uses the ones the previous step fetched (kSideUse) and first of all fetches
 // those of the plane that the next step finishes, Dp - 3, into the other set (npin, nmk), which the caller
 // passes through the wait that ends the step.
-template <int P, int ROLE, bool GIVE, bool FIN, int MODE, int RELU, bool FULL, int KD, int SIDE, bool HAS_BIAS>
-__device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const char *lbase,
+// lcur / lnxt: this lane's LDS read base in the ring slots of planes Dp / Dp + 1; b0: the fragments of the first
+// MFMA group, read (and waited for) by the previous step; on return those of the next step.  NV: how many
+// vector-memory operations the step's wait, which stands before its last MFMA group, lets stay in flight.
+template <int P, int ROLE, bool GIVE, bool FIN, int MODE, int RELU, bool FULL, int KD, int SIDE, int NV, bool HAS_BIAS>
+__device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, uint32_t lcur, uint32_t lnxt,
                                            const bf16x8 (&wf)[NFRAG], f32x16 (&acc)[NSLOT][RH],
                                            pin_t (&pin)[RH][4], mask_t (&mk)[RH][4],
-                                           pin_t (&npin)[RH][4], mask_t (&nmk)[RH][4]) {
+                                           pin_t (&npin)[RH][4], mask_t (&nmk)[RH][4], bf16x8 (&b0)[RH + 2]) {
     constexpr int NR = RH + 2;
+    static_assert(NR == 4, "frag_wait names four fragments");
+    static_assert(2 * CH_STRIDE + ((RH + 1) * LCOLS + 2) * 16 < 65536, "offset field of the LDS reads");
     constexpr int SSLOT = ROLE == 1 ? (P + 2) % NSLOT : (P + 1) % NSLOT;     // slot of the side work
     constexpr int NEXT = (P + 1) % NSLOT;      // slot of output plane Dp + 1: must be clean when this step ends
     constexpr bool ACTIVE = ROLE == 1 ? GIVE : FIN;
@@ -171,7 +176,7 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const
             for (int q = 0; q < 4; ++q) mk[h][q] = load_mask<FULL, S::BITS>(c, Dp - 4, h, q);
     }
 #pragma unroll
-    for (int r = 0; r < NR; ++r) b[0][r] = *reinterpret_cast<const bf16x8 *>(lbase + (r * LCOLS) * 16);
+    for (int r = 0; r < NR; ++r) b[0][r] = b0[r];
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi) {
         const int kw = gi >> 1, half = gi & 1;
@@ -179,9 +184,21 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const
             const int kw2 = (gi + 1) >> 1, half2 = (gi + 1) & 1;
 #pragma unroll
             for (int r = 0; r < NR; ++r)
-                b[(gi + 1) & 1][r] = *reinterpret_cast<const bf16x8 *>(
-                    lbase + half2 * 2 * CH_STRIDE + (r * LCOLS + kw2) * 16);
+                frag_read(b[(gi + 1) & 1][r], lcur, half2 * 2 * CH_STRIDE + (r * LCOLS + kw2) * 16);
+        } else {
+            // The step's synchronisation stands here, before its last MFMA group (see the one-chunk kernel's
+            // plane_step): plane Dp + 1 has landed when at most the loads of plane Dp + 2 and this step's first
+            // LOADS - 1 are in flight; this wave's hand-over writes (issued in groups 0 - 3) have reached LDS and
+            // its reads of plane Dp and of the other role's hand-over are done (lgkmcnt(0)).  Behind the barrier
+            // the first group of the next step is read while this step's last 18 MFMAs run.
+            side_fence<NV, true, SIDE != kSideNone && S::PINS, SIDE != kSideNone && S::MASK,
+                       SIDE != kSideNone && S::BITS>(npin, nmk);
+            __builtin_amdgcn_s_barrier();
+#pragma unroll
+            for (int r = 0; r < NR; ++r) frag_read(b[0][r], lnxt, (r * LCOLS) * 16);
         }
+        // this group's fragments were read a group ago; the NR reads issued just now may stay in flight
+        frag_wait<NR>(b[gi & 1]);
         // the two weight fragments of this group that live in LDS (see WL_FRAGS); the MFMAs that use them are
         // the last of the group
         bf16x8 wl2[2];
@@ -195,6 +212,9 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const
         if (gi < 2) stage(c, Dp + DIST, NG + gi);
         if (gi < 4) {
             if (ACTIVE) {
+                // (ties the copies out of the accumulation registers to this group; otherwise the compiler emits
+                // all 32 at the top of the step, in front of its first MFMA)
+                asm volatile("" : "+a"(acc[SSLOT][0]), "+a"(acc[SSLOT][1]));
                 if (ROLE == 1) {
                     give_unit(acc[SSLOT], red_w, 0, gi);
                     give_unit(acc[SSLOT], red_w, 1, gi);
@@ -234,6 +254,10 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, const
             if (i % 6 == 2) __builtin_amdgcn_sched_group_barrier(0x060, 1, 0);   // a vector memory op
         }
     }
+    // the next step's first fragments, read 18 MFMAs ago: complete before they leave the step
+    frag_wait<0>(b[0]);
+#pragma unroll
+    for (int r = 0; r < NR; ++r) b0[r] = b[0][r];
 }
 
 // The two steps after the last input plane: only the side work is left.  Dp = nplanes: chunk 1 hands over
@@ -388,14 +412,12 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int logical, i
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");      // staged planes and the parked weight fragments
     __builtin_amdgcn_s_barrier();
 
-    // End of a step: plane Dp + 1 has landed when at most the loads of planes Dp + 2, Dp + 3 are in flight
-    // (loads complete in order; stores share the counter and only make the wait stricter), and this wave's
-    // hand-over writes have reached LDS.
-#define SP3D_STEP_END()                                                                        \
-    do {                                                                                       \
-        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((DIST - 1) * LOADS) : "memory");   \
-        __builtin_amdgcn_s_barrier();                                                          \
-    } while (0)
+    // (a plane step synchronises inside itself, before its last MFMA group; a drain step at its end)
+    constexpr int NV_STEP = (DIST - 1) * LOADS - 1;     // plane Dp + 2's loads and the step's first LOADS - 1
+    const uint32_t lring = lds_addr(lbase);
+    bf16x8 b0[RH + 2];
+#pragma unroll
+    for (int r = 0; r < RH + 2; ++r) b0[r] = *reinterpret_cast<const bf16x8 *>(lbase + (r * LCOLS) * 16);
 
     auto march = [&](auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
@@ -406,32 +428,31 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int logical, i
         constexpr int FETCH = ASYNC ? kSideFetch : kSideNone, USE = ASYNC ? kSideUse : kSideNone;
         pin_t pinA[RH][4], pinB[RH][4];
         mask_t mkA[RH][4], mkB[RH][4];
-        // A step that finishes a plane issues LOADS + 8 operations after its side loads, which the wait at its
-        // end lets stay in flight; a fetch-only step issues just its staging loads after them and waits
-        // accordingly; a drain step issues no staging loads and waits for everything.
-        static_assert(LOADS + 8 >= (DIST - 1) * LOADS, "side loads must be older than what the step-end wait lets stay in flight");
+        // By its wait a step that finishes a plane has issued LOADS - 1 + 8 operations after its side loads, which
+        // the wait lets stay in flight; a fetch-only step has issued just LOADS - 1 staging loads after them and
+        // waits accordingly; a drain step issues no staging loads and waits for everything.
+        static_assert(LOADS - 1 + 8 >= NV_STEP, "side loads must be older than what the step's wait lets stay in flight");
 #define SP3D_STEP_END_SIDE(NV, NP, NM)                                              \
     do {                                                                            \
         side_fence<NV, true, ASYNC && S::PINS, ASYNC && S::MASK, ASYNC && S::BITS>(NP, NM); \
         __builtin_amdgcn_s_barrier();                                               \
     } while (0)
-        plane_step<0, ROLE, false, false, MODE, RELU, FULL, KD, kSideNone>(c, 0, lbase, wf, acc, pinA, mkA, pinB, mkB);
-        SP3D_STEP_END();
-        plane_step<1, ROLE, false, false, MODE, RELU, FULL, KD, kSideNone>(c, 1, lbase + PLANE_BYTES, wf, acc, pinA, mkA,
-                                                                          pinB, mkB);
-        SP3D_STEP_END();
-        plane_step<2, ROLE, false, false, MODE, RELU, FULL, KD, kSideNone>(c, 2, lbase + 2 * PLANE_BYTES, wf, acc, pinA,
-                                                                          mkA, pinB, mkB);
-        SP3D_STEP_END();
+        plane_step<0, ROLE, false, false, MODE, RELU, FULL, KD, kSideNone, NV_STEP>(c, 0, lring, lring + PLANE_BYTES, wf, acc,
+                                                                                   pinA, mkA, pinB, mkB, b0);
+        plane_step<1, ROLE, false, false, MODE, RELU, FULL, KD, kSideNone, NV_STEP>(
+            c, 1, lring + PLANE_BYTES, lring + 2 * PLANE_BYTES, wf, acc, pinA, mkA, pinB, mkB, b0);
+        plane_step<2, ROLE, false, false, MODE, RELU, FULL, KD, kSideNone, NV_STEP>(
+            c, 2, lring + 2 * PLANE_BYTES, lring + 3 * PLANE_BYTES, wf, acc, pinA, mkA, pinB, mkB, b0);
         // Steps 3, 4, ... with slot phase Dp mod 5 as a compile-time constant (the ring slot Dp mod 4 is a
         // run-time offset: a period of 20 steps would be needed to make both constants).  The march runs two
         // steps past the last input plane; those only hand over / finish what is left.  Step 3 is the first
         // to hand a plane over (and fetches the side values of step 4), step 4 the first to finish one.
 #define SP3D_STEP(DP, PHASE, GIVE_EN, FIN_EN, SIDE_EN, CP, CM, NP, NM)                                     \
     if ((DP) < nplanes) {                                                                                  \
-        plane_step<PHASE, ROLE, GIVE_EN, FIN_EN, MODE, RELU, FULL, KD, SIDE_EN>(                           \
-            c, (DP), lbase + ((DP) % NBUF) * PLANE_BYTES, wf, acc, CP, CM, NP, NM);                        \
-        SP3D_STEP_END_SIDE(((SIDE_EN) == kSideFetch ? LOADS : (DIST - 1) * LOADS), NP, NM);                \
+        plane_step<PHASE, ROLE, GIVE_EN, FIN_EN, MODE, RELU, FULL, KD, SIDE_EN,                            \
+                   ((SIDE_EN) == kSideFetch ? LOADS - 1 : NV_STEP)>(                                       \
+            c, (DP), lring + ((DP) % NBUF) * PLANE_BYTES, lring + (((DP) + 1) % NBUF) * PLANE_BYTES, wf, acc, CP, CM, \
+            NP, NM, b0);                                                                                   \
     } else if ((DP) < nplanes + 2) {                                                                       \
         drain_step<PHASE, ROLE, GIVE_EN, FIN_EN, MODE, RELU, FULL, KD, SIDE_EN>(c, (DP), acc, CP, CM, NP, NM); \
         SP3D_STEP_END_SIDE(((SIDE_EN) == kSideNone ? (DIST - 1) * LOADS : 0), NP, NM);                     \
@@ -461,7 +482,6 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int logical, i
     };
     if (h0 + PH <= bx.bh && w0 + PW <= bx.bw) march(std::true_type{});
     else march(std::false_type{});
-#undef SP3D_STEP_END
 }
 
 template <int MODE, bool HAS_BIAS, int RELU, int KD>
