@@ -461,8 +461,11 @@ __global__ __launch_bounds__(kThreads, 1) void conv_mfma_kernel(ConvArgs a) {
 
 
 bool conv_mfma_supported(const Geo &g, int ki, int ko, sp_dtype_t dt) {
+    // per-lane staging offsets inside a padded plane are 32-bit: element offsets in the one-chunk kernel, byte
+    // offsets in the two-chunk kernel (input channels in multiples of 64)
+    const long long lim = ki % (2 * C) == 0 ? 0x3fffffffLL : 0x7fffffffLL;
     return dt == SP_BF16 && ki % C == 0 && ko % C == 0 && ki <= 1024 && ko <= 1024 &&
-           1LL * g.ph * g.pw * (ki > ko ? ki : ko) < 0x7fffffffLL;
+           1LL * g.ph * g.pw * (ki > ko ? ki : ko) < lim;
 }
 
 static size_t pack_bytes(int ki, int ko) {
@@ -520,7 +523,8 @@ bool conv_mfma_gather_supported(const Geo &g, int ki, int ko, sp_dtype_t dt) {
     // their sum at an edge) must fit the 32-bit staging offsets
     if (!conv_mfma_supported(g, ki, ko, dt) || g.halo != 1 || g.grow != 0 || g.flat || conv_gemm_preferred(g, ki, ko))
         return false;
-    return static_cast<long long>(g.tile_vox) * (g.gw + 1) * (ki > ko ? ki : ko) < 0x7fffffffLL;
+    const long long lim = ki % (2 * C) == 0 ? 0x3fffffffLL : 0x7fffffffLL;       // see conv_mfma_supported
+    return static_cast<long long>(g.tile_vox) * (g.gw + 1) * (ki > ko ? ki : ko) < lim;
 }
 
 bool conv_mfma_bits_supported(const Geo &g, int ki, int ko, sp_dtype_t dt) {

@@ -22,10 +22,15 @@ namespace wide {      // (inside the namespace of its constants: LOADS, PLANE_BY
 
 // direct-to-LDS load as in wgrad_mfma.hip: written as assembly so that the compiler neither tracks it nor
 // drains it before unrelated LDS accesses; the kernel counts the loads itself (s_waitcnt vmcnt)
-__device__ __forceinline__ void dma16(const uint16_t *src, const char *dst) {
+// Address = uniform base (scalar registers) + this lane's unsigned 32-bit byte offset: one register per staging
+// load instead of a 64-bit pair, and no per-load address arithmetic.  Offsets can be negative (gathered halos
+// point into a neighbour tile), so they are kept with a bias of 2^31 that the base takes back.
+constexpr uint32_t kOffBias = 0x80000000u;
+__device__ __forceinline__ void dma16(const uint16_t *base, uint32_t off, const char *dst) {
     const uint32_t l = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
         (const __attribute__((address_space(3))) char *)dst));
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(l) : "memory");
+    const char *b = reinterpret_cast<const char *>(base) - static_cast<ptrdiff_t>(kOffBias);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(off), "s"(b), "s"(l) : "memory");
 }
 
 template <bool HAS_BIAS>
@@ -35,7 +40,7 @@ struct Ctx {
     int nplanes;
     int plo, phi;               // staged planes are clamped to [plo, phi]
     ptrdiff_t dlo, dhi;         // gathered halos: what to add for staged plane 0 / the last one (else 0)
-    int goff[LOADS];            // source offsets of the staging loads (elements)
+    uint32_t goff[LOADS];       // source offsets of the staging loads (bytes, biased by kOffBias)
     bool tail_lane;             // lane has a voxel in the last (partial) load of a chunk plane
     char *lds_stage;            // first chunk plane this wave fills, ring slot 0
     char *red;                  // hand-over buffer of this wave's row group (buffer 0), lane part included
@@ -58,7 +63,7 @@ __device__ __forceinline__ void stage(const Ctx<HAS_BIAS> &c, int dplane, int j)
     const char *dst = c.lds_stage + (dplane % NBUF) * PLANE_BYTES + (j / CP_LOADS) * CH_STRIDE + (j % CP_LOADS) * 1024;
     // only the last load of a chunk plane is partial (204 = 3 x 64 + 12 voxels); j is a compile-time constant
     // at every call site, so the other loads carry no predicate
-    if (j % CP_LOADS != CP_LOADS - 1 || c.tail_lane) dma16(p + c.goff[j], dst);
+    if (j % CP_LOADS != CP_LOADS - 1 || c.tail_lane) dma16(p, c.goff[j], dst);
 }
 
 template <bool FULL, bool HAS_BIAS>
@@ -350,12 +355,13 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int logical, i
     c.plo = F > 1 ? 1 : 0;
     c.phi = F > 1 ? c.nplanes - 2 : c.nplanes - 1;
     // this wave fills chunk planes 2 rg and 2 rg + 1 (channels 16 rg .. 16 rg + 15) of its input chunk
+    int goff[LOADS];            // in elements; the host has checked that twice their value fits 32 bits
 #pragma unroll
     for (int j = 0; j < LOADS; ++j) {
         const int v = 64 * (j % CP_LOADS) + lane;
         const FoldCol fc = fold_col(v % LCOLS, F, a.fold_w);
         const int row = min(h0 + v / LCOLS, bx.bh + 1), colv = min(w0 + fc.c, bx.bw + 1);
-        c.goff[j] = ((min(fc.s, F - 1) * g.ph + row) * g.pw + colv) * src_cs + (2 * rg + j / CP_LOADS) * 8;   // always addressable
+        goff[j] = ((min(fc.s, F - 1) * g.ph + row) * g.pw + colv) * src_cs + (2 * rg + j / CP_LOADS) * 8;   // always addressable
     }
     c.dlo = c.dhi = 0;
     if (a.gather) {          // see GatherShift
@@ -364,12 +370,14 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int logical, i
         for (int j = 0; j < LOADS; ++j) {
             const int v = 64 * (j % CP_LOADS) + lane;
             const int row = min(h0 + v / LCOLS, bx.bh + 1), colv = min(w0 + v % LCOLS, bx.bw + 1);
-            c.goff[j] += (row == 0 ? gs.hm : 0) + (row == g.th + 1 ? gs.hp : 0) + (colv == 0 ? gs.wm : 0) +
-                         (colv == g.tw + 1 ? gs.wp : 0);
+            goff[j] += (row == 0 ? gs.hm : 0) + (row == g.th + 1 ? gs.hp : 0) + (colv == 0 ? gs.wm : 0) +
+                       (colv == g.tw + 1 ? gs.wp : 0);
         }
         if (d0 == 0) c.dlo = gs.dm;
         if (d0 + dn == g.td) c.dhi = gs.dp;
     }
+#pragma unroll
+    for (int j = 0; j < LOADS; ++j) c.goff[j] = static_cast<uint32_t>(goff[j] * 2) + kOffBias;
     c.tail_lane = 64 * (CP_LOADS - 1) + lane < PLANE_VOX;
     c.lds_stage = lds + ROLE * CHUNK_BYTES + 2 * rg * CH_STRIDE;
     c.red = lds + RING_BYTES + rg * (RH * 4 * 1024) + lane * 16;
