@@ -84,17 +84,14 @@ __device__ __forceinline__ mask_t load_mask(const Ctx<HAS_BIAS> &c, int d, int h
     return v;
 }
 
-// chunk-0 wave: finish 4 channels of row h of plane d: own sum + the partner's (from LDS) + earlier pairs'
-// partial sums (pin, fetched at the start of the step), then store the new partial (fp32) or ReLU /
-// convert / store bf16
+// chunk-0 wave: finish 4 channels of row h of plane d: own sum + what the partner handed over (from LDS: its own
+// sum and, in the launches after a layer's first, the earlier pairs' partial sums), then store the new partial
+// (fp32) or ReLU / convert / store bf16
 template <int MODE, int RELU, bool FULL, bool HAS_BIAS>
 __device__ __forceinline__ void finish_unit(const Ctx<HAS_BIAS> &c, int d, const f32x16 (&s)[RH], const char *red,
-                                            const pin_t (&pin)[RH][4], mask_t (&mk)[RH][4], int h, int q) {
+                                            mask_t (&mk)[RH][4], int h, int q) {
     const float4 o = *reinterpret_cast<const float4 *>(red + (h * 4 + q) * 1024);
     float v0 = s[h][4 * q] + o.x, v1 = s[h][4 * q + 1] + o.y, v2 = s[h][4 * q + 2] + o.z, v3 = s[h][4 * q + 3] + o.w;
-    if (MODE == kMiddle || MODE == kLast) {
-        v0 += pin[h][q].x; v1 += pin[h][q].y; v2 += pin[h][q].z; v3 += pin[h][q].w;
-    }
     const size_t at = d * c.oplane + h * c.orow + 8 * q;
     if (MODE == kFirst || MODE == kMiddle) {
         if (FULL || c.okrow[h]) *reinterpret_cast<float4 *>(c.pbase + part_unit(d, h, q)) = make_float4(v0, v1, v2, v3);
@@ -126,9 +123,15 @@ __device__ __forceinline__ void finish_unit(const Ctx<HAS_BIAS> &c, int d, const
 }
 
 // chunk-1 wave: hand 4 channels of row h of a complete plane over to the chunk-0 wave
-__device__ __forceinline__ void give_unit(const f32x16 (&s)[RH], char *red, int h, int q) {
-    *reinterpret_cast<float4 *>(red + (h * 4 + q) * 1024) =
-        make_float4(s[h][4 * q], s[h][4 * q + 1], s[h][4 * q + 2], s[h][4 * q + 3]);
+// (PINS: plus the partial sums of the earlier pairs.  They are fetched by THIS wave, which has no epilogue of its
+// own and so has the registers for a second set of them: the fetch runs a step ahead - see side_load - where the
+// chunk-0 wave, whose registers are taken, had to load them at the start of the step that used them and sat out
+// the latency, 35 - 45 % of its cycles in the launches after a layer's first)
+template <bool PINS>
+__device__ __forceinline__ void give_unit(const f32x16 (&s)[RH], char *red, const pin_t (&pin)[RH][4], int h, int q) {
+    float4 v = make_float4(s[h][4 * q], s[h][4 * q + 1], s[h][4 * q + 2], s[h][4 * q + 3]);
+    if (PINS) { v.x += pin[h][q].x; v.y += pin[h][q].y; v.z += pin[h][q].z; v.w += pin[h][q].w; }
+    *reinterpret_cast<float4 *>(red + (h * 4 + q) * 1024) = v;
 }
 
 // One staged input plane Dp.  P = Dp mod 5: output plane Dp - kd accumulates in slot (P - kd) mod 5.
@@ -157,22 +160,27 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, uint3
     bf16x8 b[2][NR];
     char *red_w = c.red + (Dp & 1) * RED_BYTES;
     const char *red_r = c.red + ((Dp - 1) & 1) * RED_BYTES;
-    if (ROLE == 0 && SIDE != kSideNone) {
+    if (ROLE == 0 && SIDE != kSideNone) {          // mask values of the plane that the next step finishes
 #pragma unroll
         for (int h = 0; h < RH; ++h)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const size_t at = (Dp - 3) * c.oplane + h * c.orow + 8 * q;
-                if (S::PINS) side_load(npin[h][q], c.pbase + part_unit(Dp - 3, h, q));
                 if (S::MASK && !S::BITS) side_load(nmk[h][q], c.mbase + at);
                 if (S::BITS && q == 0) SP3D_SIDE_LOAD_BITS(nmk[h][0].x, c.bbase + bits_off(c, Dp - 3, h));
             }
     }
-    if (SIDE == kSideNone && ROLE == 0 && FIN && S::PINS) {
+    if (ROLE == 1 && SIDE != kSideNone && S::PINS) {      // partial sums of the plane that the next step hands over
 #pragma unroll
         for (int h = 0; h < RH; ++h)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) pin[h][q] = load_partial<FULL>(c, Dp - 4, h, q);
+            for (int q = 0; q < 4; ++q) side_load(npin[h][q], c.pbase + part_unit(Dp - 2, h, q));
+    }
+    if (SIDE == kSideNone && ROLE == 1 && GIVE && S::PINS) {
+#pragma unroll
+        for (int h = 0; h < RH; ++h)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) pin[h][q] = load_partial<FULL>(c, Dp - 3, h, q);
     }
     if (SIDE == kSideNone && ROLE == 0 && FIN && S::MASK) {
 #pragma unroll
@@ -196,8 +204,8 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, uint3
             // LOADS - 1 are in flight; this wave's hand-over writes (issued in groups 0 - 3) have reached LDS and
             // its reads of plane Dp and of the other role's hand-over are done (lgkmcnt(0)).  Behind the barrier
             // the first group of the next step is read while this step's last 18 MFMAs run.
-            side_fence<NV, true, SIDE != kSideNone && S::PINS, SIDE != kSideNone && S::MASK,
-                       SIDE != kSideNone && S::BITS>(npin, nmk);
+            side_fence<NV, true, SIDE != kSideNone && ROLE == 1 && S::PINS, SIDE != kSideNone && ROLE == 0 && S::MASK,
+                       SIDE != kSideNone && ROLE == 0 && S::BITS>(npin, nmk);
             __builtin_amdgcn_s_barrier();
 #pragma unroll
             for (int r = 0; r < NR; ++r) frag_read(b[0][r], lnxt, (r * LCOLS) * 16);
@@ -221,11 +229,11 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, uint3
                 // all 32 at the top of the step, in front of its first MFMA)
                 asm volatile("" : "+a"(acc[SSLOT][0]), "+a"(acc[SSLOT][1]));
                 if (ROLE == 1) {
-                    give_unit(acc[SSLOT], red_w, 0, gi);
-                    give_unit(acc[SSLOT], red_w, 1, gi);
+                    give_unit<S::PINS>(acc[SSLOT], red_w, pin, 0, gi);
+                    give_unit<S::PINS>(acc[SSLOT], red_w, pin, 1, gi);
                 } else {
-                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], red_r, pin, mk, 0, gi);
-                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], red_r, pin, mk, 1, gi);
+                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], red_r, mk, 0, gi);
+                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], red_r, mk, 1, gi);
                 }
             }
         } else {
@@ -282,28 +290,28 @@ __device__ __forceinline__ void drain_step(const Ctx<HAS_BIAS> &c, int Dp, f32x1
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const size_t at = (Dp - 3) * c.oplane + h * c.orow + 8 * q;
-                if (S::PINS) side_load(npin[h][q], c.pbase + part_unit(Dp - 3, h, q));
                 if (S::MASK && !S::BITS) side_load(nmk[h][q], c.mbase + at);
                 if (S::BITS && q == 0) SP3D_SIDE_LOAD_BITS(nmk[h][0].x, c.bbase + bits_off(c, Dp - 3, h));
             }
     }
     if (ROLE == 1) {
+        // (the partial sums of this last hand-over were fetched by the last plane step)
         if (GIVE && Dp == c.nplanes) {
             char *red_w = c.red + (Dp & 1) * RED_BYTES;
+            if (SIDE == kSideNone && S::PINS) {
+#pragma unroll
+                for (int h = 0; h < RH; ++h)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) pin[h][q] = load_partial<FULL>(c, Dp - 3, h, q);
+            }
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                give_unit(acc[SSLOT], red_w, 0, q);
-                give_unit(acc[SSLOT], red_w, 1, q);
+                give_unit<S::PINS>(acc[SSLOT], red_w, pin, 0, q);
+                give_unit<S::PINS>(acc[SSLOT], red_w, pin, 1, q);
             }
         }
     } else if (FIN) {
         const char *red_r = c.red + ((Dp - 1) & 1) * RED_BYTES;
-        if (SIDE == kSideNone && S::PINS) {
-#pragma unroll
-            for (int h = 0; h < RH; ++h)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) pin[h][q] = load_partial<FULL>(c, Dp - 4, h, q);
-        }
         if (SIDE == kSideNone && S::MASK) {
 #pragma unroll
             for (int h = 0; h < RH; ++h)
@@ -312,8 +320,8 @@ __device__ __forceinline__ void drain_step(const Ctx<HAS_BIAS> &c, int Dp, f32x1
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], red_r, pin, mk, 0, q);
-            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], red_r, pin, mk, 1, q);
+            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], red_r, mk, 0, q);
+            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], red_r, mk, 1, q);
         }
     }
 }
@@ -430,42 +438,48 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int logical, i
     auto march = [&](auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
         using S = Side<MODE, RELU, KD, true>;
-        // whole patches: the chunk-0 wave fetches its partial sums / mask values one step ahead (see side_load),
-        // alternating between two sets of registers
-        constexpr bool ASYNC = FULL && ROLE == 0 && S::ASYNC;
+        // whole patches: the chunk-0 wave fetches its mask values, the chunk-1 wave the partial sums it adds to what
+        // it hands over, one step ahead (see side_load), alternating between two sets of registers.  The chunk-1
+        // wave hands plane Dp - 3 over in step Dp, the chunk-0 wave finishes it in step Dp + 1: the former's chain
+        // of fetches starts a step earlier (step 2 fetches, step 3 is the first to use).
+        constexpr bool ASYNC = FULL && (ROLE == 0 ? S::MASK : S::PINS);
         constexpr int FETCH = ASYNC ? kSideFetch : kSideNone, USE = ASYNC ? kSideUse : kSideNone;
+        constexpr int SIDE2 = ROLE == 1 ? FETCH : kSideNone, SIDE3 = ROLE == 1 ? USE : FETCH;
         pin_t pinA[RH][4], pinB[RH][4];
         mask_t mkA[RH][4], mkB[RH][4];
         // By its wait a step that finishes a plane has issued LOADS - 1 + 8 operations after its side loads, which
-        // the wait lets stay in flight; a fetch-only step has issued just LOADS - 1 staging loads after them and
-        // waits accordingly; a drain step issues no staging loads and waits for everything.
+        // the wait lets stay in flight; a fetch-only step, and every step of the chunk-1 wave (which stores nothing),
+        // has issued just LOADS - 1 staging loads after them and waits accordingly; a drain step issues no staging
+        // loads and waits for everything.
         static_assert(LOADS - 1 + 8 >= NV_STEP, "side loads must be older than what the step's wait lets stay in flight");
+#define SP3D_NV_OF(SIDE_EN) \
+    (((SIDE_EN) == kSideFetch || (ROLE == 1 && (SIDE_EN) != kSideNone)) ? LOADS - 1 : NV_STEP)
 #define SP3D_STEP_END_SIDE(NV, NP, NM)                                              \
     do {                                                                            \
-        side_fence<NV, true, ASYNC && S::PINS, ASYNC && S::MASK, ASYNC && S::BITS>(NP, NM); \
+        side_fence<NV, true, ASYNC && ROLE == 1 && S::PINS, ASYNC && ROLE == 0 && S::MASK,  \
+                   ASYNC && ROLE == 0 && S::BITS>(NP, NM);                          \
         __builtin_amdgcn_s_barrier();                                               \
     } while (0)
         plane_step<0, ROLE, false, false, MODE, RELU, FULL, KD, kSideNone, NV_STEP>(c, 0, lring, lring + PLANE_BYTES, wf, acc,
                                                                                    pinA, mkA, pinB, mkB, b0);
         plane_step<1, ROLE, false, false, MODE, RELU, FULL, KD, kSideNone, NV_STEP>(
             c, 1, lring + PLANE_BYTES, lring + 2 * PLANE_BYTES, wf, acc, pinA, mkA, pinB, mkB, b0);
-        plane_step<2, ROLE, false, false, MODE, RELU, FULL, KD, kSideNone, NV_STEP>(
-            c, 2, lring + 2 * PLANE_BYTES, lring + 3 * PLANE_BYTES, wf, acc, pinA, mkA, pinB, mkB, b0);
+        plane_step<2, ROLE, false, false, MODE, RELU, FULL, KD, SIDE2, SP3D_NV_OF(SIDE2)>(
+            c, 2, lring + 2 * PLANE_BYTES, lring + 3 * PLANE_BYTES, wf, acc, pinB, mkB, pinA, mkA, b0);
         // Steps 3, 4, ... with slot phase Dp mod 5 as a compile-time constant (the ring slot Dp mod 4 is a
         // run-time offset: a period of 20 steps would be needed to make both constants).  The march runs two
         // steps past the last input plane; those only hand over / finish what is left.  Step 3 is the first
         // to hand a plane over (and fetches the side values of step 4), step 4 the first to finish one.
 #define SP3D_STEP(DP, PHASE, GIVE_EN, FIN_EN, SIDE_EN, CP, CM, NP, NM)                                     \
     if ((DP) < nplanes) {                                                                                  \
-        plane_step<PHASE, ROLE, GIVE_EN, FIN_EN, MODE, RELU, FULL, KD, SIDE_EN,                            \
-                   ((SIDE_EN) == kSideFetch ? LOADS - 1 : NV_STEP)>(                                       \
+        plane_step<PHASE, ROLE, GIVE_EN, FIN_EN, MODE, RELU, FULL, KD, SIDE_EN, SP3D_NV_OF(SIDE_EN)>(      \
             c, (DP), lring + ((DP) % NBUF) * PLANE_BYTES, lring + (((DP) + 1) % NBUF) * PLANE_BYTES, wf, acc, CP, CM, \
             NP, NM, b0);                                                                                   \
     } else if ((DP) < nplanes + 2) {                                                                       \
         drain_step<PHASE, ROLE, GIVE_EN, FIN_EN, MODE, RELU, FULL, KD, SIDE_EN>(c, (DP), acc, CP, CM, NP, NM); \
         SP3D_STEP_END_SIDE(((SIDE_EN) == kSideNone ? (DIST - 1) * LOADS : 0), NP, NM);                     \
     }
-        SP3D_STEP(3, 3, true, false, FETCH, pinA, mkA, pinB, mkB)
+        SP3D_STEP(3, 3, true, false, SIDE3, pinA, mkA, pinB, mkB)
         SP3D_STEP(4, 4, true, true, USE, pinB, mkB, pinA, mkA)
         for (int D = 5; D < nplanes + 2; D += NSLOT) {
             SP3D_STEP(D, 0, true, true, USE, pinA, mkA, pinB, mkB)
@@ -486,6 +500,7 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int logical, i
         }
 #undef SP3D_STEP
 #undef SP3D_STEP_END_SIDE
+#undef SP3D_NV_OF
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // clamped staging loads of the last steps
     };
     if (h0 + PH <= bx.bh && w0 + PW <= bx.bw) march(std::true_type{});
