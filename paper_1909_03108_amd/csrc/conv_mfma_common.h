@@ -228,10 +228,10 @@ __device__ __forceinline__ void side_fence(pin_t (&p)[2][4], mask_t (&m)[2][4]) 
 // What a kernel variant fetches per store unit besides its operands, and whether it does so by side loads.
 // Measured: the mask gains from them (3-D 32 -> 32 at 512^3: 7.45 -> 7.08 ms; 2-D: 8 - 9 %; the 3-D two-chunk
 // kernel 3 %, now that part of its weight fragments live in LDS - while its registers were all taken the second
-// register set cost 4.07 -> 4.71 ms).  The partial sums stay ordinary loads: their wait is what the launches
-// after a layer's first lose most to (the wave waits 35 - 45 % of its cycles there, against 17 % in a single
-// launch), but a second set of 32 registers for them does not fit - the two-chunk kernel then spills to scratch
-// memory, whose reloads wait on the same counter, and ran 4 % slower (128 and 256 channels, measured).
+// register set cost 4.07 -> 4.71 ms).  Partial sums: ordinary loads in the one-chunk kernel; in the two-chunk
+// kernel the wave that finishes a plane has no room for a second set of 32 registers (tried: it spills, and the
+// reloads wait on the same counter: 4 % slower), so there the OTHER chunk's wave, which has no epilogue, fetches
+// them ahead and adds them to what it hands over (conv_mfma_pair_kernel.h).
 template <int MODE, int RELU, int KD, bool PAIR> struct Side {
     static constexpr bool PINS = MODE == kMiddle || MODE == kLast;
     static constexpr bool MASK = (RELU == kMask || RELU == kMaskBits) && (MODE == kSingle || MODE == kLast);
