@@ -84,13 +84,17 @@ __device__ __forceinline__ mask_t load_mask(const Ctx<HAS_BIAS> &c, int d, int h
     return v;
 }
 
+// what the chunk-1 wave wrote for store unit q of row h (see give_unit)
+__device__ __forceinline__ float4 handed_over(const char *red, int h, int q) {
+    return *reinterpret_cast<const float4 *>(red + (h * 4 + q) * 1024);
+}
 // chunk-0 wave: finish 4 channels of row h of plane d: own sum + what the partner handed over (from LDS: its own
 // sum and, in the launches after a layer's first, the earlier pairs' partial sums), then store the new partial
 // (fp32) or ReLU / convert / store bf16
+// (o: what handed_over read for this unit)
 template <int MODE, int RELU, bool FULL, bool HAS_BIAS>
-__device__ __forceinline__ void finish_unit(const Ctx<HAS_BIAS> &c, int d, const f32x16 (&s)[RH], const char *red,
+__device__ __forceinline__ void finish_unit(const Ctx<HAS_BIAS> &c, int d, const f32x16 (&s)[RH], const float4 &o,
                                             mask_t (&mk)[RH][4], int h, int q) {
-    const float4 o = *reinterpret_cast<const float4 *>(red + (h * 4 + q) * 1024);
     float v0 = s[h][4 * q] + o.x, v1 = s[h][4 * q + 1] + o.y, v2 = s[h][4 * q + 2] + o.z, v3 = s[h][4 * q + 3] + o.w;
     const size_t at = d * c.oplane + h * c.orow + 8 * q;
     if (MODE == kFirst || MODE == kMiddle) {
@@ -214,6 +218,14 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, uint3
         frag_wait<NR>(b[gi & 1]);
         // the two weight fragments of this group that live in LDS (see WL_FRAGS); the MFMAs that use them are
         // the last of the group
+        // ... and what the chunk-1 wave handed over for this group's two store units: read here, at the top of the
+        // group, six and more MFMAs before the first addition that needs it (read where it is used, inside the
+        // unit, each of the eight units of a step began by waiting out an LDS latency: a sixth of the wave's cycles)
+        float4 ho[RH];
+        if (ROLE == 0 && ACTIVE && gi < 4) {
+#pragma unroll
+            for (int h = 0; h < RH; ++h) ho[h] = handed_over(red_r, h, gi);
+        }
         bf16x8 wl2[2];
         if (KD == 3) {
             wl2[0] = *reinterpret_cast<const bf16x8 *>(c.wl + wl_index(1, kw, half) * 1024);
@@ -232,8 +244,8 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, uint3
                     give_unit<S::PINS>(acc[SSLOT], red_w, pin, 0, gi);
                     give_unit<S::PINS>(acc[SSLOT], red_w, pin, 1, gi);
                 } else {
-                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], red_r, mk, 0, gi);
-                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], red_r, mk, 1, gi);
+                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], ho[0], mk, 0, gi);
+                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], ho[1], mk, 1, gi);
                 }
             }
         } else {
@@ -320,8 +332,8 @@ __device__ __forceinline__ void drain_step(const Ctx<HAS_BIAS> &c, int Dp, f32x1
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], red_r, mk, 0, q);
-            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], red_r, mk, 1, q);
+            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], handed_over(red_r, 0, q), mk, 0, q);
+            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], handed_over(red_r, 1, q), mk, 1, q);
         }
     }
 }
