@@ -450,7 +450,70 @@ __device__ __forceinline__ void plane_step_dma(const char *xl, const char *z0, c
     }
 }
 
+// The same step (x, z[kd]: this lane's read bases in x plane D and in dz planes D - kd; m[kd] as above) cut in two so that the
+// workgroup's barrier can stand inside it: rows R0 .. R1 - 1 of the x plane; the fragments of row R0 are in
+// xf / zf already (read by the previous call), and the call reads those of row R1 - or, for the last row, those of
+// row 0 of the NEXT plane (nx) - before its last row's MFMAs.  Rows 0 and GR + 1 carry 9 MFMAs against 12 fragment
+// reads, so at a plane boundary that begins with a barrier and reads from scratch the matrix cores wait out the
+// LDS latency with nothing to do; with the barrier behind row GR - 1 and the next plane's first fragments on
+// their way during row GR + 1 the rows follow each other without a gap.
+struct DmaPlane { const char *x; const char *z[3]; uint32_t m[3]; };
 template <int KD>
+__device__ __forceinline__ void dma_row0(const DmaPlane &pl, bf16x8 (&xf)[2][3], bf16x8 (&zf)[3][4]) {
+#pragma unroll
+    for (int kw = 0; kw < 3; ++kw) xf[0][kw] = frag(pl.x + kw * 32);
+#pragma unroll
+    for (int kd = 0; kd < 3; ++kd)
+        if (KD == 3 || kd == 1) zf[kd][0] = frag_masked(pl.z[kd], pl.m[kd]);
+}
+template <int KD, int R0, int R1>
+__device__ __forceinline__ void plane_rows_dma(const DmaPlane &pl, const DmaPlane &nx, bool bias_wave,
+                                               bf16x8 (&xf)[2][3], bf16x8 (&zf)[3][4], f32x4 (&acc)[27],
+                                               f32x4 &accb) {
+    union { uint32_t w[4]; bf16x8 v; } ones;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ones.w[i] = 0x3f803f80u;     // bf16 1.0 pairs
+    static_assert(((GR + 2) & 1) == 0 && GR == 4, "row GR + 1 reads the next plane's row 0 into buffer 0 / ring slot 0");
+#pragma unroll
+    for (int R = R0; R < R1; ++R) {
+        if (R + 1 < GR + 2) {
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) xf[(R + 1) & 1][kw] = frag(pl.x + ((R + 1) * XC + kw) * 32);
+            if (R + 1 < GR) {
+#pragma unroll
+                for (int kd = 0; kd < 3; ++kd)
+                    if (KD == 3 || kd == 1)
+                        zf[kd][(R + 1) & 3] = frag_masked(pl.z[kd] + (R + 1) * PW * 32, pl.m[kd]);
+            }
+        } else {
+            dma_row0<KD>(nx, xf, zf);      // row GR + 1 uses xf[1] and ring slot GR - 1 only
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // every dz plane passes once through each kd position (masked when it does not exist); the 2-D
+        // variant only reads position 1
+        if (bias_wave && R < GR)      // wave-uniform
+            accb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones.v, zf[KD == 1 ? 1 : 0][R & 3], accb, 0, 0, 0);
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh) {
+            const int h = R - kh;
+            if (h < 0 || h >= GR) continue;
+#pragma unroll
+            for (int kd = 0; kd < 3; ++kd)
+#pragma unroll
+                for (int kw = 0; kw < 3; ++kw) {
+                    if (KD == 1 && kd != 1) continue;
+                    const int tap = (kd * 3 + kh) * 3 + kw;
+                    acc[tap] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[R & 1][kw], zf[kd][h & 3], acc[tap],
+                                                                       0, 0, 0);
+                }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// MID: the march with the barrier inside the step (see plane_rows_dma and the loop below); otherwise the barrier
+// ends the step.
+template <int KD, bool MID>
 __global__ __launch_bounds__(kThreads) void wgrad_mfma_dma_kernel(WgradArgs a) {
     constexpr int NT = KD == 1 ? 9 : 27, T0 = KD == 1 ? 9 : 0;
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -505,6 +568,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_dma_kernel(WgradArgs a) {
 
     const size_t xplane = static_cast<size_t>(g.ph) * g.pw * xs.cs, zplane = static_cast<size_t>(g.ph) * g.pw * a.dz_cs;
 
+    int sx = 0, sz = 0;       // ring slots of the plane in use; the rings turn on from item to item
     for (int item = gsub; item < a.nitems; item += a.gpp) {
         int t = item;
         const int pw_i = t % a.nw; t /= a.nw;
@@ -559,34 +623,85 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_dma_kernel(WgradArgs a) {
         _Pragma("unroll") for (int j = 0; j < DMA_Z; ++j) dma16(pz + gz[j], lds + lz[j] + (sz) * Z_PLANE);  \
     } while (0)
 
-        // every wave has left the previous item's last plane (the barrier that ended it)
-        SP3D_STAGE(0, 0, 0);
-        SP3D_STAGE(1, 1, 1);
-        asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
+        if (MID) {
+            // The item's march.  Step D: rows 0 .. GR - 1 of x plane D; wait + barrier; stage planes D + 2; rows GR, GR + 1,
+            // during which row 0 of plane D + 1 is read.  At the barrier every wave has finished step D - 1, whose
+            // last rows read x plane D - 1 and dz plane D - 3: the slots that planes D + 2 go to, which is why the
+            // staging stands behind it; and plane D + 1 (staged behind the previous step's barrier, a whole step ago)
+            // has landed when this wave's own loads are done (vmcnt(0): nothing younger is in flight) and every other
+            // wave says the same.  The last two steps of an item stage its last plane again (clamped) into the two slots
+            // behind that plane's in both rings; the next item's first two planes go to the same slots, with no barrier
+            // in between: waves still in the last rows of this item read other slots, and a wave's loads land in order.
+            SP3D_STAGE(0, sx, sz);
+            SP3D_STAGE(1, (sx + 1 == NXB ? 0 : sx + 1), (sz + 1 == NZB ? 0 : sz + 1));
+            asm volatile("s_waitcnt vmcnt(5)" ::: "memory");      // plane 0
+            __builtin_amdgcn_s_barrier();
 
-        const int nplanes = dn + 2;
-        int sx = 0, sz = 0;                   // ring slots of planes D
-        for (int D = 0; D < nplanes; ++D) {
-            {
-                const int sx2 = sx + 2 >= NXB ? sx + 2 - NXB : sx + 2;
-                const int sz2 = sz + 2 >= NZB ? sz + 2 - NZB : sz + 2;
-                SP3D_STAGE(D + 2, sx2, sz2);
+            const int nplanes = dn + 2;
+            bf16x8 xf[2][3], zf[3][4];
+            auto plane_at = [&](int D, int sxD, int szD) {
+                const int sz1 = szD == 0 ? NZB - 1 : szD - 1;
+                const int sz2m = sz1 == 0 ? NZB - 1 : sz1 - 1;
+                DmaPlane pl;
+                pl.x = xlane + sxD * XD_BYTES;
+                pl.z[0] = zlane + szD * Z_PLANE; pl.z[1] = zlane + sz1 * Z_PLANE; pl.z[2] = zlane + sz2m * Z_PLANE;
+                pl.m[0] = D < dn ? 0xffffffffu : 0u;
+                pl.m[1] = (D >= 1 && D - 1 < dn) ? 0xffffffffu : 0u;
+                pl.m[2] = D >= 2 ? 0xffffffffu : 0u;
+                return pl;
+            };
+            DmaPlane cur = plane_at(0, sx, sz);
+            dma_row0<KD>(cur, xf, zf);
+            for (int D = 0; D < nplanes; ++D) {
+                const int sxn = sx + 1 == NXB ? 0 : sx + 1, szn = sz + 1 == NZB ? 0 : sz + 1;
+                const DmaPlane nxt = plane_at(D + 1, sxn, szn);
+                // (2-D variant: x planes 0 and dn + 1 are the undefined D margins and meet no dz plane; their
+                // rows are skipped but the fragments of the next plane's first row are still read)
+                const bool live = KD == 3 || (D >= 1 && D <= dn);
+                if (live) plane_rows_dma<KD, 0, GR>(cur, nxt, bias_wave, xf, zf, acc, accb);
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                {
+                    const int sx2 = sx + 2 >= NXB ? sx + 2 - NXB : sx + 2;
+                    const int sz2 = sz + 2 >= NZB ? sz + 2 - NZB : sz + 2;
+                    SP3D_STAGE(D + 2, sx2, sz2);
+                }
+                if (live) plane_rows_dma<KD, GR, GR + 2>(cur, nxt, bias_wave, xf, zf, acc, accb);
+                else dma_row0<KD>(nxt, xf, zf);
+                cur = nxt;
+                sx = sxn;
+                sz = szn;
             }
-            const int sz1 = sz == 0 ? NZB - 1 : sz - 1;
-            const int sz2m = sz1 == 0 ? NZB - 1 : sz1 - 1;
-            const uint32_t m0 = D < dn ? 0xffffffffu : 0u;
-            const uint32_t m1 = (D >= 1 && D - 1 < dn) ? 0xffffffffu : 0u;
-            const uint32_t m2 = D >= 2 ? 0xffffffffu : 0u;
-            // (2-D variant: x planes 0 and dn + 1 are the undefined D margins and meet no dz plane)
-            if (KD == 3 || (D >= 1 && D <= dn))
-                plane_step_dma<KD>(xlane + sx * XD_BYTES, zlane + sz * Z_PLANE, zlane + sz1 * Z_PLANE,
-                           zlane + sz2m * Z_PLANE, m0, m1, m2, bias_wave, acc, accb);
-            // plane D + 1 (staged one step ago) has landed once at most this step's loads are in flight
+        } else {
+            // every wave has left the previous item's last plane (the barrier that ended it)
+            SP3D_STAGE(0, 0, 0);
+            SP3D_STAGE(1, 1, 1);
             asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
             __builtin_amdgcn_s_barrier();
-            sx = sx + 1 == NXB ? 0 : sx + 1;
-            sz = sz + 1 == NZB ? 0 : sz + 1;
+
+            const int nplanes = dn + 2;
+            sx = 0; sz = 0;                   // ring slots of planes D
+            for (int D = 0; D < nplanes; ++D) {
+                {
+                    const int sx2 = sx + 2 >= NXB ? sx + 2 - NXB : sx + 2;
+                    const int sz2 = sz + 2 >= NZB ? sz + 2 - NZB : sz + 2;
+                    SP3D_STAGE(D + 2, sx2, sz2);
+                }
+                const int sz1 = sz == 0 ? NZB - 1 : sz - 1;
+                const int sz2m = sz1 == 0 ? NZB - 1 : sz1 - 1;
+                const uint32_t m0 = D < dn ? 0xffffffffu : 0u;
+                const uint32_t m1 = (D >= 1 && D - 1 < dn) ? 0xffffffffu : 0u;
+                const uint32_t m2 = D >= 2 ? 0xffffffffu : 0u;
+                // (2-D variant: x planes 0 and dn + 1 are the undefined D margins and meet no dz plane)
+                if (KD == 3 || (D >= 1 && D <= dn))
+                    plane_step_dma<KD>(xlane + sx * XD_BYTES, zlane + sz * Z_PLANE, zlane + sz1 * Z_PLANE,
+                               zlane + sz2m * Z_PLANE, m0, m1, m2, bias_wave, acc, accb);
+                // plane D + 1 (staged one step ago) has landed once at most this step's loads are in flight
+                asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                sx = sx + 1 == NXB ? 0 : sx + 1;
+                sz = sz + 1 == NZB ? 0 : sz + 1;
+            }
         }
     }
 #undef SP3D_STAGE
@@ -739,22 +854,31 @@ int launch_wgrad_mfma(const void *Px, const void *Pdz, float *dw, float *db, con
     // more than 64 KB of dynamic LDS has to be requested explicitly
     using Kern = void (*)(WgradArgs);
     static const Kern plain[2] = {wgrad_mfma_kernel<3>, wgrad_mfma_kernel<1>};          // [2-D variant]
-    static const Kern dma[2] = {wgrad_mfma_dma_kernel<3>, wgrad_mfma_dma_kernel<1>};
+    static const Kern dma[2][2] = {{wgrad_mfma_dma_kernel<3, false>, wgrad_mfma_dma_kernel<1, false>},
+                                   {wgrad_mfma_dma_kernel<3, true>, wgrad_mfma_dma_kernel<1, true>}};      // [MID][2-D variant]
     static const hipError_t attr = [] {
         for (int i = 0; i < 2; ++i) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(plain[i]),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
             if (e != hipSuccess) return e;
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(dma[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    DMA_LDS_BYTES);
-            if (e != hipSuccess) return e;
+            for (int m = 0; m < 2; ++m) {
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(dma[m][i]),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, DMA_LDS_BYTES);
+                if (e != hipSuccess) return e;
+            }
         }
         return hipSuccess;
     }();
     if (attr != hipSuccess) return record_hip(attr);
     // whole patches only: the direct-to-LDS loads cannot zero-fill a ragged edge
+    // The march with the barrier inside the step has no idle matrix cores at a plane boundary but stages one step
+    // ahead where the other stages two (the rings have no slot for more).  Measured: it wins where a launch has few
+    // channel pairs (32 -> 32 at 512^3: 6.00 -> 5.79 ms; 64 -> 64: -2 %) and loses from 16 pairs on (128 channels
+    // + 1 %, 256 + 5 %, 512 + 6 %), where many workgroups stream different planes at once and a plane takes longer
+    // to arrive than a step lasts.
+    const int mid = (cin / C) * (cout / C) <= 4 ? 1 : 0;
     if (g.th % PH == 0 && g.tw % PW == 0)
-        hipLaunchKernelGGL(dma[g.flat], dim3(grid), dim3(kThreads), DMA_LDS_BYTES, s, a);
+        hipLaunchKernelGGL(dma[mid][g.flat], dim3(grid), dim3(kThreads), DMA_LDS_BYTES, s, a);
     else
         hipLaunchKernelGGL(plain[g.flat], dim3(grid), dim3(kThreads), LDS_BYTES, s, a);
     int rc = record_hip(hipGetLastError());
