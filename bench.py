@@ -292,6 +292,20 @@ def main():
         torch.cuda.synchronize()
         return sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
 
+    # an event pair around a single launch of 70 us also times the gaps between the markers and the kernel (a few
+    # microseconds: the kernel trace of the same launches reads 4 - 6 % less); a run of launches between one pair
+    # of events, divided by their number, is closer to the kernel's own duration
+    def batch_ms(f, reps=20):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            f()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    batch = {"halo_pack": batch_ms(lambda: sp3d.halo_pack(Px, M, gb, c, dt, stream)),
+             "halo_unpack": batch_ms(lambda: sp3d.halo_unpack(Px, M, gb, c, dt, stream))}
     exchange_ms = median_ms(lambda: sp3d.sp_halo_exchange(Px, gb, c, dt, stream))
     full_ms = {"halo_pack": median_ms(lambda: sp3d.halo_pack(Px, M, g, c, dt, stream)),
                "halo_unpack": median_ms(lambda: sp3d.halo_unpack(Px, M, g, c, dt, stream)),
@@ -361,10 +375,14 @@ def main():
     nb_bytes = nb_vox * c * 2              # message bytes that have a receiving tile
     unpack_bytes = msg_bytes + nb_bytes    # without the flags: every margin written, those with a neighbour read
 
-    def hbm(kernel, nbytes, ms, note):
+    def hbm(kernel, nbytes, ms, note, ms_batch=None):
         gbs = nbytes / (ms * 1e-3) / 1e9
-        return {"kernel": kernel, "bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": round(gbs / PEAK_HBM_GBS, 4), "bytes": int(nbytes), "ms": round(ms, 4), "what": note}
+        r = {"kernel": kernel, "bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+             "frac": round(gbs / PEAK_HBM_GBS, 4), "bytes": int(nbytes), "ms": round(ms, 4), "what": note}
+        if ms_batch is not None:       # 20 launches in a row between one pair of events, per launch
+            r["ms_in_a_batch"] = round(ms_batch, 4)
+            r["frac_in_a_batch"] = round(nbytes / (ms_batch * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)
+        return r
 
     other = [
         {"kernel": "wgrad_mfma_kernel (conv3d_wgrad)", "bound": "mfma",
@@ -372,9 +390,11 @@ def main():
          "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
          "frac": round(flop_pass / (avg_ms["conv3d_wgrad"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)},
         hbm("halo_pack", 2 * nb_bytes, avg_ms["halo_pack"],
-            "in the step, SP_HALO_SKIP_SEND: the regions that have a receiver, read + written once"),
+            "in the step, SP_HALO_SKIP_SEND: the regions that have a receiver, read + written once",
+            batch["halo_pack"]),
         hbm("halo_unpack", 2 * nb_bytes, avg_ms["halo_unpack"],
-            "in the step, SP_HALO_KEEP_ZERO: the margins that have a neighbour, read + written once"),
+            "in the step, SP_HALO_KEEP_ZERO: the margins that have a neighbour, read + written once",
+            batch["halo_unpack"]),
         hbm("halo_pack, all 26 regions", 2 * msg_bytes, full_ms["halo_pack"],
             "after the step, no flags: every region read + written (a third of them have no receiver on this grid)"),
         hbm("halo_unpack, border zero-filled", unpack_bytes, full_ms["halo_unpack"],
