@@ -36,7 +36,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM traffic per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script with --calib-copy (each counter scaled by what it reads for the plain 1 GiB copy of known size:
 # FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); None = not measured at that size.
-MEASURED_TRAFFIC_BYTES = {512: 18.60e9}
+MEASURED_TRAFFIC_BYTES = {512: 18.53e9}
 
 
 def parse():
