@@ -229,9 +229,9 @@ __device__ __forceinline__ void side_fence(pin_t (&p)[2][4], mask_t (&m)[2][4]) 
 // Measured: the mask gains from them (3-D 32 -> 32 at 512^3: 7.45 -> 7.08 ms; 2-D: 8 - 9 %; the 3-D two-chunk
 // kernel 3 %, now that part of its weight fragments live in LDS - while its registers were all taken the second
 // register set cost 4.07 -> 4.71 ms).  Partial sums: ordinary loads in the one-chunk kernel; in the two-chunk
-// kernel the wave that finishes a plane has no room for a second set of 32 registers (tried: it spills, and the
-// reloads wait on the same counter: 4 % slower), so there the OTHER chunk's wave, which has no epilogue, fetches
-// them ahead and adds them to what it hands over (conv_mfma_pair_kernel.h).
+// kernel a wave finishes one row of its two (conv_mfma_pair_kernel.h) and has room for a second set of that row's
+// 16 registers.  (While one wave finished both rows, the second set of 32 registers spilled, and the reloads
+// wait on the same counter: 4 % slower than ordinary loads, which cost 35 - 45 % of the cycles of a launch.)
 template <int MODE, int RELU, int KD, bool PAIR> struct Side {
     static constexpr bool PINS = MODE == kMiddle || MODE == kLast;
     static constexpr bool MASK = (RELU == kMask || RELU == kMaskBits) && (MODE == kSingle || MODE == kLast);

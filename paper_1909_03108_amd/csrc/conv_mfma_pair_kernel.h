@@ -6,12 +6,12 @@
 // wide layers bandwidth-bound.  Here a workgroup contracts 64 input channels at once and adds the two
 // halves on chip: the patch is 4 rows x 32 columns, waves 0, 1 take input chunk 0 and waves 2, 3 chunk 1
 // of the pair, each for one row group of 2 rows, with the same register-resident weights, D march and
-// fragment reuse as above.  When an output plane is complete, the chunk-1 wave writes its 2 x 16
-// accumulators to a small LDS buffer (during the next step, between its MFMAs); one step later, after the
-// step barrier, the chunk-0 wave of the same rows adds them to its own, converts and stores.  A plane
-// therefore lives in an accumulator slot for five steps (three contributing, one being handed over, one
-// being stored), hence five slots.  Layers with more than one pair still go through fp32 partial sums, but
-// half as often.
+// fragment reuse as above.  The two waves with the same rows (one per chunk) share the epilogue by rows: when an
+// output plane is complete, each writes the accumulators of ONE of its two rows to a small LDS buffer (during
+// the next step, between its MFMAs); one step later, after the step barrier, the other adds them to its own,
+// converts and stores - the chunk-0 wave finishes row 0, the chunk-1 wave row 1.  A plane therefore lives in
+// an accumulator slot for five steps (three contributing, one being handed over, one being stored), hence
+// five slots.  Layers with more than one pair still go through fp32 partial sums, but half as often.
 #pragma once
 #include "conv_mfma_common.h"
 
@@ -84,18 +84,21 @@ __device__ __forceinline__ mask_t load_mask(const Ctx<HAS_BIAS> &c, int d, int h
     return v;
 }
 
-// what the chunk-1 wave wrote for store unit q of row h (see give_unit)
+// what the partner wrote for store unit q of row h (see give_unit)
 __device__ __forceinline__ float4 handed_over(const char *red, int h, int q) {
     return *reinterpret_cast<const float4 *>(red + (h * 4 + q) * 1024);
 }
-// chunk-0 wave: finish 4 channels of row h of plane d: own sum + what the partner handed over (from LDS: its own
-// sum and, in the launches after a layer's first, the earlier pairs' partial sums), then store the new partial
-// (fp32) or ReLU / convert / store bf16
+// finish 4 channels of row h of plane d: (own sum + what the partner handed over, from LDS) + the earlier pairs'
+// partial sums in the launches after a layer's first, then store the new partial (fp32) or ReLU / convert / store
+// bf16.  The order of the additions is the same whichever of the two waves finishes the row: a voxel that two
+// tiles both compute (a block of layers after one exchange) may be in row 0 in one and in row 1 in the other, and
+// has to come out with the same bits.
 // (o: what handed_over read for this unit)
 template <int MODE, int RELU, bool FULL, bool HAS_BIAS>
 __device__ __forceinline__ void finish_unit(const Ctx<HAS_BIAS> &c, int d, const f32x16 (&s)[RH], const float4 &o,
-                                            mask_t (&mk)[RH][4], int h, int q) {
+                                            const pin_t (&pin)[RH][4], mask_t (&mk)[RH][4], int h, int q) {
     float v0 = s[h][4 * q] + o.x, v1 = s[h][4 * q + 1] + o.y, v2 = s[h][4 * q + 2] + o.z, v3 = s[h][4 * q + 3] + o.w;
+    if (MODE == kMiddle || MODE == kLast) { v0 += pin[h][q].x; v1 += pin[h][q].y; v2 += pin[h][q].z; v3 += pin[h][q].w; }
     const size_t at = d * c.oplane + h * c.orow + 8 * q;
     if (MODE == kFirst || MODE == kMiddle) {
         if (FULL || c.okrow[h]) *reinterpret_cast<float4 *>(c.pbase + part_unit(d, h, q)) = make_float4(v0, v1, v2, v3);
@@ -126,71 +129,74 @@ __device__ __forceinline__ void finish_unit(const Ctx<HAS_BIAS> &c, int d, const
     }
 }
 
-// chunk-1 wave: hand 4 channels of row h of a complete plane over to the chunk-0 wave
-// (PINS: plus the partial sums of the earlier pairs.  They are fetched by THIS wave, which has no epilogue of its
-// own and so has the registers for a second set of them: the fetch runs a step ahead - see side_load - where the
-// chunk-0 wave, whose registers are taken, had to load them at the start of the step that used them and sat out
-// the latency, 35 - 45 % of its cycles in the launches after a layer's first)
-template <bool PINS>
-__device__ __forceinline__ void give_unit(const f32x16 (&s)[RH], char *red, const pin_t (&pin)[RH][4], int h, int q) {
-    float4 v = make_float4(s[h][4 * q], s[h][4 * q + 1], s[h][4 * q + 2], s[h][4 * q + 3]);
-    if (PINS) { v.x += pin[h][q].x; v.y += pin[h][q].y; v.z += pin[h][q].z; v.w += pin[h][q].w; }
-    *reinterpret_cast<float4 *>(red + (h * 4 + q) * 1024) = v;
+// hand 4 channels of row h of a complete plane over to the partner
+__device__ __forceinline__ void give_unit(const f32x16 (&s)[RH], char *red, int h, int q) {
+    *reinterpret_cast<float4 *>(red + (h * 4 + q) * 1024) =
+        make_float4(s[h][4 * q], s[h][4 * q + 1], s[h][4 * q + 2], s[h][4 * q + 3]);
+}
+
+// The wait of a step (NV vector-memory operations may stay outstanding, LDS operations none) with one row's side
+// registers as operands (see side_fence): the partial sums of the row the wave hands over, the mask values - or,
+// in the bit form, the one word kept in m[0].x - of the row it finishes.
+template <int NV, bool PINS, bool MASK, bool BITS>
+__device__ __forceinline__ void side_fence_row(pin_t (&p)[4], mask_t (&m)[4]) {
+    static_assert(!(MASK && BITS), "one form of the mask");
+#define SP3D_ROW4(a) "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3])
+    if (PINS && MASK) asm volatile("s_waitcnt vmcnt(%8) lgkmcnt(0)" : SP3D_ROW4(p), SP3D_ROW4(m) : "n"(NV) : "memory");
+    else if (PINS && BITS) asm volatile("s_waitcnt vmcnt(%5) lgkmcnt(0)" : SP3D_ROW4(p), "+v"(m[0].x) : "n"(NV) : "memory");
+    else if (PINS) asm volatile("s_waitcnt vmcnt(%4) lgkmcnt(0)" : SP3D_ROW4(p) : "n"(NV) : "memory");
+    else if (MASK) asm volatile("s_waitcnt vmcnt(%4) lgkmcnt(0)" : SP3D_ROW4(m) : "n"(NV) : "memory");
+    else if (BITS) asm volatile("s_waitcnt vmcnt(%1) lgkmcnt(0)" : "+v"(m[0].x) : "n"(NV) : "memory");
+    else asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(NV) : "memory");
+#undef SP3D_ROW4
 }
 
 // One staged input plane Dp.  P = Dp mod 5: output plane Dp - kd accumulates in slot (P - kd) mod 5.
-// ROLE 1 (chunk 1): GIVE = plane Dp - 3 (slot (P + 2) mod 5) goes to the hand-over buffer Dp & 1 and its
-// slot is cleared.  ROLE 0 (chunk 0): FIN = plane Dp - 4 (slot (P + 1) mod 5) is finished from the buffer
-// written in the previous step, (Dp - 1) & 1, and its slot returns to the bias.
-// SIDE (chunk-0 wave; see side_load): kSideNone - the step loads its own partial sums / mask values (pin, mk)
-// the ordinary way; otherwise it uses the ones the previous step fetched (kSideUse) and first of all fetches
-// those of the plane that the next step finishes, Dp - 3, into the other set (npin, nmk), which the caller
-// passes through the wait that ends the step.
+// The epilogue of the pair's 2 x 2 rows is shared by rows: the wave of chunk ROLE finishes row ROLE of its row
+// group and hands row 1 - ROLE over to its partner (the wave of the other chunk with the same rows).
+// GIVE: row 1 - ROLE of plane Dp - 3 (slot (P + 2) mod 5) goes to the hand-over buffer Dp & 1.  FIN: row ROLE of
+// plane Dp - 4 (slot (P + 1) mod 5) is finished with what the partner wrote in the previous step, buffer
+// (Dp - 1) & 1, and - in the launches after a layer's first - the earlier pairs' partial sums.  A slot returns
+// to the bias (chunk 0) or zero (chunk 1) when it becomes the slot of plane Dp + 1.  (With all the finishing on
+// the chunk-0 wave and all the handing over on the chunk-1 wave, a step lasted as long as the former's epilogue.)
+// SIDE (see side_load): the partial sums and mask values of the row that the NEXT step finishes (plane Dp - 3)
+// are fetched at the start of this step into the other register set (npin, nmk) and pass through the step's
+// wait; the step itself uses what the previous one fetched (pin, mk).  Without it the step loads what it needs
+// the ordinary way.
 // lcur / lnxt: this lane's LDS read base in the ring slots of planes Dp / Dp + 1; b0: the fragments of the first
 // MFMA group, read (and waited for) by the previous step; on return those of the next step.  NV: how many
 // vector-memory operations the step's wait, which stands before its last MFMA group, lets stay in flight.
-template <int P, int ROLE, bool GIVE, bool FIN, int MODE, int RELU, bool FULL, int KD, int SIDE, int NV, bool HAS_BIAS>
+template <int P, int ROLE, bool GIVE, bool FIN, int MODE, int RELU, bool FULL, int KD, bool SIDE, int NV, bool HAS_BIAS>
 __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, uint32_t lcur, uint32_t lnxt,
                                            const bf16x8 (&wf)[NFRAG], f32x16 (&acc)[NSLOT][RH],
                                            pin_t (&pin)[RH][4], mask_t (&mk)[RH][4],
                                            pin_t (&npin)[RH][4], mask_t (&nmk)[RH][4], bf16x8 (&b0)[RH + 2]) {
     constexpr int NR = RH + 2;
     static_assert(NR == 4, "frag_wait names four fragments");
+    static_assert(RH == 2, "one row to finish, one to hand over");
     static_assert(2 * CH_STRIDE + ((RH + 1) * LCOLS + 2) * 16 < 65536, "offset field of the LDS reads");
-    constexpr int SSLOT = ROLE == 1 ? (P + 2) % NSLOT : (P + 1) % NSLOT;     // slot of the side work
+    constexpr int FROW = ROLE, GROW = 1 - ROLE;      // the row this wave finishes / hands over
+    constexpr int GSLOT = (P + 2) % NSLOT, FSLOT = (P + 1) % NSLOT;
     constexpr int NEXT = (P + 1) % NSLOT;      // slot of output plane Dp + 1: must be clean when this step ends
-    constexpr bool ACTIVE = ROLE == 1 ? GIVE : FIN;
     using S = Side<MODE, RELU, KD, true>;
     bf16x8 b[2][NR];
     char *red_w = c.red + (Dp & 1) * RED_BYTES;
     const char *red_r = c.red + ((Dp - 1) & 1) * RED_BYTES;
-    if (ROLE == 0 && SIDE != kSideNone) {          // mask values of the plane that the next step finishes
+    if (SIDE) {
 #pragma unroll
-        for (int h = 0; h < RH; ++h)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const size_t at = (Dp - 3) * c.oplane + h * c.orow + 8 * q;
-                if (S::MASK && !S::BITS) side_load(nmk[h][q], c.mbase + at);
-                if (S::BITS && q == 0) SP3D_SIDE_LOAD_BITS(nmk[h][0].x, c.bbase + bits_off(c, Dp - 3, h));
-            }
+        for (int q = 0; q < 4; ++q) {
+            const size_t at = (Dp - 3) * c.oplane + FROW * c.orow + 8 * q;
+            if (S::PINS) side_load(npin[FROW][q], c.pbase + part_unit(Dp - 3, FROW, q));
+            if (S::MASK && !S::BITS) side_load(nmk[FROW][q], c.mbase + at);
+            if (S::BITS && q == 0) SP3D_SIDE_LOAD_BITS(nmk[FROW][0].x, c.bbase + bits_off(c, Dp - 3, FROW));
+        }
     }
-    if (ROLE == 1 && SIDE != kSideNone && S::PINS) {      // partial sums of the plane that the next step hands over
+    if (!SIDE && FIN) {
 #pragma unroll
-        for (int h = 0; h < RH; ++h)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) side_load(npin[h][q], c.pbase + part_unit(Dp - 2, h, q));
-    }
-    if (SIDE == kSideNone && ROLE == 1 && GIVE && S::PINS) {
-#pragma unroll
-        for (int h = 0; h < RH; ++h)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) pin[h][q] = load_partial<FULL>(c, Dp - 3, h, q);
-    }
-    if (SIDE == kSideNone && ROLE == 0 && FIN && S::MASK) {
-#pragma unroll
-        for (int h = 0; h < RH; ++h)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) mk[h][q] = load_mask<FULL, S::BITS>(c, Dp - 4, h, q);
+        for (int q = 0; q < 4; ++q) {
+            if (S::PINS) pin[FROW][q] = load_partial<FULL>(c, Dp - 4, FROW, q);
+            if (S::MASK) mk[FROW][q] = load_mask<FULL, S::BITS>(c, Dp - 4, FROW, q);
+        }
     }
 #pragma unroll
     for (int r = 0; r < NR; ++r) b[0][r] = b0[r];
@@ -208,8 +214,7 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, uint3
             // LOADS - 1 are in flight; this wave's hand-over writes (issued in groups 0 - 3) have reached LDS and
             // its reads of plane Dp and of the other role's hand-over are done (lgkmcnt(0)).  Behind the barrier
             // the first group of the next step is read while this step's last 18 MFMAs run.
-            side_fence<NV, true, SIDE != kSideNone && ROLE == 1 && S::PINS, SIDE != kSideNone && ROLE == 0 && S::MASK,
-                       SIDE != kSideNone && ROLE == 0 && S::BITS>(npin, nmk);
+            side_fence_row<NV, SIDE && S::PINS, SIDE && S::MASK && !S::BITS, SIDE && S::BITS>(npin[FROW], nmk[FROW]);
             __builtin_amdgcn_s_barrier();
 #pragma unroll
             for (int r = 0; r < NR; ++r) frag_read(b[0][r], lnxt, (r * LCOLS) * 16);
@@ -218,14 +223,10 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, uint3
         frag_wait<NR>(b[gi & 1]);
         // the two weight fragments of this group that live in LDS (see WL_FRAGS); the MFMAs that use them are
         // the last of the group
-        // ... and what the chunk-1 wave handed over for this group's two store units: read here, at the top of the
-        // group, six and more MFMAs before the first addition that needs it (read where it is used, inside the
-        // unit, each of the eight units of a step began by waiting out an LDS latency: a sixth of the wave's cycles)
-        float4 ho[RH];
-        if (ROLE == 0 && ACTIVE && gi < 4) {
-#pragma unroll
-            for (int h = 0; h < RH; ++h) ho[h] = handed_over(red_r, h, gi);
-        }
+        // ... and what the partner handed over for this group's store unit: read here, at the top of the group, six
+        // and more MFMAs before the first addition that needs it
+        float4 ho = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (FIN && gi < 4) ho = handed_over(red_r, FROW, gi);
         bf16x8 wl2[2];
         if (KD == 3) {
             wl2[0] = *reinterpret_cast<const bf16x8 *>(c.wl + wl_index(1, kw, half) * 1024);
@@ -236,26 +237,22 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, uint3
         stage(c, Dp + DIST, gi);
         if (gi < 2) stage(c, Dp + DIST, NG + gi);
         if (gi < 4) {
-            if (ACTIVE) {
-                // (ties the copies out of the accumulation registers to this group; otherwise the compiler emits
-                // all 32 at the top of the step, in front of its first MFMA)
-                asm volatile("" : "+a"(acc[SSLOT][0]), "+a"(acc[SSLOT][1]));
-                if (ROLE == 1) {
-                    give_unit<S::PINS>(acc[SSLOT], red_w, pin, 0, gi);
-                    give_unit<S::PINS>(acc[SSLOT], red_w, pin, 1, gi);
-                } else {
-                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], ho[0], mk, 0, gi);
-                    finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], ho[1], mk, 1, gi);
-                }
+            // (the empty statements tie the copies out of the accumulation registers to this group; otherwise the
+            // compiler emits all of them at the top of the step, in front of its first MFMA)
+            if (GIVE) {
+                asm volatile("" : "+a"(acc[GSLOT][GROW]));
+                give_unit(acc[GSLOT], red_w, GROW, gi);
+            }
+            if (FIN) {
+                asm volatile("" : "+a"(acc[FSLOT][FROW]));
+                finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[FSLOT], ho, pin, mk, FROW, gi);
             }
         } else {
             // the slot of the next output plane starts from the bias (chunk 0) or zero (chunk 1); in the first
-            // steps it holds sums for planes that do not exist.  A handed-over slot is cleared as well.
+            // steps it holds sums for planes that do not exist
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
+            for (int i = 0; i < 16; ++i)
                 acc[NEXT][gi - 4][i] = (ROLE == 0 && HAS_BIAS) ? c.bv[HAS_BIAS ? i : 0] : 0.f;
-                if (ROLE == 1 && GIVE) acc[SSLOT][gi - 4][i] = 0.f;
-            }
         }
 #pragma unroll
         for (int r = 0; r < NR; ++r)
@@ -285,56 +282,47 @@ __device__ __forceinline__ void plane_step(const Ctx<HAS_BIAS> &c, int Dp, uint3
     for (int r = 0; r < NR; ++r) b0[r] = b[0][r];
 }
 
-// The two steps after the last input plane: only the side work is left.  Dp = nplanes: chunk 1 hands over
-// the last output plane (Dp - 3 = dn - 1), chunk 0 finishes plane Dp - 4; Dp = nplanes + 1: chunk 0 finishes
-// the last plane.  Same slot arithmetic as plane_step, so every accumulator index stays a constant.
-template <int P, int ROLE, bool GIVE, bool FIN, int MODE, int RELU, bool FULL, int KD, int SIDE, bool HAS_BIAS>
+// The two steps after the last input plane: only the side work is left.  Dp = nplanes: the last output plane
+// (Dp - 3 = dn - 1) is handed over and plane Dp - 4 finished; Dp = nplanes + 1: the last plane is finished.  Same
+// slot arithmetic as plane_step, so every accumulator index stays a constant.
+template <int P, int ROLE, bool GIVE, bool FIN, int MODE, int RELU, bool FULL, int KD, bool SIDE, bool HAS_BIAS>
 __device__ __forceinline__ void drain_step(const Ctx<HAS_BIAS> &c, int Dp, f32x16 (&acc)[NSLOT][RH],
                                            pin_t (&pin)[RH][4], mask_t (&mk)[RH][4],
                                            pin_t (&npin)[RH][4], mask_t (&nmk)[RH][4]) {
-    constexpr int SSLOT = ROLE == 1 ? (P + 2) % NSLOT : (P + 1) % NSLOT;
+    constexpr int FROW = ROLE, GROW = 1 - ROLE;
+    constexpr int GSLOT = (P + 2) % NSLOT, FSLOT = (P + 1) % NSLOT;
     using S = Side<MODE, RELU, KD, true>;
-    // side loads: the first drain step, and a step 3 that is one already (a march of three planes), fetch for
-    // the step after them like a plane step
-    if (ROLE == 0 && SIDE != kSideNone && Dp <= c.nplanes) {
+    if (GIVE && Dp == c.nplanes) {
+        char *red_w = c.red + (Dp & 1) * RED_BYTES;
 #pragma unroll
-        for (int h = 0; h < RH; ++h)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const size_t at = (Dp - 3) * c.oplane + h * c.orow + 8 * q;
-                if (S::MASK && !S::BITS) side_load(nmk[h][q], c.mbase + at);
-                if (S::BITS && q == 0) SP3D_SIDE_LOAD_BITS(nmk[h][0].x, c.bbase + bits_off(c, Dp - 3, h));
-            }
+        for (int q = 0; q < 4; ++q) give_unit(acc[GSLOT], red_w, GROW, q);
     }
-    if (ROLE == 1) {
-        // (the partial sums of this last hand-over were fetched by the last plane step)
-        if (GIVE && Dp == c.nplanes) {
-            char *red_w = c.red + (Dp & 1) * RED_BYTES;
-            if (SIDE == kSideNone && S::PINS) {
-#pragma unroll
-                for (int h = 0; h < RH; ++h)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) pin[h][q] = load_partial<FULL>(c, Dp - 3, h, q);
-            }
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                give_unit<S::PINS>(acc[SSLOT], red_w, pin, 0, q);
-                give_unit<S::PINS>(acc[SSLOT], red_w, pin, 1, q);
-            }
-        }
-    } else if (FIN) {
-        const char *red_r = c.red + ((Dp - 1) & 1) * RED_BYTES;
-        if (SIDE == kSideNone && S::MASK) {
-#pragma unroll
-            for (int h = 0; h < RH; ++h)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) mk[h][q] = load_mask<FULL, S::BITS>(c, Dp - 4, h, q);
-        }
+    // Side loads for the step after this one, like a plane step's (a drain step can be step 3 already: a march of
+    // three planes).  From here to the wait that follows the step the code is one straight line: a register with
+    // a load in flight must not meet a block boundary, where the compiler may copy it.  Hence no condition on the
+    // second drain step, which needs nothing: it fetches the last plane's values once more.
+    if (SIDE) {
+        const int dl = min(Dp - 3, c.nplanes - 3);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], handed_over(red_r, 0, q), mk, 0, q);
-            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[SSLOT], handed_over(red_r, 1, q), mk, 1, q);
+            const size_t at = dl * c.oplane + FROW * c.orow + 8 * q;
+            if (S::PINS) side_load(npin[FROW][q], c.pbase + part_unit(dl, FROW, q));
+            if (S::MASK && !S::BITS) side_load(nmk[FROW][q], c.mbase + at);
+            if (S::BITS && q == 0) SP3D_SIDE_LOAD_BITS(nmk[FROW][0].x, c.bbase + bits_off(c, dl, FROW));
         }
+    }
+    if (FIN) {
+        const char *red_r = c.red + ((Dp - 1) & 1) * RED_BYTES;
+        if (!SIDE) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (S::PINS) pin[FROW][q] = load_partial<FULL>(c, Dp - 4, FROW, q);
+                if (S::MASK) mk[FROW][q] = load_mask<FULL, S::BITS>(c, Dp - 4, FROW, q);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            finish_unit<MODE, RELU, FULL>(c, Dp - 4, acc[FSLOT], handed_over(red_r, FROW, q), pin, mk, FROW, q);
     }
 }
 
@@ -413,7 +401,7 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int logical, i
     c.obase = od.base + opos;
     c.mbase = a.mask + opos;
     c.bbase = a.bits + (ovox * a.nco + cj) * 2 + hi;
-    // the chunk-0 wave of row group rg of workgroup `logical`: dchunk planes x RH rows x 4 units x 1 KB
+    // row group rg of workgroup `logical` (both of its waves): dchunk planes x RH rows x 4 units x 1 KB
     c.pbase = a.part + (static_cast<size_t>(logical) * NRG + rg) * a.dchunk * (RH * 4 * 256) + lane * 4;
 #pragma unroll
     for (int h = 0; h < RH; ++h) c.okrow[h] = h0 + rg * RH + h < bx.bh && w0 + oc.c < bx.bw && oc.s < F;
@@ -450,68 +438,57 @@ __device__ __forceinline__ void run(const ConvArgs &a, char *lds, int logical, i
     auto march = [&](auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
         using S = Side<MODE, RELU, KD, true>;
-        // whole patches: the chunk-0 wave fetches its mask values, the chunk-1 wave the partial sums it adds to what
-        // it hands over, one step ahead (see side_load), alternating between two sets of registers.  The chunk-1
-        // wave hands plane Dp - 3 over in step Dp, the chunk-0 wave finishes it in step Dp + 1: the former's chain
-        // of fetches starts a step earlier (step 2 fetches, step 3 is the first to use).
-        constexpr bool ASYNC = FULL && (ROLE == 0 ? S::MASK : S::PINS);
-        constexpr int FETCH = ASYNC ? kSideFetch : kSideNone, USE = ASYNC ? kSideUse : kSideNone;
-        constexpr int SIDE2 = ROLE == 1 ? FETCH : kSideNone, SIDE3 = ROLE == 1 ? USE : FETCH;
+        // whole patches: each wave fetches the partial sums and mask values of the row it finishes one step ahead
+        // (see side_load), alternating between two sets of registers.  Step 4 is the first to finish a row, so
+        // step 3 is the first to fetch.
+        constexpr bool SD = FULL && (S::PINS || S::MASK);
         pin_t pinA[RH][4], pinB[RH][4];
         mask_t mkA[RH][4], mkB[RH][4];
-        // By its wait a step that finishes a plane has issued LOADS - 1 + 8 operations after its side loads, which
-        // the wait lets stay in flight; a fetch-only step, and every step of the chunk-1 wave (which stores nothing),
-        // has issued just LOADS - 1 staging loads after them and waits accordingly; a drain step issues no staging
-        // loads and waits for everything.
-        static_assert(LOADS - 1 + 8 >= NV_STEP, "side loads must be older than what the step's wait lets stay in flight");
-#define SP3D_NV_OF(SIDE_EN) \
-    (((SIDE_EN) == kSideFetch || (ROLE == 1 && (SIDE_EN) != kSideNone)) ? LOADS - 1 : NV_STEP)
-#define SP3D_STEP_END_SIDE(NV, NP, NM)                                              \
-    do {                                                                            \
-        side_fence<NV, true, ASYNC && ROLE == 1 && S::PINS, ASYNC && ROLE == 0 && S::MASK,  \
-                   ASYNC && ROLE == 0 && S::BITS>(NP, NM);                          \
-        __builtin_amdgcn_s_barrier();                                               \
-    } while (0)
-        plane_step<0, ROLE, false, false, MODE, RELU, FULL, KD, kSideNone, NV_STEP>(c, 0, lring, lring + PLANE_BYTES, wf, acc,
-                                                                                   pinA, mkA, pinB, mkB, b0);
-        plane_step<1, ROLE, false, false, MODE, RELU, FULL, KD, kSideNone, NV_STEP>(
+        // By its wait a step has issued LOADS - 1 staging loads after its side loads, and four stores if it
+        // finishes a row: that many operations the wait may let stay in flight (never more than NV_STEP, which
+        // is what it takes for plane Dp + 1 to have landed).  A drain step issues no staging loads and waits for
+        // everything.
+        static_assert(LOADS - 1 + 4 <= NV_STEP, "a wait that covers the side loads covers the staged plane");
+#define SP3D_NV_OF(SIDES, FIN_EN) ((SIDES) ? LOADS - 1 + ((FIN_EN) ? 4 : 0) : NV_STEP)
+        plane_step<0, ROLE, false, false, MODE, RELU, FULL, KD, false, NV_STEP>(
+            c, 0, lring, lring + PLANE_BYTES, wf, acc, pinA, mkA, pinB, mkB, b0);
+        plane_step<1, ROLE, false, false, MODE, RELU, FULL, KD, false, NV_STEP>(
             c, 1, lring + PLANE_BYTES, lring + 2 * PLANE_BYTES, wf, acc, pinA, mkA, pinB, mkB, b0);
-        plane_step<2, ROLE, false, false, MODE, RELU, FULL, KD, SIDE2, SP3D_NV_OF(SIDE2)>(
+        plane_step<2, ROLE, false, false, MODE, RELU, FULL, KD, false, NV_STEP>(
             c, 2, lring + 2 * PLANE_BYTES, lring + 3 * PLANE_BYTES, wf, acc, pinB, mkB, pinA, mkA, b0);
         // Steps 3, 4, ... with slot phase Dp mod 5 as a compile-time constant (the ring slot Dp mod 4 is a
         // run-time offset: a period of 20 steps would be needed to make both constants).  The march runs two
         // steps past the last input plane; those only hand over / finish what is left.  Step 3 is the first
-        // to hand a plane over (and fetches the side values of step 4), step 4 the first to finish one.
-#define SP3D_STEP(DP, PHASE, GIVE_EN, FIN_EN, SIDE_EN, CP, CM, NP, NM)                                     \
+        // to hand a row over, step 4 the first to finish one.
+#define SP3D_STEP(DP, PHASE, FIN_EN, CP, CM, NP, NM)                                                       \
     if ((DP) < nplanes) {                                                                                  \
-        plane_step<PHASE, ROLE, GIVE_EN, FIN_EN, MODE, RELU, FULL, KD, SIDE_EN, SP3D_NV_OF(SIDE_EN)>(      \
+        plane_step<PHASE, ROLE, true, FIN_EN, MODE, RELU, FULL, KD, SD, SP3D_NV_OF(SD, FIN_EN)>(           \
             c, (DP), lring + ((DP) % NBUF) * PLANE_BYTES, lring + (((DP) + 1) % NBUF) * PLANE_BYTES, wf, acc, CP, CM, \
             NP, NM, b0);                                                                                   \
     } else if ((DP) < nplanes + 2) {                                                                       \
-        drain_step<PHASE, ROLE, GIVE_EN, FIN_EN, MODE, RELU, FULL, KD, SIDE_EN>(c, (DP), acc, CP, CM, NP, NM); \
-        SP3D_STEP_END_SIDE(((SIDE_EN) == kSideNone ? (DIST - 1) * LOADS : 0), NP, NM);                     \
+        drain_step<PHASE, ROLE, true, FIN_EN, MODE, RELU, FULL, KD, SD>(c, (DP), acc, CP, CM, NP, NM);     \
+        side_fence_row<(SD ? 0 : (DIST - 1) * LOADS), SD && S::PINS, SD && S::MASK && !S::BITS, SD && S::BITS>( \
+            NP[ROLE], NM[ROLE]);                                                                           \
+        __builtin_amdgcn_s_barrier();                                                                      \
     }
-        SP3D_STEP(3, 3, true, false, SIDE3, pinA, mkA, pinB, mkB)
-        SP3D_STEP(4, 4, true, true, USE, pinB, mkB, pinA, mkA)
+        SP3D_STEP(3, 3, false, pinA, mkA, pinB, mkB)
+        SP3D_STEP(4, 4, true, pinB, mkB, pinA, mkA)
         for (int D = 5; D < nplanes + 2; D += NSLOT) {
-            SP3D_STEP(D, 0, true, true, USE, pinA, mkA, pinB, mkB)
-            SP3D_STEP(D + 1, 1, true, true, USE, pinB, mkB, pinA, mkA)
-            SP3D_STEP(D + 2, 2, true, true, USE, pinA, mkA, pinB, mkB)
-            SP3D_STEP(D + 3, 3, true, true, USE, pinB, mkB, pinA, mkA)
-            SP3D_STEP(D + 4, 4, true, true, USE, pinA, mkA, pinB, mkB)
+            SP3D_STEP(D, 0, true, pinA, mkA, pinB, mkB)
+            SP3D_STEP(D + 1, 1, true, pinB, mkB, pinA, mkA)
+            SP3D_STEP(D + 2, 2, true, pinA, mkA, pinB, mkB)
+            SP3D_STEP(D + 3, 3, true, pinB, mkB, pinA, mkA)
+            SP3D_STEP(D + 4, 4, true, pinA, mkA, pinB, mkB)
             // five steps per round: the sets have changed roles
-            if (ASYNC) {
+            if (SD) {
 #pragma unroll
-                for (int h = 0; h < RH; ++h)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const pin_t tp = pinA[h][q]; pinA[h][q] = pinB[h][q]; pinB[h][q] = tp;
-                        const mask_t tm = mkA[h][q]; mkA[h][q] = mkB[h][q]; mkB[h][q] = tm;
-                    }
+                for (int q = 0; q < 4; ++q) {
+                    const pin_t tp = pinA[ROLE][q]; pinA[ROLE][q] = pinB[ROLE][q]; pinB[ROLE][q] = tp;
+                    const mask_t tm = mkA[ROLE][q]; mkA[ROLE][q] = mkB[ROLE][q]; mkB[ROLE][q] = tm;
+                }
             }
         }
 #undef SP3D_STEP
-#undef SP3D_STEP_END_SIDE
 #undef SP3D_NV_OF
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // clamped staging loads of the last steps
     };
