@@ -190,7 +190,9 @@ typedef uint32_t mask_t __attribute__((ext_vector_type(2)));
 // (DIST - 1) * LOADS operations outstanding) already covers them: the registers pass through that wait as
 // operands (side_fence), nothing reads them earlier, and they hold their data at every block boundary, where
 // the compiler is free to copy them.  The step that uses them needs no wait at all.  Marches over ragged
-// patches, whose loads are predicated, keep the ordinary loads.
+// patches, whose loads are predicated, keep the ordinary loads.  Between a side load and the wait that covers it
+// the code must be one basic block with nothing that makes the compiler move the register: a load issued under
+// a run-time condition is joined to the other path by a copy that runs before the data has arrived.
 __device__ __forceinline__ void side_load(pin_t &d, const float *p) {
     asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(d) : "v"(p) : "memory");
 }

@@ -257,15 +257,16 @@ def test_two_tensor_variants_reject_what_they_cannot_do():
     assert e.value.code == sp3d.SP_EUNSUPPORTED
 
 
-@pytest.mark.parametrize("d", [1, 2, 3, 4, 5, 6, 7, 9])
+@pytest.mark.parametrize("d", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11])
 @pytest.mark.parametrize("cin,cout,flat", [(32, 32, 0), (64, 64, 0), (32, 32, 1), (64, 64, 1), (96, 32, 0), (128, 32, 1),
-                                           (32, 96, 1), (32, 128, 0)])
+                                           (32, 96, 1), (32, 128, 0), (128, 64, 0), (192, 32, 0)])
 def test_every_march_length_with_mask_and_partial_sums(d, cin, cout, flat):
     """Whole patches (the marches that fetch mask values a step ahead into alternating register sets, and keep
     partial sums in fragment order) for every length of the D march modulo the slot and set periods: the masked
     data gradient equals the plain one followed by the mask, bit for bit, and the oracle within tolerance; layers
-    with several launches (96 and 128 kernel input channels, in the forward pass or - with the mask in the last
-    launch - in the data gradient) match the oracle too."""
+    with several launches (96, 128 and 192 kernel input channels, in the forward pass or - with the mask in the last
+    launch - in the data gradient) match the oracle too.  The two-chunk kernel's march ends with two steps that
+    fall on every phase of its five accumulator slots and on either register set as the length runs from 1 to 10."""
     n, dhw, grid = 1, (d, 8, 32), (1, 1, 1)
     g = sp3d.Geom(n, dhw, grid, 1, 0, flat)
     dt = DT["bf16"]
