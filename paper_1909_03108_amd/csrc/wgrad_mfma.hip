@@ -156,7 +156,12 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
     const int per_xcd = gridDim.x >> 3;
     const int group = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (group >= a.ngroups) return;
-    const int pair = group / a.gpp, gsub = group % a.gpp;
+    // Neighbouring groups - the same XCD, hence the same L2 - take the pairs of ONE share of the work items: they
+    // walk the same patches at the same time, and a staged chunk of x is used by cout / 32 of them, a chunk of dz
+    // by cin / 32 (a cache line of a 64-channel tensor holds both of its chunks).
+    const int npairs = a.ngroups / a.gpp;
+    const int pair = group % npairs, gsub = group / npairs;
+    const int slot = pair * a.gpp + gsub;      // where the partial sums go: the pairs one after the other
     const XSrc xs = x_source(a, C * (pair / a.nco));
     const int x_co = xs.co, dz_co = C * (pair % a.nco);   // channel offsets of this pair
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -332,7 +337,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
     }
     __syncthreads();
     if (kg == 0) {
-        float *pw = a.part_w + static_cast<size_t>(group) * NT * C * C;
+        float *pw = a.part_w + static_cast<size_t>(slot) * NT * C * C;
 #pragma unroll
         for (int t = T0; t < T0 + NT; ++t)
 #pragma unroll
@@ -349,7 +354,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs a) {
         const int chunk = tid >> 3, j = tid & 7;
         float s = 0.f;
         for (int k = chunk; k < kThreads; k += 4) s += red[k * 8 + j];
-        a.part_b[group * C + tid] = s;
+        a.part_b[slot * C + tid] = s;
     }
 }
 
@@ -521,7 +526,12 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_dma_kernel(WgradArgs a) {
     const int per_xcd = gridDim.x >> 3;
     const int group = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (group >= a.ngroups) return;
-    const int pair = group / a.gpp, gsub = group % a.gpp;
+    // Neighbouring groups - the same XCD, hence the same L2 - take the pairs of ONE share of the work items: they
+    // walk the same patches at the same time, and a staged chunk of x is used by cout / 32 of them, a chunk of dz
+    // by cin / 32 (a cache line of a 64-channel tensor holds both of its chunks).
+    const int npairs = a.ngroups / a.gpp;
+    const int pair = group % npairs, gsub = group / npairs;
+    const int slot = pair * a.gpp + gsub;      // where the partial sums go: the pairs one after the other
     const XSrc xs = x_source(a, C * (pair / a.nco));
     const int x_co = xs.co, dz_co = C * (pair % a.nco);
     const int tid = threadIdx.x, lane = tid & 63;
@@ -720,7 +730,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_dma_kernel(WgradArgs a) {
     }
     __syncthreads();
     if (kg == 0) {
-        float *pw = a.part_w + static_cast<size_t>(group) * NT * C * C;
+        float *pw = a.part_w + static_cast<size_t>(slot) * NT * C * C;
 #pragma unroll
         for (int t = T0; t < T0 + NT; ++t)
 #pragma unroll
@@ -733,7 +743,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_dma_kernel(WgradArgs a) {
     __syncthreads();
     if (bias_wave && lane < 16) red[(kg * 2 + qo) * 16 + lane] = accb[0];
     __syncthreads();
-    if (tid < C) a.part_b[group * C + tid] = red[tid] + red[C + tid];
+    if (tid < C) a.part_b[slot * C + tid] = red[tid] + red[C + tid];
 }
 
 void plan(const Geo &g, int cin, int cout, WgradArgs *a) {
