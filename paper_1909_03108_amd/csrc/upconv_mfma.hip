@@ -250,12 +250,15 @@ __global__ __launch_bounds__(kT) void upconv_dgrad_mfma_kernel(UpArgs a) {
 //   du[t][ci][co] = sum_v x[v][ci] * dy[2v + t][co],   db[co] = sum over fine voxels of dy[.][co]
 // The reduction runs over voxels while memory keeps channels contiguous, so both operands go through LDS
 // and are read back with the transposing load (4 voxels of one channel per lane and read).  Wave t of a
-// workgroup owns tap t: it stages, for every 32-voxel segment, its own copy of the x rows (NCI blocks of
-// 32 input channels) and the dy rows of its tap (one block of 32 output channels) with direct-to-LDS
-// loads into a private three-slot ring, two segments ahead, and multiplies them - the waves of a
-// workgroup never synchronise.  LDS records are voxel-major, 64 bytes (32 channels) per voxel.
+// workgroup owns tap t.  For every 32-voxel segment the workgroup stages the x rows (NCI blocks of 32 input
+// channels) ONCE - every tap multiplies the same ones - and each wave the dy rows of its tap (one block of 32
+// output channels), with direct-to-LDS loads into a ring of segments shared by the workgroup, one barrier per
+// segment.  (With a private ring per wave, each holding its own copy of the x rows, 144 KB of LDS held two
+// segments ahead, 40 % of whose bytes were distinct: the kernel ran at what that much data in flight gives,
+// 2.7 - 3.3 TB/s at 512^3 and less below.)  LDS records are voxel-major, 64 bytes (32 channels) per voxel.
 // Each workgroup writes its partial sums; a second kernel adds them in workgroup order.
-constexpr int WG_NST = 3;                     // ring slots per wave
+constexpr int wg_ring_slots(int nci) { return nci == 2 ? 7 : 8; }      // 7 x 20 KB, 8 x 18 KB
+constexpr int wg_slot_bytes(int nci) { return (nci + 8) * 2048; }      // x blocks, then the dy blocks of the 8 taps
 
 struct UpWArgs {
     const uint16_t *x, *dy;
@@ -306,18 +309,27 @@ __device__ __forceinline__ bf16x8 tr_frag(const char *p, int lane, int nvalid) {
 template <int NCI, bool FULL>
 __global__ __launch_bounds__(kT) void upconv_wgrad_mfma_kernel(UpWArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    constexpr int STAGE = (NCI + 1) * 2048;          // x blocks, then the dy block: 32 voxels x 64 bytes each
-    constexpr int DM = 2 * (NCI + 1);                // staging loads per segment and wave
-    const int group = blockIdx.x % a.ngroups, sub = blockIdx.x / a.ngroups;
+    constexpr int SLOT = wg_slot_bytes(NCI), R = wg_ring_slots(NCI);
+    constexpr int DM = 3;                            // staging loads per segment and wave
+    // Workgroup ids go round the 8 XCDs: renumbered so that an XCD holds a run of neighbours.  Neighbours are the
+    // channel groups of ONE share of the items: they walk the same segments together, and the x rows that cout / 32
+    // of them stage, the dy rows that cin / (32 NCI) of them stage, come from the XCD's L2 after the first.
+    const int bid = (gridDim.x & 7) == 0 ? (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3) : blockIdx.x;
+    const int group = bid % a.ngroups, sub = bid / a.ngroups;
     const int cg = group / a.nco, cb = group % a.nco;
     const int tid = threadIdx.x, lane = tid & 63;
-    const int tap = __builtin_amdgcn_readfirstlane(tid >> 6);
-    if (tap >= a.ntap) return;                       // the waves never synchronise
-    char *ring = lds + tap * (WG_NST * STAGE);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // 2-D variant: waves 4 .. 7 have no tap; they stage (their share of x, and the last tap's dy once more) and
+    // keep the barriers, nothing else
+    const bool active = wave < a.ntap;
+    const int tap = active ? wave : a.ntap - 1;
     // transposing-read address of this lane inside a 16-voxel group of records
     const int p16 = lane & 15;
     const int tr_off = (8 * (lane >> 5) + (p16 >> 2)) * 64 + (16 * ((lane >> 4) & 1) + 4 * (p16 & 3)) * 2;
     const int sv = lane >> 2, sc = lane & 3;         // staging: voxel within a 16-voxel group, 16-byte chunk
+    // this wave's share of the x rows: one of their 2 NCI loads of 16 voxels (four waves share each when NCI = 1,
+    // two when NCI = 2: the same bytes to the same place)
+    const int xb = NCI == 2 ? (wave >> 1) & 1 : 0, xq = wave & 1;
 
     f32x16 acc[NCI], accb;
 #pragma unroll
@@ -333,44 +345,53 @@ __global__ __launch_bounds__(kT) void upconv_wgrad_mfma_kernel(UpWArgs a) {
 
     auto stage = [&](int item, int slot) {
         const Item o = decode_item(item, a.nseg, a.gc);
-        char *dst = ring + slot * STAGE;
+        char *dst = lds + slot * SLOT;
+        {
+            const int w = min(o.w0 + 16 * xq + sv, a.gc.tw - 1);
+            const uint16_t *px = a.x + pvox(a.gc, o.tile, o.d, o.h, w) * a.cin + C * cg * NCI + 8 * sc;
+            dma16_after_reads(px + C * xb, dst + xb * 2048 + xq * 1024);
+        }
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
             const int w = min(o.w0 + 16 * q + sv, a.gc.tw - 1);
-            const uint16_t *px = a.x + pvox(a.gc, o.tile, o.d, o.h, w) * a.cin + C * cg * NCI + 8 * sc;
-#pragma unroll
-            for (int b = 0; b < NCI; ++b) dma16_after_reads(px + C * b, dst + b * 2048 + q * 1024);
             const uint16_t *pz = a.dy + fvox(a.gf, o.tile, o.d, o.h, w, tap) * a.cout + C * cb + 8 * sc;
-            dma16_after_reads(pz, dst + NCI * 2048 + q * 1024);
+            dma16_after_reads(pz, dst + (NCI + tap) * 2048 + q * 1024);
         }
     };
 
-    // items sub, sub + wpg, ...; past the end the last item is staged again (its slot is never read), so
-    // that every wave always has the same number of loads in flight
+    // items sub, sub + wpg, ...  The ring is filled R - 1 segments ahead; past the end the last item is staged
+    // again (into slots that are never read), so that every wave always has the same number of loads in flight.
+    // Every wave of the workgroup walks the same items, so the barriers match.
     const int first = sub, last = first + ((a.nitems - 1 - first) / a.wpg) * a.wpg;
-    stage(first, 0);
-    stage(min(first + a.wpg, last), 1);
+#pragma unroll
+    for (int j = 0; j < R - 1; ++j) stage(min(first + j * a.wpg, last), j);
     int slot = 0;
 #pragma unroll 1
     for (int item = first; item <= last; item += a.wpg) {
-        const int nxt = item + 2 * a.wpg;
-        stage(nxt <= last ? nxt : last, slot >= 1 ? slot - 1 : slot + 2);
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * DM) : "memory");      // this item's loads have landed
-        const char *st = ring + slot * STAGE + tr_off;
-        const int nvalid = FULL ? 32 : a.gc.tw - (item % a.nseg) * SEG;    // real voxels of the segment
+        // this wave's loads of the item have landed; behind the barrier everybody's have, and every wave has
+        // left the item before, whose slot takes the loads of the item R - 1 ahead
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((R - 2) * DM) : "memory");
+        __builtin_amdgcn_s_barrier();
+        const int nxt = item + (R - 1) * a.wpg;
+        stage(nxt <= last ? nxt : last, slot == 0 ? R - 1 : slot - 1);
+        if (active) {
+            const char *st = lds + slot * SLOT + tr_off;
+            const int nvalid = FULL ? 32 : a.gc.tw - (item % a.nseg) * SEG;    // real voxels of the segment
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            const bf16x8 zf = tr_frag<FULL>(st + NCI * 2048 + ks * 1024, lane, nvalid - 16 * ks);
+            for (int ks = 0; ks < 2; ++ks) {
+                const bf16x8 zf = tr_frag<FULL>(st + (NCI + tap) * 2048 + ks * 1024, lane, nvalid - 16 * ks);
 #pragma unroll
-            for (int b = 0; b < NCI; ++b) {
-                const bf16x8 xf = tr_frag<FULL>(st + b * 2048 + ks * 1024, lane, nvalid - 16 * ks);
-                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, zf, acc[b], 0, 0, 0);
+                for (int b = 0; b < NCI; ++b) {
+                    const bf16x8 xf = tr_frag<FULL>(st + b * 2048 + ks * 1024, lane, nvalid - 16 * ks);
+                    acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, zf, acc[b], 0, 0, 0);
+                }
+                if (bias_group) accb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones.v, zf, accb, 0, 0, 0);
             }
-            if (bias_group) accb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones.v, zf, accb, 0, 0, 0);
         }
-        slot = slot == WG_NST - 1 ? 0 : slot + 1;
+        slot = slot == R - 1 ? 0 : slot + 1;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (!active) return;
 
     // lane l holds column co = l % 32 and rows ci = 8 (i/4) + 4 (l/32) + i % 4
     const int wg = group * a.wpg + sub;
@@ -668,7 +689,7 @@ int launch_upconv_wgrad_mfma(const void *Px, const void *Pdy, float *du, float *
     a.part_w = static_cast<float *>(ws);
     a.part_b = a.part_w + static_cast<size_t>(a.ngroups) * a.wpg * 8 * nci * C * C;
     const bool full = gc.tw % SEG == 0;
-    const int lds_bytes = 8 * WG_NST * (nci + 1) * 2048;
+    const int lds_bytes = wg_ring_slots(nci) * wg_slot_bytes(nci);
     hipError_t e = hipSuccess;
     const dim3 grid(a.ngroups * a.wpg), block(kT);
 #define SP3D_UW(NCI, FULL)                                                                              \
