@@ -52,6 +52,13 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
     return r.u;
 }
 
+// Workgroup ids go round the 8 XCDs; renumbered, an XCD holds a run of neighbouring ids: workgroups that walk
+// neighbouring segments, or the channel blocks of the same segments, and share rows and cache lines through the
+// XCD's L2.
+__device__ __forceinline__ int xcd_block() {
+    return (gridDim.x & 7) == 0 ? (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3) : blockIdx.x;
+}
+
 struct Item { int tile, d, h, w0; };
 __device__ __forceinline__ Item decode_item(int item, int nseg, const Geo &gc) {
     Item o;
@@ -78,7 +85,8 @@ __device__ __forceinline__ size_t fvox(const Geo &gf, int tile, int d, int h, in
 template <int NKS>
 __global__ __launch_bounds__(kT) void upconv_fwd_mfma_kernel(UpArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    const int cb = blockIdx.x % a.nblk, sub = blockIdx.x / a.nblk;
+    const int bid = xcd_block();
+    const int cb = bid % a.nblk, sub = bid / a.nblk;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     constexpr int CIN = 16 * NKS;
@@ -183,7 +191,8 @@ __global__ __launch_bounds__(kT) void upconv_fwd_mfma_kernel(UpArgs a) {
 template <int NKS, int GCI>
 __global__ __launch_bounds__(kT) void upconv_dgrad_mfma_kernel(UpArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    const int cg = blockIdx.x % a.nblk, sub = blockIdx.x / a.nblk;
+    const int bid = xcd_block();
+    const int cg = bid % a.nblk, sub = bid / a.nblk;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     constexpr int COUT = 16 * NKS;
@@ -311,10 +320,10 @@ __global__ __launch_bounds__(kT) void upconv_wgrad_mfma_kernel(UpWArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     constexpr int SLOT = wg_slot_bytes(NCI), R = wg_ring_slots(NCI);
     constexpr int DM = 3;                            // staging loads per segment and wave
-    // Workgroup ids go round the 8 XCDs: renumbered so that an XCD holds a run of neighbours.  Neighbours are the
-    // channel groups of ONE share of the items: they walk the same segments together, and the x rows that cout / 32
-    // of them stage, the dy rows that cin / (32 NCI) of them stage, come from the XCD's L2 after the first.
-    const int bid = (gridDim.x & 7) == 0 ? (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3) : blockIdx.x;
+    // neighbours on an XCD (see xcd_block) are the channel groups of ONE share of the items: they walk the same
+    // segments together, and the x rows that cout / 32 of them stage, the dy rows that cin / (32 NCI) of them
+    // stage, come from the XCD's L2 after the first
+    const int bid = xcd_block();
     const int group = bid % a.ngroups, sub = bid / a.ngroups;
     const int cg = group / a.nco, cb = group % a.nco;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -468,7 +477,8 @@ int wgrad_plan(const Geo &gc, int cin, int cout, UpWArgs *a, int *nci) {
 template <int UNUSED = 0>
 __global__ __launch_bounds__(kT) void upconv_fwd_mfma_big_kernel(UpArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    const int blk = blockIdx.x % a.nblk, sub = blockIdx.x / a.nblk;
+    const int bid = xcd_block();
+    const int blk = bid % a.nblk, sub = bid / a.nblk;
     const int tap = blk % a.ntap, cb = blk / a.ntap;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -522,7 +532,8 @@ __global__ __launch_bounds__(kT) void upconv_fwd_mfma_big_kernel(UpArgs a) {
 
 template <int UNUSED = 0>
 __global__ __launch_bounds__(kT) void upconv_dgrad_mfma_big_kernel(UpArgs a) {
-    const int cg = blockIdx.x % a.nblk, sub = blockIdx.x / a.nblk;      // one input-channel block per workgroup
+    const int bid = xcd_block();
+    const int cg = bid % a.nblk, sub = bid / a.nblk;      // one input-channel block per workgroup
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nks = a.cout >> 4;
