@@ -96,7 +96,8 @@ __global__ __launch_bounds__(kThreads) void conv_c1_fwd_kernel(C1Args a, int nhg
     __shared__ __attribute__((aligned(16))) uint16_t lx[2][FXVOX + 8];
     __shared__ __attribute__((aligned(16))) char ly[kThreads / 64][2][YBUF];
     const Geo &g = a.g;
-    int t = blockIdx.x;
+    // workgroup ids go round the 8 XCDs; renumbered, an XCD holds a run of neighbouring row blocks and planes
+    int t = (gridDim.x & 7) == 0 ? (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3) : blockIdx.x;
     const int bh_i = t % nhg; t /= nhg;
     const int od = t % g.td; t /= g.td;               // output plane (interior coordinate)
     const int tile = t;
@@ -258,7 +259,7 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_c1_kernel(C1Args a, int cb)
     uint16_t *lx = reinterpret_cast<uint16_t *>(lds);
     char *lz = lds + (XVOX + 8) * 2;
     const Geo &g = a.g;
-    const int group = blockIdx.x;
+    const int group = (gridDim.x & 7) == 0 ? (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3) : blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 31, kg = lane >> 5;          // A: tap m, voxels 8*kg .. +7 of a 16-voxel step
     const int toff = tap_off(m);

@@ -64,6 +64,14 @@ __device__ __forceinline__ long long pidx(const Geo &g, unsigned tile, unsigned 
     return tile * g.tile_vox + (1LL * (ld + 1) * g.ph + lh + 1) * g.pw + lw + 1;
 }
 
+// Workgroup ids go round the 8 XCDs of the chip; with block i working on the i-th run of voxels every XCD touches
+// every eighth run.  Renumbered (when the grid is a multiple of 8), each XCD streams through one contiguous
+// eighth of the voxels: the pooling kernels, which touch 2 x 2 x 2 rows of the fine tensor per row of the coarse
+// one, run 5 - 6 % faster that way (the one-voxel-per-thread kernels of the 1x1x1 head 2 - 4 % slower: not used there).
+__device__ __forceinline__ unsigned xcd_block() {
+    return (gridDim.x & 7u) == 0 ? (blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3) : blockIdx.x;
+}
+
 // Fine-tensor position k of the window that belongs to coarse voxel o: 2x2x2 windows, k = 4a + 2b + c for
 // offset (a, b, c); in the 2-D variant (g.flat) 1x2x2 windows inside the voxel's own slice, k = 2b + c.
 template <int NW>
@@ -127,7 +135,7 @@ template <int MODE, int NW>
 __global__ __launch_bounds__(kThreads) void maxpool2_x8_kernel(const uint16_t *__restrict__ x,
                                                                const uint16_t *__restrict__ dy, const uint16_t *skip,
                                                                uint16_t *out, Geo gf, Geo gc, Lay l, int C) {
-    const unsigned v = blockIdx.x * (kThreads >> l.cshift) + (threadIdx.x >> l.cshift);
+    const unsigned v = xcd_block() * (kThreads >> l.cshift) + (threadIdx.x >> l.cshift);
     if (v >= l.nvox) return;
     const Vox o = decode(v, l);
     const long long pc = pidx(gc, o.tile, o.ld, o.lh, o.lw);
