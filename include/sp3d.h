@@ -314,6 +314,14 @@ int sp_pointwise_dgrad_relu(const void *Pdy, const void *p, const void *Px, void
                             int cin, int cout, sp_dtype_t dt, void *stream);
 int sp_pointwise_wgrad(const void *Px, const void *Pdy, float *dp, float *db, const sp_geom_t *g,
                        int cin, int cout, sp_dtype_t dt, void *ws, size_t ws_bytes, void *stream);
+/* The whole backward pass of a 1x1x1 layer whose input Px is a ReLU output, in one sweep over Px:
+ * sp_pointwise_dgrad_relu (Pdx, same bits) and sp_pointwise_wgrad (dp, db - may be NULL -, same bits and
+ * workspace, SP_OP_POINTWISE_WGRAD).  Px is read once instead of twice; shapes that the one-sweep kernel does
+ * not serve (more than 4 output channels, Cin not a multiple of 8, fp32) run the two passes one after the
+ * other.  Px must not overlap Pdx.  SP_EINVAL: p or Pdx NULL, overlap; SP_EWORKSPACE as sp_pointwise_wgrad. */
+int sp_pointwise_bwd_relu(const void *Px, const void *Pdy, const void *p, void *Pdx, float *dp, float *db,
+                          const sp_geom_t *g, int cin, int cout, sp_dtype_t dt, void *ws, size_t ws_bytes,
+                          void *stream);
 
 /* Channel concatenation Pout[..][ca+cb] = Pa[..][ca] ++ Pb[..][cb] and its inverse, over ALL voxels of
  * the padded arrays (margins included).  Bit-exact copies. */

@@ -652,6 +652,25 @@ int sp_pointwise_wgrad(const void *Px, const void *Pdy, float *dp, float *db, co
     return launch_wgrad_direct(Px, Pdy, dp, db, o, cin, cout, dt, ws, static_cast<hipStream_t>(stream), 1);
 }
 
+int sp_pointwise_bwd_relu(const void *Px, const void *Pdy, const void *p, void *Pdx, float *dp, float *db,
+                          const sp_geom_t *g, int cin, int cout, sp_dtype_t dt, void *ws, size_t ws_bytes,
+                          void *stream) {
+    if (!p || !Pdx) return SP_EINVAL;
+    Geo o;
+    int rc = check_glue(Px, Pdy, dp, g, cin, cout, dt, &o, nullptr);
+    if (rc != SP_OK) return rc;
+    const size_t bytes = static_cast<size_t>(o.ntiles) * o.tile_vox * cin * elem_size(dt);
+    if (!aligned16(Pdx) || overlap(Px, bytes, Pdx, bytes)) return SP_EINVAL;
+    if (!pointwise_small_supported(o, cin, cout, dt)) {      // the two passes one after the other
+        rc = sp_pointwise_dgrad_relu(Pdy, p, Px, Pdx, g, cin, cout, dt, stream);
+        if (rc != SP_OK) return rc;
+        return sp_pointwise_wgrad(Px, Pdy, dp, db, g, cin, cout, dt, ws, ws_bytes, stream);
+    }
+    if (!ws || ws_bytes < pointwise_small_wgrad_ws_bytes(o, cin, cout) || !aligned16(ws)) return SP_EWORKSPACE;
+    return launch_pointwise_small_wgrad(shifted(Px, o, cin, dt), shifted(Pdy, o, cout, dt), dp, db, o, cin, cout, ws,
+                                        static_cast<hipStream_t>(stream), p, shifted(Pdx, o, cin, dt));
+}
+
 int sp_dice_ce_loss(const void *Plogits, const void *Plabels, void *Pdlogits, float *loss, float *stats,
                     const sp_geom_t *g, int classes, sp_dtype_t dt, float w_dice, float w_ce, float eps, void *ws,
                     size_t ws_bytes, void *stream) {

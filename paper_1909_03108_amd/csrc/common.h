@@ -102,8 +102,9 @@ int launch_pointwise_small_fwd(const void *Px, const void *p, const float *bias,
 int launch_pointwise_small_dgrad(const void *Pdy, const void *p, void *Pdx, const Geo &g, int cin, int cout,
                                  hipStream_t s, const void *Pmask = nullptr);
 size_t pointwise_small_wgrad_ws_bytes(const Geo &g, int cin, int cout);
+// (p, Pdx: null, or the weights and the output of the masked data gradient computed in the same pass)
 int launch_pointwise_small_wgrad(const void *Px, const void *Pdy, float *dp, float *db, const Geo &g, int cin,
-                                 int cout, void *ws, hipStream_t s);
+                                 int cout, void *ws, hipStream_t s, const void *p = nullptr, void *Pdx = nullptr);
 // soft Dice + cross-entropy over the class logits and its gradient (loss_kernels.hip)
 bool loss_supported(const Geo &g, int classes);
 size_t loss_ws_bytes(const Geo &g, int classes);

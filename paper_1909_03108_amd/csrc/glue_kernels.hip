@@ -501,13 +501,23 @@ __global__ __launch_bounds__(kThreads) void pointwise_small_dgrad_kernel(const u
 // dp[ci][co] = sum_v x[v][ci] * dy[v][co], db[co] = sum_v dy[v][co]: a block walks over a chunk of voxels
 // with kThreads / (cin/8) voxel lanes x cin/8 channel groups (8 channels = one 16-byte load per thread);
 // the voxel lanes are then added in lane order and the block's partial goes to ws[chunk][cin*CO (+CO)].
-template <int CO>
+// DX: the same pass also writes the masked data gradient dx[v][ci] = [x[v][ci] > 0] * sum_co dy[v][co] * p[ci][co]
+// (pointwise_small_dgrad_kernel's arithmetic with x itself as the mask): a thread already holds the 8 channels of
+// x and the voxel's dy, so the layer input is read once for both gradients instead of twice.
+template <int CO, bool DX>
 __global__ __launch_bounds__(kThreads) void pointwise_small_wgrad_kernel(const uint16_t *__restrict__ x,
                                                                          const uint16_t *__restrict__ dy,
                                                                          float *__restrict__ part_w,
                                                                          float *__restrict__ part_b, Geo g, Lay l,
-                                                                         int cin, int cg_shift, unsigned chunk_vox) {
+                                                                         int cin, int cg_shift, unsigned chunk_vox,
+                                                                         const uint16_t *__restrict__ p,
+                                                                         uint16_t *__restrict__ dx) {
     __shared__ float red[kThreads * (8 * CO)];
+    __shared__ float w[DX ? kPwMaxCin * CO : 1];
+    if (DX) {
+        for (int i = threadIdx.x; i < cin * CO; i += kThreads) w[i] = bf16_to_f32(p[i]);
+        __syncthreads();
+    }
     const int cg = threadIdx.x & ((1 << cg_shift) - 1), vl = threadIdx.x >> cg_shift;
     const int nvl = kThreads >> cg_shift;
     float acc[8][CO], accb[CO];
@@ -530,6 +540,22 @@ __global__ __launch_bounds__(kThreads) void pointwise_small_wgrad_kernel(const u
         for (int co = 0; co < CO; ++co) {
             gv[co] = bf16_to_f32(dy[pv * CO + co]);
             accb[co] += gv[co];
+        }
+        if (DX) {
+            uint32_t r[4];
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+                for (int co = 0; co < CO; ++co) {
+                    s0 = fmaf(gv[co], w[(8 * cg + 2 * e2) * CO + co], s0);
+                    s1 = fmaf(gv[co], w[(8 * cg + 2 * e2 + 1) * CO + co], s1);
+                }
+                r[e2] = static_cast<uint32_t>(f32_to_bf16(s0)) | (static_cast<uint32_t>(f32_to_bf16(s1)) << 16);
+            }
+            r[0] &= positive_halves(q.x); r[1] &= positive_halves(q.y);
+            r[2] &= positive_halves(q.z); r[3] &= positive_halves(q.w);
+            *reinterpret_cast<uint4 *>(dx + pv * cin + 8 * cg) = make_uint4(r[0], r[1], r[2], r[3]);
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -833,7 +859,7 @@ size_t pointwise_small_wgrad_ws_bytes(const Geo &g, int cin, int cout) {
 }
 
 int launch_pointwise_small_wgrad(const void *Px, const void *Pdy, float *dp, float *db, const Geo &g, int cin,
-                                 int cout, void *ws, hipStream_t s) {
+                                 int cout, void *ws, hipStream_t s, const void *p, void *Pdx) {
     const Lay l = make_lay(g, 1);
     int nc; unsigned cv;
     pointwise_wgrad_plan(l.nvox, &nc, &cv);
@@ -842,8 +868,23 @@ int launch_pointwise_small_wgrad(const void *Px, const void *Pdy, float *dp, flo
     int cg_shift = 0;
     while ((1 << cg_shift) < cin / 8) ++cg_shift;
     dim3 grid(nc), block(kThreads);
-    SP3D_BY_CO(pointwise_small_wgrad_kernel, grid, block, 0, s, static_cast<const uint16_t *>(Px),
-               static_cast<const uint16_t *>(Pdy), part_w, part_b, g, l, cin, cg_shift, cv)
+#define SP3D_WG(CO)                                                                                            \
+    case CO:                                                                                                   \
+        if (Pdx)                                                                                               \
+            hipLaunchKernelGGL((pointwise_small_wgrad_kernel<CO, true>), grid, block, 0, s,                    \
+                               static_cast<const uint16_t *>(Px), static_cast<const uint16_t *>(Pdy), part_w,  \
+                               part_b, g, l, cin, cg_shift, cv, static_cast<const uint16_t *>(p),              \
+                               static_cast<uint16_t *>(Pdx));                                                  \
+        else                                                                                                   \
+            hipLaunchKernelGGL((pointwise_small_wgrad_kernel<CO, false>), grid, block, 0, s,                   \
+                               static_cast<const uint16_t *>(Px), static_cast<const uint16_t *>(Pdy), part_w,  \
+                               part_b, g, l, cin, cg_shift, cv, nullptr, nullptr);                             \
+        break;
+    switch (cout) {
+        SP3D_WG(1) SP3D_WG(2) SP3D_WG(3) SP3D_WG(4)
+    default: return SP_EUNSUPPORTED;
+    }
+#undef SP3D_WG
     int rc = record_hip(hipGetLastError());
     if (rc != SP_OK) return rc;
     rc = launch_reduce_partials(part_w, dp, nc, 1LL * cin * cout, s);

@@ -22,7 +22,7 @@ EXPORTS = ["sp_padded_elems", "sp_msg_elems", "sp_workspace_bytes", "sp_check_ge
            "conv3d_fwd_bits", "conv3d_fwd2_bits", "conv3d_dgrad_bits", "conv3d_wgrad", "conv3d_wgrad_static", "conv3d_fwd2", "conv3d_dgrad2",
            "conv3d_wgrad2", "sp_relu_bwd",
            "sp_maxpool2_fwd", "sp_maxpool2_bwd", "sp_maxpool2_bwd_join", "sp_upconv2_fwd", "sp_upconv2_dgrad", "sp_upconv2_wgrad",
-           "sp_pointwise_fwd", "sp_pointwise_dgrad", "sp_pointwise_dgrad_relu", "sp_pointwise_wgrad", "sp_concat", "sp_split", "sp_add",
+           "sp_pointwise_fwd", "sp_pointwise_dgrad", "sp_pointwise_dgrad_relu", "sp_pointwise_wgrad", "sp_pointwise_bwd_relu", "sp_concat", "sp_split", "sp_add",
            "sp_dice_ce_loss"]
 
 
@@ -111,6 +111,7 @@ def lib():
         L.sp_pointwise_dgrad.argtypes, L.sp_pointwise_dgrad.restype = [P, P, P, G, I, I, I, P], I
         L.sp_pointwise_dgrad_relu.argtypes, L.sp_pointwise_dgrad_relu.restype = [P, P, P, P, G, I, I, I, P], I
         L.sp_pointwise_wgrad.argtypes, L.sp_pointwise_wgrad.restype = [P, P, P, P, G, I, I, I, P, Z, P], I
+        L.sp_pointwise_bwd_relu.argtypes, L.sp_pointwise_bwd_relu.restype = [P, P, P, P, P, P, G, I, I, I, P, Z, P], I
         L.sp_concat.argtypes, L.sp_concat.restype = [P, I, P, I, P, G, I, P], I
         L.sp_split.argtypes, L.sp_split.restype = [P, P, I, P, I, G, I, P], I
         L.sp_add.argtypes, L.sp_add.restype = [P, P, P, G, I, I, P], I
@@ -315,6 +316,12 @@ def sp_pointwise_dgrad(Pdy, p, Pdx, g, cin, cout, dt, stream=None):
 def sp_pointwise_dgrad_relu(Pdy, p, Px, Pdx, g, cin, cout, dt, stream=None):
     _check(lib().sp_pointwise_dgrad_relu(_ptr(Pdy), _ptr(p), _ptr(Px), _ptr(Pdx), ctypes.byref(g), cin, cout, dt,
                                          _stream(stream)), "sp_pointwise_dgrad_relu")
+
+
+def sp_pointwise_bwd_relu(Px, Pdy, p, Pdx, dp, db, g, cin, cout, dt, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib().sp_pointwise_bwd_relu(_ptr(Px), _ptr(Pdy), _ptr(p), _ptr(Pdx), _ptr(dp), _ptr(db), ctypes.byref(g),
+                                       cin, cout, dt, wp, wb, _stream(stream)), "sp_pointwise_bwd_relu")
 
 
 def sp_pointwise_wgrad(Px, Pdy, dp, db, g, cin, cout, dt, ws=None, stream=None):

@@ -375,12 +375,12 @@ class UNet:
             sp3d.sp_partition(dlogits_vol, Pd, g0, self.classes, dt)
         c0 = ch[0]
         dp = torch.empty(tuple(self.w["head"].shape), dtype=torch.float32, device="cuda")
-        sp3d.sp_pointwise_wgrad(A["head.x"], Pd, dp, None, g0, c0, self.classes, dt,
-                                self._ws(sp3d.SP_OP_POINTWISE_WGRAD, g0, c0, self.classes))
-        grads["head"] = dp
         Pg = self._tmp(g0, c0)
-        # the head reads the ReLU output of the last decoder block: its data gradient applies that mask
-        sp3d.sp_pointwise_dgrad_relu(Pd, self.w["head"], A["head.x"], Pg, g0, c0, self.classes, dt)
+        # the head reads the ReLU output of the last decoder block: its data gradient applies that mask, in the
+        # same sweep over that activation as the weight gradient
+        sp3d.sp_pointwise_bwd_relu(A["head.x"], Pd, self.w["head"], Pg, dp, None, g0, c0, self.classes, dt,
+                                   self._ws(sp3d.SP_OP_POINTWISE_WGRAD, g0, c0, self.classes))
+        grads["head"] = dp
         skip_grad = {}
         for i in range(0, self.L - 1):
             g, c = self.g[i], ch[i]

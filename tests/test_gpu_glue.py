@@ -6,7 +6,7 @@ import torch
 
 from oracle import unet_ops as U
 from paper_1909_03108_amd import sp3d, synth
-from gpu_util import DT, TOL, bits, f64, rel_err, to_dev, widen
+from gpu_util import DT, TOL, bits, f64, guard_alloc, guards_intact, rel_err, to_dev, widen
 
 pytestmark = pytest.mark.gpu
 
@@ -137,6 +137,24 @@ def test_pointwise_fwd_dgrad_wgrad(n, dhw, grid, dtype, cin, cout):
     sp3d.sp_pointwise_wgrad(Px, Pdy, dp, db, g, cin, cout, dt, ws)
     ref_dp, ref_db = U.pointwise_wgrad(widen(x), widen(dy))
     assert rel_err(f64(dp), ref_dp) <= tol and rel_err(f64(db), ref_db) <= tol
+    # the whole backward pass in one sweep over the (ReLU) input: the oracle's values, and bit for bit what the two
+    # separate calls give on the same input
+    guard, Pone = guard_alloc(g.padded_shape + (cin,), Pm.dtype, 5.0)
+    dp1, db1 = torch.full_like(dp, 9.0), torch.full_like(db, 9.0)
+    sp3d.sp_pointwise_bwd_relu(Pm, Pdy, to_dev(p), Pone, dp1, db1, g, cin, cout, dt, ws)
+    assert guards_intact(guard, 5.0)
+    assert torch.equal(volume(g, Pone, cin, dt), volume(g, Pdm, cin, dt))
+    ref_dp, ref_db = U.pointwise_wgrad(widen(xr), widen(dy))
+    assert rel_err(f64(dp1), ref_dp) <= tol and rel_err(f64(db1), ref_db) <= tol
+    dp2, db2 = torch.empty_like(dp), torch.empty_like(db)
+    sp3d.sp_pointwise_wgrad(Pm, Pdy, dp2, db2, g, cin, cout, dt, ws)
+    assert torch.equal(dp1, dp2) and torch.equal(db1, db2)
+    dp3 = torch.full_like(dp, 9.0)
+    sp3d.sp_pointwise_bwd_relu(Pm, Pdy, to_dev(p), Pone, dp3, None, g, cin, cout, dt, ws)      # no bias gradient
+    assert torch.equal(dp3, dp2)
+    with pytest.raises(sp3d.Sp3dError) as e:
+        sp3d.sp_pointwise_bwd_relu(Pm, Pdy, to_dev(p), Pm, dp3, None, g, cin, cout, dt, ws)   # output on its input
+    assert e.value.code == sp3d.SP_EINVAL
 
 
 def test_pointwise_wgrad_many_partials():
