@@ -221,8 +221,7 @@ __global__ __launch_bounds__(kThreads) void conv_c1_fwd_kernel(C1Args a, int nhg
                             const uint2 lo = *reinterpret_cast<const uint2 *>(rd_at + k * YBUF + 16 * j * YROW);
                             const uint2 hi2 = *reinterpret_cast<const uint2 *>(rd_at + k * YBUF + 16 * j * YROW + 8);
                             if (oh < g.th && w0 + v < g.tw)
-                                *reinterpret_cast<uint4 *>(orow + static_cast<size_t>(v) * a.cout) =
-                                    make_uint4(lo.x, lo.y, hi2.x, hi2.y);
+                                st_stream16(orow + static_cast<size_t>(v) * a.cout, make_uint4(lo.x, lo.y, hi2.x, hi2.y));
                         }
                     }
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");

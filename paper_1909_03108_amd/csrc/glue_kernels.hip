@@ -172,7 +172,7 @@ __global__ __launch_bounds__(kThreads) void maxpool2_x8_kernel(const uint16_t *_
                 if (xv[k][e] > best[e]) { best[e] = xv[k][e]; arg[e] = k; }
         }
         if (MODE == kPoolFwd) {
-            *reinterpret_cast<uint4 *>(out + pc * C + 8 * cg) = narrow8(best);
+            st_stream16(out + pc * C + 8 * cg, narrow8(best));
             continue;
         }
         float g[8];
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(kThreads) void maxpool2_x8_kernel(const uint16_t *_
 #pragma unroll
                 for (int e = 0; e < 8; ++e) r[e] = arg[e] == k ? g[e] : 0.f;
             }
-            *reinterpret_cast<uint4 *>(out + pf[k] * C + 8 * cg) = narrow8(r);
+            st_stream16(out + pf[k] * C + 8 * cg, narrow8(r));
         }
     }
 }
@@ -495,7 +495,7 @@ __global__ __launch_bounds__(kThreads) void pointwise_small_dgrad_kernel(const u
         r[0] &= positive_halves(mv.x); r[1] &= positive_halves(mv.y);
         r[2] &= positive_halves(mv.z); r[3] &= positive_halves(mv.w);
     }
-    *reinterpret_cast<uint4 *>(dx + pv * cin + 8 * c8) = make_uint4(r[0], r[1], r[2], r[3]);
+    st_stream16(dx + pv * cin + 8 * c8, make_uint4(r[0], r[1], r[2], r[3]));
 }
 
 // dp[ci][co] = sum_v x[v][ci] * dy[v][co], db[co] = sum_v dy[v][co]: a block walks over a chunk of voxels
@@ -555,7 +555,7 @@ __global__ __launch_bounds__(kThreads) void pointwise_small_wgrad_kernel(const u
             }
             r[0] &= positive_halves(q.x); r[1] &= positive_halves(q.y);
             r[2] &= positive_halves(q.z); r[3] &= positive_halves(q.w);
-            *reinterpret_cast<uint4 *>(dx + pv * cin + 8 * cg) = make_uint4(r[0], r[1], r[2], r[3]);
+            st_stream16(dx + pv * cin + 8 * cg, make_uint4(r[0], r[1], r[2], r[3]));
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) {

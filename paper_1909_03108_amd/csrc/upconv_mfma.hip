@@ -158,8 +158,7 @@ __global__ __launch_bounds__(kT) void upconv_fwd_mfma_kernel(UpArgs a) {
                         const uint2 lo = *reinterpret_cast<const uint2 *>(tbuf + fv * TROW + 16 * rp);
                         const uint2 hi = *reinterpret_cast<const uint2 *>(tbuf + fv * TROW + 16 * rp + 8);
                         if (2 * o.w0 + fv < 2 * a.gc.tw)
-                            *reinterpret_cast<uint4 *>(prow + static_cast<size_t>(fv) * a.cout) =
-                                make_uint4(lo.x, lo.y, hi.x, hi.y);
+                            st_stream16(prow + static_cast<size_t>(fv) * a.cout, make_uint4(lo.x, lo.y, hi.x, hi.y));
                     }
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
                 }
