@@ -194,7 +194,8 @@ typedef uint32_t mask_t __attribute__((ext_vector_type(2)));
 // the code must be one basic block with nothing that makes the compiler move the register: a load issued under
 // a run-time condition is joined to the other path by a copy that runs before the data has arrived.
 __device__ __forceinline__ void side_load(pin_t &d, const float *p) {
-    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(d) : "v"(p) : "memory");
+    // (partial sums: a contiguous kilobyte per wave, read once - non-temporal)
+    asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(d) : "v"(p) : "memory");
 }
 __device__ __forceinline__ void side_load(mask_t &d, const uint16_t *p) {
     asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(d) : "v"(p) : "memory");

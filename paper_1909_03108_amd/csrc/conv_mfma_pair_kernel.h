@@ -101,7 +101,9 @@ __device__ __forceinline__ void finish_unit(const Ctx<HAS_BIAS> &c, int d, const
     if (MODE == kMiddle || MODE == kLast) { v0 += pin[h][q].x; v1 += pin[h][q].y; v2 += pin[h][q].z; v3 += pin[h][q].w; }
     const size_t at = d * c.oplane + h * c.orow + 8 * q;
     if (MODE == kFirst || MODE == kMiddle) {
-        if (FULL || c.okrow[h]) *reinterpret_cast<float4 *>(c.pbase + part_unit(d, h, q)) = make_float4(v0, v1, v2, v3);
+        // (a contiguous kilobyte per wave that the next launch reads once: non-temporal)
+        if (FULL || c.okrow[h])
+            __builtin_nontemporal_store(pin_t{v0, v1, v2, v3}, reinterpret_cast<pin_t *>(c.pbase + part_unit(d, h, q)));
         return;
     }
     if (is_relu(RELU)) {

@@ -359,7 +359,7 @@ __global__ __launch_bounds__(kThreads) void relu_bwd_bf16x8_kernel(const u32x4 *
         const uint32_t hi = positive<uint16_t>(static_cast<uint16_t>(v[k] >> 16)) ? 0xffff0000u : 0u;
         o[k] = g[k] & (lo | hi);
     }
-    dz[i] = o;
+    st_stream(&dz[i], o);
 }
 
 }  // namespace
